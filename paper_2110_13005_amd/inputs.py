@@ -1,0 +1,127 @@
+"""Seeded synthetic inputs for the stage hot path.
+
+This module only draws random numbers and snaps them to bfloat16-representable values;
+it holds none of the method's arithmetic.  Both the HIP path's tests and the CPU oracle's
+tests take their inputs from here so that they see the same numbers.
+
+Recipe (stands in for the activations a middle pipeline stage would receive when the
+paper trains GPT models on token batches, Sec. 6.1): numpy `default_rng(seed)`, float32
+standard-normal draws in a fixed order -- per layer W_qkv, W_o, W_fc1, W_fc2 with
+std `weight_std`; then (only if `perturb`) per layer LayerNorm gains/shifts and all
+biases with std `weight_std` around 1/0/0; then the M microbatch inputs x with std 1;
+then the M upstream gradients dy with std `dy_std`.  Every value is rounded once to
+bfloat16 (nearest, ties to even) and returned as float32.
+"""
+from dataclasses import dataclass
+import numpy as np
+
+PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+               "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2")
+
+
+@dataclass(frozen=True)
+class StageShape:
+    n_layers: int
+    hidden: int
+    n_heads: int
+    seq_len: int
+    microbatch_size: int
+    n_microbatches: int
+    ffn_hidden: int = 0  # 0 -> 4*hidden
+
+    @property
+    def ffn(self):
+        return self.ffn_hidden or 4 * self.hidden
+
+    @property
+    def tokens(self):
+        return self.microbatch_size * self.seq_len
+
+    def param_shapes(self):
+        h, f = self.hidden, self.ffn
+        return {"ln1_g": (h,), "ln1_b": (h,), "w_qkv": (h, 3 * h), "b_qkv": (3 * h,),
+                "w_o": (h, h), "b_o": (h,), "ln2_g": (h,), "ln2_b": (h,),
+                "w_fc1": (h, f), "b_fc1": (f,), "w_fc2": (f, h), "b_fc2": (h,)}
+
+
+# The five workloads of the benchmark definition (stage shapes 1-4; 5 is optimizer-only).
+CONFIGS = {
+    "tiny": StageShape(2, 256, 4, 128, 2, 4),
+    "12b": StageShape(4, 5120, 40, 2048, 1, 8),
+    "24b": StageShape(4, 6144, 48, 2048, 2, 16),
+    "100b": StageShape(2, 10240, 80, 2048, 1, 16),
+}
+OPT_CONFIG = dict(n=1_600_000_000, bucket_elems=1 << 26, lr=1e-4, beta1=0.9, beta2=0.95,
+                  eps=1e-8, weight_decay=0.0, step=100, grad_scale=1.0)
+
+
+def to_bf16_bits(a):
+    """float32 array -> uint16 array of bfloat16 bit patterns (nearest, ties to even)."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    r = u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def from_bf16_bits(b):
+    """uint16 bfloat16 bit patterns -> float32 values."""
+    return (np.asarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def snap_bf16(a):
+    """Round a float32 array to bfloat16-representable float32 values."""
+    return from_bf16_bits(to_bf16_bits(a)).reshape(np.shape(a))
+
+
+def _normal(rng, shape, std, mean=0.0):
+    a = rng.standard_normal(shape, dtype=np.float32)
+    if std != 1.0:
+        a *= np.float32(std)
+    if mean != 0.0:
+        a += np.float32(mean)
+    return snap_bf16(a)
+
+
+def make_stage_inputs(shape: StageShape, seed=0, perturb=False, weight_std=0.02,
+                      dy_std=1.0, n_microbatches=None):
+    """Returns (layers, xs, dys): layers = list of dicts name -> float32 array
+    (bf16-representable); xs, dys = lists of [b, s, h] float32 arrays."""
+    rng = np.random.default_rng(seed)
+    shapes = shape.param_shapes()
+    M = shape.n_microbatches if n_microbatches is None else n_microbatches
+    layers = []
+    for _ in range(shape.n_layers):
+        p = {}
+        for name in ("w_qkv", "w_o", "w_fc1", "w_fc2"):
+            p[name] = _normal(rng, shapes[name], weight_std)
+        layers.append(p)
+    for p in layers:
+        for name in PARAM_NAMES:
+            if name in p:
+                continue
+            base = 1.0 if name in ("ln1_g", "ln2_g") else 0.0
+            if perturb:
+                p[name] = _normal(rng, shapes[name], weight_std, base)
+            else:
+                p[name] = np.full(shapes[name], base, dtype=np.float32)
+    bsh = (shape.microbatch_size, shape.seq_len, shape.hidden)
+    xs = [_normal(rng, bsh, 1.0) for _ in range(M)]
+    dys = [_normal(rng, bsh, dy_std) for _ in range(M)]
+    return layers, xs, dys
+
+
+def make_adam_inputs(n, seed=0, theta_std=0.02, grad_std=1e-3, m_std=1e-4, v_std=1e-6,
+                     fresh=False):
+    """Optimizer-state inputs: (theta, m, v) float32, g16 float32 holding bf16 values.
+
+    Mid-training state: theta ~ N(0, theta_std), m ~ N(0, m_std), v = |N(0, v_std)|,
+    gradient ~ N(0, grad_std) rounded to bfloat16.  `fresh` gives m = v = 0 (first step)."""
+    rng = np.random.default_rng(seed)
+    theta = rng.standard_normal(n, dtype=np.float32) * np.float32(theta_std)
+    if fresh:
+        m = np.zeros(n, dtype=np.float32)
+        v = np.zeros(n, dtype=np.float32)
+    else:
+        m = rng.standard_normal(n, dtype=np.float32) * np.float32(m_std)
+        v = np.abs(rng.standard_normal(n, dtype=np.float32) * np.float32(v_std))
+    g16 = snap_bf16(rng.standard_normal(n, dtype=np.float32) * np.float32(grad_std))
+    return theta, m, v, g16
