@@ -1,0 +1,239 @@
+/*
+ * axonn_stage.h -- C ABI of libaxonn_stage.so (MI355X / gfx950 only).
+ *
+ * The per-GPU hot path of AxoNN (arXiv 2110.13005): one pipeline stage ("nn_shard",
+ * Sec. 3.1 / Alg. 1) of pre-LayerNorm GPT transformer layers whose Forward(msg) /
+ * Backward(msg) are driven by received messages (Alg. 2), followed by the stage's
+ * mixed-precision Adam step whose fp32 master weights and moments live in host memory
+ * and are streamed through HBM in buckets (Sec. 5.2).
+ *
+ * Conventions
+ *  - Every function returns 0 (AXONN_OK) or a negative axonn_status; nothing throws or
+ *    aborts.  axonn_last_error() gives a thread-local, library-owned message.
+ *  - "dev" pointers are HIP device pointers, "host" pointers are host memory.  bf16 means
+ *    bfloat16 bit patterns (uint16_t storage).  hip_stream arguments are hipStream_t
+ *    passed as void* (NULL = the null stream).
+ *  - All tensors are dense row-major.  Activations are [b, s, h] = [T, h] with T = b*s.
+ *    Weights are [in, out].  Per (batch, head) attention operands are column slices of the
+ *    packed qkv tensor [T, 3h]: columns [0,h) = Q, [h,2h) = K, [2h,3h) = V, head j owning
+ *    columns j*d..(j+1)*d-1 of each third.
+ *  - Unless stated otherwise a call only enqueues work on the given stream and returns;
+ *    the caller keeps every buffer alive until that stream work has completed.
+ *  - A handle may be used from one host thread at a time.
+ */
+#ifndef AXONN_STAGE_H
+#define AXONN_STAGE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  AXONN_OK = 0,
+  AXONN_EINVAL = -1,       /* bad argument: null pointer, non-positive size, ...      */
+  AXONN_ESTATE = -2,       /* call not allowed in the handle's current state           */
+  AXONN_ENOMEM = -3,       /* device or host allocation failed                         */
+  AXONN_EHIP = -4,         /* a HIP runtime call failed (message has the HIP error)    */
+  AXONN_EUNSUPPORTED = -5  /* shape outside what the kernels support (message says why)*/
+} axonn_status;
+
+const char* axonn_last_error(void);
+
+/* Pinned host memory (hipHostMalloc / hipHostFree) for the optimizer's master state. */
+int axonn_pinned_alloc(void** host_out, uint64_t bytes);
+int axonn_pinned_free(void* host);
+
+/* ------------------------------------------------------------------------------------
+ * Stage handle (Sec. 3.1: a contiguous subset of layers owned by one GPU).
+ * ---------------------------------------------------------------------------------- */
+typedef struct axonn_stage axonn_stage_t;
+
+typedef struct {
+  int32_t n_layers;        /* transformer layers in this stage                         */
+  int32_t hidden;          /* h; multiple of 8                                         */
+  int32_t n_heads;         /* a; head dim d = h / a must be 64 or 128                  */
+  int32_t ffn_hidden;      /* MLP width (4h in every benchmark shape); multiple of 8   */
+  int32_t seq_len;         /* s                                                        */
+  int32_t microbatch_size; /* b (Sec. 3.3: user-defined microbatch size); b*s % 8 == 0 */
+  int32_t n_microbatches;  /* M: microbatches per batch                                */
+  int32_t pipeline_limit;  /* max microbatches in flight (Sec. 3.3); 1..M              */
+  float ln_eps;            /* LayerNorm epsilon (inside the root, biased variance)     */
+  int32_t device;          /* HIP device ordinal                                       */
+  int32_t grad_accum_fp32; /* 1: accumulate weight gradients over microbatches in an
+                              fp32 shadow buffer, rounded once to bf16 after the M-th
+                              backward; 0: accumulate directly in the bf16 gradient
+                              buffer (the paper's 4*phi device footprint, Sec. 5.2)    */
+} axonn_stage_config;
+
+/* Allocates bf16 parameters and gradients (flat buffers), pipeline_limit activation
+ * stash slots and the backward workspace on cfg->device.  Parameters are zero except
+ * LayerNorm gains = 1; gradients are zero.  Synchronous. */
+int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out);
+/* Waits for all work of the stage, then frees everything it owns.  Synchronous. */
+int axonn_stage_destroy(axonn_stage_t* st);
+
+/* Flat parameter layout.  The stage holds 12 tensors per layer, in this order:
+ * ln1_g[h] ln1_b[h] w_qkv[h,3h] b_qkv[3h] w_o[h,h] b_o[h] ln2_g[h] ln2_b[h]
+ * w_fc1[h,f] b_fc1[f] w_fc2[f,h] b_fc2[h]; tensor idx = layer*12 + position.
+ * name is "layer<l>.<tensor>", library-owned.  offset is in elements. */
+int axonn_stage_param_count(const axonn_stage_t* st, uint64_t* n_elements);
+int axonn_stage_num_tensors(const axonn_stage_t* st, int32_t* n_tensors);
+int axonn_stage_param_layout(const axonn_stage_t* st, int32_t idx, const char** name,
+                             uint64_t* offset, int32_t* rank, int64_t dims[4]);
+/* Borrowed device pointers to the flat bf16 buffers (param_count elements each). */
+int axonn_stage_params(axonn_stage_t* st, void** dev_bf16);
+int axonn_stage_grads(axonn_stage_t* st, void** dev_bf16);
+/* Starts a new batch: the next backward overwrites the gradient accumulators instead of
+ * adding to them (so no memory is cleared), and the per-batch microbatch count restarts.
+ * Until that backward the gradient buffer still holds the previous batch's gradients. */
+int axonn_stage_zero_grad(axonn_stage_t* st, void* hip_stream);
+/* Device bytes the stage holds, by category (Sec. 5.2 accounting): [0] bf16 params,
+ * [1] bf16 grads, [2] fp32 grad shadow (0 unless grad_accum_fp32), [3] activation stash,
+ * [4] backward workspace, [5] optimizer bucket buffers (0 until attached). */
+int axonn_stage_device_bytes(const axonn_stage_t* st, uint64_t bytes[6]);
+
+/* Forward(msg) of Alg. 2: runs the stage's layers on microbatch mb_id.
+ * x_dev_bf16 [b,s,h] is read (and copied into the stash, so the caller may recycle its
+ * receive buffer once the stream work is done); y_dev_bf16 [b,s,h] is written.
+ * AXONN_ESTATE if mb_id is already in flight or pipeline_limit microbatches are. */
+int axonn_stage_forward(axonn_stage_t* st, int32_t mb_id, const void* x_dev_bf16,
+                        void* y_dev_bf16, void* hip_stream);
+/* Backward(msg) of Alg. 2: given dL/dy for microbatch mb_id, writes dL/dx to
+ * dx_dev_bf16 [b,s,h], adds the microbatch's parameter gradients into the accumulators
+ * and releases its stash slot.  AXONN_ESTATE if mb_id has no forward in flight.  After
+ * the n_microbatches-th backward since the last zero_grad the bf16 gradient buffer is
+ * final on that stream. */
+int axonn_stage_backward(axonn_stage_t* st, int32_t mb_id, const void* dy_dev_bf16,
+                         void* dx_dev_bf16, void* hip_stream);
+
+/* Message-driven mode (steady-state loop of Alg. 2).  A message is what a neighbouring
+ * pipeline stage would send: kind 0 comes from the previous stage (activations, triggers
+ * Forward), kind 1 from the next stage (gradients w.r.t. this stage's output, triggers
+ * Backward).  payload_dev is the [b,s,h] bf16 receive buffer, result_dev the [b,s,h]
+ * bf16 buffer to send onwards; ready_event (hipEvent_t or NULL) is signalled when the
+ * payload has arrived.  post() never blocks (a pre-posted receive, Sec. 4.1). */
+typedef struct {
+  int32_t kind;
+  int32_t mb_id;
+  const void* payload_dev;
+  void* result_dev;
+  void* ready_event;
+} axonn_msg;
+int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg);
+/* Consumes posted messages until n_microbatches forwards and n_microbatches backwards
+ * have been enqueued: repeatedly takes the first posted message whose payload has
+ * arrived (event query) and that is admissible (forward: a stash slot is free; backward:
+ * its forward was issued) and launches Forward or Backward for it.  Forwards go round
+ * robin over n_streams-1 library streams, backwards to their own stream (n_streams = 1:
+ * one stream for both).  Returns AXONN_ESTATE if messages remain but none can ever
+ * become admissible.  Work is only enqueued; see axonn_stage_synchronize. */
+int axonn_stage_run(axonn_stage_t* st, int32_t n_streams);
+/* Makes user_stream wait for everything the library streams have been given so far. */
+int axonn_stage_join(axonn_stage_t* st, void* user_stream);
+/* Blocks the host until all enqueued work of the stage is complete. */
+int axonn_stage_synchronize(axonn_stage_t* st);
+/* Order in which run() dispatched messages: entries are mb_id*2 + kind. */
+int axonn_stage_dispatch_log(const axonn_stage_t* st, int32_t* out, int32_t capacity,
+                             int32_t* n_written);
+
+/* ------------------------------------------------------------------------------------
+ * Offloaded, bucketed Adam (Sec. 5.2): only theta16 and grad16 live on the GPU; the fp32
+ * master weights theta and the two Adam moments live in pinned host memory.  One step
+ * fetches bucket after bucket (bucket_elems parameters) into reusable device buffers,
+ * updates it and writes it back; H2D copy, update kernel and D2H copy of consecutive
+ * buckets overlap on three streams.
+ * Per element (Sec. 2.1 mixed precision; Kingma & Ba; decoupled decay):
+ *   g = grad_scale * float(grad16);  m = b1*m + (1-b1)*g;  v = b2*v + (1-b2)*g*g
+ *   theta -= lr * ( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + weight_decay*theta )
+ *   theta16 = bf16_rne(theta)
+ * ---------------------------------------------------------------------------------- */
+typedef struct axonn_offload_adam axonn_offload_adam_t;
+/* n parameters; param16_dev / grad16_dev are caller-owned device bf16 arrays of n
+ * elements; host_master / host_m / host_v are caller-owned PINNED host fp32 arrays of n
+ * elements.  Allocates 3 sets of 3 fp32 device buffers of min(bucket_elems, n) elements.
+ * bucket_elems must be a positive multiple of 8. */
+int axonn_offload_adam_create(int32_t device, uint64_t n, uint64_t bucket_elems,
+                              void* param16_dev, const void* grad16_dev,
+                              float* host_master, float* host_m, float* host_v,
+                              axonn_offload_adam_t** out);
+int axonn_offload_adam_destroy(axonn_offload_adam_t* opt);
+/* Enqueues one full step (all buckets).  The work starts after everything already in
+ * hip_stream and hip_stream waits for its end; step t >= 1. */
+int axonn_offload_adam_step(axonn_offload_adam_t* opt, float lr, float beta1, float beta2,
+                            float eps, float weight_decay, int64_t step, float grad_scale,
+                            void* hip_stream);
+int axonn_offload_adam_device_bytes(const axonn_offload_adam_t* opt, uint64_t* bytes);
+
+/* The same, bound to a stage's own parameter and gradient buffers ("run the optimizer",
+ * Alg. 1).  n must equal the stage's param_count.  step returns AXONN_ESTATE while
+ * microbatches are in flight. */
+int axonn_stage_optimizer_attach(axonn_stage_t* st, float* host_master, float* host_m,
+                                 float* host_v, uint64_t n, uint64_t bucket_elems);
+int axonn_stage_optimizer_step(axonn_stage_t* st, float lr, float beta1, float beta2,
+                               float eps, float weight_decay, int64_t step,
+                               float grad_scale, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------
+ * Single operations of the layer (the kernels Forward/Backward are built from), exposed
+ * so that each can be checked against the oracle on its own.  All pointers are device
+ * pointers; all calls enqueue on hip_stream.
+ * ---------------------------------------------------------------------------------- */
+
+/* C[M,N] = epilogue( sum_k A(m,k) * B(n,k) ), bf16 operands, fp32 accumulation (MFMA).
+ * a_kcontig: A(m,k) = A[m*lda + k], else A[k*lda + m]; b_kcontig likewise for B(n,k).
+ * So a forward linear map y = x W is (a_kcontig=1, b_kcontig=0), its input gradient
+ * dx = dy W^T is (1,1) and its weight gradient dW = x^T dy is (0,0).
+ * M, N, K, lda, ldb, ldc (and ld_aux, ld_res) must be multiples of 8.
+ * epilogue:
+ *   0  C = bf16(acc + bias[n])                      bias may be NULL (treated as 0)
+ *   1  C = bf16(acc + bias[n] + res[m,n])
+ *   2  aux = bf16(acc + bias[n]);  C = bf16(GeLU(acc + bias[n]))     (exact erf GeLU)
+ *   3  C = bf16(acc * GeLU'(aux[m,n]))
+ *   4  C_f32 = (accumulate ? C_f32 : 0) + acc        C is float32
+ *   5  C = bf16((accumulate ? float(C) : 0) + acc)
+ */
+int axonn_gemm_bf16(int32_t a_kcontig, int32_t b_kcontig, int32_t epilogue,
+                    int64_t M, int64_t N, int64_t K,
+                    const void* A, int64_t lda, const void* B, int64_t ldb,
+                    void* C, int64_t ldc, const void* bias,
+                    const void* res, int64_t ld_res, void* aux, int64_t ld_aux,
+                    int32_t accumulate, void* hip_stream);
+
+/* Per-row LayerNorm over h (multiple of 8, <= 16384): out = g*(x-mean)*rstd + b, biased
+ * variance, rstd = 1/sqrt(var+eps).  stats[T,2] float32 = (mean, rstd). */
+int axonn_layernorm_fwd(int64_t T, int64_t h, const void* x_bf16, const void* gamma_bf16,
+                        const void* beta_bf16, float eps, void* out_bf16, float* stats,
+                        void* hip_stream);
+/* dx = (res_grad ? res_grad : 0) + dLN(dout; x, stats, gamma);
+ * dgamma_f32[h], dbeta_f32[h] are OVERWRITTEN with this call's column sums
+ * sum_t dout*xhat and sum_t dout.  workspace_f32 needs 2*ceil(T/64)*h floats. */
+int axonn_layernorm_bwd(int64_t T, int64_t h, const void* dout_bf16, const void* x_bf16,
+                        const float* stats, const void* gamma_bf16, const void* res_grad_bf16,
+                        void* dx_bf16, float* dgamma_f32, float* dbeta_f32,
+                        float* workspace_f32, void* hip_stream);
+/* out_f32[N] = sum_t y[t, n] over T rows (bias gradient).  workspace: ceil(T/64)*N floats. */
+int axonn_colsum(int64_t T, int64_t N, const void* y_bf16, int64_t ldy, float* out_f32,
+                 float* workspace_f32, void* hip_stream);
+
+/* Causal self-attention over the packed qkv [b*s, 3h] (layout above), head dim 64 or 128.
+ * o [b*s, h] bf16;  lse [b, a, s] float32 = log sum_j<=i exp(q_i.k_j / sqrt(d)). */
+int axonn_attention_fwd(int32_t b, int32_t s, int32_t n_heads, int32_t head_dim,
+                        const void* qkv_bf16, void* o_bf16, float* lse, void* hip_stream);
+/* dqkv [b*s, 3h] bf16 from do [b*s, h]; delta_ws: b*a*s floats of scratch. */
+int axonn_attention_bwd(int32_t b, int32_t s, int32_t n_heads, int32_t head_dim,
+                        const void* qkv_bf16, const void* o_bf16, const float* lse,
+                        const void* do_bf16, void* dqkv_bf16, float* delta_ws,
+                        void* hip_stream);
+
+/* Adam update of n elements resident on the device (one bucket's kernel, formula above).
+ * theta/m/v float32 are updated in place; grad16 is read; param16 is written. */
+int axonn_adam_bucket(uint64_t n, float* theta, float* m, float* v, const void* grad16,
+                      void* param16, float lr, float beta1, float beta2, float eps,
+                      float weight_decay, int64_t step, float grad_scale, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AXONN_STAGE_H */

@@ -1,0 +1,289 @@
+"""ctypes binding of libaxonn_stage.so: argument marshalling only.
+
+Every function has the name and argument order of its C declaration in
+include/axonn_stage.h.  Device buffers may be passed as torch tensors (their
+`data_ptr()` is taken) or as integer addresses; streams as `torch.cuda.Stream`,
+integer handles or None.  A negative status raises AxonnError with the library's
+message.  There is no fallback: if the shared library has not been built, loading
+fails with an error that says how to build it.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaxonn_stage.so")
+
+AXONN_OK, AXONN_EINVAL, AXONN_ESTATE, AXONN_ENOMEM, AXONN_EHIP, AXONN_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
+EPI_BIAS, EPI_BIAS_RES, EPI_BIAS_GELU, EPI_DGELU, EPI_ACC_F32, EPI_ACC_BF16 = range(6)
+
+
+class AxonnError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__("axonn status %d: %s" % (status, message))
+        self.status = status
+
+
+class axonn_stage_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_heads", C.c_int32),
+                ("ffn_hidden", C.c_int32), ("seq_len", C.c_int32), ("microbatch_size", C.c_int32),
+                ("n_microbatches", C.c_int32), ("pipeline_limit", C.c_int32), ("ln_eps", C.c_float),
+                ("device", C.c_int32), ("grad_accum_fp32", C.c_int32)]
+
+
+class axonn_msg(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("mb_id", C.c_int32), ("payload_dev", C.c_void_p),
+                ("result_dev", C.c_void_p), ("ready_event", C.c_void_p)]
+
+
+_vp, _i32, _i64, _u64, _f = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
+_PROTOTYPES = {
+    "axonn_pinned_alloc": [C.POINTER(_vp), _u64],
+    "axonn_pinned_free": [_vp],
+    "axonn_stage_create": [C.POINTER(axonn_stage_config), C.POINTER(_vp)],
+    "axonn_stage_destroy": [_vp],
+    "axonn_stage_param_count": [_vp, C.POINTER(_u64)],
+    "axonn_stage_num_tensors": [_vp, C.POINTER(_i32)],
+    "axonn_stage_param_layout": [_vp, _i32, C.POINTER(C.c_char_p), C.POINTER(_u64), C.POINTER(_i32), C.POINTER(_i64)],
+    "axonn_stage_params": [_vp, C.POINTER(_vp)],
+    "axonn_stage_grads": [_vp, C.POINTER(_vp)],
+    "axonn_stage_zero_grad": [_vp, _vp],
+    "axonn_stage_device_bytes": [_vp, C.POINTER(_u64)],
+    "axonn_stage_forward": [_vp, _i32, _vp, _vp, _vp],
+    "axonn_stage_backward": [_vp, _i32, _vp, _vp, _vp],
+    "axonn_stage_post": [_vp, C.POINTER(axonn_msg)],
+    "axonn_stage_run": [_vp, _i32],
+    "axonn_stage_join": [_vp, _vp],
+    "axonn_stage_synchronize": [_vp],
+    "axonn_stage_dispatch_log": [_vp, C.POINTER(_i32), _i32, C.POINTER(_i32)],
+    "axonn_offload_adam_create": [_i32, _u64, _u64, _vp, _vp, _vp, _vp, _vp, C.POINTER(_vp)],
+    "axonn_offload_adam_destroy": [_vp],
+    "axonn_offload_adam_step": [_vp, _f, _f, _f, _f, _f, _i64, _f, _vp],
+    "axonn_offload_adam_device_bytes": [_vp, C.POINTER(_u64)],
+    "axonn_stage_optimizer_attach": [_vp, _vp, _vp, _vp, _u64, _u64],
+    "axonn_stage_optimizer_step": [_vp, _f, _f, _f, _f, _f, _i64, _f, _vp],
+    "axonn_gemm_bf16": [_i32, _i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64,
+                        _vp, _i64, _i32, _vp],
+    "axonn_layernorm_fwd": [_i64, _i64, _vp, _vp, _vp, _f, _vp, _vp, _vp],
+    "axonn_layernorm_bwd": [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
+    "axonn_colsum": [_i64, _i64, _vp, _i64, _vp, _vp, _vp],
+    "axonn_attention_fwd": [_i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
+    "axonn_attention_bwd": [_i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
+    "axonn_adam_bucket": [_u64, _vp, _vp, _vp, _vp, _vp, _f, _f, _f, _f, _f, _i64, _f, _vp],
+}
+EXPORTED_SYMBOLS = ["axonn_last_error"] + sorted(_PROTOTYPES)
+
+_lib = None
+
+
+def load():
+    """Loads the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError("%s not found: build it with `python -m paper_2110_13005_amd.build`" % LIB_PATH)
+        lib = C.CDLL(LIB_PATH)
+        lib.axonn_last_error.restype = C.c_char_p
+        lib.axonn_last_error.argtypes = []
+        for name, args in _PROTOTYPES.items():
+            fn = getattr(lib, name)
+            fn.restype = C.c_int
+            fn.argtypes = args
+        _lib = lib
+    return _lib
+
+
+def _ptr(x):
+    """torch tensor / numpy array / int / None -> address."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if hasattr(x, "ctypes"):
+        return x.ctypes.data
+    if isinstance(x, C.c_void_p):
+        return x.value
+    raise TypeError("cannot take the address of %r" % type(x))
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream  # torch.cuda.Stream
+
+
+def _check(status):
+    if status != 0:
+        raise AxonnError(status, load().axonn_last_error().decode())
+
+
+def axonn_last_error():
+    return load().axonn_last_error().decode()
+
+
+def axonn_pinned_alloc(nbytes):
+    out = _vp()
+    _check(load().axonn_pinned_alloc(C.byref(out), nbytes))
+    return out.value
+
+
+def axonn_pinned_free(host):
+    _check(load().axonn_pinned_free(_ptr(host)))
+
+
+def axonn_stage_create(cfg):
+    out = _vp()
+    _check(load().axonn_stage_create(C.byref(cfg), C.byref(out)))
+    return out.value
+
+
+def axonn_stage_destroy(st):
+    _check(load().axonn_stage_destroy(st))
+
+
+def axonn_stage_param_count(st):
+    n = _u64()
+    _check(load().axonn_stage_param_count(st, C.byref(n)))
+    return n.value
+
+
+def axonn_stage_num_tensors(st):
+    n = _i32()
+    _check(load().axonn_stage_num_tensors(st, C.byref(n)))
+    return n.value
+
+
+def axonn_stage_param_layout(st, idx):
+    name, off, rank = C.c_char_p(), _u64(), _i32()
+    dims = (_i64 * 4)()
+    _check(load().axonn_stage_param_layout(st, idx, C.byref(name), C.byref(off), C.byref(rank), dims))
+    return name.value.decode(), off.value, tuple(dims[i] for i in range(rank.value))
+
+
+def axonn_stage_params(st):
+    p = _vp()
+    _check(load().axonn_stage_params(st, C.byref(p)))
+    return p.value
+
+
+def axonn_stage_grads(st):
+    p = _vp()
+    _check(load().axonn_stage_grads(st, C.byref(p)))
+    return p.value
+
+
+def axonn_stage_zero_grad(st, stream=None):
+    _check(load().axonn_stage_zero_grad(st, _stream(stream)))
+
+
+def axonn_stage_device_bytes(st):
+    b = (_u64 * 6)()
+    _check(load().axonn_stage_device_bytes(st, b))
+    return list(b)
+
+
+def axonn_stage_forward(st, mb_id, x, y, stream=None):
+    _check(load().axonn_stage_forward(st, mb_id, _ptr(x), _ptr(y), _stream(stream)))
+
+
+def axonn_stage_backward(st, mb_id, dy, dx, stream=None):
+    _check(load().axonn_stage_backward(st, mb_id, _ptr(dy), _ptr(dx), _stream(stream)))
+
+
+def axonn_stage_post(st, kind, mb_id, payload, result, ready_event=None):
+    ev = ready_event if (ready_event is None or isinstance(ready_event, int)) else ready_event.cuda_event
+    m = axonn_msg(kind, mb_id, _ptr(payload), _ptr(result), ev)
+    _check(load().axonn_stage_post(st, C.byref(m)))
+
+
+def axonn_stage_run(st, n_streams=2):
+    _check(load().axonn_stage_run(st, n_streams))
+
+
+def axonn_stage_join(st, stream=None):
+    _check(load().axonn_stage_join(st, _stream(stream)))
+
+
+def axonn_stage_synchronize(st):
+    _check(load().axonn_stage_synchronize(st))
+
+
+def axonn_stage_dispatch_log(st, capacity=4096):
+    buf = (_i32 * capacity)()
+    n = _i32()
+    _check(load().axonn_stage_dispatch_log(st, buf, capacity, C.byref(n)))
+    return [(buf[i] // 2, buf[i] % 2) for i in range(n.value)]
+
+
+def axonn_offload_adam_create(device, n, bucket_elems, param16, grad16, host_master, host_m, host_v):
+    out = _vp()
+    _check(load().axonn_offload_adam_create(device, n, bucket_elems, _ptr(param16), _ptr(grad16),
+                                            _ptr(host_master), _ptr(host_m), _ptr(host_v), C.byref(out)))
+    return out.value
+
+
+def axonn_offload_adam_destroy(opt):
+    _check(load().axonn_offload_adam_destroy(opt))
+
+
+def axonn_offload_adam_step(opt, lr, beta1, beta2, eps, weight_decay, step, grad_scale, stream=None):
+    _check(load().axonn_offload_adam_step(opt, lr, beta1, beta2, eps, weight_decay, step, grad_scale, _stream(stream)))
+
+
+def axonn_offload_adam_device_bytes(opt):
+    b = _u64()
+    _check(load().axonn_offload_adam_device_bytes(opt, C.byref(b)))
+    return b.value
+
+
+def axonn_stage_optimizer_attach(st, host_master, host_m, host_v, n, bucket_elems):
+    _check(load().axonn_stage_optimizer_attach(st, _ptr(host_master), _ptr(host_m), _ptr(host_v), n, bucket_elems))
+
+
+def axonn_stage_optimizer_step(st, lr, beta1, beta2, eps, weight_decay, step, grad_scale, stream=None):
+    _check(load().axonn_stage_optimizer_step(st, lr, beta1, beta2, eps, weight_decay, step, grad_scale, _stream(stream)))
+
+
+def axonn_gemm_bf16(a_kcontig, b_kcontig, epilogue, M, N, K, A, lda, B, ldb, Cmat, ldc, bias=None, res=None,
+                    ld_res=0, aux=None, ld_aux=0, accumulate=0, stream=None):
+    _check(load().axonn_gemm_bf16(a_kcontig, b_kcontig, epilogue, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(Cmat),
+                                  ldc, _ptr(bias), _ptr(res), ld_res, _ptr(aux), ld_aux, accumulate, _stream(stream)))
+
+
+def axonn_layernorm_fwd(T, h, x, gamma, beta, eps, out, stats, stream=None):
+    _check(load().axonn_layernorm_fwd(T, h, _ptr(x), _ptr(gamma), _ptr(beta), eps, _ptr(out), _ptr(stats), _stream(stream)))
+
+
+def axonn_layernorm_bwd(T, h, dout, x, stats, gamma, res_grad, dx, dgamma, dbeta, workspace, stream=None):
+    _check(load().axonn_layernorm_bwd(T, h, _ptr(dout), _ptr(x), _ptr(stats), _ptr(gamma), _ptr(res_grad), _ptr(dx),
+                                      _ptr(dgamma), _ptr(dbeta), _ptr(workspace), _stream(stream)))
+
+
+def axonn_colsum(T, N, y, ldy, out, workspace, stream=None):
+    _check(load().axonn_colsum(T, N, _ptr(y), ldy, _ptr(out), _ptr(workspace), _stream(stream)))
+
+
+def axonn_attention_fwd(b, s, n_heads, head_dim, qkv, o, lse, stream=None):
+    _check(load().axonn_attention_fwd(b, s, n_heads, head_dim, _ptr(qkv), _ptr(o), _ptr(lse), _stream(stream)))
+
+
+def axonn_attention_bwd(b, s, n_heads, head_dim, qkv, o, lse, dout, dqkv, delta_ws, stream=None):
+    _check(load().axonn_attention_bwd(b, s, n_heads, head_dim, _ptr(qkv), _ptr(o), _ptr(lse), _ptr(dout), _ptr(dqkv),
+                                      _ptr(delta_ws), _stream(stream)))
+
+
+def axonn_adam_bucket(n, theta, m, v, grad16, param16, lr, beta1, beta2, eps, weight_decay, step, grad_scale,
+                      stream=None):
+    _check(load().axonn_adam_bucket(n, _ptr(theta), _ptr(m), _ptr(v), _ptr(grad16), _ptr(param16), lr, beta1, beta2,
+                                    eps, weight_decay, step, grad_scale, _stream(stream)))
+
+
+def make_config(shape, pipeline_limit=None, ln_eps=1e-5, device=0, grad_accum_fp32=1, n_microbatches=None):
+    """axonn_stage_config from a `inputs.StageShape`."""
+    M = shape.n_microbatches if n_microbatches is None else n_microbatches
+    return axonn_stage_config(shape.n_layers, shape.hidden, shape.n_heads, shape.ffn, shape.seq_len,
+                              shape.microbatch_size, M, M if pipeline_limit is None else pipeline_limit,
+                              ln_eps, device, grad_accum_fp32)

@@ -1,0 +1,457 @@
+// Fused causal self-attention for gfx950: forward (online softmax, never materialises the
+// s x s matrix in HBM) and backward (probabilities recomputed from the stored log-sum-exp).
+//
+// All contractions run on v_mfma_f32_32x32x16_bf16.  The kernels are arranged so that the
+// score tile comes out of the MFMA with the index that is contracted NEXT held in registers
+// and the other index on lanes; the rounded tile is then fed straight back as an MFMA operand
+// from registers (no LDS round trip):
+//   forward, dQ kernel : S^T[key][query] -> lane = query, so max / sum / lse / delta are
+//                        per-lane scalars; next contraction is over keys (P V, dS K).
+//   dK/dV kernel       : S[query][key]   -> lane = key; next contraction is over queries
+//                        (P^T dO, dS^T Q).
+// Operands whose contracted index is not contiguous in the [row][d] tiles (V, and Q / dO / K
+// in the backward kernels) are fetched with the transposing LDS read.
+#include "common.h"
+
+namespace axonn {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Cooperative copy of a ROWS x D bf16 tile (rows row0.., zero beyond n_rows) by 256 threads:
+// global -> registers, then registers -> LDS with leading dimension LD.
+template <int ROWS, int D>
+struct TileRegs {
+  static constexpr int NCH = ROWS * D / 8 / 256;
+  uint4 r[NCH];
+  __device__ __forceinline__ void load(const bf16_t* base, int64_t ld, int row0, int n_rows, int tid) {
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int c = tid + j * 256;
+      const int row = c / (D / 8), ch = c % (D / 8);
+      r[j] = (row0 + row < n_rows)
+                 ? *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + row) * ld + ch * 8)
+                 : make_uint4(0, 0, 0, 0);
+    }
+  }
+  template <int LD>
+  __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
+#pragma unroll
+    for (int j = 0; j < NCH; ++j) {
+      const int c = tid + j * 256;
+      *reinterpret_cast<uint4*>(lds + (c / (D / 8)) * LD + (c % (D / 8)) * 8) = r[j];
+    }
+  }
+};
+
+__device__ __forceinline__ bf16x8 pack8(const floatx16& t, int first) {
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (bf16_t)t[first + e];
+  return o;
+}
+
+// Row fragment straight from global memory: lane holds row (row0 + lane%32), elements
+// [k0 + 8*(lane/32), +8) -- the MFMA operand layout.  Rows >= n_rows read as zero.
+__device__ __forceinline__ bf16x8 global_frag(const bf16_t* base, int64_t ld, int row, int n_rows,
+                                              int k0, int lane) {
+  bf16x8 z;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) z[e] = (bf16_t)0.f;
+  if (row >= n_rows) return z;
+  return *reinterpret_cast<const bf16x8*>(base + (int64_t)row * ld + k0 + 8 * (lane >> 5));
+}
+
+// =============================================================================== forward
+// grid: (ceil(s/128), b*a); 4 waves; wave w owns queries q0 + 32w .. +31.
+template <int D>
+__global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int a, const bf16_t* __restrict__ qkv,
+                                                       bf16_t* __restrict__ o,
+                                                       float* __restrict__ lse) {
+  constexpr int BKV = 64, LDK = D + 8, LDV = D + 32, DT = D / 32, KK = D / 16;
+  __shared__ __align__(16) bf16_t sK[BKV * LDK];
+  __shared__ __align__(16) bf16_t sV[BKV * LDV];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+  const int qt = gridDim.x - 1 - blockIdx.x;  // longest rows first
+  const int bi = blockIdx.y / a, hd = blockIdx.y % a;
+  const int h = a * D;
+  const int64_t ld = 3 * (int64_t)h;
+  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * D;
+  const bf16_t* kb = qb + h;
+  const bf16_t* vb = qb + 2 * h;
+  const int q0 = qt * 128, qw0 = q0 + 32 * wave, qi = qw0 + (lane & 31);
+  const float scale_log2 = kLog2e * rsqrtf((float)D);
+
+  bf16x8 qf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) qf[kk] = global_frag(qb, ld, qi, s, kk * 16, lane);
+
+  floatx16 oacc[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+
+  const int kv_end = min(s, q0 + 128);
+  const int n_kt = (kv_end + BKV - 1) / BKV;
+  TileRegs<BKV, D> rk, rv;
+  rk.load(kb, ld, 0, s, tid);
+  rv.load(vb, ld, 0, s, tid);
+  for (int kt = 0; kt < n_kt; ++kt) {
+    const int k0 = kt * BKV;
+    __syncthreads();
+    rk.template store<LDK>(sK, tid);
+    rv.template store<LDV>(sV, tid);
+    __syncthreads();
+    if (kt + 1 < n_kt) {
+      rk.load(kb, ld, k0 + BKV, s, tid);
+      rv.load(vb, ld, k0 + BKV, s, tid);
+    }
+    if (k0 > qw0 + 31) continue;  // every key of the tile is in this wave's future
+
+    floatx16 sacc[2];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[ks][r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+        sacc[ks] = mfma32(frag_kcontig(sK + (32 * ks) * LDK + kk * 16, LDK, lane), qf[kk], sacc[ks]);
+    }
+    const bool need_mask = (k0 + BKV - 1 > qw0);
+    float mx = -INFINITY;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        float t = sacc[ks][r] * scale_log2;
+        if (need_mask) {
+          const int key = k0 + 32 * ks + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (key > qi) t = -INFINITY;
+        }
+        sacc[ks][r] = t;
+        mx = fmaxf(mx, t);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = fast_exp2(m_run - m_new);
+    m_run = m_new;
+    float psum = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = fast_exp2(sacc[ks][r] - m_new);
+        sacc[ks][r] = p;
+        psum += p;
+      }
+    l_run = l_run * alpha + psum;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const bf16x8 pf = pack8(sacc[ks], 8 * c);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+          oacc[dt] = mfma32(frag_kstrided<true>(sV + (32 * ks + 16 * c) * LDV + dt * 32, LDV, lane),
+                            pf, oacc[dt]);
+      }
+  }
+  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (qi < s) {
+    const float inv = 1.f / l_tot;
+    bf16_t* orow = o + ((int64_t)bi * s + qi) * h + hd * D;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(oacc[dt][4 * q + e] * inv);
+        *reinterpret_cast<bf16x4*>(orow + dt * 32 + 8 * q + 4 * g) = v;
+      }
+    if (g == 0) lse[((int64_t)bi * a + hd) * s + qi] = (m_run + __log2f(l_tot)) * kLn2;
+  }
+}
+
+// ============================================================================ backward
+// delta[b][a][i] = sum_d dO[i][d] * O[i][d]
+template <int D>
+__global__ __launch_bounds__(256) void attn_delta_kernel(int64_t n_chunks, int s, int a,
+                                                         const bf16_t* __restrict__ o,
+                                                         const bf16_t* __restrict__ dout,
+                                                         float* __restrict__ delta) {
+  constexpr int LPR = D / 8;  // lanes per (row, head)
+  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  float p = 0.f;
+  if (c < n_chunks) {
+    const bf16x8 ov = *reinterpret_cast<const bf16x8*>(o + c * 8);
+    const bf16x8 dv = *reinterpret_cast<const bf16x8*>(dout + c * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) p += (float)ov[e] * (float)dv[e];
+  }
+#pragma unroll
+  for (int off = LPR / 2; off > 0; off >>= 1) p += __shfl_xor(p, off, 64);
+  if (c < n_chunks && (c % LPR) == 0) {
+    const int64_t hc = a * (int64_t)LPR;  // chunks per row
+    const int64_t row = c / hc;
+    const int hd = (int)((c % hc) / LPR);
+    const int64_t bi = row / s, i = row % s;
+    delta[(bi * a + hd) * s + i] = p;
+  }
+}
+
+// dK / dV: grid (ceil(s/128), b*a); wave w owns keys k0 + 32w .. +31 and walks the query tiles
+// at or below the diagonal.
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
+    int s, int a, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+    const float* __restrict__ lse, const float* __restrict__ delta, bf16_t* __restrict__ dqkv) {
+  constexpr int BQ = 64, LDQ = D + 8, DT = D / 32, KK = D / 16;
+  __shared__ __align__(16) bf16_t sQ[BQ * LDQ];
+  __shared__ __align__(16) bf16_t sdO[BQ * LDQ];
+  __shared__ __align__(16) float s_lse[BQ];
+  __shared__ __align__(16) float s_delta[BQ];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+  const int bi = blockIdx.y / a, hd = blockIdx.y % a;
+  const int h = a * D;
+  const int64_t ld = 3 * (int64_t)h;
+  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * D;
+  const bf16_t* kb = qb + h;
+  const bf16_t* vb = qb + 2 * h;
+  const bf16_t* dob = dout + (int64_t)bi * s * h + hd * D;
+  const float* lse_b = lse + ((int64_t)bi * a + hd) * s;
+  const float* delta_b = delta + ((int64_t)bi * a + hd) * s;
+  const int k0 = blockIdx.x * 128, kw0 = k0 + 32 * wave, kj = kw0 + (lane & 31);
+  const float scale = rsqrtf((float)D), scale_log2 = kLog2e * scale;
+
+  bf16x8 kf[KK], vf[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    kf[kk] = global_frag(kb, ld, kj, s, kk * 16, lane);
+    vf[kk] = global_frag(vb, ld, kj, s, kk * 16, lane);
+  }
+  floatx16 dvacc[DT], dkacc[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dvacc[dt][r] = dkacc[dt][r] = 0.f;
+
+  const int qt_begin = k0 / BQ, n_qt = (s + BQ - 1) / BQ;
+  TileRegs<BQ, D> rq, rdo;
+  float r_lse = 0.f, r_delta = 0.f;
+  auto prefetch = [&](int qt) {
+    rq.load(qb, ld, qt * BQ, s, tid);
+    rdo.load(dob, h, qt * BQ, s, tid);
+    if (tid < BQ) {
+      const int qrow = qt * BQ + tid;
+      r_lse = qrow < s ? lse_b[qrow] : 0.f;
+      r_delta = qrow < s ? delta_b[qrow] : 0.f;
+    }
+  };
+  prefetch(qt_begin);
+  for (int qt = qt_begin; qt < n_qt; ++qt) {
+    const int q0 = qt * BQ;
+    __syncthreads();
+    rq.template store<LDQ>(sQ, tid);
+    rdo.template store<LDQ>(sdO, tid);
+    if (tid < BQ) {
+      s_lse[tid] = r_lse * kLog2e;
+      s_delta[tid] = r_delta;
+    }
+    __syncthreads();
+    if (qt + 1 < n_qt) prefetch(qt + 1);
+#pragma unroll
+    for (int qs = 0; qs < 2; ++qs) {
+      const int qq0 = q0 + 32 * qs;
+      if (qq0 + 31 < kw0) continue;  // all these queries precede every key of this wave
+      floatx16 sacc, pacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[r] = pacc[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        sacc = mfma32(frag_kcontig(sQ + (32 * qs) * LDQ + kk * 16, LDQ, lane), kf[kk], sacc);
+        pacc = mfma32(frag_kcontig(sdO + (32 * qs) * LDQ + kk * 16, LDQ, lane), vf[kk], pacc);
+      }
+      // lane = key kj; register r = query qq0 + 8*(r/4) + 4g + r%4
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const floatx4 l4 = *reinterpret_cast<const floatx4*>(&s_lse[32 * qs + 8 * q4 + 4 * g]);
+        const floatx4 d4 = *reinterpret_cast<const floatx4*>(&s_delta[32 * qs + 8 * q4 + 4 * g]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int r = 4 * q4 + e;
+          const int qrow = qq0 + 8 * q4 + 4 * g + e;
+          float p = fast_exp2(sacc[r] * scale_log2 - l4[e]);
+          if (kj > qrow) p = 0.f;
+          sacc[r] = p;
+          pacc[r] = p * (pacc[r] - d4[e]);
+        }
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const bf16x8 pf = pack8(sacc, 8 * c);
+        const bf16x8 dsf = pack8(pacc, 8 * c);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+          dvacc[dt] = mfma32(frag_kstrided<true>(sdO + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane),
+                             pf, dvacc[dt]);
+          dkacc[dt] = mfma32(frag_kstrided<true>(sQ + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane),
+                             dsf, dkacc[dt]);
+        }
+      }
+    }
+  }
+  if (kj < s) {
+    bf16_t* dk_row = dqkv + ((int64_t)bi * s + kj) * ld + h + hd * D;
+    bf16_t* dv_row = dk_row + h;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        bf16x4 kv4, vv4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          kv4[e] = (bf16_t)(dkacc[dt][4 * q + e] * scale);
+          vv4[e] = (bf16_t)dvacc[dt][4 * q + e];
+        }
+        *reinterpret_cast<bf16x4*>(dk_row + dt * 32 + 8 * q + 4 * g) = kv4;
+        *reinterpret_cast<bf16x4*>(dv_row + dt * 32 + 8 * q + 4 * g) = vv4;
+      }
+  }
+}
+
+// dQ: grid (ceil(s/128), b*a); wave w owns queries q0 + 32w .. +31 and walks the key tiles up
+// to the diagonal (same traversal as the forward kernel).
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
+    int s, int a, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+    const float* __restrict__ lse, const float* __restrict__ delta, bf16_t* __restrict__ dqkv) {
+  constexpr int BKV = 64, LDK = D + 8, DT = D / 32, KK = D / 16;
+  __shared__ __align__(16) bf16_t sK[BKV * LDK];
+  __shared__ __align__(16) bf16_t sV[BKV * LDK];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
+  const int qt = gridDim.x - 1 - blockIdx.x;
+  const int bi = blockIdx.y / a, hd = blockIdx.y % a;
+  const int h = a * D;
+  const int64_t ld = 3 * (int64_t)h;
+  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * D;
+  const bf16_t* kb = qb + h;
+  const bf16_t* vb = qb + 2 * h;
+  const bf16_t* dob = dout + (int64_t)bi * s * h + hd * D;
+  const int q0 = qt * 128, qw0 = q0 + 32 * wave, qi = qw0 + (lane & 31);
+  const float scale = rsqrtf((float)D), scale_log2 = kLog2e * scale;
+  const float lse_q = (qi < s) ? lse[((int64_t)bi * a + hd) * s + qi] * kLog2e : 0.f;
+  const float delta_q = (qi < s) ? delta[((int64_t)bi * a + hd) * s + qi] : 0.f;
+
+  bf16x8 qf[KK], dof[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    qf[kk] = global_frag(qb, ld, qi, s, kk * 16, lane);
+    dof[kk] = global_frag(dob, h, qi, s, kk * 16, lane);
+  }
+  floatx16 dqacc[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) dqacc[dt][r] = 0.f;
+
+  const int kv_end = min(s, q0 + 128);
+  const int n_kt = (kv_end + BKV - 1) / BKV;
+  TileRegs<BKV, D> rk, rv;
+  rk.load(kb, ld, 0, s, tid);
+  rv.load(vb, ld, 0, s, tid);
+  for (int kt = 0; kt < n_kt; ++kt) {
+    const int k0 = kt * BKV;
+    __syncthreads();
+    rk.template store<LDK>(sK, tid);
+    rv.template store<LDK>(sV, tid);
+    __syncthreads();
+    if (kt + 1 < n_kt) {
+      rk.load(kb, ld, k0 + BKV, s, tid);
+      rv.load(vb, ld, k0 + BKV, s, tid);
+    }
+    if (k0 > qw0 + 31) continue;
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      floatx16 sacc, pacc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sacc[r] = pacc[r] = 0.f;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        sacc = mfma32(frag_kcontig(sK + (32 * ks) * LDK + kk * 16, LDK, lane), qf[kk], sacc);
+        pacc = mfma32(frag_kcontig(sV + (32 * ks) * LDK + kk * 16, LDK, lane), dof[kk], pacc);
+      }
+      // lane = query qi; register r = key k0 + 32ks + 8*(r/4) + 4g + r%4
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = k0 + 32 * ks + 8 * (r >> 2) + 4 * g + (r & 3);
+        float p = fast_exp2(sacc[r] * scale_log2 - lse_q);
+        if (key > qi) p = 0.f;
+        pacc[r] = p * (pacc[r] - delta_q);
+      }
+#pragma unroll
+      for (int c = 0; c < 2; ++c) {
+        const bf16x8 dsf = pack8(pacc, 8 * c);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+          dqacc[dt] = mfma32(frag_kstrided<true>(sK + (32 * ks + 16 * c) * LDK + dt * 32, LDK, lane),
+                             dsf, dqacc[dt]);
+      }
+    }
+  }
+  if (qi < s) {
+    bf16_t* dq_row = dqkv + ((int64_t)bi * s + qi) * ld + hd * D;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        bf16x4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(dqacc[dt][4 * q + e] * scale);
+        *reinterpret_cast<bf16x4*>(dq_row + dt * 32 + 8 * q + 4 * g) = v;
+      }
+  }
+}
+
+// ------------------------------------------------------------------------- launchers
+hipError_t launch_attention_fwd(int b, int s, int a, int d, const void* qkv, void* o, float* lse,
+                                hipStream_t st) {
+  const dim3 grid((unsigned)((s + 127) / 128), (unsigned)(b * a));
+  if (d == 128)
+    hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (bf16_t*)o, lse);
+  else if (d == 64)
+    hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (bf16_t*)o, lse);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
+hipError_t launch_attention_bwd(int b, int s, int a, int d, const void* qkv, const void* o,
+                                const float* lse, const void* dout, void* dqkv, float* delta,
+                                hipStream_t st) {
+  const int64_t n_chunks = (int64_t)b * s * a * d / 8;
+  const dim3 gd((unsigned)((n_chunks + 255) / 256));
+  const dim3 grid((unsigned)((s + 127) / 128), (unsigned)(b * a));
+  if (d == 128) {
+    hipLaunchKernelGGL(attn_delta_kernel<128>, gd, dim3(256), 0, st, n_chunks, s, a, (const bf16_t*)o, (const bf16_t*)dout, delta);
+    hipLaunchKernelGGL(attn_bwd_dkdv_kernel<128>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+  } else if (d == 64) {
+    hipLaunchKernelGGL(attn_delta_kernel<64>, gd, dim3(256), 0, st, n_chunks, s, a, (const bf16_t*)o, (const bf16_t*)dout, delta);
+    hipLaunchKernelGGL(attn_bwd_dkdv_kernel<64>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+  } else {
+    return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace axonn

@@ -1,0 +1,128 @@
+// Shared declarations of libaxonn_stage: vector types, MFMA fragment helpers for gfx950,
+// wavefront reductions and the internal launch functions the stage runtime calls.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace axonn {
+
+typedef __bf16 bf16_t;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+
+#define AXONN_LDS __attribute__((address_space(3)))
+
+#ifdef __HIPCC__
+// ---------------------------------------------------------------------------------
+// v_mfma_f32_32x32x16_bf16 register layout (checked on hardware):
+//   operand X (either input): lane l holds X[row = l%32][k = 8*(l/32) + i], i = 0..7
+//   result D[m][n]:           lane l, register r holds n = l%32, m = 8*(r/4) + 4*(l/32) + r%4
+// D = first_operand(rows -> m) x second_operand(rows -> n).
+// ---------------------------------------------------------------------------------
+__device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Fragment of a 32(row) x 16(k) operand block from an LDS tile stored [row][k] (k
+// contiguous, `ld` elements per row).  `base` points at (row0, k0).
+__device__ __forceinline__ bf16x8 frag_kcontig(const bf16_t* base, int ld, int lane) {
+  return *reinterpret_cast<const bf16x8*>(base + (lane & 31) * ld + 8 * (lane >> 5));
+}
+
+// ds_read_b64_tr_b16 (checked on hardware): within each group of 16 lanes, lane t supplies
+// the address of 4 consecutive 16-bit values; lane t receives element t%4 of the values
+// addressed by lanes t/4, 4 + t/4, 8 + t/4, 12 + t/4.  So if lane t addresses
+// [k = kb + t/4][r = rb + 4*(t%4) .. +3] of a [k][r] tile, lane t ends up holding
+// r = rb + t for k = kb .. kb+3.
+__device__ __forceinline__ short4v lds_read_tr16(const bf16_t* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (AXONN_LDS short4v*)p);
+}
+
+// Fragment of a 32(row) x 16(k) operand block from an LDS tile stored [k][row] (row
+// contiguous, `ld` elements per k).  `base` points at (k0, row0).
+// PERM = false: register i of lane l holds k = k0 + 8*(l/32) + i (same convention as
+//               frag_kcontig, to pair with any other operand).
+// PERM = true:  register j of lane l holds k = k0 + 8*(j/4) + 4*(l/32) + j%4, which is the
+//               order in which an MFMA result tile keeps its m index in registers 0..7 --
+//               to pair with an operand built in registers from a result tile.
+template <bool PERM>
+__device__ __forceinline__ bf16x8 frag_kstrided(const bf16_t* base, int ld, int lane) {
+  const int t = lane & 15, half = (lane >> 4) & 1, g = lane >> 5;
+  const int kq = t >> 2, r = 16 * half + 4 * (t & 3);
+  const int k_a = PERM ? 4 * g : 8 * g;
+  const int k_b = PERM ? 8 + 4 * g : 8 * g + 4;
+  union { bf16x8 v; short4v h[2]; } u;
+  u.h[0] = lds_read_tr16(base + (k_a + kq) * ld + r);
+  u.h[1] = lds_read_tr16(base + (k_b + kq) * ld + r);
+  return u.v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+__device__ __forceinline__ float bf2f(bf16_t v) { return (float)v; }
+__device__ __forceinline__ bf16_t f2bf(float v) { return (bf16_t)v; }
+
+// Exact-form GeLU pieces: Phi(x) = 0.5*(1+erf(x/sqrt2)), phi(x) = exp(-x^2/2)/sqrt(2pi).
+__device__ __forceinline__ float gelu_f(float x) {
+  return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+}
+__device__ __forceinline__ float gelu_grad_f(float x) {
+  const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752440f));
+  return cdf + x * __expf(-0.5f * x * x) * 0.39894228040143267794f;
+}
+#endif  // __HIPCC__
+
+// --------------------------------------------------------------------- host launchers
+enum GemmEpilogue {
+  EPI_BIAS = 0, EPI_BIAS_RES = 1, EPI_BIAS_GELU = 2, EPI_DGELU = 3,
+  EPI_ACC_F32 = 4, EPI_ACC_BF16 = 5
+};
+
+struct GemmArgs {
+  const bf16_t* A; const bf16_t* B; void* C;
+  const bf16_t* bias; const bf16_t* res; bf16_t* aux;
+  int64_t lda, ldb, ldc, ld_res, ld_aux;
+  int M, N, K;
+  int accumulate;
+  int tiles_m, tiles_n;
+};
+
+// All return hipError_t of the launch (hipGetLastError) and validate nothing: callers check.
+hipError_t launch_gemm(bool a_kc, bool b_kc, int epilogue, const GemmArgs& g, hipStream_t s);
+hipError_t launch_layernorm_fwd(int64_t T, int64_t h, const void* x, const void* gamma,
+                                const void* beta, float eps, void* out, float* stats,
+                                hipStream_t s);
+hipError_t launch_layernorm_bwd(int64_t T, int64_t h, const void* dout, const void* x,
+                                const float* stats, const void* gamma, const void* res_grad,
+                                void* dx, float* dgamma, float* dbeta, float* ws, hipStream_t s);
+hipError_t launch_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, float* out,
+                         float* ws, hipStream_t s);
+// dst[i] (+)= src[i] for small fp32 vectors -> bf16 or fp32 gradient accumulators.
+hipError_t launch_accum_vec(int64_t n, const float* src, void* dst, bool dst_fp32,
+                            bool accumulate, hipStream_t s);
+hipError_t launch_f32_to_bf16(uint64_t n, const float* src, void* dst, hipStream_t s);
+hipError_t launch_fill_bf16(uint64_t n, void* dst, float value, hipStream_t s);
+hipError_t launch_attention_fwd(int b, int s, int a, int d, const void* qkv, void* o,
+                                float* lse, hipStream_t st);
+hipError_t launch_attention_bwd(int b, int s, int a, int d, const void* qkv, const void* o,
+                                const float* lse, const void* dout, void* dqkv, float* delta,
+                                hipStream_t st);
+hipError_t launch_adam(uint64_t n, float* theta, float* m, float* v, const void* g16,
+                       void* p16, float lr, float b1, float b2, float eps, float wd,
+                       int64_t step, float grad_scale, hipStream_t s);
+
+}  // namespace axonn

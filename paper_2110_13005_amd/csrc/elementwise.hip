@@ -1,0 +1,365 @@
+// HBM-bound kernels of the stage: LayerNorm forward / backward, column sums (bias and
+// LayerNorm parameter gradients), small accumulate / convert helpers and the Adam bucket
+// kernel.  All of them move 16-byte vectors per lane along the contiguous dimension and
+// reduce with wavefront shuffles; none of them uses atomics, so results are reproducible.
+#include "common.h"
+
+namespace axonn {
+
+// One wavefront per row: the row lives in registers (MAXC chunks of 8 bf16 per lane), so the
+// mean and the variance are the plain two-pass definitions computed from one HBM read.
+constexpr int LN_MAXC = 32;  // 32 chunks * 64 lanes * 8 = 16384 columns max
+constexpr int LN_ROWS_PER_BLOCK = 4;
+
+__global__ __launch_bounds__(64 * LN_ROWS_PER_BLOCK) void layernorm_fwd_kernel(
+    int T, int h, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
+    const bf16_t* __restrict__ beta, float eps, bf16_t* __restrict__ out,
+    float* __restrict__ stats) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * LN_ROWS_PER_BLOCK + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const int nch = h >> 3;
+  const bf16_t* xr = x + (int64_t)row * h;
+  bf16x8 v[LN_MAXC];
+  float sum = 0.f;
+#pragma unroll
+  for (int c = 0; c < LN_MAXC; ++c) {
+    const int ch = c * 64 + lane;
+    if (c * 64 < nch && ch < nch) {
+      v[c] = *reinterpret_cast<const bf16x8*>(xr + ch * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) sum += (float)v[c][e];
+    }
+  }
+  const float mean = wave_sum(sum) / (float)h;
+  float sq = 0.f;
+#pragma unroll
+  for (int c = 0; c < LN_MAXC; ++c) {
+    const int ch = c * 64 + lane;
+    if (c * 64 < nch && ch < nch) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float d = (float)v[c][e] - mean;
+        sq += d * d;
+      }
+    }
+  }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)h + eps);
+  if (lane == 0) {
+    stats[2 * (int64_t)row] = mean;
+    stats[2 * (int64_t)row + 1] = rstd;
+  }
+  bf16_t* orow = out + (int64_t)row * h;
+#pragma unroll
+  for (int c = 0; c < LN_MAXC; ++c) {
+    const int ch = c * 64 + lane;
+    if (c * 64 < nch && ch < nch) {
+      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gamma + ch * 8);
+      const bf16x8 bv = *reinterpret_cast<const bf16x8*>(beta + ch * 8);
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        o[e] = (bf16_t)((float)gv[e] * (((float)v[c][e] - mean) * rstd) + (float)bv[e]);
+      *reinterpret_cast<bf16x8*>(orow + ch * 8) = o;
+    }
+  }
+}
+
+// dx = res + rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)),  dxhat = dout * gamma
+__global__ __launch_bounds__(64 * LN_ROWS_PER_BLOCK) void layernorm_bwd_dx_kernel(
+    int T, int h, const bf16_t* __restrict__ dout, const bf16_t* __restrict__ x,
+    const float* __restrict__ stats, const bf16_t* __restrict__ gamma,
+    const bf16_t* __restrict__ res, bf16_t* __restrict__ dx) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * LN_ROWS_PER_BLOCK + (threadIdx.x >> 6);
+  if (row >= T) return;
+  const int nch = h >> 3;
+  const float mean = stats[2 * (int64_t)row], rstd = stats[2 * (int64_t)row + 1];
+  const bf16_t* xr = x + (int64_t)row * h;
+  const bf16_t* dr = dout + (int64_t)row * h;
+  bf16x8 xv[LN_MAXC], dv[LN_MAXC];
+  float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+  for (int c = 0; c < LN_MAXC; ++c) {
+    const int ch = c * 64 + lane;
+    if (c * 64 < nch && ch < nch) {
+      xv[c] = *reinterpret_cast<const bf16x8*>(xr + ch * 8);
+      dv[c] = *reinterpret_cast<const bf16x8*>(dr + ch * 8);
+      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gamma + ch * 8);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float dxh = (float)dv[c][e] * (float)gv[e];
+        const float xh = ((float)xv[c][e] - mean) * rstd;
+        s1 += dxh;
+        s2 += dxh * xh;
+      }
+    }
+  }
+  const float m1 = wave_sum(s1) / (float)h, m2 = wave_sum(s2) / (float)h;
+  bf16_t* orow = dx + (int64_t)row * h;
+#pragma unroll
+  for (int c = 0; c < LN_MAXC; ++c) {
+    const int ch = c * 64 + lane;
+    if (c * 64 < nch && ch < nch) {
+      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gamma + ch * 8);
+      bf16x8 rv;
+      if (res) rv = *reinterpret_cast<const bf16x8*>(res + (int64_t)row * h + ch * 8);
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float dxh = (float)dv[c][e] * (float)gv[e];
+        const float xh = ((float)xv[c][e] - mean) * rstd;
+        float r = rstd * (dxh - m1 - xh * m2);
+        if (res) r += (float)rv[e];
+        o[e] = (bf16_t)r;
+      }
+      *reinterpret_cast<bf16x8*>(orow + ch * 8) = o;
+    }
+  }
+}
+
+// Column partial sums over a block of 64 rows.  Each wave owns 512 columns (8 per lane) of
+// a 16-row quarter of the block; quarters are combined through LDS.  MODE 0: sum y.
+// MODE 1: sum y and sum y * xhat with xhat = (x - mean) * rstd (LayerNorm gain gradient).
+// partial layout: [row_block][MODE+1][ncols].
+constexpr int CS_ROWS = 64;
+template <int MODE>
+__global__ __launch_bounds__(256) void colsum_partial_kernel(
+    int T, int N, const bf16_t* __restrict__ y, int64_t ldy, const bf16_t* __restrict__ x,
+    const float* __restrict__ stats, float* __restrict__ partial) {
+  __shared__ float red[3][2][64][8];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int col = (blockIdx.x * 64 + lane) * 8;
+  const int r_begin = blockIdx.y * CS_ROWS + q * (CS_ROWS / 4);
+  float a0[8], a1[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) a0[e] = a1[e] = 0.f;
+  if (col < N) {
+    for (int r = r_begin; r < r_begin + CS_ROWS / 4 && r < T; ++r) {
+      const bf16x8 yv = *reinterpret_cast<const bf16x8*>(y + (int64_t)r * ldy + col);
+      if (MODE == 1) {
+        const bf16x8 xv = *reinterpret_cast<const bf16x8*>(x + (int64_t)r * N + col);
+        const float mean = stats[2 * (int64_t)r], rstd = stats[2 * (int64_t)r + 1];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          a0[e] += (float)yv[e];
+          a1[e] += (float)yv[e] * (((float)xv[e] - mean) * rstd);
+        }
+      } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a0[e] += (float)yv[e];
+      }
+    }
+  }
+  if (q > 0) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      red[q - 1][0][lane][e] = a0[e];
+      if (MODE == 1) red[q - 1][1][lane][e] = a1[e];
+    }
+  }
+  __syncthreads();
+  if (q == 0 && col < N) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      // fixed order q = 0,1,2,3 keeps the sum reproducible
+      a0[e] = ((a0[e] + red[0][0][lane][e]) + red[1][0][lane][e]) + red[2][0][lane][e];
+      if (MODE == 1) a1[e] = ((a1[e] + red[0][1][lane][e]) + red[1][1][lane][e]) + red[2][1][lane][e];
+    }
+    float* p0 = partial + ((int64_t)blockIdx.y * (MODE + 1)) * N + col;
+    *reinterpret_cast<floatx4*>(p0) = floatx4{a0[0], a0[1], a0[2], a0[3]};
+    *reinterpret_cast<floatx4*>(p0 + 4) = floatx4{a0[4], a0[5], a0[6], a0[7]};
+    if (MODE == 1) {
+      float* p1 = p0 + N;
+      *reinterpret_cast<floatx4*>(p1) = floatx4{a1[0], a1[1], a1[2], a1[3]};
+      *reinterpret_cast<floatx4*>(p1 + 4) = floatx4{a1[4], a1[5], a1[6], a1[7]};
+    }
+  }
+}
+
+// out[k][n] = sum over row blocks of partial[rb][k][n], k < KSUM.
+template <int KSUM>
+__global__ __launch_bounds__(256) void colsum_final_kernel(int nrb, int N,
+                                                           const float* __restrict__ partial,
+                                                           float* __restrict__ out0,
+                                                           float* __restrict__ out1) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  if (n >= N) return;
+  float s0 = 0.f, s1 = 0.f;
+  for (int rb = 0; rb < nrb; ++rb) {
+    s0 += partial[((int64_t)rb * KSUM) * N + n];
+    if (KSUM == 2) s1 += partial[((int64_t)rb * KSUM + 1) * N + n];
+  }
+  out0[n] = s0;
+  if (KSUM == 2) out1[n] = s1;
+}
+
+__global__ __launch_bounds__(256) void accum_vec_kernel(int64_t n, const float* __restrict__ src,
+                                                        void* __restrict__ dst, int dst_fp32,
+                                                        int accumulate) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  if (dst_fp32) {
+    float* d = reinterpret_cast<float*>(dst);
+    d[i] = (accumulate ? d[i] : 0.f) + src[i];
+  } else {
+    bf16_t* d = reinterpret_cast<bf16_t*>(dst);
+    d[i] = (bf16_t)((accumulate ? (float)d[i] : 0.f) + src[i]);
+  }
+}
+
+__global__ __launch_bounds__(256) void f32_to_bf16_kernel(uint64_t n8, uint64_t n,
+                                                          const float* __restrict__ src,
+                                                          bf16_t* __restrict__ dst) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
+    const floatx4 a = *reinterpret_cast<const floatx4*>(src + i * 8);
+    const floatx4 b = *reinterpret_cast<const floatx4*>(src + i * 8 + 4);
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { o[e] = (bf16_t)a[e]; o[4 + e] = (bf16_t)b[e]; }
+    *reinterpret_cast<bf16x8*>(dst + i * 8) = o;
+  }
+  if (blockIdx.x == 0) {
+    for (uint64_t i = n8 * 8 + threadIdx.x; i < n; i += 256) dst[i] = (bf16_t)src[i];
+  }
+}
+
+__global__ __launch_bounds__(256) void fill_bf16_kernel(uint64_t n, bf16_t* dst, float value) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  const bf16_t v = (bf16_t)value;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = v;
+}
+
+// Adam with decoupled weight decay on one resident bucket: per element 12 B of fp32 state and
+// 2 B of bf16 gradient in, 12 B of state and 2 B of bf16 parameter out.
+struct AdamConsts {
+  float lr, b1, b2, eps, wd, grad_scale, inv_bc1, inv_bc2;
+};
+__device__ __forceinline__ void adam_elem(float& th, float& m, float& v, float g16,
+                                          const AdamConsts& c) {
+  const float g = c.grad_scale * g16;
+  m = c.b1 * m + (1.f - c.b1) * g;
+  v = c.b2 * v + (1.f - c.b2) * g * g;
+  const float mhat = m * c.inv_bc1;
+  const float vhat = v * c.inv_bc2;
+  th = th - c.lr * (mhat / (sqrtf(vhat) + c.eps) + c.wd * th);
+}
+__global__ __launch_bounds__(256) void adam_kernel(uint64_t n8, uint64_t n, float* __restrict__ theta,
+                                                   float* __restrict__ m, float* __restrict__ v,
+                                                   const bf16_t* __restrict__ g16,
+                                                   bf16_t* __restrict__ p16, AdamConsts c) {
+  const uint64_t stride = (uint64_t)gridDim.x * 256;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
+    const uint64_t o = i * 8;
+    floatx4 t0 = *reinterpret_cast<const floatx4*>(theta + o), t1 = *reinterpret_cast<const floatx4*>(theta + o + 4);
+    floatx4 m0 = *reinterpret_cast<const floatx4*>(m + o), m1 = *reinterpret_cast<const floatx4*>(m + o + 4);
+    floatx4 v0 = *reinterpret_cast<const floatx4*>(v + o), v1 = *reinterpret_cast<const floatx4*>(v + o + 4);
+    const bf16x8 gv = *reinterpret_cast<const bf16x8*>(g16 + o);
+    bf16x8 pv;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      float a = t0[e], b = m0[e], d = v0[e];
+      adam_elem(a, b, d, (float)gv[e], c);
+      t0[e] = a; m0[e] = b; v0[e] = d; pv[e] = (bf16_t)a;
+      a = t1[e]; b = m1[e]; d = v1[e];
+      adam_elem(a, b, d, (float)gv[4 + e], c);
+      t1[e] = a; m1[e] = b; v1[e] = d; pv[4 + e] = (bf16_t)a;
+    }
+    *reinterpret_cast<floatx4*>(theta + o) = t0; *reinterpret_cast<floatx4*>(theta + o + 4) = t1;
+    *reinterpret_cast<floatx4*>(m + o) = m0; *reinterpret_cast<floatx4*>(m + o + 4) = m1;
+    *reinterpret_cast<floatx4*>(v + o) = v0; *reinterpret_cast<floatx4*>(v + o + 4) = v1;
+    *reinterpret_cast<bf16x8*>(p16 + o) = pv;
+  }
+  if (blockIdx.x == 0) {
+    for (uint64_t i = n8 * 8 + threadIdx.x; i < n; i += 256) {
+      float a = theta[i], b = m[i], d = v[i];
+      adam_elem(a, b, d, (float)g16[i], c);
+      theta[i] = a; m[i] = b; v[i] = d; p16[i] = (bf16_t)a;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------- launchers
+hipError_t launch_layernorm_fwd(int64_t T, int64_t h, const void* x, const void* gamma,
+                                const void* beta, float eps, void* out, float* stats,
+                                hipStream_t s) {
+  const dim3 grid((unsigned)((T + LN_ROWS_PER_BLOCK - 1) / LN_ROWS_PER_BLOCK));
+  hipLaunchKernelGGL(layernorm_fwd_kernel, grid, dim3(64 * LN_ROWS_PER_BLOCK), 0, s, (int)T, (int)h,
+                     (const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, eps,
+                     (bf16_t*)out, stats);
+  return hipGetLastError();
+}
+
+hipError_t launch_layernorm_bwd(int64_t T, int64_t h, const void* dout, const void* x,
+                                const float* stats, const void* gamma, const void* res_grad,
+                                void* dx, float* dgamma, float* dbeta, float* ws, hipStream_t s) {
+  const dim3 grid((unsigned)((T + LN_ROWS_PER_BLOCK - 1) / LN_ROWS_PER_BLOCK));
+  hipLaunchKernelGGL(layernorm_bwd_dx_kernel, grid, dim3(64 * LN_ROWS_PER_BLOCK), 0, s, (int)T,
+                     (int)h, (const bf16_t*)dout, (const bf16_t*)x, stats, (const bf16_t*)gamma,
+                     (const bf16_t*)res_grad, (bf16_t*)dx);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const int nrb = (int)((T + CS_ROWS - 1) / CS_ROWS);
+  const dim3 g2((unsigned)((h + 511) / 512), (unsigned)nrb);
+  hipLaunchKernelGGL(colsum_partial_kernel<1>, g2, dim3(256), 0, s, (int)T, (int)h,
+                     (const bf16_t*)dout, (int64_t)h, (const bf16_t*)x, stats, ws);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colsum_final_kernel<2>, dim3((unsigned)((h + 255) / 256)), dim3(256), 0, s, nrb,
+                     (int)h, (const float*)ws, dbeta, dgamma);
+  return hipGetLastError();
+}
+
+hipError_t launch_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, float* out, float* ws,
+                         hipStream_t s) {
+  const int nrb = (int)((T + CS_ROWS - 1) / CS_ROWS);
+  const dim3 g2((unsigned)((N + 511) / 512), (unsigned)nrb);
+  hipLaunchKernelGGL(colsum_partial_kernel<0>, g2, dim3(256), 0, s, (int)T, (int)N,
+                     (const bf16_t*)y, ldy, (const bf16_t*)nullptr, (const float*)nullptr, ws);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(colsum_final_kernel<1>, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, nrb,
+                     (int)N, (const float*)ws, out, (float*)nullptr);
+  return hipGetLastError();
+}
+
+hipError_t launch_accum_vec(int64_t n, const float* src, void* dst, bool dst_fp32, bool accumulate,
+                            hipStream_t s) {
+  hipLaunchKernelGGL(accum_vec_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, src,
+                     dst, dst_fp32 ? 1 : 0, accumulate ? 1 : 0);
+  return hipGetLastError();
+}
+
+static unsigned grid_for(uint64_t work_items) {
+  uint64_t b = (work_items + 255) / 256;
+  if (b < 1) b = 1;
+  if (b > 256 * 16) b = 256 * 16;  // 16 blocks per CU, grid-stride beyond
+  return (unsigned)b;
+}
+
+hipError_t launch_f32_to_bf16(uint64_t n, const float* src, void* dst, hipStream_t s) {
+  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(grid_for(n / 8)), dim3(256), 0, s, n / 8, n, src,
+                     (bf16_t*)dst);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_bf16(uint64_t n, void* dst, float value, hipStream_t s) {
+  hipLaunchKernelGGL(fill_bf16_kernel, dim3(grid_for(n)), dim3(256), 0, s, n, (bf16_t*)dst, value);
+  return hipGetLastError();
+}
+
+hipError_t launch_adam(uint64_t n, float* theta, float* m, float* v, const void* g16, void* p16,
+                       float lr, float b1, float b2, float eps, float wd, int64_t step,
+                       float grad_scale, hipStream_t s) {
+  AdamConsts c;
+  c.lr = lr; c.b1 = b1; c.b2 = b2; c.eps = eps; c.wd = wd; c.grad_scale = grad_scale;
+  // bias corrections in double on the host: 1 - beta^t loses digits in float for beta near 1
+  c.inv_bc1 = (float)(1.0 / (1.0 - pow((double)b1, (double)step)));
+  c.inv_bc2 = (float)(1.0 / (1.0 - pow((double)b2, (double)step)));
+  hipLaunchKernelGGL(adam_kernel, dim3(grid_for(n / 8)), dim3(256), 0, s, n / 8, n, theta, m, v,
+                     (const bf16_t*)g16, (bf16_t*)p16, c);
+  return hipGetLastError();
+}
+
+}  // namespace axonn

@@ -1,0 +1,262 @@
+// bf16 MFMA GEMM family for gfx950 with fused epilogues.
+//
+//   C[m][n] = epilogue( sum_k Aop(m,k) * Bop(n,k) ),  fp32 accumulation.
+//
+// Each operand is either "k-contiguous" (stored [row][k]) or "k-strided" (stored [k][row]);
+// the three linear-layer contractions of a transformer layer map onto it as
+//   forward  y  = x W        : A k-contiguous, B k-strided   (W is [in,out])
+//   dgrad    dx = dy W^T     : A k-contiguous, B k-contiguous
+//   wgrad    dW = x^T dy     : A k-strided,    B k-strided
+// A block computes a BM x BN tile with WGM x WGN waves; tiles of A and B stream through a
+// double-buffered LDS stage (global -> registers -> LDS, one barrier per k-step).  k-contiguous
+// tiles are read back with 128-bit LDS loads, k-strided tiles with the transposing LDS load,
+// so no operand is ever transposed in HBM.  The MFMA is issued with the B fragment first, so a
+// lane of the result owns one row m and runs of 4 consecutive columns n: epilogue loads and
+// stores are 8-byte (bf16) or 16-byte (fp32) vectors along the contiguous dimension of C.
+#include "common.h"
+
+namespace axonn {
+
+template <int ROWS, int BK, bool KC>
+struct TileLayout {
+  // leading dimension in elements, padded so that fragment reads spread over LDS banks
+  static constexpr int LD = KC ? (BK + 8) : (ROWS + 32);
+  static constexpr int ELEMS = KC ? ROWS * LD : BK * LD;
+};
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
+  constexpr int NT = WGM * WGN * 64;
+  constexpr int WTM = BM / WGM, WTN = BN / WGN;
+  constexpr int TM = WTM / 32, TN = WTN / 32;
+  using LA = TileLayout<BM, BK, A_KC>;
+  using LB = TileLayout<BN, BK, B_KC>;
+  constexpr int A_CH = BM * BK / 8 / NT;  // 16-byte chunks per thread per tile
+  constexpr int B_CH = BN * BK / 8 / NT;
+  static_assert(A_CH >= 1 && B_CH >= 1, "tile too small for the block");
+  static_assert((BM * BK / 8) % NT == 0 && (BN * BK / 8) % NT == 0, "tile/threads mismatch");
+
+  __shared__ __align__(16) bf16_t sA[2][LA::ELEMS];
+  __shared__ __align__(16) bf16_t sB[2][LB::ELEMS];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WGN, wn = wave % WGN;
+
+  // Workgroups are dealt round-robin to the 8 XCDs; remap so that each XCD (own L2) works on
+  // a contiguous run of tiles, ordered m-fastest so that neighbours share the B panel.
+  int pid = blockIdx.x;
+  const int nblk = gridDim.x;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  const int tm = pid % g.tiles_m, tn = pid / g.tiles_m;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  uint4 ra[A_CH], rb[B_CH];
+
+  auto gload = [&](int kt) {
+    const int k0 = kt * BK;
+#pragma unroll
+    for (int j = 0; j < A_CH; ++j) {
+      const int c = tid + j * NT;
+      if (A_KC) {
+        const int row = c / (BK / 8), kc = c % (BK / 8);
+        const int m = m0 + row, k = k0 + kc * 8;
+        ra[j] = (m < g.M && k < g.K) ? *reinterpret_cast<const uint4*>(g.A + (int64_t)m * g.lda + k) : zero4;
+      } else {
+        const int kr = c / (BM / 8), rc = c % (BM / 8);
+        const int m = m0 + rc * 8, k = k0 + kr;
+        ra[j] = (m < g.M && k < g.K) ? *reinterpret_cast<const uint4*>(g.A + (int64_t)k * g.lda + m) : zero4;
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < B_CH; ++j) {
+      const int c = tid + j * NT;
+      if (B_KC) {
+        const int row = c / (BK / 8), kc = c % (BK / 8);
+        const int n = n0 + row, k = k0 + kc * 8;
+        rb[j] = (n < g.N && k < g.K) ? *reinterpret_cast<const uint4*>(g.B + (int64_t)n * g.ldb + k) : zero4;
+      } else {
+        const int kr = c / (BN / 8), rc = c % (BN / 8);
+        const int n = n0 + rc * 8, k = k0 + kr;
+        rb[j] = (n < g.N && k < g.K) ? *reinterpret_cast<const uint4*>(g.B + (int64_t)k * g.ldb + n) : zero4;
+      }
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < A_CH; ++j) {
+      const int c = tid + j * NT;
+      const int off = A_KC ? (c / (BK / 8)) * LA::LD + (c % (BK / 8)) * 8
+                           : (c / (BM / 8)) * LA::LD + (c % (BM / 8)) * 8;
+      *reinterpret_cast<uint4*>(&sA[buf][off]) = ra[j];
+    }
+#pragma unroll
+    for (int j = 0; j < B_CH; ++j) {
+      const int c = tid + j * NT;
+      const int off = B_KC ? (c / (BK / 8)) * LB::LD + (c % (BK / 8)) * 8
+                           : (c / (BN / 8)) * LB::LD + (c % (BN / 8)) * 8;
+      *reinterpret_cast<uint4*>(&sB[buf][off]) = rb[j];
+    }
+  };
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = (g.K + BK - 1) / BK;
+  gload(0);
+  sstore(0);
+  if (nk > 1) gload(1);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) sstore(cur ^ 1);
+    if (kt + 2 < nk) gload(kt + 2);
+    const bf16_t* a_s = sA[cur];
+    const bf16_t* b_s = sB[cur];
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 fa[TM], fb[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        const int r0 = wm * WTM + i * 32;
+        fa[i] = A_KC ? frag_kcontig(a_s + r0 * LA::LD + kk * 16, LA::LD, lane)
+                     : frag_kstrided<false>(a_s + (kk * 16) * LA::LD + r0, LA::LD, lane);
+      }
+#pragma unroll
+      for (int j = 0; j < TN; ++j) {
+        const int r0 = wn * WTN + j * 32;
+        fb[j] = B_KC ? frag_kcontig(b_s + r0 * LB::LD + kk * 16, LB::LD, lane)
+                     : frag_kstrided<false>(b_s + (kk * 16) * LB::LD + r0, LB::LD, lane);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = mfma32(fb[j], fa[i], acc[i][j]);
+    }
+    __syncthreads();
+  }
+
+  // ------------------------------------------------------------------ epilogue
+  // lane owns row m = .. + lane%32; register r of tile (i,j) is column 8*(r/4)+4*(lane/32)+r%4
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = m0 + wm * WTM + i * 32 + (lane & 31);
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int n = n0 + wn * WTN + j * 32 + 8 * q + 4 * (lane >> 5);
+        if (n >= g.N) continue;
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
+        if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
+          if (g.bias) {
+            const bf16x4 bv = *reinterpret_cast<const bf16x4*>(g.bias + n);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += (float)bv[e];
+          }
+        }
+        if (EPI == EPI_BIAS_RES) {
+          const bf16x4 rv = *reinterpret_cast<const bf16x4*>(g.res + (int64_t)m * g.ld_res + n);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
+        }
+        if (EPI == EPI_BIAS_GELU) {
+          bf16x4 pv;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) { pv[e] = (bf16_t)v[e]; v[e] = gelu_f(v[e]); }
+          *reinterpret_cast<bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n) = pv;
+        }
+        if (EPI == EPI_DGELU) {
+          const bf16x4 pv = *reinterpret_cast<const bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f((float)pv[e]);
+        }
+        if (EPI == EPI_ACC_F32) {
+          float* cp = reinterpret_cast<float*>(g.C) + (int64_t)m * g.ldc + n;
+          floatx4 o;
+          if (g.accumulate) {
+            o = *reinterpret_cast<const floatx4*>(cp);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] += v[e];
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) o[e] = v[e];
+          }
+          *reinterpret_cast<floatx4*>(cp) = o;
+        } else {
+          bf16_t* cp = reinterpret_cast<bf16_t*>(g.C) + (int64_t)m * g.ldc + n;
+          if (EPI == EPI_ACC_BF16 && g.accumulate) {
+            const bf16x4 cv = *reinterpret_cast<const bf16x4*>(cp);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] += (float)cv[e];
+          }
+          bf16x4 o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
+          *reinterpret_cast<bf16x4*>(cp) = o;
+        }
+      }
+    }
+  }
+}
+
+// Only the (layout, epilogue) pairs the layer uses are instantiated: forward maps take the
+// bias epilogues, input gradients the plain / GeLU' ones, weight gradients the accumulating ones.
+constexpr bool epilogue_allowed(bool a_kc, bool b_kc, int e) {
+  if (a_kc && !b_kc) return e == EPI_BIAS || e == EPI_BIAS_RES || e == EPI_BIAS_GELU;
+  if (a_kc && b_kc) return e == EPI_BIAS || e == EPI_DGELU;
+  if (!a_kc && !b_kc) return e == EPI_ACC_F32 || e == EPI_ACC_BF16;
+  return false;
+}
+
+template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC>
+static hipError_t launch_cfg(int epi, GemmArgs g, hipStream_t s) {
+  g.tiles_m = (g.M + BM - 1) / BM;
+  g.tiles_n = (g.N + BN - 1) / BN;
+  const dim3 grid(g.tiles_m * g.tiles_n), block(WGM * WGN * 64);
+#define AXONN_GEMM_CASE(E)                                                                      \
+  case E:                                                                                       \
+    if constexpr (epilogue_allowed(A_KC, B_KC, E)) {                                            \
+      hipLaunchKernelGGL((gemm_kernel<BM, BN, BK, WGM, WGN, A_KC, B_KC, E>), grid, block, 0, s, g); \
+      break;                                                                                    \
+    } else {                                                                                    \
+      return hipErrorInvalidValue;                                                              \
+    }
+  switch (epi) {
+    AXONN_GEMM_CASE(EPI_BIAS)
+    AXONN_GEMM_CASE(EPI_BIAS_RES)
+    AXONN_GEMM_CASE(EPI_BIAS_GELU)
+    AXONN_GEMM_CASE(EPI_DGELU)
+    AXONN_GEMM_CASE(EPI_ACC_F32)
+    AXONN_GEMM_CASE(EPI_ACC_BF16)
+    default: return hipErrorInvalidValue;
+  }
+#undef AXONN_GEMM_CASE
+  return hipGetLastError();
+}
+
+template <bool A_KC, bool B_KC>
+static hipError_t launch_layout(int epi, const GemmArgs& g, hipStream_t s) {
+  // Large tile when the problem fills the chip with it, smaller tile otherwise.
+  const int64_t big_tiles = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);
+  if (big_tiles >= 128) return launch_cfg<256, 256, 64, 2, 4, A_KC, B_KC>(epi, g, s);
+  return launch_cfg<128, 128, 64, 2, 2, A_KC, B_KC>(epi, g, s);
+}
+
+hipError_t launch_gemm(bool a_kc, bool b_kc, int epi, const GemmArgs& g, hipStream_t s) {
+  if (a_kc && b_kc) return launch_layout<true, true>(epi, g, s);
+  if (a_kc && !b_kc) return launch_layout<true, false>(epi, g, s);
+  if (!a_kc && !b_kc) return launch_layout<false, false>(epi, g, s);
+  return hipErrorInvalidValue;
+}
+
+}  // namespace axonn

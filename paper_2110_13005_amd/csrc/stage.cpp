@@ -1,0 +1,848 @@
+// Host runtime and C ABI of libaxonn_stage: the stage handle (flat parameter / gradient
+// buffers, activation stash slots, backward workspace), the per-layer forward and backward
+// launch sequences, the message-driven scheduler of Alg. 2 and the bucketed offloaded Adam
+// pipeline of Sec. 5.2.  No kernels live here; see gemm.hip, attention.hip, elementwise.hip.
+#include "../../include/axonn_stage.h"
+#include "common.h"
+
+#include <chrono>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <deque>
+#include <new>
+#include <string>
+#include <thread>
+#include <vector>
+
+using namespace axonn;
+
+namespace {
+
+thread_local std::string g_last_error;
+
+int fail(int code, const char* fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_last_error = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                     \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess)                                                                 \
+      return fail(e_ == hipErrorOutOfMemory ? AXONN_ENOMEM : AXONN_EHIP, "%s failed: %s", \
+                  #expr, hipGetErrorString(e_));                                          \
+  } while (0)
+
+#define AX_TRY(expr)       \
+  do {                     \
+    int r_ = (expr);       \
+    if (r_ != AXONN_OK) return r_; \
+  } while (0)
+
+constexpr int kTensorsPerLayer = 12;
+const char* const kTensorNames[kTensorsPerLayer] = {
+    "ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
+    "ln2_g", "ln2_b", "w_fc1", "b_fc1", "w_fc2", "b_fc2"};
+enum { P_LN1G, P_LN1B, P_WQKV, P_BQKV, P_WO, P_BO, P_LN2G, P_LN2B, P_WFC1, P_BFC1, P_WFC2, P_BFC2 };
+
+struct TensorInfo {
+  std::string name;
+  uint64_t offset;
+  int rank;
+  int64_t dims[4];
+  uint64_t numel;
+};
+
+struct LayerStash {
+  bf16_t *x, *u, *qkv, *o, *y, *w, *pre, *g;
+  float *stats1, *stats2, *lse;
+};
+
+struct Slot {
+  int mb_id = -1;
+  char* base = nullptr;
+  std::vector<LayerStash> layers;
+  hipEvent_t fwd_done = nullptr, bwd_done = nullptr;
+  bool bwd_recorded = false;
+};
+
+struct PendingMsg {
+  axonn_msg m;
+};
+
+uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+struct axonn_offload_adam {
+  int device = 0;
+  uint64_t n = 0, bucket = 0;
+  bf16_t* p16 = nullptr;
+  const bf16_t* g16 = nullptr;
+  float *h_theta = nullptr, *h_m = nullptr, *h_v = nullptr;
+  static constexpr int kSets = 3;  // one being filled, one being updated, one being drained
+  float* d_buf[kSets][3] = {};
+  hipStream_t s_h2d = nullptr, s_k = nullptr, s_d2h = nullptr;
+  hipEvent_t ev_start = nullptr, ev_h2d[kSets] = {}, ev_k[kSets] = {}, ev_d2h[kSets] = {};
+  bool d2h_recorded[kSets] = {};
+  uint64_t device_bytes = 0;
+};
+
+struct axonn_stage {
+  axonn_stage_config cfg;
+  int T = 0, h = 0, f = 0, d = 0;
+  uint64_t n_params = 0;
+  std::vector<TensorInfo> tensors;
+  bf16_t* params = nullptr;
+  bf16_t* grads = nullptr;
+  float* grads32 = nullptr;
+  std::vector<Slot> slots;
+  uint64_t slot_bytes = 0;
+  // backward workspace
+  char* ws_base = nullptr;
+  uint64_t ws_bytes = 0;
+  bf16_t *dres[2] = {}, *dy_mid = nullptr, *dpre = nullptr, *dw = nullptr, *dattn = nullptr,
+         *dqkv = nullptr, *du = nullptr;
+  float *delta = nullptr, *red_ws = nullptr, *vec0 = nullptr, *vec1 = nullptr;
+  // state
+  int in_flight = 0;
+  int bwd_count = 0;  // backwards since the last zero_grad
+  hipEvent_t last_bwd = nullptr;
+  bool last_bwd_recorded = false;
+  // message-driven mode
+  std::deque<PendingMsg> inbox;
+  std::vector<hipStream_t> streams;
+  std::vector<hipEvent_t> stream_tail;
+  int fwd_rr = 0;
+  int fwd_issued = 0, bwd_issued = 0;  // within the current batch (run mode)
+  std::vector<int32_t> dispatch_log;
+  axonn_offload_adam* opt = nullptr;
+};
+
+namespace {
+
+bf16_t* param_ptr(axonn_stage* st, int layer, int which) {
+  return st->params + st->tensors[layer * kTensorsPerLayer + which].offset;
+}
+void* grad_ptr(axonn_stage* st, int layer, int which) {
+  const uint64_t off = st->tensors[layer * kTensorsPerLayer + which].offset;
+  return st->cfg.grad_accum_fp32 ? (void*)(st->grads32 + off) : (void*)(st->grads + off);
+}
+
+int check_launch(hipError_t e, const char* what) {
+  if (e != hipSuccess) return fail(AXONN_EHIP, "launch of %s failed: %s", what, hipGetErrorString(e));
+  return AXONN_OK;
+}
+
+int gemm(bool a_kc, bool b_kc, int epi, int M, int N, int K, const void* A, int64_t lda,
+         const void* B, int64_t ldb, void* C, int64_t ldc, const void* bias, const void* res,
+         int64_t ld_res, void* aux, int64_t ld_aux, int accumulate, hipStream_t s) {
+  GemmArgs g;
+  g.A = (const bf16_t*)A; g.B = (const bf16_t*)B; g.C = C;
+  g.bias = (const bf16_t*)bias; g.res = (const bf16_t*)res; g.aux = (bf16_t*)aux;
+  g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ld_res = ld_res; g.ld_aux = ld_aux;
+  g.M = M; g.N = N; g.K = K; g.accumulate = accumulate; g.tiles_m = g.tiles_n = 0;
+  return check_launch(launch_gemm(a_kc, b_kc, epi, g, s), "gemm");
+}
+
+// -------------------------------------------------------------------- forward of a slot
+int forward_layers(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s) {
+  const int T = st->T, h = st->h, f = st->f, L = st->cfg.n_layers;
+  for (int l = 0; l < L; ++l) {
+    LayerStash& a = slot.layers[l];
+    bf16_t* z = (l + 1 < L) ? slot.layers[l + 1].x : (bf16_t*)y_out;
+    AX_TRY(check_launch(launch_layernorm_fwd(T, h, a.x, param_ptr(st, l, P_LN1G), param_ptr(st, l, P_LN1B),
+                                             st->cfg.ln_eps, a.u, a.stats1, s), "layernorm_fwd"));
+    AX_TRY(gemm(true, false, EPI_BIAS, T, 3 * h, h, a.u, h, param_ptr(st, l, P_WQKV), 3 * h, a.qkv, 3 * h,
+                param_ptr(st, l, P_BQKV), nullptr, 0, nullptr, 0, 0, s));
+    AX_TRY(check_launch(launch_attention_fwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d,
+                                             a.qkv, a.o, a.lse, s), "attention_fwd"));
+    AX_TRY(gemm(true, false, EPI_BIAS_RES, T, h, h, a.o, h, param_ptr(st, l, P_WO), h, a.y, h,
+                param_ptr(st, l, P_BO), a.x, h, nullptr, 0, 0, s));
+    AX_TRY(check_launch(launch_layernorm_fwd(T, h, a.y, param_ptr(st, l, P_LN2G), param_ptr(st, l, P_LN2B),
+                                             st->cfg.ln_eps, a.w, a.stats2, s), "layernorm_fwd"));
+    AX_TRY(gemm(true, false, EPI_BIAS_GELU, T, f, h, a.w, h, param_ptr(st, l, P_WFC1), f, a.g, f,
+                param_ptr(st, l, P_BFC1), nullptr, 0, a.pre, f, 0, s));
+    AX_TRY(gemm(true, false, EPI_BIAS_RES, T, h, f, a.g, f, param_ptr(st, l, P_WFC2), h, z, h,
+                param_ptr(st, l, P_BFC2), a.y, h, nullptr, 0, 0, s));
+  }
+  return AXONN_OK;
+}
+
+// ------------------------------------------------------------------- backward of a slot
+int vec_grad(axonn_stage* st, int layer, int which, const float* src, int n, int acc, hipStream_t s) {
+  return check_launch(launch_accum_vec(n, src, grad_ptr(st, layer, which), st->cfg.grad_accum_fp32 != 0,
+                                       acc != 0, s), "accum_vec");
+}
+
+int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out, int acc, hipStream_t s) {
+  const int T = st->T, h = st->h, f = st->f, L = st->cfg.n_layers;
+  const int wg_epi = st->cfg.grad_accum_fp32 ? EPI_ACC_F32 : EPI_ACC_BF16;
+  const bf16_t* d_in = (const bf16_t*)dy_in;
+  for (int l = L - 1; l >= 0; --l) {
+    LayerStash& a = slot.layers[l];
+    bf16_t* d_out = (l == 0) ? (bf16_t*)dx_out : st->dres[l & 1];
+    // z = y + g W2 + b2
+    AX_TRY(gemm(true, true, EPI_DGELU, T, f, h, d_in, h, param_ptr(st, l, P_WFC2), h, st->dpre, f,
+                nullptr, nullptr, 0, a.pre, f, 0, s));
+    AX_TRY(gemm(false, false, wg_epi, f, h, T, a.g, f, d_in, h, grad_ptr(st, l, P_WFC2), h,
+                nullptr, nullptr, 0, nullptr, 0, acc, s));
+    AX_TRY(check_launch(launch_colsum(T, h, d_in, h, st->vec0, st->red_ws, s), "colsum"));
+    AX_TRY(vec_grad(st, l, P_BFC2, st->vec0, h, acc, s));
+    // pre = w W1 + b1
+    AX_TRY(gemm(true, true, EPI_BIAS, T, h, f, st->dpre, f, param_ptr(st, l, P_WFC1), f, st->dw, h,
+                nullptr, nullptr, 0, nullptr, 0, 0, s));
+    AX_TRY(gemm(false, false, wg_epi, h, f, T, a.w, h, st->dpre, f, grad_ptr(st, l, P_WFC1), f,
+                nullptr, nullptr, 0, nullptr, 0, acc, s));
+    AX_TRY(check_launch(launch_colsum(T, f, st->dpre, f, st->vec0, st->red_ws, s), "colsum"));
+    AX_TRY(vec_grad(st, l, P_BFC1, st->vec0, f, acc, s));
+    // w = LN2(y); residual: dy = d_in + dLN2
+    AX_TRY(check_launch(launch_layernorm_bwd(T, h, st->dw, a.y, a.stats2, param_ptr(st, l, P_LN2G), d_in,
+                                             st->dy_mid, st->vec0, st->vec1, st->red_ws, s), "layernorm_bwd"));
+    AX_TRY(vec_grad(st, l, P_LN2G, st->vec0, h, acc, s));
+    AX_TRY(vec_grad(st, l, P_LN2B, st->vec1, h, acc, s));
+    // y = x + o Wo + bo
+    AX_TRY(gemm(true, true, EPI_BIAS, T, h, h, st->dy_mid, h, param_ptr(st, l, P_WO), h, st->dattn, h,
+                nullptr, nullptr, 0, nullptr, 0, 0, s));
+    AX_TRY(gemm(false, false, wg_epi, h, h, T, a.o, h, st->dy_mid, h, grad_ptr(st, l, P_WO), h,
+                nullptr, nullptr, 0, nullptr, 0, acc, s));
+    AX_TRY(check_launch(launch_colsum(T, h, st->dy_mid, h, st->vec0, st->red_ws, s), "colsum"));
+    AX_TRY(vec_grad(st, l, P_BO, st->vec0, h, acc, s));
+    // attention
+    AX_TRY(check_launch(launch_attention_bwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d,
+                                             a.qkv, a.o, a.lse, st->dattn, st->dqkv, st->delta, s),
+                        "attention_bwd"));
+    // qkv = u Wqkv + b
+    AX_TRY(gemm(true, true, EPI_BIAS, T, h, 3 * h, st->dqkv, 3 * h, param_ptr(st, l, P_WQKV), 3 * h, st->du, h,
+                nullptr, nullptr, 0, nullptr, 0, 0, s));
+    AX_TRY(gemm(false, false, wg_epi, h, 3 * h, T, a.u, h, st->dqkv, 3 * h, grad_ptr(st, l, P_WQKV), 3 * h,
+                nullptr, nullptr, 0, nullptr, 0, acc, s));
+    AX_TRY(check_launch(launch_colsum(T, 3 * h, st->dqkv, 3 * h, st->vec0, st->red_ws, s), "colsum"));
+    AX_TRY(vec_grad(st, l, P_BQKV, st->vec0, 3 * h, acc, s));
+    // u = LN1(x); residual: dx = dy + dLN1
+    AX_TRY(check_launch(launch_layernorm_bwd(T, h, st->du, a.x, a.stats1, param_ptr(st, l, P_LN1G), st->dy_mid,
+                                             d_out, st->vec0, st->vec1, st->red_ws, s), "layernorm_bwd"));
+    AX_TRY(vec_grad(st, l, P_LN1G, st->vec0, h, acc, s));
+    AX_TRY(vec_grad(st, l, P_LN1B, st->vec1, h, acc, s));
+    d_in = d_out;
+  }
+  return AXONN_OK;
+}
+
+Slot* find_slot(axonn_stage* st, int mb_id) {
+  for (Slot& s : st->slots)
+    if (s.mb_id == mb_id) return &s;
+  return nullptr;
+}
+
+int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s) {
+  if (mb_id < 0) return fail(AXONN_EINVAL, "forward: negative microbatch id %d", mb_id);
+  if (find_slot(st, mb_id)) return fail(AXONN_ESTATE, "forward: microbatch %d is already in flight", mb_id);
+  if (st->in_flight >= st->cfg.pipeline_limit)
+    return fail(AXONN_ESTATE, "forward: pipeline_limit (%d) microbatches already in flight",
+                st->cfg.pipeline_limit);
+  Slot* slot = find_slot(st, -1);
+  if (!slot) return fail(AXONN_ESTATE, "forward: no free stash slot");
+  // the slot's previous occupant must have finished its backward before it is overwritten
+  if (slot->bwd_recorded) HIP_TRY(hipStreamWaitEvent(s, slot->bwd_done, 0));
+  const uint64_t bytes = (uint64_t)st->T * st->h * sizeof(bf16_t);
+  HIP_TRY(hipMemcpyAsync(slot->layers[0].x, x, bytes, hipMemcpyDeviceToDevice, s));
+  AX_TRY(forward_layers(st, *slot, y, s));
+  HIP_TRY(hipEventRecord(slot->fwd_done, s));
+  slot->mb_id = mb_id;
+  st->in_flight++;
+  return AXONN_OK;
+}
+
+int do_backward(axonn_stage* st, int mb_id, const void* dy, void* dx, hipStream_t s) {
+  Slot* slot = (mb_id >= 0) ? find_slot(st, mb_id) : nullptr;
+  if (!slot) return fail(AXONN_ESTATE, "backward: microbatch %d has no forward in flight", mb_id);
+  HIP_TRY(hipStreamWaitEvent(s, slot->fwd_done, 0));
+  // backward passes share the workspace and the gradient accumulators: keep them in order
+  if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_bwd, 0));
+  const int acc = st->bwd_count > 0 ? 1 : 0;
+  AX_TRY(backward_layers(st, *slot, dy, dx, acc, s));
+  st->bwd_count++;
+  if (st->cfg.grad_accum_fp32 && st->bwd_count == st->cfg.n_microbatches)
+    AX_TRY(check_launch(launch_f32_to_bf16(st->n_params, st->grads32, st->grads, s), "f32_to_bf16"));
+  HIP_TRY(hipEventRecord(slot->bwd_done, s));
+  slot->bwd_recorded = true;
+  HIP_TRY(hipEventRecord(st->last_bwd, s));
+  st->last_bwd_recorded = true;
+  slot->mb_id = -1;
+  st->in_flight--;
+  return AXONN_OK;
+}
+
+int ensure_streams(axonn_stage* st, int n) {
+  while ((int)st->streams.size() < n) {
+    hipStream_t s;
+    hipEvent_t e;
+    HIP_TRY(hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+    HIP_TRY(hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    st->streams.push_back(s);
+    st->stream_tail.push_back(e);
+  }
+  return AXONN_OK;
+}
+
+void destroy_adam(axonn_offload_adam* o) {
+  if (!o) return;
+  (void)hipSetDevice(o->device);
+  if (o->s_h2d) (void)hipStreamSynchronize(o->s_h2d);
+  if (o->s_k) (void)hipStreamSynchronize(o->s_k);
+  if (o->s_d2h) (void)hipStreamSynchronize(o->s_d2h);
+  for (int i = 0; i < axonn_offload_adam::kSets; ++i) {
+    for (int j = 0; j < 3; ++j)
+      if (o->d_buf[i][j]) (void)hipFree(o->d_buf[i][j]);
+    if (o->ev_h2d[i]) (void)hipEventDestroy(o->ev_h2d[i]);
+    if (o->ev_k[i]) (void)hipEventDestroy(o->ev_k[i]);
+    if (o->ev_d2h[i]) (void)hipEventDestroy(o->ev_d2h[i]);
+  }
+  if (o->ev_start) (void)hipEventDestroy(o->ev_start);
+  if (o->s_h2d) (void)hipStreamDestroy(o->s_h2d);
+  if (o->s_k) (void)hipStreamDestroy(o->s_k);
+  if (o->s_d2h) (void)hipStreamDestroy(o->s_d2h);
+  delete o;
+}
+
+void destroy_stage(axonn_stage* st) {
+  if (!st) return;
+  (void)hipSetDevice(st->cfg.device);
+  (void)hipDeviceSynchronize();
+  destroy_adam(st->opt);
+  for (Slot& s : st->slots) {
+    if (s.base) (void)hipFree(s.base);
+    if (s.fwd_done) (void)hipEventDestroy(s.fwd_done);
+    if (s.bwd_done) (void)hipEventDestroy(s.bwd_done);
+  }
+  for (hipStream_t s : st->streams) (void)hipStreamDestroy(s);
+  for (hipEvent_t e : st->stream_tail) (void)hipEventDestroy(e);
+  if (st->last_bwd) (void)hipEventDestroy(st->last_bwd);
+  if (st->ws_base) (void)hipFree(st->ws_base);
+  if (st->params) (void)hipFree(st->params);
+  if (st->grads) (void)hipFree(st->grads);
+  if (st->grads32) (void)hipFree(st->grads32);
+  delete st;
+}
+
+int validate_config(const axonn_stage_config* c) {
+  if (c->n_layers < 1 || c->hidden < 1 || c->n_heads < 1 || c->ffn_hidden < 1 || c->seq_len < 1 ||
+      c->microbatch_size < 1 || c->n_microbatches < 1)
+    return fail(AXONN_EINVAL, "stage config: sizes must be positive");
+  if (c->pipeline_limit < 1 || c->pipeline_limit > c->n_microbatches)
+    return fail(AXONN_EINVAL, "stage config: pipeline_limit must be in 1..n_microbatches");
+  if (c->hidden % c->n_heads != 0) return fail(AXONN_EINVAL, "stage config: hidden %% n_heads != 0");
+  if (!(c->ln_eps > 0.f)) return fail(AXONN_EINVAL, "stage config: ln_eps must be positive");
+  if (c->device < 0) return fail(AXONN_EINVAL, "stage config: negative device ordinal");
+  const int d = c->hidden / c->n_heads;
+  if (d != 64 && d != 128)
+    return fail(AXONN_EUNSUPPORTED, "head dim %d unsupported: attention kernels exist for 64 and 128", d);
+  if (c->hidden % 8 || c->ffn_hidden % 8)
+    return fail(AXONN_EUNSUPPORTED, "hidden and ffn_hidden must be multiples of 8 (16-byte rows)");
+  if (((int64_t)c->seq_len * c->microbatch_size) % 8)
+    return fail(AXONN_EUNSUPPORTED, "microbatch_size*seq_len must be a multiple of 8");
+  if (c->hidden > 16384) return fail(AXONN_EUNSUPPORTED, "hidden > 16384 unsupported by the LayerNorm kernel");
+  if ((int64_t)c->seq_len * c->microbatch_size > (1 << 24))
+    return fail(AXONN_EUNSUPPORTED, "more than 2^24 tokens per microbatch unsupported");
+  return AXONN_OK;
+}
+
+}  // namespace
+
+// ======================================================================== C ABI
+extern "C" {
+
+const char* axonn_last_error(void) { return g_last_error.c_str(); }
+
+int axonn_pinned_alloc(void** host_out, uint64_t bytes) {
+  if (!host_out || bytes == 0) return fail(AXONN_EINVAL, "pinned_alloc: null output or zero size");
+  HIP_TRY(hipHostMalloc(host_out, bytes, hipHostMallocDefault));
+  return AXONN_OK;
+}
+int axonn_pinned_free(void* host) {
+  if (!host) return fail(AXONN_EINVAL, "pinned_free: null pointer");
+  HIP_TRY(hipHostFree(host));
+  return AXONN_OK;
+}
+
+int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
+  if (!cfg || !out) return fail(AXONN_EINVAL, "stage_create: null argument");
+  *out = nullptr;
+  AX_TRY(validate_config(cfg));
+  int ndev = 0;
+  HIP_TRY(hipGetDeviceCount(&ndev));
+  if (cfg->device >= ndev) return fail(AXONN_EINVAL, "stage_create: device %d of %d", cfg->device, ndev);
+  HIP_TRY(hipSetDevice(cfg->device));
+  axonn_stage* st = new (std::nothrow) axonn_stage();
+  if (!st) return fail(AXONN_ENOMEM, "stage_create: host allocation failed");
+  st->cfg = *cfg;
+  st->h = cfg->hidden; st->f = cfg->ffn_hidden; st->d = cfg->hidden / cfg->n_heads;
+  st->T = cfg->seq_len * cfg->microbatch_size;
+  const int64_t h = st->h, f = st->f, T = st->T;
+  // flat parameter table
+  uint64_t off = 0;
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const int64_t shp[kTensorsPerLayer][2] = {{h, 0}, {h, 0}, {h, 3 * h}, {3 * h, 0}, {h, h}, {h, 0},
+                                             {h, 0}, {h, 0}, {h, f}, {f, 0}, {f, h}, {h, 0}};
+    for (int t = 0; t < kTensorsPerLayer; ++t) {
+      TensorInfo ti;
+      ti.name = "layer" + std::to_string(l) + "." + kTensorNames[t];
+      ti.offset = off;
+      ti.rank = shp[t][1] ? 2 : 1;
+      ti.dims[0] = shp[t][0]; ti.dims[1] = shp[t][1] ? shp[t][1] : 1; ti.dims[2] = ti.dims[3] = 1;
+      ti.numel = (uint64_t)shp[t][0] * (shp[t][1] ? shp[t][1] : 1);
+      off += ti.numel;
+      st->tensors.push_back(ti);
+    }
+  }
+  st->n_params = off;
+
+  auto bail = [&](int code) { destroy_stage(st); return code; };
+#define CREATE_TRY(expr)                                                                         \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess)                                                                        \
+      return bail(fail(e_ == hipErrorOutOfMemory ? AXONN_ENOMEM : AXONN_EHIP, "%s failed: %s",   \
+                       #expr, hipGetErrorString(e_)));                                           \
+  } while (0)
+
+  CREATE_TRY(hipMalloc((void**)&st->params, st->n_params * sizeof(bf16_t)));
+  CREATE_TRY(hipMalloc((void**)&st->grads, st->n_params * sizeof(bf16_t)));
+  CREATE_TRY(hipMemset(st->params, 0, st->n_params * sizeof(bf16_t)));
+  CREATE_TRY(hipMemset(st->grads, 0, st->n_params * sizeof(bf16_t)));
+  if (cfg->grad_accum_fp32) {
+    CREATE_TRY(hipMalloc((void**)&st->grads32, st->n_params * sizeof(float)));
+    CREATE_TRY(hipMemset(st->grads32, 0, st->n_params * sizeof(float)));
+  }
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    CREATE_TRY(launch_fill_bf16(h, param_ptr(st, l, P_LN1G), 1.0f, nullptr));
+    CREATE_TRY(launch_fill_bf16(h, param_ptr(st, l, P_LN2G), 1.0f, nullptr));
+  }
+
+  // activation stash: per layer x,u,o,y,w [T,h], qkv [T,3h], pre,g [T,f], stats [T,2]x2, lse [b,a,s]
+  const uint64_t e_th = align_up((uint64_t)T * h * 2, 256), e_t3h = align_up((uint64_t)T * 3 * h * 2, 256),
+                 e_tf = align_up((uint64_t)T * f * 2, 256), e_st = align_up((uint64_t)T * 2 * 4, 256),
+                 e_lse = align_up((uint64_t)cfg->microbatch_size * cfg->n_heads * cfg->seq_len * 4, 256);
+  const uint64_t per_layer = 5 * e_th + e_t3h + 2 * e_tf + 2 * e_st + e_lse;
+  st->slot_bytes = per_layer * cfg->n_layers;
+  st->slots.resize(cfg->pipeline_limit);
+  for (Slot& s : st->slots) {
+    CREATE_TRY(hipMalloc((void**)&s.base, st->slot_bytes));
+    CREATE_TRY(hipEventCreateWithFlags(&s.fwd_done, hipEventDisableTiming));
+    CREATE_TRY(hipEventCreateWithFlags(&s.bwd_done, hipEventDisableTiming));
+    s.layers.resize(cfg->n_layers);
+    char* p = s.base;
+    for (LayerStash& a : s.layers) {
+      a.x = (bf16_t*)p; p += e_th;  a.u = (bf16_t*)p; p += e_th;  a.o = (bf16_t*)p; p += e_th;
+      a.y = (bf16_t*)p; p += e_th;  a.w = (bf16_t*)p; p += e_th;  a.qkv = (bf16_t*)p; p += e_t3h;
+      a.pre = (bf16_t*)p; p += e_tf; a.g = (bf16_t*)p; p += e_tf;
+      a.stats1 = (float*)p; p += e_st; a.stats2 = (float*)p; p += e_st; a.lse = (float*)p; p += e_lse;
+    }
+  }
+  // backward workspace
+  const int64_t wide = std::max<int64_t>(f, 3 * h);
+  const uint64_t e_red = align_up((uint64_t)2 * ((T + 63) / 64) * wide * 4, 256), e_vec = align_up((uint64_t)wide * 4, 256);
+  st->ws_bytes = 6 * e_th + e_tf + e_t3h + e_lse + e_red + 2 * e_vec;
+  CREATE_TRY(hipMalloc((void**)&st->ws_base, st->ws_bytes));
+  {
+    char* p = st->ws_base;
+    st->dres[0] = (bf16_t*)p; p += e_th; st->dres[1] = (bf16_t*)p; p += e_th; st->dy_mid = (bf16_t*)p; p += e_th;
+    st->dw = (bf16_t*)p; p += e_th; st->dattn = (bf16_t*)p; p += e_th; st->du = (bf16_t*)p; p += e_th;
+    st->dpre = (bf16_t*)p; p += e_tf; st->dqkv = (bf16_t*)p; p += e_t3h;
+    st->delta = (float*)p; p += e_lse; st->red_ws = (float*)p; p += e_red;
+    st->vec0 = (float*)p; p += e_vec; st->vec1 = (float*)p; p += e_vec;
+  }
+  CREATE_TRY(hipEventCreateWithFlags(&st->last_bwd, hipEventDisableTiming));
+  CREATE_TRY(hipDeviceSynchronize());
+#undef CREATE_TRY
+  *out = st;
+  return AXONN_OK;
+}
+
+int axonn_stage_destroy(axonn_stage_t* st) {
+  if (!st) return fail(AXONN_EINVAL, "stage_destroy: null handle");
+  destroy_stage(st);
+  return AXONN_OK;
+}
+
+int axonn_stage_param_count(const axonn_stage_t* st, uint64_t* n) {
+  if (!st || !n) return fail(AXONN_EINVAL, "param_count: null argument");
+  *n = st->n_params;
+  return AXONN_OK;
+}
+int axonn_stage_num_tensors(const axonn_stage_t* st, int32_t* n) {
+  if (!st || !n) return fail(AXONN_EINVAL, "num_tensors: null argument");
+  *n = (int32_t)st->tensors.size();
+  return AXONN_OK;
+}
+int axonn_stage_param_layout(const axonn_stage_t* st, int32_t idx, const char** name, uint64_t* offset,
+                             int32_t* rank, int64_t dims[4]) {
+  if (!st) return fail(AXONN_EINVAL, "param_layout: null handle");
+  if (idx < 0 || idx >= (int32_t)st->tensors.size()) return fail(AXONN_EINVAL, "param_layout: index %d out of range", idx);
+  const TensorInfo& t = st->tensors[idx];
+  if (name) *name = t.name.c_str();
+  if (offset) *offset = t.offset;
+  if (rank) *rank = t.rank;
+  if (dims) memcpy(dims, t.dims, sizeof t.dims);
+  return AXONN_OK;
+}
+int axonn_stage_params(axonn_stage_t* st, void** p) {
+  if (!st || !p) return fail(AXONN_EINVAL, "stage_params: null argument");
+  *p = st->params;
+  return AXONN_OK;
+}
+int axonn_stage_grads(axonn_stage_t* st, void** p) {
+  if (!st || !p) return fail(AXONN_EINVAL, "stage_grads: null argument");
+  *p = st->grads;
+  return AXONN_OK;
+}
+int axonn_stage_zero_grad(axonn_stage_t* st, void* hip_stream) {
+  if (!st) return fail(AXONN_EINVAL, "zero_grad: null handle");
+  if (st->in_flight) return fail(AXONN_ESTATE, "zero_grad: %d microbatches in flight", st->in_flight);
+  HIP_TRY(hipSetDevice(st->cfg.device));
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_bwd, 0));
+  // no memory is touched: the first backward of a batch overwrites the accumulators
+  (void)s;
+  st->bwd_count = 0;
+  st->fwd_issued = st->bwd_issued = 0;
+  st->dispatch_log.clear();
+  return AXONN_OK;
+}
+int axonn_stage_device_bytes(const axonn_stage_t* st, uint64_t bytes[6]) {
+  if (!st || !bytes) return fail(AXONN_EINVAL, "device_bytes: null argument");
+  bytes[0] = st->n_params * 2;
+  bytes[1] = st->n_params * 2;
+  bytes[2] = st->grads32 ? st->n_params * 4 : 0;
+  bytes[3] = st->slot_bytes * st->slots.size();
+  bytes[4] = st->ws_bytes;
+  bytes[5] = st->opt ? st->opt->device_bytes : 0;
+  return AXONN_OK;
+}
+
+int axonn_stage_forward(axonn_stage_t* st, int32_t mb_id, const void* x, void* y, void* hip_stream) {
+  if (!st || !x || !y) return fail(AXONN_EINVAL, "forward: null argument");
+  HIP_TRY(hipSetDevice(st->cfg.device));
+  return do_forward(st, mb_id, x, y, (hipStream_t)hip_stream);
+}
+int axonn_stage_backward(axonn_stage_t* st, int32_t mb_id, const void* dy, void* dx, void* hip_stream) {
+  if (!st || !dy || !dx) return fail(AXONN_EINVAL, "backward: null argument");
+  HIP_TRY(hipSetDevice(st->cfg.device));
+  return do_backward(st, mb_id, dy, dx, (hipStream_t)hip_stream);
+}
+
+int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg) {
+  if (!st || !msg) return fail(AXONN_EINVAL, "post: null argument");
+  if (msg->kind != 0 && msg->kind != 1) return fail(AXONN_EINVAL, "post: kind must be 0 (forward) or 1 (backward)");
+  if (!msg->payload_dev || !msg->result_dev) return fail(AXONN_EINVAL, "post: null payload or result buffer");
+  if (msg->mb_id < 0) return fail(AXONN_EINVAL, "post: negative microbatch id");
+  int same = 0;
+  for (const PendingMsg& p : st->inbox)
+    if (p.m.kind == msg->kind) {
+      ++same;
+      if (p.m.mb_id == msg->mb_id) return fail(AXONN_ESTATE, "post: duplicate message for microbatch %d", msg->mb_id);
+    }
+  const int issued = msg->kind == 0 ? st->fwd_issued : st->bwd_issued;
+  if (issued + same >= st->cfg.n_microbatches)
+    return fail(AXONN_ESTATE, "post: more than n_microbatches (%d) messages of kind %d in this batch",
+                st->cfg.n_microbatches, msg->kind);
+  st->inbox.push_back(PendingMsg{*msg});
+  return AXONN_OK;
+}
+
+int axonn_stage_run(axonn_stage_t* st, int32_t n_streams) {
+  if (!st) return fail(AXONN_EINVAL, "run: null handle");
+  if (n_streams < 1 || n_streams > 8) return fail(AXONN_EINVAL, "run: n_streams must be in 1..8");
+  HIP_TRY(hipSetDevice(st->cfg.device));
+  AX_TRY(ensure_streams(st, n_streams));
+  const int M = st->cfg.n_microbatches;
+  const auto t_start = std::chrono::steady_clock::now();
+  while (st->fwd_issued < M || st->bwd_issued < M) {
+    // first posted message that has arrived and is admissible
+    int chosen = -1;
+    bool any_admissible = false;
+    for (size_t i = 0; i < st->inbox.size(); ++i) {
+      const axonn_msg& m = st->inbox[i].m;
+      const bool admissible = (m.kind == 0)
+                                  ? (st->in_flight < st->cfg.pipeline_limit && !find_slot(st, m.mb_id))
+                                  : (find_slot(st, m.mb_id) != nullptr);
+      if (!admissible) continue;
+      any_admissible = true;
+      if (m.ready_event) {
+        const hipError_t q = hipEventQuery((hipEvent_t)m.ready_event);
+        if (q == hipErrorNotReady) continue;
+        if (q != hipSuccess) return fail(AXONN_EHIP, "run: hipEventQuery failed: %s", hipGetErrorString(q));
+      }
+      chosen = (int)i;
+      break;
+    }
+    if (chosen < 0) {
+      if (!any_admissible)
+        return fail(AXONN_ESTATE,
+                    "run: %d forward and %d backward messages still expected but none of the %zu posted "
+                    "messages can be scheduled", M - st->fwd_issued, M - st->bwd_issued, st->inbox.size());
+      if (std::chrono::steady_clock::now() - t_start > std::chrono::seconds(120))
+        return fail(AXONN_ESTATE, "run: waited 120 s for a posted message to arrive");
+      std::this_thread::yield();
+      continue;
+    }
+    const axonn_msg m = st->inbox[chosen].m;
+    st->inbox.erase(st->inbox.begin() + chosen);
+    int si;
+    if (m.kind == 1 || n_streams == 1) {
+      si = 0;  // backwards keep to one stream: they share accumulators and workspace
+    } else {
+      si = 1 + (st->fwd_rr++ % (n_streams - 1));
+    }
+    hipStream_t s = st->streams[si];
+    if (m.ready_event) HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)m.ready_event, 0));
+    if (m.kind == 0) {
+      AX_TRY(do_forward(st, m.mb_id, m.payload_dev, m.result_dev, s));
+      st->fwd_issued++;
+    } else {
+      AX_TRY(do_backward(st, m.mb_id, m.payload_dev, m.result_dev, s));
+      st->bwd_issued++;
+    }
+    st->dispatch_log.push_back(m.mb_id * 2 + m.kind);
+  }
+  return AXONN_OK;
+}
+
+int axonn_stage_join(axonn_stage_t* st, void* user_stream) {
+  if (!st) return fail(AXONN_EINVAL, "join: null handle");
+  HIP_TRY(hipSetDevice(st->cfg.device));
+  for (size_t i = 0; i < st->streams.size(); ++i) {
+    HIP_TRY(hipEventRecord(st->stream_tail[i], st->streams[i]));
+    HIP_TRY(hipStreamWaitEvent((hipStream_t)user_stream, st->stream_tail[i], 0));
+  }
+  return AXONN_OK;
+}
+
+int axonn_stage_synchronize(axonn_stage_t* st) {
+  if (!st) return fail(AXONN_EINVAL, "synchronize: null handle");
+  HIP_TRY(hipSetDevice(st->cfg.device));
+  HIP_TRY(hipDeviceSynchronize());
+  return AXONN_OK;
+}
+
+int axonn_stage_dispatch_log(const axonn_stage_t* st, int32_t* out, int32_t capacity, int32_t* n_written) {
+  if (!st || !n_written || (capacity > 0 && !out)) return fail(AXONN_EINVAL, "dispatch_log: null argument");
+  int n = 0;
+  for (; n < capacity && n < (int)st->dispatch_log.size(); ++n) out[n] = st->dispatch_log[n];
+  *n_written = n;
+  return AXONN_OK;
+}
+
+// ----------------------------------------------------------------- offloaded Adam
+int axonn_offload_adam_create(int32_t device, uint64_t n, uint64_t bucket_elems, void* param16_dev,
+                              const void* grad16_dev, float* host_master, float* host_m, float* host_v,
+                              axonn_offload_adam_t** out) {
+  if (!out) return fail(AXONN_EINVAL, "adam_create: null output");
+  *out = nullptr;
+  if (!param16_dev || !grad16_dev || !host_master || !host_m || !host_v)
+    return fail(AXONN_EINVAL, "adam_create: null buffer");
+  if (n == 0) return fail(AXONN_EINVAL, "adam_create: n == 0");
+  if (bucket_elems == 0 || bucket_elems % 8) return fail(AXONN_EINVAL, "adam_create: bucket_elems must be a positive multiple of 8");
+  int ndev = 0;
+  HIP_TRY(hipGetDeviceCount(&ndev));
+  if (device < 0 || device >= ndev) return fail(AXONN_EINVAL, "adam_create: device %d of %d", device, ndev);
+  HIP_TRY(hipSetDevice(device));
+  axonn_offload_adam* o = new (std::nothrow) axonn_offload_adam();
+  if (!o) return fail(AXONN_ENOMEM, "adam_create: host allocation failed");
+  o->device = device; o->n = n; o->bucket = std::min<uint64_t>(bucket_elems, align_up(n, 8));
+  o->p16 = (bf16_t*)param16_dev; o->g16 = (const bf16_t*)grad16_dev;
+  o->h_theta = host_master; o->h_m = host_m; o->h_v = host_v;
+#define ADAM_TRY(expr)                                                                           \
+  do {                                                                                           \
+    hipError_t e_ = (expr);                                                                      \
+    if (e_ != hipSuccess) {                                                                      \
+      destroy_adam(o);                                                                           \
+      return fail(e_ == hipErrorOutOfMemory ? AXONN_ENOMEM : AXONN_EHIP, "%s failed: %s", #expr, \
+                  hipGetErrorString(e_));                                                        \
+    }                                                                                            \
+  } while (0)
+  for (int i = 0; i < axonn_offload_adam::kSets; ++i) {
+    for (int j = 0; j < 3; ++j) {
+      ADAM_TRY(hipMalloc((void**)&o->d_buf[i][j], o->bucket * sizeof(float)));
+      o->device_bytes += o->bucket * sizeof(float);
+    }
+    ADAM_TRY(hipEventCreateWithFlags(&o->ev_h2d[i], hipEventDisableTiming));
+    ADAM_TRY(hipEventCreateWithFlags(&o->ev_k[i], hipEventDisableTiming));
+    ADAM_TRY(hipEventCreateWithFlags(&o->ev_d2h[i], hipEventDisableTiming));
+  }
+  ADAM_TRY(hipEventCreateWithFlags(&o->ev_start, hipEventDisableTiming));
+  ADAM_TRY(hipStreamCreateWithFlags(&o->s_h2d, hipStreamNonBlocking));
+  ADAM_TRY(hipStreamCreateWithFlags(&o->s_k, hipStreamNonBlocking));
+  ADAM_TRY(hipStreamCreateWithFlags(&o->s_d2h, hipStreamNonBlocking));
+#undef ADAM_TRY
+  *out = o;
+  return AXONN_OK;
+}
+
+int axonn_offload_adam_destroy(axonn_offload_adam_t* opt) {
+  if (!opt) return fail(AXONN_EINVAL, "adam_destroy: null handle");
+  destroy_adam(opt);
+  return AXONN_OK;
+}
+
+int axonn_offload_adam_device_bytes(const axonn_offload_adam_t* opt, uint64_t* bytes) {
+  if (!opt || !bytes) return fail(AXONN_EINVAL, "adam_device_bytes: null argument");
+  *bytes = opt->device_bytes;
+  return AXONN_OK;
+}
+
+int axonn_offload_adam_step(axonn_offload_adam_t* o, float lr, float beta1, float beta2, float eps,
+                            float weight_decay, int64_t step, float grad_scale, void* hip_stream) {
+  if (!o) return fail(AXONN_EINVAL, "adam_step: null handle");
+  if (step < 1) return fail(AXONN_EINVAL, "adam_step: step must be >= 1 (got %lld)", (long long)step);
+  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
+    return fail(AXONN_EINVAL, "adam_step: betas must be in [0,1)");
+  HIP_TRY(hipSetDevice(o->device));
+  hipStream_t user = (hipStream_t)hip_stream;
+  constexpr int S = axonn_offload_adam::kSets;
+  // everything already queued on the caller's stream (the gradients) comes first
+  HIP_TRY(hipEventRecord(o->ev_start, user));
+  HIP_TRY(hipStreamWaitEvent(o->s_h2d, o->ev_start, 0));
+  HIP_TRY(hipStreamWaitEvent(o->s_k, o->ev_start, 0));
+  HIP_TRY(hipStreamWaitEvent(o->s_d2h, o->ev_start, 0));
+  const uint64_t nb = (o->n + o->bucket - 1) / o->bucket;
+  for (uint64_t b = 0; b < nb; ++b) {
+    const int set = (int)(b % S);
+    const uint64_t off = b * o->bucket;
+    const uint64_t cnt = std::min<uint64_t>(o->bucket, o->n - off);
+    const size_t bytes = cnt * sizeof(float);
+    // fetch: the set must have been drained by the bucket that used it last
+    if (o->d2h_recorded[set]) HIP_TRY(hipStreamWaitEvent(o->s_h2d, o->ev_d2h[set], 0));
+    HIP_TRY(hipMemcpyAsync(o->d_buf[set][0], o->h_theta + off, bytes, hipMemcpyHostToDevice, o->s_h2d));
+    HIP_TRY(hipMemcpyAsync(o->d_buf[set][1], o->h_m + off, bytes, hipMemcpyHostToDevice, o->s_h2d));
+    HIP_TRY(hipMemcpyAsync(o->d_buf[set][2], o->h_v + off, bytes, hipMemcpyHostToDevice, o->s_h2d));
+    HIP_TRY(hipEventRecord(o->ev_h2d[set], o->s_h2d));
+    // update
+    HIP_TRY(hipStreamWaitEvent(o->s_k, o->ev_h2d[set], 0));
+    AX_TRY(check_launch(launch_adam(cnt, o->d_buf[set][0], o->d_buf[set][1], o->d_buf[set][2], o->g16 + off,
+                                    o->p16 + off, lr, beta1, beta2, eps, weight_decay, step, grad_scale, o->s_k),
+                        "adam"));
+    HIP_TRY(hipEventRecord(o->ev_k[set], o->s_k));
+    // offload
+    HIP_TRY(hipStreamWaitEvent(o->s_d2h, o->ev_k[set], 0));
+    HIP_TRY(hipMemcpyAsync(o->h_theta + off, o->d_buf[set][0], bytes, hipMemcpyDeviceToHost, o->s_d2h));
+    HIP_TRY(hipMemcpyAsync(o->h_m + off, o->d_buf[set][1], bytes, hipMemcpyDeviceToHost, o->s_d2h));
+    HIP_TRY(hipMemcpyAsync(o->h_v + off, o->d_buf[set][2], bytes, hipMemcpyDeviceToHost, o->s_d2h));
+    HIP_TRY(hipEventRecord(o->ev_d2h[set], o->s_d2h));
+    o->d2h_recorded[set] = true;
+  }
+  // the caller's stream continues after the last bucket is back in host memory
+  const int last = (int)((nb - 1) % S);
+  HIP_TRY(hipStreamWaitEvent(user, o->ev_d2h[last], 0));
+  HIP_TRY(hipStreamWaitEvent(user, o->ev_k[last], 0));
+  return AXONN_OK;
+}
+
+int axonn_stage_optimizer_attach(axonn_stage_t* st, float* host_master, float* host_m, float* host_v,
+                                 uint64_t n, uint64_t bucket_elems) {
+  if (!st) return fail(AXONN_EINVAL, "optimizer_attach: null handle");
+  if (n != st->n_params) return fail(AXONN_EINVAL, "optimizer_attach: n (%llu) != param_count (%llu)",
+                                     (unsigned long long)n, (unsigned long long)st->n_params);
+  if (st->opt) { destroy_adam(st->opt); st->opt = nullptr; }
+  return axonn_offload_adam_create(st->cfg.device, n, bucket_elems, st->params, st->grads, host_master,
+                                   host_m, host_v, &st->opt);
+}
+
+int axonn_stage_optimizer_step(axonn_stage_t* st, float lr, float beta1, float beta2, float eps,
+                               float weight_decay, int64_t step, float grad_scale, void* hip_stream) {
+  if (!st) return fail(AXONN_EINVAL, "optimizer_step: null handle");
+  if (!st->opt) return fail(AXONN_ESTATE, "optimizer_step: no optimizer attached");
+  if (st->in_flight) return fail(AXONN_ESTATE, "optimizer_step: %d microbatches in flight", st->in_flight);
+  HIP_TRY(hipSetDevice(st->cfg.device));
+  hipStream_t user = (hipStream_t)hip_stream;
+  if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(user, st->last_bwd, 0));
+  return axonn_offload_adam_step(st->opt, lr, beta1, beta2, eps, weight_decay, step, grad_scale, hip_stream);
+}
+
+// -------------------------------------------------------------- single operations
+int axonn_gemm_bf16(int32_t a_kcontig, int32_t b_kcontig, int32_t epilogue, int64_t M, int64_t N, int64_t K,
+                    const void* A, int64_t lda, const void* B, int64_t ldb, void* C, int64_t ldc,
+                    const void* bias, const void* res, int64_t ld_res, void* aux, int64_t ld_aux,
+                    int32_t accumulate, void* hip_stream) {
+  if (!A || !B || !C) return fail(AXONN_EINVAL, "gemm: null operand");
+  if (M < 1 || N < 1 || K < 1) return fail(AXONN_EINVAL, "gemm: non-positive size");
+  if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24)) return fail(AXONN_EUNSUPPORTED, "gemm: dimension above 2^24");
+  if ((M | N | K | lda | ldb | ldc) % 8) return fail(AXONN_EUNSUPPORTED, "gemm: M, N, K and leading dimensions must be multiples of 8");
+  if (epilogue < 0 || epilogue > 5) return fail(AXONN_EINVAL, "gemm: unknown epilogue %d", epilogue);
+  const bool akc = a_kcontig != 0, bkc = b_kcontig != 0;
+  const bool fwd = akc && !bkc, dgrad = akc && bkc, wgrad = !akc && !bkc;
+  const bool ok = (fwd && epilogue <= 2) || (dgrad && (epilogue == 0 || epilogue == 3)) ||
+                  (wgrad && (epilogue == 4 || epilogue == 5));
+  if (!ok) return fail(AXONN_EUNSUPPORTED, "gemm: epilogue %d is not built for layout (a_kcontig=%d, b_kcontig=%d)",
+                       epilogue, (int)akc, (int)bkc);
+  if (lda < (akc ? K : M) || ldb < (bkc ? K : N) || ldc < N) return fail(AXONN_EINVAL, "gemm: leading dimension too small");
+  if (epilogue == 1 && (!res || ld_res < N || ld_res % 8)) return fail(AXONN_EINVAL, "gemm: epilogue 1 needs res with ld_res >= N, multiple of 8");
+  if ((epilogue == 2 || epilogue == 3) && (!aux || ld_aux < N || ld_aux % 8)) return fail(AXONN_EINVAL, "gemm: epilogue %d needs aux with ld_aux >= N, multiple of 8", epilogue);
+  return gemm(akc, bkc, epilogue, (int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc, bias, res, ld_res, aux, ld_aux,
+              accumulate, (hipStream_t)hip_stream);
+}
+
+int axonn_layernorm_fwd(int64_t T, int64_t h, const void* x, const void* gamma, const void* beta, float eps,
+                        void* out, float* stats, void* hip_stream) {
+  if (!x || !gamma || !beta || !out || !stats) return fail(AXONN_EINVAL, "layernorm_fwd: null argument");
+  if (T < 1 || h < 1) return fail(AXONN_EINVAL, "layernorm_fwd: non-positive size");
+  if (h % 8 || h > 16384) return fail(AXONN_EUNSUPPORTED, "layernorm_fwd: h must be a multiple of 8 and <= 16384");
+  return check_launch(launch_layernorm_fwd(T, h, x, gamma, beta, eps, out, stats, (hipStream_t)hip_stream), "layernorm_fwd");
+}
+
+int axonn_layernorm_bwd(int64_t T, int64_t h, const void* dout, const void* x, const float* stats,
+                        const void* gamma, const void* res_grad, void* dx, float* dgamma, float* dbeta,
+                        float* workspace, void* hip_stream) {
+  if (!dout || !x || !stats || !gamma || !dx || !dgamma || !dbeta || !workspace)
+    return fail(AXONN_EINVAL, "layernorm_bwd: null argument");
+  if (T < 1 || h < 1) return fail(AXONN_EINVAL, "layernorm_bwd: non-positive size");
+  if (h % 8 || h > 16384) return fail(AXONN_EUNSUPPORTED, "layernorm_bwd: h must be a multiple of 8 and <= 16384");
+  return check_launch(launch_layernorm_bwd(T, h, dout, x, stats, gamma, res_grad, dx, dgamma, dbeta, workspace,
+                                           (hipStream_t)hip_stream), "layernorm_bwd");
+}
+
+int axonn_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, float* out, float* workspace, void* hip_stream) {
+  if (!y || !out || !workspace) return fail(AXONN_EINVAL, "colsum: null argument");
+  if (T < 1 || N < 1) return fail(AXONN_EINVAL, "colsum: non-positive size");
+  if (N % 8 || ldy % 8 || ldy < N) return fail(AXONN_EUNSUPPORTED, "colsum: N and ldy must be multiples of 8, ldy >= N");
+  return check_launch(launch_colsum(T, N, y, ldy, out, workspace, (hipStream_t)hip_stream), "colsum");
+}
+
+int axonn_attention_fwd(int32_t b, int32_t s, int32_t n_heads, int32_t head_dim, const void* qkv, void* o,
+                        float* lse, void* hip_stream) {
+  if (!qkv || !o || !lse) return fail(AXONN_EINVAL, "attention_fwd: null argument");
+  if (b < 1 || s < 1 || n_heads < 1) return fail(AXONN_EINVAL, "attention_fwd: non-positive size");
+  if (head_dim != 64 && head_dim != 128) return fail(AXONN_EUNSUPPORTED, "attention_fwd: head dim must be 64 or 128");
+  if ((int64_t)b * n_heads > 65535) return fail(AXONN_EUNSUPPORTED, "attention_fwd: b*n_heads > 65535");
+  return check_launch(launch_attention_fwd(b, s, n_heads, head_dim, qkv, o, lse, (hipStream_t)hip_stream), "attention_fwd");
+}
+
+int axonn_attention_bwd(int32_t b, int32_t s, int32_t n_heads, int32_t head_dim, const void* qkv, const void* o,
+                        const float* lse, const void* dout, void* dqkv, float* delta_ws, void* hip_stream) {
+  if (!qkv || !o || !lse || !dout || !dqkv || !delta_ws) return fail(AXONN_EINVAL, "attention_bwd: null argument");
+  if (b < 1 || s < 1 || n_heads < 1) return fail(AXONN_EINVAL, "attention_bwd: non-positive size");
+  if (head_dim != 64 && head_dim != 128) return fail(AXONN_EUNSUPPORTED, "attention_bwd: head dim must be 64 or 128");
+  if ((int64_t)b * n_heads > 65535) return fail(AXONN_EUNSUPPORTED, "attention_bwd: b*n_heads > 65535");
+  return check_launch(launch_attention_bwd(b, s, n_heads, head_dim, qkv, o, lse, dout, dqkv, delta_ws,
+                                           (hipStream_t)hip_stream), "attention_bwd");
+}
+
+int axonn_adam_bucket(uint64_t n, float* theta, float* m, float* v, const void* grad16, void* param16, float lr,
+                      float beta1, float beta2, float eps, float weight_decay, int64_t step, float grad_scale,
+                      void* hip_stream) {
+  if (!theta || !m || !v || !grad16 || !param16) return fail(AXONN_EINVAL, "adam_bucket: null argument");
+  if (n == 0) return fail(AXONN_EINVAL, "adam_bucket: n == 0");
+  if (step < 1) return fail(AXONN_EINVAL, "adam_bucket: step must be >= 1");
+  return check_launch(launch_adam(n, theta, m, v, grad16, param16, lr, beta1, beta2, eps, weight_decay, step,
+                                  grad_scale, (hipStream_t)hip_stream), "adam");
+}
+
+}  // extern "C"

@@ -1,0 +1,250 @@
+"""GPU parity of the single operations against the fp64 oracle, through the C ABI.
+
+Tolerances (relative Frobenius, derived from the arithmetic): every output is one bf16
+rounding (2^-9 relative per element, ~2.3e-3 worst case, ~1.1e-3 rms) of an fp32-accumulated
+value; fused epilogues add one more rounding of an intermediate.  5e-3 bounds single-op
+outputs with margin and is 4x tighter than the stage-level forward bound (2e-2)."""
+import numpy as np
+import pytest
+
+import oracle
+from oracle import transformer as OT
+from paper_2110_13005_amd import binding as B
+from paper_2110_13005_amd.inputs import snap_bf16
+from helpers import rel_fro, dev_bf16, dev_f32, host
+
+pytestmark = pytest.mark.gpu
+TOL = 5e-3
+
+
+def _rng_bf16(rng, shape, std=1.0):
+    return snap_bf16((rng.standard_normal(shape) * std).astype(np.float32))
+
+
+# ------------------------------------------------------------------------- GEMM
+GEMM_SHAPES = [
+    (256, 256, 64),      # one big tile, one k-step
+    (512, 768, 256),     # several 256-tiles -> big-tile kernel? (2x3=6 tiles -> small-tile path)
+    (2048, 4096, 512),   # 128 big tiles: big-tile kernel
+    (200, 136, 72),      # ragged in every dimension (multiples of 8 only)
+    (8, 8, 8),           # degenerate minimum
+    (264, 2056, 1032),   # ragged tails on a multi-tile problem
+]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_forward_layout_bias_res_gelu(M, N, K):
+    import torch
+    rng = np.random.default_rng(M + N + K)
+    x = _rng_bf16(rng, (M, K)); w = _rng_bf16(rng, (K, N), 0.05); bias = _rng_bf16(rng, (N,), 0.5)
+    res = _rng_bf16(rng, (M, N))
+    ref = x.astype(np.float64) @ w.astype(np.float64) + bias
+    dx, dw, db, dr = dev_bf16(x), dev_bf16(w), dev_bf16(bias), dev_bf16(res)
+    out = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, dx, K, dw, N, out, N, bias=db)
+    assert rel_fro(host(out), ref) < TOL
+    B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, dx, K, dw, N, out, N, bias=None)
+    assert rel_fro(host(out), ref - bias) < TOL
+    B.axonn_gemm_bf16(1, 0, B.EPI_BIAS_RES, M, N, K, dx, K, dw, N, out, N, bias=db, res=dr, ld_res=N)
+    assert rel_fro(host(out), ref + res) < TOL
+    pre = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    B.axonn_gemm_bf16(1, 0, B.EPI_BIAS_GELU, M, N, K, dx, K, dw, N, out, N, bias=db, aux=pre, ld_aux=N)
+    torch.cuda.synchronize()
+    assert rel_fro(host(pre), ref) < TOL
+    assert rel_fro(host(out), OT.gelu(ref)) < TOL
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_dgrad_layout_plain_and_dgelu(M, N, K):
+    """dx = dy W^T: A [M,K] k-contiguous, B = W stored [N,K] (rows n, k contiguous)."""
+    import torch
+    rng = np.random.default_rng(M * 3 + N + K)
+    dy = _rng_bf16(rng, (M, K)); w = _rng_bf16(rng, (N, K), 0.05); pre = _rng_bf16(rng, (M, N))
+    ref = dy.astype(np.float64) @ w.astype(np.float64).T
+    a, b, p = dev_bf16(dy), dev_bf16(w), dev_bf16(pre)
+    out = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    B.axonn_gemm_bf16(1, 1, B.EPI_BIAS, M, N, K, a, K, b, K, out, N)
+    assert rel_fro(host(out), ref) < TOL
+    B.axonn_gemm_bf16(1, 1, B.EPI_DGELU, M, N, K, a, K, b, K, out, N, aux=p, ld_aux=N)
+    assert rel_fro(host(out), ref * OT.gelu_grad(pre.astype(np.float64))) < TOL
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_wgrad_layout_accumulate(M, N, K):
+    """dW = x^T dy: A = x stored [K,M], B = dy stored [K,N]; fp32 and bf16 accumulators."""
+    import torch
+    rng = np.random.default_rng(M + N * 5 + K)
+    x = _rng_bf16(rng, (K, M)); dy = _rng_bf16(rng, (K, N))
+    ref = x.astype(np.float64).T @ dy.astype(np.float64)
+    a, b = dev_bf16(x), dev_bf16(dy)
+    c32 = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
+    B.axonn_gemm_bf16(0, 0, B.EPI_ACC_F32, M, N, K, a, M, b, N, c32, N, accumulate=0)   # overwrite
+    assert rel_fro(host(c32), ref) < 1e-5
+    B.axonn_gemm_bf16(0, 0, B.EPI_ACC_F32, M, N, K, a, M, b, N, c32, N, accumulate=1)
+    assert rel_fro(host(c32), 2 * ref) < 1e-5
+    c16 = torch.full((M, N), 7.0, dtype=torch.bfloat16, device="cuda")
+    B.axonn_gemm_bf16(0, 0, B.EPI_ACC_BF16, M, N, K, a, M, b, N, c16, N, accumulate=0)
+    first = host(c16)
+    assert rel_fro(first, ref) < TOL
+    B.axonn_gemm_bf16(0, 0, B.EPI_ACC_BF16, M, N, K, a, M, b, N, c16, N, accumulate=1)
+    assert rel_fro(host(c16), first + ref) < TOL
+
+
+def test_gemm_strided_operands_and_run_to_run_determinism():
+    """Leading dimensions larger than the logical width (the qkv weight-gradient uses slices)."""
+    import torch
+    rng = np.random.default_rng(5)
+    M, N, K, lda, ldb, ldc = 136, 264, 520, 600, 320, 400
+    abuf = _rng_bf16(rng, (M, lda)); bbuf = _rng_bf16(rng, (K, ldb), 0.05)
+    ref = abuf[:, :K].astype(np.float64) @ bbuf[:, :N].astype(np.float64)
+    a, b = dev_bf16(abuf), dev_bf16(bbuf)
+    out = torch.zeros(M, ldc, dtype=torch.bfloat16, device="cuda")
+    B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, a, lda, b, ldb, out, ldc)
+    first = out.clone()
+    assert rel_fro(host(out)[:, :N], ref) < TOL
+    assert not host(out)[:, N:].any()                     # nothing written outside the tile
+    B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, a, lda, b, ldb, out, ldc)
+    torch.cuda.synchronize()
+    assert torch.equal(first, out)
+
+
+# -------------------------------------------------------------------- LayerNorm
+@pytest.mark.parametrize("T,h", [(256, 256), (77, 5120), (8, 8), (300, 10240), (64, 1000)])
+def test_layernorm_fwd_bwd(T, h):
+    import torch
+    rng = np.random.default_rng(T + h)
+    x = _rng_bf16(rng, (T, h), 2.0) + snap_bf16(np.float32(0.5))
+    x = snap_bf16(x)
+    g = _rng_bf16(rng, (h,), 0.2) + 1; g = snap_bf16(g)
+    bta = _rng_bf16(rng, (h,), 0.2)
+    dout = _rng_bf16(rng, (T, h)); resg = _rng_bf16(rng, (T, h))
+    eps = 1e-5
+    ref, xhat, rstd = OT.layernorm_fwd(x, g.astype(np.float64), bta.astype(np.float64), eps)
+    dxr, dgr, dbr = OT.layernorm_bwd(dout.astype(np.float64), xhat, rstd, g.astype(np.float64))
+    X, G, Bt, DO, RG = dev_bf16(x), dev_bf16(g), dev_bf16(bta), dev_bf16(dout), dev_bf16(resg)
+    out = torch.empty(T, h, dtype=torch.bfloat16, device="cuda")
+    stats = torch.empty(T, 2, dtype=torch.float32, device="cuda")
+    B.axonn_layernorm_fwd(T, h, X, G, Bt, eps, out, stats)
+    assert rel_fro(host(out), ref) < TOL
+    st = host(stats)
+    assert rel_fro(st[:, 0], x.astype(np.float64).mean(-1)) < 1e-4 or np.abs(st[:, 0] - x.mean(-1)).max() < 1e-5
+    assert rel_fro(st[:, 1], rstd[:, 0]) < 1e-5
+    dx = torch.empty(T, h, dtype=torch.bfloat16, device="cuda")
+    dg = torch.empty(h, dtype=torch.float32, device="cuda")
+    db = torch.empty(h, dtype=torch.float32, device="cuda")
+    ws = torch.empty(2 * ((T + 63) // 64) * h, dtype=torch.float32, device="cuda")
+    B.axonn_layernorm_bwd(T, h, DO, X, stats, G, RG, dx, dg, db, ws)
+    assert rel_fro(host(dx), dxr + resg) < TOL
+    assert rel_fro(host(dg), dgr) < 1e-4
+    assert rel_fro(host(db), dbr) < 1e-4
+    B.axonn_layernorm_bwd(T, h, DO, X, stats, G, None, dx, dg, db, ws)
+    assert rel_fro(host(dx), dxr) < TOL
+
+
+def test_layernorm_constant_row_gives_beta():
+    import torch
+    T, h = 8, 512
+    x = np.full((T, h), 3.0, np.float32)
+    g = snap_bf16(np.linspace(0.5, 1.5, h).astype(np.float32)); bta = snap_bf16(np.linspace(-1, 1, h).astype(np.float32))
+    out = torch.empty(T, h, dtype=torch.bfloat16, device="cuda")
+    stats = torch.empty(T, 2, dtype=torch.float32, device="cuda")
+    B.axonn_layernorm_fwd(T, h, dev_bf16(x), dev_bf16(g), dev_bf16(bta), 1e-5, out, stats)
+    assert np.array_equal(host(out), np.broadcast_to(bta.astype(np.float64), (T, h)))
+
+
+@pytest.mark.parametrize("T,N,ld", [(256, 768, 768), (100, 520, 1024), (8, 8, 8), (2048, 1024, 1024)])
+def test_colsum(T, N, ld):
+    import torch
+    rng = np.random.default_rng(T + N)
+    y = _rng_bf16(rng, (T, ld))
+    out = torch.empty(N, dtype=torch.float32, device="cuda")
+    ws = torch.empty(((T + 63) // 64) * N, dtype=torch.float32, device="cuda")
+    B.axonn_colsum(T, N, dev_bf16(y), ld, out, ws)
+    assert rel_fro(host(out), y[:, :N].astype(np.float64).sum(0)) < 1e-5
+
+
+# -------------------------------------------------------------------- attention
+ATTN_SHAPES = [
+    (2, 128, 4, 64),    # tiny-config shape
+    (1, 256, 2, 128),   # two query tiles, head dim 128
+    (1, 200, 3, 128),   # ragged sequence (not a multiple of any tile)
+    (2, 72, 2, 64),     # shorter than one tile
+    (1, 8, 1, 64),      # minimum
+    (1, 520, 2, 128),   # several tiles + ragged tail
+]
+
+
+def _attn_ref(qkv, dout, b, s, a, d):
+    h = a * d
+    q3 = qkv.astype(np.float64).reshape(b, s, 3 * h)
+    q, k, v = q3[..., :h], q3[..., h:2 * h], q3[..., 2 * h:]
+    o, P = OT.causal_attention_fwd(q, k, v, a)
+    dq, dk, dv = OT.causal_attention_bwd(dout.astype(np.float64).reshape(b, s, h), q, k, v, P, a)
+    # lse from the definition (log of the masked sum of exp scores)
+    qh = q.reshape(b, s, a, d).transpose(0, 2, 1, 3); kh = k.reshape(b, s, a, d).transpose(0, 2, 1, 3)
+    S = qh @ kh.transpose(0, 1, 3, 2) / np.sqrt(d)
+    S = np.where(np.tril(np.ones((s, s), bool)), S, -np.inf)
+    mx = S.max(-1, keepdims=True)
+    lse = (mx + np.log(np.exp(S - mx).sum(-1, keepdims=True)))[..., 0]
+    return o.reshape(b * s, h), lse, np.concatenate([dq, dk, dv], -1).reshape(b * s, 3 * h)
+
+
+@pytest.mark.parametrize("b,s,a,d", ATTN_SHAPES)
+def test_attention_fwd_bwd(b, s, a, d):
+    import torch
+    rng = np.random.default_rng(b * 1000 + s + a + d)
+    h = a * d
+    qkv = _rng_bf16(rng, (b * s, 3 * h)); dout = _rng_bf16(rng, (b * s, h))
+    o_ref, lse_ref, dqkv_ref = _attn_ref(qkv, dout, b, s, a, d)
+    QKV, DO = dev_bf16(qkv), dev_bf16(dout)
+    o = torch.zeros(b * s, h, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(b, a, s, dtype=torch.float32, device="cuda")
+    B.axonn_attention_fwd(b, s, a, d, QKV, o, lse)
+    assert rel_fro(host(o), o_ref) < TOL
+    assert np.abs(host(lse) - lse_ref).max() < 2e-3
+    dqkv = torch.zeros(b * s, 3 * h, dtype=torch.bfloat16, device="cuda")
+    delta = torch.zeros(b * a * s, dtype=torch.float32, device="cuda")
+    B.axonn_attention_bwd(b, s, a, d, QKV, o, lse, DO, dqkv, delta)
+    got = host(dqkv)
+    # backward consumes the GPU's own bf16 o (one extra rounding in delta): 2x the single-op bound
+    for name, sl in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
+        assert rel_fro(got[:, sl], dqkv_ref[:, sl]) < 2 * TOL, name
+    # first token attends only to itself: its output is its value row (bit exact)
+    v0 = qkv.reshape(b, s, 3 * h)[:, 0, 2 * h:]
+    assert np.array_equal(host(o).reshape(b, s, h)[:, 0], v0.astype(np.float64))
+
+
+def test_attention_large_scores_stay_finite():
+    """Scores of order +-100: the running-max subtraction must keep exp in range."""
+    import torch
+    rng = np.random.default_rng(3)
+    b, s, a, d = 1, 192, 2, 64
+    h = a * d
+    qkv = _rng_bf16(rng, (b * s, 3 * h)); qkv[:, :2 * h] *= 4; qkv = snap_bf16(qkv)
+    o_ref, lse_ref, _ = _attn_ref(qkv, np.zeros((b * s, h), np.float32), b, s, a, d)
+    o = torch.zeros(b * s, h, dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros(b, a, s, dtype=torch.float32, device="cuda")
+    B.axonn_attention_fwd(b, s, a, d, dev_bf16(qkv), o, lse)
+    got = host(o)
+    assert np.isfinite(got).all() and rel_fro(got, o_ref) < TOL
+
+
+# ------------------------------------------------------------------------- Adam
+@pytest.mark.parametrize("n", [8, 1000, 65536 + 24, 1 << 20])
+@pytest.mark.parametrize("fresh,wd,step,gs", [(False, 0.0, 100, 1.0), (True, 0.01, 1, 0.25)])
+def test_adam_bucket_kernel(n, fresh, wd, step, gs):
+    import torch
+    from paper_2110_13005_amd.inputs import make_adam_inputs
+    th, m, v, g16 = make_adam_inputs(n, seed=n, fresh=fresh)
+    lr, b1, b2, eps = 1e-4, 0.9, 0.95, 1e-8
+    rt, rm, rv, r16 = oracle.adam_step(th, m, v, g16, lr, b1, b2, eps, wd, step, gs)
+    TH, Mm, V, G = dev_f32(th), dev_f32(m), dev_f32(v), dev_bf16(g16)
+    P16 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    B.axonn_adam_bucket(n, TH, Mm, V, G, P16, lr, b1, b2, eps, wd, step, gs)
+    assert rel_fro(host(TH), rt) <= 1e-6
+    assert rel_fro(host(Mm), rm) <= 1e-6
+    assert rel_fro(host(V), rv) <= 1e-6
+    # theta16 is the bf16 rounding of the GPU's own fp32 theta, bit for bit
+    assert torch.equal(P16, TH.to(torch.bfloat16))
+    # and within one bf16 ulp of the oracle's
+    assert np.abs(host(P16) - r16).max() <= np.abs(r16).max() * 2.0 ** -7

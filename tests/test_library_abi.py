@@ -1,0 +1,54 @@
+"""CPU-side checks of the C-ABI library: it loads without a GPU and exports every symbol the
+header declares; argument validation that needs no device returns the documented codes."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2110_13005_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _header_symbols():
+    text = open(os.path.join(ROOT, "include", "axonn_stage.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(axonn_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load()
+    syms = _header_symbols()
+    assert len(syms) >= 30
+    for s in syms:
+        assert hasattr(lib, s), "missing export: " + s
+    assert sorted(B.EXPORTED_SYMBOLS) == syms, "binding and header disagree"
+
+
+def test_argument_validation_without_device():
+    lib = B.load()
+    assert lib.axonn_stage_create(None, None) == B.AXONN_EINVAL
+    assert b"null" in lib.axonn_last_error()
+    out = ctypes.c_void_p()
+    cfg = B.axonn_stage_config(2, 256, 3, 1024, 128, 2, 4, 4, 1e-5, 0, 1)   # 256 % 3 != 0
+    assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EINVAL
+    cfg = B.axonn_stage_config(2, 256, 8, 1024, 128, 2, 4, 4, 1e-5, 0, 1)   # head dim 32
+    assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EUNSUPPORTED
+    assert b"head dim" in lib.axonn_last_error()
+    cfg = B.axonn_stage_config(2, 256, 4, 1024, 128, 2, 4, 5, 1e-5, 0, 1)   # pipeline_limit > M
+    assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EINVAL
+    cfg = B.axonn_stage_config(2, 256, 4, 1024, 3, 1, 4, 4, 1e-5, 0, 1)     # 3 tokens
+    assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EUNSUPPORTED
+    with pytest.raises(B.AxonnError) as e:
+        B.axonn_gemm_bf16(1, 0, 0, 64, 64, 60, 1, 64, 1, 64, 1, 64)          # K % 8 != 0
+    assert e.value.status == B.AXONN_EUNSUPPORTED
+    with pytest.raises(B.AxonnError) as e:
+        B.axonn_gemm_bf16(0, 1, 0, 64, 64, 64, 1, 64, 1, 64, 1, 64)          # layout not built
+    assert e.value.status == B.AXONN_EUNSUPPORTED
+    with pytest.raises(B.AxonnError) as e:
+        B.axonn_adam_bucket(8, 1, 1, 1, 1, 1, 1e-3, 0.9, 0.95, 1e-8, 0.0, 0, 1.0)  # step 0
+    assert e.value.status == B.AXONN_EINVAL
+    with pytest.raises(B.AxonnError) as e:
+        B.axonn_attention_fwd(1, 128, 4, 32, 1, 1, 1)
+    assert e.value.status == B.AXONN_EUNSUPPORTED
