@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the stage hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 12b] [--streams 2]
+
+A step is one batch through the whole hot path: start of batch, M forward and M backward
+messages through the message-driven scheduler, then the bucketed host-offloaded Adam step
+on the stage's parameters.  Inputs (weights, microbatch activations, upstream gradients,
+optimizer state) are resident before the timed region.  The headline `value` is the
+forward+backward rate (analytic causal FLOPs / time of the forward+backward region, which
+HIP events separate from the optimizer region inside every step); `ms_per_step` is the whole
+step including the optimizer.  One JSON line is printed.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", default="12b", choices=["tiny", "12b", "24b", "100b"])
+    ap.add_argument("--streams", type=int, default=2, help="library streams of the message-driven run")
+    ap.add_argument("--pipeline-limit", type=int, default=0, help="0 = all microbatches in flight")
+    ap.add_argument("--grad-accum", default="fp32", choices=["fp32", "bf16"])
+    ap.add_argument("--bucket-elems", type=int, default=1 << 26)
+    ap.add_argument("--no-optimizer", action="store_true", help="diagnostic: leave the Adam step out of the step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-profile", action="store_true")
+    return ap.parse_args()
+
+
+def cpu_baseline(shape):
+    """The fp64 oracle timed on the host: one layer, one microbatch of the workload."""
+    import oracle
+    from paper_2110_13005_amd import flops
+    from paper_2110_13005_amd.inputs import StageShape, make_stage_inputs
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    one = StageShape(1, shape.hidden, shape.n_heads, shape.seq_len, shape.microbatch_size, 1, shape.ffn_hidden)
+    layers, xs, dys = make_stage_inputs(one, seed=0)
+    t0 = time.perf_counter()
+    oracle.stage_batch(xs, dys, layers, one.n_heads, 1e-5)
+    dt = time.perf_counter() - t0
+    fl = flops.stage_batch_flops(one, causal=True)
+    frac = "1 of %d layers x 1 of %d microbatches" % (shape.n_layers, shape.n_microbatches)
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
+            "sample": "%s of the workload, fp64 numpy oracle, %.1f s; causal FLOP count" % (frac, dt),
+            "tokens_per_s": one.tokens / dt / shape.n_layers,
+            "seconds": dt}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives or sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2110_13005_amd import binding as B, flops
+    from paper_2110_13005_amd.inputs import CONFIGS, OPT_CONFIG
+    from paper_2110_13005_amd.stage import Stage
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.load()
+    sh = CONFIGS[args.config]
+    M = sh.n_microbatches
+    P = args.pipeline_limit or M
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(0)
+    g = torch.Generator(device=dev)
+    g.manual_seed(0)
+
+    st = Stage(sh, pipeline_limit=P, grad_accum_fp32=1 if args.grad_accum == "fp32" else 0)
+    n = st.n_params
+    # synthetic weights ~N(0, 0.02) (LayerNorm gains 1, biases 0), generated on the device in chunks;
+    # fp32 master copy in pinned host memory, bf16 copy = its rounding
+    host_ptrs, host_arrs = [], []
+    if not args.no_optimizer:
+        import ctypes
+        for _ in range(3):
+            p = B.axonn_pinned_alloc(4 * n)
+            host_ptrs.append(p)
+            host_arrs.append(torch.from_numpy(np.ctypeslib.as_array((ctypes.c_float * n).from_address(p))))
+    for name, (off, dims) in st.layout.items():
+        numel = int(np.prod(dims))
+        short = name.split(".")[1]
+        if short.startswith("w_"):
+            step = 1 << 26
+            for o in range(0, numel, step):
+                c = min(step, numel - o)
+                w = torch.randn(c, generator=g, device=dev, dtype=torch.float32) * 0.02
+                st.params[off + o: off + o + c] = w.to(torch.bfloat16)
+                if host_arrs:
+                    host_arrs[0][off + o: off + o + c] = w.cpu()
+        elif host_arrs:
+            host_arrs[0][off: off + numel] = st.params[off: off + numel].float().cpu()
+    if host_arrs:
+        # mid-training optimizer state: m ~ N(0,1e-4), v = |N(0,1e-6)|
+        step = 1 << 26
+        for o in range(0, n, step):
+            c = min(step, n - o)
+            host_arrs[1][o:o + c] = (torch.randn(c, generator=g, device=dev) * 1e-4).cpu()
+            host_arrs[2][o:o + c] = (torch.randn(c, generator=g, device=dev) * 1e-6).abs().cpu()
+        B.axonn_stage_optimizer_attach(st.handle, host_ptrs[0], host_ptrs[1], host_ptrs[2], n, args.bucket_elems)
+    bsh = (sh.microbatch_size, sh.seq_len, sh.hidden)
+    X = [torch.randn(bsh, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(M)]
+    # upstream gradients ~N(0,1), as a neighbouring stage would send them (any 1/M lives in grad_scale)
+    DY = [torch.randn(bsh, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(M)]
+    Y = [torch.empty(bsh, device=dev, dtype=torch.bfloat16) for _ in range(M)]
+    DX = [torch.empty(bsh, device=dev, dtype=torch.bfloat16) for _ in range(M)]
+    torch.cuda.synchronize()
+
+    # message order of a middle stage: P forwards of warm-up, then one backward / one forward, then drain
+    order, f, b = [], 0, 0
+    while f < min(P, M):
+        order.append((0, f)); f += 1
+    while b < M:
+        order.append((1, b)); b += 1
+        if f < M:
+            order.append((0, f)); f += 1
+
+    main_stream = torch.cuda.Stream()
+    oc = OPT_CONFIG
+
+    def one_step(step_no, ev):
+        with torch.cuda.stream(main_stream):
+            ev[0].record(main_stream)
+            st.zero_grad(main_stream)
+            for kind, i in order:
+                st.post(kind, i, X[i] if kind == 0 else DY[i], Y[i] if kind == 0 else DX[i])
+            st.run(args.streams, main_stream)
+            st.join(main_stream)
+            ev[1].record(main_stream)
+            if not args.no_optimizer:
+                B.axonn_stage_optimizer_step(st.handle, oc["lr"], oc["beta1"], oc["beta2"], oc["eps"], oc["weight_decay"],
+                                             oc["step"] + step_no, 1.0 / M, main_stream)
+            ev[2].record(main_stream)
+
+    def events():
+        return [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+
+    for w in range(args.warmup):
+        one_step(w, events())
+    torch.cuda.synchronize()
+    evs = [events() for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        one_step(args.warmup + k, evs[k])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    fb_ms = [e[0].elapsed_time(e[1]) for e in evs]
+    opt_ms = [e[1].elapsed_time(e[2]) for e in evs]
+    fb_mean = float(np.mean(fb_ms))
+    fl = flops.stage_batch_flops(sh, causal=True)
+    fl_paper = flops.stage_batch_flops(sh, causal=False)
+    tflops = fl / (fb_mean * 1e-3) / 1e12
+    tokens = M * sh.tokens
+
+    out = {
+        "metric": "stage fwd+bwd TFLOP/s per MI355X and % of bf16 MFMA peak; tokens/s",
+        "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s stage: %d layers, h=%d, heads=%d, ffn=%d, seq=%d, microbatch=%d, %d microbatches, "
+                               "pipeline_limit=%d" % (args.config, sh.n_layers, sh.hidden, sh.n_heads, sh.ffn,
+                                                      sh.seq_len, sh.microbatch_size, M, P),
+                   "streams": args.streams, "grad_accum": args.grad_accum, "bucket_elems": args.bucket_elems,
+                   "optimizer_in_step": not args.no_optimizer},
+        "pct_of_bf16_mfma_peak": 100.0 * tflops / flops.PEAK_BF16_DENSE_TFLOPS,
+        "peak_tflops_used": flops.PEAK_BF16_DENSE_TFLOPS,
+        "tokens_per_s": tokens / (fb_mean * 1e-3),
+        "tokens_per_s_whole_step": tokens / (wall / args.steps),
+        "fwd_bwd_ms": {"mean": fb_mean, "min": float(np.min(fb_ms))},
+        "tflops_paper_convention": fl_paper / (fb_mean * 1e-3) / 1e12,
+        "paper_context": "49.4-54.78% of V100 fp16 peak per GPU on 48-384 V100s (whole system, counts recompute)",
+    }
+    if not args.no_optimizer:
+        om = float(np.mean(opt_ms))
+        out["optimizer"] = {"ms": om, "params": n, "host_link_GBps_each_way": 12.0 * n / (om * 1e-3) / 1e9,
+                            "buckets": (n + args.bucket_elems - 1) // args.bucket_elems}
+
+    # per-kernel averages: one more batch on a single stream with launch timing on
+    if not args.no_kernel_profile:
+        B.axonn_profile_enable(True)
+        with torch.cuda.stream(main_stream):
+            st.zero_grad(main_stream)
+            for kind, i in order:
+                st.post(kind, i, X[i] if kind == 0 else DY[i], Y[i] if kind == 0 else DX[i])
+            st.run(1, main_stream)
+            st.join(main_stream)
+        torch.cuda.synchronize()
+        prof = B.axonn_profile_collect()
+        B.axonn_profile_enable(False)
+        h, f_, T = sh.hidden, sh.ffn, sh.tokens
+        per_layer_mb = 2 * T * (4 * h * h + 2 * h * f_)          # FLOPs of one GEMM layout per layer per microbatch
+        kern = {}
+        for cat, (ms, cnt) in prof.items():
+            if cnt:
+                kern[cat] = {"launches": int(cnt), "avg_ms": ms / cnt, "total_ms": ms}
+        for cat in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"):
+            if cat in kern:
+                kern[cat]["tflops"] = per_layer_mb * sh.n_layers * M / (kern[cat]["total_ms"] * 1e-3) / 1e12
+        out["kernels"] = kern
+        dom = max((c for c in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad") if c in kern), key=lambda c: kern[c]["total_ms"])
+        ach = kern[dom]["tflops"]
+        out["roofline"] = {"bound": "mfma", "achieved": ach, "peak": flops.PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
+                           "frac": ach / flops.PEAK_BF16_DENSE_TFLOPS, "traffic": None, "kernel": dom,
+                           "avg_launch_ms": kern[dom]["avg_ms"],
+                           "flops_per_launch": per_layer_mb / 4.0}
+    st.close()
+    for p in host_ptrs:
+        B.axonn_pinned_free(p)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(sh)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -127,9 +127,10 @@ int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg);
  * arrived (event query) and that is admissible (forward: a stash slot is free; backward:
  * its forward was issued) and launches Forward or Backward for it.  Forwards go round
  * robin over n_streams-1 library streams, backwards to their own stream (n_streams = 1:
- * one stream for both).  Returns AXONN_ESTATE if messages remain but none can ever
+ * one stream for both); they start after everything already queued on hip_stream (use
+ * axonn_stage_join to make hip_stream wait for them in turn).  Returns AXONN_ESTATE if messages remain but none can ever
  * become admissible.  Work is only enqueued; see axonn_stage_synchronize. */
-int axonn_stage_run(axonn_stage_t* st, int32_t n_streams);
+int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream);
 /* Makes user_stream wait for everything the library streams have been given so far. */
 int axonn_stage_join(axonn_stage_t* st, void* user_stream);
 /* Blocks the host until all enqueued work of the stage is complete. */
@@ -148,6 +149,8 @@ int axonn_stage_dispatch_log(const axonn_stage_t* st, int32_t* out, int32_t capa
  *   g = grad_scale * float(grad16);  m = b1*m + (1-b1)*g;  v = b2*v + (1-b2)*g*g
  *   theta -= lr * ( (m/(1-b1^t)) / (sqrt(v/(1-b2^t)) + eps) + weight_decay*theta )
  *   theta16 = bf16_rne(theta)
+ * Hyper-parameters are doubles: 1-b1, 1-b2 and the bias corrections are formed in double
+ * on the host and rounded once to the kernel's float constants.
  * ---------------------------------------------------------------------------------- */
 typedef struct axonn_offload_adam axonn_offload_adam_t;
 /* n parameters; param16_dev / grad16_dev are caller-owned device bf16 arrays of n
@@ -161,8 +164,8 @@ int axonn_offload_adam_create(int32_t device, uint64_t n, uint64_t bucket_elems,
 int axonn_offload_adam_destroy(axonn_offload_adam_t* opt);
 /* Enqueues one full step (all buckets).  The work starts after everything already in
  * hip_stream and hip_stream waits for its end; step t >= 1. */
-int axonn_offload_adam_step(axonn_offload_adam_t* opt, float lr, float beta1, float beta2,
-                            float eps, float weight_decay, int64_t step, float grad_scale,
+int axonn_offload_adam_step(axonn_offload_adam_t* opt, double lr, double beta1, double beta2,
+                            double eps, double weight_decay, int64_t step, double grad_scale,
                             void* hip_stream);
 int axonn_offload_adam_device_bytes(const axonn_offload_adam_t* opt, uint64_t* bytes);
 
@@ -171,9 +174,9 @@ int axonn_offload_adam_device_bytes(const axonn_offload_adam_t* opt, uint64_t* b
  * microbatches are in flight. */
 int axonn_stage_optimizer_attach(axonn_stage_t* st, float* host_master, float* host_m,
                                  float* host_v, uint64_t n, uint64_t bucket_elems);
-int axonn_stage_optimizer_step(axonn_stage_t* st, float lr, float beta1, float beta2,
-                               float eps, float weight_decay, int64_t step,
-                               float grad_scale, void* hip_stream);
+int axonn_stage_optimizer_step(axonn_stage_t* st, double lr, double beta1, double beta2,
+                               double eps, double weight_decay, int64_t step,
+                               double grad_scale, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------
  * Single operations of the layer (the kernels Forward/Backward are built from), exposed
@@ -230,8 +233,23 @@ int axonn_attention_bwd(int32_t b, int32_t s, int32_t n_heads, int32_t head_dim,
 /* Adam update of n elements resident on the device (one bucket's kernel, formula above).
  * theta/m/v float32 are updated in place; grad16 is read; param16 is written. */
 int axonn_adam_bucket(uint64_t n, float* theta, float* m, float* v, const void* grad16,
-                      void* param16, float lr, float beta1, float beta2, float eps,
-                      float weight_decay, int64_t step, float grad_scale, void* hip_stream);
+                      void* param16, double lr, double beta1, double beta2, double eps,
+                      double weight_decay, int64_t step, double grad_scale, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------
+ * Launch timing (measurement aid, off by default).  While enabled, every kernel launch the
+ * library makes is bracketed by a pair of HIP events on the stream it is launched on;
+ * collect() waits for them, adds up elapsed milliseconds and launch counts per category
+ * and clears the records.  Categories (num_categories of them, names by index): the three
+ * GEMM layouts, attention forward / backward, LayerNorm forward / backward, column sums,
+ * small accumulations, gradient conversion, Adam, input copy.  Process-wide, not
+ * thread-safe.  Intervals of kernels that overlap on different streams are each counted
+ * in full.
+ * ---------------------------------------------------------------------------------- */
+int axonn_profile_enable(int32_t on);
+int axonn_profile_num_categories(int32_t* n);
+int axonn_profile_category_name(int32_t idx, const char** name);
+int axonn_profile_collect(double* total_ms, int64_t* launches, int32_t n_categories);
 
 #ifdef __cplusplus
 }

@@ -35,7 +35,7 @@ class axonn_msg(C.Structure):
                 ("result_dev", C.c_void_p), ("ready_event", C.c_void_p)]
 
 
-_vp, _i32, _i64, _u64, _f = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float
+_vp, _i32, _i64, _u64, _f, _d = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float, C.c_double
 _PROTOTYPES = {
     "axonn_pinned_alloc": [C.POINTER(_vp), _u64],
     "axonn_pinned_free": [_vp],
@@ -51,16 +51,16 @@ _PROTOTYPES = {
     "axonn_stage_forward": [_vp, _i32, _vp, _vp, _vp],
     "axonn_stage_backward": [_vp, _i32, _vp, _vp, _vp],
     "axonn_stage_post": [_vp, C.POINTER(axonn_msg)],
-    "axonn_stage_run": [_vp, _i32],
+    "axonn_stage_run": [_vp, _i32, _vp],
     "axonn_stage_join": [_vp, _vp],
     "axonn_stage_synchronize": [_vp],
     "axonn_stage_dispatch_log": [_vp, C.POINTER(_i32), _i32, C.POINTER(_i32)],
     "axonn_offload_adam_create": [_i32, _u64, _u64, _vp, _vp, _vp, _vp, _vp, C.POINTER(_vp)],
     "axonn_offload_adam_destroy": [_vp],
-    "axonn_offload_adam_step": [_vp, _f, _f, _f, _f, _f, _i64, _f, _vp],
+    "axonn_offload_adam_step": [_vp, _d, _d, _d, _d, _d, _i64, _d, _vp],
     "axonn_offload_adam_device_bytes": [_vp, C.POINTER(_u64)],
     "axonn_stage_optimizer_attach": [_vp, _vp, _vp, _vp, _u64, _u64],
-    "axonn_stage_optimizer_step": [_vp, _f, _f, _f, _f, _f, _i64, _f, _vp],
+    "axonn_stage_optimizer_step": [_vp, _d, _d, _d, _d, _d, _i64, _d, _vp],
     "axonn_gemm_bf16": [_i32, _i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64,
                         _vp, _i64, _i32, _vp],
     "axonn_layernorm_fwd": [_i64, _i64, _vp, _vp, _vp, _f, _vp, _vp, _vp],
@@ -68,7 +68,11 @@ _PROTOTYPES = {
     "axonn_colsum": [_i64, _i64, _vp, _i64, _vp, _vp, _vp],
     "axonn_attention_fwd": [_i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
     "axonn_attention_bwd": [_i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
-    "axonn_adam_bucket": [_u64, _vp, _vp, _vp, _vp, _vp, _f, _f, _f, _f, _f, _i64, _f, _vp],
+    "axonn_profile_enable": [_i32],
+    "axonn_profile_num_categories": [C.POINTER(_i32)],
+    "axonn_profile_category_name": [_i32, C.POINTER(C.c_char_p)],
+    "axonn_profile_collect": [C.POINTER(C.c_double), C.POINTER(_i64), _i32],
+    "axonn_adam_bucket": [_u64, _vp, _vp, _vp, _vp, _vp, _d, _d, _d, _d, _d, _i64, _d, _vp],
 }
 EXPORTED_SYMBOLS = ["axonn_last_error"] + sorted(_PROTOTYPES)
 
@@ -81,6 +85,10 @@ def load():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ImportError("%s not found: build it with `python -m paper_2110_13005_amd.build`" % LIB_PATH)
+        # torch brings its own HIP runtime; it must be the one already in the process when this
+        # library's dependency on libamdhip64 is resolved, or the two runtimes do not share devices,
+        # streams and allocations
+        import torch  # noqa: F401
         lib = C.CDLL(LIB_PATH)
         lib.axonn_last_error.restype = C.c_char_p
         lib.axonn_last_error.argtypes = []
@@ -199,8 +207,8 @@ def axonn_stage_post(st, kind, mb_id, payload, result, ready_event=None):
     _check(load().axonn_stage_post(st, C.byref(m)))
 
 
-def axonn_stage_run(st, n_streams=2):
-    _check(load().axonn_stage_run(st, n_streams))
+def axonn_stage_run(st, n_streams=2, stream=None):
+    _check(load().axonn_stage_run(st, n_streams, _stream(stream)))
 
 
 def axonn_stage_join(st, stream=None):
@@ -279,6 +287,31 @@ def axonn_adam_bucket(n, theta, m, v, grad16, param16, lr, beta1, beta2, eps, we
                       stream=None):
     _check(load().axonn_adam_bucket(n, _ptr(theta), _ptr(m), _ptr(v), _ptr(grad16), _ptr(param16), lr, beta1, beta2,
                                     eps, weight_decay, step, grad_scale, _stream(stream)))
+
+
+def axonn_profile_enable(on):
+    _check(load().axonn_profile_enable(1 if on else 0))
+
+
+def axonn_profile_num_categories():
+    n = _i32()
+    _check(load().axonn_profile_num_categories(C.byref(n)))
+    return n.value
+
+
+def axonn_profile_category_name(idx):
+    name = C.c_char_p()
+    _check(load().axonn_profile_category_name(idx, C.byref(name)))
+    return name.value.decode()
+
+
+def axonn_profile_collect():
+    """-> {category: (total_ms, launches)}"""
+    n = axonn_profile_num_categories()
+    ms = (C.c_double * n)()
+    cnt = (_i64 * n)()
+    _check(load().axonn_profile_collect(ms, cnt, n))
+    return {axonn_profile_category_name(i): (ms[i], cnt[i]) for i in range(n)}
 
 
 def make_config(shape, pipeline_limit=None, ln_eps=1e-5, device=0, grad_accum_fp32=1, n_microbatches=None):

@@ -122,7 +122,7 @@ hipError_t launch_attention_bwd(int b, int s, int a, int d, const void* qkv, con
                                 const float* lse, const void* dout, void* dqkv, float* delta,
                                 hipStream_t st);
 hipError_t launch_adam(uint64_t n, float* theta, float* m, float* v, const void* g16,
-                       void* p16, float lr, float b1, float b2, float eps, float wd,
-                       int64_t step, float grad_scale, hipStream_t s);
+                       void* p16, double lr, double b1, double b2, double eps, double wd,
+                       int64_t step, double grad_scale, hipStream_t s);
 
 }  // namespace axonn

@@ -234,13 +234,13 @@ __global__ __launch_bounds__(256) void fill_bf16_kernel(uint64_t n, bf16_t* dst,
 // Adam with decoupled weight decay on one resident bucket: per element 12 B of fp32 state and
 // 2 B of bf16 gradient in, 12 B of state and 2 B of bf16 parameter out.
 struct AdamConsts {
-  float lr, b1, b2, eps, wd, grad_scale, inv_bc1, inv_bc2;
+  float lr, b1, b2, omb1, omb2, eps, wd, grad_scale, inv_bc1, inv_bc2;
 };
 __device__ __forceinline__ void adam_elem(float& th, float& m, float& v, float g16,
                                           const AdamConsts& c) {
   const float g = c.grad_scale * g16;
-  m = c.b1 * m + (1.f - c.b1) * g;
-  v = c.b2 * v + (1.f - c.b2) * g * g;
+  m = c.b1 * m + c.omb1 * g;
+  v = c.b2 * v + c.omb2 * g * g;
   const float mhat = m * c.inv_bc1;
   const float vhat = v * c.inv_bc2;
   th = th - c.lr * (mhat / (sqrtf(vhat) + c.eps) + c.wd * th);
@@ -350,13 +350,16 @@ hipError_t launch_fill_bf16(uint64_t n, void* dst, float value, hipStream_t s) {
 }
 
 hipError_t launch_adam(uint64_t n, float* theta, float* m, float* v, const void* g16, void* p16,
-                       float lr, float b1, float b2, float eps, float wd, int64_t step,
-                       float grad_scale, hipStream_t s) {
+                       double lr, double b1, double b2, double eps, double wd, int64_t step,
+                       double grad_scale, hipStream_t s) {
   AdamConsts c;
-  c.lr = lr; c.b1 = b1; c.b2 = b2; c.eps = eps; c.wd = wd; c.grad_scale = grad_scale;
-  // bias corrections in double on the host: 1 - beta^t loses digits in float for beta near 1
-  c.inv_bc1 = (float)(1.0 / (1.0 - pow((double)b1, (double)step)));
-  c.inv_bc2 = (float)(1.0 / (1.0 - pow((double)b2, (double)step)));
+  c.lr = (float)lr; c.b1 = (float)b1; c.b2 = (float)b2; c.eps = (float)eps; c.wd = (float)wd;
+  c.grad_scale = (float)grad_scale;
+  // 1 - beta and the bias corrections in double on the host: they lose digits in float for
+  // beta near 1
+  c.omb1 = (float)(1.0 - b1); c.omb2 = (float)(1.0 - b2);
+  c.inv_bc1 = (float)(1.0 / (1.0 - pow(b1, (double)step)));
+  c.inv_bc2 = (float)(1.0 / (1.0 - pow(b2, (double)step)));
   hipLaunchKernelGGL(adam_kernel, dim3(grid_for(n / 8)), dim3(256), 0, s, n / 8, n, theta, m, v,
                      (const bf16_t*)g16, (bf16_t*)p16, c);
   return hipGetLastError();

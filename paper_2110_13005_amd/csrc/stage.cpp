@@ -46,6 +46,38 @@ int fail(int code, const char* fmt, ...) {
     if (r_ != AXONN_OK) return r_; \
   } while (0)
 
+
+// ---- optional per-launch timing: event pairs around every kernel launch, by category ----
+enum ProfCat { PC_GEMM_FWD, PC_GEMM_DGRAD, PC_GEMM_WGRAD, PC_ATTN_FWD, PC_ATTN_BWD, PC_LN_FWD,
+               PC_LN_BWD, PC_COLSUM, PC_ACCUM_VEC, PC_GRAD_CONVERT, PC_ADAM, PC_COPY_IN, PC_COUNT };
+const char* const kProfNames[PC_COUNT] = {
+    "gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attention_fwd", "attention_bwd", "layernorm_fwd",
+    "layernorm_bwd", "colsum", "accum_vec", "grad_convert", "adam", "copy_in"};
+struct ProfRec { int cat; hipEvent_t a, b; };
+bool g_prof_on = false;
+std::vector<ProfRec> g_prof_recs;
+std::vector<hipEvent_t> g_prof_pool;
+
+hipEvent_t prof_event() {
+  if (!g_prof_pool.empty()) { hipEvent_t e = g_prof_pool.back(); g_prof_pool.pop_back(); return e; }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+struct ProfScope {
+  hipStream_t s; hipEvent_t a = nullptr, b = nullptr; int cat;
+  ProfScope(int cat_, hipStream_t s_) : s(s_), cat(cat_) {
+    if (!g_prof_on) return;
+    a = prof_event(); b = prof_event();
+    if (a && b) (void)hipEventRecord(a, s);
+  }
+  ~ProfScope() {
+    if (!a || !b) return;
+    (void)hipEventRecord(b, s);
+    g_prof_recs.push_back(ProfRec{cat, a, b});
+  }
+};
+
 constexpr int kTensorsPerLayer = 12;
 const char* const kTensorNames[kTensorsPerLayer] = {
     "ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
@@ -114,7 +146,7 @@ struct axonn_stage {
   // state
   int in_flight = 0;
   int bwd_count = 0;  // backwards since the last zero_grad
-  hipEvent_t last_bwd = nullptr;
+  hipEvent_t last_bwd = nullptr, fork_ev = nullptr;
   bool last_bwd_recorded = false;
   // message-driven mode
   std::deque<PendingMsg> inbox;
@@ -149,7 +181,38 @@ int gemm(bool a_kc, bool b_kc, int epi, int M, int N, int K, const void* A, int6
   g.bias = (const bf16_t*)bias; g.res = (const bf16_t*)res; g.aux = (bf16_t*)aux;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ld_res = ld_res; g.ld_aux = ld_aux;
   g.M = M; g.N = N; g.K = K; g.accumulate = accumulate; g.tiles_m = g.tiles_n = 0;
+  ProfScope ps(a_kc ? (b_kc ? PC_GEMM_DGRAD : PC_GEMM_FWD) : PC_GEMM_WGRAD, s);
   return check_launch(launch_gemm(a_kc, b_kc, epi, g, s), "gemm");
+}
+
+
+int ln_fwd(int64_t T, int64_t h, const void* x, const void* g, const void* b, float eps, void* out,
+           float* stats, hipStream_t s) {
+  ProfScope ps(PC_LN_FWD, s);
+  return check_launch(launch_layernorm_fwd(T, h, x, g, b, eps, out, stats, s), "layernorm_fwd");
+}
+int ln_bwd(int64_t T, int64_t h, const void* dout, const void* x, const float* stats, const void* g,
+           const void* res, void* dx, float* dg, float* db, float* ws, hipStream_t s) {
+  ProfScope ps(PC_LN_BWD, s);
+  return check_launch(launch_layernorm_bwd(T, h, dout, x, stats, g, res, dx, dg, db, ws, s), "layernorm_bwd");
+}
+int colsum(int64_t T, int64_t N, const void* y, int64_t ldy, float* out, float* ws, hipStream_t s) {
+  ProfScope ps(PC_COLSUM, s);
+  return check_launch(launch_colsum(T, N, y, ldy, out, ws, s), "colsum");
+}
+int attn_fwd(int b, int sq, int a, int d, const void* qkv, void* o, float* lse, hipStream_t s) {
+  ProfScope ps(PC_ATTN_FWD, s);
+  return check_launch(launch_attention_fwd(b, sq, a, d, qkv, o, lse, s), "attention_fwd");
+}
+int attn_bwd(int b, int sq, int a, int d, const void* qkv, const void* o, const float* lse, const void* dout,
+             void* dqkv, float* delta, hipStream_t s) {
+  ProfScope ps(PC_ATTN_BWD, s);
+  return check_launch(launch_attention_bwd(b, sq, a, d, qkv, o, lse, dout, dqkv, delta, s), "attention_bwd");
+}
+int adam(uint64_t n, float* th, float* m, float* v, const void* g16, void* p16, double lr, double b1, double b2,
+         double eps, double wd, int64_t step, double gs, hipStream_t s) {
+  ProfScope ps(PC_ADAM, s);
+  return check_launch(launch_adam(n, th, m, v, g16, p16, lr, b1, b2, eps, wd, step, gs, s), "adam");
 }
 
 // -------------------------------------------------------------------- forward of a slot
@@ -158,16 +221,13 @@ int forward_layers(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s) {
   for (int l = 0; l < L; ++l) {
     LayerStash& a = slot.layers[l];
     bf16_t* z = (l + 1 < L) ? slot.layers[l + 1].x : (bf16_t*)y_out;
-    AX_TRY(check_launch(launch_layernorm_fwd(T, h, a.x, param_ptr(st, l, P_LN1G), param_ptr(st, l, P_LN1B),
-                                             st->cfg.ln_eps, a.u, a.stats1, s), "layernorm_fwd"));
+    AX_TRY(ln_fwd(T, h, a.x, param_ptr(st, l, P_LN1G), param_ptr(st, l, P_LN1B), st->cfg.ln_eps, a.u, a.stats1, s));
     AX_TRY(gemm(true, false, EPI_BIAS, T, 3 * h, h, a.u, h, param_ptr(st, l, P_WQKV), 3 * h, a.qkv, 3 * h,
                 param_ptr(st, l, P_BQKV), nullptr, 0, nullptr, 0, 0, s));
-    AX_TRY(check_launch(launch_attention_fwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d,
-                                             a.qkv, a.o, a.lse, s), "attention_fwd"));
+    AX_TRY(attn_fwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d, a.qkv, a.o, a.lse, s));
     AX_TRY(gemm(true, false, EPI_BIAS_RES, T, h, h, a.o, h, param_ptr(st, l, P_WO), h, a.y, h,
                 param_ptr(st, l, P_BO), a.x, h, nullptr, 0, 0, s));
-    AX_TRY(check_launch(launch_layernorm_fwd(T, h, a.y, param_ptr(st, l, P_LN2G), param_ptr(st, l, P_LN2B),
-                                             st->cfg.ln_eps, a.w, a.stats2, s), "layernorm_fwd"));
+    AX_TRY(ln_fwd(T, h, a.y, param_ptr(st, l, P_LN2G), param_ptr(st, l, P_LN2B), st->cfg.ln_eps, a.w, a.stats2, s));
     AX_TRY(gemm(true, false, EPI_BIAS_GELU, T, f, h, a.w, h, param_ptr(st, l, P_WFC1), f, a.g, f,
                 param_ptr(st, l, P_BFC1), nullptr, 0, a.pre, f, 0, s));
     AX_TRY(gemm(true, false, EPI_BIAS_RES, T, h, f, a.g, f, param_ptr(st, l, P_WFC2), h, z, h,
@@ -178,6 +238,7 @@ int forward_layers(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s) {
 
 // ------------------------------------------------------------------- backward of a slot
 int vec_grad(axonn_stage* st, int layer, int which, const float* src, int n, int acc, hipStream_t s) {
+  ProfScope ps(PC_ACCUM_VEC, s);
   return check_launch(launch_accum_vec(n, src, grad_ptr(st, layer, which), st->cfg.grad_accum_fp32 != 0,
                                        acc != 0, s), "accum_vec");
 }
@@ -194,18 +255,18 @@ int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out
                 nullptr, nullptr, 0, a.pre, f, 0, s));
     AX_TRY(gemm(false, false, wg_epi, f, h, T, a.g, f, d_in, h, grad_ptr(st, l, P_WFC2), h,
                 nullptr, nullptr, 0, nullptr, 0, acc, s));
-    AX_TRY(check_launch(launch_colsum(T, h, d_in, h, st->vec0, st->red_ws, s), "colsum"));
+    AX_TRY(colsum(T, h, d_in, h, st->vec0, st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_BFC2, st->vec0, h, acc, s));
     // pre = w W1 + b1
     AX_TRY(gemm(true, true, EPI_BIAS, T, h, f, st->dpre, f, param_ptr(st, l, P_WFC1), f, st->dw, h,
                 nullptr, nullptr, 0, nullptr, 0, 0, s));
     AX_TRY(gemm(false, false, wg_epi, h, f, T, a.w, h, st->dpre, f, grad_ptr(st, l, P_WFC1), f,
                 nullptr, nullptr, 0, nullptr, 0, acc, s));
-    AX_TRY(check_launch(launch_colsum(T, f, st->dpre, f, st->vec0, st->red_ws, s), "colsum"));
+    AX_TRY(colsum(T, f, st->dpre, f, st->vec0, st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_BFC1, st->vec0, f, acc, s));
     // w = LN2(y); residual: dy = d_in + dLN2
-    AX_TRY(check_launch(launch_layernorm_bwd(T, h, st->dw, a.y, a.stats2, param_ptr(st, l, P_LN2G), d_in,
-                                             st->dy_mid, st->vec0, st->vec1, st->red_ws, s), "layernorm_bwd"));
+    AX_TRY(ln_bwd(T, h, st->dw, a.y, a.stats2, param_ptr(st, l, P_LN2G), d_in, st->dy_mid, st->vec0, st->vec1,
+                  st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_LN2G, st->vec0, h, acc, s));
     AX_TRY(vec_grad(st, l, P_LN2B, st->vec1, h, acc, s));
     // y = x + o Wo + bo
@@ -213,22 +274,21 @@ int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out
                 nullptr, nullptr, 0, nullptr, 0, 0, s));
     AX_TRY(gemm(false, false, wg_epi, h, h, T, a.o, h, st->dy_mid, h, grad_ptr(st, l, P_WO), h,
                 nullptr, nullptr, 0, nullptr, 0, acc, s));
-    AX_TRY(check_launch(launch_colsum(T, h, st->dy_mid, h, st->vec0, st->red_ws, s), "colsum"));
+    AX_TRY(colsum(T, h, st->dy_mid, h, st->vec0, st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_BO, st->vec0, h, acc, s));
     // attention
-    AX_TRY(check_launch(launch_attention_bwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d,
-                                             a.qkv, a.o, a.lse, st->dattn, st->dqkv, st->delta, s),
-                        "attention_bwd"));
+    AX_TRY(attn_bwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d, a.qkv, a.o, a.lse, st->dattn,
+                    st->dqkv, st->delta, s));
     // qkv = u Wqkv + b
     AX_TRY(gemm(true, true, EPI_BIAS, T, h, 3 * h, st->dqkv, 3 * h, param_ptr(st, l, P_WQKV), 3 * h, st->du, h,
                 nullptr, nullptr, 0, nullptr, 0, 0, s));
     AX_TRY(gemm(false, false, wg_epi, h, 3 * h, T, a.u, h, st->dqkv, 3 * h, grad_ptr(st, l, P_WQKV), 3 * h,
                 nullptr, nullptr, 0, nullptr, 0, acc, s));
-    AX_TRY(check_launch(launch_colsum(T, 3 * h, st->dqkv, 3 * h, st->vec0, st->red_ws, s), "colsum"));
+    AX_TRY(colsum(T, 3 * h, st->dqkv, 3 * h, st->vec0, st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_BQKV, st->vec0, 3 * h, acc, s));
     // u = LN1(x); residual: dx = dy + dLN1
-    AX_TRY(check_launch(launch_layernorm_bwd(T, h, st->du, a.x, a.stats1, param_ptr(st, l, P_LN1G), st->dy_mid,
-                                             d_out, st->vec0, st->vec1, st->red_ws, s), "layernorm_bwd"));
+    AX_TRY(ln_bwd(T, h, st->du, a.x, a.stats1, param_ptr(st, l, P_LN1G), st->dy_mid, d_out, st->vec0, st->vec1,
+                  st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_LN1G, st->vec0, h, acc, s));
     AX_TRY(vec_grad(st, l, P_LN1B, st->vec1, h, acc, s));
     d_in = d_out;
@@ -253,7 +313,10 @@ int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s
   // the slot's previous occupant must have finished its backward before it is overwritten
   if (slot->bwd_recorded) HIP_TRY(hipStreamWaitEvent(s, slot->bwd_done, 0));
   const uint64_t bytes = (uint64_t)st->T * st->h * sizeof(bf16_t);
-  HIP_TRY(hipMemcpyAsync(slot->layers[0].x, x, bytes, hipMemcpyDeviceToDevice, s));
+  {
+    ProfScope ps(PC_COPY_IN, s);
+    HIP_TRY(hipMemcpyAsync(slot->layers[0].x, x, bytes, hipMemcpyDeviceToDevice, s));
+  }
   AX_TRY(forward_layers(st, *slot, y, s));
   HIP_TRY(hipEventRecord(slot->fwd_done, s));
   slot->mb_id = mb_id;
@@ -270,8 +333,10 @@ int do_backward(axonn_stage* st, int mb_id, const void* dy, void* dx, hipStream_
   const int acc = st->bwd_count > 0 ? 1 : 0;
   AX_TRY(backward_layers(st, *slot, dy, dx, acc, s));
   st->bwd_count++;
-  if (st->cfg.grad_accum_fp32 && st->bwd_count == st->cfg.n_microbatches)
+  if (st->cfg.grad_accum_fp32 && st->bwd_count == st->cfg.n_microbatches) {
+    ProfScope ps(PC_GRAD_CONVERT, s);
     AX_TRY(check_launch(launch_f32_to_bf16(st->n_params, st->grads32, st->grads, s), "f32_to_bf16"));
+  }
   HIP_TRY(hipEventRecord(slot->bwd_done, s));
   slot->bwd_recorded = true;
   HIP_TRY(hipEventRecord(st->last_bwd, s));
@@ -326,6 +391,7 @@ void destroy_stage(axonn_stage* st) {
   for (hipStream_t s : st->streams) (void)hipStreamDestroy(s);
   for (hipEvent_t e : st->stream_tail) (void)hipEventDestroy(e);
   if (st->last_bwd) (void)hipEventDestroy(st->last_bwd);
+  if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
   if (st->ws_base) (void)hipFree(st->ws_base);
   if (st->params) (void)hipFree(st->params);
   if (st->grads) (void)hipFree(st->grads);
@@ -461,6 +527,7 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
     st->vec0 = (float*)p; p += e_vec; st->vec1 = (float*)p; p += e_vec;
   }
   CREATE_TRY(hipEventCreateWithFlags(&st->last_bwd, hipEventDisableTiming));
+  CREATE_TRY(hipEventCreateWithFlags(&st->fork_ev, hipEventDisableTiming));
   CREATE_TRY(hipDeviceSynchronize());
 #undef CREATE_TRY
   *out = st;
@@ -558,11 +625,14 @@ int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg) {
   return AXONN_OK;
 }
 
-int axonn_stage_run(axonn_stage_t* st, int32_t n_streams) {
+int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream) {
   if (!st) return fail(AXONN_EINVAL, "run: null handle");
   if (n_streams < 1 || n_streams > 8) return fail(AXONN_EINVAL, "run: n_streams must be in 1..8");
   HIP_TRY(hipSetDevice(st->cfg.device));
   AX_TRY(ensure_streams(st, n_streams));
+  // the library streams start after everything already queued on the caller's stream
+  HIP_TRY(hipEventRecord(st->fork_ev, (hipStream_t)hip_stream));
+  for (int i = 0; i < n_streams; ++i) HIP_TRY(hipStreamWaitEvent(st->streams[i], st->fork_ev, 0));
   const int M = st->cfg.n_microbatches;
   const auto t_start = std::chrono::steady_clock::now();
   while (st->fwd_issued < M || st->bwd_issued < M) {
@@ -699,11 +769,11 @@ int axonn_offload_adam_device_bytes(const axonn_offload_adam_t* opt, uint64_t* b
   return AXONN_OK;
 }
 
-int axonn_offload_adam_step(axonn_offload_adam_t* o, float lr, float beta1, float beta2, float eps,
-                            float weight_decay, int64_t step, float grad_scale, void* hip_stream) {
+int axonn_offload_adam_step(axonn_offload_adam_t* o, double lr, double beta1, double beta2, double eps,
+                            double weight_decay, int64_t step, double grad_scale, void* hip_stream) {
   if (!o) return fail(AXONN_EINVAL, "adam_step: null handle");
   if (step < 1) return fail(AXONN_EINVAL, "adam_step: step must be >= 1 (got %lld)", (long long)step);
-  if (!(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f))
+  if (!(beta1 >= 0. && beta1 < 1.) || !(beta2 >= 0. && beta2 < 1.))
     return fail(AXONN_EINVAL, "adam_step: betas must be in [0,1)");
   HIP_TRY(hipSetDevice(o->device));
   hipStream_t user = (hipStream_t)hip_stream;
@@ -727,9 +797,8 @@ int axonn_offload_adam_step(axonn_offload_adam_t* o, float lr, float beta1, floa
     HIP_TRY(hipEventRecord(o->ev_h2d[set], o->s_h2d));
     // update
     HIP_TRY(hipStreamWaitEvent(o->s_k, o->ev_h2d[set], 0));
-    AX_TRY(check_launch(launch_adam(cnt, o->d_buf[set][0], o->d_buf[set][1], o->d_buf[set][2], o->g16 + off,
-                                    o->p16 + off, lr, beta1, beta2, eps, weight_decay, step, grad_scale, o->s_k),
-                        "adam"));
+    AX_TRY(adam(cnt, o->d_buf[set][0], o->d_buf[set][1], o->d_buf[set][2], o->g16 + off, o->p16 + off, lr, beta1,
+                beta2, eps, weight_decay, step, grad_scale, o->s_k));
     HIP_TRY(hipEventRecord(o->ev_k[set], o->s_k));
     // offload
     HIP_TRY(hipStreamWaitEvent(o->s_d2h, o->ev_k[set], 0));
@@ -756,8 +825,8 @@ int axonn_stage_optimizer_attach(axonn_stage_t* st, float* host_master, float* h
                                    host_m, host_v, &st->opt);
 }
 
-int axonn_stage_optimizer_step(axonn_stage_t* st, float lr, float beta1, float beta2, float eps,
-                               float weight_decay, int64_t step, float grad_scale, void* hip_stream) {
+int axonn_stage_optimizer_step(axonn_stage_t* st, double lr, double beta1, double beta2, double eps,
+                               double weight_decay, int64_t step, double grad_scale, void* hip_stream) {
   if (!st) return fail(AXONN_EINVAL, "optimizer_step: null handle");
   if (!st->opt) return fail(AXONN_ESTATE, "optimizer_step: no optimizer attached");
   if (st->in_flight) return fail(AXONN_ESTATE, "optimizer_step: %d microbatches in flight", st->in_flight);
@@ -765,6 +834,41 @@ int axonn_stage_optimizer_step(axonn_stage_t* st, float lr, float beta1, float b
   hipStream_t user = (hipStream_t)hip_stream;
   if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(user, st->last_bwd, 0));
   return axonn_offload_adam_step(st->opt, lr, beta1, beta2, eps, weight_decay, step, grad_scale, hip_stream);
+}
+
+
+// ----------------------------------------------------------------- launch timing
+int axonn_profile_enable(int32_t on) {
+  g_prof_on = on != 0;
+  return AXONN_OK;
+}
+int axonn_profile_num_categories(int32_t* n) {
+  if (!n) return fail(AXONN_EINVAL, "profile_num_categories: null argument");
+  *n = PC_COUNT;
+  return AXONN_OK;
+}
+int axonn_profile_category_name(int32_t idx, const char** name) {
+  if (!name || idx < 0 || idx >= PC_COUNT) return fail(AXONN_EINVAL, "profile_category_name: bad argument");
+  *name = kProfNames[idx];
+  return AXONN_OK;
+}
+int axonn_profile_collect(double* total_ms, int64_t* launches, int32_t n_categories) {
+  if (!total_ms || !launches || n_categories < PC_COUNT)
+    return fail(AXONN_EINVAL, "profile_collect: need arrays of at least %d entries", (int)PC_COUNT);
+  for (int i = 0; i < n_categories; ++i) { total_ms[i] = 0.0; launches[i] = 0; }
+  int rc = AXONN_OK;
+  for (ProfRec& r : g_prof_recs) {
+    float ms = 0.f;
+    hipError_t e = hipEventSynchronize(r.b);
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, r.a, r.b);
+    if (e != hipSuccess && rc == AXONN_OK)
+      rc = fail(AXONN_EHIP, "profile_collect: %s", hipGetErrorString(e));
+    if (e == hipSuccess) { total_ms[r.cat] += ms; launches[r.cat]++; }
+    g_prof_pool.push_back(r.a);
+    g_prof_pool.push_back(r.b);
+  }
+  g_prof_recs.clear();
+  return rc;
 }
 
 // -------------------------------------------------------------- single operations
@@ -835,12 +939,14 @@ int axonn_attention_bwd(int32_t b, int32_t s, int32_t n_heads, int32_t head_dim,
                                            (hipStream_t)hip_stream), "attention_bwd");
 }
 
-int axonn_adam_bucket(uint64_t n, float* theta, float* m, float* v, const void* grad16, void* param16, float lr,
-                      float beta1, float beta2, float eps, float weight_decay, int64_t step, float grad_scale,
+int axonn_adam_bucket(uint64_t n, float* theta, float* m, float* v, const void* grad16, void* param16, double lr,
+                      double beta1, double beta2, double eps, double weight_decay, int64_t step, double grad_scale,
                       void* hip_stream) {
   if (!theta || !m || !v || !grad16 || !param16) return fail(AXONN_EINVAL, "adam_bucket: null argument");
   if (n == 0) return fail(AXONN_EINVAL, "adam_bucket: n == 0");
   if (step < 1) return fail(AXONN_EINVAL, "adam_bucket: step must be >= 1");
+  if (!(beta1 >= 0. && beta1 < 1.) || !(beta2 >= 0. && beta2 < 1.))
+    return fail(AXONN_EINVAL, "adam_bucket: betas must be in [0,1)");
   return check_launch(launch_adam(n, theta, m, v, grad16, param16, lr, beta1, beta2, eps, weight_decay, step,
                                   grad_scale, (hipStream_t)hip_stream), "adam");
 }

@@ -1,0 +1,361 @@
+"""GPU parity of the whole stage path against the fp64 oracle, through the C ABI.
+
+Bounds are the ones the benchmark definition states: forward activations <= 2e-2, weight and
+input gradients <= 3e-2 (relative Frobenius, per tensor, max over tensors), Adam fp32 master
+state <= 1e-6."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2110_13005_amd import binding as B
+from paper_2110_13005_amd.inputs import CONFIGS, StageShape, make_stage_inputs, make_adam_inputs
+from paper_2110_13005_amd.stage import Stage
+from helpers import rel_fro, dev_bf16, dev_f32, host
+
+pytestmark = pytest.mark.gpu
+FWD_TOL, GRAD_TOL, ADAM_TOL = 2e-2, 3e-2, 1e-6
+EPS = 1e-5
+
+
+def _run_direct(stage, xs, dys, order=None):
+    """All forwards then all backwards (or a given order of (kind, mb)) on the null stream."""
+    import torch
+    M = len(xs)
+    X = [dev_bf16(x) for x in xs]
+    DY = [dev_bf16(d) for d in dys]
+    Y = [torch.zeros_like(X[0]) for _ in range(M)]
+    DX = [torch.zeros_like(X[0]) for _ in range(M)]
+    stage.zero_grad()
+    if order is None:
+        order = [(0, i) for i in range(M)] + [(1, i) for i in range(M)]
+    for kind, i in order:
+        if kind == 0:
+            stage.forward(i, X[i], Y[i])
+        else:
+            stage.backward(i, DY[i], DX[i])
+    torch.cuda.synchronize()
+    return [host(y) for y in Y], [host(d) for d in DX], stage.grads_numpy()
+
+
+def _check(outs, dxs, grads, ref, fwd_tol=FWD_TOL, grad_tol=GRAD_TOL):
+    r_outs, r_dxs, r_tot = ref
+    worst = {"fwd": 0.0, "dx": 0.0, "grad": 0.0}
+    for o, r in zip(outs, r_outs):
+        worst["fwd"] = max(worst["fwd"], rel_fro(o.reshape(r.shape), r))
+    for o, r in zip(dxs, r_dxs):
+        worst["dx"] = max(worst["dx"], rel_fro(o.reshape(r.shape), r))
+    for li, g in enumerate(grads):
+        for name, arr in g.items():
+            e = rel_fro(arr, r_tot[li][name])
+            assert e <= grad_tol, ("layer%d.%s" % (li, name), e)
+            worst["grad"] = max(worst["grad"], e)
+    assert worst["fwd"] <= fwd_tol, worst
+    assert worst["dx"] <= grad_tol, worst
+    return worst
+
+
+@pytest.mark.parametrize("perturb", [False, True])
+@pytest.mark.parametrize("fp32_acc", [1, 0])
+def test_tiny_config_parity(perturb, fp32_acc):
+    """Config 1 of the benchmark definition, seed 0; also with non-trivial LayerNorm
+    parameters and biases so that those gradient paths carry signal."""
+    sh = CONFIGS["tiny"]
+    layers, xs, dys = make_stage_inputs(sh, seed=0, perturb=perturb)
+    ref = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
+    with Stage(sh, grad_accum_fp32=fp32_acc) as st:
+        st.load_params(layers)
+        outs, dxs, grads = _run_direct(st, xs, dys)
+    if not perturb:
+        # biases start at zero and LayerNorm shifts at zero: their gradients are still non-zero
+        assert np.linalg.norm(ref[2][0]["b_qkv"]) > 0
+    _check(outs, dxs, grads, ref)
+
+
+@pytest.mark.parametrize("sh", [
+    StageShape(1, 128, 2, 72, 1, 2),          # one layer, ragged sequence, head dim 64
+    StageShape(3, 384, 3, 200, 2, 3, 1000),   # head dim 128, ragged T = 400, ffn not 4h
+    StageShape(1, 64, 1, 8, 1, 1),            # smallest supported shape
+], ids=["ragged72", "ragged200_ffn1000", "minimal"])
+def test_ragged_and_degenerate_shapes(sh):
+    layers, xs, dys = make_stage_inputs(sh, seed=3, perturb=True)
+    ref = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
+    with Stage(sh) as st:
+        st.load_params(layers)
+        outs, dxs, grads = _run_direct(st, xs, dys)
+    _check(outs, dxs, grads, ref)
+
+
+def test_zero_output_projections_give_identity():
+    """Degenerate case of the method: W_o = W_fc2 = 0 (and zero biases) makes every layer the
+    identity, forward and backward, bit for bit."""
+    sh = StageShape(2, 256, 4, 128, 1, 1)
+    layers, xs, dys = make_stage_inputs(sh, seed=1)
+    for p in layers:
+        p["w_o"][:] = 0
+        p["w_fc2"][:] = 0
+    with Stage(sh) as st:
+        st.load_params(layers)
+        outs, dxs, _ = _run_direct(st, xs, dys)
+    assert np.array_equal(outs[0].reshape(xs[0].shape), xs[0].astype(np.float64))
+    assert np.array_equal(dxs[0].reshape(dys[0].shape), dys[0].astype(np.float64))
+
+
+def _schedules(M, P):
+    """Valid message orders for a middle stage (warm-up depth w, then one-forward-one-backward,
+    then drain), as lists of (kind, mb)."""
+    out = {}
+    for w in sorted({1, max(1, P // 2), P}):
+        order, f, b = [], 0, 0
+        while f < min(w, M):
+            order.append((0, f)); f += 1
+        while b < M:
+            order.append((1, b)); b += 1
+            if f < M:
+                order.append((0, f)); f += 1
+        out["warmup%d" % w] = order
+    return out
+
+
+def test_schedule_independence_direct_calls():
+    """The paper's correctness claim (Sec. 7.1): scheduling must not change the result.  Every
+    valid interleaving gives the oracle's result, and the interleavings agree with each other
+    up to accumulation order."""
+    sh = CONFIGS["tiny"]
+    layers, xs, dys = make_stage_inputs(sh, seed=0, perturb=True)
+    ref = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
+    results = {}
+    with Stage(sh) as st:
+        st.load_params(layers)
+        for name, order in _schedules(sh.n_microbatches, sh.n_microbatches).items():
+            results[name] = _run_direct(st, xs, dys, order)
+            _check(*results[name], ref)
+        rng = np.random.default_rng(0)
+        # seeded random valid order: a backward may only follow its own forward
+        order, fwd_done, pending_b = [], 0, []
+        while len(order) < 2 * sh.n_microbatches:
+            choices = ([("f", fwd_done)] if fwd_done < sh.n_microbatches else []) + [("b", i) for i in pending_b]
+            k, i = choices[rng.integers(len(choices))]
+            if k == "f":
+                order.append((0, i)); pending_b.append(i); fwd_done += 1
+            else:
+                order.append((1, i)); pending_b.remove(i)
+        results["random"] = _run_direct(st, xs, dys, order)
+        _check(*results["random"], ref)
+    base = results["warmup1"]
+    for name, r in results.items():
+        for a, b in zip(r[0] + r[1], base[0] + base[1]):
+            assert np.array_equal(a, b), name          # per-microbatch tensors do not depend on order
+        for ga, gb in zip(r[2], base[2]):
+            for k in ga:
+                assert rel_fro(ga[k], gb[k]) <= 1e-3, (name, k)
+
+
+@pytest.mark.parametrize("n_streams", [1, 2, 3])
+def test_message_driven_run_matches_oracle_and_respects_pipeline_limit(n_streams):
+    import torch
+    sh = CONFIGS["tiny"]
+    M, P = sh.n_microbatches, 2
+    layers, xs, dys = make_stage_inputs(sh, seed=0, perturb=True)
+    ref = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
+    with Stage(sh, pipeline_limit=P) as st:
+        st.load_params(layers)
+        X = [dev_bf16(x) for x in xs]; DY = [dev_bf16(d) for d in dys]
+        Y = [torch.zeros_like(X[0]) for _ in range(M)]; DX = [torch.zeros_like(X[0]) for _ in range(M)]
+        st.zero_grad()
+        # all forward messages are posted first: the scheduler must hold forwards back once P are
+        # in flight and take the backward messages that free a slot
+        for i in range(M):
+            st.post(0, i, X[i], Y[i])
+        for i in range(M):
+            st.post(1, i, DY[i], DX[i])
+        st.run(n_streams)
+        st.join()
+        torch.cuda.synchronize()
+        log = B.axonn_stage_dispatch_log(st.handle)
+        assert len(log) == 2 * M and sorted(log) == sorted([(i, k) for i in range(M) for k in (0, 1)])
+        live, peak = set(), 0
+        for mb, kind in log:
+            if kind == 0:
+                live.add(mb)
+            else:
+                assert mb in live
+                live.remove(mb)
+            peak = max(peak, len(live))
+        assert peak == P                                  # steady state holds exactly pipeline_limit
+        _check([host(y) for y in Y], [host(d) for d in DX], st.grads_numpy(), ref)
+
+
+def test_message_arrival_order_follows_ready_events():
+    """A message whose payload has not arrived (event not yet signalled) is passed over for one
+    that has: forward vs backward is decided by what is ready, not by posting order."""
+    import torch
+    sh = StageShape(1, 128, 2, 64, 1, 2)
+    layers, xs, dys = make_stage_inputs(sh, seed=2)
+    with Stage(sh) as st:
+        st.load_params(layers)
+        X = [dev_bf16(x) for x in xs]; DY = [dev_bf16(d) for d in dys]
+        Y = [torch.zeros_like(X[0]) for _ in range(2)]; DX = [torch.zeros_like(X[0]) for _ in range(2)]
+        comm = torch.cuda.Stream()
+        late = torch.cuda.Event()
+        with torch.cuda.stream(comm):
+            torch.cuda._sleep(int(2.4e9 * 0.2))           # ~0.2 s: message 0's payload is "in transit"
+            late.record(comm)
+        st.zero_grad()
+        st.post(0, 0, X[0], Y[0], ready_event=late)
+        st.post(0, 1, X[1], Y[1])
+        st.post(1, 1, DY[1], DX[1])
+        st.post(1, 0, DY[0], DX[0])
+        st.run(2)
+        st.join()
+        torch.cuda.synchronize()
+        log = B.axonn_stage_dispatch_log(st.handle)
+        assert log[0] == (1, 0) and log[1] == (1, 1)      # microbatch 1 went first, fwd then bwd
+        assert log[2:] == [(0, 0), (0, 1)]
+
+
+def test_state_errors_leave_stage_usable():
+    import torch
+    sh = StageShape(1, 128, 2, 64, 1, 3)
+    layers, xs, dys = make_stage_inputs(sh, seed=2)
+    with Stage(sh, pipeline_limit=2) as st:
+        st.load_params(layers)
+        X = [dev_bf16(x) for x in xs]; Y = torch.zeros_like(X[0]); D = torch.zeros_like(X[0])
+        with pytest.raises(B.AxonnError) as e:
+            st.backward(0, X[0], D)                       # backward before its forward
+        assert e.value.status == B.AXONN_ESTATE
+        st.forward(0, X[0], Y)
+        with pytest.raises(B.AxonnError) as e:
+            st.forward(0, X[0], Y)                        # duplicate microbatch id
+        assert e.value.status == B.AXONN_ESTATE
+        st.forward(1, X[1], Y)
+        with pytest.raises(B.AxonnError) as e:
+            st.forward(2, X[2], Y)                        # pipeline_limit overflow
+        assert e.value.status == B.AXONN_ESTATE and "pipeline_limit" in str(e.value)
+        with pytest.raises(B.AxonnError) as e:
+            st.zero_grad()                                # microbatches in flight
+        assert e.value.status == B.AXONN_ESTATE
+        with pytest.raises(B.AxonnError) as e:
+            B.axonn_stage_forward(st.handle, 5, None, Y)  # null pointer
+        assert e.value.status == B.AXONN_EINVAL
+        st.backward(0, X[0], D)
+        st.forward(2, X[2], Y)                            # slot freed: usable again
+        st.backward(1, X[1], D)
+        st.backward(2, X[2], D)
+        # message mode: only backward messages posted and nothing in flight -> cannot progress
+        st.zero_grad()
+        st.post(1, 0, X[0], D)
+        with pytest.raises(B.AxonnError) as e:
+            st.run(2)
+        assert e.value.status == B.AXONN_ESTATE
+        with pytest.raises(B.AxonnError) as e:
+            st.post(1, 0, X[0], D)                        # duplicate message
+        assert e.value.status == B.AXONN_ESTATE
+        torch.cuda.synchronize()
+
+
+def test_fixed_schedule_is_bit_reproducible():
+    sh = CONFIGS["tiny"]
+    layers, xs, dys = make_stage_inputs(sh, seed=0, perturb=True)
+    with Stage(sh) as st:
+        st.load_params(layers)
+        a = _run_direct(st, xs, dys)
+        b = _run_direct(st, xs, dys)
+    for x, y in zip(a[0] + a[1], b[0] + b[1]):
+        assert np.array_equal(x, y)
+    for ga, gb in zip(a[2], b[2]):
+        for k in ga:
+            assert np.array_equal(ga[k], gb[k]), k
+
+
+def test_device_memory_accounting():
+    """Sec. 5.2: parameters and gradients take 4*phi bytes on the device (2 + 2), the optimizer
+    n_sets * 12 * bsize (theta, m, v buckets; the bf16 gradient is read in place, so the paper's
+    4*bsize descale scratch is not needed)."""
+    sh = CONFIGS["tiny"]
+    with Stage(sh, grad_accum_fp32=0) as st:
+        by = B.axonn_stage_device_bytes(st.handle)
+        phi = st.n_params
+        assert by[0] + by[1] == 4 * phi and by[2] == 0
+        per_layer = 2 * sh.tokens * (8 * sh.hidden + 2 * sh.ffn)
+        assert by[3] >= sh.n_microbatches * sh.n_layers * per_layer
+        assert by[3] <= 1.1 * sh.n_microbatches * sh.n_layers * per_layer + (1 << 20)
+        bucket = 1 << 16
+        n = phi
+        hm = [B.axonn_pinned_alloc(4 * n) for _ in range(3)]
+        B.axonn_stage_optimizer_attach(st.handle, hm[0], hm[1], hm[2], n, bucket)
+        assert B.axonn_stage_device_bytes(st.handle)[5] == 3 * 12 * bucket
+    for p in hm:
+        B.axonn_pinned_free(p)
+    with Stage(sh, grad_accum_fp32=1) as st:
+        assert B.axonn_stage_device_bytes(st.handle)[2] == 4 * st.n_params
+
+
+def _pinned_array(n):
+    import ctypes
+    p = B.axonn_pinned_alloc(4 * n)
+    arr = np.ctypeslib.as_array((ctypes.c_float * n).from_address(p))
+    return p, arr
+
+
+@pytest.mark.parametrize("n,bucket,fresh,wd,step,gs", [
+    (1_000_000, 1 << 18, False, 0.0, 100, 1.0),     # 4 buckets, ragged last
+    (300_000, 1 << 16, True, 0.01, 1, 0.125),       # 5 buckets, first step, decay, descale
+    (5000, 1 << 16, False, 0.0, 7, 1.0),            # single partial bucket, n % 8 == 0
+    (12_345, 4096, False, 0.0, 3, 1.0),             # n not a multiple of 8
+])
+def test_offloaded_adam_matches_oracle(n, bucket, fresh, wd, step, gs):
+    import torch
+    th, m, v, g16 = make_adam_inputs(n, seed=n, fresh=fresh)
+    lr, b1, b2, eps = 1e-4, 0.9, 0.95, 1e-8
+    rt, rm, rv, r16 = oracle.adam_step(th, m, v, g16, lr, b1, b2, eps, wd, step, gs)
+    ptrs, arrs = zip(*[_pinned_array(n) for _ in range(3)])
+    arrs[0][:] = th; arrs[1][:] = m; arrs[2][:] = v
+    G = dev_bf16(g16)
+    P16 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    opt = B.axonn_offload_adam_create(0, n, bucket, P16, G, ptrs[0], ptrs[1], ptrs[2])
+    try:
+        assert B.axonn_offload_adam_device_bytes(opt) == 3 * 12 * min(bucket, (n + 7) // 8 * 8)
+        B.axonn_offload_adam_step(opt, lr, b1, b2, eps, wd, step, gs)
+        torch.cuda.synchronize()
+        assert rel_fro(arrs[0], rt) <= ADAM_TOL
+        assert rel_fro(arrs[1], rm) <= ADAM_TOL
+        assert rel_fro(arrs[2], rv) <= ADAM_TOL
+        got16 = host(P16)
+        assert np.array_equal(got16, oracle.bf16_round(arrs[0]).astype(np.float64))   # bf16 of own master, bit exact
+        assert np.abs(got16 - r16).max() <= np.abs(r16).max() * 2.0 ** -7             # <= 1 ulp of the oracle's
+        # second step continues from the offloaded state
+        rt2, rm2, rv2, _ = oracle.adam_step(rt, rm, rv, g16, lr, b1, b2, eps, wd, step + 1, gs)
+        B.axonn_offload_adam_step(opt, lr, b1, b2, eps, wd, step + 1, gs)
+        torch.cuda.synchronize()
+        assert rel_fro(arrs[0], rt2) <= ADAM_TOL and rel_fro(arrs[1], rm2) <= ADAM_TOL
+    finally:
+        B.axonn_offload_adam_destroy(opt)
+        for p in ptrs:
+            B.axonn_pinned_free(p)
+
+
+def test_stage_batch_then_optimizer_step():
+    """Alg. 1's per-GPU body: all microbatches forward/backward, then "run the optimizer" on the
+    stage's own bf16 parameter / gradient buffers with grad_scale = 1/M."""
+    import torch
+    sh = CONFIGS["tiny"]
+    M = sh.n_microbatches
+    layers, xs, dys = make_stage_inputs(sh, seed=0, perturb=True)
+    with Stage(sh) as st:
+        st.load_params(layers)
+        n = st.n_params
+        ptrs, arrs = zip(*[_pinned_array(n) for _ in range(3)])
+        theta0 = st.params.float().cpu().numpy()
+        arrs[0][:] = theta0; arrs[1][:] = 0; arrs[2][:] = 0
+        _run_direct(st, xs, dys)
+        g16 = st.grads.float().cpu().numpy()
+        B.axonn_stage_optimizer_attach(st.handle, ptrs[0], ptrs[1], ptrs[2], n, 1 << 18)
+        with pytest.raises(B.AxonnError):
+            B.axonn_stage_optimizer_attach(st.handle, ptrs[0], ptrs[1], ptrs[2], n - 8, 1 << 18)
+        B.axonn_stage_optimizer_step(st.handle, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1, 1.0 / M)
+        torch.cuda.synchronize()
+        rt, rm, rv, r16 = oracle.adam_step(theta0, 0 * theta0, 0 * theta0, g16, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1, 1.0 / M)
+        assert rel_fro(arrs[0], rt) <= ADAM_TOL and rel_fro(arrs[1], rm) <= ADAM_TOL and rel_fro(arrs[2], rv) <= ADAM_TOL
+        assert np.array_equal(host(st.params), oracle.bf16_round(arrs[0]).astype(np.float64))
+    for p in ptrs:
+        B.axonn_pinned_free(p)

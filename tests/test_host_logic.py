@@ -1,0 +1,55 @@
+"""CPU tests of host-side bookkeeping: FLOP and parameter counters, input recipe."""
+import os
+import numpy as np
+
+from paper_2110_13005_amd import flops
+from paper_2110_13005_amd.inputs import CONFIGS, make_stage_inputs, make_adam_inputs, StageShape, to_bf16_bits, from_bf16_bits
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def test_flop_counter_matches_paper_eq3_without_recompute_and_lm_head():
+    """GEMM-shape count of fwd+bwd equals 72*b*s*L*h^2*(1 + s/6h) per microbatch under the
+    paper's non-causal attention convention (Eq. 3 with the recompute forward and the V term
+    removed), for every stage shape."""
+    for sh in CONFIGS.values():
+        ours = flops.stage_batch_flops(sh, causal=False)
+        paper = flops.narayanan_flops(sh.microbatch_size, sh.seq_len, sh.n_layers, sh.hidden, recompute=False) * sh.n_microbatches
+        assert abs(ours - paper) <= 1e-9 * paper
+    assert abs(flops.stage_batch_flops(CONFIGS["12b"]) - 1.2782e14) < 1e10
+    assert abs(flops.stage_batch_flops(CONFIGS["12b"], causal=False) - 1.3194e14) < 1e10
+
+
+def test_param_count_reproduces_table1_model_sizes():
+    """12*L*h^2 (+13*L*h) plus the 51200 x h embedding gives the nominal sizes of Table 1."""
+    for line in open(os.path.join(GOLDEN, "table1_model_sizes.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        nominal, L, h, a = (int(t) for t in line.split())
+        n = flops.stage_param_count(L, h) + 51200 * h
+        assert abs(n / 1e9 - nominal) / nominal < 0.04, (nominal, n)
+        assert h % a == 0
+
+
+def test_stage_param_count_formula():
+    for sh in CONFIGS.values():
+        h = sh.hidden
+        assert flops.stage_param_count(sh.n_layers, h) == sh.n_layers * (12 * h * h + 13 * h)
+    assert flops.stage_param_count(4, 5120) == 1_258_557_440
+
+
+def test_input_recipe_is_seeded_and_bf16_representable():
+    sh = StageShape(2, 64, 1, 16, 2, 3)
+    a = make_stage_inputs(sh, seed=0)
+    b = make_stage_inputs(sh, seed=0)
+    c = make_stage_inputs(sh, seed=1)
+    assert all(np.array_equal(x, y) for x, y in zip(a[1], b[1]))
+    assert not np.array_equal(a[1][0], c[1][0])
+    w = a[0][0]["w_qkv"]
+    assert np.array_equal(from_bf16_bits(to_bf16_bits(w)).reshape(w.shape), w)
+    assert abs(w.std() - 0.02) < 2e-3 and abs(a[1][0].std() - 1) < 0.05
+    assert (a[0][0]["ln1_g"] == 1).all() and not a[0][0]["b_qkv"].any()
+    p = make_stage_inputs(sh, seed=0, perturb=True)[0][0]
+    assert p["b_qkv"].any() and abs(p["ln2_g"].mean() - 1) < 0.02
+    th, m, v, g = make_adam_inputs(4096, seed=0)
+    assert (v >= 0).all() and abs(g.std() - 1e-3) < 1e-4 and abs(m.std() - 1e-4) < 1e-5
