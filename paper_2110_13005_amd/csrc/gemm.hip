@@ -17,6 +17,12 @@
 
 namespace axonn {
 
+// Chunks of a tile that fall outside the matrix are fetched from here instead, so that every
+// load is unconditional and nothing has to be patched after it arrives.
+__device__ __align__(16) uint32_t g_zero_chunk[4] = {0u, 0u, 0u, 0u};
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // 16-byte chunk kept in registers
+
 template <int ROWS, int BK, bool KC>
 struct TileLayout {
   // leading dimension in elements, padded so that fragment reads spread over LDS banks
@@ -50,54 +56,67 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
   const int tm = pid % g.tiles_m, tn = pid / g.tiles_m;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
-  uint4 ra[A_CH], rb[B_CH];
+  // Per-thread view of the tile copy: chunk j of this thread is 16 bytes at pa[j] (advanced by
+  // one k-step per iteration), valid if its row is inside the matrix (fixed) and its k is (checked
+  // per step).  Out-of-range chunks read a zero chunk instead, so the loads are unconditional
+  // and stay in registers until the next step stores them to LDS.
+  const bf16_t* pa[A_CH];
+  const bf16_t* pb[B_CH];
+  bool va[A_CH], vb[B_CH];
+  int ka[A_CH], kb[B_CH], oa[A_CH], ob[B_CH];
+#pragma unroll
+  for (int j = 0; j < A_CH; ++j) {
+    const int c = tid + j * NT;
+    if (A_KC) {
+      const int row = c / (BK / 8), kc = c % (BK / 8);
+      va[j] = (m0 + row) < g.M; ka[j] = kc * 8;
+      pa[j] = g.A + (int64_t)(m0 + row) * g.lda + kc * 8;
+      oa[j] = row * LA::LD + kc * 8;
+    } else {
+      const int kr = c / (BM / 8), rc = c % (BM / 8);
+      va[j] = (m0 + rc * 8) < g.M; ka[j] = kr;
+      pa[j] = g.A + (int64_t)kr * g.lda + m0 + rc * 8;
+      oa[j] = kr * LA::LD + rc * 8;
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < B_CH; ++j) {
+    const int c = tid + j * NT;
+    if (B_KC) {
+      const int row = c / (BK / 8), kc = c % (BK / 8);
+      vb[j] = (n0 + row) < g.N; kb[j] = kc * 8;
+      pb[j] = g.B + (int64_t)(n0 + row) * g.ldb + kc * 8;
+      ob[j] = row * LB::LD + kc * 8;
+    } else {
+      const int kr = c / (BN / 8), rc = c % (BN / 8);
+      vb[j] = (n0 + rc * 8) < g.N; kb[j] = kr;
+      pb[j] = g.B + (int64_t)kr * g.ldb + n0 + rc * 8;
+      ob[j] = kr * LB::LD + rc * 8;
+    }
+  }
+  const int64_t step_a = A_KC ? (int64_t)BK : (int64_t)BK * g.lda;
+  const int64_t step_b = B_KC ? (int64_t)BK : (int64_t)BK * g.ldb;
+  const int K = g.K;
+  const bf16_t* zero_chunk = reinterpret_cast<const bf16_t*>(g_zero_chunk);
+  u32x4 ra[A_CH], rb[B_CH];
 
-  auto gload = [&](int kt) {
-    const int k0 = kt * BK;
-#pragma unroll
-    for (int j = 0; j < A_CH; ++j) {
-      const int c = tid + j * NT;
-      if (A_KC) {
-        const int row = c / (BK / 8), kc = c % (BK / 8);
-        const int m = m0 + row, k = k0 + kc * 8;
-        ra[j] = (m < g.M && k < g.K) ? *reinterpret_cast<const uint4*>(g.A + (int64_t)m * g.lda + k) : zero4;
-      } else {
-        const int kr = c / (BM / 8), rc = c % (BM / 8);
-        const int m = m0 + rc * 8, k = k0 + kr;
-        ra[j] = (m < g.M && k < g.K) ? *reinterpret_cast<const uint4*>(g.A + (int64_t)k * g.lda + m) : zero4;
-      }
-    }
-#pragma unroll
-    for (int j = 0; j < B_CH; ++j) {
-      const int c = tid + j * NT;
-      if (B_KC) {
-        const int row = c / (BK / 8), kc = c % (BK / 8);
-        const int n = n0 + row, k = k0 + kc * 8;
-        rb[j] = (n < g.N && k < g.K) ? *reinterpret_cast<const uint4*>(g.B + (int64_t)n * g.ldb + k) : zero4;
-      } else {
-        const int kr = c / (BN / 8), rc = c % (BN / 8);
-        const int n = n0 + rc * 8, k = k0 + kr;
-        rb[j] = (n < g.N && k < g.K) ? *reinterpret_cast<const uint4*>(g.B + (int64_t)k * g.ldb + n) : zero4;
-      }
-    }
-  };
-  auto sstore = [&](int buf) {
-#pragma unroll
-    for (int j = 0; j < A_CH; ++j) {
-      const int c = tid + j * NT;
-      const int off = A_KC ? (c / (BK / 8)) * LA::LD + (c % (BK / 8)) * 8
-                           : (c / (BM / 8)) * LA::LD + (c % (BM / 8)) * 8;
-      *reinterpret_cast<uint4*>(&sA[buf][off]) = ra[j];
-    }
-#pragma unroll
-    for (int j = 0; j < B_CH; ++j) {
-      const int c = tid + j * NT;
-      const int off = B_KC ? (c / (BK / 8)) * LB::LD + (c % (BK / 8)) * 8
-                           : (c / (BN / 8)) * LB::LD + (c % (BN / 8)) * 8;
-      *reinterpret_cast<uint4*>(&sB[buf][off]) = rb[j];
-    }
-  };
+#define AXONN_GLOAD(k0)                                                        \
+  _Pragma("unroll") for (int j = 0; j < A_CH; ++j) {                           \
+    const bool ok = va[j] && ((k0) + ka[j] < K);                               \
+    ra[j] = *reinterpret_cast<const u32x4*>(ok ? pa[j] : zero_chunk);          \
+    pa[j] += step_a;                                                           \
+  }                                                                            \
+  _Pragma("unroll") for (int j = 0; j < B_CH; ++j) {                           \
+    const bool ok = vb[j] && ((k0) + kb[j] < K);                               \
+    rb[j] = *reinterpret_cast<const u32x4*>(ok ? pb[j] : zero_chunk);          \
+    pb[j] += step_b;                                                           \
+  }                                                                            \
+  __builtin_amdgcn_sched_barrier(0);
+#define AXONN_SSTORE(buf)                                                      \
+  _Pragma("unroll") for (int j = 0; j < A_CH; ++j)                             \
+    *reinterpret_cast<u32x4*>(&sA[buf][oa[j]]) = ra[j];                        \
+  _Pragma("unroll") for (int j = 0; j < B_CH; ++j)                             \
+    *reinterpret_cast<u32x4*>(&sB[buf][ob[j]]) = rb[j];
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -107,16 +126,17 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int nk = (g.K + BK - 1) / BK;
-  gload(0);
-  sstore(0);
-  if (nk > 1) gload(1);
+  const int nk = (K + BK - 1) / BK;
+  AXONN_GLOAD(0)
+  AXONN_SSTORE(0)
+  AXONN_GLOAD(BK)          // tile 1 (all zeros if there is none)
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < nk) sstore(cur ^ 1);
-    if (kt + 2 < nk) gload(kt + 2);
+    // registers hold tile kt+1: park it in the other buffer, then fetch tile kt+2
+    AXONN_SSTORE(cur ^ 1)
+    AXONN_GLOAD((kt + 2) * BK)
     const bf16_t* a_s = sA[cur];
     const bf16_t* b_s = sB[cur];
 #pragma unroll
@@ -141,6 +161,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
     }
     __syncthreads();
   }
+#undef AXONN_GLOAD
+#undef AXONN_SSTORE
 
   // ------------------------------------------------------------------ epilogue
   // lane owns row m = .. + lane%32; register r of tile (i,j) is column 8*(r/4)+4*(lane/32)+r%4
