@@ -32,6 +32,7 @@ def parse():
     ap.add_argument("--streams", type=int, default=2, help="library streams of the message-driven run")
     ap.add_argument("--pipeline-limit", type=int, default=0, help="0 = all microbatches in flight")
     ap.add_argument("--grad-accum", default="fp32", choices=["fp32", "bf16"])
+    ap.add_argument("--wgrad-group", type=int, default=0, help="microbatches per weight-gradient contraction (0 = as many as possible)")
     ap.add_argument("--bucket-elems", type=int, default=1 << 26)
     ap.add_argument("--no-optimizer", action="store_true", help="diagnostic: leave the Adam step out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -85,7 +86,7 @@ def main():
     g = torch.Generator(device=dev)
     g.manual_seed(0)
 
-    st = Stage(sh, pipeline_limit=P, grad_accum_fp32=1 if args.grad_accum == "fp32" else 0)
+    st = Stage(sh, pipeline_limit=P, grad_accum_fp32=1 if args.grad_accum == "fp32" else 0, wgrad_group=args.wgrad_group)
     n = st.n_params
     # synthetic weights ~N(0, 0.02) (LayerNorm gains 1, biases 0), generated on the device in chunks;
     # fp32 master copy in pinned host memory, bf16 copy = its rounding
@@ -179,7 +180,7 @@ def main():
         "config": {"workload": "%s stage: %d layers, h=%d, heads=%d, ffn=%d, seq=%d, microbatch=%d, %d microbatches, "
                                "pipeline_limit=%d" % (args.config, sh.n_layers, sh.hidden, sh.n_heads, sh.ffn,
                                                       sh.seq_len, sh.microbatch_size, M, P),
-                   "streams": args.streams, "grad_accum": args.grad_accum, "bucket_elems": args.bucket_elems,
+                   "streams": args.streams, "grad_accum": args.grad_accum, "wgrad_group": args.wgrad_group, "bucket_elems": args.bucket_elems,
                    "optimizer_in_step": not args.no_optimizer},
         "pct_of_bf16_mfma_peak": 100.0 * tflops / flops.PEAK_BF16_DENSE_TFLOPS,
         "peak_tflops_used": flops.PEAK_BF16_DENSE_TFLOPS,

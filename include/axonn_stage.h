@@ -65,10 +65,16 @@ typedef struct {
                               fp32 shadow buffer, rounded once to bf16 after the M-th
                               backward; 0: accumulate directly in the bf16 gradient
                               buffer (the paper's 4*phi device footprint, Sec. 5.2)    */
+  int32_t wgrad_group;     /* weight gradients are formed for groups of microbatches in
+                              one contraction over all their tokens, not per microbatch:
+                              a group is closed once this many backwards are pending
+                              (0: only when a stash slot is needed or the batch ends)  */
 } axonn_stage_config;
 
 /* Allocates bf16 parameters and gradients (flat buffers), pipeline_limit activation
- * stash slots and the backward workspace on cfg->device.  Parameters are zero except
+ * stash slots (forward activations plus the output gradients of the linear maps, which
+ * stay until the slot's weight gradients have been formed) and the backward workspace on
+ * cfg->device.  Parameters are zero except
  * LayerNorm gains = 1; gradients are zero.  Synchronous. */
 int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out);
 /* Waits for all work of the stage, then frees everything it owns.  Synchronous. */
@@ -101,10 +107,12 @@ int axonn_stage_device_bytes(const axonn_stage_t* st, uint64_t bytes[6]);
 int axonn_stage_forward(axonn_stage_t* st, int32_t mb_id, const void* x_dev_bf16,
                         void* y_dev_bf16, void* hip_stream);
 /* Backward(msg) of Alg. 2: given dL/dy for microbatch mb_id, writes dL/dx to
- * dx_dev_bf16 [b,s,h], adds the microbatch's parameter gradients into the accumulators
- * and releases its stash slot.  AXONN_ESTATE if mb_id has no forward in flight.  After
- * the n_microbatches-th backward since the last zero_grad the bf16 gradient buffer is
- * final on that stream. */
+ * dx_dev_bf16 [b,s,h] (dy is copied, so the caller may recycle its receive buffer), adds
+ * the bias and LayerNorm gradients into the accumulators and leaves the microbatch's
+ * weight gradients pending (see wgrad_group); the microbatch no longer counts as in
+ * flight.  AXONN_ESTATE if mb_id has no forward in flight.  After the n_microbatches-th
+ * backward since the last zero_grad all pending weight gradients are formed and the bf16
+ * gradient buffer is final on that stream; before that its contents are unspecified. */
 int axonn_stage_backward(axonn_stage_t* st, int32_t mb_id, const void* dy_dev_bf16,
                          void* dx_dev_bf16, void* hip_stream);
 

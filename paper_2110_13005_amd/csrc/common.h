@@ -92,11 +92,18 @@ enum GemmEpilogue {
   EPI_ACC_F32 = 4, EPI_ACC_BF16 = 5
 };
 
+// The contraction index may be split into up to kMaxKSegments segments of K elements each that
+// live in different buffers (same shape and leading dimension): segment s of operand A starts at
+// A_seg[s].  This is how a weight gradient is summed over several microbatches in one launch.
+constexpr int kMaxKSegments = 16;
 struct GemmArgs {
-  const bf16_t* A; const bf16_t* B; void* C;
+  const bf16_t* A_seg[kMaxKSegments];
+  const bf16_t* B_seg[kMaxKSegments];
+  void* C;
   const bf16_t* bias; const bf16_t* res; bf16_t* aux;
   int64_t lda, ldb, ldc, ld_res, ld_aux;
-  int M, N, K;
+  int M, N, K;       // K = length of ONE segment
+  int n_seg;
   int accumulate;
   int tiles_m, tiles_n;
 };

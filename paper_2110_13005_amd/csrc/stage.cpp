@@ -93,16 +93,25 @@ struct TensorInfo {
 };
 
 struct LayerStash {
+  // forward activations kept for the backward pass
   bf16_t *x, *u, *qkv, *o, *y, *w, *pre, *g;
   float *stats1, *stats2, *lse;
+  // output gradients of the four linear maps, written by the backward pass and kept until the
+  // weight gradients of a group of microbatches are formed in one contraction
+  bf16_t *dz, *dpre, *dy_mid, *dqkv;
 };
 
+enum SlotState { SLOT_FREE, SLOT_LIVE, SLOT_AWAIT_WGRAD };
+
 struct Slot {
-  int mb_id = -1;
+  int state = SLOT_FREE;
+  int mb_id = -1;          // valid while SLOT_LIVE (forward issued, backward not yet)
   char* base = nullptr;
   std::vector<LayerStash> layers;
-  hipEvent_t fwd_done = nullptr, bwd_done = nullptr;
-  bool bwd_recorded = false;
+  // fwd_done: forward finished; dgrad_done: backward's activation-gradient chain finished;
+  // released: the weight-gradient contraction that read the slot finished (slot reusable)
+  hipEvent_t fwd_done = nullptr, dgrad_done = nullptr, released = nullptr;
+  bool released_recorded = false;
 };
 
 struct PendingMsg {
@@ -140,14 +149,16 @@ struct axonn_stage {
   // backward workspace
   char* ws_base = nullptr;
   uint64_t ws_bytes = 0;
-  bf16_t *dres[2] = {}, *dy_mid = nullptr, *dpre = nullptr, *dw = nullptr, *dattn = nullptr,
-         *dqkv = nullptr, *du = nullptr;
+  bf16_t *dw = nullptr, *dattn = nullptr, *du = nullptr;
   float *delta = nullptr, *red_ws = nullptr, *vec0 = nullptr, *vec1 = nullptr;
   // state
   int in_flight = 0;
   int bwd_count = 0;  // backwards since the last zero_grad
-  hipEvent_t last_bwd = nullptr, fork_ev = nullptr;
-  bool last_bwd_recorded = false;
+  hipEvent_t last_bwd = nullptr, last_wgrad = nullptr, fork_ev = nullptr;
+  bool last_bwd_recorded = false, last_wgrad_recorded = false;
+  int wgrad_flushes = 0;              // weight-gradient contractions since the last zero_grad
+  hipStream_t wgrad_stream = nullptr; // message-driven mode: weight gradients overlap other work
+  hipEvent_t wgrad_tail = nullptr;
   // message-driven mode
   std::deque<PendingMsg> inbox;
   std::vector<hipStream_t> streams;
@@ -177,7 +188,8 @@ int gemm(bool a_kc, bool b_kc, int epi, int M, int N, int K, const void* A, int6
          const void* B, int64_t ldb, void* C, int64_t ldc, const void* bias, const void* res,
          int64_t ld_res, void* aux, int64_t ld_aux, int accumulate, hipStream_t s) {
   GemmArgs g;
-  g.A = (const bf16_t*)A; g.B = (const bf16_t*)B; g.C = C;
+  memset(&g, 0, sizeof g);
+  g.A_seg[0] = (const bf16_t*)A; g.B_seg[0] = (const bf16_t*)B; g.C = C; g.n_seg = 1;
   g.bias = (const bf16_t*)bias; g.res = (const bf16_t*)res; g.aux = (bf16_t*)aux;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ld_res = ld_res; g.ld_aux = ld_aux;
   g.M = M; g.N = N; g.K = K; g.accumulate = accumulate; g.tiles_m = g.tiles_n = 0;
@@ -245,73 +257,136 @@ int vec_grad(axonn_stage* st, int layer, int which, const float* src, int n, int
 
 int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out, int acc, hipStream_t s) {
   const int T = st->T, h = st->h, f = st->f, L = st->cfg.n_layers;
-  const int wg_epi = st->cfg.grad_accum_fp32 ? EPI_ACC_F32 : EPI_ACC_BF16;
-  const bf16_t* d_in = (const bf16_t*)dy_in;
+  // the upstream gradient is copied into the stash: it is an operand of the deferred weight
+  // gradient and the caller may recycle its receive buffer
+  {
+    ProfScope ps(PC_COPY_IN, s);
+    HIP_TRY(hipMemcpyAsync(slot.layers[L - 1].dz, dy_in, (uint64_t)T * h * sizeof(bf16_t), hipMemcpyDeviceToDevice, s));
+  }
   for (int l = L - 1; l >= 0; --l) {
     LayerStash& a = slot.layers[l];
-    bf16_t* d_out = (l == 0) ? (bf16_t*)dx_out : st->dres[l & 1];
+    const bf16_t* d_in = a.dz;
+    bf16_t* d_out = (l == 0) ? (bf16_t*)dx_out : slot.layers[l - 1].dz;
     // z = y + g W2 + b2
-    AX_TRY(gemm(true, true, EPI_DGELU, T, f, h, d_in, h, param_ptr(st, l, P_WFC2), h, st->dpre, f,
+    AX_TRY(gemm(true, true, EPI_DGELU, T, f, h, d_in, h, param_ptr(st, l, P_WFC2), h, a.dpre, f,
                 nullptr, nullptr, 0, a.pre, f, 0, s));
-    AX_TRY(gemm(false, false, wg_epi, f, h, T, a.g, f, d_in, h, grad_ptr(st, l, P_WFC2), h,
-                nullptr, nullptr, 0, nullptr, 0, acc, s));
     AX_TRY(colsum(T, h, d_in, h, st->vec0, st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_BFC2, st->vec0, h, acc, s));
     // pre = w W1 + b1
-    AX_TRY(gemm(true, true, EPI_BIAS, T, h, f, st->dpre, f, param_ptr(st, l, P_WFC1), f, st->dw, h,
+    AX_TRY(gemm(true, true, EPI_BIAS, T, h, f, a.dpre, f, param_ptr(st, l, P_WFC1), f, st->dw, h,
                 nullptr, nullptr, 0, nullptr, 0, 0, s));
-    AX_TRY(gemm(false, false, wg_epi, h, f, T, a.w, h, st->dpre, f, grad_ptr(st, l, P_WFC1), f,
-                nullptr, nullptr, 0, nullptr, 0, acc, s));
-    AX_TRY(colsum(T, f, st->dpre, f, st->vec0, st->red_ws, s));
+    AX_TRY(colsum(T, f, a.dpre, f, st->vec0, st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_BFC1, st->vec0, f, acc, s));
     // w = LN2(y); residual: dy = d_in + dLN2
-    AX_TRY(ln_bwd(T, h, st->dw, a.y, a.stats2, param_ptr(st, l, P_LN2G), d_in, st->dy_mid, st->vec0, st->vec1,
+    AX_TRY(ln_bwd(T, h, st->dw, a.y, a.stats2, param_ptr(st, l, P_LN2G), d_in, a.dy_mid, st->vec0, st->vec1,
                   st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_LN2G, st->vec0, h, acc, s));
     AX_TRY(vec_grad(st, l, P_LN2B, st->vec1, h, acc, s));
     // y = x + o Wo + bo
-    AX_TRY(gemm(true, true, EPI_BIAS, T, h, h, st->dy_mid, h, param_ptr(st, l, P_WO), h, st->dattn, h,
+    AX_TRY(gemm(true, true, EPI_BIAS, T, h, h, a.dy_mid, h, param_ptr(st, l, P_WO), h, st->dattn, h,
                 nullptr, nullptr, 0, nullptr, 0, 0, s));
-    AX_TRY(gemm(false, false, wg_epi, h, h, T, a.o, h, st->dy_mid, h, grad_ptr(st, l, P_WO), h,
-                nullptr, nullptr, 0, nullptr, 0, acc, s));
-    AX_TRY(colsum(T, h, st->dy_mid, h, st->vec0, st->red_ws, s));
+    AX_TRY(colsum(T, h, a.dy_mid, h, st->vec0, st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_BO, st->vec0, h, acc, s));
     // attention
     AX_TRY(attn_bwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d, a.qkv, a.o, a.lse, st->dattn,
-                    st->dqkv, st->delta, s));
+                    a.dqkv, st->delta, s));
     // qkv = u Wqkv + b
-    AX_TRY(gemm(true, true, EPI_BIAS, T, h, 3 * h, st->dqkv, 3 * h, param_ptr(st, l, P_WQKV), 3 * h, st->du, h,
+    AX_TRY(gemm(true, true, EPI_BIAS, T, h, 3 * h, a.dqkv, 3 * h, param_ptr(st, l, P_WQKV), 3 * h, st->du, h,
                 nullptr, nullptr, 0, nullptr, 0, 0, s));
-    AX_TRY(gemm(false, false, wg_epi, h, 3 * h, T, a.u, h, st->dqkv, 3 * h, grad_ptr(st, l, P_WQKV), 3 * h,
-                nullptr, nullptr, 0, nullptr, 0, acc, s));
-    AX_TRY(colsum(T, 3 * h, st->dqkv, 3 * h, st->vec0, st->red_ws, s));
+    AX_TRY(colsum(T, 3 * h, a.dqkv, 3 * h, st->vec0, st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_BQKV, st->vec0, 3 * h, acc, s));
     // u = LN1(x); residual: dx = dy + dLN1
-    AX_TRY(ln_bwd(T, h, st->du, a.x, a.stats1, param_ptr(st, l, P_LN1G), st->dy_mid, d_out, st->vec0, st->vec1,
+    AX_TRY(ln_bwd(T, h, st->du, a.x, a.stats1, param_ptr(st, l, P_LN1G), a.dy_mid, d_out, st->vec0, st->vec1,
                   st->red_ws, s));
     AX_TRY(vec_grad(st, l, P_LN1G, st->vec0, h, acc, s));
     AX_TRY(vec_grad(st, l, P_LN1B, st->vec1, h, acc, s));
-    d_in = d_out;
   }
   return AXONN_OK;
 }
 
-Slot* find_slot(axonn_stage* st, int mb_id) {
+// Weight gradients of every slot that has finished its backward chain, summed over those
+// microbatches inside one contraction per weight (the token index of all of them is the
+// contraction index): dW = sum_mb x_mb^T dy_mb.  Runs on `s` after the chains it reads and after
+// the previous such pass (they update the same accumulators), then releases the slots.
+int gemm_seg(int epi, int M, int N, int K, const bf16_t* const* A, int64_t lda, const bf16_t* const* B,
+             int64_t ldb, int n_seg, void* C, int64_t ldc, int accumulate, hipStream_t s) {
+  GemmArgs g;
+  memset(&g, 0, sizeof g);
+  for (int i = 0; i < n_seg; ++i) { g.A_seg[i] = A[i]; g.B_seg[i] = B[i]; }
+  g.n_seg = n_seg; g.C = C; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
+  g.M = M; g.N = N; g.K = K; g.accumulate = accumulate;
+  ProfScope ps(PC_GEMM_WGRAD, s);
+  return check_launch(launch_gemm(false, false, epi, g, s), "gemm (weight gradient)");
+}
+
+int flush_wgrad(axonn_stage* st, hipStream_t s) {
+  std::vector<Slot*> ready;
+  for (Slot& sl : st->slots)
+    if (sl.state == SLOT_AWAIT_WGRAD) ready.push_back(&sl);
+  if (ready.empty()) return AXONN_OK;
+  const int T = st->T, h = st->h, f = st->f, L = st->cfg.n_layers;
+  const int epi = st->cfg.grad_accum_fp32 ? EPI_ACC_F32 : EPI_ACC_BF16;
+  for (Slot* sl : ready) HIP_TRY(hipStreamWaitEvent(s, sl->dgrad_done, 0));
+  if (st->last_wgrad_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_wgrad, 0));
+  for (size_t first = 0; first < ready.size(); first += kMaxKSegments) {
+    const int n = (int)std::min<size_t>(kMaxKSegments, ready.size() - first);
+    const int acc = st->wgrad_flushes > 0 ? 1 : 0;
+    const bf16_t *A[kMaxKSegments], *B[kMaxKSegments];
+    for (int l = 0; l < L; ++l) {
+      for (int i = 0; i < n; ++i) { A[i] = ready[first + i]->layers[l].g; B[i] = ready[first + i]->layers[l].dz; }
+      AX_TRY(gemm_seg(epi, f, h, T, A, f, B, h, n, grad_ptr(st, l, P_WFC2), h, acc, s));
+      for (int i = 0; i < n; ++i) { A[i] = ready[first + i]->layers[l].w; B[i] = ready[first + i]->layers[l].dpre; }
+      AX_TRY(gemm_seg(epi, h, f, T, A, h, B, f, n, grad_ptr(st, l, P_WFC1), f, acc, s));
+      for (int i = 0; i < n; ++i) { A[i] = ready[first + i]->layers[l].o; B[i] = ready[first + i]->layers[l].dy_mid; }
+      AX_TRY(gemm_seg(epi, h, h, T, A, h, B, h, n, grad_ptr(st, l, P_WO), h, acc, s));
+      for (int i = 0; i < n; ++i) { A[i] = ready[first + i]->layers[l].u; B[i] = ready[first + i]->layers[l].dqkv; }
+      AX_TRY(gemm_seg(epi, h, 3 * h, T, A, h, B, 3 * h, n, grad_ptr(st, l, P_WQKV), 3 * h, acc, s));
+    }
+    st->wgrad_flushes++;
+  }
+  HIP_TRY(hipEventRecord(st->last_wgrad, s));
+  st->last_wgrad_recorded = true;
+  for (Slot* sl : ready) {
+    HIP_TRY(hipEventRecord(sl->released, s));
+    sl->released_recorded = true;
+    sl->state = SLOT_FREE;
+  }
+  return AXONN_OK;
+}
+
+int count_state(const axonn_stage* st, int state) {
+  int n = 0;
+  for (const Slot& s : st->slots) n += (s.state == state);
+  return n;
+}
+
+Slot* find_live(axonn_stage* st, int mb_id) {
   for (Slot& s : st->slots)
-    if (s.mb_id == mb_id) return &s;
+    if (s.state == SLOT_LIVE && s.mb_id == mb_id) return &s;
+  return nullptr;
+}
+Slot* find_free(axonn_stage* st) {
+  for (Slot& s : st->slots)
+    if (s.state == SLOT_FREE) return &s;
   return nullptr;
 }
 
-int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s) {
+// `ws` is the stream weight-gradient passes go to (the caller's stream in direct mode).
+int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s, hipStream_t ws) {
   if (mb_id < 0) return fail(AXONN_EINVAL, "forward: negative microbatch id %d", mb_id);
-  if (find_slot(st, mb_id)) return fail(AXONN_ESTATE, "forward: microbatch %d is already in flight", mb_id);
+  if (find_live(st, mb_id)) return fail(AXONN_ESTATE, "forward: microbatch %d is already in flight", mb_id);
   if (st->in_flight >= st->cfg.pipeline_limit)
     return fail(AXONN_ESTATE, "forward: pipeline_limit (%d) microbatches already in flight",
                 st->cfg.pipeline_limit);
-  Slot* slot = find_slot(st, -1);
+  Slot* slot = find_free(st);
+  if (!slot) {
+    // every slot not in flight is waiting for its weight gradients: form them now
+    AX_TRY(flush_wgrad(st, ws));
+    slot = find_free(st);
+  }
   if (!slot) return fail(AXONN_ESTATE, "forward: no free stash slot");
-  // the slot's previous occupant must have finished its backward before it is overwritten
-  if (slot->bwd_recorded) HIP_TRY(hipStreamWaitEvent(s, slot->bwd_done, 0));
+  // the weight-gradient pass that read the slot's previous contents must have finished
+  if (slot->released_recorded) HIP_TRY(hipStreamWaitEvent(s, slot->released, 0));
   const uint64_t bytes = (uint64_t)st->T * st->h * sizeof(bf16_t);
   {
     ProfScope ps(PC_COPY_IN, s);
@@ -319,30 +394,38 @@ int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s
   }
   AX_TRY(forward_layers(st, *slot, y, s));
   HIP_TRY(hipEventRecord(slot->fwd_done, s));
+  slot->state = SLOT_LIVE;
   slot->mb_id = mb_id;
   st->in_flight++;
   return AXONN_OK;
 }
 
-int do_backward(axonn_stage* st, int mb_id, const void* dy, void* dx, hipStream_t s) {
-  Slot* slot = (mb_id >= 0) ? find_slot(st, mb_id) : nullptr;
+int do_backward(axonn_stage* st, int mb_id, const void* dy, void* dx, hipStream_t s, hipStream_t ws) {
+  Slot* slot = (mb_id >= 0) ? find_live(st, mb_id) : nullptr;
   if (!slot) return fail(AXONN_ESTATE, "backward: microbatch %d has no forward in flight", mb_id);
   HIP_TRY(hipStreamWaitEvent(s, slot->fwd_done, 0));
-  // backward passes share the workspace and the gradient accumulators: keep them in order
+  // backward chains share the workspace and the bias / LayerNorm accumulators: keep them in order
   if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_bwd, 0));
   const int acc = st->bwd_count > 0 ? 1 : 0;
   AX_TRY(backward_layers(st, *slot, dy, dx, acc, s));
   st->bwd_count++;
-  if (st->cfg.grad_accum_fp32 && st->bwd_count == st->cfg.n_microbatches) {
-    ProfScope ps(PC_GRAD_CONVERT, s);
-    AX_TRY(check_launch(launch_f32_to_bf16(st->n_params, st->grads32, st->grads, s), "f32_to_bf16"));
-  }
-  HIP_TRY(hipEventRecord(slot->bwd_done, s));
-  slot->bwd_recorded = true;
+  HIP_TRY(hipEventRecord(slot->dgrad_done, s));
   HIP_TRY(hipEventRecord(st->last_bwd, s));
   st->last_bwd_recorded = true;
+  slot->state = SLOT_AWAIT_WGRAD;
   slot->mb_id = -1;
   st->in_flight--;
+  const bool last = st->bwd_count == st->cfg.n_microbatches;
+  const int group = st->cfg.wgrad_group;
+  if (last || (group > 0 && count_state(st, SLOT_AWAIT_WGRAD) >= group)) AX_TRY(flush_wgrad(st, ws));
+  if (last && st->cfg.grad_accum_fp32) {
+    // bias / LayerNorm gradients of the last chain (stream s) and all weight gradients (stream ws)
+    if (ws != s) HIP_TRY(hipStreamWaitEvent(ws, st->last_bwd, 0));
+    ProfScope ps(PC_GRAD_CONVERT, ws);
+    AX_TRY(check_launch(launch_f32_to_bf16(st->n_params, st->grads32, st->grads, ws), "f32_to_bf16"));
+    HIP_TRY(hipEventRecord(st->last_wgrad, ws));
+    st->last_wgrad_recorded = true;
+  }
   return AXONN_OK;
 }
 
@@ -386,12 +469,16 @@ void destroy_stage(axonn_stage* st) {
   for (Slot& s : st->slots) {
     if (s.base) (void)hipFree(s.base);
     if (s.fwd_done) (void)hipEventDestroy(s.fwd_done);
-    if (s.bwd_done) (void)hipEventDestroy(s.bwd_done);
+    if (s.dgrad_done) (void)hipEventDestroy(s.dgrad_done);
+    if (s.released) (void)hipEventDestroy(s.released);
   }
   for (hipStream_t s : st->streams) (void)hipStreamDestroy(s);
   for (hipEvent_t e : st->stream_tail) (void)hipEventDestroy(e);
   if (st->last_bwd) (void)hipEventDestroy(st->last_bwd);
   if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
+  if (st->last_wgrad) (void)hipEventDestroy(st->last_wgrad);
+  if (st->wgrad_tail) (void)hipEventDestroy(st->wgrad_tail);
+  if (st->wgrad_stream) (void)hipStreamDestroy(st->wgrad_stream);
   if (st->ws_base) (void)hipFree(st->ws_base);
   if (st->params) (void)hipFree(st->params);
   if (st->grads) (void)hipFree(st->grads);
@@ -408,6 +495,7 @@ int validate_config(const axonn_stage_config* c) {
   if (c->hidden % c->n_heads != 0) return fail(AXONN_EINVAL, "stage config: hidden %% n_heads != 0");
   if (!(c->ln_eps > 0.f)) return fail(AXONN_EINVAL, "stage config: ln_eps must be positive");
   if (c->device < 0) return fail(AXONN_EINVAL, "stage config: negative device ordinal");
+  if (c->wgrad_group < 0) return fail(AXONN_EINVAL, "stage config: negative wgrad_group");
   const int d = c->hidden / c->n_heads;
   if (d != 64 && d != 128)
     return fail(AXONN_EUNSUPPORTED, "head dim %d unsupported: attention kernels exist for 64 and 128", d);
@@ -494,16 +582,18 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
   }
 
   // activation stash: per layer x,u,o,y,w [T,h], qkv [T,3h], pre,g [T,f], stats [T,2]x2, lse [b,a,s]
+  // plus the output gradients kept for the deferred weight gradients: dz,dy_mid [T,h], dpre [T,f], dqkv [T,3h]
   const uint64_t e_th = align_up((uint64_t)T * h * 2, 256), e_t3h = align_up((uint64_t)T * 3 * h * 2, 256),
                  e_tf = align_up((uint64_t)T * f * 2, 256), e_st = align_up((uint64_t)T * 2 * 4, 256),
                  e_lse = align_up((uint64_t)cfg->microbatch_size * cfg->n_heads * cfg->seq_len * 4, 256);
-  const uint64_t per_layer = 5 * e_th + e_t3h + 2 * e_tf + 2 * e_st + e_lse;
+  const uint64_t per_layer = 7 * e_th + 2 * e_t3h + 3 * e_tf + 2 * e_st + e_lse;
   st->slot_bytes = per_layer * cfg->n_layers;
   st->slots.resize(cfg->pipeline_limit);
   for (Slot& s : st->slots) {
     CREATE_TRY(hipMalloc((void**)&s.base, st->slot_bytes));
     CREATE_TRY(hipEventCreateWithFlags(&s.fwd_done, hipEventDisableTiming));
-    CREATE_TRY(hipEventCreateWithFlags(&s.bwd_done, hipEventDisableTiming));
+    CREATE_TRY(hipEventCreateWithFlags(&s.dgrad_done, hipEventDisableTiming));
+    CREATE_TRY(hipEventCreateWithFlags(&s.released, hipEventDisableTiming));
     s.layers.resize(cfg->n_layers);
     char* p = s.base;
     for (LayerStash& a : s.layers) {
@@ -511,22 +601,24 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
       a.y = (bf16_t*)p; p += e_th;  a.w = (bf16_t*)p; p += e_th;  a.qkv = (bf16_t*)p; p += e_t3h;
       a.pre = (bf16_t*)p; p += e_tf; a.g = (bf16_t*)p; p += e_tf;
       a.stats1 = (float*)p; p += e_st; a.stats2 = (float*)p; p += e_st; a.lse = (float*)p; p += e_lse;
+      a.dz = (bf16_t*)p; p += e_th; a.dy_mid = (bf16_t*)p; p += e_th;
+      a.dpre = (bf16_t*)p; p += e_tf; a.dqkv = (bf16_t*)p; p += e_t3h;
     }
   }
   // backward workspace
   const int64_t wide = std::max<int64_t>(f, 3 * h);
   const uint64_t e_red = align_up((uint64_t)2 * ((T + 63) / 64) * wide * 4, 256), e_vec = align_up((uint64_t)wide * 4, 256);
-  st->ws_bytes = 6 * e_th + e_tf + e_t3h + e_lse + e_red + 2 * e_vec;
+  st->ws_bytes = 3 * e_th + e_lse + e_red + 2 * e_vec;
   CREATE_TRY(hipMalloc((void**)&st->ws_base, st->ws_bytes));
   {
     char* p = st->ws_base;
-    st->dres[0] = (bf16_t*)p; p += e_th; st->dres[1] = (bf16_t*)p; p += e_th; st->dy_mid = (bf16_t*)p; p += e_th;
     st->dw = (bf16_t*)p; p += e_th; st->dattn = (bf16_t*)p; p += e_th; st->du = (bf16_t*)p; p += e_th;
-    st->dpre = (bf16_t*)p; p += e_tf; st->dqkv = (bf16_t*)p; p += e_t3h;
     st->delta = (float*)p; p += e_lse; st->red_ws = (float*)p; p += e_red;
     st->vec0 = (float*)p; p += e_vec; st->vec1 = (float*)p; p += e_vec;
   }
   CREATE_TRY(hipEventCreateWithFlags(&st->last_bwd, hipEventDisableTiming));
+  CREATE_TRY(hipEventCreateWithFlags(&st->last_wgrad, hipEventDisableTiming));
+  CREATE_TRY(hipEventCreateWithFlags(&st->wgrad_tail, hipEventDisableTiming));
   CREATE_TRY(hipEventCreateWithFlags(&st->fork_ev, hipEventDisableTiming));
   CREATE_TRY(hipDeviceSynchronize());
 #undef CREATE_TRY
@@ -577,9 +669,13 @@ int axonn_stage_zero_grad(axonn_stage_t* st, void* hip_stream) {
   HIP_TRY(hipSetDevice(st->cfg.device));
   hipStream_t s = (hipStream_t)hip_stream;
   if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_bwd, 0));
-  // no memory is touched: the first backward of a batch overwrites the accumulators
-  (void)s;
+  if (st->last_wgrad_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_wgrad, 0));
+  // no memory is touched: the first backward / weight-gradient pass of a batch overwrites the
+  // accumulators.  Microbatches whose weight gradients were still pending are dropped.
+  for (Slot& sl : st->slots)
+    if (sl.state == SLOT_AWAIT_WGRAD) sl.state = SLOT_FREE;
   st->bwd_count = 0;
+  st->wgrad_flushes = 0;
   st->fwd_issued = st->bwd_issued = 0;
   st->dispatch_log.clear();
   return AXONN_OK;
@@ -598,12 +694,12 @@ int axonn_stage_device_bytes(const axonn_stage_t* st, uint64_t bytes[6]) {
 int axonn_stage_forward(axonn_stage_t* st, int32_t mb_id, const void* x, void* y, void* hip_stream) {
   if (!st || !x || !y) return fail(AXONN_EINVAL, "forward: null argument");
   HIP_TRY(hipSetDevice(st->cfg.device));
-  return do_forward(st, mb_id, x, y, (hipStream_t)hip_stream);
+  return do_forward(st, mb_id, x, y, (hipStream_t)hip_stream, (hipStream_t)hip_stream);
 }
 int axonn_stage_backward(axonn_stage_t* st, int32_t mb_id, const void* dy, void* dx, void* hip_stream) {
   if (!st || !dy || !dx) return fail(AXONN_EINVAL, "backward: null argument");
   HIP_TRY(hipSetDevice(st->cfg.device));
-  return do_backward(st, mb_id, dy, dx, (hipStream_t)hip_stream);
+  return do_backward(st, mb_id, dy, dx, (hipStream_t)hip_stream, (hipStream_t)hip_stream);
 }
 
 int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg) {
@@ -633,6 +729,14 @@ int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream) {
   // the library streams start after everything already queued on the caller's stream
   HIP_TRY(hipEventRecord(st->fork_ev, (hipStream_t)hip_stream));
   for (int i = 0; i < n_streams; ++i) HIP_TRY(hipStreamWaitEvent(st->streams[i], st->fork_ev, 0));
+  // weight-gradient passes get a stream of their own when there is more than one, so that they
+  // overlap the next microbatches' work
+  hipStream_t ws = st->streams[0];
+  if (n_streams > 1) {
+    if (!st->wgrad_stream) HIP_TRY(hipStreamCreateWithFlags(&st->wgrad_stream, hipStreamNonBlocking));
+    ws = st->wgrad_stream;
+    HIP_TRY(hipStreamWaitEvent(ws, st->fork_ev, 0));
+  }
   const int M = st->cfg.n_microbatches;
   const auto t_start = std::chrono::steady_clock::now();
   while (st->fwd_issued < M || st->bwd_issued < M) {
@@ -642,8 +746,8 @@ int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream) {
     for (size_t i = 0; i < st->inbox.size(); ++i) {
       const axonn_msg& m = st->inbox[i].m;
       const bool admissible = (m.kind == 0)
-                                  ? (st->in_flight < st->cfg.pipeline_limit && !find_slot(st, m.mb_id))
-                                  : (find_slot(st, m.mb_id) != nullptr);
+                                  ? (st->in_flight < st->cfg.pipeline_limit && !find_live(st, m.mb_id))
+                                  : (find_live(st, m.mb_id) != nullptr);
       if (!admissible) continue;
       any_admissible = true;
       if (m.ready_event) {
@@ -675,10 +779,10 @@ int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream) {
     hipStream_t s = st->streams[si];
     if (m.ready_event) HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)m.ready_event, 0));
     if (m.kind == 0) {
-      AX_TRY(do_forward(st, m.mb_id, m.payload_dev, m.result_dev, s));
+      AX_TRY(do_forward(st, m.mb_id, m.payload_dev, m.result_dev, s, ws));
       st->fwd_issued++;
     } else {
-      AX_TRY(do_backward(st, m.mb_id, m.payload_dev, m.result_dev, s));
+      AX_TRY(do_backward(st, m.mb_id, m.payload_dev, m.result_dev, s, ws));
       st->bwd_issued++;
     }
     st->dispatch_log.push_back(m.mb_id * 2 + m.kind);
@@ -692,6 +796,10 @@ int axonn_stage_join(axonn_stage_t* st, void* user_stream) {
   for (size_t i = 0; i < st->streams.size(); ++i) {
     HIP_TRY(hipEventRecord(st->stream_tail[i], st->streams[i]));
     HIP_TRY(hipStreamWaitEvent((hipStream_t)user_stream, st->stream_tail[i], 0));
+  }
+  if (st->wgrad_stream) {
+    HIP_TRY(hipEventRecord(st->wgrad_tail, st->wgrad_stream));
+    HIP_TRY(hipStreamWaitEvent((hipStream_t)user_stream, st->wgrad_tail, 0));
   }
   return AXONN_OK;
 }
@@ -833,6 +941,10 @@ int axonn_stage_optimizer_step(axonn_stage_t* st, double lr, double beta1, doubl
   HIP_TRY(hipSetDevice(st->cfg.device));
   hipStream_t user = (hipStream_t)hip_stream;
   if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(user, st->last_bwd, 0));
+  if (st->last_wgrad_recorded) HIP_TRY(hipStreamWaitEvent(user, st->last_wgrad, 0));
+  if (count_state(st, SLOT_AWAIT_WGRAD))
+    return fail(AXONN_ESTATE, "optimizer_step: %d microbatches still await their weight gradients (fewer than "
+                "n_microbatches backwards since zero_grad)", count_state(st, SLOT_AWAIT_WGRAD));
   return axonn_offload_adam_step(st->opt, lr, beta1, beta2, eps, weight_decay, step, grad_scale, hip_stream);
 }
 

@@ -1,0 +1,156 @@
+"""Parity at the full benchmark sizes (12B-, 24B- and 100B-class stage shapes, and the
+1.6e9-parameter offloaded optimizer step), in the launch configuration bench.py times: all
+microbatches in flight, message-driven run on two library streams.
+
+The fp64 oracle is too slow for a whole batch at these sizes, so it computes microbatch 0 only:
+  * its stage output and input gradient are compared in full (per-microbatch tensors do not depend
+    on the other microbatches);
+  * the parameter gradients of a batch that holds microbatch 0 alone are compared in full;
+  * the full batch is tied to that by linearity, a property that holds at any size: the gradients
+    of the M-microbatch run equal the sum of the gradients of single-microbatch runs (checked on
+    sampled tensors against two further single-microbatch GPU runs where M allows).
+Bounds: the benchmark definition's (2e-2 forward, 3e-2 gradients, 1e-6 Adam master state)."""
+import sys
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2110_13005_amd import binding as B
+from paper_2110_13005_amd.inputs import CONFIGS, OPT_CONFIG, StageShape, make_stage_inputs
+from paper_2110_13005_amd.stage import Stage
+from helpers import rel_fro, dev_bf16, host
+
+pytestmark = pytest.mark.gpu
+EPS = 1e-5
+
+
+def _say(msg):
+    print("[fullsize] " + msg, flush=True)
+    sys.stdout.flush()
+
+
+def _message_run(st, X, DY, Y, DX, n_streams=2):
+    import torch
+    M = len(X)
+    st.zero_grad()
+    for i in range(M):
+        st.post(0, i, X[i], Y[i])
+    for i in range(M):
+        st.post(1, i, DY[i], DX[i])
+    st.run(n_streams)
+    st.join()
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("name", ["12b", "24b", "100b"])
+def test_full_size_stage_parity(name):
+    import torch
+    sh = CONFIGS[name]
+    M = sh.n_microbatches
+    t0 = time.time()
+    _say("%s: generating inputs (seed 0)" % name)
+    # the recipe draws all M microbatches; only microbatch 0's values are needed on the host
+    layers, xs, dys = make_stage_inputs(sh, seed=0, n_microbatches=1)
+    rng = np.random.default_rng(1)
+    with Stage(sh) as st:
+        st.load_params(layers)
+        bsh = (sh.microbatch_size, sh.seq_len, sh.hidden)
+        X = [dev_bf16(xs[0])] + [torch.randn(bsh, device="cuda").to(torch.bfloat16) for _ in range(M - 1)]
+        DY = [dev_bf16(dys[0])] + [torch.randn(bsh, device="cuda").to(torch.bfloat16) for _ in range(M - 1)]
+        Y = [torch.zeros_like(X[0]) for _ in range(M)]
+        DX = [torch.zeros_like(X[0]) for _ in range(M)]
+        _say("%s: GPU batch of %d microbatches, message-driven, 2 streams" % (name, M))
+        _message_run(st, X, DY, Y, DX)
+        y0, dx0 = host(Y[0]), host(DX[0])
+        # sampled parameter-gradient tensors of the full batch, for the linearity check
+        names = ["layer0.w_qkv", "layer%d.w_fc2" % (sh.n_layers - 1), "layer0.ln1_g", "layer%d.b_fc1" % (sh.n_layers - 1)]
+        full = {n: st.tensor(n, grad=True).double().clone() for n in names}
+    # single-microbatch batches on a stage with one slot
+    one = StageShape(sh.n_layers, sh.hidden, sh.n_heads, sh.seq_len, sh.microbatch_size, 1, sh.ffn_hidden)
+    with Stage(one) as s1:
+        s1.load_params(layers)
+        acc = {n: 0.0 for n in names}
+        g0 = None
+        Yt, DXt = torch.zeros_like(X[0]), torch.zeros_like(X[0])
+        for i in range(M):
+            _message_run(s1, [X[i]], [DY[i]], [Yt], [DXt], n_streams=1)
+            for n in names:
+                acc[n] = acc[n] + s1.tensor(n, grad=True).double()
+            if i == 0:
+                g0 = s1.grads_numpy()
+                assert torch.equal(Yt, Y[0]) and torch.equal(DXt, DX[0])   # same kernels, same bits
+    for n in names:
+        e = float((full[n] - acc[n]).norm() / acc[n].norm())
+        _say("%s: linearity %s rel err %.2e" % (name, n, e))
+        assert e <= 1e-2, (n, e)       # M roundings of bf16 single-batch gradients vs one rounding
+    _say("%s: oracle on microbatch 0 (fp64, host) ..." % name)
+    t1 = time.time()
+    ref_out, ref_dx, ref_g = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
+    _say("%s: oracle took %.0f s" % (name, time.time() - t1))
+    e_f = rel_fro(y0.reshape(ref_out[0].shape), ref_out[0])
+    e_b = rel_fro(dx0.reshape(ref_dx[0].shape), ref_dx[0])
+    worst, worst_name = 0.0, ""
+    for li, g in enumerate(g0):
+        for k, v in g.items():
+            e = rel_fro(v, ref_g[li][k])
+            if e > worst:
+                worst, worst_name = e, "layer%d.%s" % (li, k)
+    _say("%s: forward %.3e  dx %.3e  worst grad %.3e (%s)  total %.0f s" % (name, e_f, e_b, worst, worst_name, time.time() - t0))
+    assert e_f <= 2e-2 and e_b <= 3e-2 and worst <= 3e-2
+
+
+def test_full_size_offloaded_adam():
+    """Config 5: 1.6e9 parameters, 2^26-element buckets (24, last one ragged), mid-training
+    state, lr 1e-4, betas (0.9, 0.95), eps 1e-8, step 100.  The oracle is evaluated on sampled
+    index ranges: the first and last elements, every bucket boundary and seeded random blocks."""
+    import ctypes
+    import torch
+    oc = OPT_CONFIG
+    n, bucket = oc["n"], oc["bucket_elems"]
+    _say("adam: allocating 3 x %.1f GB pinned" % (4 * n / 1e9))
+    ptrs = [B.axonn_pinned_alloc(4 * n) for _ in range(3)]
+    arrs = [np.ctypeslib.as_array((ctypes.c_float * n).from_address(p)) for p in ptrs]
+    g = torch.Generator(device="cuda"); g.manual_seed(0)
+    G16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    P16 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    step = 1 << 26
+    for o in range(0, n, step):
+        c = min(step, n - o)
+        torch.from_numpy(arrs[0][o:o + c]).copy_(torch.randn(c, generator=g, device="cuda") * 0.02)
+        torch.from_numpy(arrs[1][o:o + c]).copy_(torch.randn(c, generator=g, device="cuda") * 1e-4)
+        torch.from_numpy(arrs[2][o:o + c]).copy_((torch.randn(c, generator=g, device="cuda") * 1e-6).abs())
+        G16[o:o + c] = (torch.randn(c, generator=g, device="cuda") * 1e-3).to(torch.bfloat16)
+    torch.cuda.synchronize()
+    # sampled ranges, inputs copied out before the step overwrites them
+    rng = np.random.default_rng(0)
+    starts = [0, n - 4096] + [b * bucket - 2048 for b in range(1, (n + bucket - 1) // bucket)]
+    starts += [int(s) for s in rng.integers(0, n - 4096, size=40)]
+    sample = [(s, s + 4096) for s in starts]
+    before = [(arrs[0][a:b].copy(), arrs[1][a:b].copy(), arrs[2][a:b].copy(), G16[a:b].float().cpu().numpy()) for a, b in sample]
+    opt = B.axonn_offload_adam_create(0, n, bucket, P16, G16, ptrs[0], ptrs[1], ptrs[2])
+    try:
+        assert B.axonn_offload_adam_device_bytes(opt) == 3 * 12 * bucket     # footprint independent of n
+        _say("adam: step over %d buckets" % ((n + bucket - 1) // bucket))
+        t0 = time.time()
+        B.axonn_offload_adam_step(opt, oc["lr"], oc["beta1"], oc["beta2"], oc["eps"], oc["weight_decay"], oc["step"], oc["grad_scale"])
+        torch.cuda.synchronize()
+        _say("adam: step took %.3f s" % (time.time() - t0))
+        worst = 0.0
+        for (a, b), (th, m, v, g16) in zip(sample, before):
+            rt, rm, rv, r16 = oracle.adam_step(th, m, v, g16, oc["lr"], oc["beta1"], oc["beta2"], oc["eps"], oc["weight_decay"], oc["step"], oc["grad_scale"])
+            worst = max(worst, rel_fro(arrs[0][a:b], rt), rel_fro(arrs[1][a:b], rm), rel_fro(arrs[2][a:b], rv))
+            got16 = P16[a:b].float().cpu().numpy()
+            assert np.array_equal(got16, oracle.bf16_round(arrs[0][a:b]))
+            assert np.abs(got16 - r16).max() <= np.abs(r16).max() * 2.0 ** -7
+        _say("adam: worst relative error %.2e" % worst)
+        assert worst <= 1e-6
+        # everything was touched exactly once: bf16 parameters are the rounding of the master copy
+        for o in range(0, n, step):
+            c = min(step, n - o)
+            assert torch.equal(P16[o:o + c].cpu(), torch.from_numpy(arrs[0][o:o + c]).to(torch.bfloat16))
+    finally:
+        B.axonn_offload_adam_destroy(opt)
+        for p in ptrs:
+            B.axonn_pinned_free(p)
