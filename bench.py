@@ -23,6 +23,11 @@ sys.path.insert(0, ROOT)
 import numpy as np  # noqa: E402
 
 
+# HBM bytes per launch of the weight-gradient GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (summaries and the scaling by a plain copy under profiles/); keyed by (config, wgrad_group, grad_accum).
+WGRAD_TRAFFIC_BYTES = {}
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -32,7 +37,7 @@ def parse():
     ap.add_argument("--streams", type=int, default=2, help="library streams of the message-driven run")
     ap.add_argument("--pipeline-limit", type=int, default=0, help="0 = all microbatches in flight")
     ap.add_argument("--grad-accum", default="fp32", choices=["fp32", "bf16"])
-    ap.add_argument("--wgrad-group", type=int, default=0, help="microbatches per weight-gradient contraction (0 = as many as possible)")
+    ap.add_argument("--wgrad-group", type=int, default=2, help="microbatches per weight-gradient contraction (0 = as many as possible)")
     ap.add_argument("--bucket-elems", type=int, default=1 << 26)
     ap.add_argument("--no-optimizer", action="store_true", help="diagnostic: leave the Adam step out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -50,17 +55,17 @@ def cpu_baseline(shape):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    one = StageShape(1, shape.hidden, shape.n_heads, shape.seq_len, shape.microbatch_size, 1, shape.ffn_hidden)
+    one = StageShape(shape.n_layers, shape.hidden, shape.n_heads, shape.seq_len, shape.microbatch_size, 1,
+                     shape.ffn_hidden)
     layers, xs, dys = make_stage_inputs(one, seed=0)
     t0 = time.perf_counter()
     oracle.stage_batch(xs, dys, layers, one.n_heads, 1e-5)
     dt = time.perf_counter() - t0
     fl = flops.stage_batch_flops(one, causal=True)
-    frac = "1 of %d layers x 1 of %d microbatches" % (shape.n_layers, shape.n_microbatches)
     return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle",
-            "sample": "%s of the workload, fp64 numpy oracle, %.1f s; causal FLOP count" % (frac, dt),
-            "tokens_per_s": one.tokens / dt / shape.n_layers,
-            "seconds": dt}
+            "sample": "1 of %d microbatches of the workload through the whole stage (fwd+bwd), fp64 numpy "
+                      "oracle, %.1f s; causal FLOP count" % (shape.n_microbatches, dt),
+            "tokens_per_s": one.tokens / dt, "seconds": dt}
 
 
 def main():
@@ -217,12 +222,27 @@ def main():
             if cat in kern:
                 kern[cat]["tflops"] = per_layer_mb * sh.n_layers * M / (kern[cat]["total_ms"] * 1e-3) / 1e12
         out["kernels"] = kern
-        dom = max((c for c in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad") if c in kern), key=lambda c: kern[c]["total_ms"])
-        ach = kern[dom]["tflops"]
-        out["roofline"] = {"bound": "mfma", "achieved": ach, "peak": flops.PEAK_BF16_DENSE_TFLOPS, "unit": "TFLOP/s",
-                           "frac": ach / flops.PEAK_BF16_DENSE_TFLOPS, "traffic": None, "kernel": dom,
-                           "avg_launch_ms": kern[dom]["avg_ms"],
-                           "flops_per_launch": per_layer_mb / 4.0}
+        # roofline of the largest single kernel by time: the weight-gradient GEMM
+        # (gemm_kernel<256,256,64,2,4,false,false,EPI_ACC_*>), one launch = one weight of one layer for a
+        # group of microbatches; its four shapes average to per_layer_mb/4 FLOP per microbatch
+        dom = "gemm_wgrad"
+        if dom in kern:
+            per_launch = per_layer_mb * sh.n_layers * M / kern[dom]["launches"]
+            ach = per_launch / (kern[dom]["avg_ms"] * 1e-3) / 1e12
+            out["roofline"] = {"bound": "mfma", "achieved": ach, "peak": flops.PEAK_BF16_DENSE_TFLOPS,
+                               "unit": "TFLOP/s", "frac": ach / flops.PEAK_BF16_DENSE_TFLOPS,
+                               "traffic": WGRAD_TRAFFIC_BYTES.get((args.config, args.wgrad_group, args.grad_accum)),
+                               "kernel": "axonn::gemm_kernel<256,256,64,2,4,false,false,%d> (weight gradient)"
+                                         % (4 if args.grad_accum == "fp32" else 5),
+                               "avg_launch_ms": kern[dom]["avg_ms"], "flops_per_launch": per_launch,
+                               "measured": "launch timing events on the launching stream, one single-stream batch"}
+    # a plain device copy of known size (256 MiB read + 256 MiB written): the reference the HBM byte
+    # counters of a profiling run are scaled by
+    cal = torch.empty(1 << 27, dtype=torch.int16, device=dev)
+    cal2 = torch.empty_like(cal)
+    cal2.copy_(cal)
+    torch.cuda.synchronize()
+    del cal, cal2
     st.close()
     for p in host_ptrs:
         B.axonn_pinned_free(p)
