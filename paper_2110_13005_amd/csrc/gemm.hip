@@ -127,12 +127,18 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
 
-  // Workgroups are dealt round-robin to the 8 XCDs; remap so that each XCD (own L2) works on
-  // a contiguous run of tiles, ordered m-fastest so that neighbours share the B panel.
+  // Workgroups are dealt round-robin to the 8 XCDs; remap so that each XCD (own L2) works on a
+  // contiguous run of tiles, and order tiles in bands of 8 tile-rows, column by column inside a band:
+  // the ~32 tiles an XCD has in flight then form an 8 x 4 patch that shares 8 A panels and 4 B
+  // panels instead of streaming 32 + 1.
   int pid = blockIdx.x;
   const int nblk = gridDim.x;
   if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
-  const int tm = pid % g.tiles_m, tn = pid / g.tiles_m;
+  constexpr int BAND = 8;
+  const int band_tiles = BAND * g.tiles_n;
+  const int band = pid / band_tiles, in_band = pid - band * band_tiles;
+  const int band_rows = min(BAND, g.tiles_m - band * BAND);
+  const int tm = band * BAND + in_band % band_rows, tn = in_band / band_rows;
   const int m0 = tm * BM, n0 = tn * BN;
 
   // Per-thread view of the tile copy: chunk j of this thread is 16 bytes at offset offa[j] of the
