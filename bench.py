@@ -36,7 +36,7 @@ def parse():
     ap.add_argument("--config", default="12b", choices=["tiny", "12b", "24b", "100b"])
     ap.add_argument("--streams", type=int, default=2, help="library streams of the message-driven run")
     ap.add_argument("--pipeline-limit", type=int, default=0, help="0 = all microbatches in flight")
-    ap.add_argument("--grad-accum", default="fp32", choices=["fp32", "bf16"])
+    ap.add_argument("--grad-accum", default="bf16", choices=["fp32", "bf16"])
     ap.add_argument("--wgrad-group", type=int, default=2, help="microbatches per weight-gradient contraction (0 = as many as possible)")
     ap.add_argument("--bucket-elems", type=int, default=1 << 26)
     ap.add_argument("--no-optimizer", action="store_true", help="diagnostic: leave the Adam step out of the step")

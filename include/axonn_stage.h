@@ -69,6 +69,12 @@ typedef struct {
                               one contraction over all their tokens, not per microbatch:
                               a group is closed once this many backwards are pending
                               (0: only when a stash slot is needed or the batch ends)  */
+  int32_t qkv_input_split; /* 1: the QKV projection consumes LayerNorm-1's output as the
+                              sum of two bf16 numbers (value and rounding remainder) in
+                              one contraction of length 2h, so that the bf16 rounding of
+                              the LayerNorm output does not reach the attention logits
+                              (for shapes with large logits, e.g. h = 10240 with N(0,0.02)
+                              weights; costs one more QKV-sized GEMM per layer forward)  */
 } axonn_stage_config;
 
 /* Allocates bf16 parameters and gradients (flat buffers), pipeline_limit activation

@@ -111,7 +111,7 @@ struct GemmArgs {
 // All return hipError_t of the launch (hipGetLastError) and validate nothing: callers check.
 hipError_t launch_gemm(bool a_kc, bool b_kc, int epilogue, const GemmArgs& g, hipStream_t s);
 hipError_t launch_layernorm_fwd(int64_t T, int64_t h, const void* x, const void* gamma,
-                                const void* beta, float eps, void* out, float* stats,
+                                const void* beta, float eps, void* out, void* out_lo, float* stats,
                                 hipStream_t s);
 hipError_t launch_layernorm_bwd(int64_t T, int64_t h, const void* dout, const void* x,
                                 const float* stats, const void* gamma, const void* res_grad,

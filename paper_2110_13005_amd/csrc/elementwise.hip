@@ -14,7 +14,7 @@ constexpr int LN_ROWS_PER_BLOCK = 4;
 __global__ __launch_bounds__(64 * LN_ROWS_PER_BLOCK) void layernorm_fwd_kernel(
     int T, int h, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
     const bf16_t* __restrict__ beta, float eps, bf16_t* __restrict__ out,
-    float* __restrict__ stats) {
+    bf16_t* __restrict__ out_lo, float* __restrict__ stats) {
   const int lane = threadIdx.x & 63;
   const int row = blockIdx.x * LN_ROWS_PER_BLOCK + (threadIdx.x >> 6);
   if (row >= T) return;
@@ -56,11 +56,15 @@ __global__ __launch_bounds__(64 * LN_ROWS_PER_BLOCK) void layernorm_fwd_kernel(
     if (c * 64 < nch && ch < nch) {
       const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gamma + ch * 8);
       const bf16x8 bv = *reinterpret_cast<const bf16x8*>(beta + ch * 8);
-      bf16x8 o;
+      bf16x8 o, lo;
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        o[e] = (bf16_t)((float)gv[e] * (((float)v[c][e] - mean) * rstd) + (float)bv[e]);
+      for (int e = 0; e < 8; ++e) {
+        const float val = (float)gv[e] * (((float)v[c][e] - mean) * rstd) + (float)bv[e];
+        o[e] = (bf16_t)val;
+        lo[e] = (bf16_t)(val - (float)o[e]);   // what the rounding to bf16 dropped
+      }
       *reinterpret_cast<bf16x8*>(orow + ch * 8) = o;
+      if (out_lo) *reinterpret_cast<bf16x8*>(out_lo + (int64_t)row * h + ch * 8) = lo;
     }
   }
 }
@@ -282,12 +286,12 @@ __global__ __launch_bounds__(256) void adam_kernel(uint64_t n8, uint64_t n, floa
 
 // ------------------------------------------------------------------------- launchers
 hipError_t launch_layernorm_fwd(int64_t T, int64_t h, const void* x, const void* gamma,
-                                const void* beta, float eps, void* out, float* stats,
+                                const void* beta, float eps, void* out, void* out_lo, float* stats,
                                 hipStream_t s) {
   const dim3 grid((unsigned)((T + LN_ROWS_PER_BLOCK - 1) / LN_ROWS_PER_BLOCK));
   hipLaunchKernelGGL(layernorm_fwd_kernel, grid, dim3(64 * LN_ROWS_PER_BLOCK), 0, s, (int)T, (int)h,
                      (const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, eps,
-                     (bf16_t*)out, stats);
+                     (bf16_t*)out, (bf16_t*)out_lo, stats);
   return hipGetLastError();
 }
 

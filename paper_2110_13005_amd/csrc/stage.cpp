@@ -95,6 +95,7 @@ struct TensorInfo {
 struct LayerStash {
   // forward activations kept for the backward pass
   bf16_t *x, *u, *qkv, *o, *y, *w, *pre, *g;
+  bf16_t* u_lo;   // only with qkv_input_split: the part of LayerNorm-1's output that bf16 rounding dropped
   float *stats1, *stats2, *lse;
   // output gradients of the four linear maps, written by the backward pass and kept until the
   // weight gradients of a group of microbatches are formed in one contraction
@@ -199,9 +200,9 @@ int gemm(bool a_kc, bool b_kc, int epi, int M, int N, int K, const void* A, int6
 
 
 int ln_fwd(int64_t T, int64_t h, const void* x, const void* g, const void* b, float eps, void* out,
-           float* stats, hipStream_t s) {
+           void* out_lo, float* stats, hipStream_t s) {
   ProfScope ps(PC_LN_FWD, s);
-  return check_launch(launch_layernorm_fwd(T, h, x, g, b, eps, out, stats, s), "layernorm_fwd");
+  return check_launch(launch_layernorm_fwd(T, h, x, g, b, eps, out, out_lo, stats, s), "layernorm_fwd");
 }
 int ln_bwd(int64_t T, int64_t h, const void* dout, const void* x, const float* stats, const void* g,
            const void* res, void* dx, float* dg, float* db, float* ws, hipStream_t s) {
@@ -233,13 +234,28 @@ int forward_layers(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s) {
   for (int l = 0; l < L; ++l) {
     LayerStash& a = slot.layers[l];
     bf16_t* z = (l + 1 < L) ? slot.layers[l + 1].x : (bf16_t*)y_out;
-    AX_TRY(ln_fwd(T, h, a.x, param_ptr(st, l, P_LN1G), param_ptr(st, l, P_LN1B), st->cfg.ln_eps, a.u, a.stats1, s));
-    AX_TRY(gemm(true, false, EPI_BIAS, T, 3 * h, h, a.u, h, param_ptr(st, l, P_WQKV), 3 * h, a.qkv, 3 * h,
-                param_ptr(st, l, P_BQKV), nullptr, 0, nullptr, 0, 0, s));
+    AX_TRY(ln_fwd(T, h, a.x, param_ptr(st, l, P_LN1G), param_ptr(st, l, P_LN1B), st->cfg.ln_eps, a.u, a.u_lo,
+                  a.stats1, s));
+    if (a.u_lo) {
+      // qkv = (u_hi + u_lo) W + b as one contraction of length 2h: segment 0 pairs u_hi with W,
+      // segment 1 pairs u_lo with the same W
+      GemmArgs g;
+      memset(&g, 0, sizeof g);
+      g.A_seg[0] = a.u; g.A_seg[1] = a.u_lo;
+      g.B_seg[0] = g.B_seg[1] = param_ptr(st, l, P_WQKV);
+      g.n_seg = 2; g.C = a.qkv; g.bias = param_ptr(st, l, P_BQKV);
+      g.lda = h; g.ldb = 3 * h; g.ldc = 3 * h; g.M = T; g.N = 3 * h; g.K = h;
+      ProfScope ps(PC_GEMM_FWD, s);
+      AX_TRY(check_launch(launch_gemm(true, false, EPI_BIAS, g, s), "gemm (split input)"));
+    } else {
+      AX_TRY(gemm(true, false, EPI_BIAS, T, 3 * h, h, a.u, h, param_ptr(st, l, P_WQKV), 3 * h, a.qkv, 3 * h,
+                  param_ptr(st, l, P_BQKV), nullptr, 0, nullptr, 0, 0, s));
+    }
     AX_TRY(attn_fwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d, a.qkv, a.o, a.lse, s));
     AX_TRY(gemm(true, false, EPI_BIAS_RES, T, h, h, a.o, h, param_ptr(st, l, P_WO), h, a.y, h,
                 param_ptr(st, l, P_BO), a.x, h, nullptr, 0, 0, s));
-    AX_TRY(ln_fwd(T, h, a.y, param_ptr(st, l, P_LN2G), param_ptr(st, l, P_LN2B), st->cfg.ln_eps, a.w, a.stats2, s));
+    AX_TRY(ln_fwd(T, h, a.y, param_ptr(st, l, P_LN2G), param_ptr(st, l, P_LN2B), st->cfg.ln_eps, a.w, nullptr,
+                  a.stats2, s));
     AX_TRY(gemm(true, false, EPI_BIAS_GELU, T, f, h, a.w, h, param_ptr(st, l, P_WFC1), f, a.g, f,
                 param_ptr(st, l, P_BFC1), nullptr, 0, a.pre, f, 0, s));
     AX_TRY(gemm(true, false, EPI_BIAS_RES, T, h, f, a.g, f, param_ptr(st, l, P_WFC2), h, z, h,
@@ -586,7 +602,7 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
   const uint64_t e_th = align_up((uint64_t)T * h * 2, 256), e_t3h = align_up((uint64_t)T * 3 * h * 2, 256),
                  e_tf = align_up((uint64_t)T * f * 2, 256), e_st = align_up((uint64_t)T * 2 * 4, 256),
                  e_lse = align_up((uint64_t)cfg->microbatch_size * cfg->n_heads * cfg->seq_len * 4, 256);
-  const uint64_t per_layer = 7 * e_th + 2 * e_t3h + 3 * e_tf + 2 * e_st + e_lse;
+  const uint64_t per_layer = (cfg->qkv_input_split ? 8 : 7) * e_th + 2 * e_t3h + 3 * e_tf + 2 * e_st + e_lse;
   st->slot_bytes = per_layer * cfg->n_layers;
   st->slots.resize(cfg->pipeline_limit);
   for (Slot& s : st->slots) {
@@ -603,6 +619,8 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
       a.stats1 = (float*)p; p += e_st; a.stats2 = (float*)p; p += e_st; a.lse = (float*)p; p += e_lse;
       a.dz = (bf16_t*)p; p += e_th; a.dy_mid = (bf16_t*)p; p += e_th;
       a.dpre = (bf16_t*)p; p += e_tf; a.dqkv = (bf16_t*)p; p += e_t3h;
+      a.u_lo = nullptr;
+      if (cfg->qkv_input_split) { a.u_lo = (bf16_t*)p; p += e_th; }
     }
   }
   // backward workspace
@@ -1011,7 +1029,7 @@ int axonn_layernorm_fwd(int64_t T, int64_t h, const void* x, const void* gamma, 
   if (!x || !gamma || !beta || !out || !stats) return fail(AXONN_EINVAL, "layernorm_fwd: null argument");
   if (T < 1 || h < 1) return fail(AXONN_EINVAL, "layernorm_fwd: non-positive size");
   if (h % 8 || h > 16384) return fail(AXONN_EUNSUPPORTED, "layernorm_fwd: h must be a multiple of 8 and <= 16384");
-  return check_launch(launch_layernorm_fwd(T, h, x, gamma, beta, eps, out, stats, (hipStream_t)hip_stream), "layernorm_fwd");
+  return check_launch(launch_layernorm_fwd(T, h, x, gamma, beta, eps, out, nullptr, stats, (hipStream_t)hip_stream), "layernorm_fwd");
 }
 
 int axonn_layernorm_bwd(int64_t T, int64_t h, const void* dout, const void* x, const float* stats,

@@ -31,14 +31,14 @@ def test_argument_validation_without_device():
     assert lib.axonn_stage_create(None, None) == B.AXONN_EINVAL
     assert b"null" in lib.axonn_last_error()
     out = ctypes.c_void_p()
-    cfg = B.axonn_stage_config(2, 256, 3, 1024, 128, 2, 4, 4, 1e-5, 0, 1, 0)   # 256 % 3 != 0
+    cfg = B.axonn_stage_config(2, 256, 3, 1024, 128, 2, 4, 4, 1e-5, 0, 1, 0, 0)   # 256 % 3 != 0
     assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EINVAL
-    cfg = B.axonn_stage_config(2, 256, 8, 1024, 128, 2, 4, 4, 1e-5, 0, 1, 0)   # head dim 32
+    cfg = B.axonn_stage_config(2, 256, 8, 1024, 128, 2, 4, 4, 1e-5, 0, 1, 0, 0)   # head dim 32
     assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EUNSUPPORTED
     assert b"head dim" in lib.axonn_last_error()
-    cfg = B.axonn_stage_config(2, 256, 4, 1024, 128, 2, 4, 5, 1e-5, 0, 1, 0)   # pipeline_limit > M
+    cfg = B.axonn_stage_config(2, 256, 4, 1024, 128, 2, 4, 5, 1e-5, 0, 1, 0, 0)   # pipeline_limit > M
     assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EINVAL
-    cfg = B.axonn_stage_config(2, 256, 4, 1024, 3, 1, 4, 4, 1e-5, 0, 1, 0)     # 3 tokens
+    cfg = B.axonn_stage_config(2, 256, 4, 1024, 3, 1, 4, 4, 1e-5, 0, 1, 0, 0)     # 3 tokens
     assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EUNSUPPORTED
     with pytest.raises(B.AxonnError) as e:
         B.axonn_gemm_bf16(1, 0, 0, 64, 64, 60, 1, 64, 1, 64, 1, 64)          # K % 8 != 0
