@@ -67,7 +67,7 @@ __device__ __forceinline__ bf16x8 global_frag(const bf16_t* base, int64_t ld, in
 // =============================================================================== forward
 // grid: (ceil(s/128), b*a); 4 waves; wave w owns queries q0 + 32w .. +31.
 template <int D>
-__global__ __launch_bounds__(256) void attn_fwd_kernel(int s, int a, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int s, int a, const bf16_t* __restrict__ qkv,
                                                        bf16_t* __restrict__ o,
                                                        float* __restrict__ lse) {
   constexpr int BKV = 64, LDK = D + 8, LDV = D + 32, DT = D / 32, KK = D / 16;
@@ -331,7 +331,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
 // dQ: grid (ceil(s/128), b*a); wave w owns queries q0 + 32w .. +31 and walks the key tiles up
 // to the diagonal (same traversal as the forward kernel).
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dq_kernel(
+__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     int s, int a, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
     const float* __restrict__ lse, const float* __restrict__ delta, bf16_t* __restrict__ dqkv) {
   constexpr int BKV = 64, LDK = D + 8, DT = D / 32, KK = D / 16;
