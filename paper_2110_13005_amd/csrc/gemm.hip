@@ -14,6 +14,7 @@
 // lane of the result owns one row m and runs of 4 consecutive columns n: epilogue loads and
 // stores are 8-byte (bf16) or 16-byte (fp32) vectors along the contiguous dimension of C.
 #include "common.h"
+#include <cstdlib>
 
 namespace axonn {
 
@@ -273,6 +274,377 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
   gemm_epilogue<EPI, TM, TN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, lane);
 }
 
+// ------------------------------------------------------------------------------------------
+// Large-problem kernel: 256 x 256 x 64 block tile, 4 waves (2 x 2), wave tile 128 x 128 held in
+// 256 accumulator registers, so that each byte read from LDS feeds twice the MFMA work of a
+// 128 x 64 wave tile.  One wave per SIMD: latency is hidden inside the wave by software
+// pipelining.  A k-step is four phases of 16 MFMAs (one 16-wide k slice each); the fragments of a
+// slice are read from LDS one phase ahead, tile kt+1 is written to the other LDS buffer during
+// phase 0, the fetch of tile kt+2 is issued during phase 1, and the single barrier of the step sits
+// after phase 2, so phase 3 already reads slice 0 of tile kt+1.
+// Tiles are fetched with buffer loads: an offset at or beyond the descriptor's size returns zeros
+// without touching memory, which covers rows outside the matrix, the k tail and the tiles past the
+// last one without branches or per-chunk pointers.
+constexpr uint32_t kOutOfRange = 0x80000000u;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
+  constexpr int BM = 256, BN = 256, BK = 64, CH = 8;   // CH: 16-byte chunks per thread, operand and tile
+  constexpr int TM = 4, TN = 4;
+  using LA = TileLayout<BM, BK, A_KC>;
+  using LB = TileLayout<BN, BK, B_KC>;
+  __shared__ __align__(16) bf16_t sA[2][LA::ELEMS];
+  __shared__ __align__(16) bf16_t sB[2][LB::ELEMS];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  int pid = blockIdx.x;
+  const int nblk = gridDim.x;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  constexpr int BAND = 8;
+  const int band_tiles = BAND * g.tiles_n;
+  const int band = pid / band_tiles, in_band = pid - band * band_tiles;
+  const int band_rows = min(BAND, g.tiles_m - band * BAND);
+  const int tm = band * BAND + in_band % band_rows, tn = in_band / band_rows;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  // Chunk j of this thread: byte offset v? + j * j? from the segment base, advanced by s? per k-step;
+  // it lands at element w? + j * WJ? of the LDS tile.
+  const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
+  uint32_t va, vb, ja, jb, sa, sb, nra, nrb;
+  int wa, wb, kca = 0, kcb = 0;
+  constexpr int WJA = A_KC ? 32 * LA::LD : 8 * LA::LD;
+  constexpr int WJB = B_KC ? 32 * LB::LD : 8 * LB::LD;
+  if (A_KC) {
+    const int row = tid >> 3, kc = tid & 7;
+    va = ((uint32_t)(m0 + row) * lda + kc * 8) * 2u; ja = 32u * lda * 2u; sa = BK * 2u;
+    wa = row * LA::LD + kc * 8; kca = kc * 8; nra = (uint32_t)g.M * lda * 2u;
+  } else {
+    const int kr = tid >> 5, rc = tid & 31;
+    va = (m0 + rc * 8 < g.M) ? ((uint32_t)kr * lda + m0 + rc * 8) * 2u : kOutOfRange;
+    ja = 8u * lda * 2u; sa = BK * lda * 2u;
+    wa = kr * LA::LD + rc * 8; nra = (uint32_t)g.K * lda * 2u;
+  }
+  if (B_KC) {
+    const int row = tid >> 3, kc = tid & 7;
+    vb = ((uint32_t)(n0 + row) * ldb + kc * 8) * 2u; jb = 32u * ldb * 2u; sb = BK * 2u;
+    wb = row * LB::LD + kc * 8; kcb = kc * 8; nrb = (uint32_t)g.N * ldb * 2u;
+  } else {
+    const int kr = tid >> 5, rc = tid & 31;
+    vb = (n0 + rc * 8 < g.N) ? ((uint32_t)kr * ldb + n0 + rc * 8) * 2u : kOutOfRange;
+    jb = 8u * ldb * 2u; sb = BK * ldb * 2u;
+    wb = kr * LB::LD + rc * 8; nrb = (uint32_t)g.K * ldb * 2u;
+  }
+  const int K = g.K;
+  const int tps = (K + BK - 1) / BK;      // k-tiles per segment
+  const int nk = tps * g.n_seg;
+  __amdgpu_buffer_rsrc_t rsa = make_rsrc(g.A_seg[0], nra), rsb = make_rsrc(g.B_seg[0], nrb);
+  u32x4 ra[CH], rb[CH];
+  int ld_seg = 0, ld_kin = 0;            // segment and k-tile within it of the NEXT tile to fetch
+
+  // Fetch of the next tile, split so that it can be interleaved with MFMAs: BEGIN computes the
+  // offsets, CHUNK(q) issues load q (0..7 operand A, 8..15 operand B), END advances to the next tile.
+  uint32_t xa, xb;
+#define AXONN_GLOAD_BEGIN()                                                                    \
+  {                                                                                            \
+    const bool live = ld_seg < g.n_seg;                                                        \
+    xa = ((live & (!A_KC | (ld_kin * BK + kca < K))) ? va : kOutOfRange) + (uint32_t)ld_kin * sa; \
+    xb = ((live & (!B_KC | (ld_kin * BK + kcb < K))) ? vb : kOutOfRange) + (uint32_t)ld_kin * sb; \
+  }
+#define AXONN_GLOAD_CHUNK(q)                                                                   \
+  if ((q) < CH) ra[(q) & 7] = __builtin_amdgcn_raw_buffer_load_b128(rsa, xa + ((q) & 7) * ja, 0, 0); \
+  else          rb[(q) & 7] = __builtin_amdgcn_raw_buffer_load_b128(rsb, xb + ((q) & 7) * jb, 0, 0);
+#define AXONN_GLOAD_END()                                                                      \
+  if (++ld_kin == tps) {                                                                       \
+    ld_kin = 0;                                                                                \
+    ++ld_seg;                                                                                  \
+    const int sidx = ld_seg < g.n_seg ? ld_seg : 0;                                            \
+    rsa = make_rsrc(g.A_seg[sidx], nra);                                                       \
+    rsb = make_rsrc(g.B_seg[sidx], nrb);                                                       \
+  }
+#define AXONN_SSTORE_CHUNK(buf, q)                                                             \
+  if ((q) < CH) *reinterpret_cast<u32x4*>(&sA[buf][wa + ((q) & 7) * WJA]) = ra[(q) & 7];       \
+  else          *reinterpret_cast<u32x4*>(&sB[buf][wb + ((q) & 7) * WJB]) = rb[(q) & 7];
+  // Fragment q of k slice kk of the tile in buffer buf -> fragment set F, in the order the MFMAs of
+  // the slice consume them: a0 b0 b1 b2 b3 a1 a2 a3.
+#define AXONN_FRAG(F, buf, kk, q)                                                              \
+  if ((q) == 0 || ((q) >= 5 && (q) < 8)) {                                                     \
+    const int i = (q) == 0 ? 0 : (q) - 4;                                                      \
+    const int r0 = wm * 128 + i * 32;                                                          \
+    fa[F][i] = A_KC ? frag_kcontig(sA[buf] + r0 * LA::LD + (kk) * 16, LA::LD, lane)            \
+                    : frag_kstrided<false>(sA[buf] + ((kk) * 16) * LA::LD + r0, LA::LD, lane); \
+  } else if ((q) < 5) {                                                                        \
+    const int j = (q) - 1;                                                                     \
+    const int r0 = wn * 128 + j * 32;                                                          \
+    fb[F][j] = B_KC ? frag_kcontig(sB[buf] + r0 * LB::LD + (kk) * 16, LB::LD, lane)            \
+                    : frag_kstrided<false>(sB[buf] + ((kk) * 16) * LB::LD + r0, LB::LD, lane); \
+  }
+  // One phase: the 16 MFMAs of the slice held in fragment set F.  After MFMA q (q < 8) the wave issues
+  // the read of fragment q of the next slice; after MFMAs 0,2,4,6 it writes chunk c0 + q/2 of the tile
+  // copy to LDS buffer wbuf, and after MFMAs 8,10,12,14 it reloads that chunk's registers with the same
+  // chunk of the tile one further ahead.  Every chunk is so in flight for one whole k-step, and the
+  // LDS writes are spread evenly over the phases.
+#define AXONN_PHASE(F, nbuf, nkk, wbuf, c0)                                                    \
+  _Pragma("unroll") for (int q = 0; q < 16; ++q) {                                             \
+    acc[q >> 2][q & 3] = mfma32(fb[F][q & 3], fa[F][q >> 2], acc[q >> 2][q & 3]);              \
+    AXONN_FRAG((F) ^ 1, nbuf, nkk, q)                                                          \
+    if (q < 8 && (q & 1) == 0) { AXONN_SSTORE_CHUNK(wbuf, (c0) + (q >> 1)) }                   \
+    if (q >= 8 && (q & 1) == 0) { AXONN_GLOAD_CHUNK((c0) + ((q - 8) >> 1)) }                   \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }
+  // One k-step on the tile kt in buffer CUR.  Phases 0-2 move chunks 4..15 of tile kt+1 from registers
+  // to the other buffer and fetch those chunks of tile kt+2; after the barrier every wave is done with
+  // buffer CUR, so phase 3 already stores chunks 0..3 of tile kt+2 there and fetches those of tile kt+3.
+#define AXONN_KSTEP(CUR)                                                                       \
+  AXONN_PHASE(0, CUR, 1, (CUR) ^ 1, 4)                                                         \
+  AXONN_PHASE(1, CUR, 2, (CUR) ^ 1, 8)                                                         \
+  AXONN_PHASE(0, CUR, 3, (CUR) ^ 1, 12)                                                        \
+  AXONN_GLOAD_END()                                                                            \
+  AXONN_GLOAD_BEGIN()                                                                          \
+  lds_barrier();                                                                               \
+  AXONN_PHASE(1, (CUR) ^ 1, 0, CUR, 0)
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  bf16x8 fa[2][TM], fb[2][TN];
+
+  // prologue: tile 0 in buffer 0; chunks 0..3 of tile 1 in buffer 1 and its other chunks in registers;
+  // chunks 0..3 of tile 2 on their way (tiles that do not exist read as zeros)
+  AXONN_GLOAD_BEGIN()
+#pragma unroll
+  for (int q = 0; q < 16; ++q) { AXONN_GLOAD_CHUNK(q) }
+  AXONN_GLOAD_END()
+#pragma unroll
+  for (int q = 0; q < 16; ++q) { AXONN_SSTORE_CHUNK(0, q) }
+  AXONN_GLOAD_BEGIN()
+#pragma unroll
+  for (int q = 0; q < 16; ++q) { AXONN_GLOAD_CHUNK(q) }
+  AXONN_GLOAD_END()
+#pragma unroll
+  for (int q = 0; q < 4; ++q) { AXONN_SSTORE_CHUNK(1, q) }
+  AXONN_GLOAD_BEGIN()
+#pragma unroll
+  for (int q = 0; q < 4; ++q) { AXONN_GLOAD_CHUNK(q) }
+  lds_barrier();
+#pragma unroll
+  for (int q = 0; q < 8; ++q) { AXONN_FRAG(0, 0, 0, q) }
+  // two k-steps per iteration so that the buffer index is a constant; an odd tile count is padded
+  // with a tile of zeros
+  for (int kt = 0; kt < nk; kt += 2) {
+    AXONN_KSTEP(0)
+    AXONN_KSTEP(1)
+  }
+#undef AXONN_GLOAD_BEGIN
+#undef AXONN_GLOAD_CHUNK
+#undef AXONN_GLOAD_END
+#undef AXONN_SSTORE_CHUNK
+#undef AXONN_FRAG
+#undef AXONN_PHASE
+#undef AXONN_KSTEP
+
+  gemm_epilogue<EPI, TM, TN>(acc, g, m0 + wm * 128, n0 + wn * 128, lane);
+}
+
+// ------------------------------------------------------------------------------------------
+// Large-problem kernel with asynchronous tile copies: same 256 x 256 block tile and 2 x 2 waves as
+// above, but the tiles go from global memory straight into LDS (buffer loads with the LDS bit: lane l
+// of a wave deposits its 16 bytes at M0 + 16*l), without passing through registers or LDS-store
+// instructions.  The k dimension advances in sub-tiles of 32 through a ring of four LDS stages; one
+// sub-tile is two phases of 16 MFMAs, with one barrier in between:
+//   phase A: MFMAs on k slice 0 of sub-tile t, LDS reads of slice 1;
+//   wait until this thread's copies of sub-tile t+1 have landed, barrier (now every wave has also
+//   finished reading stage t%4);
+//   phase B: MFMAs on slice 1, LDS reads of slice 0 of sub-tile t+1, and the copies of sub-tile t+4
+//   into stage t%4 are issued -- three sub-tiles of MFMA work ahead of their use.
+// Copies deposit 1 KiB per wave contiguously, so tiles cannot be padded; bank conflicts are avoided by
+// permuting the 16-byte chunks instead (which chunk a lane fetches is free):
+//   k-contiguous operand, stored [row][32 k] = 4 chunks per row: chunk c of row r sits at position
+//     c ^ ((r >> 1) & 3) -- 8 consecutive rows put the same c at 8 different 16-byte bank groups;
+//   k-strided operand, stored [k][256 rows] = 8 units of 64 bytes per k: unit u of row k sits at
+//     u ^ (k & 1), the same bank pattern as padding each k row by 64 bytes.
+__device__ __forceinline__ void lds_dma16(u32x4 rsrc, uint32_t voffset, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+               :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory");
+}
+
+__device__ __forceinline__ u32x4 make_rsrc_words(const void* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)p;
+  return u32x4{(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
+}
+
+template <bool A_KC, bool B_KC, int EPI>
+__global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
+  constexpr int BM = 256, BN = 256, BK = 32, NST = 4, TM = 4, TN = 4;
+  constexpr int OPB = 16384;                 // bytes of one operand's sub-tile
+  constexpr int STB = 2 * OPB;               // bytes of one stage (A then B)
+  __shared__ __align__(1024) char smem[NST * STB];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  int pid = blockIdx.x;
+  const int nblk = gridDim.x;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  constexpr int BAND = 8;
+  const int band_tiles = BAND * g.tiles_n;
+  const int band = pid / band_tiles, in_band = pid - band * band_tiles;
+  const int band_rows = min(BAND, g.tiles_m - band * BAND);
+  const int tm = band * BAND + in_band % band_rows, tn = in_band / band_rows;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  // ---- copy side.  Copy j (0..3) of a wave fills LDS bytes [(4j + wave) KiB, +1 KiB) of the operand's
+  // sub-tile; v? is this lane's byte offset from the segment base for j = 0, j? the stride in j, s? the
+  // advance per sub-tile.
+  const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
+  uint32_t va, vb, ja, jb, sa, sb, nra, nrb;
+  int kca = 0, kcb = 0;
+  if (A_KC) {
+    const int row = wave * 16 + (lane >> 2), c = (lane & 3) ^ ((lane >> 3) & 3);
+    va = ((uint32_t)(m0 + row) * lda + c * 8) * 2u; ja = 64u * lda * 2u; sa = BK * 2u;
+    kca = c * 8; nra = (uint32_t)g.M * lda * 2u;
+  } else {
+    const int kl = wave * 2 + (lane >> 5), c = (lane & 31) ^ ((lane >> 5) << 2);
+    va = (m0 + c * 8 < g.M) ? ((uint32_t)kl * lda + m0 + c * 8) * 2u : kOutOfRange;
+    ja = 8u * lda * 2u; sa = BK * lda * 2u; nra = (uint32_t)g.K * lda * 2u;
+  }
+  if (B_KC) {
+    const int row = wave * 16 + (lane >> 2), c = (lane & 3) ^ ((lane >> 3) & 3);
+    vb = ((uint32_t)(n0 + row) * ldb + c * 8) * 2u; jb = 64u * ldb * 2u; sb = BK * 2u;
+    kcb = c * 8; nrb = (uint32_t)g.N * ldb * 2u;
+  } else {
+    const int kl = wave * 2 + (lane >> 5), c = (lane & 31) ^ ((lane >> 5) << 2);
+    vb = (n0 + c * 8 < g.N) ? ((uint32_t)kl * ldb + n0 + c * 8) * 2u : kOutOfRange;
+    jb = 8u * ldb * 2u; sb = BK * ldb * 2u; nrb = (uint32_t)g.K * ldb * 2u;
+  }
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(AXONN_LDS char*)smem + (uint32_t)wave * 1024u;
+
+  // ---- fragment side: per-lane byte offsets inside an operand's sub-tile (two per operand; the
+  // rest of an address is a compile-time constant)
+  uint32_t fa0, fa1, fb0, fb1;
+  {
+    const int t = lane & 15, half = (lane >> 4) & 1, gq = lane >> 5, kq = t >> 2;
+    const uint32_t kc_lane = (uint32_t)(lane & 31) * 64u + (uint32_t)((gq ^ ((lane >> 1) & 3)) * 16);
+    const uint32_t ks_lane = (uint32_t)(8 * gq + kq) * 512u + (uint32_t)(16 * half + 4 * (t & 3)) * 2u;
+    const uint32_t swz = (uint32_t)(kq & 1) * 64u;
+    if (A_KC) { fa0 = (uint32_t)wm * 8192u + kc_lane; fa1 = fa0 ^ 32u; }
+    else      { fa0 = (uint32_t)wm * 256u + ks_lane + swz; fa1 = (uint32_t)wm * 256u + ks_lane + (64u ^ swz); }
+    if (B_KC) { fb0 = (uint32_t)wn * 8192u + kc_lane; fb1 = fb0 ^ 32u; }
+    else      { fb0 = (uint32_t)wn * 256u + ks_lane + swz; fb1 = (uint32_t)wn * 256u + ks_lane + (64u ^ swz); }
+  }
+
+  const int K = g.K;
+  const int tps = (K + BK - 1) / BK;      // sub-tiles per segment
+  const int nsub = tps * g.n_seg;
+  u32x4 rsa = make_rsrc_words(g.A_seg[0], nra), rsb = make_rsrc_words(g.B_seg[0], nrb);
+  int ld_seg = 0, ld_kin = 0;            // segment and sub-tile within it of the NEXT sub-tile to fetch
+  uint32_t xa, xb;
+
+#define AXONN_COPY_BEGIN()                                                                     \
+  {                                                                                            \
+    const bool live = ld_seg < g.n_seg;                                                        \
+    xa = ((live & (!A_KC | (ld_kin * BK + kca < K))) ? va : kOutOfRange) + (uint32_t)ld_kin * sa; \
+    xb = ((live & (!B_KC | (ld_kin * BK + kcb < K))) ? vb : kOutOfRange) + (uint32_t)ld_kin * sb; \
+  }
+  // copy q of the sub-tile (0..3 operand A, 4..7 operand B) into stage S
+#define AXONN_COPY_CHUNK(S, q)                                                                 \
+  if ((q) < 4) lds_dma16(rsa, xa + ((q) & 3) * ja, lds0 + (S) * STB + ((q) & 3) * 4096);       \
+  else         lds_dma16(rsb, xb + ((q) & 3) * jb, lds0 + (S) * STB + OPB + ((q) & 3) * 4096);
+#define AXONN_COPY_END()                                                                       \
+  if (++ld_kin == tps) {                                                                       \
+    ld_kin = 0;                                                                                \
+    ++ld_seg;                                                                                  \
+    const int sidx = ld_seg < g.n_seg ? ld_seg : 0;                                            \
+    rsa = make_rsrc_words(g.A_seg[sidx], nra);                                                 \
+    rsb = make_rsrc_words(g.B_seg[sidx], nrb);                                                 \
+  }
+  // Fragment q of k slice kk (0 or 1) of the sub-tile in stage S -> fragment set F, in the order the
+  // MFMAs of the slice consume them: a0 b0 b1 b2 b3 a1 a2 a3.
+#define AXONN_FRAG_LOAD(dst, KC, f0, f1, base, i, kk)                                          \
+  if (KC) {                                                                                    \
+    dst = *reinterpret_cast<const bf16x8*>(smem + (base) + (i) * 2048 + ((kk) ? f1 : f0));     \
+  } else {                                                                                     \
+    union { bf16x8 v; short4v h[2]; } u_;                                                      \
+    const char* p_ = smem + (base) + ((i) >> 1) * 128 + (kk) * 8192 + (((i) & 1) ? f1 : f0);   \
+    u_.h[0] = lds_read_tr16(reinterpret_cast<const bf16_t*>(p_));                              \
+    u_.h[1] = lds_read_tr16(reinterpret_cast<const bf16_t*>(p_ + 2048));                       \
+    dst = u_.v;                                                                                \
+  }
+#define AXONN_FRAG(F, S, kk, q)                                                                \
+  if ((q) == 0 || ((q) >= 5 && (q) < 8)) {                                                     \
+    const int i = (q) == 0 ? 0 : (q) - 4;                                                      \
+    AXONN_FRAG_LOAD(fa[F][i], A_KC, fa0, fa1, (S) * STB, i, kk)                                \
+  } else if ((q) < 5) {                                                                        \
+    const int j = (q) - 1;                                                                     \
+    AXONN_FRAG_LOAD(fb[F][j], B_KC, fb0, fb1, (S) * STB + OPB, j, kk)                          \
+  }
+#define AXONN_SUBTILE(S)                                                                       \
+  _Pragma("unroll") for (int q = 0; q < 16; ++q) {                                             \
+    acc[q >> 2][q & 3] = mfma32(fb[0][q & 3], fa[0][q >> 2], acc[q >> 2][q & 3]);              \
+    AXONN_FRAG(1, S, 1, q)                                                                     \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }                                                                                            \
+  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");                                            \
+  lds_barrier();                                                                               \
+  AXONN_COPY_BEGIN()                                                                           \
+  _Pragma("unroll") for (int q = 0; q < 16; ++q) {                                             \
+    acc[q >> 2][q & 3] = mfma32(fb[1][q & 3], fa[1][q >> 2], acc[q >> 2][q & 3]);              \
+    AXONN_FRAG(0, ((S) + 1) & 3, 0, q)                                                         \
+    if (q >= 8) { AXONN_COPY_CHUNK(S, q - 8) }                                                 \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }                                                                                            \
+  AXONN_COPY_END()
+
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  bf16x8 fa[2][TM], fb[2][TN];
+
+  // prologue: sub-tiles 0..3 on their way into stages 0..3 (sub-tiles that do not exist read as zeros)
+#pragma unroll
+  for (int st = 0; st < NST; ++st) {
+    AXONN_COPY_BEGIN()
+#pragma unroll
+    for (int q = 0; q < 8; ++q) { AXONN_COPY_CHUNK(st, q) }
+    AXONN_COPY_END()
+  }
+  asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+  lds_barrier();
+#pragma unroll
+  for (int q = 0; q < 8; ++q) { AXONN_FRAG(0, 0, 0, q) }
+  // four sub-tiles per iteration so that the stage index is a constant; the count is padded with
+  // sub-tiles of zeros
+  for (int t = 0; t < nsub; t += NST) {
+    AXONN_SUBTILE(0)
+    AXONN_SUBTILE(1)
+    AXONN_SUBTILE(2)
+    AXONN_SUBTILE(3)
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#undef AXONN_COPY_BEGIN
+#undef AXONN_COPY_CHUNK
+#undef AXONN_COPY_END
+#undef AXONN_FRAG_LOAD
+#undef AXONN_FRAG
+#undef AXONN_SUBTILE
+
+  gemm_epilogue<EPI, TM, TN>(acc, g, m0 + wm * 128, n0 + wn * 128, lane);
+}
+
 // Only the (layout, epilogue) pairs the layer uses are instantiated: forward maps take the
 // bias epilogues, input gradients the plain / GeLU' ones, weight gradients the accumulating ones.
 constexpr bool epilogue_allowed(bool a_kc, bool b_kc, int e) {
@@ -308,11 +680,64 @@ static hipError_t launch_cfg(int epi, GemmArgs g, hipStream_t s) {
   return hipGetLastError();
 }
 
+static bool use_dma_kernel() {
+  static const bool v = [] { const char* e = getenv("AXONN_GEMM_DMA"); return !(e && *e == '0'); }();
+  return v;
+}
+
+template <bool A_KC, bool B_KC>
+static hipError_t launch_big(int epi, GemmArgs g, hipStream_t s) {
+  g.tiles_m = (g.M + 255) / 256;
+  g.tiles_n = (g.N + 255) / 256;
+  const dim3 grid(g.tiles_m * g.tiles_n), block(256);
+#define AXONN_GEMM_CASE(E)                                                                      \
+  case E:                                                                                       \
+    if constexpr (epilogue_allowed(A_KC, B_KC, E)) {                                            \
+      if (use_dma_kernel())                                                                     \
+        hipLaunchKernelGGL((gemm_dma_kernel<A_KC, B_KC, E>), grid, block, 0, s, g);             \
+      else                                                                                      \
+        hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, E>), grid, block, 0, s, g);             \
+      break;                                                                                    \
+    } else {                                                                                    \
+      return hipErrorInvalidValue;                                                              \
+    }
+  switch (epi) {
+    AXONN_GEMM_CASE(EPI_BIAS)
+    AXONN_GEMM_CASE(EPI_BIAS_RES)
+    AXONN_GEMM_CASE(EPI_BIAS_GELU)
+    AXONN_GEMM_CASE(EPI_DGELU)
+    AXONN_GEMM_CASE(EPI_ACC_F32)
+    AXONN_GEMM_CASE(EPI_ACC_BF16)
+    default: return hipErrorInvalidValue;
+  }
+#undef AXONN_GEMM_CASE
+  return hipGetLastError();
+}
+
+// The large-problem kernel addresses an operand with 32-bit byte offsets from the segment base.
+static bool fits_32bit_offsets(int64_t rows, int64_t ld) {
+  return ld > 0 && (rows + 1024) * ld * 2 < (int64_t(1) << 31);
+}
+
+// Number of 256 x 256 tiles from which the large-problem kernel is used (half the CUs by default);
+// AXONN_GEMM_BIG_MIN_TILES overrides it, for tuning.
+static int64_t big_tile_threshold() {
+  static const int64_t v = [] {
+    const char* e = getenv("AXONN_GEMM_BIG_MIN_TILES");
+    return e && *e ? (int64_t)atoll(e) : (int64_t)128;
+  }();
+  return v;
+}
+
 template <bool A_KC, bool B_KC>
 static hipError_t launch_layout(int epi, const GemmArgs& g, hipStream_t s) {
   // Large tile when the problem fills the chip with it, smaller tile otherwise.
   const int64_t big_tiles = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);
-  if (big_tiles >= 128) return launch_cfg<256, 256, 64, 2, 4, A_KC, B_KC>(epi, g, s);
+  if (big_tiles >= big_tile_threshold()) {
+    if (fits_32bit_offsets(A_KC ? g.M : g.K, g.lda) && fits_32bit_offsets(B_KC ? g.N : g.K, g.ldb))
+      return launch_big<A_KC, B_KC>(epi, g, s);
+    return launch_cfg<256, 256, 64, 2, 4, A_KC, B_KC>(epi, g, s);
+  }
   return launch_cfg<128, 128, 64, 2, 2, A_KC, B_KC>(epi, g, s);
 }
 

@@ -29,6 +29,8 @@ GEMM_SHAPES = [
     (200, 136, 72),      # ragged in every dimension (multiples of 8 only)
     (8, 8, 8),           # degenerate minimum
     (264, 2056, 1032),   # ragged tails on a multi-tile problem
+    (2056, 4104, 264),   # big-tile kernel: ragged rows and columns, k tail, odd number of k-tiles
+    (4096, 2048, 448),   # big-tile kernel: odd number of k-tiles, no tail
 ]
 
 
@@ -88,6 +90,24 @@ def test_gemm_wgrad_layout_accumulate(M, N, K):
     assert rel_fro(first, ref) < TOL
     B.axonn_gemm_bf16(0, 0, B.EPI_ACC_BF16, M, N, K, a, M, b, N, c16, N, accumulate=1)
     assert rel_fro(host(c16), first + ref) < TOL
+
+
+def test_gemm_big_tile_strided_operands():
+    """The big-tile kernel with leading dimensions larger than the logical widths and a k tail: what lies
+    beyond K in a row of a k-contiguous operand must not enter the sum."""
+    import torch
+    rng = np.random.default_rng(6)
+    M, N, K = 2048, 4096, 200
+    for a_kc, b_kc, epi in ((1, 0, B.EPI_BIAS), (1, 1, B.EPI_BIAS), (0, 0, B.EPI_ACC_BF16)):
+        ash, bsh = ((M, K) if a_kc else (K, M)), ((N, K) if b_kc else (K, N))
+        lda, ldb, ldc = ash[1] + 72, bsh[1] + 136, N + 8
+        abuf = _rng_bf16(rng, (ash[0], lda)); bbuf = _rng_bf16(rng, (bsh[0], ldb), 0.05)
+        am, bm = abuf[:, :ash[1]].astype(np.float64), bbuf[:, :bsh[1]].astype(np.float64)
+        ref = (am if a_kc else am.T) @ (bm.T if b_kc else bm)
+        out = torch.zeros(M, ldc, dtype=torch.bfloat16, device="cuda")
+        B.axonn_gemm_bf16(a_kc, b_kc, epi, M, N, K, dev_bf16(abuf), lda, dev_bf16(bbuf), ldb, out, ldc)
+        assert rel_fro(host(out)[:, :N], ref) < TOL, (a_kc, b_kc)
+        assert not host(out)[:, N:].any()
 
 
 def test_gemm_strided_operands_and_run_to_run_determinism():
