@@ -27,6 +27,23 @@ __device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// v_mfma_f32_16x16x32_bf16 register layout:
+//   operand X (either input): lane l holds X[row = l%16][k = 8*(l/16) + i], i = 0..7
+//   result D[m][n]:           lane l, register r holds n = l%16, m = 4*(l/16) + r
+// Same work per cycle as the 32x32x16 form, but it draws less power per FLOP (less accumulator
+// traffic), which matters once the whole chip runs MFMAs and the clock is power-limited.
+__device__ __forceinline__ floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+// The same instruction with the accumulator pinned to the accumulation registers (a[...]): a kernel
+// whose 256 accumulators fill that file exactly needs every one of them there, and the register
+// allocator does not get this right by itself.  The compiler does not see an MFMA here, so the
+// caller keeps MFMA hazards itself: a few idle cycles between writing an accumulator with another
+// instruction and the first MFMA on it, and >= 18 between the last MFMA and reading the result.
+__device__ __forceinline__ void mfma16_acc(floatx4& c, bf16x8 a, bf16x8 b) {
+  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+
 // Fragment of a 32(row) x 16(k) operand block from an LDS tile stored [row][k] (k
 // contiguous, `ld` elements per row).  `base` points at (row0, k0).
 __device__ __forceinline__ bf16x8 frag_kcontig(const bf16_t* base, int ld, int lane) {
@@ -59,6 +76,19 @@ __device__ __forceinline__ bf16x8 frag_kstrided(const bf16_t* base, int ld, int 
   union { bf16x8 v; short4v h[2]; } u;
   u.h[0] = lds_read_tr16(base + (k_a + kq) * ld + r);
   u.h[1] = lds_read_tr16(base + (k_b + kq) * ld + r);
+  return u.v;
+}
+
+// The same two fragment readers for a 16(row) x 32(k) operand block of the 16x16x32 MFMA.
+__device__ __forceinline__ bf16x8 frag16_kcontig(const bf16_t* base, int ld, int lane) {
+  return *reinterpret_cast<const bf16x8*>(base + (lane & 15) * ld + 8 * (lane >> 4));
+}
+__device__ __forceinline__ bf16x8 frag16_kstrided(const bf16_t* base, int ld, int lane) {
+  const int t = lane & 15, g = lane >> 4;
+  const int kq = t >> 2, r = 4 * (t & 3);
+  union { bf16x8 v; short4v h[2]; } u;
+  u.h[0] = lds_read_tr16(base + (8 * g + kq) * ld + r);
+  u.h[1] = lds_read_tr16(base + (8 * g + 4 + kq) * ld + r);
   return u.v;
 }
 

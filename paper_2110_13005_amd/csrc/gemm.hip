@@ -39,8 +39,60 @@ struct TileLayout {
   static constexpr int ELEMS = KC ? ROWS * LD : BK * LD;
 };
 
-// Writes one wave's TM x TN result tiles.  The MFMA was issued with the B fragment first, so
-// lane l owns row m_base + 32*i + l%32 and register r of tile (i,j) is column
+// Epilogue of 4 consecutive columns n..n+3 of row m (both inside the matrix), v = the sums.
+template <int EPI>
+__device__ __forceinline__ void epilogue_run(float (&v)[4], const GemmArgs& g, int m, int n) {
+  if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
+    if (g.bias) {
+      const bf16x4 bv = *reinterpret_cast<const bf16x4*>(g.bias + n);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] += (float)bv[e];
+    }
+  }
+  if (EPI == EPI_BIAS_RES) {
+    const bf16x4 rv = *reinterpret_cast<const bf16x4*>(g.res + (int64_t)m * g.ld_res + n);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
+  }
+  if (EPI == EPI_BIAS_GELU) {
+    bf16x4 pv;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { pv[e] = (bf16_t)v[e]; v[e] = gelu_f(v[e]); }
+    *reinterpret_cast<bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n) = pv;
+  }
+  if (EPI == EPI_DGELU) {
+    const bf16x4 pv = *reinterpret_cast<const bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f((float)pv[e]);
+  }
+  if (EPI == EPI_ACC_F32) {
+    float* cp = reinterpret_cast<float*>(g.C) + (int64_t)m * g.ldc + n;
+    floatx4 o;
+    if (g.accumulate) {
+      o = *reinterpret_cast<const floatx4*>(cp);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] += v[e];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) o[e] = v[e];
+    }
+    *reinterpret_cast<floatx4*>(cp) = o;
+  } else {
+    bf16_t* cp = reinterpret_cast<bf16_t*>(g.C) + (int64_t)m * g.ldc + n;
+    if (EPI == EPI_ACC_BF16 && g.accumulate) {
+      const bf16x4 cv = *reinterpret_cast<const bf16x4*>(cp);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] += (float)cv[e];
+    }
+    bf16x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
+    *reinterpret_cast<bf16x4*>(cp) = o;
+  }
+}
+
+// Writes one wave's TM x TN result tiles of the 32x32x16 MFMA.  The MFMA was issued with the B
+// fragment first, so lane l owns row m_base + 32*i + l%32 and register r of tile (i,j) is column
 // n_base + 32*j + 8*(r/4) + 4*(l/32) + r%4: runs of 4 consecutive columns per lane.
 template <int EPI, int TM, int TN>
 __device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[TM][TN], const GemmArgs& g,
@@ -58,54 +110,29 @@ __device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[TM][TN], con
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-        if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
-          if (g.bias) {
-            const bf16x4 bv = *reinterpret_cast<const bf16x4*>(g.bias + n);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)bv[e];
-          }
-        }
-        if (EPI == EPI_BIAS_RES) {
-          const bf16x4 rv = *reinterpret_cast<const bf16x4*>(g.res + (int64_t)m * g.ld_res + n);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
-        }
-        if (EPI == EPI_BIAS_GELU) {
-          bf16x4 pv;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) { pv[e] = (bf16_t)v[e]; v[e] = gelu_f(v[e]); }
-          *reinterpret_cast<bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n) = pv;
-        }
-        if (EPI == EPI_DGELU) {
-          const bf16x4 pv = *reinterpret_cast<const bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f((float)pv[e]);
-        }
-        if (EPI == EPI_ACC_F32) {
-          float* cp = reinterpret_cast<float*>(g.C) + (int64_t)m * g.ldc + n;
-          floatx4 o;
-          if (g.accumulate) {
-            o = *reinterpret_cast<const floatx4*>(cp);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] += v[e];
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) o[e] = v[e];
-          }
-          *reinterpret_cast<floatx4*>(cp) = o;
-        } else {
-          bf16_t* cp = reinterpret_cast<bf16_t*>(g.C) + (int64_t)m * g.ldc + n;
-          if (EPI == EPI_ACC_BF16 && g.accumulate) {
-            const bf16x4 cv = *reinterpret_cast<const bf16x4*>(cp);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) v[e] += (float)cv[e];
-          }
-          bf16x4 o;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
-          *reinterpret_cast<bf16x4*>(cp) = o;
-        }
+        epilogue_run<EPI>(v, g, m, n);
       }
+    }
+  }
+}
+
+// The same for tiles of the 16x16x32 MFMA (B fragment first): lane l owns row m_base + 16*i + l%16
+// and the 4 registers of tile (i,j) are columns n_base + 16*j + 4*(l/16) + 0..3.
+template <int EPI, int TM, int TN>
+__device__ __forceinline__ void gemm_epilogue16(const floatx4 (&acc)[TM][TN], const GemmArgs& g,
+                                                int m_base, int n_base, int lane) {
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int m = m_base + i * 16 + (lane & 15);
+    if (m >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int n = n_base + j * 16 + 4 * (lane >> 4);
+      if (n >= g.N) continue;
+      float v[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e];
+      epilogue_run<EPI>(v, g, m, n);
     }
   }
 }
@@ -275,13 +302,13 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Large-problem kernel: 256 x 256 x 64 block tile, 4 waves (2 x 2), wave tile 128 x 128 held in
-// 256 accumulator registers, so that each byte read from LDS feeds twice the MFMA work of a
-// 128 x 64 wave tile.  One wave per SIMD: latency is hidden inside the wave by software
-// pipelining.  A k-step is four phases of 16 MFMAs (one 16-wide k slice each); the fragments of a
-// slice are read from LDS one phase ahead, tile kt+1 is written to the other LDS buffer during
-// phase 0, the fetch of tile kt+2 is issued during phase 1, and the single barrier of the step sits
-// after phase 2, so phase 3 already reads slice 0 of tile kt+1.
+// Large-problem kernel: 256 x 256 x 64 block tile, 4 waves (2 x 2), wave tile 128 x 128 = 8 x 8 tiles
+// of the 16x16x32 MFMA held in 256 accumulator registers, so that each byte read from LDS feeds
+// twice the MFMA work of a 128 x 64 wave tile.  One wave per SIMD: latency is hidden inside the wave
+// by software pipelining.  A k-step is two phases of 64 MFMAs (one 32-wide k slice each); the
+// fragments of a slice are read from LDS one phase ahead; the copy of the next tiles (registers ->
+// LDS, then the registers are reloaded from global memory) is spread evenly over the MFMAs of both
+// phases, and the single barrier of the step sits between them.
 // Tiles are fetched with buffer loads: an offset at or beyond the descriptor's size returns zeros
 // without touching memory, which covers rows outside the matrix, the k tail and the tiles past the
 // last one without branches or per-chunk pointers.
@@ -294,7 +321,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 template <bool A_KC, bool B_KC, int EPI>
 __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
   constexpr int BM = 256, BN = 256, BK = 64, CH = 8;   // CH: 16-byte chunks per thread, operand and tile
-  constexpr int TM = 4, TN = 4;
+  constexpr int TM = 8, TN = 8;
   using LA = TileLayout<BM, BK, A_KC>;
   using LB = TileLayout<BN, BK, B_KC>;
   __shared__ __align__(16) bf16_t sA[2][LA::ELEMS];
@@ -370,56 +397,68 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
 #define AXONN_SSTORE_CHUNK(buf, q)                                                             \
   if ((q) < CH) *reinterpret_cast<u32x4*>(&sA[buf][wa + ((q) & 7) * WJA]) = ra[(q) & 7];       \
   else          *reinterpret_cast<u32x4*>(&sB[buf][wb + ((q) & 7) * WJB]) = rb[(q) & 7];
-  // Fragment q of k slice kk of the tile in buffer buf -> fragment set F, in the order the MFMAs of
-  // the slice consume them: a0 b0 b1 b2 b3 a1 a2 a3.
+  // Fragment q (0..15) of k slice kk (0 or 1) of the tile in buffer buf -> fragment set F, in the
+  // order the MFMAs of the slice consume them: a0 b0..b7 a1..a7.
 #define AXONN_FRAG(F, buf, kk, q)                                                              \
-  if ((q) == 0 || ((q) >= 5 && (q) < 8)) {                                                     \
-    const int i = (q) == 0 ? 0 : (q) - 4;                                                      \
-    const int r0 = wm * 128 + i * 32;                                                          \
-    fa[F][i] = A_KC ? frag_kcontig(sA[buf] + r0 * LA::LD + (kk) * 16, LA::LD, lane)            \
-                    : frag_kstrided<false>(sA[buf] + ((kk) * 16) * LA::LD + r0, LA::LD, lane); \
-  } else if ((q) < 5) {                                                                        \
+  if ((q) == 0 || (q) > 8) {                                                                   \
+    const int i = (q) == 0 ? 0 : (q) - 8;                                                      \
+    const int r0 = wm * 128 + i * 16;                                                          \
+    fa[F][i] = A_KC ? frag16_kcontig(sA[buf] + r0 * LA::LD + (kk) * 32, LA::LD, lane)          \
+                    : frag16_kstrided(sA[buf] + ((kk) * 32) * LA::LD + r0, LA::LD, lane);      \
+  } else {                                                                                     \
     const int j = (q) - 1;                                                                     \
-    const int r0 = wn * 128 + j * 32;                                                          \
-    fb[F][j] = B_KC ? frag_kcontig(sB[buf] + r0 * LB::LD + (kk) * 16, LB::LD, lane)            \
-                    : frag_kstrided<false>(sB[buf] + ((kk) * 16) * LB::LD + r0, LB::LD, lane); \
+    const int r0 = wn * 128 + j * 16;                                                          \
+    fb[F][j] = B_KC ? frag16_kcontig(sB[buf] + r0 * LB::LD + (kk) * 32, LB::LD, lane)          \
+                    : frag16_kstrided(sB[buf] + ((kk) * 32) * LB::LD + r0, LB::LD, lane);      \
   }
-  // One phase: the 16 MFMAs of the slice held in fragment set F.  After MFMA q (q < 8) the wave issues
-  // the read of fragment q of the next slice; after MFMAs 0,2,4,6 it writes chunk c0 + q/2 of the tile
-  // copy to LDS buffer wbuf, and after MFMAs 8,10,12,14 it reloads that chunk's registers with the same
-  // chunk of the tile one further ahead.  Every chunk is so in flight for one whole k-step, and the
-  // LDS writes are spread evenly over the phases.
-#define AXONN_PHASE(F, nbuf, nkk, wbuf, c0)                                                    \
-  _Pragma("unroll") for (int q = 0; q < 16; ++q) {                                             \
-    acc[q >> 2][q & 3] = mfma32(fb[F][q & 3], fa[F][q >> 2], acc[q >> 2][q & 3]);              \
-    AXONN_FRAG((F) ^ 1, nbuf, nkk, q)                                                          \
-    if (q < 8 && (q & 1) == 0) { AXONN_SSTORE_CHUNK(wbuf, (c0) + (q >> 1)) }                   \
-    if (q >= 8 && (q & 1) == 0) { AXONN_GLOAD_CHUNK((c0) + ((q - 8) >> 1)) }                   \
-    __builtin_amdgcn_sched_barrier(0);                                                         \
-  }
-  // One k-step on the tile kt in buffer CUR.  Phases 0-2 move chunks 4..15 of tile kt+1 from registers
-  // to the other buffer and fetch those chunks of tile kt+2; after the barrier every wave is done with
-  // buffer CUR, so phase 3 already stores chunks 0..3 of tile kt+2 there and fetches those of tile kt+3.
+  // One k-step on the tile kt in buffer CUR: two phases of 64 MFMAs (k slices 0 and 1), between which
+  // the other memory instructions are spread as evenly as their dependences allow, so that neither the
+  // LDS nor the issue port sees bursts:
+  //   phase 0: fragment reads of slice 1 (one every 4 MFMAs); chunks 8..15 of tile kt+1 go from
+  //            registers to buffer CUR^1 (first half), then their registers are reloaded with those
+  //            chunks of tile kt+2 (second half);
+  //   barrier after MFMA 5 of phase 1: by then all of the above has completed, every wave is done with
+  //            buffer CUR and tile kt+1 is complete in buffer CUR^1;
+  //   phase 1: fragment reads of slice 0 of tile kt+1; chunks 0..7 of tile kt+2 go to buffer CUR and
+  //            are reloaded with those of tile kt+3.
+  // Every chunk is so in flight for one whole k-step.
+#define AXONN_MFMA(F, q) mfma16_acc(acc[(q) >> 3][(q) & 7], fb[F][(q) & 7], fa[F][(q) >> 3]);
 #define AXONN_KSTEP(CUR)                                                                       \
-  AXONN_PHASE(0, CUR, 1, (CUR) ^ 1, 4)                                                         \
-  AXONN_PHASE(1, CUR, 2, (CUR) ^ 1, 8)                                                         \
-  AXONN_PHASE(0, CUR, 3, (CUR) ^ 1, 12)                                                        \
+  _Pragma("unroll") for (int q = 0; q < 64; ++q) {                                             \
+    AXONN_MFMA(0, q)                                                                           \
+    if ((q & 3) == 0) { AXONN_FRAG(1, CUR, 1, q >> 2) }                                        \
+    if (q < 32 && (q & 3) == 2) { AXONN_SSTORE_CHUNK((CUR) ^ 1, 8 + (q >> 2)) }                \
+    if (q >= 32 && (q & 3) == 2) { AXONN_GLOAD_CHUNK(8 + ((q - 32) >> 2)) }                    \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }                                                                                            \
   AXONN_GLOAD_END()                                                                            \
   AXONN_GLOAD_BEGIN()                                                                          \
+  _Pragma("unroll") for (int q = 0; q < 6; ++q) {                                              \
+    AXONN_MFMA(1, q)                                                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }                                                                                            \
   lds_barrier();                                                                               \
-  AXONN_PHASE(1, (CUR) ^ 1, 0, CUR, 0)
+  _Pragma("unroll") for (int q = 6; q < 64; ++q) {                                             \
+    AXONN_MFMA(1, q)                                                                           \
+    /* fragment f at MFMA 8 + 3f + f/2 (f = 0..15), chunk c stored at 10 + 6c, reloaded at 13 + 6c */ \
+    if (q >= 8 && (q - 8) % 7 == 0) { AXONN_FRAG(0, (CUR) ^ 1, 0, 2 * ((q - 8) / 7)) }         \
+    if (q >= 8 && (q - 8) % 7 == 3) { AXONN_FRAG(0, (CUR) ^ 1, 0, 2 * ((q - 8) / 7) + 1) }     \
+    if (q >= 10 && (q - 10) % 6 == 0 && (q - 10) / 6 < 8) { AXONN_SSTORE_CHUNK(CUR, (q - 10) / 6) } \
+    if (q >= 13 && (q - 13) % 6 == 0 && (q - 13) / 6 < 8) { AXONN_GLOAD_CHUNK((q - 13) / 6) }  \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }
 
-  floatx16 acc[TM][TN];
+  floatx4 acc[TM][TN];
 #pragma unroll
   for (int i = 0; i < TM; ++i)
 #pragma unroll
     for (int j = 0; j < TN; ++j)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
   bf16x8 fa[2][TM], fb[2][TN];
 
-  // prologue: tile 0 in buffer 0; chunks 0..3 of tile 1 in buffer 1 and its other chunks in registers;
-  // chunks 0..3 of tile 2 on their way (tiles that do not exist read as zeros)
+  // prologue: tile 0 in buffer 0; chunks 0..7 of tile 1 in buffer 1 and its other chunks in registers;
+  // chunks 0..7 of tile 2 on their way (tiles that do not exist read as zeros)
   AXONN_GLOAD_BEGIN()
 #pragma unroll
   for (int q = 0; q < 16; ++q) { AXONN_GLOAD_CHUNK(q) }
@@ -431,28 +470,30 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
   for (int q = 0; q < 16; ++q) { AXONN_GLOAD_CHUNK(q) }
   AXONN_GLOAD_END()
 #pragma unroll
-  for (int q = 0; q < 4; ++q) { AXONN_SSTORE_CHUNK(1, q) }
+  for (int q = 0; q < 8; ++q) { AXONN_SSTORE_CHUNK(1, q) }
   AXONN_GLOAD_BEGIN()
 #pragma unroll
-  for (int q = 0; q < 4; ++q) { AXONN_GLOAD_CHUNK(q) }
+  for (int q = 0; q < 8; ++q) { AXONN_GLOAD_CHUNK(q) }
   lds_barrier();
 #pragma unroll
-  for (int q = 0; q < 8; ++q) { AXONN_FRAG(0, 0, 0, q) }
+  for (int q = 0; q < 16; ++q) { AXONN_FRAG(0, 0, 0, q) }
+  asm volatile("s_nop 7" ::: "memory");      // accumulators were just zeroed: settle before the first MFMA
   // two k-steps per iteration so that the buffer index is a constant; an odd tile count is padded
   // with a tile of zeros
   for (int kt = 0; kt < nk; kt += 2) {
     AXONN_KSTEP(0)
     AXONN_KSTEP(1)
   }
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // last MFMAs drain before the results are read
 #undef AXONN_GLOAD_BEGIN
 #undef AXONN_GLOAD_CHUNK
 #undef AXONN_GLOAD_END
 #undef AXONN_SSTORE_CHUNK
 #undef AXONN_FRAG
-#undef AXONN_PHASE
+#undef AXONN_MFMA
 #undef AXONN_KSTEP
 
-  gemm_epilogue<EPI, TM, TN>(acc, g, m0 + wm * 128, n0 + wn * 128, lane);
+  gemm_epilogue16<EPI, TM, TN>(acc, g, m0 + wm * 128, n0 + wn * 128, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -681,7 +722,7 @@ static hipError_t launch_cfg(int epi, GemmArgs g, hipStream_t s) {
 }
 
 static bool use_dma_kernel() {
-  static const bool v = [] { const char* e = getenv("AXONN_GEMM_DMA"); return !(e && *e == '0'); }();
+  static const bool v = [] { const char* e = getenv("AXONN_GEMM_DMA"); return e && *e == '1'; }();
   return v;
 }
 
