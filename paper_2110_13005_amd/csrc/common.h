@@ -143,14 +143,15 @@ hipError_t launch_gemm(bool a_kc, bool b_kc, int epilogue, const GemmArgs& g, hi
 hipError_t launch_layernorm_fwd(int64_t T, int64_t h, const void* x, const void* gamma,
                                 const void* beta, float eps, void* out, void* out_lo, float* stats,
                                 hipStream_t s);
+// dgamma / dbeta and the column sums of launch_colsum go to `out` vectors: acc_mode 0 stores fp32
+// sums; acc_mode 1 stores and acc_mode 2 adds to vectors of the gradient accumulation type (fp32 if
+// dst_fp32, else bf16).
 hipError_t launch_layernorm_bwd(int64_t T, int64_t h, const void* dout, const void* x,
                                 const float* stats, const void* gamma, const void* res_grad,
-                                void* dx, float* dgamma, float* dbeta, float* ws, hipStream_t s);
-hipError_t launch_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, float* out,
-                         float* ws, hipStream_t s);
-// dst[i] (+)= src[i] for small fp32 vectors -> bf16 or fp32 gradient accumulators.
-hipError_t launch_accum_vec(int64_t n, const float* src, void* dst, bool dst_fp32,
-                            bool accumulate, hipStream_t s);
+                                void* dx, void* dgamma, void* dbeta, int acc_mode, bool dst_fp32,
+                                float* ws, hipStream_t s);
+hipError_t launch_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, void* out, int acc_mode,
+                         bool dst_fp32, float* ws, hipStream_t s);
 hipError_t launch_f32_to_bf16(uint64_t n, const float* src, void* dst, hipStream_t s);
 hipError_t launch_fill_bf16(uint64_t n, void* dst, float value, hipStream_t s);
 hipError_t launch_attention_fwd(int b, int s, int a, int d, const void* qkv, void* o,

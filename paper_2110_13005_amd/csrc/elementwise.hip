@@ -6,37 +6,49 @@
 
 namespace axonn {
 
-// One wavefront per row: the row lives in registers (MAXC chunks of 8 bf16 per lane), so the
-// mean and the variance are the plain two-pass definitions computed from one HBM read.
-constexpr int LN_MAXC = 32;  // 32 chunks * 64 lanes * 8 = 16384 columns max
-constexpr int LN_ROWS_PER_BLOCK = 4;
+// One workgroup of 4 wavefronts per row: the row lives in registers (MAXC chunks of 8 bf16 per
+// lane, chunk c of thread t is chunk c*256 + t of the row), so the mean and the variance are the
+// plain two-pass definitions computed from one HBM read; the four wavefront sums are combined
+// through LDS in a fixed order.  MAXC is the smallest power of two that covers the row, so that a
+// thread holds few registers and many rows are in flight per CU.
+constexpr int LN_THREADS = 256;
+constexpr int LN_MAX_COLS = 16 * LN_THREADS * 8;   // 32768
 
-__global__ __launch_bounds__(64 * LN_ROWS_PER_BLOCK) void layernorm_fwd_kernel(
+__device__ __forceinline__ float block_sum4(float v, float (&red)[4], int lane, int wave) {
+  v = wave_sum(v);
+  __syncthreads();                 // previous use of red[] is over
+  if (lane == 0) red[wave] = v;
+  __syncthreads();
+  return ((red[0] + red[1]) + red[2]) + red[3];
+}
+
+template <int MAXC>
+__global__ __launch_bounds__(LN_THREADS) void layernorm_fwd_kernel(
     int T, int h, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
     const bf16_t* __restrict__ beta, float eps, bf16_t* __restrict__ out,
     bf16_t* __restrict__ out_lo, float* __restrict__ stats) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * LN_ROWS_PER_BLOCK + (threadIdx.x >> 6);
-  if (row >= T) return;
+  __shared__ float red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = blockIdx.x;
   const int nch = h >> 3;
   const bf16_t* xr = x + (int64_t)row * h;
-  bf16x8 v[LN_MAXC];
+  bf16x8 v[MAXC];
   float sum = 0.f;
 #pragma unroll
-  for (int c = 0; c < LN_MAXC; ++c) {
-    const int ch = c * 64 + lane;
-    if (c * 64 < nch && ch < nch) {
+  for (int c = 0; c < MAXC; ++c) {
+    const int ch = c * LN_THREADS + tid;
+    if (ch < nch) {
       v[c] = *reinterpret_cast<const bf16x8*>(xr + ch * 8);
 #pragma unroll
       for (int e = 0; e < 8; ++e) sum += (float)v[c][e];
     }
   }
-  const float mean = wave_sum(sum) / (float)h;
+  const float mean = block_sum4(sum, red, lane, wave) / (float)h;
   float sq = 0.f;
 #pragma unroll
-  for (int c = 0; c < LN_MAXC; ++c) {
-    const int ch = c * 64 + lane;
-    if (c * 64 < nch && ch < nch) {
+  for (int c = 0; c < MAXC; ++c) {
+    const int ch = c * LN_THREADS + tid;
+    if (ch < nch) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float d = (float)v[c][e] - mean;
@@ -44,16 +56,16 @@ __global__ __launch_bounds__(64 * LN_ROWS_PER_BLOCK) void layernorm_fwd_kernel(
       }
     }
   }
-  const float rstd = rsqrtf(wave_sum(sq) / (float)h + eps);
-  if (lane == 0) {
+  const float rstd = rsqrtf(block_sum4(sq, red, lane, wave) / (float)h + eps);
+  if (tid == 0) {
     stats[2 * (int64_t)row] = mean;
     stats[2 * (int64_t)row + 1] = rstd;
   }
   bf16_t* orow = out + (int64_t)row * h;
 #pragma unroll
-  for (int c = 0; c < LN_MAXC; ++c) {
-    const int ch = c * 64 + lane;
-    if (c * 64 < nch && ch < nch) {
+  for (int c = 0; c < MAXC; ++c) {
+    const int ch = c * LN_THREADS + tid;
+    if (ch < nch) {
       const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gamma + ch * 8);
       const bf16x8 bv = *reinterpret_cast<const bf16x8*>(beta + ch * 8);
       bf16x8 o, lo;
@@ -70,23 +82,24 @@ __global__ __launch_bounds__(64 * LN_ROWS_PER_BLOCK) void layernorm_fwd_kernel(
 }
 
 // dx = res + rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)),  dxhat = dout * gamma
-__global__ __launch_bounds__(64 * LN_ROWS_PER_BLOCK) void layernorm_bwd_dx_kernel(
+template <int MAXC>
+__global__ __launch_bounds__(LN_THREADS) void layernorm_bwd_dx_kernel(
     int T, int h, const bf16_t* __restrict__ dout, const bf16_t* __restrict__ x,
     const float* __restrict__ stats, const bf16_t* __restrict__ gamma,
     const bf16_t* __restrict__ res, bf16_t* __restrict__ dx) {
-  const int lane = threadIdx.x & 63;
-  const int row = blockIdx.x * LN_ROWS_PER_BLOCK + (threadIdx.x >> 6);
-  if (row >= T) return;
+  __shared__ float red[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int row = blockIdx.x;
   const int nch = h >> 3;
   const float mean = stats[2 * (int64_t)row], rstd = stats[2 * (int64_t)row + 1];
   const bf16_t* xr = x + (int64_t)row * h;
   const bf16_t* dr = dout + (int64_t)row * h;
-  bf16x8 xv[LN_MAXC], dv[LN_MAXC];
+  bf16x8 xv[MAXC], dv[MAXC];
   float s1 = 0.f, s2 = 0.f;
 #pragma unroll
-  for (int c = 0; c < LN_MAXC; ++c) {
-    const int ch = c * 64 + lane;
-    if (c * 64 < nch && ch < nch) {
+  for (int c = 0; c < MAXC; ++c) {
+    const int ch = c * LN_THREADS + tid;
+    if (ch < nch) {
       xv[c] = *reinterpret_cast<const bf16x8*>(xr + ch * 8);
       dv[c] = *reinterpret_cast<const bf16x8*>(dr + ch * 8);
       const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gamma + ch * 8);
@@ -99,12 +112,13 @@ __global__ __launch_bounds__(64 * LN_ROWS_PER_BLOCK) void layernorm_bwd_dx_kerne
       }
     }
   }
-  const float m1 = wave_sum(s1) / (float)h, m2 = wave_sum(s2) / (float)h;
+  const float m1 = block_sum4(s1, red, lane, wave) / (float)h;
+  const float m2 = block_sum4(s2, red, lane, wave) / (float)h;
   bf16_t* orow = dx + (int64_t)row * h;
 #pragma unroll
-  for (int c = 0; c < LN_MAXC; ++c) {
-    const int ch = c * 64 + lane;
-    if (c * 64 < nch && ch < nch) {
+  for (int c = 0; c < MAXC; ++c) {
+    const int ch = c * LN_THREADS + tid;
+    if (ch < nch) {
       const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gamma + ch * 8);
       bf16x8 rv;
       if (res) rv = *reinterpret_cast<const bf16x8*>(res + (int64_t)row * h + ch * 8);
@@ -181,12 +195,19 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(
   }
 }
 
-// out[k][n] = sum over row blocks of partial[rb][k][n], k < KSUM.
+// out[k][n] = sum over row blocks of partial[rb][k][n], k < KSUM.  The sums are either stored as
+// fp32 (acc_mode 0), or stored into / added to gradient vectors of the accumulation type
+// (acc_mode 1 / 2; dst_fp32 says whether that type is fp32 or bf16).
+template <typename T>
+__device__ __forceinline__ void put_sum(T* dst, int n, float v, int acc_mode) {
+  dst[n] = (T)((acc_mode == 2 ? (float)dst[n] : 0.f) + v);
+}
 template <int KSUM>
 __global__ __launch_bounds__(256) void colsum_final_kernel(int nrb, int N,
                                                            const float* __restrict__ partial,
-                                                           float* __restrict__ out0,
-                                                           float* __restrict__ out1) {
+                                                           void* __restrict__ out0,
+                                                           void* __restrict__ out1,
+                                                           int acc_mode, int dst_fp32) {
   const int n = blockIdx.x * 256 + threadIdx.x;
   if (n >= N) return;
   float s0 = 0.f, s1 = 0.f;
@@ -194,21 +215,12 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(int nrb, int N,
     s0 += partial[((int64_t)rb * KSUM) * N + n];
     if (KSUM == 2) s1 += partial[((int64_t)rb * KSUM + 1) * N + n];
   }
-  out0[n] = s0;
-  if (KSUM == 2) out1[n] = s1;
-}
-
-__global__ __launch_bounds__(256) void accum_vec_kernel(int64_t n, const float* __restrict__ src,
-                                                        void* __restrict__ dst, int dst_fp32,
-                                                        int accumulate) {
-  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n) return;
-  if (dst_fp32) {
-    float* d = reinterpret_cast<float*>(dst);
-    d[i] = (accumulate ? d[i] : 0.f) + src[i];
+  if (acc_mode == 0 || dst_fp32) {
+    put_sum(reinterpret_cast<float*>(out0), n, s0, acc_mode);
+    if (KSUM == 2) put_sum(reinterpret_cast<float*>(out1), n, s1, acc_mode);
   } else {
-    bf16_t* d = reinterpret_cast<bf16_t*>(dst);
-    d[i] = (bf16_t)((accumulate ? (float)d[i] : 0.f) + src[i]);
+    put_sum(reinterpret_cast<bf16_t*>(out0), n, s0, acc_mode);
+    if (KSUM == 2) put_sum(reinterpret_cast<bf16_t*>(out1), n, s1, acc_mode);
   }
 }
 
@@ -285,23 +297,33 @@ __global__ __launch_bounds__(256) void adam_kernel(uint64_t n8, uint64_t n, floa
 }
 
 // ------------------------------------------------------------------------- launchers
+#define AXONN_LN_DISPATCH(KERNEL, ...)                                                        \
+  {                                                                                           \
+    const dim3 grid((unsigned)T), block(LN_THREADS);                                          \
+    const int64_t per_thread = (h + LN_THREADS * 8 - 1) / (LN_THREADS * 8);                   \
+    if (per_thread <= 1) hipLaunchKernelGGL(KERNEL<1>, grid, block, 0, s, __VA_ARGS__);       \
+    else if (per_thread <= 2) hipLaunchKernelGGL(KERNEL<2>, grid, block, 0, s, __VA_ARGS__);  \
+    else if (per_thread <= 4) hipLaunchKernelGGL(KERNEL<4>, grid, block, 0, s, __VA_ARGS__);  \
+    else if (per_thread <= 8) hipLaunchKernelGGL(KERNEL<8>, grid, block, 0, s, __VA_ARGS__);  \
+    else hipLaunchKernelGGL(KERNEL<16>, grid, block, 0, s, __VA_ARGS__);                      \
+  }
+
 hipError_t launch_layernorm_fwd(int64_t T, int64_t h, const void* x, const void* gamma,
                                 const void* beta, float eps, void* out, void* out_lo, float* stats,
                                 hipStream_t s) {
-  const dim3 grid((unsigned)((T + LN_ROWS_PER_BLOCK - 1) / LN_ROWS_PER_BLOCK));
-  hipLaunchKernelGGL(layernorm_fwd_kernel, grid, dim3(64 * LN_ROWS_PER_BLOCK), 0, s, (int)T, (int)h,
-                     (const bf16_t*)x, (const bf16_t*)gamma, (const bf16_t*)beta, eps,
-                     (bf16_t*)out, (bf16_t*)out_lo, stats);
+  if (h > LN_MAX_COLS || T <= 0) return hipErrorInvalidValue;
+  AXONN_LN_DISPATCH(layernorm_fwd_kernel, (int)T, (int)h, (const bf16_t*)x, (const bf16_t*)gamma,
+                    (const bf16_t*)beta, eps, (bf16_t*)out, (bf16_t*)out_lo, stats)
   return hipGetLastError();
 }
 
 hipError_t launch_layernorm_bwd(int64_t T, int64_t h, const void* dout, const void* x,
                                 const float* stats, const void* gamma, const void* res_grad,
-                                void* dx, float* dgamma, float* dbeta, float* ws, hipStream_t s) {
-  const dim3 grid((unsigned)((T + LN_ROWS_PER_BLOCK - 1) / LN_ROWS_PER_BLOCK));
-  hipLaunchKernelGGL(layernorm_bwd_dx_kernel, grid, dim3(64 * LN_ROWS_PER_BLOCK), 0, s, (int)T,
-                     (int)h, (const bf16_t*)dout, (const bf16_t*)x, stats, (const bf16_t*)gamma,
-                     (const bf16_t*)res_grad, (bf16_t*)dx);
+                                void* dx, void* dgamma, void* dbeta, int acc_mode, bool dst_fp32,
+                                float* ws, hipStream_t s) {
+  if (h > LN_MAX_COLS || T <= 0) return hipErrorInvalidValue;
+  AXONN_LN_DISPATCH(layernorm_bwd_dx_kernel, (int)T, (int)h, (const bf16_t*)dout, (const bf16_t*)x,
+                    stats, (const bf16_t*)gamma, (const bf16_t*)res_grad, (bf16_t*)dx)
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int nrb = (int)((T + CS_ROWS - 1) / CS_ROWS);
@@ -311,12 +333,13 @@ hipError_t launch_layernorm_bwd(int64_t T, int64_t h, const void* dout, const vo
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_final_kernel<2>, dim3((unsigned)((h + 255) / 256)), dim3(256), 0, s, nrb,
-                     (int)h, (const float*)ws, dbeta, dgamma);
+                     (int)h, (const float*)ws, dbeta, dgamma, acc_mode, dst_fp32 ? 1 : 0);
   return hipGetLastError();
 }
+#undef AXONN_LN_DISPATCH
 
-hipError_t launch_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, float* out, float* ws,
-                         hipStream_t s) {
+hipError_t launch_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, void* out, int acc_mode,
+                         bool dst_fp32, float* ws, hipStream_t s) {
   const int nrb = (int)((T + CS_ROWS - 1) / CS_ROWS);
   const dim3 g2((unsigned)((N + 511) / 512), (unsigned)nrb);
   hipLaunchKernelGGL(colsum_partial_kernel<0>, g2, dim3(256), 0, s, (int)T, (int)N,
@@ -324,14 +347,7 @@ hipError_t launch_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, float
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_final_kernel<1>, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, nrb,
-                     (int)N, (const float*)ws, out, (float*)nullptr);
-  return hipGetLastError();
-}
-
-hipError_t launch_accum_vec(int64_t n, const float* src, void* dst, bool dst_fp32, bool accumulate,
-                            hipStream_t s) {
-  hipLaunchKernelGGL(accum_vec_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, n, src,
-                     dst, dst_fp32 ? 1 : 0, accumulate ? 1 : 0);
+                     (int)N, (const float*)ws, out, (void*)nullptr, acc_mode, dst_fp32 ? 1 : 0);
   return hipGetLastError();
 }
 

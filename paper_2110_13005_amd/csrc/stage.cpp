@@ -49,10 +49,10 @@ int fail(int code, const char* fmt, ...) {
 
 // ---- optional per-launch timing: event pairs around every kernel launch, by category ----
 enum ProfCat { PC_GEMM_FWD, PC_GEMM_DGRAD, PC_GEMM_WGRAD, PC_ATTN_FWD, PC_ATTN_BWD, PC_LN_FWD,
-               PC_LN_BWD, PC_COLSUM, PC_ACCUM_VEC, PC_GRAD_CONVERT, PC_ADAM, PC_COPY_IN, PC_COUNT };
+               PC_LN_BWD, PC_COLSUM, PC_GRAD_CONVERT, PC_ADAM, PC_COPY_IN, PC_COUNT };
 const char* const kProfNames[PC_COUNT] = {
     "gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attention_fwd", "attention_bwd", "layernorm_fwd",
-    "layernorm_bwd", "colsum", "accum_vec", "grad_convert", "adam", "copy_in"};
+    "layernorm_bwd", "colsum", "grad_convert", "adam", "copy_in"};
 struct ProfRec { int cat; hipEvent_t a, b; };
 bool g_prof_on = false;
 std::vector<ProfRec> g_prof_recs;
@@ -151,7 +151,7 @@ struct axonn_stage {
   char* ws_base = nullptr;
   uint64_t ws_bytes = 0;
   bf16_t *dw = nullptr, *dattn = nullptr, *du = nullptr;
-  float *delta = nullptr, *red_ws = nullptr, *vec0 = nullptr, *vec1 = nullptr;
+  float *delta = nullptr, *red_ws = nullptr;
   // state
   int in_flight = 0;
   int bwd_count = 0;  // backwards since the last zero_grad
@@ -204,14 +204,20 @@ int ln_fwd(int64_t T, int64_t h, const void* x, const void* g, const void* b, fl
   ProfScope ps(PC_LN_FWD, s);
   return check_launch(launch_layernorm_fwd(T, h, x, g, b, eps, out, out_lo, stats, s), "layernorm_fwd");
 }
-int ln_bwd(int64_t T, int64_t h, const void* dout, const void* x, const float* stats, const void* g,
-           const void* res, void* dx, float* dg, float* db, float* ws, hipStream_t s) {
+// The LayerNorm parameter gradients and the bias gradients (column sums) go straight into the
+// gradient accumulators: stored if acc == 0, added otherwise.
+int ln_bwd(axonn_stage* st, int layer, int which_g, int which_b, int64_t T, int64_t h, const void* dout,
+           const void* x, const float* stats, const void* g, const void* res, void* dx, int acc, hipStream_t s) {
   ProfScope ps(PC_LN_BWD, s);
-  return check_launch(launch_layernorm_bwd(T, h, dout, x, stats, g, res, dx, dg, db, ws, s), "layernorm_bwd");
+  return check_launch(launch_layernorm_bwd(T, h, dout, x, stats, g, res, dx, grad_ptr(st, layer, which_g),
+                                           grad_ptr(st, layer, which_b), acc ? 2 : 1,
+                                           st->cfg.grad_accum_fp32 != 0, st->red_ws, s), "layernorm_bwd");
 }
-int colsum(int64_t T, int64_t N, const void* y, int64_t ldy, float* out, float* ws, hipStream_t s) {
+int bias_grad(axonn_stage* st, int layer, int which, int64_t T, int64_t N, const void* y, int64_t ldy, int acc,
+              hipStream_t s) {
   ProfScope ps(PC_COLSUM, s);
-  return check_launch(launch_colsum(T, N, y, ldy, out, ws, s), "colsum");
+  return check_launch(launch_colsum(T, N, y, ldy, grad_ptr(st, layer, which), acc ? 2 : 1,
+                                    st->cfg.grad_accum_fp32 != 0, st->red_ws, s), "colsum");
 }
 int attn_fwd(int b, int sq, int a, int d, const void* qkv, void* o, float* lse, hipStream_t s) {
   ProfScope ps(PC_ATTN_FWD, s);
@@ -265,12 +271,6 @@ int forward_layers(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s) {
 }
 
 // ------------------------------------------------------------------- backward of a slot
-int vec_grad(axonn_stage* st, int layer, int which, const float* src, int n, int acc, hipStream_t s) {
-  ProfScope ps(PC_ACCUM_VEC, s);
-  return check_launch(launch_accum_vec(n, src, grad_ptr(st, layer, which), st->cfg.grad_accum_fp32 != 0,
-                                       acc != 0, s), "accum_vec");
-}
-
 int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out, int acc, hipStream_t s) {
   const int T = st->T, h = st->h, f = st->f, L = st->cfg.n_layers;
   // the upstream gradient is copied into the stash: it is an operand of the deferred weight
@@ -286,36 +286,28 @@ int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out
     // z = y + g W2 + b2
     AX_TRY(gemm(true, true, EPI_DGELU, T, f, h, d_in, h, param_ptr(st, l, P_WFC2), h, a.dpre, f,
                 nullptr, nullptr, 0, a.pre, f, 0, s));
-    AX_TRY(colsum(T, h, d_in, h, st->vec0, st->red_ws, s));
-    AX_TRY(vec_grad(st, l, P_BFC2, st->vec0, h, acc, s));
+    AX_TRY(bias_grad(st, l, P_BFC2, T, h, d_in, h, acc, s));
     // pre = w W1 + b1
     AX_TRY(gemm(true, true, EPI_BIAS, T, h, f, a.dpre, f, param_ptr(st, l, P_WFC1), f, st->dw, h,
                 nullptr, nullptr, 0, nullptr, 0, 0, s));
-    AX_TRY(colsum(T, f, a.dpre, f, st->vec0, st->red_ws, s));
-    AX_TRY(vec_grad(st, l, P_BFC1, st->vec0, f, acc, s));
+    AX_TRY(bias_grad(st, l, P_BFC1, T, f, a.dpre, f, acc, s));
     // w = LN2(y); residual: dy = d_in + dLN2
-    AX_TRY(ln_bwd(T, h, st->dw, a.y, a.stats2, param_ptr(st, l, P_LN2G), d_in, a.dy_mid, st->vec0, st->vec1,
-                  st->red_ws, s));
-    AX_TRY(vec_grad(st, l, P_LN2G, st->vec0, h, acc, s));
-    AX_TRY(vec_grad(st, l, P_LN2B, st->vec1, h, acc, s));
+    AX_TRY(ln_bwd(st, l, P_LN2G, P_LN2B, T, h, st->dw, a.y, a.stats2, param_ptr(st, l, P_LN2G), d_in, a.dy_mid,
+                  acc, s));
     // y = x + o Wo + bo
     AX_TRY(gemm(true, true, EPI_BIAS, T, h, h, a.dy_mid, h, param_ptr(st, l, P_WO), h, st->dattn, h,
                 nullptr, nullptr, 0, nullptr, 0, 0, s));
-    AX_TRY(colsum(T, h, a.dy_mid, h, st->vec0, st->red_ws, s));
-    AX_TRY(vec_grad(st, l, P_BO, st->vec0, h, acc, s));
+    AX_TRY(bias_grad(st, l, P_BO, T, h, a.dy_mid, h, acc, s));
     // attention
     AX_TRY(attn_bwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d, a.qkv, a.o, a.lse, st->dattn,
                     a.dqkv, st->delta, s));
     // qkv = u Wqkv + b
     AX_TRY(gemm(true, true, EPI_BIAS, T, h, 3 * h, a.dqkv, 3 * h, param_ptr(st, l, P_WQKV), 3 * h, st->du, h,
                 nullptr, nullptr, 0, nullptr, 0, 0, s));
-    AX_TRY(colsum(T, 3 * h, a.dqkv, 3 * h, st->vec0, st->red_ws, s));
-    AX_TRY(vec_grad(st, l, P_BQKV, st->vec0, 3 * h, acc, s));
+    AX_TRY(bias_grad(st, l, P_BQKV, T, 3 * h, a.dqkv, 3 * h, acc, s));
     // u = LN1(x); residual: dx = dy + dLN1
-    AX_TRY(ln_bwd(T, h, st->du, a.x, a.stats1, param_ptr(st, l, P_LN1G), a.dy_mid, d_out, st->vec0, st->vec1,
-                  st->red_ws, s));
-    AX_TRY(vec_grad(st, l, P_LN1G, st->vec0, h, acc, s));
-    AX_TRY(vec_grad(st, l, P_LN1B, st->vec1, h, acc, s));
+    AX_TRY(ln_bwd(st, l, P_LN1G, P_LN1B, T, h, st->du, a.x, a.stats1, param_ptr(st, l, P_LN1G), a.dy_mid, d_out,
+                  acc, s));
   }
   return AXONN_OK;
 }
@@ -625,14 +617,13 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
   }
   // backward workspace
   const int64_t wide = std::max<int64_t>(f, 3 * h);
-  const uint64_t e_red = align_up((uint64_t)2 * ((T + 63) / 64) * wide * 4, 256), e_vec = align_up((uint64_t)wide * 4, 256);
-  st->ws_bytes = 3 * e_th + e_lse + e_red + 2 * e_vec;
+  const uint64_t e_red = align_up((uint64_t)2 * ((T + 63) / 64) * wide * 4, 256);
+  st->ws_bytes = 3 * e_th + e_lse + e_red;
   CREATE_TRY(hipMalloc((void**)&st->ws_base, st->ws_bytes));
   {
     char* p = st->ws_base;
     st->dw = (bf16_t*)p; p += e_th; st->dattn = (bf16_t*)p; p += e_th; st->du = (bf16_t*)p; p += e_th;
     st->delta = (float*)p; p += e_lse; st->red_ws = (float*)p; p += e_red;
-    st->vec0 = (float*)p; p += e_vec; st->vec1 = (float*)p; p += e_vec;
   }
   CREATE_TRY(hipEventCreateWithFlags(&st->last_bwd, hipEventDisableTiming));
   CREATE_TRY(hipEventCreateWithFlags(&st->last_wgrad, hipEventDisableTiming));
@@ -1039,15 +1030,15 @@ int axonn_layernorm_bwd(int64_t T, int64_t h, const void* dout, const void* x, c
     return fail(AXONN_EINVAL, "layernorm_bwd: null argument");
   if (T < 1 || h < 1) return fail(AXONN_EINVAL, "layernorm_bwd: non-positive size");
   if (h % 8 || h > 16384) return fail(AXONN_EUNSUPPORTED, "layernorm_bwd: h must be a multiple of 8 and <= 16384");
-  return check_launch(launch_layernorm_bwd(T, h, dout, x, stats, gamma, res_grad, dx, dgamma, dbeta, workspace,
-                                           (hipStream_t)hip_stream), "layernorm_bwd");
+  return check_launch(launch_layernorm_bwd(T, h, dout, x, stats, gamma, res_grad, dx, dgamma, dbeta, 0, true,
+                                           workspace, (hipStream_t)hip_stream), "layernorm_bwd");
 }
 
 int axonn_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, float* out, float* workspace, void* hip_stream) {
   if (!y || !out || !workspace) return fail(AXONN_EINVAL, "colsum: null argument");
   if (T < 1 || N < 1) return fail(AXONN_EINVAL, "colsum: non-positive size");
   if (N % 8 || ldy % 8 || ldy < N) return fail(AXONN_EUNSUPPORTED, "colsum: N and ldy must be multiples of 8, ldy >= N");
-  return check_launch(launch_colsum(T, N, y, ldy, out, workspace, (hipStream_t)hip_stream), "colsum");
+  return check_launch(launch_colsum(T, N, y, ldy, out, 0, true, workspace, (hipStream_t)hip_stream), "colsum");
 }
 
 int axonn_attention_fwd(int32_t b, int32_t s, int32_t n_heads, int32_t head_dim, const void* qkv, void* o,
