@@ -106,13 +106,31 @@ __device__ __forceinline__ float wave_max(float v) {
 __device__ __forceinline__ float bf2f(bf16_t v) { return (float)v; }
 __device__ __forceinline__ bf16_t f2bf(float v) { return (bf16_t)v; }
 
-// Exact-form GeLU pieces: Phi(x) = 0.5*(1+erf(x/sqrt2)), phi(x) = exp(-x^2/2)/sqrt(2pi).
+// GeLU pieces in the exact (erf) form: Phi(x) = 0.5*(1+erf(x/sqrt2)), phi(x) = exp(-x^2/2)/sqrt(2pi).
+// erfc(z), z >= 0, is evaluated as a degree-5 polynomial in 1/(1 + p z) times exp(-z^2) (Abramowitz &
+// Stegun 7.1.26, absolute error <= 1.5e-7, i.e. one fp32 ulp of values near 1); Phi takes erfc(|x|/sqrt2)
+// on the side of the tail, so there is no cancellation for negative x.  `e` returns exp(-x^2/2), which
+// the derivative needs as well.
+__device__ __forceinline__ float normal_cdf_f(float x, float& e) {
+  const float z = fabsf(x) * 0.70710678118654752440f;
+  const float t = __frcp_rn(1.0f + 0.3275911f * z);
+  e = __expf(-z * z);
+  float p = 1.061405429f;
+  p = p * t - 1.453152027f;
+  p = p * t + 1.421413741f;
+  p = p * t - 0.284496736f;
+  p = p * t + 0.254829592f;
+  const float half_erfc = 0.5f * p * t * e;
+  return x >= 0.f ? 1.0f - half_erfc : half_erfc;
+}
 __device__ __forceinline__ float gelu_f(float x) {
-  return 0.5f * x * (1.0f + erff(x * 0.70710678118654752440f));
+  float e;
+  return x * normal_cdf_f(x, e);
 }
 __device__ __forceinline__ float gelu_grad_f(float x) {
-  const float cdf = 0.5f * (1.0f + erff(x * 0.70710678118654752440f));
-  return cdf + x * __expf(-0.5f * x * x) * 0.39894228040143267794f;
+  float e;
+  const float cdf = normal_cdf_f(x, e);
+  return cdf + x * e * 0.39894228040143267794f;
 }
 #endif  // __HIPCC__
 

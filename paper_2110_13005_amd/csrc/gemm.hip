@@ -39,20 +39,74 @@ struct TileLayout {
   static constexpr int ELEMS = KC ? ROWS * LD : BK * LD;
 };
 
-// Epilogue of 4 consecutive columns n..n+3 of row m (both inside the matrix), v = the sums.
+// Bias of columns n..n+3 as floats (zeros if there is none or the epilogue takes none).
 template <int EPI>
-__device__ __forceinline__ void epilogue_run(float (&v)[4], const GemmArgs& g, int m, int n) {
+__device__ __forceinline__ void load_bias4(float (&bv)[4], const GemmArgs& g, int n) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) bv[e] = 0.f;
   if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
     if (g.bias) {
-      const bf16x4 bv = *reinterpret_cast<const bf16x4*>(g.bias + n);
+      const bf16x4 b4 = *reinterpret_cast<const bf16x4*>(g.bias + n);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] += (float)bv[e];
+      for (int e = 0; e < 4; ++e) bv[e] = (float)b4[e];
     }
   }
-  if (EPI == EPI_BIAS_RES) {
-    const bf16x4 rv = *reinterpret_cast<const bf16x4*>(g.res + (int64_t)m * g.ld_res + n);
+}
+
+// What an epilogue reads at the position of its result: the residual, the stored pre-activation, or
+// the previous value of an accumulating C.  `raw` holds the 4 values as loaded (bf16 in the low half
+// of the words, or fp32); loading is separate from the arithmetic so that a caller can have the loads
+// of many positions in flight before it consumes the first.
+struct EpiOperand { uint32_t raw[4]; };
+
+template <int EPI>
+__device__ __forceinline__ bool epi_reads_operand(const GemmArgs& g) {
+  return EPI == EPI_BIAS_RES || EPI == EPI_DGELU ||
+         ((EPI == EPI_ACC_F32 || EPI == EPI_ACC_BF16) && g.accumulate);
+}
+
+template <int EPI>
+__device__ __forceinline__ EpiOperand epi_load_operand(const GemmArgs& g, int m, int n) {
+  EpiOperand o;
+  if (EPI == EPI_ACC_F32) {
+    const u32x4 t = *reinterpret_cast<const u32x4*>(reinterpret_cast<const float*>(g.C) + (int64_t)m * g.ldc + n);
+    o.raw[0] = t[0]; o.raw[1] = t[1]; o.raw[2] = t[2]; o.raw[3] = t[3];
+  } else {
+    const bf16_t* p = EPI == EPI_BIAS_RES ? g.res + (int64_t)m * g.ld_res + n
+                    : EPI == EPI_DGELU    ? g.aux + (int64_t)m * g.ld_aux + n
+                                          : reinterpret_cast<const bf16_t*>(g.C) + (int64_t)m * g.ldc + n;
+    const uint2 t = *reinterpret_cast<const uint2*>(p);
+    o.raw[0] = t.x; o.raw[1] = t.y; o.raw[2] = 0u; o.raw[3] = 0u;
+  }
+  return o;
+}
+
+// The 4 operand values as floats.
+template <int EPI>
+__device__ __forceinline__ void epi_operand_values(const EpiOperand& o, float (&x)[4]) {
+  if (EPI == EPI_ACC_F32) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] += (float)rv[e];
+    for (int e = 0; e < 4; ++e) x[e] = __uint_as_float(o.raw[e]);
+  } else {
+    x[0] = __uint_as_float(o.raw[0] << 16); x[1] = __uint_as_float(o.raw[0] & 0xffff0000u);
+    x[2] = __uint_as_float(o.raw[1] << 16); x[3] = __uint_as_float(o.raw[1] & 0xffff0000u);
+  }
+}
+
+// Epilogue of 4 consecutive columns n..n+3 of row m (both inside the matrix): v = the sums, bv = their
+// bias, `o` = the operand loaded with epi_load_operand (ignored if the epilogue reads none).
+template <int EPI>
+__device__ __forceinline__ void epi_finish(float (&v)[4], const float (&bv)[4], const EpiOperand& o,
+                                           const GemmArgs& g, int m, int n) {
+  float x[4] = {0.f, 0.f, 0.f, 0.f};
+  if (epi_reads_operand<EPI>(g)) epi_operand_values<EPI>(o, x);
+  if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += bv[e];
+  }
+  if (EPI == EPI_BIAS_RES || EPI == EPI_ACC_F32 || EPI == EPI_ACC_BF16) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += x[e];
   }
   if (EPI == EPI_BIAS_GELU) {
     bf16x4 pv;
@@ -61,34 +115,26 @@ __device__ __forceinline__ void epilogue_run(float (&v)[4], const GemmArgs& g, i
     *reinterpret_cast<bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n) = pv;
   }
   if (EPI == EPI_DGELU) {
-    const bf16x4 pv = *reinterpret_cast<const bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f((float)pv[e]);
+    for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f(x[e]);
   }
   if (EPI == EPI_ACC_F32) {
-    float* cp = reinterpret_cast<float*>(g.C) + (int64_t)m * g.ldc + n;
-    floatx4 o;
-    if (g.accumulate) {
-      o = *reinterpret_cast<const floatx4*>(cp);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] += v[e];
-    } else {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) o[e] = v[e];
-    }
-    *reinterpret_cast<floatx4*>(cp) = o;
+    *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(g.C) + (int64_t)m * g.ldc + n) =
+        floatx4{v[0], v[1], v[2], v[3]};
   } else {
-    bf16_t* cp = reinterpret_cast<bf16_t*>(g.C) + (int64_t)m * g.ldc + n;
-    if (EPI == EPI_ACC_BF16 && g.accumulate) {
-      const bf16x4 cv = *reinterpret_cast<const bf16x4*>(cp);
+    bf16x4 ov;
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] += (float)cv[e];
-    }
-    bf16x4 o;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) o[e] = (bf16_t)v[e];
-    *reinterpret_cast<bf16x4*>(cp) = o;
+    for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)v[e];
+    *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(g.C) + (int64_t)m * g.ldc + n) = ov;
   }
+}
+
+template <int EPI>
+__device__ __forceinline__ void epilogue_run(float (&v)[4], const float (&bv)[4], const GemmArgs& g,
+                                             int m, int n) {
+  EpiOperand o;
+  if (epi_reads_operand<EPI>(g)) o = epi_load_operand<EPI>(g, m, n);
+  epi_finish<EPI>(v, bv, o, g, m, n);
 }
 
 // Writes one wave's TM x TN result tiles of the 32x32x16 MFMA.  The MFMA was issued with the B
@@ -110,29 +156,59 @@ __device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[TM][TN], con
         float v[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e];
-        epilogue_run<EPI>(v, g, m, n);
+        float bv[4];
+        load_bias4<EPI>(bv, g, n);
+        epilogue_run<EPI>(v, bv, g, m, n);
       }
     }
   }
 }
 
-// The same for tiles of the 16x16x32 MFMA (B fragment first): lane l owns row m_base + 16*i + l%16
-// and the 4 registers of tile (i,j) are columns n_base + 16*j + 4*(l/16) + 0..3.
-template <int EPI, int TM, int TN>
-__device__ __forceinline__ void gemm_epilogue16(const floatx4 (&acc)[TM][TN], const GemmArgs& g,
-                                                int m_base, int n_base, int lane) {
+// Epilogue of a 128 x 128 wave tile held as 8 x 8 tiles of the 16x16x32 MFMA (B fragment first: lane l
+// owns row 16*i + l%16 and the 4 registers of tile (i,j) are columns 16*j + 4*(l/16) + 0..3).  Stored
+// straight from that layout a wave instruction would touch 16 rows with 32 bytes each; instead the wave
+// passes its tile, 64 rows at a time, through its own LDS region (row stride 132 floats: conflict-free
+// both ways) and comes back with lane l owning columns 4*(l%32)..+3 of rows 2t + l/32: a wave
+// instruction then covers two rows with 256 (bf16) or 512 (fp32) contiguous bytes each, for C as well
+// as for the residual / pre-activation operands.  `stage` is wave-private: no workgroup barrier here.
+constexpr int kStageLd = 132;
+constexpr int kStageFloatsPerWave = 64 * kStageLd;     // 33792 bytes
+template <int EPI>
+__device__ __forceinline__ void gemm_epilogue_staged(const floatx4 (&acc)[8][8], const GemmArgs& g,
+                                                     int m_base, int n_base, int lane, float* stage) {
+  const int n = n_base + 4 * (lane & 31);
+  float bv[4];
+  if (n < g.N) load_bias4<EPI>(bv, g, n);
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int m = m_base + i * 16 + (lane & 15);
-    if (m >= g.M) continue;
+  for (int p = 0; p < 2; ++p) {
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n_base + j * 16 + 4 * (lane >> 4);
-      if (n >= g.N) continue;
-      float v[4];
+    for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) v[e] = acc[i][j][e];
-      epilogue_run<EPI>(v, g, m, n);
+      for (int j = 0; j < 8; ++j)
+        *reinterpret_cast<floatx4*>(stage + (16 * ii + (lane & 15)) * kStageLd + 16 * j + 4 * (lane >> 4)) =
+            acc[4 * p + ii][j];
+    // 32 row pairs per pass, 16 at a time: first the loads of whatever the epilogue reads at its
+    // output positions, all in flight together, then the arithmetic and the stores
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+      EpiOperand opnd[16];
+      if (epi_reads_operand<EPI>(g)) {
+#pragma unroll
+        for (int tt = 0; tt < 16; ++tt) {
+          const int m = m_base + 64 * p + 2 * (16 * hh + tt) + (lane >> 5);
+          if (m < g.M && n < g.N) opnd[tt] = epi_load_operand<EPI>(g, m, n);
+        }
+      }
+#pragma unroll
+      for (int tt = 0; tt < 16; ++tt) {
+        const int r = 2 * (16 * hh + tt) + (lane >> 5);
+        const floatx4 x = *reinterpret_cast<const floatx4*>(stage + r * kStageLd + 4 * (lane & 31));
+        const int m = m_base + 64 * p + r;
+        if (m < g.M && n < g.N) {
+          float v[4] = {x[0], x[1], x[2], x[3]};
+          epi_finish<EPI>(v, bv, opnd[tt], g, m, n);
+        }
+      }
     }
   }
 }
@@ -324,8 +400,12 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
   constexpr int TM = 8, TN = 8;
   using LA = TileLayout<BM, BK, A_KC>;
   using LB = TileLayout<BN, BK, B_KC>;
-  __shared__ __align__(16) bf16_t sA[2][LA::ELEMS];
-  __shared__ __align__(16) bf16_t sB[2][LB::ELEMS];
+  // one LDS block: A buffers 0,1, then B buffers 0,1; the epilogue reuses it as staging space
+  constexpr int LDS_BYTES = 2 * (LA::ELEMS + LB::ELEMS) * (int)sizeof(bf16_t);
+  static_assert(LDS_BYTES >= 4 * kStageFloatsPerWave * (int)sizeof(float), "staging space of the epilogue");
+  __shared__ __align__(16) char smem[LDS_BYTES];
+#define sA(buf) (reinterpret_cast<bf16_t*>(smem) + (buf) * LA::ELEMS)
+#define sB(buf) (reinterpret_cast<bf16_t*>(smem) + 2 * LA::ELEMS + (buf) * LB::ELEMS)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -395,21 +475,21 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
     rsb = make_rsrc(g.B_seg[sidx], nrb);                                                       \
   }
 #define AXONN_SSTORE_CHUNK(buf, q)                                                             \
-  if ((q) < CH) *reinterpret_cast<u32x4*>(&sA[buf][wa + ((q) & 7) * WJA]) = ra[(q) & 7];       \
-  else          *reinterpret_cast<u32x4*>(&sB[buf][wb + ((q) & 7) * WJB]) = rb[(q) & 7];
+  if ((q) < CH) *reinterpret_cast<u32x4*>(&sA(buf)[wa + ((q) & 7) * WJA]) = ra[(q) & 7];       \
+  else          *reinterpret_cast<u32x4*>(&sB(buf)[wb + ((q) & 7) * WJB]) = rb[(q) & 7];
   // Fragment q (0..15) of k slice kk (0 or 1) of the tile in buffer buf -> fragment set F, in the
   // order the MFMAs of the slice consume them: a0 b0..b7 a1..a7.
 #define AXONN_FRAG(F, buf, kk, q)                                                              \
   if ((q) == 0 || (q) > 8) {                                                                   \
     const int i = (q) == 0 ? 0 : (q) - 8;                                                      \
     const int r0 = wm * 128 + i * 16;                                                          \
-    fa[F][i] = A_KC ? frag16_kcontig(sA[buf] + r0 * LA::LD + (kk) * 32, LA::LD, lane)          \
-                    : frag16_kstrided(sA[buf] + ((kk) * 32) * LA::LD + r0, LA::LD, lane);      \
+    fa[F][i] = A_KC ? frag16_kcontig(sA(buf) + r0 * LA::LD + (kk) * 32, LA::LD, lane)          \
+                    : frag16_kstrided(sA(buf) + ((kk) * 32) * LA::LD + r0, LA::LD, lane);      \
   } else {                                                                                     \
     const int j = (q) - 1;                                                                     \
     const int r0 = wn * 128 + j * 16;                                                          \
-    fb[F][j] = B_KC ? frag16_kcontig(sB[buf] + r0 * LB::LD + (kk) * 32, LB::LD, lane)          \
-                    : frag16_kstrided(sB[buf] + ((kk) * 32) * LB::LD + r0, LB::LD, lane);      \
+    fb[F][j] = B_KC ? frag16_kcontig(sB(buf) + r0 * LB::LD + (kk) * 32, LB::LD, lane)          \
+                    : frag16_kstrided(sB(buf) + ((kk) * 32) * LB::LD + r0, LB::LD, lane);      \
   }
   // One k-step on the tile kt in buffer CUR: two phases of 64 MFMAs (k slices 0 and 1), between which
   // the other memory instructions are spread as evenly as their dependences allow, so that neither the
@@ -493,7 +573,11 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
 #undef AXONN_MFMA
 #undef AXONN_KSTEP
 
-  gemm_epilogue16<EPI, TM, TN>(acc, g, m0 + wm * 128, n0 + wn * 128, lane);
+  lds_barrier();                                          // every wave is done with the tiles in LDS
+  gemm_epilogue_staged<EPI>(acc, g, m0 + wm * 128, n0 + wn * 128, lane,
+                            reinterpret_cast<float*>(smem) + wave * kStageFloatsPerWave);
+#undef sA
+#undef sB
 }
 
 // ------------------------------------------------------------------------------------------
