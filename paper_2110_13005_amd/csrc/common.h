@@ -153,6 +153,8 @@ struct GemmArgs {
   int M, N, K;       // K = length of ONE segment
   int n_seg;
   int accumulate;
+  int concurrent;    // other kernels share the chip with this launch: prefer the most efficient tile shape
+                     // over one whose tile count fills the CUs a whole number of times
   int tiles_m, tiles_n;
 };
 

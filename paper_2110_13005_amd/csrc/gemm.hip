@@ -164,28 +164,34 @@ __device__ __forceinline__ void gemm_epilogue(const floatx16 (&acc)[TM][TN], con
   }
 }
 
-// Epilogue of a 128 x 128 wave tile held as 8 x 8 tiles of the 16x16x32 MFMA (B fragment first: lane l
-// owns row 16*i + l%16 and the 4 registers of tile (i,j) are columns 16*j + 4*(l/16) + 0..3).  Stored
+// Epilogue of a 128 x 16*TN wave tile held as 8 x TN tiles of the 16x16x32 MFMA (B fragment first: lane
+// l owns row 16*i + l%16 and the 4 registers of tile (i,j) are columns 16*j + 4*(l/16) + 0..3).  Stored
 // straight from that layout a wave instruction would touch 16 rows with 32 bytes each; instead the wave
-// passes its tile, 64 rows at a time, through its own LDS region (row stride 132 floats: conflict-free
-// both ways) and comes back with lane l owning columns 4*(l%32)..+3 of rows 2t + l/32: a wave
-// instruction then covers two rows with 256 (bf16) or 512 (fp32) contiguous bytes each, for C as well
-// as for the residual / pre-activation operands.  `stage` is wave-private: no workgroup barrier here.
-constexpr int kStageLd = 132;
-constexpr int kStageFloatsPerWave = 64 * kStageLd;     // 33792 bytes
-template <int EPI>
-__device__ __forceinline__ void gemm_epilogue_staged(const floatx4 (&acc)[8][8], const GemmArgs& g,
+// passes its tile, 64 rows at a time, through its own LDS region (row stride 16*TN + 4 floats:
+// conflict-free both ways) and comes back with lane l owning columns 4*(l%32)..+3 of rows 2t + l/32: a
+// wave instruction then covers two rows with up to 256 (bf16) or 512 (fp32) contiguous bytes each, for C
+// as well as for the residual / pre-activation operands.  `stage` is wave-private: no workgroup barrier.
+template <int TN>
+struct StageLayout {
+  static constexpr int LD = 16 * TN + 4;
+  static constexpr int FLOATS_PER_WAVE = 64 * LD;
+};
+template <int EPI, int TN>
+__device__ __forceinline__ void gemm_epilogue_staged(const floatx4 (&acc)[8][TN], const GemmArgs& g,
                                                      int m_base, int n_base, int lane, float* stage) {
-  const int n = n_base + 4 * (lane & 31);
+  constexpr int LD = StageLayout<TN>::LD;
+  const int nl = 4 * (lane & 31);                 // column inside the wave tile
+  const int n = n_base + nl;
+  const bool col_ok = nl < 16 * TN && n < g.N;
   float bv[4];
-  if (n < g.N) load_bias4<EPI>(bv, g, n);
+  if (col_ok) load_bias4<EPI>(bv, g, n);
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
 #pragma unroll
     for (int ii = 0; ii < 4; ++ii)
 #pragma unroll
-      for (int j = 0; j < 8; ++j)
-        *reinterpret_cast<floatx4*>(stage + (16 * ii + (lane & 15)) * kStageLd + 16 * j + 4 * (lane >> 4)) =
+      for (int j = 0; j < TN; ++j)
+        *reinterpret_cast<floatx4*>(stage + (16 * ii + (lane & 15)) * LD + 16 * j + 4 * (lane >> 4)) =
             acc[4 * p + ii][j];
     // 32 row pairs per pass, 16 at a time: first the loads of whatever the epilogue reads at its
     // output positions, all in flight together, then the arithmetic and the stores
@@ -196,15 +202,15 @@ __device__ __forceinline__ void gemm_epilogue_staged(const floatx4 (&acc)[8][8],
 #pragma unroll
         for (int tt = 0; tt < 16; ++tt) {
           const int m = m_base + 64 * p + 2 * (16 * hh + tt) + (lane >> 5);
-          if (m < g.M && n < g.N) opnd[tt] = epi_load_operand<EPI>(g, m, n);
+          if (m < g.M && col_ok) opnd[tt] = epi_load_operand<EPI>(g, m, n);
         }
       }
 #pragma unroll
       for (int tt = 0; tt < 16; ++tt) {
         const int r = 2 * (16 * hh + tt) + (lane >> 5);
-        const floatx4 x = *reinterpret_cast<const floatx4*>(stage + r * kStageLd + 4 * (lane & 31));
         const int m = m_base + 64 * p + r;
-        if (m < g.M && n < g.N) {
+        if (m < g.M && col_ok) {
+          const floatx4 x = *reinterpret_cast<const floatx4*>(stage + r * LD + nl);
           float v[4] = {x[0], x[1], x[2], x[3]};
           epi_finish<EPI>(v, bv, opnd[tt], g, m, n);
         }
@@ -378,13 +384,16 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
 }
 
 // ------------------------------------------------------------------------------------------
-// Large-problem kernel: 256 x 256 x 64 block tile, 4 waves (2 x 2), wave tile 128 x 128 = 8 x 8 tiles
-// of the 16x16x32 MFMA held in 256 accumulator registers, so that each byte read from LDS feeds
-// twice the MFMA work of a 128 x 64 wave tile.  One wave per SIMD: latency is hidden inside the wave
-// by software pipelining.  A k-step is two phases of 64 MFMAs (one 32-wide k slice each); the
-// fragments of a slice are read from LDS one phase ahead; the copy of the next tiles (registers ->
-// LDS, then the registers are reloaded from global memory) is spread evenly over the MFMAs of both
-// phases, and the single barrier of the step sits between them.
+// Large-problem kernel: 256 x (32*TN) x 64 block tile, 4 waves (2 x 2), wave tile 128 x 16*TN = 8 x TN
+// tiles of the 16x16x32 MFMA held in accumulation registers (all 256 of them for TN = 8), so that each
+// byte read from LDS feeds twice the MFMA work of a 128 x 64 wave tile.  TN = 8 is the most efficient
+// shape; TN = 5 and 6 (block widths 160 and 192) exist because the tile count of a problem should fill
+// the 256 CUs a whole number of times (hidden sizes of 5 * 2^k and 3 * 2^k divide evenly by them).
+// One wave per SIMD: latency is hidden inside the wave by software pipelining.  A k-step is two
+// phases of 8*TN MFMAs (one 32-wide k slice each); the fragments of a slice are read from LDS one phase
+// ahead; the copy of the next tiles (registers -> LDS, then the registers are reloaded from global
+// memory) is spread over the MFMAs of both phases, and the single barrier of the step sits just
+// after the start of the second phase.
 // Tiles are fetched with buffer loads: an offset at or beyond the descriptor's size returns zeros
 // without touching memory, which covers rows outside the matrix, the k tail and the tiles past the
 // last one without branches or per-chunk pointers.
@@ -394,15 +403,29 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
 }
 
-template <bool A_KC, bool B_KC, int EPI>
+// Item idx of n items spread evenly over the MFMA slots [first, first + span), and its inverse (-1: no
+// item at slot q).  span >= n, so that no two items share a slot.
+constexpr int spread_slot(int idx, int n, int first, int span) { return first + idx * span / n; }
+constexpr int item_at(int q, int n, int first, int span) {
+  if (q < first) return -1;
+  const int i = ((q - first) * n + span - 1) / span;     // the only candidate: smallest i with slot >= q
+  return (i < n && spread_slot(i, n, first, span) == q) ? i : -1;
+}
+
+template <bool A_KC, bool B_KC, int EPI, int TN>
 __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
-  constexpr int BM = 256, BN = 256, BK = 64, CH = 8;   // CH: 16-byte chunks per thread, operand and tile
-  constexpr int TM = 8, TN = 8;
+  constexpr int BM = 256, BN = 32 * TN, BK = 64, TM = 8;
+  // 16-byte chunks per thread and tile of A and of B.  A k-strided B tile always takes the copy pattern
+  // and the LDS layout of the 256-wide tile (8 chunks per thread, 32 per k); the lanes whose columns lie
+  // beyond a narrower block read "out of range" (zeros, no memory traffic) into LDS columns nobody uses.
+  constexpr int NCA = 8, NCB = B_KC ? TN : 8;
+  constexpr int NM = TM * TN;           // MFMAs per phase
+  constexpr int NF = TM + TN;           // fragments per k slice
   using LA = TileLayout<BM, BK, A_KC>;
-  using LB = TileLayout<BN, BK, B_KC>;
+  using LB = TileLayout<B_KC ? BN : 256, BK, B_KC>;
   // one LDS block: A buffers 0,1, then B buffers 0,1; the epilogue reuses it as staging space
   constexpr int LDS_BYTES = 2 * (LA::ELEMS + LB::ELEMS) * (int)sizeof(bf16_t);
-  static_assert(LDS_BYTES >= 4 * kStageFloatsPerWave * (int)sizeof(float), "staging space of the epilogue");
+  static_assert(LDS_BYTES >= 4 * StageLayout<TN>::FLOATS_PER_WAVE * (int)sizeof(float), "staging space of the epilogue");
   __shared__ __align__(16) char smem[LDS_BYTES];
 #define sA(buf) (reinterpret_cast<bf16_t*>(smem) + (buf) * LA::ELEMS)
 #define sB(buf) (reinterpret_cast<bf16_t*>(smem) + 2 * LA::ELEMS + (buf) * LB::ELEMS)
@@ -410,6 +433,8 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
 
+  // Workgroups are dealt round-robin to the 8 XCDs; remap so that each XCD (own L2) works on a
+  // contiguous run of tiles, ordered in bands of 8 tile-rows, column by column inside a band.
   int pid = blockIdx.x;
   const int nblk = gridDim.x;
   if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
@@ -420,8 +445,8 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
   const int tm = band * BAND + in_band % band_rows, tn = in_band / band_rows;
   const int m0 = tm * BM, n0 = tn * BN;
 
-  // Chunk j of this thread: byte offset v? + j * j? from the segment base, advanced by s? per k-step;
-  // it lands at element w? + j * WJ? of the LDS tile.
+  // Chunk j of this thread of operand A: byte offset va + j * ja from the segment base, advanced by sa per
+  // k-step; it lands at element wa + j * WJA of the LDS tile.  The same for B.
   const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
   uint32_t va, vb, ja, jb, sa, sb, nra, nrb;
   int wa, wb, kca = 0, kcb = 0;
@@ -443,7 +468,7 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
     wb = row * LB::LD + kc * 8; kcb = kc * 8; nrb = (uint32_t)g.N * ldb * 2u;
   } else {
     const int kr = tid >> 5, rc = tid & 31;
-    vb = (n0 + rc * 8 < g.N) ? ((uint32_t)kr * ldb + n0 + rc * 8) * 2u : kOutOfRange;
+    vb = (rc * 8 < BN && n0 + rc * 8 < g.N) ? ((uint32_t)kr * ldb + n0 + rc * 8) * 2u : kOutOfRange;
     jb = 8u * ldb * 2u; sb = BK * ldb * 2u;
     wb = kr * LB::LD + rc * 8; nrb = (uint32_t)g.K * ldb * 2u;
   }
@@ -451,11 +476,11 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
   const int tps = (K + BK - 1) / BK;      // k-tiles per segment
   const int nk = tps * g.n_seg;
   __amdgpu_buffer_rsrc_t rsa = make_rsrc(g.A_seg[0], nra), rsb = make_rsrc(g.B_seg[0], nrb);
-  u32x4 ra[CH], rb[CH];
+  u32x4 ra[NCA], rb[NCB];
   int ld_seg = 0, ld_kin = 0;            // segment and k-tile within it of the NEXT tile to fetch
 
   // Fetch of the next tile, split so that it can be interleaved with MFMAs: BEGIN computes the
-  // offsets, CHUNK(q) issues load q (0..7 operand A, 8..15 operand B), END advances to the next tile.
+  // offsets, LOAD_A/B(c) issue the load of chunk c, END advances to the next tile.
   uint32_t xa, xb;
 #define AXONN_GLOAD_BEGIN()                                                                    \
   {                                                                                            \
@@ -463,9 +488,8 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
     xa = ((live & (!A_KC | (ld_kin * BK + kca < K))) ? va : kOutOfRange) + (uint32_t)ld_kin * sa; \
     xb = ((live & (!B_KC | (ld_kin * BK + kcb < K))) ? vb : kOutOfRange) + (uint32_t)ld_kin * sb; \
   }
-#define AXONN_GLOAD_CHUNK(q)                                                                   \
-  if ((q) < CH) ra[(q) & 7] = __builtin_amdgcn_raw_buffer_load_b128(rsa, xa + ((q) & 7) * ja, 0, 0); \
-  else          rb[(q) & 7] = __builtin_amdgcn_raw_buffer_load_b128(rsb, xb + ((q) & 7) * jb, 0, 0);
+#define AXONN_LOAD_A(c) ra[c] = __builtin_amdgcn_raw_buffer_load_b128(rsa, xa + (c) * ja, 0, 0);
+#define AXONN_LOAD_B(c) rb[c] = __builtin_amdgcn_raw_buffer_load_b128(rsb, xb + (c) * jb, 0, 0);
 #define AXONN_GLOAD_END()                                                                      \
   if (++ld_kin == tps) {                                                                       \
     ld_kin = 0;                                                                                \
@@ -474,41 +498,40 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
     rsa = make_rsrc(g.A_seg[sidx], nra);                                                       \
     rsb = make_rsrc(g.B_seg[sidx], nrb);                                                       \
   }
-#define AXONN_SSTORE_CHUNK(buf, q)                                                             \
-  if ((q) < CH) *reinterpret_cast<u32x4*>(&sA(buf)[wa + ((q) & 7) * WJA]) = ra[(q) & 7];       \
-  else          *reinterpret_cast<u32x4*>(&sB(buf)[wb + ((q) & 7) * WJB]) = rb[(q) & 7];
-  // Fragment q (0..15) of k slice kk (0 or 1) of the tile in buffer buf -> fragment set F, in the
-  // order the MFMAs of the slice consume them: a0 b0..b7 a1..a7.
-#define AXONN_FRAG(F, buf, kk, q)                                                              \
-  if ((q) == 0 || (q) > 8) {                                                                   \
-    const int i = (q) == 0 ? 0 : (q) - 8;                                                      \
+#define AXONN_STORE_A(buf, c) *reinterpret_cast<u32x4*>(&sA(buf)[wa + (c) * WJA]) = ra[c];
+#define AXONN_STORE_B(buf, c) *reinterpret_cast<u32x4*>(&sB(buf)[wb + (c) * WJB]) = rb[c];
+  // Fragment f (0..NF-1) of k slice kk (0 or 1) of the tile in buffer buf -> fragment set F, in the
+  // order the MFMAs of the slice consume them: a0 b0..b(TN-1) a1..a7.
+#define AXONN_FRAG(F, buf, kk, f)                                                              \
+  if ((f) == 0 || (f) > TN) {                                                                  \
+    const int i = (f) == 0 ? 0 : (f) - TN;                                                     \
     const int r0 = wm * 128 + i * 16;                                                          \
     fa[F][i] = A_KC ? frag16_kcontig(sA(buf) + r0 * LA::LD + (kk) * 32, LA::LD, lane)          \
                     : frag16_kstrided(sA(buf) + ((kk) * 32) * LA::LD + r0, LA::LD, lane);      \
   } else {                                                                                     \
-    const int j = (q) - 1;                                                                     \
-    const int r0 = wn * 128 + j * 16;                                                          \
+    const int j = (f) - 1;                                                                     \
+    const int r0 = wn * (16 * TN) + j * 16;                                                    \
     fb[F][j] = B_KC ? frag16_kcontig(sB(buf) + r0 * LB::LD + (kk) * 32, LB::LD, lane)          \
                     : frag16_kstrided(sB(buf) + ((kk) * 32) * LB::LD + r0, LB::LD, lane);      \
   }
-  // One k-step on the tile kt in buffer CUR: two phases of 64 MFMAs (k slices 0 and 1), between which
+#define AXONN_MFMA(F, q) mfma16_acc(acc[(q) / TN][(q) % TN], fb[F][(q) % TN], fa[F][(q) / TN]);
+  // One k-step on the tile kt in buffer CUR: two phases of NM MFMAs (k slices 0 and 1), between which
   // the other memory instructions are spread as evenly as their dependences allow, so that neither the
   // LDS nor the issue port sees bursts:
-  //   phase 0: fragment reads of slice 1 (one every 4 MFMAs); chunks 8..15 of tile kt+1 go from
-  //            registers to buffer CUR^1 (first half), then their registers are reloaded with those
-  //            chunks of tile kt+2 (second half);
+  //   phase 0: fragment reads of slice 1; the B chunks of tile kt+1 go from registers to buffer CUR^1
+  //            (first half), then their registers are reloaded with those chunks of tile kt+2 (second
+  //            half);
   //   barrier after MFMA 5 of phase 1: by then all of the above has completed, every wave is done with
   //            buffer CUR and tile kt+1 is complete in buffer CUR^1;
-  //   phase 1: fragment reads of slice 0 of tile kt+1; chunks 0..7 of tile kt+2 go to buffer CUR and
+  //   phase 1: fragment reads of slice 0 of tile kt+1; the A chunks of tile kt+2 go to buffer CUR and
   //            are reloaded with those of tile kt+3.
   // Every chunk is so in flight for one whole k-step.
-#define AXONN_MFMA(F, q) mfma16_acc(acc[(q) >> 3][(q) & 7], fb[F][(q) & 7], fa[F][(q) >> 3]);
 #define AXONN_KSTEP(CUR)                                                                       \
-  _Pragma("unroll") for (int q = 0; q < 64; ++q) {                                             \
+  _Pragma("unroll") for (int q = 0; q < NM; ++q) {                                             \
     AXONN_MFMA(0, q)                                                                           \
-    if ((q & 3) == 0) { AXONN_FRAG(1, CUR, 1, q >> 2) }                                        \
-    if (q < 32 && (q & 3) == 2) { AXONN_SSTORE_CHUNK((CUR) ^ 1, 8 + (q >> 2)) }                \
-    if (q >= 32 && (q & 3) == 2) { AXONN_GLOAD_CHUNK(8 + ((q - 32) >> 2)) }                    \
+    { const int f = item_at(q, NF, 0, NM - 3); if (f >= 0) { AXONN_FRAG(1, CUR, 1, f) } }      \
+    { const int c = item_at(q, NCB, 1, NM / 2 - 1); if (c >= 0) { AXONN_STORE_B((CUR) ^ 1, c) } } \
+    { const int c = item_at(q, NCB, NM / 2 + 1, NM / 2 - 1); if (c >= 0) { AXONN_LOAD_B(c) } } \
     __builtin_amdgcn_sched_barrier(0);                                                         \
   }                                                                                            \
   AXONN_GLOAD_END()                                                                            \
@@ -518,13 +541,11 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
     __builtin_amdgcn_sched_barrier(0);                                                         \
   }                                                                                            \
   lds_barrier();                                                                               \
-  _Pragma("unroll") for (int q = 6; q < 64; ++q) {                                             \
+  _Pragma("unroll") for (int q = 6; q < NM; ++q) {                                             \
     AXONN_MFMA(1, q)                                                                           \
-    /* fragment f at MFMA 8 + 3f + f/2 (f = 0..15), chunk c stored at 10 + 6c, reloaded at 13 + 6c */ \
-    if (q >= 8 && (q - 8) % 7 == 0) { AXONN_FRAG(0, (CUR) ^ 1, 0, 2 * ((q - 8) / 7)) }         \
-    if (q >= 8 && (q - 8) % 7 == 3) { AXONN_FRAG(0, (CUR) ^ 1, 0, 2 * ((q - 8) / 7) + 1) }     \
-    if (q >= 10 && (q - 10) % 6 == 0 && (q - 10) / 6 < 8) { AXONN_SSTORE_CHUNK(CUR, (q - 10) / 6) } \
-    if (q >= 13 && (q - 13) % 6 == 0 && (q - 13) / 6 < 8) { AXONN_GLOAD_CHUNK((q - 13) / 6) }  \
+    { const int f = item_at(q, NF, 8, NM - 8); if (f >= 0) { AXONN_FRAG(0, (CUR) ^ 1, 0, f) } } \
+    { const int c = item_at(q, NCA, 9, NM - 12); if (c >= 0) { AXONN_STORE_A(CUR, c) } }       \
+    { const int c = item_at(q, NCA, 11, NM - 12); if (c >= 0) { AXONN_LOAD_A(c) } }            \
     __builtin_amdgcn_sched_barrier(0);                                                         \
   }
 
@@ -537,26 +558,32 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
   bf16x8 fa[2][TM], fb[2][TN];
 
-  // prologue: tile 0 in buffer 0; chunks 0..7 of tile 1 in buffer 1 and its other chunks in registers;
-  // chunks 0..7 of tile 2 on their way (tiles that do not exist read as zeros)
+  // prologue: tile 0 in buffer 0; the A chunks of tile 1 in buffer 1 and its B chunks in registers;
+  // the A chunks of tile 2 on their way (tiles that do not exist read as zeros)
   AXONN_GLOAD_BEGIN()
 #pragma unroll
-  for (int q = 0; q < 16; ++q) { AXONN_GLOAD_CHUNK(q) }
+  for (int c = 0; c < NCA; ++c) { AXONN_LOAD_A(c) }
+#pragma unroll
+  for (int c = 0; c < NCB; ++c) { AXONN_LOAD_B(c) }
   AXONN_GLOAD_END()
 #pragma unroll
-  for (int q = 0; q < 16; ++q) { AXONN_SSTORE_CHUNK(0, q) }
+  for (int c = 0; c < NCA; ++c) { AXONN_STORE_A(0, c) }
+#pragma unroll
+  for (int c = 0; c < NCB; ++c) { AXONN_STORE_B(0, c) }
   AXONN_GLOAD_BEGIN()
 #pragma unroll
-  for (int q = 0; q < 16; ++q) { AXONN_GLOAD_CHUNK(q) }
+  for (int c = 0; c < NCA; ++c) { AXONN_LOAD_A(c) }
+#pragma unroll
+  for (int c = 0; c < NCB; ++c) { AXONN_LOAD_B(c) }
   AXONN_GLOAD_END()
 #pragma unroll
-  for (int q = 0; q < 8; ++q) { AXONN_SSTORE_CHUNK(1, q) }
+  for (int c = 0; c < NCA; ++c) { AXONN_STORE_A(1, c) }
   AXONN_GLOAD_BEGIN()
 #pragma unroll
-  for (int q = 0; q < 8; ++q) { AXONN_GLOAD_CHUNK(q) }
+  for (int c = 0; c < NCA; ++c) { AXONN_LOAD_A(c) }
   lds_barrier();
 #pragma unroll
-  for (int q = 0; q < 16; ++q) { AXONN_FRAG(0, 0, 0, q) }
+  for (int f = 0; f < NF; ++f) { AXONN_FRAG(0, 0, 0, f) }
   asm volatile("s_nop 7" ::: "memory");      // accumulators were just zeroed: settle before the first MFMA
   // two k-steps per iteration so that the buffer index is a constant; an odd tile count is padded
   // with a tile of zeros
@@ -566,208 +593,20 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
   }
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // last MFMAs drain before the results are read
 #undef AXONN_GLOAD_BEGIN
-#undef AXONN_GLOAD_CHUNK
+#undef AXONN_LOAD_A
+#undef AXONN_LOAD_B
 #undef AXONN_GLOAD_END
-#undef AXONN_SSTORE_CHUNK
+#undef AXONN_STORE_A
+#undef AXONN_STORE_B
 #undef AXONN_FRAG
 #undef AXONN_MFMA
 #undef AXONN_KSTEP
 
   lds_barrier();                                          // every wave is done with the tiles in LDS
-  gemm_epilogue_staged<EPI>(acc, g, m0 + wm * 128, n0 + wn * 128, lane,
-                            reinterpret_cast<float*>(smem) + wave * kStageFloatsPerWave);
+  gemm_epilogue_staged<EPI, TN>(acc, g, m0 + wm * 128, n0 + wn * (16 * TN), lane,
+                                reinterpret_cast<float*>(smem) + wave * StageLayout<TN>::FLOATS_PER_WAVE);
 #undef sA
 #undef sB
-}
-
-// ------------------------------------------------------------------------------------------
-// Large-problem kernel with asynchronous tile copies: same 256 x 256 block tile and 2 x 2 waves as
-// above, but the tiles go from global memory straight into LDS (buffer loads with the LDS bit: lane l
-// of a wave deposits its 16 bytes at M0 + 16*l), without passing through registers or LDS-store
-// instructions.  The k dimension advances in sub-tiles of 32 through a ring of four LDS stages; one
-// sub-tile is two phases of 16 MFMAs, with one barrier in between:
-//   phase A: MFMAs on k slice 0 of sub-tile t, LDS reads of slice 1;
-//   wait until this thread's copies of sub-tile t+1 have landed, barrier (now every wave has also
-//   finished reading stage t%4);
-//   phase B: MFMAs on slice 1, LDS reads of slice 0 of sub-tile t+1, and the copies of sub-tile t+4
-//   into stage t%4 are issued -- three sub-tiles of MFMA work ahead of their use.
-// Copies deposit 1 KiB per wave contiguously, so tiles cannot be padded; bank conflicts are avoided by
-// permuting the 16-byte chunks instead (which chunk a lane fetches is free):
-//   k-contiguous operand, stored [row][32 k] = 4 chunks per row: chunk c of row r sits at position
-//     c ^ ((r >> 1) & 3) -- 8 consecutive rows put the same c at 8 different 16-byte bank groups;
-//   k-strided operand, stored [k][256 rows] = 8 units of 64 bytes per k: unit u of row k sits at
-//     u ^ (k & 1), the same bank pattern as padding each k row by 64 bytes.
-__device__ __forceinline__ void lds_dma16(u32x4 rsrc, uint32_t voffset, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
-               :: "s"(lds_addr), "v"(voffset), "s"(rsrc) : "memory");
-}
-
-__device__ __forceinline__ u32x4 make_rsrc_words(const void* p, uint32_t bytes) {
-  const uint64_t a = (uint64_t)p;
-  return u32x4{(uint32_t)a, (uint32_t)(a >> 32) & 0xffffu, bytes, 0x00020000u};
-}
-
-template <bool A_KC, bool B_KC, int EPI>
-__global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
-  constexpr int BM = 256, BN = 256, BK = 32, NST = 4, TM = 4, TN = 4;
-  constexpr int OPB = 16384;                 // bytes of one operand's sub-tile
-  constexpr int STB = 2 * OPB;               // bytes of one stage (A then B)
-  __shared__ __align__(1024) char smem[NST * STB];
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave >> 1, wn = wave & 1;
-
-  int pid = blockIdx.x;
-  const int nblk = gridDim.x;
-  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
-  constexpr int BAND = 8;
-  const int band_tiles = BAND * g.tiles_n;
-  const int band = pid / band_tiles, in_band = pid - band * band_tiles;
-  const int band_rows = min(BAND, g.tiles_m - band * BAND);
-  const int tm = band * BAND + in_band % band_rows, tn = in_band / band_rows;
-  const int m0 = tm * BM, n0 = tn * BN;
-
-  // ---- copy side.  Copy j (0..3) of a wave fills LDS bytes [(4j + wave) KiB, +1 KiB) of the operand's
-  // sub-tile; v? is this lane's byte offset from the segment base for j = 0, j? the stride in j, s? the
-  // advance per sub-tile.
-  const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
-  uint32_t va, vb, ja, jb, sa, sb, nra, nrb;
-  int kca = 0, kcb = 0;
-  if (A_KC) {
-    const int row = wave * 16 + (lane >> 2), c = (lane & 3) ^ ((lane >> 3) & 3);
-    va = ((uint32_t)(m0 + row) * lda + c * 8) * 2u; ja = 64u * lda * 2u; sa = BK * 2u;
-    kca = c * 8; nra = (uint32_t)g.M * lda * 2u;
-  } else {
-    const int kl = wave * 2 + (lane >> 5), c = (lane & 31) ^ ((lane >> 5) << 2);
-    va = (m0 + c * 8 < g.M) ? ((uint32_t)kl * lda + m0 + c * 8) * 2u : kOutOfRange;
-    ja = 8u * lda * 2u; sa = BK * lda * 2u; nra = (uint32_t)g.K * lda * 2u;
-  }
-  if (B_KC) {
-    const int row = wave * 16 + (lane >> 2), c = (lane & 3) ^ ((lane >> 3) & 3);
-    vb = ((uint32_t)(n0 + row) * ldb + c * 8) * 2u; jb = 64u * ldb * 2u; sb = BK * 2u;
-    kcb = c * 8; nrb = (uint32_t)g.N * ldb * 2u;
-  } else {
-    const int kl = wave * 2 + (lane >> 5), c = (lane & 31) ^ ((lane >> 5) << 2);
-    vb = (n0 + c * 8 < g.N) ? ((uint32_t)kl * ldb + n0 + c * 8) * 2u : kOutOfRange;
-    jb = 8u * ldb * 2u; sb = BK * ldb * 2u; nrb = (uint32_t)g.K * ldb * 2u;
-  }
-  const uint32_t lds0 = (uint32_t)(uintptr_t)(AXONN_LDS char*)smem + (uint32_t)wave * 1024u;
-
-  // ---- fragment side: per-lane byte offsets inside an operand's sub-tile (two per operand; the
-  // rest of an address is a compile-time constant)
-  uint32_t fa0, fa1, fb0, fb1;
-  {
-    const int t = lane & 15, half = (lane >> 4) & 1, gq = lane >> 5, kq = t >> 2;
-    const uint32_t kc_lane = (uint32_t)(lane & 31) * 64u + (uint32_t)((gq ^ ((lane >> 1) & 3)) * 16);
-    const uint32_t ks_lane = (uint32_t)(8 * gq + kq) * 512u + (uint32_t)(16 * half + 4 * (t & 3)) * 2u;
-    const uint32_t swz = (uint32_t)(kq & 1) * 64u;
-    if (A_KC) { fa0 = (uint32_t)wm * 8192u + kc_lane; fa1 = fa0 ^ 32u; }
-    else      { fa0 = (uint32_t)wm * 256u + ks_lane + swz; fa1 = (uint32_t)wm * 256u + ks_lane + (64u ^ swz); }
-    if (B_KC) { fb0 = (uint32_t)wn * 8192u + kc_lane; fb1 = fb0 ^ 32u; }
-    else      { fb0 = (uint32_t)wn * 256u + ks_lane + swz; fb1 = (uint32_t)wn * 256u + ks_lane + (64u ^ swz); }
-  }
-
-  const int K = g.K;
-  const int tps = (K + BK - 1) / BK;      // sub-tiles per segment
-  const int nsub = tps * g.n_seg;
-  u32x4 rsa = make_rsrc_words(g.A_seg[0], nra), rsb = make_rsrc_words(g.B_seg[0], nrb);
-  int ld_seg = 0, ld_kin = 0;            // segment and sub-tile within it of the NEXT sub-tile to fetch
-  uint32_t xa, xb;
-
-#define AXONN_COPY_BEGIN()                                                                     \
-  {                                                                                            \
-    const bool live = ld_seg < g.n_seg;                                                        \
-    xa = ((live & (!A_KC | (ld_kin * BK + kca < K))) ? va : kOutOfRange) + (uint32_t)ld_kin * sa; \
-    xb = ((live & (!B_KC | (ld_kin * BK + kcb < K))) ? vb : kOutOfRange) + (uint32_t)ld_kin * sb; \
-  }
-  // copy q of the sub-tile (0..3 operand A, 4..7 operand B) into stage S
-#define AXONN_COPY_CHUNK(S, q)                                                                 \
-  if ((q) < 4) lds_dma16(rsa, xa + ((q) & 3) * ja, lds0 + (S) * STB + ((q) & 3) * 4096);       \
-  else         lds_dma16(rsb, xb + ((q) & 3) * jb, lds0 + (S) * STB + OPB + ((q) & 3) * 4096);
-#define AXONN_COPY_END()                                                                       \
-  if (++ld_kin == tps) {                                                                       \
-    ld_kin = 0;                                                                                \
-    ++ld_seg;                                                                                  \
-    const int sidx = ld_seg < g.n_seg ? ld_seg : 0;                                            \
-    rsa = make_rsrc_words(g.A_seg[sidx], nra);                                                 \
-    rsb = make_rsrc_words(g.B_seg[sidx], nrb);                                                 \
-  }
-  // Fragment q of k slice kk (0 or 1) of the sub-tile in stage S -> fragment set F, in the order the
-  // MFMAs of the slice consume them: a0 b0 b1 b2 b3 a1 a2 a3.
-#define AXONN_FRAG_LOAD(dst, KC, f0, f1, base, i, kk)                                          \
-  if (KC) {                                                                                    \
-    dst = *reinterpret_cast<const bf16x8*>(smem + (base) + (i) * 2048 + ((kk) ? f1 : f0));     \
-  } else {                                                                                     \
-    union { bf16x8 v; short4v h[2]; } u_;                                                      \
-    const char* p_ = smem + (base) + ((i) >> 1) * 128 + (kk) * 8192 + (((i) & 1) ? f1 : f0);   \
-    u_.h[0] = lds_read_tr16(reinterpret_cast<const bf16_t*>(p_));                              \
-    u_.h[1] = lds_read_tr16(reinterpret_cast<const bf16_t*>(p_ + 2048));                       \
-    dst = u_.v;                                                                                \
-  }
-#define AXONN_FRAG(F, S, kk, q)                                                                \
-  if ((q) == 0 || ((q) >= 5 && (q) < 8)) {                                                     \
-    const int i = (q) == 0 ? 0 : (q) - 4;                                                      \
-    AXONN_FRAG_LOAD(fa[F][i], A_KC, fa0, fa1, (S) * STB, i, kk)                                \
-  } else if ((q) < 5) {                                                                        \
-    const int j = (q) - 1;                                                                     \
-    AXONN_FRAG_LOAD(fb[F][j], B_KC, fb0, fb1, (S) * STB + OPB, j, kk)                          \
-  }
-#define AXONN_SUBTILE(S)                                                                       \
-  _Pragma("unroll") for (int q = 0; q < 16; ++q) {                                             \
-    acc[q >> 2][q & 3] = mfma32(fb[0][q & 3], fa[0][q >> 2], acc[q >> 2][q & 3]);              \
-    AXONN_FRAG(1, S, 1, q)                                                                     \
-    __builtin_amdgcn_sched_barrier(0);                                                         \
-  }                                                                                            \
-  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");                                            \
-  lds_barrier();                                                                               \
-  AXONN_COPY_BEGIN()                                                                           \
-  _Pragma("unroll") for (int q = 0; q < 16; ++q) {                                             \
-    acc[q >> 2][q & 3] = mfma32(fb[1][q & 3], fa[1][q >> 2], acc[q >> 2][q & 3]);              \
-    AXONN_FRAG(0, ((S) + 1) & 3, 0, q)                                                         \
-    if (q >= 8) { AXONN_COPY_CHUNK(S, q - 8) }                                                 \
-    __builtin_amdgcn_sched_barrier(0);                                                         \
-  }                                                                                            \
-  AXONN_COPY_END()
-
-  floatx16 acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  bf16x8 fa[2][TM], fb[2][TN];
-
-  // prologue: sub-tiles 0..3 on their way into stages 0..3 (sub-tiles that do not exist read as zeros)
-#pragma unroll
-  for (int st = 0; st < NST; ++st) {
-    AXONN_COPY_BEGIN()
-#pragma unroll
-    for (int q = 0; q < 8; ++q) { AXONN_COPY_CHUNK(st, q) }
-    AXONN_COPY_END()
-  }
-  asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-  lds_barrier();
-#pragma unroll
-  for (int q = 0; q < 8; ++q) { AXONN_FRAG(0, 0, 0, q) }
-  // four sub-tiles per iteration so that the stage index is a constant; the count is padded with
-  // sub-tiles of zeros
-  for (int t = 0; t < nsub; t += NST) {
-    AXONN_SUBTILE(0)
-    AXONN_SUBTILE(1)
-    AXONN_SUBTILE(2)
-    AXONN_SUBTILE(3)
-  }
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-#undef AXONN_COPY_BEGIN
-#undef AXONN_COPY_CHUNK
-#undef AXONN_COPY_END
-#undef AXONN_FRAG_LOAD
-#undef AXONN_FRAG
-#undef AXONN_SUBTILE
-
-  gemm_epilogue<EPI, TM, TN>(acc, g, m0 + wm * 128, n0 + wn * 128, lane);
 }
 
 // Only the (layout, epilogue) pairs the layer uses are instantiated: forward maps take the
@@ -805,23 +644,15 @@ static hipError_t launch_cfg(int epi, GemmArgs g, hipStream_t s) {
   return hipGetLastError();
 }
 
-static bool use_dma_kernel() {
-  static const bool v = [] { const char* e = getenv("AXONN_GEMM_DMA"); return e && *e == '1'; }();
-  return v;
-}
-
-template <bool A_KC, bool B_KC>
+template <bool A_KC, bool B_KC, int TN>
 static hipError_t launch_big(int epi, GemmArgs g, hipStream_t s) {
   g.tiles_m = (g.M + 255) / 256;
-  g.tiles_n = (g.N + 255) / 256;
+  g.tiles_n = (g.N + 32 * TN - 1) / (32 * TN);
   const dim3 grid(g.tiles_m * g.tiles_n), block(256);
 #define AXONN_GEMM_CASE(E)                                                                      \
   case E:                                                                                       \
     if constexpr (epilogue_allowed(A_KC, B_KC, E)) {                                            \
-      if (use_dma_kernel())                                                                     \
-        hipLaunchKernelGGL((gemm_dma_kernel<A_KC, B_KC, E>), grid, block, 0, s, g);             \
-      else                                                                                      \
-        hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, E>), grid, block, 0, s, g);             \
+      hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, E, TN>), grid, block, 0, s, g);           \
       break;                                                                                    \
     } else {                                                                                    \
       return hipErrorInvalidValue;                                                              \
@@ -845,13 +676,37 @@ static bool fits_32bit_offsets(int64_t rows, int64_t ld) {
 }
 
 // Number of 256 x 256 tiles from which the large-problem kernel is used (half the CUs by default);
-// AXONN_GEMM_BIG_MIN_TILES overrides it, for tuning.
+// AXONN_GEMM_BIG_MIN_TILES overrides it, AXONN_GEMM_TILE_N (160, 192 or 256) fixes the block width: both
+// for tuning.
+static int64_t env_int(const char* name, int64_t dflt) {
+  const char* e = getenv(name);
+  return e && *e ? (int64_t)atoll(e) : dflt;
+}
 static int64_t big_tile_threshold() {
-  static const int64_t v = [] {
-    const char* e = getenv("AXONN_GEMM_BIG_MIN_TILES");
-    return e && *e ? (int64_t)atoll(e) : (int64_t)128;
-  }();
+  static const int64_t v = env_int("AXONN_GEMM_BIG_MIN_TILES", 128);
   return v;
+}
+
+// Block width of the large-problem kernel for an M x N x (nk k-steps) problem: the one with the lowest
+// modelled time (when the launch has the chip to itself; otherwise the widest).  A round (up to 256 tiles, one per CU) costs a fixed part (fill, epilogue) plus nk
+// k-steps whose duration grows with the number of MFMAs (8 * TN per phase) on top of a part that does
+// not (the A tile is fetched whatever the width).  Constants in microseconds, fitted to measurements
+// on full rounds of the 12B-class shapes.
+static int choose_tn(int64_t M, int64_t N, int64_t nk, bool concurrent) {
+  static const int64_t forced = env_int("AXONN_GEMM_TILE_N", 0);
+  if (forced == 160) return 5;
+  if (forced == 192) return 6;
+  if (forced == 256 || concurrent) return 8;
+  const int cand[3] = {8, 6, 5};
+  int best = 8;
+  double best_cost = 0;
+  for (int tn : cand) {
+    const int64_t tiles = ((M + 255) / 256) * ((N + 32 * tn - 1) / (32 * tn));
+    const int64_t rounds = (tiles + 255) / 256;
+    const double cost = rounds * (20.0 + nk * (0.55 + 0.15 * tn));
+    if (best_cost == 0 || cost < best_cost * 0.98) { best = tn; best_cost = cost; }
+  }
+  return best;
 }
 
 template <bool A_KC, bool B_KC>
@@ -859,8 +714,14 @@ static hipError_t launch_layout(int epi, const GemmArgs& g, hipStream_t s) {
   // Large tile when the problem fills the chip with it, smaller tile otherwise.
   const int64_t big_tiles = (int64_t)((g.M + 255) / 256) * ((g.N + 255) / 256);
   if (big_tiles >= big_tile_threshold()) {
-    if (fits_32bit_offsets(A_KC ? g.M : g.K, g.lda) && fits_32bit_offsets(B_KC ? g.N : g.K, g.ldb))
-      return launch_big<A_KC, B_KC>(epi, g, s);
+    if (fits_32bit_offsets(A_KC ? g.M : g.K, g.lda) && fits_32bit_offsets(B_KC ? g.N : g.K, g.ldb)) {
+      const int64_t nk = (int64_t)((g.K + 63) / 64) * g.n_seg;
+      switch (choose_tn(g.M, g.N, nk, g.concurrent != 0)) {
+        case 5: return launch_big<A_KC, B_KC, 5>(epi, g, s);
+        case 6: return launch_big<A_KC, B_KC, 6>(epi, g, s);
+        default: return launch_big<A_KC, B_KC, 8>(epi, g, s);
+      }
+    }
     return launch_cfg<256, 256, 64, 2, 4, A_KC, B_KC>(epi, g, s);
   }
   return launch_cfg<128, 128, 64, 2, 2, A_KC, B_KC>(epi, g, s);

@@ -185,6 +185,10 @@ int check_launch(hipError_t e, const char* what) {
   return AXONN_OK;
 }
 
+// Set while axonn_stage_run enqueues work on several streams: the GEMMs then share the chip with the
+// kernels of the other streams.
+static thread_local int t_concurrent = 0;
+
 int gemm(bool a_kc, bool b_kc, int epi, int M, int N, int K, const void* A, int64_t lda,
          const void* B, int64_t ldb, void* C, int64_t ldc, const void* bias, const void* res,
          int64_t ld_res, void* aux, int64_t ld_aux, int accumulate, hipStream_t s) {
@@ -194,6 +198,7 @@ int gemm(bool a_kc, bool b_kc, int epi, int M, int N, int K, const void* A, int6
   g.bias = (const bf16_t*)bias; g.res = (const bf16_t*)res; g.aux = (bf16_t*)aux;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ld_res = ld_res; g.ld_aux = ld_aux;
   g.M = M; g.N = N; g.K = K; g.accumulate = accumulate; g.tiles_m = g.tiles_n = 0;
+  g.concurrent = t_concurrent;
   ProfScope ps(a_kc ? (b_kc ? PC_GEMM_DGRAD : PC_GEMM_FWD) : PC_GEMM_WGRAD, s);
   return check_launch(launch_gemm(a_kc, b_kc, epi, g, s), "gemm");
 }
@@ -251,6 +256,7 @@ int forward_layers(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s) {
       g.B_seg[0] = g.B_seg[1] = param_ptr(st, l, P_WQKV);
       g.n_seg = 2; g.C = a.qkv; g.bias = param_ptr(st, l, P_BQKV);
       g.lda = h; g.ldb = 3 * h; g.ldc = 3 * h; g.M = T; g.N = 3 * h; g.K = h;
+      g.concurrent = t_concurrent;
       ProfScope ps(PC_GEMM_FWD, s);
       AX_TRY(check_launch(launch_gemm(true, false, EPI_BIAS, g, s), "gemm (split input)"));
     } else {
@@ -323,6 +329,7 @@ int gemm_seg(int epi, int M, int N, int K, const bf16_t* const* A, int64_t lda, 
   for (int i = 0; i < n_seg; ++i) { g.A_seg[i] = A[i]; g.B_seg[i] = B[i]; }
   g.n_seg = n_seg; g.C = C; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
   g.M = M; g.N = N; g.K = K; g.accumulate = accumulate;
+  g.concurrent = t_concurrent;
   ProfScope ps(PC_GEMM_WGRAD, s);
   return check_launch(launch_gemm(false, false, epi, g, s), "gemm (weight gradient)");
 }
@@ -741,6 +748,10 @@ int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream) {
   // weight-gradient passes get a stream of their own when there is more than one, so that they
   // overlap the next microbatches' work
   hipStream_t ws = st->streams[0];
+  struct ConcurrentScope {
+    explicit ConcurrentScope(int v) { t_concurrent = v; }
+    ~ConcurrentScope() { t_concurrent = 0; }
+  } concurrent_scope(n_streams > 1 ? 1 : 0);
   if (n_streams > 1) {
     if (!st->wgrad_stream) HIP_TRY(hipStreamCreateWithFlags(&st->wgrad_stream, hipStreamNonBlocking));
     ws = st->wgrad_stream;

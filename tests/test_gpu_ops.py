@@ -29,7 +29,11 @@ GEMM_SHAPES = [
     (200, 136, 72),      # ragged in every dimension (multiples of 8 only)
     (8, 8, 8),           # degenerate minimum
     (264, 2056, 1032),   # ragged tails on a multi-tile problem
-    (2056, 4104, 264),   # big-tile kernel: ragged rows and columns, k tail, odd number of k-tiles
+    # big-tile kernel, ragged rows and columns, k tail, odd number of k-tiles; the launcher picks
+    # block widths 160, 192 and 256 for these three
+    (2056, 4104, 264),
+    (2056, 4512, 264),
+    (2056, 5464, 264),
     (4096, 2048, 448),   # big-tile kernel: odd number of k-tiles, no tail
 ]
 
