@@ -25,7 +25,7 @@ import numpy as np  # noqa: E402
 
 # HBM bytes per launch of the weight-gradient GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and the scaling by a plain copy under profiles/); keyed by (config, wgrad_group, grad_accum).
-WGRAD_TRAFFIC_BYTES = {("12b", 2, "fp32"): 1.674e9}   # profiles/gemm_wgrad_12b_hbm_traffic.md
+WGRAD_TRAFFIC_BYTES = {("12b", 2, "bf16"): 1.363e9}   # profiles/gemm_wgrad_12b_hbm_traffic.md
 
 
 def parse():
@@ -223,7 +223,7 @@ def main():
                 kern[cat]["tflops"] = per_layer_mb * sh.n_layers * M / (kern[cat]["total_ms"] * 1e-3) / 1e12
         out["kernels"] = kern
         # roofline of the largest single kernel by time: the weight-gradient GEMM
-        # (gemm_kernel<256,256,64,2,4,false,false,EPI_ACC_*>), one launch = one weight of one layer for a
+        # (gemm_big_kernel<false,false,EPI_ACC_*,8>), one launch = one weight of one layer for a
         # group of microbatches; its four shapes average to per_layer_mb/4 FLOP per microbatch
         dom = "gemm_wgrad"
         if dom in kern:
@@ -232,7 +232,7 @@ def main():
             out["roofline"] = {"bound": "mfma", "achieved": ach, "peak": flops.PEAK_BF16_DENSE_TFLOPS,
                                "unit": "TFLOP/s", "frac": ach / flops.PEAK_BF16_DENSE_TFLOPS,
                                "traffic": WGRAD_TRAFFIC_BYTES.get((args.config, args.wgrad_group, args.grad_accum)),
-                               "kernel": "axonn::gemm_kernel<256,256,64,2,4,false,false,%d> (weight gradient)"
+                               "kernel": "axonn::gemm_big_kernel<false,false,%d,8> (weight gradient)"
                                          % (4 if args.grad_accum == "fp32" else 5),
                                "avg_launch_ms": kern[dom]["avg_ms"], "flops_per_launch": per_launch,
                                "measured": "launch timing events on the launching stream, one single-stream batch"}
