@@ -64,18 +64,37 @@ __device__ __forceinline__ bf16x8 global_frag(const bf16_t* base, int64_t ld, in
   return *reinterpret_cast<const bf16x8*>(base + (int64_t)row * ld + k0 + 8 * (lane >> 5));
 }
 
+// Work assignment of the attention kernels: block id of a 1-D grid of n_tiles * n_bh blocks -> (rank of
+// the tile, batch*head index).  Workgroups are dealt round-robin to the 8 XCDs, each with an L2 of its
+// own, so XCD x gets ids x, x+8, ...: those are mapped to a contiguous range of (batch, head) pairs, so
+// that the K/V (or Q/dO) rows of a head are fetched into one L2 instead of all eight; inside the range
+// the tiles of rank 0 (the longest-running ones under causal masking) of every head come first.
+__device__ __forceinline__ void attn_block(int n_bh, int& rank, int& bh) {
+  const int id = blockIdx.x;
+  if ((gridDim.x & 7) == 0 && (n_bh & 7) == 0) {
+    const int per_xcd = n_bh >> 3, j = id >> 3;        // j-th block of XCD id % 8
+    rank = j / per_xcd;
+    bh = (id & 7) * per_xcd + j % per_xcd;
+  } else {
+    rank = id / n_bh;
+    bh = id % n_bh;
+  }
+}
+
 // =============================================================================== forward
 // grid: (ceil(s/128), b*a); 4 waves; wave w owns queries q0 + 32w .. +31.
 template <int D>
-__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int s, int a, const bf16_t* __restrict__ qkv,
+__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int s, int a, int n_bh, const bf16_t* __restrict__ qkv,
                                                        bf16_t* __restrict__ o,
                                                        float* __restrict__ lse) {
   constexpr int BKV = 64, LDK = D + 8, LDV = D + 32, DT = D / 32, KK = D / 16;
   __shared__ __align__(16) bf16_t sK[BKV * LDK];
   __shared__ __align__(16) bf16_t sV[BKV * LDV];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-  const int qt = gridDim.x - 1 - blockIdx.x;  // longest rows first
-  const int bi = blockIdx.y / a, hd = blockIdx.y % a;
+  int rank, bh;
+  attn_block(n_bh, rank, bh);
+  const int qt = (s + 127) / 128 - 1 - rank;  // longest rows first
+  const int bi = bh / a, hd = bh % a;
   const int h = a * D;
   const int64_t ld = 3 * (int64_t)h;
   const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * D;
@@ -212,7 +231,7 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(int64_t n_chunks, int s
 // at or below the diagonal.
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
-    int s, int a, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+    int s, int a, int n_bh, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
     const float* __restrict__ lse, const float* __restrict__ delta, bf16_t* __restrict__ dqkv) {
   constexpr int BQ = 64, LDQ = D + 8, DT = D / 32, KK = D / 16;
   __shared__ __align__(16) bf16_t sQ[BQ * LDQ];
@@ -220,7 +239,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
   __shared__ __align__(16) float s_lse[BQ];
   __shared__ __align__(16) float s_delta[BQ];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-  const int bi = blockIdx.y / a, hd = blockIdx.y % a;
+  int rank, bh;
+  attn_block(n_bh, rank, bh);                  // key tile `rank` walks n_tiles - rank query tiles: longest first
+  const int bi = bh / a, hd = bh % a;
   const int h = a * D;
   const int64_t ld = 3 * (int64_t)h;
   const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * D;
@@ -229,7 +250,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
   const bf16_t* dob = dout + (int64_t)bi * s * h + hd * D;
   const float* lse_b = lse + ((int64_t)bi * a + hd) * s;
   const float* delta_b = delta + ((int64_t)bi * a + hd) * s;
-  const int k0 = blockIdx.x * 128, kw0 = k0 + 32 * wave, kj = kw0 + (lane & 31);
+  const int k0 = rank * 128, kw0 = k0 + 32 * wave, kj = kw0 + (lane & 31);
   const float scale = rsqrtf((float)D), scale_log2 = kLog2e * scale;
 
   bf16x8 kf[KK], vf[KK];
@@ -332,14 +353,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
 // to the diagonal (same traversal as the forward kernel).
 template <int D>
 __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
-    int s, int a, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+    int s, int a, int n_bh, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
     const float* __restrict__ lse, const float* __restrict__ delta, bf16_t* __restrict__ dqkv) {
   constexpr int BKV = 64, LDK = D + 8, DT = D / 32, KK = D / 16;
   __shared__ __align__(16) bf16_t sK[BKV * LDK];
   __shared__ __align__(16) bf16_t sV[BKV * LDK];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
-  const int qt = gridDim.x - 1 - blockIdx.x;
-  const int bi = blockIdx.y / a, hd = blockIdx.y % a;
+  int rank, bh;
+  attn_block(n_bh, rank, bh);
+  const int qt = (s + 127) / 128 - 1 - rank;
+  const int bi = bh / a, hd = bh % a;
   const int h = a * D;
   const int64_t ld = 3 * (int64_t)h;
   const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * D;
@@ -424,11 +447,11 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
 // ------------------------------------------------------------------------- launchers
 hipError_t launch_attention_fwd(int b, int s, int a, int d, const void* qkv, void* o, float* lse,
                                 hipStream_t st) {
-  const dim3 grid((unsigned)((s + 127) / 128), (unsigned)(b * a));
+  const dim3 grid((unsigned)(((s + 127) / 128) * b * a));
   if (d == 128)
-    hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (bf16_t*)o, lse);
+    hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (bf16_t*)o, lse);
   else if (d == 64)
-    hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (bf16_t*)o, lse);
+    hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (bf16_t*)o, lse);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();
@@ -439,15 +462,15 @@ hipError_t launch_attention_bwd(int b, int s, int a, int d, const void* qkv, con
                                 hipStream_t st) {
   const int64_t n_chunks = (int64_t)b * s * a * d / 8;
   const dim3 gd((unsigned)((n_chunks + 255) / 256));
-  const dim3 grid((unsigned)((s + 127) / 128), (unsigned)(b * a));
+  const dim3 grid((unsigned)(((s + 127) / 128) * b * a));
   if (d == 128) {
     hipLaunchKernelGGL(attn_delta_kernel<128>, gd, dim3(256), 0, st, n_chunks, s, a, (const bf16_t*)o, (const bf16_t*)dout, delta);
-    hipLaunchKernelGGL(attn_bwd_dkdv_kernel<128>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+    hipLaunchKernelGGL(attn_bwd_dkdv_kernel<128>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
   } else if (d == 64) {
     hipLaunchKernelGGL(attn_delta_kernel<64>, gd, dim3(256), 0, st, n_chunks, s, a, (const bf16_t*)o, (const bf16_t*)dout, delta);
-    hipLaunchKernelGGL(attn_bwd_dkdv_kernel<64>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(256), 0, st, s, a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+    hipLaunchKernelGGL(attn_bwd_dkdv_kernel<64>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+    hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
   } else {
     return hipErrorInvalidValue;
   }
