@@ -202,19 +202,33 @@ template <typename T>
 __device__ __forceinline__ void put_sum(T* dst, int n, float v, int acc_mode) {
   dst[n] = (T)((acc_mode == 2 ? (float)dst[n] : 0.f) + v);
 }
+// A block owns 64 columns; its four wavefronts each sum every fourth row block (loads independent of one
+// another, so they are all in flight at once), and the four sums are combined through LDS in a fixed order.
 template <int KSUM>
 __global__ __launch_bounds__(256) void colsum_final_kernel(int nrb, int N,
                                                            const float* __restrict__ partial,
                                                            void* __restrict__ out0,
                                                            void* __restrict__ out1,
                                                            int acc_mode, int dst_fp32) {
-  const int n = blockIdx.x * 256 + threadIdx.x;
-  if (n >= N) return;
+  __shared__ float red[3][KSUM][64];
+  const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
+  const int n = blockIdx.x * 64 + lane;
   float s0 = 0.f, s1 = 0.f;
-  for (int rb = 0; rb < nrb; ++rb) {
-    s0 += partial[((int64_t)rb * KSUM) * N + n];
-    if (KSUM == 2) s1 += partial[((int64_t)rb * KSUM + 1) * N + n];
+  if (n < N) {
+#pragma unroll 8
+    for (int rb = q; rb < nrb; rb += 4) {
+      s0 += partial[((int64_t)rb * KSUM) * N + n];
+      if (KSUM == 2) s1 += partial[((int64_t)rb * KSUM + 1) * N + n];
+    }
   }
+  if (q > 0) {
+    red[q - 1][0][lane] = s0;
+    if (KSUM == 2) red[q - 1][KSUM - 1][lane] = s1;
+  }
+  __syncthreads();
+  if (q != 0 || n >= N) return;
+  s0 = ((s0 + red[0][0][lane]) + red[1][0][lane]) + red[2][0][lane];
+  if (KSUM == 2) s1 = ((s1 + red[0][KSUM - 1][lane]) + red[1][KSUM - 1][lane]) + red[2][KSUM - 1][lane];
   if (acc_mode == 0 || dst_fp32) {
     put_sum(reinterpret_cast<float*>(out0), n, s0, acc_mode);
     if (KSUM == 2) put_sum(reinterpret_cast<float*>(out1), n, s1, acc_mode);
@@ -332,7 +346,7 @@ hipError_t launch_layernorm_bwd(int64_t T, int64_t h, const void* dout, const vo
                      (const bf16_t*)dout, (int64_t)h, (const bf16_t*)x, stats, ws);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_final_kernel<2>, dim3((unsigned)((h + 255) / 256)), dim3(256), 0, s, nrb,
+  hipLaunchKernelGGL(colsum_final_kernel<2>, dim3((unsigned)((h + 63) / 64)), dim3(256), 0, s, nrb,
                      (int)h, (const float*)ws, dbeta, dgamma, acc_mode, dst_fp32 ? 1 : 0);
   return hipGetLastError();
 }
@@ -346,7 +360,7 @@ hipError_t launch_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, void*
                      (const bf16_t*)y, ldy, (const bf16_t*)nullptr, (const float*)nullptr, ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(colsum_final_kernel<1>, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, nrb,
+  hipLaunchKernelGGL(colsum_final_kernel<1>, dim3((unsigned)((N + 63) / 64)), dim3(256), 0, s, nrb,
                      (int)N, (const float*)ws, out, (void*)nullptr, acc_mode, dst_fp32 ? 1 : 0);
   return hipGetLastError();
 }
