@@ -191,7 +191,7 @@ def main():
         "peak_tflops_used": flops.PEAK_BF16_DENSE_TFLOPS,
         "tokens_per_s": tokens / (fb_mean * 1e-3),
         "tokens_per_s_whole_step": tokens / (wall / args.steps),
-        "fwd_bwd_ms": {"mean": fb_mean, "min": float(np.min(fb_ms))},
+        "fwd_bwd_ms": {"mean": fb_mean, "min": float(np.min(fb_ms)), "per_step": [round(float(x), 3) for x in fb_ms]},
         "tflops_paper_convention": fl_paper / (fb_mean * 1e-3) / 1e12,
         "paper_context": "49.4-54.78% of V100 fp16 peak per GPU on 48-384 V100s (whole system, counts recompute)",
     }
