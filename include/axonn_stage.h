@@ -206,8 +206,9 @@ int axonn_stage_optimizer_step(axonn_stage_t* st, double lr, double beta1, doubl
  * epilogue:
  *   0  C = bf16(acc + bias[n])                      bias may be NULL (treated as 0)
  *   1  C = bf16(acc + bias[n] + res[m,n])
- *   2  aux = bf16(acc + bias[n]);  C = bf16(GeLU(acc + bias[n]))     (exact erf GeLU)
- *   3  C = bf16(acc * GeLU'(aux[m,n]))
+ *   2  z = acc + bias[n];  C = bf16(GeLU(z));  aux = bf16(GeLU'(z))  (exact erf GeLU; the derivative is
+ *      stored instead of z, from the unrounded z, so that the backward epilogue is a multiplication)
+ *   3  C = bf16(acc * aux[m,n])                      aux = the derivative stored by epilogue 2
  *   4  C_f32 = (accumulate ? C_f32 : 0) + acc        C is float32
  *   5  C = bf16((accumulate ? float(C) : 0) + acc)
  */

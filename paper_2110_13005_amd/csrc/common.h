@@ -132,6 +132,13 @@ __device__ __forceinline__ float gelu_grad_f(float x) {
   const float cdf = normal_cdf_f(x, e);
   return cdf + x * e * 0.39894228040143267794f;
 }
+// GeLU(x) and GeLU'(x) together (they share Phi and the exponential).
+__device__ __forceinline__ void gelu_with_grad_f(float x, float& y, float& dy) {
+  float e;
+  const float cdf = normal_cdf_f(x, e);
+  y = x * cdf;
+  dy = cdf + x * e * 0.39894228040143267794f;
+}
 #endif  // __HIPCC__
 
 // --------------------------------------------------------------------- host launchers

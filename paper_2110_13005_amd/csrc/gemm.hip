@@ -109,14 +109,21 @@ __device__ __forceinline__ void epi_finish(float (&v)[4], const float (&bv)[4], 
     for (int e = 0; e < 4; ++e) v[e] += x[e];
   }
   if (EPI == EPI_BIAS_GELU) {
-    bf16x4 pv;
+    // the derivative is formed here, from the unrounded pre-activation, and stored in its place: the
+    // backward epilogue is then one multiplication
+    bf16x4 dv;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { pv[e] = (bf16_t)v[e]; v[e] = gelu_f(v[e]); }
-    *reinterpret_cast<bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n) = pv;
+    for (int e = 0; e < 4; ++e) {
+      float y, dy;
+      gelu_with_grad_f(v[e], y, dy);
+      v[e] = y;
+      dv[e] = (bf16_t)dy;
+    }
+    *reinterpret_cast<bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n) = dv;
   }
   if (EPI == EPI_DGELU) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) v[e] *= gelu_grad_f(x[e]);
+    for (int e = 0; e < 4; ++e) v[e] *= x[e];
   }
   if (EPI == EPI_ACC_F32) {
     *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(g.C) + (int64_t)m * g.ldc + n) =

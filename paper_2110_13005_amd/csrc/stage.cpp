@@ -94,7 +94,7 @@ struct TensorInfo {
 
 struct LayerStash {
   // forward activations kept for the backward pass
-  bf16_t *x, *u, *qkv, *o, *y, *w, *pre, *g;
+  bf16_t *x, *u, *qkv, *o, *y, *w, *pre, *g;   // pre: GeLU'(w W1 + b1), the derivative at the pre-activation
   bf16_t* u_lo;   // only with qkv_input_split: the part of LayerNorm-1's output that bf16 rounding dropped
   float *stats1, *stats2, *lse;
   // output gradients of the four linear maps, written by the backward pass and kept until the
@@ -596,7 +596,8 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
     CREATE_TRY(launch_fill_bf16(h, param_ptr(st, l, P_LN2G), 1.0f, nullptr));
   }
 
-  // activation stash: per layer x,u,o,y,w [T,h], qkv [T,3h], pre,g [T,f], stats [T,2]x2, lse [b,a,s]
+  // activation stash: per layer x,u,o,y,w [T,h], qkv [T,3h], pre (GeLU' of the pre-activation),g [T,f],
+  // stats [T,2]x2, lse [b,a,s]
   // plus the output gradients kept for the deferred weight gradients: dz,dy_mid [T,h], dpre [T,f], dqkv [T,3h]
   const uint64_t e_th = align_up((uint64_t)T * h * 2, 256), e_t3h = align_up((uint64_t)T * 3 * h * 2, 256),
                  e_tf = align_up((uint64_t)T * f * 2, 256), e_st = align_up((uint64_t)T * 2 * 4, 256),
