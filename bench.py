@@ -25,7 +25,7 @@ import numpy as np  # noqa: E402
 
 # HBM bytes per launch of the weight-gradient GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and the scaling by a plain copy under profiles/); keyed by (config, wgrad_group, grad_accum).
-WGRAD_TRAFFIC_BYTES = {("12b", 2, "bf16"): 1.363e9}   # profiles/gemm_wgrad_12b_hbm_traffic.md
+WGRAD_TRAFFIC_BYTES = {("12b", 3, "bf16"): 1.706e9, ("12b", 2, "bf16"): 1.363e9}   # profiles/gemm_wgrad_12b_hbm_traffic.md
 
 
 def parse():
@@ -37,7 +37,7 @@ def parse():
     ap.add_argument("--streams", type=int, default=2, help="library streams of the message-driven run")
     ap.add_argument("--pipeline-limit", type=int, default=0, help="0 = all microbatches in flight")
     ap.add_argument("--grad-accum", default="bf16", choices=["fp32", "bf16"])
-    ap.add_argument("--wgrad-group", type=int, default=2, help="microbatches per weight-gradient contraction (0 = as many as possible)")
+    ap.add_argument("--wgrad-group", type=int, default=3, help="microbatches per weight-gradient contraction (0 = as many as possible)")
     ap.add_argument("--bucket-elems", type=int, default=1 << 26)
     ap.add_argument("--no-optimizer", action="store_true", help="diagnostic: leave the Adam step out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
