@@ -192,6 +192,19 @@ __device__ __forceinline__ void gemm_epilogue_staged(const floatx4 (&acc)[8][TN]
   const bool col_ok = nl < 16 * TN && n < g.N;
   float bv[4];
   if (col_ok) load_bias4<EPI>(bv, g, n);
+  // What the epilogue reads at its output positions (residual, stored derivative, accumulating C) is
+  // loaded in batches whose loads are all in flight together: the whole wave tile at once (64 row pairs,
+  // 2 registers each) for bf16 operands, 16 row pairs at a time for an fp32 C.
+  constexpr int OB = (EPI == EPI_ACC_F32) ? 16 : 64;
+  EpiOperand opnd[OB];
+  const bool reads = epi_reads_operand<EPI>(g);
+  if (OB == 64 && reads) {
+#pragma unroll
+    for (int t = 0; t < 64; ++t) {
+      const int m = m_base + 2 * t + (lane >> 5);
+      if (m < g.M && col_ok) opnd[t] = epi_load_operand<EPI>(g, m, n);
+    }
+  }
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
 #pragma unroll
@@ -200,12 +213,9 @@ __device__ __forceinline__ void gemm_epilogue_staged(const floatx4 (&acc)[8][TN]
       for (int j = 0; j < TN; ++j)
         *reinterpret_cast<floatx4*>(stage + (16 * ii + (lane & 15)) * LD + 16 * j + 4 * (lane >> 4)) =
             acc[4 * p + ii][j];
-    // 32 row pairs per pass, 16 at a time: first the loads of whatever the epilogue reads at its
-    // output positions, all in flight together, then the arithmetic and the stores
 #pragma unroll
     for (int hh = 0; hh < 2; ++hh) {
-      EpiOperand opnd[16];
-      if (epi_reads_operand<EPI>(g)) {
+      if (OB == 16 && reads) {
 #pragma unroll
         for (int tt = 0; tt < 16; ++tt) {
           const int m = m_base + 64 * p + 2 * (16 * hh + tt) + (lane >> 5);
@@ -219,7 +229,7 @@ __device__ __forceinline__ void gemm_epilogue_staged(const floatx4 (&acc)[8][TN]
         if (m < g.M && col_ok) {
           const floatx4 x = *reinterpret_cast<const floatx4*>(stage + r * LD + nl);
           float v[4] = {x[0], x[1], x[2], x[3]};
-          epi_finish<EPI>(v, bv, opnd[tt], g, m, n);
+          epi_finish<EPI>(v, bv, opnd[OB == 64 ? 32 * p + 16 * hh + tt : tt], g, m, n);
         }
       }
     }
