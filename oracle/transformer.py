@@ -195,3 +195,59 @@ def stage_batch(xs, dys, layers, n_heads, eps):
             for k in t:
                 t[k] += g[k]
     return outs, dxs, tot
+
+
+# ------------------------------------------------------- activation checkpointing
+# Sec. 5.1: with stride ac (a factor of the layer count) only the outputs of layers
+# ac, 2ac, ... are kept by the forward pass; a layer's other activations are regenerated
+# from the nearest kept tensor when its backward pass runs.  For a stage, the output of
+# the previous stage's last layer (the stage input) is the first kept tensor, and the
+# stage's own last output is sent onwards rather than kept.
+def stage_forward_checkpointed(x, layers, n_heads, eps, ac):
+    """Forward(msg) keeping only the inputs of layers 0, ac, 2ac, ...
+
+    Returns (output, kept) where kept[j] is the input of layer j*ac."""
+    n = len(layers)
+    if ac < 1 or n % ac != 0:
+        raise ValueError("the checkpointing stride must be a factor of the layer count")
+    kept = []
+    a = np.asarray(x, _F)
+    for i, p in enumerate(layers):
+        if i % ac == 0:
+            kept.append(a)
+        a, _ = layer_forward(a, p, n_heads, eps)   # the cache is dropped at once
+    return a, kept
+
+
+def stage_backward_checkpointed(dy, kept, layers, n_heads, eps, ac, live_log=None):
+    """Backward(msg) from the kept tensors: segment by segment from the last, the
+    segment's ac layers are run forward again from its kept input, then differentiated.
+
+    live_log, if a list, receives the number of layer caches alive after each
+    regeneration (the "+ ac" term of Eq. 1).  Returns (dx, [per-layer grads dict])."""
+    n = len(layers)
+    d = np.asarray(dy, _F)
+    grads = [None] * n
+    for j in reversed(range(n // ac)):
+        lo = j * ac
+        _, caches = stage_forward(kept[j], layers[lo:lo + ac], n_heads, eps)
+        if live_log is not None:
+            live_log.append(len(caches))
+        d, grads[lo:lo + ac] = stage_backward(d, caches, layers[lo:lo + ac], n_heads)
+        del caches
+    return d, grads
+
+
+def activation_memory(n_layers, g_inter, ac):
+    """Eq. 1 up to its constant of proportionality, in units of one layer's activations:
+    g_inter microbatches in flight, each holding n_layers / (g_inter * ac) kept tensors,
+    plus the layer being processed, plus the ac regenerated layers of one segment."""
+    return g_inter * (n_layers / (g_inter * ac)) + 1 + ac
+
+
+def checkpoint_stride(n_layers, g_inter):
+    """Sec. 5.1: the factor of the per-GPU layer count n_layers / g_inter closest to
+    sqrt(n_layers) (ties: the smaller factor)."""
+    per_gpu = n_layers // g_inter
+    factors = [a for a in range(1, per_gpu + 1) if per_gpu % a == 0]
+    return min(factors, key=lambda a: (abs(a - np.sqrt(n_layers)), a))
