@@ -75,12 +75,22 @@ typedef struct {
                               the LayerNorm output does not reach the attention logits
                               (for shapes with large logits, e.g. h = 10240 with N(0,0.02)
                               weights; costs one more QKV-sized GEMM per layer forward)  */
+  int32_t ckpt_stride;     /* activation checkpointing (Sec. 5.1): 0 keeps every activation of
+                              a microbatch in flight; ac > 0 (a factor of n_layers) keeps only
+                              the inputs of layers 0, ac, 2ac, ... and Backward regenerates
+                              each segment of ac layers from its kept input before it
+                              differentiates it.  Weight gradients are then formed per
+                              microbatch and segment, right after the segment's backward
+                              chain (wgrad_group is ignored): the regenerated activations
+                              live in shared buffers that the next segment overwrites      */
 } axonn_stage_config;
 
 /* Allocates bf16 parameters and gradients (flat buffers), pipeline_limit activation
  * stash slots (forward activations plus the output gradients of the linear maps, which
- * stay until the slot's weight gradients have been formed) and the backward workspace on
- * cfg->device.  Parameters are zero except
+ * stay until the slot's weight gradients have been formed; with ckpt_stride = ac only
+ * n_layers / ac kept layer inputs per slot, plus five shared activation buffers: two of
+ * one layer for forward passes, three of ac layers for regeneration, cf. Eq. 1) and the
+ * backward workspace on cfg->device.  Parameters are zero except
  * LayerNorm gains = 1; gradients are zero.  Synchronous. */
 int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out);
 /* Waits for all work of the stage, then frees everything it owns.  Synchronous. */
@@ -103,7 +113,8 @@ int axonn_stage_grads(axonn_stage_t* st, void** dev_bf16);
 int axonn_stage_zero_grad(axonn_stage_t* st, void* hip_stream);
 /* Device bytes the stage holds, by category (Sec. 5.2 accounting): [0] bf16 params,
  * [1] bf16 grads, [2] fp32 grad shadow (0 unless grad_accum_fp32), [3] activation stash,
- * [4] backward workspace, [5] optimizer bucket buffers (0 until attached). */
+ * [4] backward workspace (with ckpt_stride: including the shared activation buffers),
+ * [5] optimizer bucket buffers (0 until attached). */
 int axonn_stage_device_bytes(const axonn_stage_t* st, uint64_t bytes[6]);
 
 /* Forward(msg) of Alg. 2: runs the stage's layers on microbatch mb_id.

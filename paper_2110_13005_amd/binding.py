@@ -28,7 +28,7 @@ class axonn_stage_config(C.Structure):
                 ("ffn_hidden", C.c_int32), ("seq_len", C.c_int32), ("microbatch_size", C.c_int32),
                 ("n_microbatches", C.c_int32), ("pipeline_limit", C.c_int32), ("ln_eps", C.c_float),
                 ("device", C.c_int32), ("grad_accum_fp32", C.c_int32), ("wgrad_group", C.c_int32),
-                ("qkv_input_split", C.c_int32)]
+                ("qkv_input_split", C.c_int32), ("ckpt_stride", C.c_int32)]
 
 
 class axonn_msg(C.Structure):
@@ -316,9 +316,9 @@ def axonn_profile_collect():
 
 
 def make_config(shape, pipeline_limit=None, ln_eps=1e-5, device=0, grad_accum_fp32=1, n_microbatches=None,
-                wgrad_group=0, qkv_input_split=0):
+                wgrad_group=0, qkv_input_split=0, ckpt_stride=0):
     """axonn_stage_config from a `inputs.StageShape`."""
     M = shape.n_microbatches if n_microbatches is None else n_microbatches
     return axonn_stage_config(shape.n_layers, shape.hidden, shape.n_heads, shape.ffn, shape.seq_len,
                               shape.microbatch_size, M, M if pipeline_limit is None else pipeline_limit,
-                              ln_eps, device, grad_accum_fp32, wgrad_group, qkv_input_split)
+                              ln_eps, device, grad_accum_fp32, wgrad_group, qkv_input_split, ckpt_stride)

@@ -119,6 +119,18 @@ struct PendingMsg {
   axonn_msg m;
 };
 
+// With activation checkpointing (Sec. 5.1) a slot keeps only the inputs of layers 0, ac, 2ac, ...; every
+// other activation lives in a set like this one, shared by all microbatches: a forward pass runs its layers
+// through a one-layer set, a backward pass regenerates a segment of ac layers into an ac-layer set.
+struct ActSet {
+  char* base = nullptr;
+  std::vector<LayerStash> layers;
+  bf16_t* x2 = nullptr;             // forward sets: second buffer for the layer inputs that are not kept
+  hipEvent_t chain_done = nullptr;  // the backward chain through the set has finished (stream of the chain)
+  hipEvent_t released = nullptr;    // the last work that reads or writes the set has finished
+  bool released_recorded = false;
+};
+
 uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace
@@ -152,6 +164,10 @@ struct axonn_stage {
   uint64_t ws_bytes = 0;
   bf16_t *dw = nullptr, *dattn = nullptr, *du = nullptr;
   float *delta = nullptr, *red_ws = nullptr;
+  // activation checkpointing: shared activation sets (empty when cfg.ckpt_stride == 0)
+  std::vector<ActSet> fwd_sets, regen_sets;
+  unsigned fwd_set_rr = 0, regen_rr = 0;
+  uint64_t act_set_bytes = 0;
   // state
   int in_flight = 0;
   int bwd_count = 0;  // backwards since the last zero_grad
@@ -239,82 +255,111 @@ int adam(uint64_t n, float* th, float* m, float* v, const void* g16, void* p16, 
   return check_launch(launch_adam(n, th, m, v, g16, p16, lr, b1, b2, eps, wd, step, gs, s), "adam");
 }
 
-// -------------------------------------------------------------------- forward of a slot
-int forward_layers(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s) {
-  const int T = st->T, h = st->h, f = st->f, L = st->cfg.n_layers;
-  for (int l = 0; l < L; ++l) {
-    LayerStash& a = slot.layers[l];
-    bf16_t* z = (l + 1 < L) ? slot.layers[l + 1].x : (bf16_t*)y_out;
-    AX_TRY(ln_fwd(T, h, a.x, param_ptr(st, l, P_LN1G), param_ptr(st, l, P_LN1B), st->cfg.ln_eps, a.u, a.u_lo,
-                  a.stats1, s));
-    if (a.u_lo) {
-      // qkv = (u_hi + u_lo) W + b as one contraction of length 2h: segment 0 pairs u_hi with W,
-      // segment 1 pairs u_lo with the same W
-      GemmArgs g;
-      memset(&g, 0, sizeof g);
-      g.A_seg[0] = a.u; g.A_seg[1] = a.u_lo;
-      g.B_seg[0] = g.B_seg[1] = param_ptr(st, l, P_WQKV);
-      g.n_seg = 2; g.C = a.qkv; g.bias = param_ptr(st, l, P_BQKV);
-      g.lda = h; g.ldb = 3 * h; g.ldc = 3 * h; g.M = T; g.N = 3 * h; g.K = h;
-      g.concurrent = t_concurrent;
-      ProfScope ps(PC_GEMM_FWD, s);
-      AX_TRY(check_launch(launch_gemm(true, false, EPI_BIAS, g, s), "gemm (split input)"));
-    } else {
-      AX_TRY(gemm(true, false, EPI_BIAS, T, 3 * h, h, a.u, h, param_ptr(st, l, P_WQKV), 3 * h, a.qkv, 3 * h,
-                  param_ptr(st, l, P_BQKV), nullptr, 0, nullptr, 0, 0, s));
-    }
-    AX_TRY(attn_fwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d, a.qkv, a.o, a.lse, s));
-    AX_TRY(gemm(true, false, EPI_BIAS_RES, T, h, h, a.o, h, param_ptr(st, l, P_WO), h, a.y, h,
-                param_ptr(st, l, P_BO), a.x, h, nullptr, 0, 0, s));
-    AX_TRY(ln_fwd(T, h, a.y, param_ptr(st, l, P_LN2G), param_ptr(st, l, P_LN2B), st->cfg.ln_eps, a.w, nullptr,
-                  a.stats2, s));
-    AX_TRY(gemm(true, false, EPI_BIAS_GELU, T, f, h, a.w, h, param_ptr(st, l, P_WFC1), f, a.g, f,
-                param_ptr(st, l, P_BFC1), nullptr, 0, a.pre, f, 0, s));
+// ------------------------------------------------------------------- forward of a layer
+// Runs layer l on a.x, filling the activations of `a`; z receives the layer's output (null: the last
+// contraction is left out, for a regenerated layer whose output nobody reads).
+int forward_layer(axonn_stage* st, int l, const LayerStash& a, bf16_t* z, hipStream_t s) {
+  const int T = st->T, h = st->h, f = st->f;
+  AX_TRY(ln_fwd(T, h, a.x, param_ptr(st, l, P_LN1G), param_ptr(st, l, P_LN1B), st->cfg.ln_eps, a.u, a.u_lo,
+                a.stats1, s));
+  if (a.u_lo) {
+    // qkv = (u_hi + u_lo) W + b as one contraction of length 2h: segment 0 pairs u_hi with W,
+    // segment 1 pairs u_lo with the same W
+    GemmArgs g;
+    memset(&g, 0, sizeof g);
+    g.A_seg[0] = a.u; g.A_seg[1] = a.u_lo;
+    g.B_seg[0] = g.B_seg[1] = param_ptr(st, l, P_WQKV);
+    g.n_seg = 2; g.C = a.qkv; g.bias = param_ptr(st, l, P_BQKV);
+    g.lda = h; g.ldb = 3 * h; g.ldc = 3 * h; g.M = T; g.N = 3 * h; g.K = h;
+    g.concurrent = t_concurrent;
+    ProfScope ps(PC_GEMM_FWD, s);
+    AX_TRY(check_launch(launch_gemm(true, false, EPI_BIAS, g, s), "gemm (split input)"));
+  } else {
+    AX_TRY(gemm(true, false, EPI_BIAS, T, 3 * h, h, a.u, h, param_ptr(st, l, P_WQKV), 3 * h, a.qkv, 3 * h,
+                param_ptr(st, l, P_BQKV), nullptr, 0, nullptr, 0, 0, s));
+  }
+  AX_TRY(attn_fwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d, a.qkv, a.o, a.lse, s));
+  AX_TRY(gemm(true, false, EPI_BIAS_RES, T, h, h, a.o, h, param_ptr(st, l, P_WO), h, a.y, h,
+              param_ptr(st, l, P_BO), a.x, h, nullptr, 0, 0, s));
+  AX_TRY(ln_fwd(T, h, a.y, param_ptr(st, l, P_LN2G), param_ptr(st, l, P_LN2B), st->cfg.ln_eps, a.w, nullptr,
+                a.stats2, s));
+  AX_TRY(gemm(true, false, EPI_BIAS_GELU, T, f, h, a.w, h, param_ptr(st, l, P_WFC1), f, a.g, f,
+              param_ptr(st, l, P_BFC1), nullptr, 0, a.pre, f, 0, s));
+  if (z)
     AX_TRY(gemm(true, false, EPI_BIAS_RES, T, h, f, a.g, f, param_ptr(st, l, P_WFC2), h, z, h,
                 param_ptr(st, l, P_BFC2), a.y, h, nullptr, 0, 0, s));
-  }
   return AXONN_OK;
 }
 
-// ------------------------------------------------------------------- backward of a slot
+int forward_layers(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s) {
+  const int L = st->cfg.n_layers;
+  for (int l = 0; l < L; ++l)
+    AX_TRY(forward_layer(st, l, slot.layers[l], (l + 1 < L) ? slot.layers[l + 1].x : (bf16_t*)y_out, s));
+  return AXONN_OK;
+}
+
+// Forward pass that keeps only the inputs of layers 0, ac, 2ac, ... in the slot (Sec. 5.1); all other
+// activations go through a shared one-layer set and are overwritten by the next layer.
+int forward_layers_ckpt(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s) {
+  const int L = st->cfg.n_layers, ac = st->cfg.ckpt_stride;
+  ActSet& F = st->fwd_sets[st->fwd_set_rr++ % st->fwd_sets.size()];
+  if (F.released_recorded) HIP_TRY(hipStreamWaitEvent(s, F.released, 0));
+  bf16_t* const xb[2] = {F.layers[0].x, F.x2};
+  for (int l = 0; l < L; ++l) {
+    LayerStash a = F.layers[0];
+    a.x = (l % ac == 0) ? slot.layers[l].x : xb[l & 1];
+    bf16_t* z = (l + 1 == L) ? (bf16_t*)y_out : ((l + 1) % ac == 0) ? slot.layers[l + 1].x : xb[(l + 1) & 1];
+    AX_TRY(forward_layer(st, l, a, z, s));
+  }
+  HIP_TRY(hipEventRecord(F.released, s));
+  F.released_recorded = true;
+  return AXONN_OK;
+}
+
+// ------------------------------------------------------------------ backward of a layer
+// Given dL/d(output) in a.dz, writes dL/d(input) to d_out, the output gradients of the four linear maps
+// to a.dpre, a.dy_mid, a.dqkv (a.dz is the fourth) and adds the bias / LayerNorm gradients.
+int backward_layer(axonn_stage* st, int l, const LayerStash& a, bf16_t* d_out, int acc, hipStream_t s) {
+  const int T = st->T, h = st->h, f = st->f;
+  const bf16_t* d_in = a.dz;
+  // z = y + g W2 + b2
+  AX_TRY(gemm(true, true, EPI_DGELU, T, f, h, d_in, h, param_ptr(st, l, P_WFC2), h, a.dpre, f,
+              nullptr, nullptr, 0, a.pre, f, 0, s));
+  AX_TRY(bias_grad(st, l, P_BFC2, T, h, d_in, h, acc, s));
+  // pre = w W1 + b1
+  AX_TRY(gemm(true, true, EPI_BIAS, T, h, f, a.dpre, f, param_ptr(st, l, P_WFC1), f, st->dw, h,
+              nullptr, nullptr, 0, nullptr, 0, 0, s));
+  AX_TRY(bias_grad(st, l, P_BFC1, T, f, a.dpre, f, acc, s));
+  // w = LN2(y); residual: dy = d_in + dLN2
+  AX_TRY(ln_bwd(st, l, P_LN2G, P_LN2B, T, h, st->dw, a.y, a.stats2, param_ptr(st, l, P_LN2G), d_in, a.dy_mid,
+                acc, s));
+  // y = x + o Wo + bo
+  AX_TRY(gemm(true, true, EPI_BIAS, T, h, h, a.dy_mid, h, param_ptr(st, l, P_WO), h, st->dattn, h,
+              nullptr, nullptr, 0, nullptr, 0, 0, s));
+  AX_TRY(bias_grad(st, l, P_BO, T, h, a.dy_mid, h, acc, s));
+  // attention
+  AX_TRY(attn_bwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d, a.qkv, a.o, a.lse, st->dattn,
+                  a.dqkv, st->delta, s));
+  // qkv = u Wqkv + b
+  AX_TRY(gemm(true, true, EPI_BIAS, T, h, 3 * h, a.dqkv, 3 * h, param_ptr(st, l, P_WQKV), 3 * h, st->du, h,
+              nullptr, nullptr, 0, nullptr, 0, 0, s));
+  AX_TRY(bias_grad(st, l, P_BQKV, T, 3 * h, a.dqkv, 3 * h, acc, s));
+  // u = LN1(x); residual: dx = dy + dLN1
+  AX_TRY(ln_bwd(st, l, P_LN1G, P_LN1B, T, h, st->du, a.x, a.stats1, param_ptr(st, l, P_LN1G), a.dy_mid, d_out,
+                acc, s));
+  return AXONN_OK;
+}
+
 int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out, int acc, hipStream_t s) {
-  const int T = st->T, h = st->h, f = st->f, L = st->cfg.n_layers;
+  const int T = st->T, h = st->h, L = st->cfg.n_layers;
   // the upstream gradient is copied into the stash: it is an operand of the deferred weight
   // gradient and the caller may recycle its receive buffer
   {
     ProfScope ps(PC_COPY_IN, s);
     HIP_TRY(hipMemcpyAsync(slot.layers[L - 1].dz, dy_in, (uint64_t)T * h * sizeof(bf16_t), hipMemcpyDeviceToDevice, s));
   }
-  for (int l = L - 1; l >= 0; --l) {
-    LayerStash& a = slot.layers[l];
-    const bf16_t* d_in = a.dz;
-    bf16_t* d_out = (l == 0) ? (bf16_t*)dx_out : slot.layers[l - 1].dz;
-    // z = y + g W2 + b2
-    AX_TRY(gemm(true, true, EPI_DGELU, T, f, h, d_in, h, param_ptr(st, l, P_WFC2), h, a.dpre, f,
-                nullptr, nullptr, 0, a.pre, f, 0, s));
-    AX_TRY(bias_grad(st, l, P_BFC2, T, h, d_in, h, acc, s));
-    // pre = w W1 + b1
-    AX_TRY(gemm(true, true, EPI_BIAS, T, h, f, a.dpre, f, param_ptr(st, l, P_WFC1), f, st->dw, h,
-                nullptr, nullptr, 0, nullptr, 0, 0, s));
-    AX_TRY(bias_grad(st, l, P_BFC1, T, f, a.dpre, f, acc, s));
-    // w = LN2(y); residual: dy = d_in + dLN2
-    AX_TRY(ln_bwd(st, l, P_LN2G, P_LN2B, T, h, st->dw, a.y, a.stats2, param_ptr(st, l, P_LN2G), d_in, a.dy_mid,
-                  acc, s));
-    // y = x + o Wo + bo
-    AX_TRY(gemm(true, true, EPI_BIAS, T, h, h, a.dy_mid, h, param_ptr(st, l, P_WO), h, st->dattn, h,
-                nullptr, nullptr, 0, nullptr, 0, 0, s));
-    AX_TRY(bias_grad(st, l, P_BO, T, h, a.dy_mid, h, acc, s));
-    // attention
-    AX_TRY(attn_bwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d, a.qkv, a.o, a.lse, st->dattn,
-                    a.dqkv, st->delta, s));
-    // qkv = u Wqkv + b
-    AX_TRY(gemm(true, true, EPI_BIAS, T, h, 3 * h, a.dqkv, 3 * h, param_ptr(st, l, P_WQKV), 3 * h, st->du, h,
-                nullptr, nullptr, 0, nullptr, 0, 0, s));
-    AX_TRY(bias_grad(st, l, P_BQKV, T, 3 * h, a.dqkv, 3 * h, acc, s));
-    // u = LN1(x); residual: dx = dy + dLN1
-    AX_TRY(ln_bwd(st, l, P_LN1G, P_LN1B, T, h, st->du, a.x, a.stats1, param_ptr(st, l, P_LN1G), a.dy_mid, d_out,
-                  acc, s));
-  }
+  for (int l = L - 1; l >= 0; --l)
+    AX_TRY(backward_layer(st, l, slot.layers[l], (l == 0) ? (bf16_t*)dx_out : slot.layers[l - 1].dz, acc, s));
   return AXONN_OK;
 }
 
@@ -334,28 +379,37 @@ int gemm_seg(int epi, int M, int N, int K, const bf16_t* const* A, int64_t lda, 
   return check_launch(launch_gemm(false, false, epi, g, s), "gemm (weight gradient)");
 }
 
+// dW += sum_i in_i^T dout_i for the four weights of layer l over n activation records
+int wgrad_layer(axonn_stage* st, int l, const LayerStash* const* rec, int n, int acc, hipStream_t s) {
+  const int T = st->T, h = st->h, f = st->f;
+  const int epi = st->cfg.grad_accum_fp32 ? EPI_ACC_F32 : EPI_ACC_BF16;
+  const bf16_t *A[kMaxKSegments], *B[kMaxKSegments];
+  for (int i = 0; i < n; ++i) { A[i] = rec[i]->g; B[i] = rec[i]->dz; }
+  AX_TRY(gemm_seg(epi, f, h, T, A, f, B, h, n, grad_ptr(st, l, P_WFC2), h, acc, s));
+  for (int i = 0; i < n; ++i) { A[i] = rec[i]->w; B[i] = rec[i]->dpre; }
+  AX_TRY(gemm_seg(epi, h, f, T, A, h, B, f, n, grad_ptr(st, l, P_WFC1), f, acc, s));
+  for (int i = 0; i < n; ++i) { A[i] = rec[i]->o; B[i] = rec[i]->dy_mid; }
+  AX_TRY(gemm_seg(epi, h, h, T, A, h, B, h, n, grad_ptr(st, l, P_WO), h, acc, s));
+  for (int i = 0; i < n; ++i) { A[i] = rec[i]->u; B[i] = rec[i]->dqkv; }
+  AX_TRY(gemm_seg(epi, h, 3 * h, T, A, h, B, 3 * h, n, grad_ptr(st, l, P_WQKV), 3 * h, acc, s));
+  return AXONN_OK;
+}
+
 int flush_wgrad(axonn_stage* st, hipStream_t s) {
   std::vector<Slot*> ready;
   for (Slot& sl : st->slots)
     if (sl.state == SLOT_AWAIT_WGRAD) ready.push_back(&sl);
   if (ready.empty()) return AXONN_OK;
-  const int T = st->T, h = st->h, f = st->f, L = st->cfg.n_layers;
-  const int epi = st->cfg.grad_accum_fp32 ? EPI_ACC_F32 : EPI_ACC_BF16;
+  const int L = st->cfg.n_layers;
   for (Slot* sl : ready) HIP_TRY(hipStreamWaitEvent(s, sl->dgrad_done, 0));
   if (st->last_wgrad_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_wgrad, 0));
   for (size_t first = 0; first < ready.size(); first += kMaxKSegments) {
     const int n = (int)std::min<size_t>(kMaxKSegments, ready.size() - first);
     const int acc = st->wgrad_flushes > 0 ? 1 : 0;
-    const bf16_t *A[kMaxKSegments], *B[kMaxKSegments];
+    const LayerStash* rec[kMaxKSegments];
     for (int l = 0; l < L; ++l) {
-      for (int i = 0; i < n; ++i) { A[i] = ready[first + i]->layers[l].g; B[i] = ready[first + i]->layers[l].dz; }
-      AX_TRY(gemm_seg(epi, f, h, T, A, f, B, h, n, grad_ptr(st, l, P_WFC2), h, acc, s));
-      for (int i = 0; i < n; ++i) { A[i] = ready[first + i]->layers[l].w; B[i] = ready[first + i]->layers[l].dpre; }
-      AX_TRY(gemm_seg(epi, h, f, T, A, h, B, f, n, grad_ptr(st, l, P_WFC1), f, acc, s));
-      for (int i = 0; i < n; ++i) { A[i] = ready[first + i]->layers[l].o; B[i] = ready[first + i]->layers[l].dy_mid; }
-      AX_TRY(gemm_seg(epi, h, h, T, A, h, B, h, n, grad_ptr(st, l, P_WO), h, acc, s));
-      for (int i = 0; i < n; ++i) { A[i] = ready[first + i]->layers[l].u; B[i] = ready[first + i]->layers[l].dqkv; }
-      AX_TRY(gemm_seg(epi, h, 3 * h, T, A, h, B, 3 * h, n, grad_ptr(st, l, P_WQKV), 3 * h, acc, s));
+      for (int i = 0; i < n; ++i) rec[i] = &ready[first + i]->layers[l];
+      AX_TRY(wgrad_layer(st, l, rec, n, acc, s));
     }
     st->wgrad_flushes++;
   }
@@ -365,6 +419,50 @@ int flush_wgrad(axonn_stage* st, hipStream_t s) {
     HIP_TRY(hipEventRecord(sl->released, s));
     sl->released_recorded = true;
     sl->state = SLOT_FREE;
+  }
+  return AXONN_OK;
+}
+
+// Backward pass from kept layer inputs (Sec. 5.1).  Segment by segment from the last: the segment's ac
+// layers are run forward again from the kept input into a shared activation set (the output of the
+// segment's last layer is not needed and not formed), the gradient chain runs back through them on `s`,
+// and their weight gradients follow at once on `ws`, since the set is about to be reused.  Three sets
+// rotate: while `ws` still reads one, the chain regenerates into the next and leaves the gradient that
+// crosses the segment boundary in the one after.
+int backward_layers_ckpt(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out, int acc, hipStream_t s,
+                         hipStream_t ws) {
+  const int T = st->T, h = st->h, L = st->cfg.n_layers, ac = st->cfg.ckpt_stride;
+  const size_t n_sets = st->regen_sets.size();
+  for (int seg = L / ac - 1; seg >= 0; --seg) {
+    ActSet& R = st->regen_sets[st->regen_rr % n_sets];
+    ActSet& Rnext = st->regen_sets[(st->regen_rr + 1) % n_sets];
+    st->regen_rr++;
+    if (R.released_recorded) HIP_TRY(hipStreamWaitEvent(s, R.released, 0));
+    if (seg > 0 && Rnext.released_recorded) HIP_TRY(hipStreamWaitEvent(s, Rnext.released, 0));
+    if (seg == L / ac - 1) {
+      // the upstream gradient is an operand of the weight gradient, which may outlive the caller's buffer
+      ProfScope ps(PC_COPY_IN, s);
+      HIP_TRY(hipMemcpyAsync(R.layers[ac - 1].dz, dy_in, (uint64_t)T * h * sizeof(bf16_t), hipMemcpyDeviceToDevice, s));
+    }
+    std::vector<LayerStash> rec(R.layers.begin(), R.layers.begin() + ac);
+    rec[0].x = slot.layers[seg * ac].x;
+    for (int i = 0; i < ac; ++i)
+      AX_TRY(forward_layer(st, seg * ac + i, rec[i], (i + 1 < ac) ? rec[i + 1].x : nullptr, s));
+    for (int i = ac - 1; i >= 0; --i) {
+      bf16_t* d_out = (i > 0) ? rec[i - 1].dz : (seg == 0) ? (bf16_t*)dx_out : Rnext.layers[ac - 1].dz;
+      AX_TRY(backward_layer(st, seg * ac + i, rec[i], d_out, acc, s));
+    }
+    HIP_TRY(hipEventRecord(R.chain_done, s));
+    if (ws != s) HIP_TRY(hipStreamWaitEvent(ws, R.chain_done, 0));
+    if (st->last_wgrad_recorded) HIP_TRY(hipStreamWaitEvent(ws, st->last_wgrad, 0));
+    for (int i = 0; i < ac; ++i) {
+      const LayerStash* one[1] = {&rec[i]};
+      AX_TRY(wgrad_layer(st, seg * ac + i, one, 1, acc, ws));
+    }
+    HIP_TRY(hipEventRecord(st->last_wgrad, ws));
+    st->last_wgrad_recorded = true;
+    HIP_TRY(hipEventRecord(R.released, ws));
+    R.released_recorded = true;
   }
   return AXONN_OK;
 }
@@ -407,7 +505,8 @@ int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s
     ProfScope ps(PC_COPY_IN, s);
     HIP_TRY(hipMemcpyAsync(slot->layers[0].x, x, bytes, hipMemcpyDeviceToDevice, s));
   }
-  AX_TRY(forward_layers(st, *slot, y, s));
+  if (st->cfg.ckpt_stride > 0) AX_TRY(forward_layers_ckpt(st, *slot, y, s));
+  else AX_TRY(forward_layers(st, *slot, y, s));
   HIP_TRY(hipEventRecord(slot->fwd_done, s));
   slot->state = SLOT_LIVE;
   slot->mb_id = mb_id;
@@ -422,17 +521,27 @@ int do_backward(axonn_stage* st, int mb_id, const void* dy, void* dx, hipStream_
   // backward chains share the workspace and the bias / LayerNorm accumulators: keep them in order
   if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_bwd, 0));
   const int acc = st->bwd_count > 0 ? 1 : 0;
-  AX_TRY(backward_layers(st, *slot, dy, dx, acc, s));
+  const bool ckpt = st->cfg.ckpt_stride > 0;
+  if (ckpt) AX_TRY(backward_layers_ckpt(st, *slot, dy, dx, acc, s, ws));
+  else AX_TRY(backward_layers(st, *slot, dy, dx, acc, s));
   st->bwd_count++;
   HIP_TRY(hipEventRecord(slot->dgrad_done, s));
   HIP_TRY(hipEventRecord(st->last_bwd, s));
   st->last_bwd_recorded = true;
-  slot->state = SLOT_AWAIT_WGRAD;
   slot->mb_id = -1;
   st->in_flight--;
   const bool last = st->bwd_count == st->cfg.n_microbatches;
-  const int group = st->cfg.wgrad_group;
-  if (last || (group > 0 && count_state(st, SLOT_AWAIT_WGRAD) >= group)) AX_TRY(flush_wgrad(st, ws));
+  if (ckpt) {
+    // the weight gradients are already queued and read the shared sets: the slot (kept inputs only) is
+    // free as soon as the chain on `s` is through
+    HIP_TRY(hipEventRecord(slot->released, s));
+    slot->released_recorded = true;
+    slot->state = SLOT_FREE;
+  } else {
+    slot->state = SLOT_AWAIT_WGRAD;
+    const int group = st->cfg.wgrad_group;
+    if (last || (group > 0 && count_state(st, SLOT_AWAIT_WGRAD) >= group)) AX_TRY(flush_wgrad(st, ws));
+  }
   if (last && st->cfg.grad_accum_fp32) {
     // bias / LayerNorm gradients of the last chain (stream s) and all weight gradients (stream ws)
     if (ws != s) HIP_TRY(hipStreamWaitEvent(ws, st->last_bwd, 0));
@@ -494,6 +603,12 @@ void destroy_stage(axonn_stage* st) {
   if (st->last_wgrad) (void)hipEventDestroy(st->last_wgrad);
   if (st->wgrad_tail) (void)hipEventDestroy(st->wgrad_tail);
   if (st->wgrad_stream) (void)hipStreamDestroy(st->wgrad_stream);
+  for (std::vector<ActSet>* sets : {&st->fwd_sets, &st->regen_sets})
+    for (ActSet& a : *sets) {
+      if (a.base) (void)hipFree(a.base);
+      if (a.chain_done) (void)hipEventDestroy(a.chain_done);
+      if (a.released) (void)hipEventDestroy(a.released);
+    }
   if (st->ws_base) (void)hipFree(st->ws_base);
   if (st->params) (void)hipFree(st->params);
   if (st->grads) (void)hipFree(st->grads);
@@ -511,6 +626,9 @@ int validate_config(const axonn_stage_config* c) {
   if (!(c->ln_eps > 0.f)) return fail(AXONN_EINVAL, "stage config: ln_eps must be positive");
   if (c->device < 0) return fail(AXONN_EINVAL, "stage config: negative device ordinal");
   if (c->wgrad_group < 0) return fail(AXONN_EINVAL, "stage config: negative wgrad_group");
+  if (c->ckpt_stride < 0 || (c->ckpt_stride > 0 && c->n_layers % c->ckpt_stride != 0))
+    return fail(AXONN_EINVAL, "stage config: ckpt_stride (%d) must be 0 or a factor of n_layers (%d)",
+                c->ckpt_stride, c->n_layers);
   const int d = c->hidden / c->n_heads;
   if (d != 64 && d != 128)
     return fail(AXONN_EUNSUPPORTED, "head dim %d unsupported: attention kernels exist for 64 and 128", d);
@@ -603,7 +721,19 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
                  e_tf = align_up((uint64_t)T * f * 2, 256), e_st = align_up((uint64_t)T * 2 * 4, 256),
                  e_lse = align_up((uint64_t)cfg->microbatch_size * cfg->n_heads * cfg->seq_len * 4, 256);
   const uint64_t per_layer = (cfg->qkv_input_split ? 8 : 7) * e_th + 2 * e_t3h + 3 * e_tf + 2 * e_st + e_lse;
-  st->slot_bytes = per_layer * cfg->n_layers;
+  // carves one layer's record out of p
+  auto carve = [&](char*& p, LayerStash& a) {
+    a.x = (bf16_t*)p; p += e_th;  a.u = (bf16_t*)p; p += e_th;  a.o = (bf16_t*)p; p += e_th;
+    a.y = (bf16_t*)p; p += e_th;  a.w = (bf16_t*)p; p += e_th;  a.qkv = (bf16_t*)p; p += e_t3h;
+    a.pre = (bf16_t*)p; p += e_tf; a.g = (bf16_t*)p; p += e_tf;
+    a.stats1 = (float*)p; p += e_st; a.stats2 = (float*)p; p += e_st; a.lse = (float*)p; p += e_lse;
+    a.dz = (bf16_t*)p; p += e_th; a.dy_mid = (bf16_t*)p; p += e_th;
+    a.dpre = (bf16_t*)p; p += e_tf; a.dqkv = (bf16_t*)p; p += e_t3h;
+    a.u_lo = nullptr;
+    if (cfg->qkv_input_split) { a.u_lo = (bf16_t*)p; p += e_th; }
+  };
+  const int ac = cfg->ckpt_stride;
+  st->slot_bytes = ac > 0 ? (uint64_t)(cfg->n_layers / ac) * e_th : per_layer * cfg->n_layers;
   st->slots.resize(cfg->pipeline_limit);
   for (Slot& s : st->slots) {
     CREATE_TRY(hipMalloc((void**)&s.base, st->slot_bytes));
@@ -612,16 +742,37 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
     CREATE_TRY(hipEventCreateWithFlags(&s.released, hipEventDisableTiming));
     s.layers.resize(cfg->n_layers);
     char* p = s.base;
-    for (LayerStash& a : s.layers) {
-      a.x = (bf16_t*)p; p += e_th;  a.u = (bf16_t*)p; p += e_th;  a.o = (bf16_t*)p; p += e_th;
-      a.y = (bf16_t*)p; p += e_th;  a.w = (bf16_t*)p; p += e_th;  a.qkv = (bf16_t*)p; p += e_t3h;
-      a.pre = (bf16_t*)p; p += e_tf; a.g = (bf16_t*)p; p += e_tf;
-      a.stats1 = (float*)p; p += e_st; a.stats2 = (float*)p; p += e_st; a.lse = (float*)p; p += e_lse;
-      a.dz = (bf16_t*)p; p += e_th; a.dy_mid = (bf16_t*)p; p += e_th;
-      a.dpre = (bf16_t*)p; p += e_tf; a.dqkv = (bf16_t*)p; p += e_t3h;
-      a.u_lo = nullptr;
-      if (cfg->qkv_input_split) { a.u_lo = (bf16_t*)p; p += e_th; }
+    for (int l = 0; l < cfg->n_layers; ++l) {
+      LayerStash& a = s.layers[l];
+      if (ac > 0) {
+        // only the inputs of layers 0, ac, 2ac, ... are kept (Sec. 5.1)
+        memset(&a, 0, sizeof a);
+        if (l % ac == 0) { a.x = (bf16_t*)p; p += e_th; }
+      } else {
+        carve(p, a);
+      }
     }
+  }
+  if (ac > 0) {
+    // shared activation sets: two one-layer sets for forward passes (one more buffer each for the layer
+    // inputs that are not kept), three ac-layer sets for regeneration in backward passes
+    auto make_set = [&](ActSet& a, int n_layers, bool second_x) -> hipError_t {
+      const uint64_t bytes = (uint64_t)n_layers * per_layer + (second_x ? e_th : 0);
+      hipError_t e = hipMalloc((void**)&a.base, bytes);
+      if (e != hipSuccess) return e;
+      st->act_set_bytes += bytes;
+      if ((e = hipEventCreateWithFlags(&a.chain_done, hipEventDisableTiming)) != hipSuccess) return e;
+      if ((e = hipEventCreateWithFlags(&a.released, hipEventDisableTiming)) != hipSuccess) return e;
+      a.layers.resize(n_layers);
+      char* p = a.base;
+      for (LayerStash& l : a.layers) carve(p, l);
+      if (second_x) { a.x2 = (bf16_t*)p; p += e_th; }
+      return hipSuccess;
+    };
+    st->fwd_sets.resize(2);
+    st->regen_sets.resize(3);
+    for (ActSet& a : st->fwd_sets) CREATE_TRY(make_set(a, 1, true));
+    for (ActSet& a : st->regen_sets) CREATE_TRY(make_set(a, ac, false));
   }
   // backward workspace
   const int64_t wide = std::max<int64_t>(f, 3 * h);
@@ -703,7 +854,7 @@ int axonn_stage_device_bytes(const axonn_stage_t* st, uint64_t bytes[6]) {
   bytes[1] = st->n_params * 2;
   bytes[2] = st->grads32 ? st->n_params * 4 : 0;
   bytes[3] = st->slot_bytes * st->slots.size();
-  bytes[4] = st->ws_bytes;
+  bytes[4] = st->ws_bytes + st->act_set_bytes;
   bytes[5] = st->opt ? st->opt->device_bytes : 0;
   return AXONN_OK;
 }

@@ -21,11 +21,11 @@ def _view(ptr, n, dtype):
 
 class Stage:
     def __init__(self, shape, pipeline_limit=None, ln_eps=1e-5, device=0, grad_accum_fp32=1,
-                 n_microbatches=None, wgrad_group=0, qkv_input_split=0):
+                 n_microbatches=None, wgrad_group=0, qkv_input_split=0, ckpt_stride=0):
         import torch
         self.shape = shape
         self.cfg = B.make_config(shape, pipeline_limit, ln_eps, device, grad_accum_fp32, n_microbatches, wgrad_group,
-                                 qkv_input_split)
+                                 qkv_input_split, ckpt_stride)
         self.handle = B.axonn_stage_create(self.cfg)
         self.n_params = B.axonn_stage_param_count(self.handle)
         self.layout = {}

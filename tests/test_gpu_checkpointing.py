@@ -1,0 +1,118 @@
+"""GPU parity of the stage path with activation checkpointing (Sec. 5.1) against the fp64 oracle's
+regenerating pass, through the C ABI, plus what regeneration must not change and what it must save."""
+import numpy as np
+import pytest
+
+from oracle import transformer as OT
+from paper_2110_13005_amd import binding as B
+from paper_2110_13005_amd.inputs import CONFIGS, StageShape, make_stage_inputs
+from paper_2110_13005_amd.stage import Stage
+from helpers import rel_fro, dev_bf16, host
+from test_gpu_stage import _run_direct, _check, _schedules, EPS
+
+pytestmark = pytest.mark.gpu
+
+
+def _oracle_ckpt_batch(xs, dys, layers, n_heads, ac):
+    layers = [{k: np.asarray(v, np.float64) for k, v in p.items()} for p in layers]
+    tot = [{k: np.zeros_like(v) for k, v in p.items()} for p in layers]
+    outs, dxs = [], []
+    for x, dy in zip(xs, dys):
+        z, kept = OT.stage_forward_checkpointed(x, layers, n_heads, EPS, ac)
+        dx, grads = OT.stage_backward_checkpointed(dy, kept, layers, n_heads, EPS, ac)
+        outs.append(z); dxs.append(dx)
+        for t, g in zip(tot, grads):
+            for k in t:
+                t[k] += g[k]
+    return outs, dxs, tot
+
+
+@pytest.mark.parametrize("ac", [1, 2, 4])
+@pytest.mark.parametrize("fp32_acc", [1, 0])
+def test_checkpointed_stage_parity(ac, fp32_acc):
+    """Four layers, every stride that divides them; rows and widths that leave ragged tiles."""
+    sh = StageShape(4, 192, 3, 96, 2, 3)
+    layers, xs, dys = make_stage_inputs(sh, seed=2, perturb=True)
+    ref = _oracle_ckpt_batch(xs, dys, layers, sh.n_heads, ac)
+    with Stage(sh, grad_accum_fp32=fp32_acc, ckpt_stride=ac) as st:
+        st.load_params(layers)
+        outs, dxs, grads = _run_direct(st, xs, dys)
+    _check(outs, dxs, grads, ref)
+
+
+def test_regeneration_changes_no_activation_or_input_gradient():
+    """The regenerated activations are the forward pass's own (same kernels, same inputs), so outputs
+    and input gradients are bit-identical to the run that keeps everything; the weight gradients differ
+    only by the order of accumulation over microbatches."""
+    sh = CONFIGS["tiny"]
+    layers, xs, dys = make_stage_inputs(sh, seed=0, perturb=True)
+    res = {}
+    for ac in (0, 1, 2):
+        with Stage(sh, grad_accum_fp32=1, ckpt_stride=ac) as st:
+            st.load_params(layers)
+            res[ac] = _run_direct(st, xs, dys)
+    for ac in (1, 2):
+        for a, b in zip(res[ac][0] + res[ac][1], res[0][0] + res[0][1]):
+            assert np.array_equal(a, b), ac
+        for ga, gb in zip(res[ac][2], res[0][2]):
+            for k in ga:
+                assert rel_fro(ga[k], gb[k]) <= 1e-3, (ac, k)
+
+
+def test_checkpointed_schedules_and_slot_reuse():
+    """Interleaved schedules with fewer slots than microbatches: kept inputs are recycled and the shared
+    activation buffers rotate; every order gives the oracle's result."""
+    sh = StageShape(4, 128, 2, 64, 1, 6)
+    layers, xs, dys = make_stage_inputs(sh, seed=3, perturb=True)
+    ref = _oracle_ckpt_batch(xs, dys, layers, sh.n_heads, 2)
+    with Stage(sh, pipeline_limit=2, ckpt_stride=2) as st:
+        st.load_params(layers)
+        for name, order in _schedules(sh.n_microbatches, 2).items():
+            _check(*_run_direct(st, xs, dys, order), ref)
+
+
+@pytest.mark.parametrize("n_streams", [1, 2, 3])
+def test_checkpointed_message_driven_run(n_streams):
+    import torch
+    sh = StageShape(4, 256, 4, 128, 2, 5)
+    M, P = sh.n_microbatches, 2
+    layers, xs, dys = make_stage_inputs(sh, seed=4, perturb=True)
+    ref = _oracle_ckpt_batch(xs, dys, layers, sh.n_heads, 2)
+    with Stage(sh, pipeline_limit=P, grad_accum_fp32=0, ckpt_stride=2) as st:
+        st.load_params(layers)
+        X = [dev_bf16(x) for x in xs]; DY = [dev_bf16(d) for d in dys]
+        Y = [torch.zeros_like(X[0]) for _ in range(M)]; DX = [torch.zeros_like(X[0]) for _ in range(M)]
+        for rep in range(2):   # the second batch starts with every shared buffer in use
+            st.zero_grad()
+            for i in range(M):
+                st.post(0, i, X[i], Y[i])
+            for i in range(M):
+                st.post(1, i, DY[i], DX[i])
+            st.run(n_streams)
+            st.join()
+            torch.cuda.synchronize()
+            _check([host(y) for y in Y], [host(d) for d in DX], st.grads_numpy(), ref)
+
+
+def test_checkpointing_memory_follows_eq1():
+    """Eq. 1: P microbatches in flight keep L/ac layer inputs each; the regenerated activations (ac layers
+    per buffer) are shared by all of them."""
+    sh = StageShape(4, 256, 4, 128, 2, 4)
+    x_bytes = 2 * sh.tokens * sh.hidden
+    per_layer = 2 * sh.tokens * (13 * sh.hidden + 3 * sh.ffn)
+    sizes = {}
+    for ac in (0, 1, 2, 4):
+        with Stage(sh, ckpt_stride=ac) as st:
+            sizes[ac] = B.axonn_stage_device_bytes(st.handle)
+    ws0 = sizes[0][4]
+    for ac in (1, 2, 4):
+        kept = sh.n_microbatches * (sh.n_layers // ac) * x_bytes
+        assert kept <= sizes[ac][3] <= kept + (1 << 16)
+        shared = sizes[ac][4] - ws0
+        assert (3 * ac + 2) * per_layer <= shared <= 1.1 * (3 * ac + 2) * per_layer + x_bytes * 2 + (1 << 20)
+    assert sizes[0][3] >= sh.n_microbatches * sh.n_layers * per_layer
+    # with more microbatches in flight than shared buffers, keeping inputs only is the smaller footprint
+    sh16 = StageShape(4, 256, 4, 128, 2, 16)
+    with Stage(sh16, ckpt_stride=0) as a, Stage(sh16, ckpt_stride=2) as b:
+        sa, sb = B.axonn_stage_device_bytes(a.handle), B.axonn_stage_device_bytes(b.handle)
+        assert sb[3] + sb[4] < 0.6 * (sa[3] + sa[4])

@@ -40,6 +40,9 @@ def test_argument_validation_without_device():
     assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EINVAL
     cfg = B.axonn_stage_config(2, 256, 4, 1024, 3, 1, 4, 4, 1e-5, 0, 1, 0, 0)     # 3 tokens
     assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EUNSUPPORTED
+    cfg = B.axonn_stage_config(4, 256, 4, 1024, 128, 2, 4, 4, 1e-5, 0, 1, 0, 0, 3)  # stride 3, 4 layers
+    assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EINVAL
+    assert b"ckpt_stride" in lib.axonn_last_error()
     with pytest.raises(B.AxonnError) as e:
         B.axonn_gemm_bf16(1, 0, 0, 64, 64, 60, 1, 64, 1, 64, 1, 64)          # K % 8 != 0
     assert e.value.status == B.AXONN_EUNSUPPORTED
