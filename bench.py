@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--pipeline-limit", type=int, default=0, help="0 = all microbatches in flight")
     ap.add_argument("--grad-accum", default="bf16", choices=["fp32", "bf16"])
     ap.add_argument("--wgrad-group", type=int, default=3, help="microbatches per weight-gradient contraction (0 = as many as possible)")
+    ap.add_argument("--ckpt-stride", type=int, default=0,
+                    help="activation checkpointing stride ac (0 = keep all activations, the default workload)")
     ap.add_argument("--bucket-elems", type=int, default=1 << 26)
     ap.add_argument("--no-optimizer", action="store_true", help="diagnostic: leave the Adam step out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -91,7 +93,8 @@ def main():
     g = torch.Generator(device=dev)
     g.manual_seed(0)
 
-    st = Stage(sh, pipeline_limit=P, grad_accum_fp32=1 if args.grad_accum == "fp32" else 0, wgrad_group=args.wgrad_group)
+    st = Stage(sh, pipeline_limit=P, grad_accum_fp32=1 if args.grad_accum == "fp32" else 0, wgrad_group=args.wgrad_group,
+               ckpt_stride=args.ckpt_stride)
     n = st.n_params
     # synthetic weights ~N(0, 0.02) (LayerNorm gains 1, biases 0), generated on the device in chunks;
     # fp32 master copy in pinned host memory, bf16 copy = its rounding
@@ -186,13 +189,16 @@ def main():
                                "pipeline_limit=%d" % (args.config, sh.n_layers, sh.hidden, sh.n_heads, sh.ffn,
                                                       sh.seq_len, sh.microbatch_size, M, P),
                    "streams": args.streams, "grad_accum": args.grad_accum, "wgrad_group": args.wgrad_group, "bucket_elems": args.bucket_elems,
-                   "optimizer_in_step": not args.no_optimizer},
+                   "ckpt_stride": args.ckpt_stride, "optimizer_in_step": not args.no_optimizer},
         "pct_of_bf16_mfma_peak": 100.0 * tflops / flops.PEAK_BF16_DENSE_TFLOPS,
         "peak_tflops_used": flops.PEAK_BF16_DENSE_TFLOPS,
         "tokens_per_s": tokens / (fb_mean * 1e-3),
         "tokens_per_s_whole_step": tokens / (wall / args.steps),
         "fwd_bwd_ms": {"mean": fb_mean, "min": float(np.min(fb_ms)), "per_step": [round(float(x), 3) for x in fb_ms]},
         "tflops_paper_convention": fl_paper / (fb_mean * 1e-3) / 1e12,
+        "tflops_executed": (fl + flops.regeneration_flops(sh, args.ckpt_stride)) / (fb_mean * 1e-3) / 1e12,
+        "device_bytes": dict(zip(("params", "grads", "grad_shadow", "stash", "workspace", "optimizer"),
+                                 B.axonn_stage_device_bytes(st.handle))),
         "paper_context": "49.4-54.78% of V100 fp16 peak per GPU on 48-384 V100s (whole system, counts recompute)",
     }
     if not args.no_optimizer:
@@ -220,7 +226,10 @@ def main():
                 kern[cat] = {"launches": int(cnt), "avg_ms": ms / cnt, "total_ms": ms}
         for cat in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"):
             if cat in kern:
-                kern[cat]["tflops"] = per_layer_mb * sh.n_layers * M / (kern[cat]["total_ms"] * 1e-3) / 1e12
+                work = per_layer_mb * sh.n_layers * M
+                if cat == "gemm_fwd" and args.ckpt_stride:   # regenerated forward GEMMs, one FC2 per segment left out
+                    work += work - M * (sh.n_layers // args.ckpt_stride) * 2 * T * h * f_
+                kern[cat]["tflops"] = work / (kern[cat]["total_ms"] * 1e-3) / 1e12
         out["kernels"] = kern
         # roofline of the largest single kernel by time: the weight-gradient GEMM
         # (gemm_big_kernel<false,false,EPI_ACC_*,8>), one launch = one weight of one layer for a

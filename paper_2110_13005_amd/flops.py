@@ -4,8 +4,10 @@ Forward FLOPs of one layer on T = b*s tokens: the four weight GEMMs cost 2*T*(3h
 h*f + f*h) (= 24*T*h^2 when f = 4h); attention's two contractions cost 4*b*s^2*h when every
 (query, key) pair is counted (the paper's convention: the s/6h term of its Eq. 3) and
 half of that when only the causal pairs j <= i are (the work the method has to do).
-Forward + backward = 3x forward; this build stores activations, so there is no recompute
-forward (the paper's factor 96 = 4 * 24 contains one, Sec. 6.2)."""
+Forward + backward = 3x forward when activations are stored; with activation checkpointing
+(Sec. 5.1) the backward pass first runs the forward pass again (the paper's factor 96 = 4 * 24
+contains one, Sec. 6.2), except that this build leaves out the last contraction of every
+regenerated segment, whose result nobody reads."""
 
 PEAK_BF16_DENSE_TFLOPS = 2516.6   # MI355X: 256 CU x 2.4 GHz x 4096 flop/clk/CU
 PEAK_HBM_GBPS = 8000.0
@@ -23,6 +25,17 @@ def stage_batch_flops(shape, causal=True, n_microbatches=None):
     M = shape.n_microbatches if n_microbatches is None else n_microbatches
     return 3 * shape.n_layers * M * layer_forward_flops(
         shape.hidden, shape.ffn, shape.seq_len, shape.microbatch_size, causal)
+
+
+def regeneration_flops(shape, ckpt_stride, causal=True, n_microbatches=None):
+    """FLOPs of the forward work that backward passes repeat with checkpointing stride ckpt_stride
+    (0: none): one forward per layer minus the second MLP contraction of each segment's last layer."""
+    if not ckpt_stride:
+        return 0
+    M = shape.n_microbatches if n_microbatches is None else n_microbatches
+    per_layer = layer_forward_flops(shape.hidden, shape.ffn, shape.seq_len, shape.microbatch_size, causal)
+    skipped = 2 * shape.tokens * shape.hidden * shape.ffn
+    return M * (shape.n_layers * per_layer - (shape.n_layers // ckpt_stride) * skipped)
 
 
 def narayanan_flops(b, s, l, h, V=0, recompute=True):

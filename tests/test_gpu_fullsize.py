@@ -44,8 +44,10 @@ def _message_run(st, X, DY, Y, DX, n_streams=2):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("name", ["12b", "24b", "100b"])
-def test_full_size_stage_parity(name):
+@pytest.mark.parametrize("name,ac", [("12b", 0), ("24b", 0), ("100b", 0), ("12b", 2)])
+def test_full_size_stage_parity(name, ac):
+    """ac > 0: the same with activation checkpointing of that stride (Sec. 5.1), against the oracle's
+    regenerating pass."""
     import torch
     sh = CONFIGS[name]
     M = sh.n_microbatches
@@ -58,7 +60,8 @@ def test_full_size_stage_parity(name):
     # the 100B shape additionally takes the split-input QKV projection: with h = 10240 and N(0, 0.02)
     # weights the attention logits have standard deviation 4 and the peaked softmax amplifies the bf16
     # rounding of LayerNorm's output about sixfold (without it the worst gradient error is 3.4e-2)
-    opts = dict(grad_accum_fp32=0, wgrad_group=3, qkv_input_split=1 if name == "100b" else 0)
+    opts = dict(grad_accum_fp32=0, wgrad_group=3, qkv_input_split=1 if name == "100b" else 0, ckpt_stride=ac)
+    name = name if not ac else "%s/ac=%d" % (name, ac)
     with Stage(sh, **opts) as st:
         st.load_params(layers)
         bsh = (sh.microbatch_size, sh.seq_len, sh.hidden)
@@ -92,7 +95,14 @@ def test_full_size_stage_parity(name):
         assert e <= 1e-2, (n, e)       # M roundings of bf16 single-batch gradients vs one rounding
     _say("%s: oracle on microbatch 0 (fp64, host) ..." % name)
     t1 = time.time()
-    ref_out, ref_dx, ref_g = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
+    if ac:
+        from oracle import transformer as OT
+        l64 = [{k: np.asarray(v, np.float64) for k, v in p.items()} for p in layers]
+        z, kept = OT.stage_forward_checkpointed(xs[0], l64, sh.n_heads, EPS, ac)
+        dx, ref_g = OT.stage_backward_checkpointed(dys[0], kept, l64, sh.n_heads, EPS, ac)
+        ref_out, ref_dx = [z], [dx]
+    else:
+        ref_out, ref_dx, ref_g = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
     _say("%s: oracle took %.0f s" % (name, time.time() - t1))
     e_f = rel_fro(y0.reshape(ref_out[0].shape), ref_out[0])
     e_b = rel_fro(dx0.reshape(ref_dx[0].shape), ref_dx[0])
