@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--ckpt-stride", type=int, default=0,
                     help="activation checkpointing stride ac (0 = keep all activations, the default workload)")
     ap.add_argument("--bucket-elems", type=int, default=1 << 26)
+    ap.add_argument("--overlap-chunk", type=int, default=1,
+                    help="chunk size k (buckets) of the extra measurement with the optimizer step overlapped with "
+                         "the backward tail; 0 = skip that measurement")
     ap.add_argument("--no-optimizer", action="store_true", help="diagnostic: leave the Adam step out of the step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-profile", action="store_true")
@@ -146,18 +149,26 @@ def main():
     main_stream = torch.cuda.Stream()
     oc = OPT_CONFIG
 
-    def one_step(step_no, ev):
+    def one_step(step_no, ev, overlap_chunk=0):
+        """ev[0]: start, ev[1]: forward+backward work complete, ev[2]: step complete.  overlap_chunk > 0: the
+        optimizer step is queued right after the messages are dispatched and starts on the last layers'
+        buckets while the backward tail still runs; there is then no ev[1] (a stream that waited for the
+        batch alone would hold up whatever shares its hardware queue, the early fetches included)."""
         with torch.cuda.stream(main_stream):
             ev[0].record(main_stream)
             st.zero_grad(main_stream)
             for kind, i in order:
                 st.post(kind, i, X[i] if kind == 0 else DY[i], Y[i] if kind == 0 else DX[i])
             st.run(args.streams, main_stream)
-            st.join(main_stream)
-            ev[1].record(main_stream)
-            if not args.no_optimizer:
-                B.axonn_stage_optimizer_step(st.handle, oc["lr"], oc["beta1"], oc["beta2"], oc["eps"], oc["weight_decay"],
-                                             oc["step"] + step_no, 1.0 / M, main_stream)
+            hyper = (oc["lr"], oc["beta1"], oc["beta2"], oc["eps"], oc["weight_decay"], oc["step"] + step_no, 1.0 / M)
+            if overlap_chunk and not args.no_optimizer:
+                B.axonn_stage_optimizer_step_overlapped(st.handle, *hyper, overlap_chunk, main_stream)
+                st.join(main_stream)
+            else:
+                st.join(main_stream)
+                ev[1].record(main_stream)
+                if not args.no_optimizer:
+                    B.axonn_stage_optimizer_step(st.handle, *hyper, main_stream)
             ev[2].record(main_stream)
 
     def events():
@@ -205,6 +216,21 @@ def main():
         om = float(np.mean(opt_ms))
         out["optimizer"] = {"ms": om, "params": n, "host_link_GBps_each_way": 12.0 * n / (om * 1e-3) / 1e9,
                             "buckets": (n + args.bucket_elems - 1) // args.bucket_elems}
+        if args.overlap_chunk > 0:
+            # the same steps with the optimizer step overlapped with the backward tail (not part of `value`)
+            k_steps = max(2, min(args.steps, 5))
+            one_step(args.warmup + args.steps, events(), args.overlap_chunk)
+            torch.cuda.synchronize()
+            evo = [events() for _ in range(k_steps)]
+            t1 = time.perf_counter()
+            for k in range(k_steps):
+                one_step(args.warmup + args.steps + 1 + k, evo[k], args.overlap_chunk)
+            torch.cuda.synchronize()
+            wall_o = time.perf_counter() - t1
+            out["optimizer_overlapped"] = {
+                "chunk_buckets": args.overlap_chunk, "steps": k_steps, "ms_per_step": wall_o / k_steps * 1e3,
+                "ms_per_step_plain": wall / args.steps * 1e3,
+                "tokens_per_s_whole_step": tokens / (wall_o / k_steps)}
 
     # per-kernel averages: one more batch on a single stream with launch timing on
     if not args.no_kernel_profile:

@@ -202,6 +202,25 @@ int axonn_stage_optimizer_attach(axonn_stage_t* st, float* host_master, float* h
 int axonn_stage_optimizer_step(axonn_stage_t* st, double lr, double beta1, double beta2,
                                double eps, double weight_decay, int64_t step,
                                double grad_scale, void* hip_stream);
+/* The same step, started while the tail of the batch's backward work is still running (the
+ * one-GPU counterpart of Sec. 5.3, where a chunk of k buckets enters the optimizer as soon
+ * as its gradients have arrived).  Gradients become final layer by layer from the last
+ * layer down while the batch's last microbatch passes through Backward; the buckets are
+ * processed from the highest offset down in chunks of chunk_buckets (the paper's k), a
+ * chunk's updates starting when the lowest layer it touches is final; the fetches of the
+ * fp32 state do not wait for gradients at all (after a message-driven run with forward
+ * streams the first ones are queued on a forward stream, which is idle once the batch's
+ * forwards are through, so that they run during the backward work; those fetches are
+ * ordered after the previous step, not after hip_stream: the host state must be in place
+ * when the call is made).  Call it after the batch's last message has
+ * been dispatched (axonn_stage_run has returned, or the n_microbatches-th
+ * axonn_stage_backward) -- no axonn_stage_join is needed in between; AXONN_ESTATE before
+ * that.  hip_stream continues when the step is complete, which implies the batch is.
+ * Results are identical to axonn_stage_optimizer_step's. */
+int axonn_stage_optimizer_step_overlapped(axonn_stage_t* st, double lr, double beta1,
+                                          double beta2, double eps, double weight_decay,
+                                          int64_t step, double grad_scale,
+                                          int32_t chunk_buckets, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------
  * Single operations of the layer (the kernels Forward/Backward are built from), exposed

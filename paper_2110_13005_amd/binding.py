@@ -62,6 +62,7 @@ _PROTOTYPES = {
     "axonn_offload_adam_device_bytes": [_vp, C.POINTER(_u64)],
     "axonn_stage_optimizer_attach": [_vp, _vp, _vp, _vp, _u64, _u64],
     "axonn_stage_optimizer_step": [_vp, _d, _d, _d, _d, _d, _i64, _d, _vp],
+    "axonn_stage_optimizer_step_overlapped": [_vp, _d, _d, _d, _d, _d, _i64, _d, _i32, _vp],
     "axonn_gemm_bf16": [_i32, _i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64,
                         _vp, _i64, _i32, _vp],
     "axonn_layernorm_fwd": [_i64, _i64, _vp, _vp, _vp, _f, _vp, _vp, _vp],
@@ -254,6 +255,12 @@ def axonn_stage_optimizer_attach(st, host_master, host_m, host_v, n, bucket_elem
 
 def axonn_stage_optimizer_step(st, lr, beta1, beta2, eps, weight_decay, step, grad_scale, stream=None):
     _check(load().axonn_stage_optimizer_step(st, lr, beta1, beta2, eps, weight_decay, step, grad_scale, _stream(stream)))
+
+
+def axonn_stage_optimizer_step_overlapped(st, lr, beta1, beta2, eps, weight_decay, step, grad_scale, chunk_buckets,
+                                          stream=None):
+    _check(load().axonn_stage_optimizer_step_overlapped(st, lr, beta1, beta2, eps, weight_decay, step, grad_scale,
+                                                        chunk_buckets, _stream(stream)))
 
 
 def axonn_gemm_bf16(a_kcontig, b_kcontig, epilogue, M, N, K, A, lda, B, ldb, Cmat, ldc, bias=None, res=None,

@@ -11,6 +11,7 @@
 #include <cstdio>
 #include <cstring>
 #include <deque>
+#include <functional>
 #include <new>
 #include <string>
 #include <thread>
@@ -174,6 +175,11 @@ struct axonn_stage {
   hipEvent_t last_bwd = nullptr, last_wgrad = nullptr, fork_ev = nullptr;
   bool last_bwd_recorded = false, last_wgrad_recorded = false;
   int wgrad_flushes = 0;              // weight-gradient contractions since the last zero_grad
+  // per layer, for the last microbatch of a batch: chain_layer[l] = its backward chain has passed layer l;
+  // grads_final[l] = every gradient of layer l is final in the bf16 buffer (the overlapped optimizer step
+  // starts on a layer's parameters from there)
+  std::vector<hipEvent_t> chain_layer, grads_final;
+  bool grads_final_recorded = false;
   hipStream_t wgrad_stream = nullptr; // message-driven mode: weight gradients overlap other work
   hipEvent_t wgrad_tail = nullptr;
   // message-driven mode
@@ -350,7 +356,8 @@ int backward_layer(axonn_stage* st, int l, const LayerStash& a, bf16_t* d_out, i
   return AXONN_OK;
 }
 
-int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out, int acc, hipStream_t s) {
+int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out, int acc, bool last,
+                    hipStream_t s) {
   const int T = st->T, h = st->h, L = st->cfg.n_layers;
   // the upstream gradient is copied into the stash: it is an operand of the deferred weight
   // gradient and the caller may recycle its receive buffer
@@ -358,8 +365,10 @@ int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out
     ProfScope ps(PC_COPY_IN, s);
     HIP_TRY(hipMemcpyAsync(slot.layers[L - 1].dz, dy_in, (uint64_t)T * h * sizeof(bf16_t), hipMemcpyDeviceToDevice, s));
   }
-  for (int l = L - 1; l >= 0; --l)
+  for (int l = L - 1; l >= 0; --l) {
     AX_TRY(backward_layer(st, l, slot.layers[l], (l == 0) ? (bf16_t*)dx_out : slot.layers[l - 1].dz, acc, s));
+    if (last) HIP_TRY(hipEventRecord(st->chain_layer[l], s));
+  }
   return AXONN_OK;
 }
 
@@ -395,24 +404,46 @@ int wgrad_layer(axonn_stage* st, int l, const LayerStash* const* rec, int n, int
   return AXONN_OK;
 }
 
-int flush_wgrad(axonn_stage* st, hipStream_t s) {
+// Rounds layer l's fp32 gradient accumulators into the bf16 gradient buffer (fp32 accumulation only) and
+// marks the layer's gradients final on `s`.
+int finish_layer_grads(axonn_stage* st, int l, hipStream_t s) {
+  if (st->cfg.grad_accum_fp32) {
+    const uint64_t lo = st->tensors[l * kTensorsPerLayer].offset;
+    const uint64_t hi = (l + 1 < st->cfg.n_layers) ? st->tensors[(l + 1) * kTensorsPerLayer].offset : st->n_params;
+    ProfScope ps(PC_GRAD_CONVERT, s);
+    AX_TRY(check_launch(launch_f32_to_bf16(hi - lo, st->grads32 + lo, st->grads + lo, s), "f32_to_bf16"));
+  }
+  HIP_TRY(hipEventRecord(st->grads_final[l], s));
+  return AXONN_OK;
+}
+
+// Weight gradients of every slot that has finished its backward chain (see above).  `last_slot` is the
+// slot of the batch's last microbatch when this is the batch's final pass (else null): the pass then
+// follows that microbatch's chain layer by layer from the last layer down, and finishes each layer's
+// gradients as soon as its contractions are queued.
+int flush_wgrad(axonn_stage* st, hipStream_t s, Slot* last_slot = nullptr) {
   std::vector<Slot*> ready;
   for (Slot& sl : st->slots)
     if (sl.state == SLOT_AWAIT_WGRAD) ready.push_back(&sl);
   if (ready.empty()) return AXONN_OK;
   const int L = st->cfg.n_layers;
-  for (Slot* sl : ready) HIP_TRY(hipStreamWaitEvent(s, sl->dgrad_done, 0));
+  for (Slot* sl : ready)
+    if (sl != last_slot) HIP_TRY(hipStreamWaitEvent(s, sl->dgrad_done, 0));
   if (st->last_wgrad_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_wgrad, 0));
-  for (size_t first = 0; first < ready.size(); first += kMaxKSegments) {
-    const int n = (int)std::min<size_t>(kMaxKSegments, ready.size() - first);
-    const int acc = st->wgrad_flushes > 0 ? 1 : 0;
-    const LayerStash* rec[kMaxKSegments];
-    for (int l = 0; l < L; ++l) {
-      for (int i = 0; i < n; ++i) rec[i] = &ready[first + i]->layers[l];
+  for (int i = 0; i < L; ++i) {
+    const int l = last_slot ? L - 1 - i : i;
+    if (last_slot) HIP_TRY(hipStreamWaitEvent(s, st->chain_layer[l], 0));
+    for (size_t first = 0; first < ready.size(); first += kMaxKSegments) {
+      const int n = (int)std::min<size_t>(kMaxKSegments, ready.size() - first);
+      const int acc = (st->wgrad_flushes > 0 || first > 0) ? 1 : 0;
+      const LayerStash* rec[kMaxKSegments];
+      for (int k = 0; k < n; ++k) rec[k] = &ready[first + k]->layers[l];
       AX_TRY(wgrad_layer(st, l, rec, n, acc, s));
     }
-    st->wgrad_flushes++;
+    if (last_slot) AX_TRY(finish_layer_grads(st, l, s));
   }
+  st->wgrad_flushes++;
+  if (last_slot) st->grads_final_recorded = true;
   HIP_TRY(hipEventRecord(st->last_wgrad, s));
   st->last_wgrad_recorded = true;
   for (Slot* sl : ready) {
@@ -428,9 +459,9 @@ int flush_wgrad(axonn_stage* st, hipStream_t s) {
 // segment's last layer is not needed and not formed), the gradient chain runs back through them on `s`,
 // and their weight gradients follow at once on `ws`, since the set is about to be reused.  Three sets
 // rotate: while `ws` still reads one, the chain regenerates into the next and leaves the gradient that
-// crosses the segment boundary in the one after.
-int backward_layers_ckpt(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out, int acc, hipStream_t s,
-                         hipStream_t ws) {
+// crosses the segment boundary in the one after.  `last`: this is the batch's last microbatch.
+int backward_layers_ckpt(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out, int acc, bool last,
+                         hipStream_t s, hipStream_t ws) {
   const int T = st->T, h = st->h, L = st->cfg.n_layers, ac = st->cfg.ckpt_stride;
   const size_t n_sets = st->regen_sets.size();
   for (int seg = L / ac - 1; seg >= 0; --seg) {
@@ -459,6 +490,9 @@ int backward_layers_ckpt(axonn_stage* st, Slot& slot, const void* dy_in, void* d
       const LayerStash* one[1] = {&rec[i]};
       AX_TRY(wgrad_layer(st, seg * ac + i, one, 1, acc, ws));
     }
+    // last microbatch of the batch: the segment's gradients are final (the chain has passed its layers)
+    if (last)
+      for (int i = ac - 1; i >= 0; --i) AX_TRY(finish_layer_grads(st, seg * ac + i, ws));
     HIP_TRY(hipEventRecord(st->last_wgrad, ws));
     st->last_wgrad_recorded = true;
     HIP_TRY(hipEventRecord(R.released, ws));
@@ -522,33 +556,27 @@ int do_backward(axonn_stage* st, int mb_id, const void* dy, void* dx, hipStream_
   if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_bwd, 0));
   const int acc = st->bwd_count > 0 ? 1 : 0;
   const bool ckpt = st->cfg.ckpt_stride > 0;
-  if (ckpt) AX_TRY(backward_layers_ckpt(st, *slot, dy, dx, acc, s, ws));
-  else AX_TRY(backward_layers(st, *slot, dy, dx, acc, s));
+  const bool last = st->bwd_count + 1 == st->cfg.n_microbatches;
+  if (ckpt) AX_TRY(backward_layers_ckpt(st, *slot, dy, dx, acc, last, s, ws));
+  else AX_TRY(backward_layers(st, *slot, dy, dx, acc, last, s));
   st->bwd_count++;
   HIP_TRY(hipEventRecord(slot->dgrad_done, s));
   HIP_TRY(hipEventRecord(st->last_bwd, s));
   st->last_bwd_recorded = true;
   slot->mb_id = -1;
   st->in_flight--;
-  const bool last = st->bwd_count == st->cfg.n_microbatches;
   if (ckpt) {
     // the weight gradients are already queued and read the shared sets: the slot (kept inputs only) is
     // free as soon as the chain on `s` is through
     HIP_TRY(hipEventRecord(slot->released, s));
     slot->released_recorded = true;
     slot->state = SLOT_FREE;
+    if (last) st->grads_final_recorded = true;
   } else {
     slot->state = SLOT_AWAIT_WGRAD;
     const int group = st->cfg.wgrad_group;
-    if (last || (group > 0 && count_state(st, SLOT_AWAIT_WGRAD) >= group)) AX_TRY(flush_wgrad(st, ws));
-  }
-  if (last && st->cfg.grad_accum_fp32) {
-    // bias / LayerNorm gradients of the last chain (stream s) and all weight gradients (stream ws)
-    if (ws != s) HIP_TRY(hipStreamWaitEvent(ws, st->last_bwd, 0));
-    ProfScope ps(PC_GRAD_CONVERT, ws);
-    AX_TRY(check_launch(launch_f32_to_bf16(st->n_params, st->grads32, st->grads, ws), "f32_to_bf16"));
-    HIP_TRY(hipEventRecord(st->last_wgrad, ws));
-    st->last_wgrad_recorded = true;
+    if (last) AX_TRY(flush_wgrad(st, ws, slot));
+    else if (group > 0 && count_state(st, SLOT_AWAIT_WGRAD) >= group) AX_TRY(flush_wgrad(st, ws));
   }
   return AXONN_OK;
 }
@@ -598,6 +626,8 @@ void destroy_stage(axonn_stage* st) {
   }
   for (hipStream_t s : st->streams) (void)hipStreamDestroy(s);
   for (hipEvent_t e : st->stream_tail) (void)hipEventDestroy(e);
+  for (hipEvent_t e : st->chain_layer) if (e) (void)hipEventDestroy(e);
+  for (hipEvent_t e : st->grads_final) if (e) (void)hipEventDestroy(e);
   if (st->last_bwd) (void)hipEventDestroy(st->last_bwd);
   if (st->fork_ev) (void)hipEventDestroy(st->fork_ev);
   if (st->last_wgrad) (void)hipEventDestroy(st->last_wgrad);
@@ -788,6 +818,12 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
   CREATE_TRY(hipEventCreateWithFlags(&st->last_wgrad, hipEventDisableTiming));
   CREATE_TRY(hipEventCreateWithFlags(&st->wgrad_tail, hipEventDisableTiming));
   CREATE_TRY(hipEventCreateWithFlags(&st->fork_ev, hipEventDisableTiming));
+  st->chain_layer.assign(cfg->n_layers, nullptr);
+  st->grads_final.assign(cfg->n_layers, nullptr);
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    CREATE_TRY(hipEventCreateWithFlags(&st->chain_layer[l], hipEventDisableTiming));
+    CREATE_TRY(hipEventCreateWithFlags(&st->grads_final[l], hipEventDisableTiming));
+  }
   CREATE_TRY(hipDeviceSynchronize());
 #undef CREATE_TRY
   *out = st;
@@ -844,6 +880,7 @@ int axonn_stage_zero_grad(axonn_stage_t* st, void* hip_stream) {
     if (sl.state == SLOT_AWAIT_WGRAD) sl.state = SLOT_FREE;
   st->bwd_count = 0;
   st->wgrad_flushes = 0;
+  st->grads_final_recorded = false;
   st->fwd_issued = st->bwd_issued = 0;
   st->dispatch_log.clear();
   return AXONN_OK;
@@ -1049,33 +1086,53 @@ int axonn_offload_adam_device_bytes(const axonn_offload_adam_t* opt, uint64_t* b
   return AXONN_OK;
 }
 
-int axonn_offload_adam_step(axonn_offload_adam_t* o, double lr, double beta1, double beta2, double eps,
-                            double weight_decay, int64_t step, double grad_scale, void* hip_stream) {
-  if (!o) return fail(AXONN_EINVAL, "adam_step: null handle");
+namespace {
+int fetch_bucket(axonn_offload_adam* o, int set, uint64_t off, size_t bytes, hipStream_t s) {
+  // the set must have been drained by the bucket that used it last
+  if (o->d2h_recorded[set]) HIP_TRY(hipStreamWaitEvent(s, o->ev_d2h[set], 0));
+  HIP_TRY(hipMemcpyAsync(o->d_buf[set][0], o->h_theta + off, bytes, hipMemcpyHostToDevice, s));
+  HIP_TRY(hipMemcpyAsync(o->d_buf[set][1], o->h_m + off, bytes, hipMemcpyHostToDevice, s));
+  HIP_TRY(hipMemcpyAsync(o->d_buf[set][2], o->h_v + off, bytes, hipMemcpyHostToDevice, s));
+  HIP_TRY(hipEventRecord(o->ev_h2d[set], s));
+  return AXONN_OK;
+}
+
+// One pass over all buckets.  Without `gate`: in ascending order, after everything queued on the caller's
+// stream.  With `gate`: in descending order and in chunks of chunk_buckets buckets; the updates of a chunk
+// start once gate(lo, hi) (elements [lo, hi) of the chunk) has fired, while the fetches of the fp32 state
+// do not wait for gradients at all.  `early` (or null): a stream that has nothing left to do but the work
+// already queued on it; the first fetches (one per buffer set) go there instead of the fetch stream, whose
+// commands may share a hardware queue with busy streams and would then start behind all their queued work.
+int adam_pass(axonn_offload_adam* o, double lr, double beta1, double beta2, double eps, double weight_decay,
+              int64_t step, double grad_scale, hipStream_t user, int chunk_buckets,
+              const std::function<hipEvent_t(uint64_t, uint64_t)>* gate, hipStream_t early) {
   if (step < 1) return fail(AXONN_EINVAL, "adam_step: step must be >= 1 (got %lld)", (long long)step);
   if (!(beta1 >= 0. && beta1 < 1.) || !(beta2 >= 0. && beta2 < 1.))
     return fail(AXONN_EINVAL, "adam_step: betas must be in [0,1)");
   HIP_TRY(hipSetDevice(o->device));
-  hipStream_t user = (hipStream_t)hip_stream;
   constexpr int S = axonn_offload_adam::kSets;
-  // everything already queued on the caller's stream (the gradients) comes first
+  // everything already queued on the caller's stream comes first
   HIP_TRY(hipEventRecord(o->ev_start, user));
   HIP_TRY(hipStreamWaitEvent(o->s_h2d, o->ev_start, 0));
   HIP_TRY(hipStreamWaitEvent(o->s_k, o->ev_start, 0));
   HIP_TRY(hipStreamWaitEvent(o->s_d2h, o->ev_start, 0));
+  // the early fetches deliberately do not wait for the caller's stream: an event recorded there can sit in a
+  // hardware queue behind the whole batch; they are ordered after the previous pass by the sets' drain events
   const uint64_t nb = (o->n + o->bucket - 1) / o->bucket;
-  for (uint64_t b = 0; b < nb; ++b) {
-    const int set = (int)(b % S);
+  for (uint64_t i = 0; i < nb; ++i) {
+    const uint64_t b = gate ? nb - 1 - i : i;
+    const int set = (int)(i % S);
     const uint64_t off = b * o->bucket;
     const uint64_t cnt = std::min<uint64_t>(o->bucket, o->n - off);
     const size_t bytes = cnt * sizeof(float);
-    // fetch: the set must have been drained by the bucket that used it last
-    if (o->d2h_recorded[set]) HIP_TRY(hipStreamWaitEvent(o->s_h2d, o->ev_d2h[set], 0));
-    HIP_TRY(hipMemcpyAsync(o->d_buf[set][0], o->h_theta + off, bytes, hipMemcpyHostToDevice, o->s_h2d));
-    HIP_TRY(hipMemcpyAsync(o->d_buf[set][1], o->h_m + off, bytes, hipMemcpyHostToDevice, o->s_h2d));
-    HIP_TRY(hipMemcpyAsync(o->d_buf[set][2], o->h_v + off, bytes, hipMemcpyHostToDevice, o->s_h2d));
-    HIP_TRY(hipEventRecord(o->ev_h2d[set], o->s_h2d));
+    AX_TRY(fetch_bucket(o, set, off, bytes, (early && i < (uint64_t)S) ? early : o->s_h2d));
     // update
+    if (gate && i % (uint64_t)chunk_buckets == 0) {
+      // the chunk: the next chunk_buckets buckets in processing order, i.e. downwards from this one
+      const uint64_t n_in_chunk = std::min<uint64_t>((uint64_t)chunk_buckets, nb - i);
+      const uint64_t lo = (b + 1 - n_in_chunk) * o->bucket;
+      HIP_TRY(hipStreamWaitEvent(o->s_k, (*gate)(lo, off + cnt), 0));
+    }
     HIP_TRY(hipStreamWaitEvent(o->s_k, o->ev_h2d[set], 0));
     AX_TRY(adam(cnt, o->d_buf[set][0], o->d_buf[set][1], o->d_buf[set][2], o->g16 + off, o->p16 + off, lr, beta1,
                 beta2, eps, weight_decay, step, grad_scale, o->s_k));
@@ -1093,6 +1150,14 @@ int axonn_offload_adam_step(axonn_offload_adam_t* o, double lr, double beta1, do
   HIP_TRY(hipStreamWaitEvent(user, o->ev_d2h[last], 0));
   HIP_TRY(hipStreamWaitEvent(user, o->ev_k[last], 0));
   return AXONN_OK;
+}
+}  // namespace
+
+int axonn_offload_adam_step(axonn_offload_adam_t* o, double lr, double beta1, double beta2, double eps,
+                            double weight_decay, int64_t step, double grad_scale, void* hip_stream) {
+  if (!o) return fail(AXONN_EINVAL, "adam_step: null handle");
+  return adam_pass(o, lr, beta1, beta2, eps, weight_decay, step, grad_scale, (hipStream_t)hip_stream, 1, nullptr,
+                   nullptr);
 }
 
 int axonn_stage_optimizer_attach(axonn_stage_t* st, float* host_master, float* host_m, float* host_v,
@@ -1120,6 +1185,30 @@ int axonn_stage_optimizer_step(axonn_stage_t* st, double lr, double beta1, doubl
   return axonn_offload_adam_step(st->opt, lr, beta1, beta2, eps, weight_decay, step, grad_scale, hip_stream);
 }
 
+
+int axonn_stage_optimizer_step_overlapped(axonn_stage_t* st, double lr, double beta1, double beta2, double eps,
+                                          double weight_decay, int64_t step, double grad_scale,
+                                          int32_t chunk_buckets, void* hip_stream) {
+  if (!st) return fail(AXONN_EINVAL, "optimizer_step_overlapped: null handle");
+  if (!st->opt) return fail(AXONN_ESTATE, "optimizer_step_overlapped: no optimizer attached");
+  if (chunk_buckets < 1) return fail(AXONN_EINVAL, "optimizer_step_overlapped: chunk_buckets must be >= 1");
+  if (st->in_flight) return fail(AXONN_ESTATE, "optimizer_step_overlapped: %d microbatches in flight", st->in_flight);
+  if (!st->grads_final_recorded)
+    return fail(AXONN_ESTATE, "optimizer_step_overlapped: the batch is not complete (%d of %d backwards since "
+                "zero_grad)", st->bwd_count, st->cfg.n_microbatches);
+  HIP_TRY(hipSetDevice(st->cfg.device));
+  const int L = st->cfg.n_layers;
+  // gradients become final from the last layer down: a chunk may start once the lowest layer it touches is
+  const std::function<hipEvent_t(uint64_t, uint64_t)> gate = [st, L](uint64_t lo, uint64_t) {
+    int l = 0;
+    while (l + 1 < L && st->tensors[(l + 1) * kTensorsPerLayer].offset <= lo) ++l;
+    return st->grads_final[l];
+  };
+  // message-driven mode with forward streams: the first of them has no more work in this batch
+  hipStream_t early = st->streams.size() > 1 ? st->streams[1] : nullptr;
+  return adam_pass(st->opt, lr, beta1, beta2, eps, weight_decay, step, grad_scale, (hipStream_t)hip_stream,
+                   chunk_buckets, &gate, early);
+}
 
 // ----------------------------------------------------------------- launch timing
 int axonn_profile_enable(int32_t on) {
