@@ -145,6 +145,8 @@ typedef struct {
   const void* payload_dev;
   void* result_dev;
   void* ready_event;
+  const void* targets_dev; /* last stage only (axonn_stage_attach_ends): int32 [b,s] target ids  */
+  void* loss_dev;          /* last stage only: one float, the microbatch's pre-divided loss      */
 } axonn_msg;
 int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg);
 /* Consumes posted messages until n_microbatches forwards and n_microbatches backwards
@@ -221,6 +223,66 @@ int axonn_stage_optimizer_step_overlapped(axonn_stage_t* st, double lr, double b
                                           double beta2, double eps, double weight_decay,
                                           int64_t step, double grad_scale,
                                           int32_t chunk_buckets, void* hip_stream);
+
+/* ------------------------------------------------------------------------------------
+ * The two ends of the pipeline (the special cases of Alg. 2).  The first stage (i = 0)
+ * turns a microbatch of token ids into activations: x[b,i,:] = wte[token[b,i],:] + wpe[i,:].
+ * The last stage (i = G_inter - 1) applies a final LayerNorm and the LM head, computes the
+ * token-mean cross-entropy divided by the number of microbatches of the batch (Sec. 4.2:
+ * the loss is pre-divided, so that gradients summed over microbatches are those of the
+ * batch mean) and starts Backward(1) at once.  The paper prints no equations for them;
+ * these are the GPT ones, with a head matrix of its own ([h, V]; tying it to the token
+ * table needs a collective between the first and the last GPU).  Vocabulary 51200 in the
+ * paper's runs (Sec. 6.1); the head is the V/16lh term of Eq. 3.
+ * Both objects own flat bf16 parameter and gradient buffers (embedding: wte[V,h] then
+ * wpe[s,h]; head: lnf_g[h], lnf_b[h], w_head[h,V]; parameters start at zero, LayerNorm gain
+ * at one) that axonn_offload_adam_create can be pointed at.  Gradients accumulate in bf16
+ * over the calls since the last zero_grad (the first call overwrites).  Ids outside
+ * [0, vocab) are clamped into range.  All calls enqueue on hip_stream.
+ * ---------------------------------------------------------------------------------- */
+typedef struct axonn_embed axonn_embed_t;
+typedef struct axonn_head axonn_head_t;
+/* hidden % 8 == 0. */
+int axonn_embed_create(int32_t device, int32_t vocab, int32_t hidden, int32_t seq_len,
+                       int32_t microbatch_size, axonn_embed_t** out);
+int axonn_embed_destroy(axonn_embed_t* e);
+/* Borrowed device pointers and the element count (vocab + seq_len) * hidden; any may be NULL. */
+int axonn_embed_buffers(axonn_embed_t* e, void** params_dev_bf16, void** grads_dev_bf16,
+                        uint64_t* n_elements);
+int axonn_embed_zero_grad(axonn_embed_t* e);
+/* tokens_dev: int32 [b,s] on the device; x_dev_bf16: [b,s,h] written. */
+int axonn_embed_forward(axonn_embed_t* e, const int32_t* tokens_dev, void* x_dev_bf16,
+                        void* hip_stream);
+/* Adds the microbatch's table gradients: every use of a row adds its dx row (summed in
+ * fp32 in token order, one writer per row: reproducible); dwpe[i,:] += sum_b dx[b,i,:]. */
+int axonn_embed_backward(axonn_embed_t* e, const int32_t* tokens_dev, const void* dx_dev_bf16,
+                         void* hip_stream);
+/* hidden, vocab and tokens_per_microbatch (= b*s) multiples of 8.  Holds a [b*s, vocab]
+ * bf16 logit buffer. */
+int axonn_head_create(int32_t device, int32_t vocab, int32_t hidden,
+                      int32_t tokens_per_microbatch, int32_t n_microbatches, float ln_eps,
+                      axonn_head_t** out);
+int axonn_head_destroy(axonn_head_t* hd);
+int axonn_head_buffers(axonn_head_t* hd, void** params_dev_bf16, void** grads_dev_bf16,
+                       uint64_t* n_elements);
+int axonn_head_zero_grad(axonn_head_t* hd);
+/* Forward, loss and Backward(1) of one microbatch: x_dev_bf16 [b,s,h] is the last layer's
+ * output, targets_dev int32 [b,s]; loss_dev receives one float (mean token loss / number
+ * of microbatches), dx_dev_bf16 [b,s,h] the gradient to run the stage's Backward on; the
+ * head's gradients are accumulated. */
+int axonn_head_forward_backward(axonn_head_t* hd, const void* x_dev_bf16,
+                                const int32_t* targets_dev, float* loss_dev,
+                                void* dx_dev_bf16, void* hip_stream);
+/* Makes a stage the first and / or the last one of the pipeline (either handle may be NULL;
+ * the handles stay the caller's).  In message-driven mode a forward message to a first
+ * stage then carries int32 token ids [b,s] as payload (the buffer must stay valid until the
+ * microbatch's backward has run) and its backward messages may leave result_dev NULL; a
+ * forward message to a last stage carries targets_dev and loss_dev, is followed at once by
+ * the loss and Backward, and result_dev receives the input gradient to send back; a last
+ * stage accepts no backward messages.  axonn_stage_zero_grad also restarts the ends'
+ * accumulation.  With ends attached axonn_stage_forward / _backward return AXONN_ESTATE.
+ * Sizes must match the stage's (AXONN_EINVAL otherwise). */
+int axonn_stage_attach_ends(axonn_stage_t* st, axonn_embed_t* embed, axonn_head_t* head);
 
 /* ------------------------------------------------------------------------------------
  * Single operations of the layer (the kernels Forward/Backward are built from), exposed

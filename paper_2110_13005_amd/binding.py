@@ -33,7 +33,8 @@ class axonn_stage_config(C.Structure):
 
 class axonn_msg(C.Structure):
     _fields_ = [("kind", C.c_int32), ("mb_id", C.c_int32), ("payload_dev", C.c_void_p),
-                ("result_dev", C.c_void_p), ("ready_event", C.c_void_p)]
+                ("result_dev", C.c_void_p), ("ready_event", C.c_void_p),
+                ("targets_dev", C.c_void_p), ("loss_dev", C.c_void_p)]
 
 
 _vp, _i32, _i64, _u64, _f, _d = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float, C.c_double
@@ -56,6 +57,18 @@ _PROTOTYPES = {
     "axonn_stage_join": [_vp, _vp],
     "axonn_stage_synchronize": [_vp],
     "axonn_stage_dispatch_log": [_vp, C.POINTER(_i32), _i32, C.POINTER(_i32)],
+    "axonn_embed_create": [_i32, _i32, _i32, _i32, _i32, C.POINTER(_vp)],
+    "axonn_embed_destroy": [_vp],
+    "axonn_embed_buffers": [_vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_u64)],
+    "axonn_embed_zero_grad": [_vp],
+    "axonn_embed_forward": [_vp, _vp, _vp, _vp],
+    "axonn_embed_backward": [_vp, _vp, _vp, _vp],
+    "axonn_head_create": [_i32, _i32, _i32, _i32, _i32, _f, C.POINTER(_vp)],
+    "axonn_head_destroy": [_vp],
+    "axonn_head_buffers": [_vp, C.POINTER(_vp), C.POINTER(_vp), C.POINTER(_u64)],
+    "axonn_head_zero_grad": [_vp],
+    "axonn_head_forward_backward": [_vp, _vp, _vp, _vp, _vp, _vp],
+    "axonn_stage_attach_ends": [_vp, _vp, _vp],
     "axonn_offload_adam_create": [_i32, _u64, _u64, _vp, _vp, _vp, _vp, _vp, C.POINTER(_vp)],
     "axonn_offload_adam_destroy": [_vp],
     "axonn_offload_adam_step": [_vp, _d, _d, _d, _d, _d, _i64, _d, _vp],
@@ -203,10 +216,70 @@ def axonn_stage_backward(st, mb_id, dy, dx, stream=None):
     _check(load().axonn_stage_backward(st, mb_id, _ptr(dy), _ptr(dx), _stream(stream)))
 
 
-def axonn_stage_post(st, kind, mb_id, payload, result, ready_event=None):
+def axonn_stage_post(st, kind, mb_id, payload, result, ready_event=None, targets=None, loss=None):
     ev = ready_event if (ready_event is None or isinstance(ready_event, int)) else ready_event.cuda_event
-    m = axonn_msg(kind, mb_id, _ptr(payload), _ptr(result), ev)
+    m = axonn_msg(kind, mb_id, _ptr(payload), _ptr(result), ev, _ptr(targets), _ptr(loss))
     _check(load().axonn_stage_post(st, C.byref(m)))
+
+
+def axonn_embed_create(device, vocab, hidden, seq_len, microbatch_size):
+    out = _vp()
+    _check(load().axonn_embed_create(device, vocab, hidden, seq_len, microbatch_size, C.byref(out)))
+    return out
+
+
+def axonn_embed_destroy(e):
+    _check(load().axonn_embed_destroy(e))
+
+
+def _buffers(fn, handle):
+    p, g, n = _vp(), _vp(), _u64()
+    _check(fn(handle, C.byref(p), C.byref(g), C.byref(n)))
+    return p.value, g.value, n.value
+
+
+def axonn_embed_buffers(e):
+    """(params pointer, grads pointer, element count)."""
+    return _buffers(load().axonn_embed_buffers, e)
+
+
+def axonn_embed_zero_grad(e):
+    _check(load().axonn_embed_zero_grad(e))
+
+
+def axonn_embed_forward(e, tokens, x, stream=None):
+    _check(load().axonn_embed_forward(e, _ptr(tokens), _ptr(x), _stream(stream)))
+
+
+def axonn_embed_backward(e, tokens, dx, stream=None):
+    _check(load().axonn_embed_backward(e, _ptr(tokens), _ptr(dx), _stream(stream)))
+
+
+def axonn_head_create(device, vocab, hidden, tokens_per_microbatch, n_microbatches, ln_eps=1e-5):
+    out = _vp()
+    _check(load().axonn_head_create(device, vocab, hidden, tokens_per_microbatch, n_microbatches, ln_eps, C.byref(out)))
+    return out
+
+
+def axonn_head_destroy(hd):
+    _check(load().axonn_head_destroy(hd))
+
+
+def axonn_head_buffers(hd):
+    """(params pointer, grads pointer, element count)."""
+    return _buffers(load().axonn_head_buffers, hd)
+
+
+def axonn_head_zero_grad(hd):
+    _check(load().axonn_head_zero_grad(hd))
+
+
+def axonn_head_forward_backward(hd, x, targets, loss, dx, stream=None):
+    _check(load().axonn_head_forward_backward(hd, _ptr(x), _ptr(targets), _ptr(loss), _ptr(dx), _stream(stream)))
+
+
+def axonn_stage_attach_ends(st, embed=None, head=None):
+    _check(load().axonn_stage_attach_ends(st, embed, head))
 
 
 def axonn_stage_run(st, n_streams=2, stream=None):

@@ -186,6 +186,14 @@ hipError_t launch_attention_fwd(int b, int s, int a, int d, const void* qkv, voi
 hipError_t launch_attention_bwd(int b, int s, int a, int d, const void* qkv, const void* o,
                                 const float* lse, const void* dout, void* dqkv, float* delta,
                                 hipStream_t st);
+hipError_t launch_embed_fwd(int T, int h, int s, int vocab, const int* tokens, const void* wte, const void* wpe,
+                            void* x, hipStream_t st);
+hipError_t launch_embed_bwd(int b, int s, int h, int vocab, const int* tokens, const void* dx, void* dwte,
+                            void* dwpe, int accumulate, hipStream_t st);
+// Cross-entropy over bf16 logits [T, V]: token_loss[t] and loss[0] = sum_t token_loss[t] / (T * n_microbatches);
+// the logits are overwritten by dloss/dlogits.
+hipError_t launch_xent(int T, int V, void* logits, const int* targets, int n_microbatches, float* token_loss,
+                       float* loss, hipStream_t st);
 hipError_t launch_adam(uint64_t n, float* theta, float* m, float* v, const void* g16,
                        void* p16, double lr, double b1, double b2, double eps, double wd,
                        int64_t step, double grad_scale, hipStream_t s);

@@ -50,10 +50,10 @@ int fail(int code, const char* fmt, ...) {
 
 // ---- optional per-launch timing: event pairs around every kernel launch, by category ----
 enum ProfCat { PC_GEMM_FWD, PC_GEMM_DGRAD, PC_GEMM_WGRAD, PC_ATTN_FWD, PC_ATTN_BWD, PC_LN_FWD,
-               PC_LN_BWD, PC_COLSUM, PC_GRAD_CONVERT, PC_ADAM, PC_COPY_IN, PC_COUNT };
+               PC_LN_BWD, PC_COLSUM, PC_GRAD_CONVERT, PC_ADAM, PC_COPY_IN, PC_EMBED, PC_XENT, PC_COUNT };
 const char* const kProfNames[PC_COUNT] = {
     "gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attention_fwd", "attention_bwd", "layernorm_fwd",
-    "layernorm_bwd", "colsum", "grad_convert", "adam", "copy_in"};
+    "layernorm_bwd", "colsum", "grad_convert", "adam", "copy_in", "embedding", "cross_entropy"};
 struct ProfRec { int cat; hipEvent_t a, b; };
 bool g_prof_on = false;
 std::vector<ProfRec> g_prof_recs;
@@ -114,6 +114,8 @@ struct Slot {
   // released: the weight-gradient contraction that read the slot finished (slot reusable)
   hipEvent_t fwd_done = nullptr, dgrad_done = nullptr, released = nullptr;
   bool released_recorded = false;
+  const int32_t* tokens = nullptr;   // first stage: the microbatch's token ids, needed again by Backward
+  bf16_t* head_y = nullptr;          // last stage: the stage output the head consumes
 };
 
 struct PendingMsg {
@@ -148,6 +150,28 @@ struct axonn_offload_adam {
   hipEvent_t ev_start = nullptr, ev_h2d[kSets] = {}, ev_k[kSets] = {}, ev_d2h[kSets] = {};
   bool d2h_recorded[kSets] = {};
   uint64_t device_bytes = 0;
+};
+
+// First-stage extras (Alg. 2, i = 0): token and position tables in one flat bf16 buffer [wte | wpe].
+struct axonn_embed {
+  int device = 0, vocab = 0, h = 0, s = 0, b = 0;
+  uint64_t n_params = 0;
+  bf16_t *params = nullptr, *grads = nullptr;
+  int bwd_count = 0;   // backward passes since zero_grad
+};
+
+// Last-stage extras (Alg. 2, i = G_inter - 1): final LayerNorm, LM head, loss.  Flat bf16 buffer
+// [lnf_g | lnf_b | w_head[h, V]].
+struct axonn_head {
+  int device = 0, vocab = 0, h = 0, T = 0, M = 0;
+  float eps = 1e-5f;
+  uint64_t n_params = 0;
+  bf16_t *params = nullptr, *grads = nullptr;
+  char* ws_base = nullptr;
+  uint64_t ws_bytes = 0;
+  bf16_t *a = nullptr, *logits = nullptr, *da = nullptr;
+  float *stats = nullptr, *token_loss = nullptr, *red_ws = nullptr;
+  int count = 0;       // microbatches since zero_grad
 };
 
 struct axonn_stage {
@@ -190,6 +214,10 @@ struct axonn_stage {
   int fwd_issued = 0, bwd_issued = 0;  // within the current batch (run mode)
   std::vector<int32_t> dispatch_log;
   axonn_offload_adam* opt = nullptr;
+  // the two ends of the pipeline, when this stage is the first and / or the last one (borrowed handles)
+  axonn_embed* embed = nullptr;
+  axonn_head* head = nullptr;
+  bf16_t *embed_dx = nullptr, *head_dx = nullptr, *head_y_base = nullptr;
 };
 
 namespace {
@@ -519,6 +547,9 @@ Slot* find_free(axonn_stage* st) {
 }
 
 // `ws` is the stream weight-gradient passes go to (the caller's stream in direct mode).
+int embed_forward(axonn_embed* e, const int32_t* tokens, void* x, hipStream_t s);
+
+// `x` holds [b,s,h] bf16 activations, or, on a stage with an embedding attached, [b,s] int32 token ids.
 int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s, hipStream_t ws) {
   if (mb_id < 0) return fail(AXONN_EINVAL, "forward: negative microbatch id %d", mb_id);
   if (find_live(st, mb_id)) return fail(AXONN_ESTATE, "forward: microbatch %d is already in flight", mb_id);
@@ -535,7 +566,11 @@ int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s
   // the weight-gradient pass that read the slot's previous contents must have finished
   if (slot->released_recorded) HIP_TRY(hipStreamWaitEvent(s, slot->released, 0));
   const uint64_t bytes = (uint64_t)st->T * st->h * sizeof(bf16_t);
-  {
+  if (st->head) y = slot->head_y;   // the last stage's output goes to its own head, not onwards
+  if (st->embed) {
+    slot->tokens = (const int32_t*)x;
+    AX_TRY(embed_forward(st->embed, slot->tokens, slot->layers[0].x, s));
+  } else {
     ProfScope ps(PC_COPY_IN, s);
     HIP_TRY(hipMemcpyAsync(slot->layers[0].x, x, bytes, hipMemcpyDeviceToDevice, s));
   }
@@ -580,6 +615,23 @@ int do_backward(axonn_stage* st, int mb_id, const void* dy, void* dx, hipStream_
   }
   return AXONN_OK;
 }
+
+int embed_backward(axonn_embed* e, const int32_t* tokens, const void* dx, hipStream_t s);
+
+// Backward(msg), followed on the first stage by the embedding's backward pass.
+int backward_msg(axonn_stage* st, int mb_id, const void* dy, void* dx, hipStream_t s, hipStream_t ws) {
+  if (!st->embed) return do_backward(st, mb_id, dy, dx, s, ws);
+  Slot* slot = (mb_id >= 0) ? find_live(st, mb_id) : nullptr;
+  const int32_t* tokens = slot ? slot->tokens : nullptr;
+  AX_TRY(do_backward(st, mb_id, dy, st->embed_dx, s, ws));
+  AX_TRY(embed_backward(st->embed, tokens, st->embed_dx, s));
+  // the next backward chain overwrites embed_dx: it must follow the embedding's pass as well
+  HIP_TRY(hipEventRecord(st->last_bwd, s));
+  return AXONN_OK;
+}
+
+int head_forward_backward(axonn_head* hd, const void* x, const int32_t* targets, float* loss, void* dx,
+                          hipStream_t s);
 
 int ensure_streams(axonn_stage* st, int n) {
   while ((int)st->streams.size() < n) {
@@ -639,6 +691,9 @@ void destroy_stage(axonn_stage* st) {
       if (a.chain_done) (void)hipEventDestroy(a.chain_done);
       if (a.released) (void)hipEventDestroy(a.released);
     }
+  if (st->embed_dx) (void)hipFree(st->embed_dx);
+  if (st->head_dx) (void)hipFree(st->head_dx);
+  if (st->head_y_base) (void)hipFree(st->head_y_base);
   if (st->ws_base) (void)hipFree(st->ws_base);
   if (st->params) (void)hipFree(st->params);
   if (st->grads) (void)hipFree(st->grads);
@@ -669,6 +724,55 @@ int validate_config(const axonn_stage_config* c) {
   if (c->hidden > 16384) return fail(AXONN_EUNSUPPORTED, "hidden > 16384 unsupported by the LayerNorm kernel");
   if ((int64_t)c->seq_len * c->microbatch_size > (1 << 24))
     return fail(AXONN_EUNSUPPORTED, "more than 2^24 tokens per microbatch unsupported");
+  return AXONN_OK;
+}
+
+// ------------------------------------------------------------------ the pipeline's two ends
+int embed_forward(axonn_embed* e, const int32_t* tokens, void* x, hipStream_t s) {
+  ProfScope ps(PC_EMBED, s);
+  return check_launch(launch_embed_fwd(e->b * e->s, e->h, e->s, e->vocab, tokens, e->params,
+                                       e->params + (uint64_t)e->vocab * e->h, x, s), "embed_fwd");
+}
+
+int embed_backward(axonn_embed* e, const int32_t* tokens, const void* dx, hipStream_t s) {
+  bf16_t* dwte = e->grads;
+  bf16_t* dwpe = e->grads + (uint64_t)e->vocab * e->h;
+  const int acc = e->bwd_count > 0 ? 1 : 0;
+  ProfScope ps(PC_EMBED, s);
+  // the table kernel touches only the rows whose ids occur: the first pass of a batch clears the table
+  if (!acc) AX_TRY(check_launch(launch_fill_bf16((uint64_t)e->vocab * e->h, dwte, 0.0f, s), "fill"));
+  AX_TRY(check_launch(launch_embed_bwd(e->b, e->s, e->h, e->vocab, tokens, dx, dwte, dwpe, acc, s), "embed_bwd"));
+  e->bwd_count++;
+  return AXONN_OK;
+}
+
+// Forward of the last-stage extras followed at once by Backward(1) (Alg. 2): a = LN(x), logits = a W,
+// loss and dL/dlogits in place, dW += a^T dlogits, da = dlogits W^T, dx = LN'(da).
+int head_forward_backward(axonn_head* hd, const void* x, const int32_t* targets, float* loss, void* dx,
+                          hipStream_t s) {
+  const int T = hd->T, h = hd->h, V = hd->vocab;
+  bf16_t* g = hd->params;
+  bf16_t* bt = hd->params + h;
+  bf16_t* W = hd->params + 2 * (uint64_t)h;
+  const int acc = hd->count > 0 ? 1 : 0;
+  AX_TRY(ln_fwd(T, h, x, g, bt, hd->eps, hd->a, nullptr, hd->stats, s));
+  AX_TRY(gemm(true, false, EPI_BIAS, T, V, h, hd->a, h, W, V, hd->logits, V, nullptr, nullptr, 0, nullptr, 0, 0, s));
+  {
+    ProfScope ps(PC_XENT, s);
+    AX_TRY(check_launch(launch_xent(T, V, hd->logits, targets, hd->M, hd->token_loss, loss, s), "cross_entropy"));
+  }
+  {
+    const bf16_t* A[1] = {hd->a};
+    const bf16_t* B[1] = {hd->logits};
+    AX_TRY(gemm_seg(EPI_ACC_BF16, h, V, T, A, h, B, V, 1, hd->grads + 2 * (uint64_t)h, V, acc, s));
+  }
+  AX_TRY(gemm(true, true, EPI_BIAS, T, h, V, hd->logits, V, W, V, hd->da, h, nullptr, nullptr, 0, nullptr, 0, 0, s));
+  {
+    ProfScope ps(PC_LN_BWD, s);
+    AX_TRY(check_launch(launch_layernorm_bwd(T, h, hd->da, x, hd->stats, g, nullptr, dx, hd->grads, hd->grads + h,
+                                             acc ? 2 : 1, false, hd->red_ws, s), "layernorm_bwd (head)"));
+  }
+  hd->count++;
   return AXONN_OK;
 }
 
@@ -881,6 +985,8 @@ int axonn_stage_zero_grad(axonn_stage_t* st, void* hip_stream) {
   st->bwd_count = 0;
   st->wgrad_flushes = 0;
   st->grads_final_recorded = false;
+  if (st->embed) st->embed->bwd_count = 0;
+  if (st->head) st->head->count = 0;
   st->fwd_issued = st->bwd_issued = 0;
   st->dispatch_log.clear();
   return AXONN_OK;
@@ -898,11 +1004,15 @@ int axonn_stage_device_bytes(const axonn_stage_t* st, uint64_t bytes[6]) {
 
 int axonn_stage_forward(axonn_stage_t* st, int32_t mb_id, const void* x, void* y, void* hip_stream) {
   if (!st || !x || !y) return fail(AXONN_EINVAL, "forward: null argument");
+  if (st->embed || st->head)
+    return fail(AXONN_ESTATE, "forward: a stage with the pipeline's ends attached runs in message-driven mode");
   HIP_TRY(hipSetDevice(st->cfg.device));
   return do_forward(st, mb_id, x, y, (hipStream_t)hip_stream, (hipStream_t)hip_stream);
 }
 int axonn_stage_backward(axonn_stage_t* st, int32_t mb_id, const void* dy, void* dx, void* hip_stream) {
   if (!st || !dy || !dx) return fail(AXONN_EINVAL, "backward: null argument");
+  if (st->embed || st->head)
+    return fail(AXONN_ESTATE, "backward: a stage with the pipeline's ends attached runs in message-driven mode");
   HIP_TRY(hipSetDevice(st->cfg.device));
   return do_backward(st, mb_id, dy, dx, (hipStream_t)hip_stream, (hipStream_t)hip_stream);
 }
@@ -910,7 +1020,15 @@ int axonn_stage_backward(axonn_stage_t* st, int32_t mb_id, const void* dy, void*
 int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg) {
   if (!st || !msg) return fail(AXONN_EINVAL, "post: null argument");
   if (msg->kind != 0 && msg->kind != 1) return fail(AXONN_EINVAL, "post: kind must be 0 (forward) or 1 (backward)");
-  if (!msg->payload_dev || !msg->result_dev) return fail(AXONN_EINVAL, "post: null payload or result buffer");
+  if (!msg->payload_dev) return fail(AXONN_EINVAL, "post: null payload");
+  // a result nobody receives may be left out: the input gradient of a stage that starts with the embedding
+  const bool result_unused = st->embed && (msg->kind == 1 || st->head);
+  if (!msg->result_dev && !result_unused) return fail(AXONN_EINVAL, "post: null result buffer");
+  if (st->head && msg->kind == 1)
+    return fail(AXONN_ESTATE, "post: the last stage starts Backward itself after each Forward (Alg. 2); it takes "
+                "no messages from a next stage");
+  if (st->head && msg->kind == 0 && (!msg->targets_dev || !msg->loss_dev))
+    return fail(AXONN_EINVAL, "post: a forward message to the last stage needs targets_dev and loss_dev");
   if (msg->mb_id < 0) return fail(AXONN_EINVAL, "post: negative microbatch id");
   int same = 0;
   for (const PendingMsg& p : st->inbox)
@@ -990,11 +1108,25 @@ int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream) {
     if (m.kind == 0) {
       AX_TRY(do_forward(st, m.mb_id, m.payload_dev, m.result_dev, s, ws));
       st->fwd_issued++;
+      st->dispatch_log.push_back(m.mb_id * 2);
+      if (st->head) {
+        // last stage (Alg. 2): the loss follows the forward pass and Backward(1) starts at once, on the
+        // stream of the backward chains
+        Slot* slot = find_live(st, m.mb_id);
+        hipStream_t bs = st->streams[0];
+        HIP_TRY(hipStreamWaitEvent(bs, slot->fwd_done, 0));
+        if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(bs, st->last_bwd, 0));   // head_dx is shared
+        AX_TRY(head_forward_backward(st->head, slot->head_y, (const int32_t*)m.targets_dev, (float*)m.loss_dev,
+                                     st->head_dx, bs));
+        AX_TRY(backward_msg(st, m.mb_id, st->head_dx, m.result_dev, bs, ws));
+        st->bwd_issued++;
+        st->dispatch_log.push_back(m.mb_id * 2 + 1);
+      }
     } else {
-      AX_TRY(do_backward(st, m.mb_id, m.payload_dev, m.result_dev, s, ws));
+      AX_TRY(backward_msg(st, m.mb_id, m.payload_dev, m.result_dev, s, ws));
       st->bwd_issued++;
+      st->dispatch_log.push_back(m.mb_id * 2 + 1);
     }
-    st->dispatch_log.push_back(m.mb_id * 2 + m.kind);
   }
   return AXONN_OK;
 }
@@ -1208,6 +1340,159 @@ int axonn_stage_optimizer_step_overlapped(axonn_stage_t* st, double lr, double b
   hipStream_t early = st->streams.size() > 1 ? st->streams[1] : nullptr;
   return adam_pass(st->opt, lr, beta1, beta2, eps, weight_decay, step, grad_scale, (hipStream_t)hip_stream,
                    chunk_buckets, &gate, early);
+}
+
+// ------------------------------------------------------------- first / last stage extras
+int axonn_embed_create(int32_t device, int32_t vocab, int32_t hidden, int32_t seq_len, int32_t microbatch_size,
+                       axonn_embed_t** out) {
+  if (!out) return fail(AXONN_EINVAL, "embed_create: null argument");
+  *out = nullptr;
+  if (device < 0 || vocab < 1 || hidden < 8 || seq_len < 1 || microbatch_size < 1)
+    return fail(AXONN_EINVAL, "embed_create: sizes must be positive");
+  if (hidden % 8) return fail(AXONN_EUNSUPPORTED, "embed_create: hidden must be a multiple of 8 (16-byte rows)");
+  HIP_TRY(hipSetDevice(device));
+  axonn_embed* e = new (std::nothrow) axonn_embed();
+  if (!e) return fail(AXONN_ENOMEM, "embed_create: host allocation failed");
+  e->device = device; e->vocab = vocab; e->h = hidden; e->s = seq_len; e->b = microbatch_size;
+  e->n_params = ((uint64_t)vocab + seq_len) * hidden;
+  hipError_t err = hipMalloc((void**)&e->params, e->n_params * sizeof(bf16_t));
+  if (err == hipSuccess) err = hipMalloc((void**)&e->grads, e->n_params * sizeof(bf16_t));
+  if (err == hipSuccess) err = hipMemset(e->params, 0, e->n_params * sizeof(bf16_t));
+  if (err == hipSuccess) err = hipMemset(e->grads, 0, e->n_params * sizeof(bf16_t));
+  if (err != hipSuccess) {
+    if (e->params) (void)hipFree(e->params);
+    if (e->grads) (void)hipFree(e->grads);
+    delete e;
+    return fail(err == hipErrorOutOfMemory ? AXONN_ENOMEM : AXONN_EHIP, "embed_create: %s", hipGetErrorString(err));
+  }
+  *out = e;
+  return AXONN_OK;
+}
+int axonn_embed_destroy(axonn_embed_t* e) {
+  if (!e) return fail(AXONN_EINVAL, "embed_destroy: null handle");
+  (void)hipSetDevice(e->device);
+  (void)hipDeviceSynchronize();
+  (void)hipFree(e->params);
+  (void)hipFree(e->grads);
+  delete e;
+  return AXONN_OK;
+}
+int axonn_embed_buffers(axonn_embed_t* e, void** params_dev_bf16, void** grads_dev_bf16, uint64_t* n_elements) {
+  if (!e) return fail(AXONN_EINVAL, "embed_buffers: null handle");
+  if (params_dev_bf16) *params_dev_bf16 = e->params;
+  if (grads_dev_bf16) *grads_dev_bf16 = e->grads;
+  if (n_elements) *n_elements = e->n_params;
+  return AXONN_OK;
+}
+int axonn_embed_zero_grad(axonn_embed_t* e) {
+  if (!e) return fail(AXONN_EINVAL, "embed_zero_grad: null handle");
+  e->bwd_count = 0;
+  return AXONN_OK;
+}
+int axonn_embed_forward(axonn_embed_t* e, const int32_t* tokens_dev, void* x_dev_bf16, void* hip_stream) {
+  if (!e || !tokens_dev || !x_dev_bf16) return fail(AXONN_EINVAL, "embed_forward: null argument");
+  HIP_TRY(hipSetDevice(e->device));
+  return embed_forward(e, tokens_dev, x_dev_bf16, (hipStream_t)hip_stream);
+}
+int axonn_embed_backward(axonn_embed_t* e, const int32_t* tokens_dev, const void* dx_dev_bf16, void* hip_stream) {
+  if (!e || !tokens_dev || !dx_dev_bf16) return fail(AXONN_EINVAL, "embed_backward: null argument");
+  HIP_TRY(hipSetDevice(e->device));
+  return embed_backward(e, tokens_dev, dx_dev_bf16, (hipStream_t)hip_stream);
+}
+
+int axonn_head_create(int32_t device, int32_t vocab, int32_t hidden, int32_t tokens_per_microbatch,
+                      int32_t n_microbatches, float ln_eps, axonn_head_t** out) {
+  if (!out) return fail(AXONN_EINVAL, "head_create: null argument");
+  *out = nullptr;
+  if (device < 0 || vocab < 1 || hidden < 8 || tokens_per_microbatch < 1 || n_microbatches < 1 || !(ln_eps > 0.f))
+    return fail(AXONN_EINVAL, "head_create: sizes and ln_eps must be positive");
+  if (hidden % 8 || vocab % 8 || tokens_per_microbatch % 8)
+    return fail(AXONN_EUNSUPPORTED, "head_create: hidden, vocab and tokens_per_microbatch must be multiples of 8");
+  if (hidden > 16384) return fail(AXONN_EUNSUPPORTED, "head_create: hidden > 16384 unsupported by the LayerNorm kernel");
+  if ((int64_t)tokens_per_microbatch > (1 << 24)) return fail(AXONN_EUNSUPPORTED, "head_create: too many tokens");
+  HIP_TRY(hipSetDevice(device));
+  axonn_head* hd = new (std::nothrow) axonn_head();
+  if (!hd) return fail(AXONN_ENOMEM, "head_create: host allocation failed");
+  hd->device = device; hd->vocab = vocab; hd->h = hidden; hd->T = tokens_per_microbatch; hd->M = n_microbatches;
+  hd->eps = ln_eps;
+  const uint64_t T = hd->T, h = hd->h, V = hd->vocab;
+  hd->n_params = 2 * h + h * V;
+  const uint64_t e_th = align_up(T * h * 2, 256), e_tv = align_up(T * V * 2, 256), e_st = align_up(T * 2 * 4, 256),
+                 e_tl = align_up(T * 4, 256), e_red = align_up(2 * ((T + 63) / 64) * h * 4, 256);
+  hd->ws_bytes = 2 * e_th + e_tv + e_st + e_tl + e_red;
+  hipError_t err = hipMalloc((void**)&hd->params, hd->n_params * sizeof(bf16_t));
+  if (err == hipSuccess) err = hipMalloc((void**)&hd->grads, hd->n_params * sizeof(bf16_t));
+  if (err == hipSuccess) err = hipMalloc((void**)&hd->ws_base, hd->ws_bytes);
+  if (err == hipSuccess) err = hipMemset(hd->params, 0, hd->n_params * sizeof(bf16_t));
+  if (err == hipSuccess) err = hipMemset(hd->grads, 0, hd->n_params * sizeof(bf16_t));
+  if (err == hipSuccess) err = launch_fill_bf16(h, hd->params, 1.0f, nullptr);   // LayerNorm gain 1
+  if (err == hipSuccess) err = hipDeviceSynchronize();
+  if (err != hipSuccess) {
+    if (hd->params) (void)hipFree(hd->params);
+    if (hd->grads) (void)hipFree(hd->grads);
+    if (hd->ws_base) (void)hipFree(hd->ws_base);
+    delete hd;
+    return fail(err == hipErrorOutOfMemory ? AXONN_ENOMEM : AXONN_EHIP, "head_create: %s", hipGetErrorString(err));
+  }
+  char* p = hd->ws_base;
+  hd->a = (bf16_t*)p; p += e_th; hd->da = (bf16_t*)p; p += e_th; hd->logits = (bf16_t*)p; p += e_tv;
+  hd->stats = (float*)p; p += e_st; hd->token_loss = (float*)p; p += e_tl; hd->red_ws = (float*)p; p += e_red;
+  *out = hd;
+  return AXONN_OK;
+}
+int axonn_head_destroy(axonn_head_t* hd) {
+  if (!hd) return fail(AXONN_EINVAL, "head_destroy: null handle");
+  (void)hipSetDevice(hd->device);
+  (void)hipDeviceSynchronize();
+  (void)hipFree(hd->params);
+  (void)hipFree(hd->grads);
+  (void)hipFree(hd->ws_base);
+  delete hd;
+  return AXONN_OK;
+}
+int axonn_head_buffers(axonn_head_t* hd, void** params_dev_bf16, void** grads_dev_bf16, uint64_t* n_elements) {
+  if (!hd) return fail(AXONN_EINVAL, "head_buffers: null handle");
+  if (params_dev_bf16) *params_dev_bf16 = hd->params;
+  if (grads_dev_bf16) *grads_dev_bf16 = hd->grads;
+  if (n_elements) *n_elements = hd->n_params;
+  return AXONN_OK;
+}
+int axonn_head_zero_grad(axonn_head_t* hd) {
+  if (!hd) return fail(AXONN_EINVAL, "head_zero_grad: null handle");
+  hd->count = 0;
+  return AXONN_OK;
+}
+int axonn_head_forward_backward(axonn_head_t* hd, const void* x_dev_bf16, const int32_t* targets_dev,
+                                float* loss_dev, void* dx_dev_bf16, void* hip_stream) {
+  if (!hd || !x_dev_bf16 || !targets_dev || !loss_dev || !dx_dev_bf16)
+    return fail(AXONN_EINVAL, "head_forward_backward: null argument");
+  HIP_TRY(hipSetDevice(hd->device));
+  return head_forward_backward(hd, x_dev_bf16, targets_dev, loss_dev, dx_dev_bf16, (hipStream_t)hip_stream);
+}
+
+int axonn_stage_attach_ends(axonn_stage_t* st, axonn_embed_t* embed, axonn_head_t* head) {
+  if (!st) return fail(AXONN_EINVAL, "attach_ends: null handle");
+  if (st->in_flight || !st->inbox.empty()) return fail(AXONN_ESTATE, "attach_ends: work in flight");
+  if (embed && (embed->h != st->h || embed->s != st->cfg.seq_len || embed->b != st->cfg.microbatch_size ||
+                embed->device != st->cfg.device))
+    return fail(AXONN_EINVAL, "attach_ends: the embedding's hidden size, sequence length, microbatch size or device "
+                "differ from the stage's");
+  if (head && (head->h != st->h || head->T != st->T || head->M != st->cfg.n_microbatches ||
+               head->device != st->cfg.device))
+    return fail(AXONN_EINVAL, "attach_ends: the head's hidden size, tokens per microbatch, microbatch count or "
+                "device differ from the stage's");
+  HIP_TRY(hipSetDevice(st->cfg.device));
+  HIP_TRY(hipDeviceSynchronize());
+  const uint64_t e_th = align_up((uint64_t)st->T * st->h * 2, 256);
+  if (embed && !st->embed_dx) HIP_TRY(hipMalloc((void**)&st->embed_dx, e_th));
+  if (head && !st->head_dx) {
+    HIP_TRY(hipMalloc((void**)&st->head_dx, e_th));
+    HIP_TRY(hipMalloc((void**)&st->head_y_base, e_th * st->slots.size()));
+    for (size_t i = 0; i < st->slots.size(); ++i) st->slots[i].head_y = (bf16_t*)((char*)st->head_y_base + i * e_th);
+  }
+  st->embed = embed;
+  st->head = head;
+  return AXONN_OK;
 }
 
 // ----------------------------------------------------------------- launch timing

@@ -109,6 +109,27 @@ def make_stage_inputs(shape: StageShape, seed=0, perturb=False, weight_std=0.02,
     return layers, xs, dys
 
 
+def make_lm_inputs(shape: StageShape, vocab, seed=0, table_std=0.02, head_std=0.02, perturb=True):
+    """Inputs of the pipeline's two ends: (tokens, targets, wte, wpe, lnf_g, lnf_b, w_head).
+
+    tokens, targets: lists (one per microbatch) of int [b, s] arrays, uniform over the vocabulary (stands in for
+    tokenised text; repeats occur whenever b*s is not small against the vocabulary); wte [V,h] and wpe [s,h]
+    ~ N(0, table_std); w_head [h,V] ~ N(0, head_std); final LayerNorm gain / shift 1 / 0, perturbed by
+    N(0, 0.02) if `perturb`.  float32 arrays hold bf16-representable values."""
+    rng = np.random.default_rng(seed)
+    h, s, b, M = shape.hidden, shape.seq_len, shape.microbatch_size, shape.n_microbatches
+    wte = _normal(rng, (vocab, h), table_std)
+    wpe = _normal(rng, (s, h), table_std)
+    w_head = _normal(rng, (h, vocab), head_std)
+    if perturb:
+        g, bt = _normal(rng, (h,), 0.02, 1.0), _normal(rng, (h,), 0.02, 0.0)
+    else:
+        g, bt = np.ones(h, np.float32), np.zeros(h, np.float32)
+    tokens = [rng.integers(0, vocab, (b, s)) for _ in range(M)]
+    targets = [rng.integers(0, vocab, (b, s)) for _ in range(M)]
+    return tokens, targets, wte, wpe, g, bt, w_head
+
+
 def make_adam_inputs(n, seed=0, theta_std=0.02, grad_std=1e-3, m_std=1e-4, v_std=1e-6,
                      fresh=False):
     """Optimizer-state inputs: (theta, m, v) float32, g16 float32 holding bf16 values.

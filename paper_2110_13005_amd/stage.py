@@ -19,6 +19,12 @@ def _view(ptr, n, dtype):
     return torch.as_tensor(_Holder(), device="cuda").view(dtype)
 
 
+def view_bf16(ptr, n):
+    """bf16 torch view of `n` elements of library-owned device memory at `ptr`."""
+    import torch
+    return _view(ptr, n, torch.bfloat16)
+
+
 class Stage:
     def __init__(self, shape, pipeline_limit=None, ln_eps=1e-5, device=0, grad_accum_fp32=1,
                  n_microbatches=None, wgrad_group=0, qkv_input_split=0, ckpt_stride=0):
@@ -79,8 +85,8 @@ class Stage:
     def backward(self, mb_id, dy, dx, stream=None):
         B.axonn_stage_backward(self.handle, mb_id, dy, dx, stream)
 
-    def post(self, kind, mb_id, payload, result, ready_event=None):
-        B.axonn_stage_post(self.handle, kind, mb_id, payload, result, ready_event)
+    def post(self, kind, mb_id, payload, result, ready_event=None, targets=None, loss=None):
+        B.axonn_stage_post(self.handle, kind, mb_id, payload, result, ready_event, targets, loss)
 
     def run(self, n_streams=2, stream=None):
         B.axonn_stage_run(self.handle, n_streams, stream)
