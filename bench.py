@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--wgrad-group", type=int, default=3, help="microbatches per weight-gradient contraction (0 = as many as possible)")
     ap.add_argument("--ckpt-stride", type=int, default=0,
                     help="activation checkpointing stride ac (0 = keep all activations, the default workload)")
+    ap.add_argument("--ends", action="store_true",
+                    help="second workload: the stage is both the first and the last one (token embedding in front, "
+                         "final LayerNorm + LM head + loss behind, vocabulary 51200); forward messages carry token ids")
     ap.add_argument("--bucket-elems", type=int, default=1 << 26)
     ap.add_argument("--overlap-chunk", type=int, default=1,
                     help="chunk size k (buckets) of the extra measurement with the optimizer step overlapped with "
@@ -135,6 +138,24 @@ def main():
     DY = [torch.randn(bsh, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(M)]
     Y = [torch.empty(bsh, device=dev, dtype=torch.bfloat16) for _ in range(M)]
     DX = [torch.empty(bsh, device=dev, dtype=torch.bfloat16) for _ in range(M)]
+    VOCAB = 51200
+    embed = head = None
+    if args.ends:
+        embed = B.axonn_embed_create(0, VOCAB, sh.hidden, sh.seq_len, sh.microbatch_size)
+        head = B.axonn_head_create(0, VOCAB, sh.hidden, sh.tokens, M, 1e-5)
+        from paper_2110_13005_amd.stage import view_bf16
+        for handle, fn in ((embed, B.axonn_embed_buffers), (head, B.axonn_head_buffers)):
+            pp, _, nn = fn(handle)
+            v = view_bf16(pp, nn)
+            lo = 2 * sh.hidden if handle is head else 0          # the final LayerNorm keeps gain 1, shift 0
+            for o in range(lo, nn, 1 << 26):
+                c = min(1 << 26, nn - o)
+                v[o:o + c] = (torch.randn(c, generator=g, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+            del v
+        B.axonn_stage_attach_ends(st.handle, embed, head)
+        TOK = [torch.randint(0, VOCAB, (sh.microbatch_size, sh.seq_len), generator=g, device=dev, dtype=torch.int32) for _ in range(M)]
+        TGT = [torch.randint(0, VOCAB, (sh.microbatch_size, sh.seq_len), generator=g, device=dev, dtype=torch.int32) for _ in range(M)]
+        LOSS = torch.zeros(M, device=dev)
     torch.cuda.synchronize()
 
     # message order of a middle stage: P forwards of warm-up, then one backward / one forward, then drain
@@ -149,6 +170,14 @@ def main():
     main_stream = torch.cuda.Stream()
     oc = OPT_CONFIG
 
+    def post_all():
+        if args.ends:      # every forward message is followed at once by the loss and Backward (Alg. 2, last stage)
+            for i in range(M):
+                st.post(0, i, TOK[i], None, targets=TGT[i], loss=LOSS[i:i + 1])
+        else:
+            for kind, i in order:
+                st.post(kind, i, X[i] if kind == 0 else DY[i], Y[i] if kind == 0 else DX[i])
+
     def one_step(step_no, ev, overlap_chunk=0):
         """ev[0]: start, ev[1]: forward+backward work complete, ev[2]: step complete.  overlap_chunk > 0: the
         optimizer step is queued right after the messages are dispatched and starts on the last layers'
@@ -157,8 +186,7 @@ def main():
         with torch.cuda.stream(main_stream):
             ev[0].record(main_stream)
             st.zero_grad(main_stream)
-            for kind, i in order:
-                st.post(kind, i, X[i] if kind == 0 else DY[i], Y[i] if kind == 0 else DX[i])
+            post_all()
             st.run(args.streams, main_stream)
             hyper = (oc["lr"], oc["beta1"], oc["beta2"], oc["eps"], oc["weight_decay"], oc["step"] + step_no, 1.0 / M)
             if overlap_chunk and not args.no_optimizer:
@@ -188,6 +216,9 @@ def main():
     fb_mean = float(np.mean(fb_ms))
     fl = flops.stage_batch_flops(sh, causal=True)
     fl_paper = flops.stage_batch_flops(sh, causal=False)
+    fl_head = 3 * 2 * sh.tokens * sh.hidden * VOCAB * M if args.ends else 0    # Eq. 3's V/16lh term
+    fl += fl_head
+    fl_paper += fl_head
     tflops = fl / (fb_mean * 1e-3) / 1e12
     tokens = M * sh.tokens
 
@@ -200,7 +231,8 @@ def main():
                                "pipeline_limit=%d" % (args.config, sh.n_layers, sh.hidden, sh.n_heads, sh.ffn,
                                                       sh.seq_len, sh.microbatch_size, M, P),
                    "streams": args.streams, "grad_accum": args.grad_accum, "wgrad_group": args.wgrad_group, "bucket_elems": args.bucket_elems,
-                   "ckpt_stride": args.ckpt_stride, "optimizer_in_step": not args.no_optimizer},
+                   "ckpt_stride": args.ckpt_stride, "ends": "embedding + LM head, V=%d" % VOCAB if args.ends else "none",
+                   "optimizer_in_step": not args.no_optimizer},
         "pct_of_bf16_mfma_peak": 100.0 * tflops / flops.PEAK_BF16_DENSE_TFLOPS,
         "peak_tflops_used": flops.PEAK_BF16_DENSE_TFLOPS,
         "tokens_per_s": tokens / (fb_mean * 1e-3),
@@ -237,8 +269,7 @@ def main():
         B.axonn_profile_enable(True)
         with torch.cuda.stream(main_stream):
             st.zero_grad(main_stream)
-            for kind, i in order:
-                st.post(kind, i, X[i] if kind == 0 else DY[i], Y[i] if kind == 0 else DX[i])
+            post_all()
             st.run(1, main_stream)
             st.join(main_stream)
         torch.cuda.synchronize()
@@ -256,13 +287,20 @@ def main():
                 if cat == "gemm_fwd" and args.ckpt_stride:   # regenerated forward GEMMs, one FC2 per segment left out
                     work += work - M * (sh.n_layers // args.ckpt_stride) * 2 * T * h * f_
                 kern[cat]["tflops"] = work / (kern[cat]["total_ms"] * 1e-3) / 1e12
+        if args.ends:
+            for cat in ("gemm_fwd", "gemm_dgrad", "gemm_wgrad"):     # each holds one of the head's three contractions
+                kern[cat]["tflops"] = (per_layer_mb * sh.n_layers * M + fl_head / 3) / (kern[cat]["total_ms"] * 1e-3) / 1e12
+            if "cross_entropy" in kern:   # logits read twice and written once, bf16; the loss reduction is negligible
+                kern["cross_entropy"]["GBps"] = 3 * 2.0 * T * VOCAB * M / (kern["cross_entropy"]["total_ms"] * 1e-3) / 1e9
+            if "embedding" in kern:
+                kern["embedding"]["note"] = "forward gather, table clear (first microbatch), table and position gradients"
         out["kernels"] = kern
         # roofline of the largest single kernel by time: the weight-gradient GEMM
         # (gemm_big_kernel<false,false,EPI_ACC_*,8>), one launch = one weight of one layer for a
         # group of microbatches; its four shapes average to per_layer_mb/4 FLOP per microbatch
         dom = "gemm_wgrad"
         if dom in kern:
-            per_launch = per_layer_mb * sh.n_layers * M / kern[dom]["launches"]
+            per_launch = (per_layer_mb * sh.n_layers * M + fl_head / 3) / kern[dom]["launches"]
             ach = per_launch / (kern[dom]["avg_ms"] * 1e-3) / 1e12
             out["roofline"] = {"bound": "mfma", "achieved": ach, "peak": flops.PEAK_BF16_DENSE_TFLOPS,
                                "unit": "TFLOP/s", "frac": ach / flops.PEAK_BF16_DENSE_TFLOPS,
@@ -279,6 +317,9 @@ def main():
     torch.cuda.synchronize()
     del cal, cal2
     st.close()
+    if embed:
+        B.axonn_embed_destroy(embed)
+        B.axonn_head_destroy(head)
     for p in host_ptrs:
         B.axonn_pinned_free(p)
     if not args.no_cpu_baseline:

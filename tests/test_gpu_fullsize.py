@@ -116,6 +116,52 @@ def test_full_size_stage_parity(name, ac):
     assert e_f <= 2e-2 and e_b <= 3e-2 and worst <= 3e-2
 
 
+def test_full_size_last_stage_head():
+    """The last stage's extras at the 12B shape and the paper's vocabulary (Sec. 6.1): T = 2048 tokens,
+    h = 5120, V = 51200, 8 microbatches in the pre-division.  The oracle computes the whole microbatch; the
+    5120 x 51200 head gradient is compared on sampled column blocks (first, last, seeded random) and in norm."""
+    import torch
+    from oracle import lm_ends as OE
+    T, h, V, M = 2048, 5120, 51200, 8
+    rng = np.random.default_rng(0)
+    _say("head: generating inputs")
+    from paper_2110_13005_amd.inputs import snap_bf16
+    from paper_2110_13005_amd.stage import view_bf16
+    x = snap_bf16(rng.standard_normal((1, T, h), dtype=np.float32))
+    W = snap_bf16(rng.standard_normal((h, V), dtype=np.float32) * np.float32(0.02))
+    g = snap_bf16((1 + 0.02 * rng.standard_normal(h)).astype(np.float32))
+    bt = snap_bf16((0.02 * rng.standard_normal(h)).astype(np.float32))
+    tg = rng.integers(0, V, (1, T))
+    hd = B.axonn_head_create(0, V, h, T, M, EPS)
+    try:
+        p, gr, n = B.axonn_head_buffers(hd)
+        params, grads = view_bf16(p, n), view_bf16(gr, n)
+        params[:h] = dev_bf16(g); params[h:2 * h] = dev_bf16(bt); params[2 * h:] = dev_bf16(W).reshape(-1)
+        loss = torch.zeros(1, device="cuda"); dx = torch.zeros(T, h, dtype=torch.bfloat16, device="cuda")
+        X = dev_bf16(x); TG = torch.from_numpy(tg.astype(np.int32)).cuda()
+        _say("head: GPU forward + loss + backward")
+        B.axonn_head_forward_backward(hd, X, TG, loss, dx)
+        torch.cuda.synchronize()
+        _say("head: oracle (fp64, host) ...")
+        t1 = time.time()
+        rl, c = OE.head_loss_forward(x, g, bt, W, tg, EPS, M)
+        rdx, rg = OE.head_loss_backward(c, g, W, tg, M)
+        _say("head: oracle took %.0f s" % (time.time() - t1))
+        e_l = abs(loss.item() - rl) / abs(rl)
+        e_dx = rel_fro(host(dx).reshape(rdx.shape), rdx)
+        gW = grads[2 * h:].view(h, V)
+        cols = [0, V - 512] + [int(c0) for c0 in rng.integers(0, V // 512 - 1, 6) * 512]
+        e_w = max(rel_fro(host(gW[:, c0:c0 + 512]), rg["w_head"][:, c0:c0 + 512]) for c0 in cols)
+        e_norm = abs(float(gW.float().norm()) - np.linalg.norm(rg["w_head"])) / np.linalg.norm(rg["w_head"])
+        e_g = max(rel_fro(host(grads[:h]), rg["lnf_g"]), rel_fro(host(grads[h:2 * h]), rg["lnf_b"]))
+        _say("head: loss %.5f (oracle %.5f, rel %.1e)  dx %.2e  dW blocks %.2e  |dW| %.1e  LN grads %.2e"
+             % (loss.item(), rl, e_l, e_dx, e_w, e_norm, e_g))
+        assert e_l <= 2e-3 and e_dx <= 3e-2 and e_w <= 3e-2 and e_norm <= 1e-2 and e_g <= 3e-2
+    finally:
+        params = grads = None
+        B.axonn_head_destroy(hd)
+
+
 def test_full_size_offloaded_adam():
     """Config 5: 1.6e9 parameters, 2^26-element buckets (24, last one ragged), mid-training
     state, lr 1e-4, betas (0.9, 0.95), eps 1e-8, step 100.  The oracle is evaluated on sampled
