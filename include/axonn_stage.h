@@ -53,7 +53,10 @@ typedef struct axonn_stage axonn_stage_t;
 typedef struct {
   int32_t n_layers;        /* transformer layers in this stage                         */
   int32_t hidden;          /* h; multiple of 8                                         */
-  int32_t n_heads;         /* a; head dim d = h / a must be 64 or 128                  */
+  int32_t n_heads;         /* a; head dim d = h / a: a multiple of 4, at most 192
+                              (64 and 128 have kernels of their own; other sizes, such
+                              as the 188 of the paper's Table 1, run on the next of 64 /
+                              128 / 192 with the columns beyond d masked)              */
   int32_t ffn_hidden;      /* MLP width (4h in every benchmark shape); multiple of 8   */
   int32_t seq_len;         /* s                                                        */
   int32_t microbatch_size; /* b (Sec. 3.3: user-defined microbatch size); b*s % 8 == 0 */
@@ -327,7 +330,8 @@ int axonn_layernorm_bwd(int64_t T, int64_t h, const void* dout_bf16, const void*
 int axonn_colsum(int64_t T, int64_t N, const void* y_bf16, int64_t ldy, float* out_f32,
                  float* workspace_f32, void* hip_stream);
 
-/* Causal self-attention over the packed qkv [b*s, 3h] (layout above), head dim 64 or 128.
+/* Causal self-attention over the packed qkv [b*s, 3h] (layout above); head dim a multiple
+ * of 4, at most 192; h = n_heads * head_dim a multiple of 8.
  * o [b*s, h] bf16;  lse [b, a, s] float32 = log sum_j<=i exp(q_i.k_j / sqrt(d)). */
 int axonn_attention_fwd(int32_t b, int32_t s, int32_t n_heads, int32_t head_dim,
                         const void* qkv_bf16, void* o_bf16, float* lse, void* hip_stream);

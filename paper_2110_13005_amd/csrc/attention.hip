@@ -20,19 +20,40 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// The kernels are compiled for head dimensions D = 64, 128 and 192.  EXACT: the head dimension is D.
+// Otherwise the real head dimension d (a multiple of 4, d <= D) is a run-time argument and the columns
+// d .. D-1 of every head read as zero and are never written: zero columns add nothing to q.k, and the
+// padded columns of V give output columns nobody stores.  Heads then start at multiples of 8 bytes only, so
+// the 8 elements at columns [col, col + 8) of a head row are fetched as two 8-byte halves.
+template <bool EXACT>
+__device__ __forceinline__ uint4 load_cols8(const bf16_t* p, int col, int d) {
+  if (EXACT) return *reinterpret_cast<const uint4*>(p);
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (col + 4 <= d) {
+    const uint2 lo = *reinterpret_cast<const uint2*>(p);
+    v.x = lo.x; v.y = lo.y;
+  }
+  if (col + 8 <= d) {
+    const uint2 hi = *reinterpret_cast<const uint2*>(p + 4);
+    v.z = hi.x; v.w = hi.y;
+  }
+  return v;
+}
+
 // Cooperative copy of a ROWS x D bf16 tile (rows row0.., zero beyond n_rows) by 256 threads:
 // global -> registers, then registers -> LDS with leading dimension LD.
 template <int ROWS, int D>
 struct TileRegs {
   static constexpr int NCH = ROWS * D / 8 / 256;
   uint4 r[NCH];
-  __device__ __forceinline__ void load(const bf16_t* base, int64_t ld, int row0, int n_rows, int tid) {
+  template <bool EXACT>
+  __device__ __forceinline__ void load(const bf16_t* base, int64_t ld, int row0, int n_rows, int d, int tid) {
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
       const int c = tid + j * 256;
       const int row = c / (D / 8), ch = c % (D / 8);
       r[j] = (row0 + row < n_rows)
-                 ? *reinterpret_cast<const uint4*>(base + (int64_t)(row0 + row) * ld + ch * 8)
+                 ? load_cols8<EXACT>(base + (int64_t)(row0 + row) * ld + ch * 8, ch * 8, d)
                  : make_uint4(0, 0, 0, 0);
     }
   }
@@ -55,13 +76,13 @@ __device__ __forceinline__ bf16x8 pack8(const floatx16& t, int first) {
 
 // Row fragment straight from global memory: lane holds row (row0 + lane%32), elements
 // [k0 + 8*(lane/32), +8) -- the MFMA operand layout.  Rows >= n_rows read as zero.
+template <bool EXACT>
 __device__ __forceinline__ bf16x8 global_frag(const bf16_t* base, int64_t ld, int row, int n_rows,
-                                              int k0, int lane) {
-  bf16x8 z;
-#pragma unroll
-  for (int e = 0; e < 8; ++e) z[e] = (bf16_t)0.f;
-  if (row >= n_rows) return z;
-  return *reinterpret_cast<const bf16x8*>(base + (int64_t)row * ld + k0 + 8 * (lane >> 5));
+                                              int k0, int lane, int d) {
+  uint4 v = make_uint4(0, 0, 0, 0);
+  const int col = k0 + 8 * (lane >> 5);
+  if (row < n_rows) v = load_cols8<EXACT>(base + (int64_t)row * ld + col, col, d);
+  return __builtin_bit_cast(bf16x8, v);
 }
 
 // Work assignment of the attention kernels: block id of a 1-D grid of n_tiles * n_bh blocks -> (rank of
@@ -83,8 +104,9 @@ __device__ __forceinline__ void attn_block(int n_bh, int& rank, int& bh) {
 
 // =============================================================================== forward
 // grid: (ceil(s/128), b*a); 4 waves; wave w owns queries q0 + 32w .. +31.
-template <int D>
-__global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int s, int a, int n_bh, const bf16_t* __restrict__ qkv,
+template <int D, bool EXACT>
+__global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, int a, int n_bh, int d_arg,
+                                                       const bf16_t* __restrict__ qkv,
                                                        bf16_t* __restrict__ o,
                                                        float* __restrict__ lse) {
   constexpr int BKV = 64, LDK = D + 8, LDV = D + 32, DT = D / 32, KK = D / 16;
@@ -95,17 +117,18 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int s, int a, int n_bh
   attn_block(n_bh, rank, bh);
   const int qt = (s + 127) / 128 - 1 - rank;  // longest rows first
   const int bi = bh / a, hd = bh % a;
-  const int h = a * D;
+  const int d = EXACT ? D : d_arg;
+  const int h = a * d;
   const int64_t ld = 3 * (int64_t)h;
-  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * D;
+  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * d;
   const bf16_t* kb = qb + h;
   const bf16_t* vb = qb + 2 * h;
   const int q0 = qt * 128, qw0 = q0 + 32 * wave, qi = qw0 + (lane & 31);
-  const float scale_log2 = kLog2e * rsqrtf((float)D);
+  const float scale_log2 = kLog2e * rsqrtf((float)d);
 
   bf16x8 qf[KK];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) qf[kk] = global_frag(qb, ld, qi, s, kk * 16, lane);
+  for (int kk = 0; kk < KK; ++kk) qf[kk] = global_frag<EXACT>(qb, ld, qi, s, kk * 16, lane, d);
 
   floatx16 oacc[DT];
 #pragma unroll
@@ -117,8 +140,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int s, int a, int n_bh
   const int kv_end = min(s, q0 + 128);
   const int n_kt = (kv_end + BKV - 1) / BKV;
   TileRegs<BKV, D> rk, rv;
-  rk.load(kb, ld, 0, s, tid);
-  rv.load(vb, ld, 0, s, tid);
+  rk.template load<EXACT>(kb, ld, 0, s, d, tid);
+  rv.template load<EXACT>(vb, ld, 0, s, d, tid);
   for (int kt = 0; kt < n_kt; ++kt) {
     const int k0 = kt * BKV;
     __syncthreads();
@@ -126,8 +149,8 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int s, int a, int n_bh
     rv.template store<LDV>(sV, tid);
     __syncthreads();
     if (kt + 1 < n_kt) {
-      rk.load(kb, ld, k0 + BKV, s, tid);
-      rv.load(vb, ld, k0 + BKV, s, tid);
+      rk.template load<EXACT>(kb, ld, k0 + BKV, s, d, tid);
+      rv.template load<EXACT>(vb, ld, k0 + BKV, s, d, tid);
     }
     if (k0 > qw0 + 31) continue;  // every key of the tile is in this wave's future
 
@@ -186,7 +209,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int s, int a, int n_bh
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (qi < s) {
     const float inv = 1.f / l_tot;
-    bf16_t* orow = o + ((int64_t)bi * s + qi) * h + hd * D;
+    bf16_t* orow = o + ((int64_t)bi * s + qi) * h + hd * d;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -194,7 +217,7 @@ __global__ __launch_bounds__(256, 2) void attn_fwd_kernel(int s, int a, int n_bh
         bf16x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(oacc[dt][4 * q + e] * inv);
-        *reinterpret_cast<bf16x4*>(orow + dt * 32 + 8 * q + 4 * g) = v;
+        if (EXACT || dt * 32 + 8 * q + 4 * g < d) *reinterpret_cast<bf16x4*>(orow + dt * 32 + 8 * q + 4 * g) = v;
       }
     if (g == 0) lse[((int64_t)bi * a + hd) * s + qi] = (m_run + __log2f(l_tot)) * kLn2;
   }
@@ -227,11 +250,40 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(int64_t n_chunks, int s
   }
 }
 
+// The same for any head dimension d that is a multiple of 4: 16 lanes per (row, head), 4 elements per lane
+// and step.
+__global__ __launch_bounds__(256) void attn_delta_general_kernel(int64_t n_pairs, int s, int a, int d,
+                                                                 const bf16_t* __restrict__ o,
+                                                                 const bf16_t* __restrict__ dout,
+                                                                 float* __restrict__ delta) {
+  const int64_t pair = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);   // (row, head)
+  const int j = threadIdx.x & 15;
+  float p = 0.f;
+  if (pair < n_pairs) {
+    const bf16_t* op = o + pair * d;          // rows are a * d long: pair * d = row * a * d + head * d
+    const bf16_t* dp = dout + pair * d;
+    for (int c = 4 * j; c < d; c += 64) {
+      const bf16x4 ov = *reinterpret_cast<const bf16x4*>(op + c);
+      const bf16x4 dv = *reinterpret_cast<const bf16x4*>(dp + c);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) p += (float)ov[e] * (float)dv[e];
+    }
+  }
+#pragma unroll
+  for (int off = 8; off > 0; off >>= 1) p += __shfl_xor(p, off, 64);
+  if (pair < n_pairs && j == 0) {
+    const int64_t row = pair / a;
+    const int hd = (int)(pair % a);
+    const int64_t bi = row / s, i = row % s;
+    delta[(bi * a + hd) * s + i] = p;
+  }
+}
+
 // dK / dV: grid (ceil(s/128), b*a); wave w owns keys k0 + 32w .. +31 and walks the query tiles
 // at or below the diagonal.
-template <int D>
+template <int D, bool EXACT>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
-    int s, int a, int n_bh, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+    int s, int a, int n_bh, int d_arg, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
     const float* __restrict__ lse, const float* __restrict__ delta, bf16_t* __restrict__ dqkv) {
   constexpr int BQ = 64, LDQ = D + 8, DT = D / 32, KK = D / 16;
   __shared__ __align__(16) bf16_t sQ[BQ * LDQ];
@@ -242,22 +294,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
   int rank, bh;
   attn_block(n_bh, rank, bh);                  // key tile `rank` walks n_tiles - rank query tiles: longest first
   const int bi = bh / a, hd = bh % a;
-  const int h = a * D;
+  const int d = EXACT ? D : d_arg;
+  const int h = a * d;
   const int64_t ld = 3 * (int64_t)h;
-  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * D;
+  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * d;
   const bf16_t* kb = qb + h;
   const bf16_t* vb = qb + 2 * h;
-  const bf16_t* dob = dout + (int64_t)bi * s * h + hd * D;
+  const bf16_t* dob = dout + (int64_t)bi * s * h + hd * d;
   const float* lse_b = lse + ((int64_t)bi * a + hd) * s;
   const float* delta_b = delta + ((int64_t)bi * a + hd) * s;
   const int k0 = rank * 128, kw0 = k0 + 32 * wave, kj = kw0 + (lane & 31);
-  const float scale = rsqrtf((float)D), scale_log2 = kLog2e * scale;
+  const float scale = rsqrtf((float)d), scale_log2 = kLog2e * scale;
 
   bf16x8 kf[KK], vf[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
-    kf[kk] = global_frag(kb, ld, kj, s, kk * 16, lane);
-    vf[kk] = global_frag(vb, ld, kj, s, kk * 16, lane);
+    kf[kk] = global_frag<EXACT>(kb, ld, kj, s, kk * 16, lane, d);
+    vf[kk] = global_frag<EXACT>(vb, ld, kj, s, kk * 16, lane, d);
   }
   floatx16 dvacc[DT], dkacc[DT];
 #pragma unroll
@@ -269,8 +322,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
   TileRegs<BQ, D> rq, rdo;
   float r_lse = 0.f, r_delta = 0.f;
   auto prefetch = [&](int qt) {
-    rq.load(qb, ld, qt * BQ, s, tid);
-    rdo.load(dob, h, qt * BQ, s, tid);
+    rq.template load<EXACT>(qb, ld, qt * BQ, s, d, tid);
+    rdo.template load<EXACT>(dob, h, qt * BQ, s, d, tid);
     if (tid < BQ) {
       const int qrow = qt * BQ + tid;
       r_lse = qrow < s ? lse_b[qrow] : 0.f;
@@ -331,7 +384,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
     }
   }
   if (kj < s) {
-    bf16_t* dk_row = dqkv + ((int64_t)bi * s + kj) * ld + h + hd * D;
+    bf16_t* dk_row = dqkv + ((int64_t)bi * s + kj) * ld + h + hd * d;
     bf16_t* dv_row = dk_row + h;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -343,17 +396,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
           kv4[e] = (bf16_t)(dkacc[dt][4 * q + e] * scale);
           vv4[e] = (bf16_t)dvacc[dt][4 * q + e];
         }
-        *reinterpret_cast<bf16x4*>(dk_row + dt * 32 + 8 * q + 4 * g) = kv4;
-        *reinterpret_cast<bf16x4*>(dv_row + dt * 32 + 8 * q + 4 * g) = vv4;
+        if (EXACT || dt * 32 + 8 * q + 4 * g < d) {
+          *reinterpret_cast<bf16x4*>(dk_row + dt * 32 + 8 * q + 4 * g) = kv4;
+          *reinterpret_cast<bf16x4*>(dv_row + dt * 32 + 8 * q + 4 * g) = vv4;
+        }
       }
   }
 }
 
 // dQ: grid (ceil(s/128), b*a); wave w owns queries q0 + 32w .. +31 and walks the key tiles up
 // to the diagonal (same traversal as the forward kernel).
-template <int D>
-__global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
-    int s, int a, int n_bh, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
+template <int D, bool EXACT>
+__global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
+    int s, int a, int n_bh, int d_arg, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
     const float* __restrict__ lse, const float* __restrict__ delta, bf16_t* __restrict__ dqkv) {
   constexpr int BKV = 64, LDK = D + 8, DT = D / 32, KK = D / 16;
   __shared__ __align__(16) bf16_t sK[BKV * LDK];
@@ -363,22 +418,23 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   attn_block(n_bh, rank, bh);
   const int qt = (s + 127) / 128 - 1 - rank;
   const int bi = bh / a, hd = bh % a;
-  const int h = a * D;
+  const int d = EXACT ? D : d_arg;
+  const int h = a * d;
   const int64_t ld = 3 * (int64_t)h;
-  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * D;
+  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * d;
   const bf16_t* kb = qb + h;
   const bf16_t* vb = qb + 2 * h;
-  const bf16_t* dob = dout + (int64_t)bi * s * h + hd * D;
+  const bf16_t* dob = dout + (int64_t)bi * s * h + hd * d;
   const int q0 = qt * 128, qw0 = q0 + 32 * wave, qi = qw0 + (lane & 31);
-  const float scale = rsqrtf((float)D), scale_log2 = kLog2e * scale;
+  const float scale = rsqrtf((float)d), scale_log2 = kLog2e * scale;
   const float lse_q = (qi < s) ? lse[((int64_t)bi * a + hd) * s + qi] * kLog2e : 0.f;
   const float delta_q = (qi < s) ? delta[((int64_t)bi * a + hd) * s + qi] : 0.f;
 
   bf16x8 qf[KK], dof[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
-    qf[kk] = global_frag(qb, ld, qi, s, kk * 16, lane);
-    dof[kk] = global_frag(dob, h, qi, s, kk * 16, lane);
+    qf[kk] = global_frag<EXACT>(qb, ld, qi, s, kk * 16, lane, d);
+    dof[kk] = global_frag<EXACT>(dob, h, qi, s, kk * 16, lane, d);
   }
   floatx16 dqacc[DT];
 #pragma unroll
@@ -389,8 +445,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
   const int kv_end = min(s, q0 + 128);
   const int n_kt = (kv_end + BKV - 1) / BKV;
   TileRegs<BKV, D> rk, rv;
-  rk.load(kb, ld, 0, s, tid);
-  rv.load(vb, ld, 0, s, tid);
+  rk.template load<EXACT>(kb, ld, 0, s, d, tid);
+  rv.template load<EXACT>(vb, ld, 0, s, d, tid);
   for (int kt = 0; kt < n_kt; ++kt) {
     const int k0 = kt * BKV;
     __syncthreads();
@@ -398,8 +454,8 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     rv.template store<LDK>(sV, tid);
     __syncthreads();
     if (kt + 1 < n_kt) {
-      rk.load(kb, ld, k0 + BKV, s, tid);
-      rv.load(vb, ld, k0 + BKV, s, tid);
+      rk.template load<EXACT>(kb, ld, k0 + BKV, s, d, tid);
+      rv.template load<EXACT>(vb, ld, k0 + BKV, s, d, tid);
     }
     if (k0 > qw0 + 31) continue;
 #pragma unroll
@@ -431,7 +487,7 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
     }
   }
   if (qi < s) {
-    bf16_t* dq_row = dqkv + ((int64_t)bi * s + qi) * ld + hd * D;
+    bf16_t* dq_row = dqkv + ((int64_t)bi * s + qi) * ld + hd * d;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -439,42 +495,58 @@ __global__ __launch_bounds__(256, 2) void attn_bwd_dq_kernel(
         bf16x4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(dqacc[dt][4 * q + e] * scale);
-        *reinterpret_cast<bf16x4*>(dq_row + dt * 32 + 8 * q + 4 * g) = v;
+        if (EXACT || dt * 32 + 8 * q + 4 * g < d) *reinterpret_cast<bf16x4*>(dq_row + dt * 32 + 8 * q + 4 * g) = v;
       }
   }
 }
 
 // ------------------------------------------------------------------------- launchers
+// d = 64 or 128: the kernels compiled for exactly that head dimension.  Any other multiple of 4 up to 192:
+// the next compiled size with the columns beyond d masked.
+#define AXONN_ATTN_DISPATCH(KERNEL, ...)                                                              \
+  do {                                                                                                \
+    if (d == 64) hipLaunchKernelGGL((KERNEL<64, true>), grid, dim3(256), 0, st, __VA_ARGS__);         \
+    else if (d == 128) hipLaunchKernelGGL((KERNEL<128, true>), grid, dim3(256), 0, st, __VA_ARGS__);  \
+    else if (d < 64) hipLaunchKernelGGL((KERNEL<64, false>), grid, dim3(256), 0, st, __VA_ARGS__);    \
+    else if (d < 128) hipLaunchKernelGGL((KERNEL<128, false>), grid, dim3(256), 0, st, __VA_ARGS__);  \
+    else hipLaunchKernelGGL((KERNEL<192, false>), grid, dim3(256), 0, st, __VA_ARGS__);               \
+  } while (0)
+
+static bool head_dim_supported(int d) { return d >= 4 && d <= 192 && d % 4 == 0; }
+
 hipError_t launch_attention_fwd(int b, int s, int a, int d, const void* qkv, void* o, float* lse,
                                 hipStream_t st) {
+  if (!head_dim_supported(d)) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(((s + 127) / 128) * b * a));
-  if (d == 128)
-    hipLaunchKernelGGL(attn_fwd_kernel<128>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (bf16_t*)o, lse);
-  else if (d == 64)
-    hipLaunchKernelGGL(attn_fwd_kernel<64>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (bf16_t*)o, lse);
-  else
-    return hipErrorInvalidValue;
+  AXONN_ATTN_DISPATCH(attn_fwd_kernel, s, a, b * a, d, (const bf16_t*)qkv, (bf16_t*)o, lse);
   return hipGetLastError();
 }
 
 hipError_t launch_attention_bwd(int b, int s, int a, int d, const void* qkv, const void* o,
                                 const float* lse, const void* dout, void* dqkv, float* delta,
                                 hipStream_t st) {
-  const int64_t n_chunks = (int64_t)b * s * a * d / 8;
-  const dim3 gd((unsigned)((n_chunks + 255) / 256));
-  const dim3 grid((unsigned)(((s + 127) / 128) * b * a));
-  if (d == 128) {
-    hipLaunchKernelGGL(attn_delta_kernel<128>, gd, dim3(256), 0, st, n_chunks, s, a, (const bf16_t*)o, (const bf16_t*)dout, delta);
-    hipLaunchKernelGGL(attn_bwd_dkdv_kernel<128>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<128>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
-  } else if (d == 64) {
-    hipLaunchKernelGGL(attn_delta_kernel<64>, gd, dim3(256), 0, st, n_chunks, s, a, (const bf16_t*)o, (const bf16_t*)dout, delta);
-    hipLaunchKernelGGL(attn_bwd_dkdv_kernel<64>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
-    hipLaunchKernelGGL(attn_bwd_dq_kernel<64>, grid, dim3(256), 0, st, s, a, b * a, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+  if (!head_dim_supported(d)) return hipErrorInvalidValue;
+  if (d == 64 || d == 128) {
+    const int64_t n_chunks = (int64_t)b * s * a * d / 8;
+    const dim3 gd((unsigned)((n_chunks + 255) / 256));
+    if (d == 128)
+      hipLaunchKernelGGL(attn_delta_kernel<128>, gd, dim3(256), 0, st, n_chunks, s, a, (const bf16_t*)o, (const bf16_t*)dout, delta);
+    else
+      hipLaunchKernelGGL(attn_delta_kernel<64>, gd, dim3(256), 0, st, n_chunks, s, a, (const bf16_t*)o, (const bf16_t*)dout, delta);
   } else {
-    return hipErrorInvalidValue;
+    const int64_t n_pairs = (int64_t)b * s * a;
+    hipLaunchKernelGGL(attn_delta_general_kernel, dim3((unsigned)((n_pairs + 15) / 16)), dim3(256), 0, st, n_pairs, s, a, d,
+                       (const bf16_t*)o, (const bf16_t*)dout, delta);
   }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  const dim3 grid((unsigned)(((s + 127) / 128) * b * a));
+  AXONN_ATTN_DISPATCH(attn_bwd_dkdv_kernel, s, a, b * a, d, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  AXONN_ATTN_DISPATCH(attn_bwd_dq_kernel, s, a, b * a, d, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
   return hipGetLastError();
 }
+#undef AXONN_ATTN_DISPATCH
 
 }  // namespace axonn

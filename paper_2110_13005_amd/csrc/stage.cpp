@@ -715,8 +715,8 @@ int validate_config(const axonn_stage_config* c) {
     return fail(AXONN_EINVAL, "stage config: ckpt_stride (%d) must be 0 or a factor of n_layers (%d)",
                 c->ckpt_stride, c->n_layers);
   const int d = c->hidden / c->n_heads;
-  if (d != 64 && d != 128)
-    return fail(AXONN_EUNSUPPORTED, "head dim %d unsupported: attention kernels exist for 64 and 128", d);
+  if (d % 4 || d > 192)
+    return fail(AXONN_EUNSUPPORTED, "head dim %d unsupported: it must be a multiple of 4, at most 192", d);
   if (c->hidden % 8 || c->ffn_hidden % 8)
     return fail(AXONN_EUNSUPPORTED, "hidden and ffn_hidden must be multiples of 8 (16-byte rows)");
   if (((int64_t)c->seq_len * c->microbatch_size) % 8)
@@ -1582,7 +1582,9 @@ int axonn_attention_fwd(int32_t b, int32_t s, int32_t n_heads, int32_t head_dim,
                         float* lse, void* hip_stream) {
   if (!qkv || !o || !lse) return fail(AXONN_EINVAL, "attention_fwd: null argument");
   if (b < 1 || s < 1 || n_heads < 1) return fail(AXONN_EINVAL, "attention_fwd: non-positive size");
-  if (head_dim != 64 && head_dim != 128) return fail(AXONN_EUNSUPPORTED, "attention_fwd: head dim must be 64 or 128");
+  if (head_dim < 4 || head_dim % 4 || head_dim > 192 || ((int64_t)n_heads * head_dim) % 8)
+    return fail(AXONN_EUNSUPPORTED, "attention_fwd: head dim must be a multiple of 4, at most 192, and n_heads * "
+                "head_dim a multiple of 8");
   if ((int64_t)b * n_heads > 65535) return fail(AXONN_EUNSUPPORTED, "attention_fwd: b*n_heads > 65535");
   return check_launch(launch_attention_fwd(b, s, n_heads, head_dim, qkv, o, lse, (hipStream_t)hip_stream), "attention_fwd");
 }
@@ -1591,7 +1593,9 @@ int axonn_attention_bwd(int32_t b, int32_t s, int32_t n_heads, int32_t head_dim,
                         const float* lse, const void* dout, void* dqkv, float* delta_ws, void* hip_stream) {
   if (!qkv || !o || !lse || !dout || !dqkv || !delta_ws) return fail(AXONN_EINVAL, "attention_bwd: null argument");
   if (b < 1 || s < 1 || n_heads < 1) return fail(AXONN_EINVAL, "attention_bwd: non-positive size");
-  if (head_dim != 64 && head_dim != 128) return fail(AXONN_EUNSUPPORTED, "attention_bwd: head dim must be 64 or 128");
+  if (head_dim < 4 || head_dim % 4 || head_dim > 192 || ((int64_t)n_heads * head_dim) % 8)
+    return fail(AXONN_EUNSUPPORTED, "attention_bwd: head dim must be a multiple of 4, at most 192, and n_heads * "
+                "head_dim a multiple of 8");
   if ((int64_t)b * n_heads > 65535) return fail(AXONN_EUNSUPPORTED, "attention_bwd: b*n_heads > 65535");
   return check_launch(launch_attention_bwd(b, s, n_heads, head_dim, qkv, o, lse, dout, dqkv, delta_ws,
                                            (hipStream_t)hip_stream), "attention_bwd");

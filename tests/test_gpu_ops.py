@@ -195,6 +195,17 @@ ATTN_SHAPES = [
     (2, 72, 2, 64),     # shorter than one tile
     (1, 8, 1, 64),      # minimum
     (1, 520, 2, 128),   # several tiles + ragged tail
+    # head dimensions without a kernel of their own: multiples of 4 up to 192, run with masked columns
+    (1, 200, 2, 188),   # the paper's Table 1 head dimension (h = 4512, 24 heads), on the 192 kernel
+    (1, 264, 2, 176),   # Table 1: 6336 / 36
+    (1, 300, 4, 136),   # Table 1: 6528 / 48
+    (1, 520, 2, 156),   # Table 1: 9360 / 60
+    (2, 136, 2, 44),    # on the 64 kernel, half of a 16-byte chunk at the end of every head
+    (1, 300, 4, 100),   # on the 128 kernel
+    (1, 96, 2, 32),     # less than the smallest kernel
+    (1, 130, 6, 36),
+    (1, 64, 2, 4),      # minimum: one 8-byte half chunk per head
+    (1, 100, 2, 192),   # exactly the largest compiled size
 ]
 
 

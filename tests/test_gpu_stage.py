@@ -90,7 +90,9 @@ def test_split_input_qkv_projection_parity_and_effect():
     StageShape(1, 128, 2, 72, 1, 2),          # one layer, ragged sequence, head dim 64
     StageShape(3, 384, 3, 200, 2, 3, 1000),   # head dim 128, ragged T = 400, ffn not 4h
     StageShape(1, 64, 1, 8, 1, 1),            # smallest supported shape
-], ids=["ragged72", "ragged200_ffn1000", "minimal"])
+    StageShape(2, 376, 2, 136, 2, 2),         # head dim 188 as in the paper's Table 1 (4512 / 24)
+    StageShape(2, 264, 6, 80, 1, 2),          # head dim 44
+], ids=["ragged72", "ragged200_ffn1000", "minimal", "headdim188", "headdim44"])
 def test_ragged_and_degenerate_shapes(sh):
     layers, xs, dys = make_stage_inputs(sh, seed=3, perturb=True)
     ref = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)

@@ -33,7 +33,7 @@ def test_argument_validation_without_device():
     out = ctypes.c_void_p()
     cfg = B.axonn_stage_config(2, 256, 3, 1024, 128, 2, 4, 4, 1e-5, 0, 1, 0, 0)   # 256 % 3 != 0
     assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EINVAL
-    cfg = B.axonn_stage_config(2, 256, 8, 1024, 128, 2, 4, 4, 1e-5, 0, 1, 0, 0)   # head dim 32
+    cfg = B.axonn_stage_config(2, 2048, 8, 8192, 128, 2, 4, 4, 1e-5, 0, 1, 0, 0)  # head dim 256
     assert lib.axonn_stage_create(ctypes.byref(cfg), ctypes.byref(out)) == B.AXONN_EUNSUPPORTED
     assert b"head dim" in lib.axonn_last_error()
     cfg = B.axonn_stage_config(2, 256, 4, 1024, 128, 2, 4, 5, 1e-5, 0, 1, 0, 0)   # pipeline_limit > M
@@ -53,5 +53,5 @@ def test_argument_validation_without_device():
         B.axonn_adam_bucket(8, 1, 1, 1, 1, 1, 1e-3, 0.9, 0.95, 1e-8, 0.0, 0, 1.0)  # step 0
     assert e.value.status == B.AXONN_EINVAL
     with pytest.raises(B.AxonnError) as e:
-        B.axonn_attention_fwd(1, 128, 4, 32, 1, 1, 1)
+        B.axonn_attention_fwd(1, 128, 4, 200, 1, 1, 1)
     assert e.value.status == B.AXONN_EUNSUPPORTED
