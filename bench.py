@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", default="12b", choices=["tiny", "12b", "24b", "100b"])
+    ap.add_argument("--config", default="12b", choices=["tiny", "12b", "24b", "100b", "table1_12b"])
     ap.add_argument("--streams", type=int, default=2, help="library streams of the message-driven run")
     ap.add_argument("--pipeline-limit", type=int, default=0, help="0 = all microbatches in flight")
     ap.add_argument("--grad-accum", default="bf16", choices=["fp32", "bf16"])
@@ -93,7 +93,8 @@ def main():
     B.load()
     sh = CONFIGS[args.config]
     M = sh.n_microbatches
-    P = args.pipeline_limit or M
+    from paper_2110_13005_amd.inputs import PIPELINE_LIMITS
+    P = args.pipeline_limit or PIPELINE_LIMITS.get(args.config, M)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(0)
     g = torch.Generator(device=dev)

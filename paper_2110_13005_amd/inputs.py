@@ -50,7 +50,12 @@ CONFIGS = {
     "12b": StageShape(4, 5120, 40, 2048, 1, 8),
     "24b": StageShape(4, 6144, 48, 2048, 2, 16),
     "100b": StageShape(2, 10240, 80, 2048, 1, 16),
+    # the paper's own 12B model (Table 1: 48 layers, hidden 4512, 24 heads => head dim 188) as one of its
+    # G_inter = 6 stages sees it (Table 2): 8 layers, sequence 512, microbatch 8 (Sec. 6.1); 16 microbatches
+    # stand in for the 256 of a batch, 6 of them in flight
+    "table1_12b": StageShape(8, 4512, 24, 512, 8, 16),
 }
+PIPELINE_LIMITS = {"table1_12b": 6}   # configs whose pipeline_limit is not "all microbatches in flight"
 OPT_CONFIG = dict(n=1_600_000_000, bucket_elems=1 << 26, lr=1e-4, beta1=0.9, beta2=0.95,
                   eps=1e-8, weight_decay=0.0, step=100, grad_scale=1.0)
 

@@ -44,12 +44,16 @@ def _message_run(st, X, DY, Y, DX, n_streams=2):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("name,ac", [("12b", 0), ("24b", 0), ("100b", 0), ("12b", 2)])
+@pytest.mark.parametrize("name,ac", [("12b", 0), ("24b", 0), ("100b", 0), ("12b", 2), ("table1_12b", 0)])
 def test_full_size_stage_parity(name, ac):
     """ac > 0: the same with activation checkpointing of that stride (Sec. 5.1), against the oracle's
     regenerating pass."""
     import torch
     sh = CONFIGS[name]
+    if name == "table1_12b":
+        # the paper's own shape (head dim 188, sequence 512, microbatch 8): 4 of the stage's 8 layers and 6 of the
+        # microbatches keep the oracle's share of the test near half a minute
+        sh = StageShape(4, sh.hidden, sh.n_heads, sh.seq_len, sh.microbatch_size, 6)
     M = sh.n_microbatches
     t0 = time.time()
     _say("%s: generating inputs (seed 0)" % name)
