@@ -273,6 +273,9 @@ def main():
             post_all()
             st.run(1, main_stream)
             st.join(main_stream)
+            if not args.no_optimizer:    # one more optimizer step, for the Adam kernel's own time
+                B.axonn_stage_optimizer_step(st.handle, oc["lr"], oc["beta1"], oc["beta2"], oc["eps"], oc["weight_decay"],
+                                             oc["step"] + 10000, 1.0 / M, main_stream)
         torch.cuda.synchronize()
         prof = B.axonn_profile_collect()
         B.axonn_profile_enable(False)
@@ -295,6 +298,14 @@ def main():
                 kern["cross_entropy"]["GBps"] = 3 * 2.0 * T * VOCAB * M / (kern["cross_entropy"]["total_ms"] * 1e-3) / 1e9
             if "embedding" in kern:
                 kern["embedding"]["note"] = "forward gather, table clear (first microbatch), table and position gradients"
+        # HBM-bound kernels: algorithmic bytes per launch / average launch time
+        if "layernorm_fwd" in kern:      # read x, write the normalised row (bf16 each) + 8 B of statistics per row
+            kern["layernorm_fwd"]["GBps"] = (4.0 * T * h + 8.0 * T) / (kern["layernorm_fwd"]["avg_ms"] * 1e-3) / 1e9
+        if "adam" in kern:               # theta, m, v read and written (fp32), gradient read and parameter written (bf16)
+            kern["adam"]["GBps"] = 28.0 * n / (kern["adam"]["total_ms"] * 1e-3) / 1e9
+        for cat in ("layernorm_fwd", "adam", "cross_entropy"):
+            if cat in kern and "GBps" in kern[cat]:
+                kern[cat]["frac_of_hbm_peak"] = kern[cat]["GBps"] / flops.PEAK_HBM_GBPS
         out["kernels"] = kern
         # roofline of the largest single kernel by time: the weight-gradient GEMM
         # (gemm_big_kernel<false,false,EPI_ACC_*,8>), one launch = one weight of one layer for a
