@@ -217,7 +217,7 @@ def main():
     fb_mean = float(np.mean(fb_ms))
     fl = flops.stage_batch_flops(sh, causal=True)
     fl_paper = flops.stage_batch_flops(sh, causal=False)
-    fl_head = 3 * 2 * sh.tokens * sh.hidden * VOCAB * M if args.ends else 0    # Eq. 3's V/16lh term
+    fl_head = flops.lm_head_flops(sh, VOCAB) if args.ends else 0    # cf. Eq. 3's V/16lh term
     fl += fl_head
     fl_paper += fl_head
     tflops = fl / (fb_mean * 1e-3) / 1e12

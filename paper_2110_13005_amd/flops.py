@@ -38,6 +38,13 @@ def regeneration_flops(shape, ckpt_stride, causal=True, n_microbatches=None):
     return M * (shape.n_layers * per_layer - (shape.n_layers // ckpt_stride) * skipped)
 
 
+def lm_head_flops(shape, vocab, n_microbatches=None):
+    """fwd + bwd FLOPs of the last stage's LM head over a batch: three contractions of 2*T*h*V each per
+    microbatch (logits, their input gradient, the head's weight gradient): Eq. 3's V/16lh term, 6*b*s*h*V."""
+    M = shape.n_microbatches if n_microbatches is None else n_microbatches
+    return 3 * 2 * shape.tokens * shape.hidden * vocab * M
+
+
 def narayanan_flops(b, s, l, h, V=0, recompute=True):
     """The paper's Eq. 3 numerator without the time: 96*b*s*l*h^2*(1 + s/6h + V/16lh), or the
     72-form when there is no recompute forward."""

@@ -20,6 +20,20 @@ def test_flop_counter_matches_paper_eq3_without_recompute_and_lm_head():
     assert abs(flops.stage_batch_flops(CONFIGS["12b"], causal=False) - 1.3194e14) < 1e10
 
 
+def test_lm_head_flops_are_the_vocabulary_term_of_eq3():
+    """Eq. 3 as printed: 96*b*s*l*h^2 * V/(16*l*h) = 6*b*s*h*V, exactly the three contractions of the head
+    (logits, input gradient, weight gradient; the head is not recomputed, so this term does not shrink with the
+    recompute factor)."""
+    for sh in CONFIGS.values():
+        V = 51200
+        ours = flops.lm_head_flops(sh, V)
+        with_v = flops.narayanan_flops(sh.microbatch_size, sh.seq_len, sh.n_layers, sh.hidden, V=V, recompute=True)
+        without = flops.narayanan_flops(sh.microbatch_size, sh.seq_len, sh.n_layers, sh.hidden, V=0, recompute=True)
+        eq3_term = (with_v - without) * sh.n_microbatches
+        assert abs(eq3_term - 6.0 * sh.tokens * sh.hidden * V * sh.n_microbatches) <= 1e-9 * eq3_term
+        assert abs(ours - eq3_term) <= 1e-9 * ours
+
+
 def test_regeneration_flops_reach_the_paper_factor_96():
     """With a full recompute forward the count is 4/3 of the stored-activation count (96 vs 72 in Eq. 3);
     this build's regeneration is that minus one h x f contraction per segment."""
