@@ -150,6 +150,9 @@ typedef struct {
   void* ready_event;
   const void* targets_dev; /* last stage only (axonn_stage_attach_ends): int32 [b,s] target ids  */
   void* loss_dev;          /* last stage only: one float, the microbatch's pre-divided loss      */
+  void* done_event;        /* hipEvent_t or NULL: recorded when the message's work is enqueued, it
+                              fires once result_dev is complete -- the "Send(output)" of Alg. 2:
+                              the neighbour's message for this microbatch takes it as ready_event */
 } axonn_msg;
 int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg);
 /* Consumes posted messages until n_microbatches forwards and n_microbatches backwards
@@ -161,6 +164,13 @@ int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg);
  * axonn_stage_join to make hip_stream wait for them in turn).  Returns AXONN_ESTATE if messages remain but none can ever
  * become admissible.  Work is only enqueued; see axonn_stage_synchronize. */
 int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream);
+/* The same loop without blocking: dispatches the posted messages that are admissible and have
+ * arrived right now and returns; n_dispatched (may be NULL) receives their number, n_remaining
+ * (may be NULL) the number of messages the batch still expects.  One host thread can serve
+ * several stages of a pipeline in turn with it, posting to a stage's neighbours what its
+ * dispatch log shows as done (with the message's done_event as their ready_event). */
+int axonn_stage_poll(axonn_stage_t* st, int32_t n_streams, void* hip_stream,
+                     int32_t* n_dispatched, int32_t* n_remaining);
 /* Makes user_stream wait for everything the library streams have been given so far. */
 int axonn_stage_join(axonn_stage_t* st, void* user_stream);
 /* Blocks the host until all enqueued work of the stage is complete. */

@@ -34,7 +34,7 @@ class axonn_stage_config(C.Structure):
 class axonn_msg(C.Structure):
     _fields_ = [("kind", C.c_int32), ("mb_id", C.c_int32), ("payload_dev", C.c_void_p),
                 ("result_dev", C.c_void_p), ("ready_event", C.c_void_p),
-                ("targets_dev", C.c_void_p), ("loss_dev", C.c_void_p)]
+                ("targets_dev", C.c_void_p), ("loss_dev", C.c_void_p), ("done_event", C.c_void_p)]
 
 
 _vp, _i32, _i64, _u64, _f, _d = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float, C.c_double
@@ -54,6 +54,7 @@ _PROTOTYPES = {
     "axonn_stage_backward": [_vp, _i32, _vp, _vp, _vp],
     "axonn_stage_post": [_vp, C.POINTER(axonn_msg)],
     "axonn_stage_run": [_vp, _i32, _vp],
+    "axonn_stage_poll": [_vp, _i32, _vp, C.POINTER(_i32), C.POINTER(_i32)],
     "axonn_stage_join": [_vp, _vp],
     "axonn_stage_synchronize": [_vp],
     "axonn_stage_dispatch_log": [_vp, C.POINTER(_i32), _i32, C.POINTER(_i32)],
@@ -216,10 +217,23 @@ def axonn_stage_backward(st, mb_id, dy, dx, stream=None):
     _check(load().axonn_stage_backward(st, mb_id, _ptr(dy), _ptr(dx), _stream(stream)))
 
 
-def axonn_stage_post(st, kind, mb_id, payload, result, ready_event=None, targets=None, loss=None):
-    ev = ready_event if (ready_event is None or isinstance(ready_event, int)) else ready_event.cuda_event
-    m = axonn_msg(kind, mb_id, _ptr(payload), _ptr(result), ev, _ptr(targets), _ptr(loss))
+def _event(ev):
+    return ev if (ev is None or isinstance(ev, int)) else ev.cuda_event
+
+
+def axonn_stage_post(st, kind, mb_id, payload, result, ready_event=None, targets=None, loss=None, done_event=None):
+    """ready_event / done_event: hipEvent_t handles (int) or torch.cuda.Event objects that have been recorded at
+    least once (torch creates the underlying event at the first record)."""
+    m = axonn_msg(kind, mb_id, _ptr(payload), _ptr(result), _event(ready_event), _ptr(targets), _ptr(loss),
+                  _event(done_event))
     _check(load().axonn_stage_post(st, C.byref(m)))
+
+
+def axonn_stage_poll(st, n_streams=2, stream=None):
+    """(messages dispatched by this call, messages the batch still expects)."""
+    n, r = _i32(), _i32()
+    _check(load().axonn_stage_poll(st, n_streams, _stream(stream), C.byref(n), C.byref(r)))
+    return n.value, r.value
 
 
 def axonn_embed_create(device, vocab, hidden, seq_len, microbatch_size):

@@ -1044,9 +1044,14 @@ int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg) {
   return AXONN_OK;
 }
 
-int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream) {
-  if (!st) return fail(AXONN_EINVAL, "run: null handle");
-  if (n_streams < 1 || n_streams > 8) return fail(AXONN_EINVAL, "run: n_streams must be in 1..8");
+}  // extern "C"
+
+namespace {
+// The receive loop of Alg. 2.  blocking: until the batch's last message is dispatched (waiting for posted
+// messages to arrive; an error if none can ever be scheduled).  Otherwise: dispatches what is ready now and
+// returns, so that one host thread can serve several stages in turn.
+int run_loop(axonn_stage* st, int n_streams, void* hip_stream, bool blocking, int32_t* n_dispatched) {
+  if (n_dispatched) *n_dispatched = 0;
   HIP_TRY(hipSetDevice(st->cfg.device));
   AX_TRY(ensure_streams(st, n_streams));
   // the library streams start after everything already queued on the caller's stream
@@ -1086,6 +1091,7 @@ int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream) {
       break;
     }
     if (chosen < 0) {
+      if (!blocking) break;
       if (!any_admissible)
         return fail(AXONN_ESTATE,
                     "run: %d forward and %d backward messages still expected but none of the %zu posted "
@@ -1121,14 +1127,35 @@ int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream) {
         AX_TRY(backward_msg(st, m.mb_id, st->head_dx, m.result_dev, bs, ws));
         st->bwd_issued++;
         st->dispatch_log.push_back(m.mb_id * 2 + 1);
+        s = bs;
       }
     } else {
       AX_TRY(backward_msg(st, m.mb_id, m.payload_dev, m.result_dev, s, ws));
       st->bwd_issued++;
       st->dispatch_log.push_back(m.mb_id * 2 + 1);
     }
+    // the result buffer is complete once this fires: what a neighbouring stage's message waits for
+    if (m.done_event) HIP_TRY(hipEventRecord((hipEvent_t)m.done_event, s));
+    if (n_dispatched) ++*n_dispatched;
   }
   return AXONN_OK;
+}
+}  // namespace
+
+extern "C" {
+int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream) {
+  if (!st) return fail(AXONN_EINVAL, "run: null handle");
+  if (n_streams < 1 || n_streams > 8) return fail(AXONN_EINVAL, "run: n_streams must be in 1..8");
+  return run_loop(st, n_streams, hip_stream, true, nullptr);
+}
+
+int axonn_stage_poll(axonn_stage_t* st, int32_t n_streams, void* hip_stream, int32_t* n_dispatched,
+                     int32_t* n_remaining) {
+  if (!st) return fail(AXONN_EINVAL, "poll: null handle");
+  if (n_streams < 1 || n_streams > 8) return fail(AXONN_EINVAL, "poll: n_streams must be in 1..8");
+  const int rc = run_loop(st, n_streams, hip_stream, false, n_dispatched);
+  if (n_remaining) *n_remaining = 2 * st->cfg.n_microbatches - st->fwd_issued - st->bwd_issued;
+  return rc;
 }
 
 int axonn_stage_join(axonn_stage_t* st, void* user_stream) {

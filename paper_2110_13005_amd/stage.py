@@ -85,8 +85,11 @@ class Stage:
     def backward(self, mb_id, dy, dx, stream=None):
         B.axonn_stage_backward(self.handle, mb_id, dy, dx, stream)
 
-    def post(self, kind, mb_id, payload, result, ready_event=None, targets=None, loss=None):
-        B.axonn_stage_post(self.handle, kind, mb_id, payload, result, ready_event, targets, loss)
+    def post(self, kind, mb_id, payload, result, ready_event=None, targets=None, loss=None, done_event=None):
+        B.axonn_stage_post(self.handle, kind, mb_id, payload, result, ready_event, targets, loss, done_event)
+
+    def poll(self, n_streams=2, stream=None):
+        return B.axonn_stage_poll(self.handle, n_streams, stream)
 
     def run(self, n_streams=2, stream=None):
         B.axonn_stage_run(self.handle, n_streams, stream)
