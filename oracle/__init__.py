@@ -13,10 +13,14 @@ definition written out: ordinary forward pass, ordinary reverse-mode gradients
 summed over microbatches, ordinary Adam, all in float64, one microbatch at a time,
 no buckets, no streams, no tiling.
 
+Modules: transformer (layers, stage, activation checkpointing of Sec. 5.1 with Eq. 1 and
+the stride rule), lm_ends (first stage's embedding; last stage's final LayerNorm, LM head
+and pre-divided loss, Alg. 2 / Sec. 4.2), adam.
+
 Parity pins (see tests/test_oracle_*.py): every gradient formula is pinned by central
-finite differences; softmax, LayerNorm, GeLU, the linear maps, and Adam are pinned by
-closed forms, special cases and independent library routines.  No function here is
-"parity unpinned".
+finite differences; softmax, LayerNorm, GeLU, the linear maps, the loss and Adam are
+pinned by closed forms, special cases and independent library routines; the regenerating
+pass is pinned to the plain one.  No function here is "parity unpinned".
 """
 from .transformer import (  # noqa: F401
     layernorm_fwd, layernorm_bwd, gelu, gelu_grad, causal_attention_fwd,
