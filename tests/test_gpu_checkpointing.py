@@ -7,8 +7,7 @@ from oracle import transformer as OT
 from paper_2110_13005_amd import binding as B
 from paper_2110_13005_amd.inputs import CONFIGS, StageShape, make_stage_inputs
 from paper_2110_13005_amd.stage import Stage
-from helpers import rel_fro, dev_bf16, host
-from test_gpu_stage import _run_direct, _check, _schedules, EPS
+from helpers import rel_fro, dev_bf16, host, run_direct, check_batch, schedules, EPS
 
 pytestmark = pytest.mark.gpu
 
@@ -36,8 +35,8 @@ def test_checkpointed_stage_parity(ac, fp32_acc):
     ref = _oracle_ckpt_batch(xs, dys, layers, sh.n_heads, ac)
     with Stage(sh, grad_accum_fp32=fp32_acc, ckpt_stride=ac) as st:
         st.load_params(layers)
-        outs, dxs, grads = _run_direct(st, xs, dys)
-    _check(outs, dxs, grads, ref)
+        outs, dxs, grads = run_direct(st, xs, dys)
+    check_batch(outs, dxs, grads, ref)
 
 
 def test_regeneration_changes_no_activation_or_input_gradient():
@@ -50,7 +49,7 @@ def test_regeneration_changes_no_activation_or_input_gradient():
     for ac in (0, 1, 2):
         with Stage(sh, grad_accum_fp32=1, ckpt_stride=ac) as st:
             st.load_params(layers)
-            res[ac] = _run_direct(st, xs, dys)
+            res[ac] = run_direct(st, xs, dys)
     for ac in (1, 2):
         for a, b in zip(res[ac][0] + res[ac][1], res[0][0] + res[0][1]):
             assert np.array_equal(a, b), ac
@@ -67,8 +66,8 @@ def test_checkpointed_schedules_and_slot_reuse():
     ref = _oracle_ckpt_batch(xs, dys, layers, sh.n_heads, 2)
     with Stage(sh, pipeline_limit=2, ckpt_stride=2) as st:
         st.load_params(layers)
-        for name, order in _schedules(sh.n_microbatches, 2).items():
-            _check(*_run_direct(st, xs, dys, order), ref)
+        for name, order in schedules(sh.n_microbatches, 2).items():
+            check_batch(*run_direct(st, xs, dys, order), ref)
 
 
 @pytest.mark.parametrize("n_streams", [1, 2, 3])
@@ -91,7 +90,7 @@ def test_checkpointed_message_driven_run(n_streams):
             st.run(n_streams)
             st.join()
             torch.cuda.synchronize()
-            _check([host(y) for y in Y], [host(d) for d in DX], st.grads_numpy(), ref)
+            check_batch([host(y) for y in Y], [host(d) for d in DX], st.grads_numpy(), ref)
 
 
 def test_checkpointing_memory_follows_eq1():

@@ -9,59 +9,9 @@ from oracle import transformer as OT
 from paper_2110_13005_amd import binding as B
 from paper_2110_13005_amd.inputs import StageShape, make_stage_inputs, make_lm_inputs, snap_bf16
 from paper_2110_13005_amd.stage import Stage, view_bf16
-from helpers import rel_fro, dev_bf16, host
+from helpers import rel_fro, dev_bf16, host, dev_i32, EmbedHandle, HeadHandle, oracle_model, FWD_TOL, GRAD_TOL, EPS
 
 pytestmark = pytest.mark.gpu
-FWD_TOL, GRAD_TOL = 2e-2, 3e-2
-EPS = 1e-5
-
-
-def _dev_i32(a):
-    import torch
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
-
-
-class _Embed:
-    def __init__(self, vocab, h, s, b, wte, wpe):
-        import torch
-        self.h = B.axonn_embed_create(0, vocab, h, s, b)
-        p, g, n = B.axonn_embed_buffers(self.h)
-        assert n == (vocab + s) * h
-        self.params, self.grads = view_bf16(p, n), view_bf16(g, n)
-        self.params[:vocab * h] = dev_bf16(wte).reshape(-1)
-        self.params[vocab * h:] = dev_bf16(wpe).reshape(-1)
-        self.vocab, self.hid, self.s = vocab, h, s
-        torch.cuda.synchronize()
-
-    def grads_numpy(self):
-        g = host(self.grads)
-        return g[:self.vocab * self.hid].reshape(self.vocab, self.hid), g[self.vocab * self.hid:].reshape(self.s, self.hid)
-
-    def close(self):
-        self.params = self.grads = None
-        B.axonn_embed_destroy(self.h)
-
-
-class _Head:
-    def __init__(self, vocab, h, T, M, lnf_g, lnf_b, w_head):
-        import torch
-        self.h = B.axonn_head_create(0, vocab, h, T, M, EPS)
-        p, g, n = B.axonn_head_buffers(self.h)
-        assert n == 2 * h + h * vocab
-        self.params, self.grads = view_bf16(p, n), view_bf16(g, n)
-        self.params[:h] = dev_bf16(lnf_g); self.params[h:2 * h] = dev_bf16(lnf_b)
-        self.params[2 * h:] = dev_bf16(w_head).reshape(-1)
-        self.vocab, self.hid = vocab, h
-        torch.cuda.synchronize()
-
-    def grads_numpy(self):
-        g = host(self.grads)
-        h = self.hid
-        return {"lnf_g": g[:h], "lnf_b": g[h:2 * h], "w_head": g[2 * h:].reshape(h, self.vocab)}
-
-    def close(self):
-        self.params = self.grads = None
-        B.axonn_head_destroy(self.h)
 
 
 def test_embedding_forward_backward_with_repeated_and_out_of_range_ids():
@@ -69,7 +19,7 @@ def test_embedding_forward_backward_with_repeated_and_out_of_range_ids():
     rng = np.random.default_rng(0)
     V, h, s, b = 40, 136, 24, 3                    # few rows: many repeats; 136 columns: a ragged vector tail
     wte, wpe = snap_bf16(rng.standard_normal((V, h), dtype=np.float32)), snap_bf16(rng.standard_normal((s, h), dtype=np.float32))
-    e = _Embed(V, h, s, b, wte, wpe)
+    e = EmbedHandle(V, h, s, b, wte, wpe)
     try:
         tot_te, tot_pe = 0.0, 0.0
         for it in range(3):
@@ -78,11 +28,11 @@ def test_embedding_forward_backward_with_repeated_and_out_of_range_ids():
                 tokens[0, 0], tokens[1, 3], tokens[2, 5] = -7, V, V + 1000      # clamped to 0, V-1, V-1
             clamped = np.clip(tokens, 0, V - 1)
             x = torch.zeros(b, s, h, dtype=torch.bfloat16, device="cuda")
-            B.axonn_embed_forward(e.h, _dev_i32(tokens), x)
+            B.axonn_embed_forward(e.h, dev_i32(tokens), x)
             ref = OE.embedding_forward(clamped, wte, wpe)
             assert rel_fro(host(x), ref) <= 4e-3                               # one bf16 rounding of the sum
             dx = snap_bf16(rng.standard_normal((b, s, h), dtype=np.float32))
-            B.axonn_embed_backward(e.h, _dev_i32(tokens), dev_bf16(dx))
+            B.axonn_embed_backward(e.h, dev_i32(tokens), dev_bf16(dx))
             torch.cuda.synchronize()
             dte, dpe = OE.embedding_backward(dx, clamped, V, s)
             tot_te, tot_pe = tot_te + dte, tot_pe + dpe
@@ -93,7 +43,7 @@ def test_embedding_forward_backward_with_repeated_and_out_of_range_ids():
                 assert not gte[unused].any()                                   # rows nobody used stay exactly zero
         B.axonn_embed_zero_grad(e.h)                                           # the next pass overwrites
         tokens = rng.integers(0, V, (b, s)); dx = snap_bf16(rng.standard_normal((b, s, h), dtype=np.float32))
-        B.axonn_embed_backward(e.h, _dev_i32(tokens), dev_bf16(dx))
+        B.axonn_embed_backward(e.h, dev_i32(tokens), dev_bf16(dx))
         torch.cuda.synchronize()
         dte, dpe = OE.embedding_backward(dx, tokens, V, s)
         gte, gpe = e.grads_numpy()
@@ -109,13 +59,13 @@ def test_head_loss_and_backward(T, h, V, M):
     rng = np.random.default_rng(T)
     g = snap_bf16((1 + 0.1 * rng.standard_normal(h)).astype(np.float32)); bt = snap_bf16((0.1 * rng.standard_normal(h)).astype(np.float32))
     W = snap_bf16((0.05 * rng.standard_normal((h, V))).astype(np.float32))
-    hd = _Head(V, h, T, M, g, bt, W)
+    hd = HeadHandle(V, h, T, M, g, bt, W)
     try:
         tot = None
         for it in range(M):
             x = snap_bf16(rng.standard_normal((1, T, h), dtype=np.float32)); tg = rng.integers(0, V, (1, T))
             loss = torch.zeros(1, device="cuda"); dx = torch.zeros(T, h, dtype=torch.bfloat16, device="cuda")
-            B.axonn_head_forward_backward(hd.h, dev_bf16(x), _dev_i32(tg), loss, dx)
+            B.axonn_head_forward_backward(hd.h, dev_bf16(x), dev_i32(tg), loss, dx)
             torch.cuda.synchronize()
             rl, c = OE.head_loss_forward(x, g, bt, W, tg, EPS, M)
             rdx, rg = OE.head_loss_backward(c, g, W, tg, M)
@@ -129,29 +79,6 @@ def test_head_loss_and_backward(T, h, V, M):
         hd.close()
 
 
-def _oracle_model(tokens, targets, wte, wpe, layers, g, bt, W, n_heads, M):
-    l64 = [{k: np.asarray(v, np.float64) for k, v in p.items()} for p in layers]
-    losses, tot = [], None
-    for tk, tg in zip(tokens, targets):
-        z, caches = OT.stage_forward(OE.embedding_forward(tk, wte, wpe), l64, n_heads, EPS)
-        loss, c = OE.head_loss_forward(z, g, bt, W, tg, EPS, M)
-        dz, gh = OE.head_loss_backward(c, g, W, tg, M)
-        dx, gl = OT.stage_backward(dz, caches, l64, n_heads)
-        dte, dpe = OE.embedding_backward(dx, tk, wte.shape[0], wpe.shape[0])
-        cur = dict(layers=gl, head=gh, wte=dte, wpe=dpe)
-        losses.append(loss)
-        if tot is None:
-            tot = cur
-        else:
-            tot["wte"] += dte; tot["wpe"] += dpe
-            for k in gh:
-                tot["head"][k] += gh[k]
-            for a, b_ in zip(tot["layers"], gl):
-                for k in a:
-                    a[k] += b_[k]
-    return losses, tot
-
-
 @pytest.mark.parametrize("n_streams,ckpt", [(1, 0), (2, 0), (3, 2)])
 def test_whole_model_on_one_stage_message_driven(n_streams, ckpt):
     """A stage that is both the first and the last one: token messages in, losses out, every gradient against the
@@ -161,15 +88,15 @@ def test_whole_model_on_one_stage_message_driven(n_streams, ckpt):
     V = 520
     layers, _, _ = make_stage_inputs(sh, seed=11, perturb=True)
     tokens, targets, wte, wpe, g, bt, W = make_lm_inputs(sh, V, seed=12)
-    ref_losses, ref = _oracle_model(tokens, targets, wte, wpe, layers, g, bt, W, sh.n_heads, sh.n_microbatches)
+    ref_losses, ref = oracle_model(tokens, targets, wte, wpe, layers, g, bt, W, sh.n_heads, sh.n_microbatches)
     M = sh.n_microbatches
-    e = _Embed(V, sh.hidden, sh.seq_len, sh.microbatch_size, wte, wpe)
-    hd = _Head(V, sh.hidden, sh.tokens, M, g, bt, W)
+    e = EmbedHandle(V, sh.hidden, sh.seq_len, sh.microbatch_size, wte, wpe)
+    hd = HeadHandle(V, sh.hidden, sh.tokens, M, g, bt, W)
     try:
         with Stage(sh, pipeline_limit=2, ckpt_stride=ckpt) as st:
             st.load_params(layers)
             B.axonn_stage_attach_ends(st.handle, e.h, hd.h)
-            TK = [_dev_i32(t) for t in tokens]; TG = [_dev_i32(t) for t in targets]
+            TK = [dev_i32(t) for t in tokens]; TG = [dev_i32(t) for t in targets]
             losses = torch.zeros(M, device="cuda")
             for rep in range(2):        # the second batch must start from cleared accumulators at both ends
                 st.zero_grad()
@@ -206,13 +133,13 @@ def test_first_stage_and_last_stage_separately():
     tokens, targets, wte, wpe, g, bt, W = make_lm_inputs(sh, V, seed=14)
     l64 = [{k: np.asarray(v, np.float64) for k, v in p.items()} for p in layers]
     # first stage
-    e = _Embed(V, sh.hidden, sh.seq_len, sh.microbatch_size, wte, wpe)
+    e = EmbedHandle(V, sh.hidden, sh.seq_len, sh.microbatch_size, wte, wpe)
     try:
         with Stage(sh) as st:
             st.load_params(layers)
             B.axonn_stage_attach_ends(st.handle, e.h, None)
             Y = [torch.zeros(sh.microbatch_size, sh.seq_len, sh.hidden, dtype=torch.bfloat16, device="cuda") for _ in range(M)]
-            TK = [_dev_i32(t) for t in tokens]; DY = [dev_bf16(d) for d in dys]
+            TK = [dev_i32(t) for t in tokens]; DY = [dev_bf16(d) for d in dys]
             st.zero_grad()
             for i in range(M):
                 st.post(0, i, TK[i], Y[i])
@@ -229,14 +156,14 @@ def test_first_stage_and_last_stage_separately():
     finally:
         e.close()
     # last stage
-    hd = _Head(V, sh.hidden, sh.tokens, M, g, bt, W)
+    hd = HeadHandle(V, sh.hidden, sh.tokens, M, g, bt, W)
     try:
         with Stage(sh) as st:
             st.load_params(layers)
             B.axonn_stage_attach_ends(st.handle, None, hd.h)
             X = [dev_bf16(x) for x in xs]
             DX = [torch.zeros_like(X[0]) for _ in range(M)]
-            TG = [_dev_i32(t) for t in targets]
+            TG = [dev_i32(t) for t in targets]
             losses = torch.zeros(M, device="cuda")
             st.zero_grad()
             with pytest.raises(B.AxonnError):

@@ -8,8 +8,7 @@ import pytest
 from paper_2110_13005_amd import binding as B
 from paper_2110_13005_amd.inputs import StageShape, make_stage_inputs, make_lm_inputs
 from paper_2110_13005_amd.stage import Stage
-from helpers import rel_fro
-from test_gpu_lm_ends import _Embed, _Head, _dev_i32, _oracle_model, GRAD_TOL
+from helpers import rel_fro, EmbedHandle, HeadHandle, dev_i32, oracle_model, GRAD_TOL
 
 pytestmark = pytest.mark.gpu
 
@@ -29,16 +28,16 @@ def test_two_stage_pipeline_message_driven(n_streams, limit_a):
     V, M = 520, whole.n_microbatches
     layers, _, _ = make_stage_inputs(whole, seed=21, perturb=True)
     tokens, targets, wte, wpe, g, bt, W = make_lm_inputs(whole, V, seed=22)
-    ref_losses, ref = _oracle_model(tokens, targets, wte, wpe, layers, g, bt, W, whole.n_heads, M)
-    e = _Embed(V, whole.hidden, whole.seq_len, whole.microbatch_size, wte, wpe)
-    hd = _Head(V, whole.hidden, whole.tokens, M, g, bt, W)
+    ref_losses, ref = oracle_model(tokens, targets, wte, wpe, layers, g, bt, W, whole.n_heads, M)
+    e = EmbedHandle(V, whole.hidden, whole.seq_len, whole.microbatch_size, wte, wpe)
+    hd = HeadHandle(V, whole.hidden, whole.tokens, M, g, bt, W)
     try:
         with Stage(half, pipeline_limit=limit_a) as A, Stage(half, pipeline_limit=2) as Bst:
             A.load_params(layers[:2]); Bst.load_params(layers[2:])
             B.axonn_stage_attach_ends(A.handle, e.h, None)
             B.axonn_stage_attach_ends(Bst.handle, None, hd.h)
             bsh = (whole.microbatch_size, whole.seq_len, whole.hidden)
-            TK = [_dev_i32(t) for t in tokens]; TG = [_dev_i32(t) for t in targets]
+            TK = [dev_i32(t) for t in tokens]; TG = [dev_i32(t) for t in targets]
             ACT = [torch.zeros(bsh, dtype=torch.bfloat16, device="cuda") for _ in range(M)]    # A -> B
             GRD = [torch.zeros(bsh, dtype=torch.bfloat16, device="cuda") for _ in range(M)]    # B -> A
             sent = [_event() for _ in range(M)]; back = [_event() for _ in range(M)]

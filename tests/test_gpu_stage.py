@@ -10,48 +10,10 @@ import oracle
 from paper_2110_13005_amd import binding as B
 from paper_2110_13005_amd.inputs import CONFIGS, StageShape, make_stage_inputs, make_adam_inputs
 from paper_2110_13005_amd.stage import Stage
-from helpers import rel_fro, dev_bf16, dev_f32, host
+from helpers import (rel_fro, dev_bf16, dev_f32, host, run_direct, check_batch, schedules, FWD_TOL, GRAD_TOL,
+                     ADAM_TOL, EPS)
 
 pytestmark = pytest.mark.gpu
-FWD_TOL, GRAD_TOL, ADAM_TOL = 2e-2, 3e-2, 1e-6
-EPS = 1e-5
-
-
-def _run_direct(stage, xs, dys, order=None):
-    """All forwards then all backwards (or a given order of (kind, mb)) on the null stream."""
-    import torch
-    M = len(xs)
-    X = [dev_bf16(x) for x in xs]
-    DY = [dev_bf16(d) for d in dys]
-    Y = [torch.zeros_like(X[0]) for _ in range(M)]
-    DX = [torch.zeros_like(X[0]) for _ in range(M)]
-    stage.zero_grad()
-    if order is None:
-        order = [(0, i) for i in range(M)] + [(1, i) for i in range(M)]
-    for kind, i in order:
-        if kind == 0:
-            stage.forward(i, X[i], Y[i])
-        else:
-            stage.backward(i, DY[i], DX[i])
-    torch.cuda.synchronize()
-    return [host(y) for y in Y], [host(d) for d in DX], stage.grads_numpy()
-
-
-def _check(outs, dxs, grads, ref, fwd_tol=FWD_TOL, grad_tol=GRAD_TOL):
-    r_outs, r_dxs, r_tot = ref
-    worst = {"fwd": 0.0, "dx": 0.0, "grad": 0.0}
-    for o, r in zip(outs, r_outs):
-        worst["fwd"] = max(worst["fwd"], rel_fro(o.reshape(r.shape), r))
-    for o, r in zip(dxs, r_dxs):
-        worst["dx"] = max(worst["dx"], rel_fro(o.reshape(r.shape), r))
-    for li, g in enumerate(grads):
-        for name, arr in g.items():
-            e = rel_fro(arr, r_tot[li][name])
-            assert e <= grad_tol, ("layer%d.%s" % (li, name), e)
-            worst["grad"] = max(worst["grad"], e)
-    assert worst["fwd"] <= fwd_tol, worst
-    assert worst["dx"] <= grad_tol, worst
-    return worst
 
 
 @pytest.mark.parametrize("perturb", [False, True])
@@ -64,11 +26,11 @@ def test_tiny_config_parity(perturb, fp32_acc):
     ref = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
     with Stage(sh, grad_accum_fp32=fp32_acc) as st:
         st.load_params(layers)
-        outs, dxs, grads = _run_direct(st, xs, dys)
+        outs, dxs, grads = run_direct(st, xs, dys)
     if not perturb:
         # biases start at zero and LayerNorm shifts at zero: their gradients are still non-zero
         assert np.linalg.norm(ref[2][0]["b_qkv"]) > 0
-    _check(outs, dxs, grads, ref)
+    check_batch(outs, dxs, grads, ref)
 
 
 def test_split_input_qkv_projection_parity_and_effect():
@@ -81,8 +43,8 @@ def test_split_input_qkv_projection_parity_and_effect():
     for split in (0, 1):
         with Stage(sh, qkv_input_split=split) as st:
             st.load_params(layers)
-            outs, dxs, grads = _run_direct(st, xs, dys)
-        errs.append(_check(outs, dxs, grads, ref))
+            outs, dxs, grads = run_direct(st, xs, dys)
+        errs.append(check_batch(outs, dxs, grads, ref))
     assert errs[1]["grad"] < errs[0]["grad"] and errs[1]["fwd"] < errs[0]["fwd"], errs
 
 
@@ -98,8 +60,8 @@ def test_ragged_and_degenerate_shapes(sh):
     ref = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
     with Stage(sh) as st:
         st.load_params(layers)
-        outs, dxs, grads = _run_direct(st, xs, dys)
-    _check(outs, dxs, grads, ref)
+        outs, dxs, grads = run_direct(st, xs, dys)
+    check_batch(outs, dxs, grads, ref)
 
 
 def test_zero_output_projections_give_identity():
@@ -112,25 +74,9 @@ def test_zero_output_projections_give_identity():
         p["w_fc2"][:] = 0
     with Stage(sh) as st:
         st.load_params(layers)
-        outs, dxs, _ = _run_direct(st, xs, dys)
+        outs, dxs, _ = run_direct(st, xs, dys)
     assert np.array_equal(outs[0].reshape(xs[0].shape), xs[0].astype(np.float64))
     assert np.array_equal(dxs[0].reshape(dys[0].shape), dys[0].astype(np.float64))
-
-
-def _schedules(M, P):
-    """Valid message orders for a middle stage (warm-up depth w, then one-forward-one-backward,
-    then drain), as lists of (kind, mb)."""
-    out = {}
-    for w in sorted({1, max(1, P // 2), P}):
-        order, f, b = [], 0, 0
-        while f < min(w, M):
-            order.append((0, f)); f += 1
-        while b < M:
-            order.append((1, b)); b += 1
-            if f < M:
-                order.append((0, f)); f += 1
-        out["warmup%d" % w] = order
-    return out
 
 
 def test_schedule_independence_direct_calls():
@@ -143,9 +89,9 @@ def test_schedule_independence_direct_calls():
     results = {}
     with Stage(sh) as st:
         st.load_params(layers)
-        for name, order in _schedules(sh.n_microbatches, sh.n_microbatches).items():
-            results[name] = _run_direct(st, xs, dys, order)
-            _check(*results[name], ref)
+        for name, order in schedules(sh.n_microbatches, sh.n_microbatches).items():
+            results[name] = run_direct(st, xs, dys, order)
+            check_batch(*results[name], ref)
         rng = np.random.default_rng(0)
         # seeded random valid order: a backward may only follow its own forward
         order, fwd_done, pending_b = [], 0, []
@@ -156,8 +102,8 @@ def test_schedule_independence_direct_calls():
                 order.append((0, i)); pending_b.append(i); fwd_done += 1
             else:
                 order.append((1, i)); pending_b.remove(i)
-        results["random"] = _run_direct(st, xs, dys, order)
-        _check(*results["random"], ref)
+        results["random"] = run_direct(st, xs, dys, order)
+        check_batch(*results["random"], ref)
     base = results["warmup1"]
     for name, r in results.items():
         for a, b in zip(r[0] + r[1], base[0] + base[1]):
@@ -199,7 +145,7 @@ def test_message_driven_run_matches_oracle_and_respects_pipeline_limit(n_streams
                 live.remove(mb)
             peak = max(peak, len(live))
         assert peak == P                                  # steady state holds exactly pipeline_limit
-        _check([host(y) for y in Y], [host(d) for d in DX], st.grads_numpy(), ref)
+        check_batch([host(y) for y in Y], [host(d) for d in DX], st.grads_numpy(), ref)
 
 
 def test_message_arrival_order_follows_ready_events():
@@ -275,8 +221,8 @@ def test_fixed_schedule_is_bit_reproducible():
     layers, xs, dys = make_stage_inputs(sh, seed=0, perturb=True)
     with Stage(sh) as st:
         st.load_params(layers)
-        a = _run_direct(st, xs, dys)
-        b = _run_direct(st, xs, dys)
+        a = run_direct(st, xs, dys)
+        b = run_direct(st, xs, dys)
     for x, y in zip(a[0] + a[1], b[0] + b[1]):
         assert np.array_equal(x, y)
     for ga, gb in zip(a[2], b[2]):
@@ -364,7 +310,7 @@ def test_stage_batch_then_optimizer_step():
         ptrs, arrs = zip(*[_pinned_array(n) for _ in range(3)])
         theta0 = st.params.float().cpu().numpy()
         arrs[0][:] = theta0; arrs[1][:] = 0; arrs[2][:] = 0
-        _run_direct(st, xs, dys)
+        run_direct(st, xs, dys)
         g16 = st.grads.float().cpu().numpy()
         B.axonn_stage_optimizer_attach(st.handle, ptrs[0], ptrs[1], ptrs[2], n, 1 << 18)
         with pytest.raises(B.AxonnError):
