@@ -25,7 +25,7 @@ import numpy as np  # noqa: E402
 
 # HBM bytes per launch of the weight-gradient GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and the scaling by a plain copy under profiles/); keyed by (config, wgrad_group, grad_accum).
-WGRAD_TRAFFIC_BYTES = {("12b", 3, "bf16"): 1.703e9, ("12b", 2, "bf16"): 1.363e9}   # profiles/gemm_wgrad_12b_hbm_traffic.md
+WGRAD_TRAFFIC_BYTES = {("12b", 3, "bf16"): 1.811e9}   # profiles/gemm_wgrad_12b_hbm_traffic.md
 
 
 def parse():
@@ -308,7 +308,7 @@ def main():
                 kern[cat]["frac_of_hbm_peak"] = kern[cat]["GBps"] / flops.PEAK_HBM_GBPS
         out["kernels"] = kern
         # roofline of the largest single kernel by time: the weight-gradient GEMM
-        # (gemm_big_kernel<false,false,EPI_ACC_*,8>), one launch = one weight of one layer for a
+        # (gemm_dma_kernel<false,false,5,8> for bf16 accumulators), one launch = one weight of one layer for a
         # group of microbatches; its four shapes average to per_layer_mb/4 FLOP per microbatch
         dom = "gemm_wgrad"
         if dom in kern:
@@ -317,8 +317,8 @@ def main():
             out["roofline"] = {"bound": "mfma", "achieved": ach, "peak": flops.PEAK_BF16_DENSE_TFLOPS,
                                "unit": "TFLOP/s", "frac": ach / flops.PEAK_BF16_DENSE_TFLOPS,
                                "traffic": WGRAD_TRAFFIC_BYTES.get((args.config, args.wgrad_group, args.grad_accum)),
-                               "kernel": "axonn::gemm_big_kernel<false,false,%d,8> (weight gradient)"
-                                         % (4 if args.grad_accum == "fp32" else 5),
+                               "kernel": ("axonn::gemm_big_kernel<false,false,4,8>" if args.grad_accum == "fp32"
+                                          else "axonn::gemm_dma_kernel<false,false,5,8>") + " (weight gradient)",
                                "avg_launch_ms": kern[dom]["avg_ms"], "flops_per_launch": per_launch,
                                "measured": "launch timing events on the launching stream, one single-stream batch"}
     # a plain device copy of known size (256 MiB read + 256 MiB written): the reference the HBM byte

@@ -626,6 +626,266 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
 #undef sB
 }
 
+// ---------------------------------------------------------------------------------------------
+// gemm_dma_kernel: the tiling of gemm_big_kernel (256 x 32*TN x 64 block, 2 x 2 waves, one wave per
+// SIMD, 128 x 16*TN wave tile of 16x16x32 MFMAs) with the tiles copied global -> LDS by the memory
+// pipeline itself (`buffer_load_dwordx4 ... lds`): no staging registers, no LDS store instructions, no
+// vector ALU work for addresses inside the loop.  For problems whose K is a multiple of 64.
+//
+// One such instruction writes the 64 chunks of 16 bytes its lanes fetch to 1 KB of consecutive LDS
+// bytes in lane order (M0 holds the start), so the LDS tiles cannot be padded; instead the lanes
+// fetch a permutation of the chunks, chosen so that the fragment reads stay free of bank conflicts:
+//   k-contiguous tile  [row][64 k]: 128 bytes per row; slot p of row r holds chunk p ^ ((r >> 1) & 7).
+//                      An instruction covers 8 rows.
+//   k-strided tile     [k][256 rows]: 512 bytes per k, in natural order.  An instruction covers the k
+//                      rows 8c + w and 8c + w + 4 (one per half wave); its 1 KB block is followed by
+//                      32 bytes of padding, so that the 8 k rows a transposing read touches in one
+//                      pass (k0 .. k0+3 and k0+8 .. k0+11, 32 bytes each) fall into different banks.
+// Two stages of one 64-wide k tile each.  In k-step kt (tile kt in stage CUR): phase 0 multiplies k slice
+// 0 while the fragments of slice 1 are read; a few MFMAs into phase 1 the wave waits for its own copies
+// of tile kt+1 (issued a k-step earlier) and meets the others at the barrier: tile kt+1 is complete in
+// stage CUR^1 and nobody reads stage CUR any more; the rest of phase 1 reads the slice-0 fragments of
+// tile kt+1 and issues the copies of tile kt+2 into stage CUR.
+// The copies are inline assembly: the compiler neither sees them nor counts them in vmcnt, so the
+// waits on them are written out here, and the loop contains no other vector memory instruction.
+__device__ __forceinline__ void dma_chunk16(u32x4 rsrc, uint32_t voffset, uint32_t soffset, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :
+               : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory");
+}
+// The same in two parts, for an independent instruction (an MFMA) in between instead of the s_nop.
+__device__ __forceinline__ void dma_set_m0(uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0" : : "s"(lds_addr) : "memory");
+}
+__device__ __forceinline__ void dma_chunk16_m0(u32x4 rsrc, uint32_t voffset, uint32_t soffset) {
+  asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds" : : "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+}
+__device__ __forceinline__ void dma_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Buffer descriptor words of `bytes` bytes at p (raw buffer, offsets at or beyond `bytes` read zeros).
+__device__ __forceinline__ u32x4 rsrc_words(const void* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)p;
+  u32x4 r;
+  r[0] = (uint32_t)a; r[1] = (uint32_t)(a >> 32) & 0xffffu; r[2] = bytes; r[3] = 0x00020000u;
+  return r;
+}
+
+template <bool A_KC, bool B_KC, int EPI, int TN>
+__global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
+  constexpr int BM = 256, BN = 32 * TN, BK = 64, TM = 8;
+  constexpr int NCA = 8, NCB = B_KC ? TN : 8;     // copy instructions per wave and tile
+  constexpr int NM = TM * TN, NF = TM + TN, ND = NCA + NCB;
+  // The copies of a k-step are spread over all of phase 1 behind the barrier.  Issued back to back they
+  // would have longer until the next barrier, but the memory pipeline takes them only so fast and the
+  // MFMAs behind a copy that cannot issue wait with it: measured 6-9 % slower.
+#ifndef AXONN_DMA_SPAN
+#define AXONN_DMA_SPAN (NM - 8)
+#endif
+  constexpr int DMA_FIRST = 7, DMA_SPAN = AXONN_DMA_SPAN;
+  constexpr int KS_BLOCK = 1024 + 32;             // two k rows of a k-strided tile and their padding
+  constexpr int SA = A_KC ? BM * BK * 2 : 32 * KS_BLOCK;              // bytes of one stage of A
+  constexpr int SB = B_KC ? BN * BK * 2 : 32 * KS_BLOCK;              // and of B
+  constexpr int TILE_BYTES = 2 * (SA + SB);
+  constexpr int EPI_BYTES = 4 * StageLayout<TN>::FLOATS_PER_WAVE * (int)sizeof(float);
+  constexpr int LDS_BYTES = TILE_BYTES > EPI_BYTES ? TILE_BYTES : EPI_BYTES;
+  __shared__ __align__(1024) char smem[LDS_BYTES];   // A stage 0, A stage 1, B stage 0, B stage 1
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 1, wn = wave & 1;
+
+  int pid = blockIdx.x;
+  const int nblk = gridDim.x;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  constexpr int BAND = 8;
+  const int band_tiles = BAND * g.tiles_n;
+  const int band = pid / band_tiles, in_band = pid - band * band_tiles;
+  const int band_rows = min(BAND, g.tiles_m - band * BAND);
+  const int tm = band * BAND + in_band % band_rows, tn = in_band / band_rows;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  // Copy instruction c of this wave: the byte offset of each lane's chunk from the segment base in
+  // k-tile 0 (kOutOfRange for rows outside the matrix), and the bytes to add per k-tile (uniform).
+  const uint32_t lda = (uint32_t)g.lda, ldb = (uint32_t)g.ldb;
+  uint32_t va[NCA], vb[NCB];
+  uint32_t sa, sb, nra, nrb;
+  if (A_KC) {
+    const int q = (lane & 7) ^ (((wave & 1) << 2) + (lane >> 4));
+#pragma unroll
+    for (int c = 0; c < NCA; ++c) {
+      const int row = m0 + (c * 4 + wave) * 8 + (lane >> 3);
+      va[c] = row < g.M ? ((uint32_t)row * lda + q * 8) * 2u : kOutOfRange;
+    }
+    sa = BK * 2u; nra = (uint32_t)g.M * lda * 2u;
+  } else {
+#pragma unroll
+    for (int c = 0; c < NCA; ++c) {
+      const int k = 8 * c + wave + 4 * (lane >> 5);
+      const int col = m0 + ((lane & 31) << 3);
+      va[c] = col < g.M ? ((uint32_t)k * lda + col) * 2u : kOutOfRange;
+    }
+    sa = BK * lda * 2u; nra = (uint32_t)g.K * lda * 2u;
+  }
+  if (B_KC) {
+    const int q = (lane & 7) ^ (((wave & 1) << 2) + (lane >> 4));
+#pragma unroll
+    for (int c = 0; c < NCB; ++c) {
+      const int row = n0 + (c * 4 + wave) * 8 + (lane >> 3);
+      vb[c] = row < g.N ? ((uint32_t)row * ldb + q * 8) * 2u : kOutOfRange;
+    }
+    sb = BK * 2u; nrb = (uint32_t)g.N * ldb * 2u;
+  } else {
+#pragma unroll
+    for (int c = 0; c < NCB; ++c) {
+      const int k = 8 * c + wave + 4 * (lane >> 5);
+      const int cl = (lane & 31) << 3;
+      vb[c] = (cl < BN && n0 + cl < g.N) ? ((uint32_t)k * ldb + n0 + cl) * 2u : kOutOfRange;
+    }
+    sb = BK * ldb * 2u; nrb = (uint32_t)g.K * ldb * 2u;
+  }
+
+  // Fragment reads: per-lane byte offsets into `smem` that do not depend on stage and k slice.
+  //   k-contiguous: rows r0 + lane%16 (r0 a multiple of 16), chunk 4*kk + lane/16 of the row; one offset
+  //                 per k slice, fragment i adds i * 16 rows.
+  //   k-strided:    k rows 32*kk + 8*(lane/16) + (lane%16)/4 (+4 for the second half: the other half of
+  //                 the same block), elements r0 + 4*(lane%4) .. +3; one offset.
+  const int ft = lane & 15, fg = lane >> 4;
+  uint32_t fa_off[A_KC ? 2 : 1], fb_off[B_KC ? 2 : 1];
+  if (A_KC) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+      fa_off[kk] = (uint32_t)((wm * 128 + ft) * 128 + ((((kk << 2) + fg) ^ ((lane >> 1) & 7)) << 4));
+  } else {
+    fa_off[0] = (uint32_t)((4 * fg + (ft >> 2)) * KS_BLOCK + (wm * 128 + 4 * (ft & 3)) * 2);
+  }
+  if (B_KC) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+      fb_off[kk] = (uint32_t)(2 * SA + (wn * 16 * TN + ft) * 128 + ((((kk << 2) + fg) ^ ((lane >> 1) & 7)) << 4));
+  } else {
+    fb_off[0] = (uint32_t)(2 * SA + (4 * fg + (ft >> 2)) * KS_BLOCK + (wn * 16 * TN + 4 * (ft & 3)) * 2);
+  }
+
+  const int tps = g.K / BK;               // k-tiles per segment (K is a multiple of BK)
+  const int nk = tps * g.n_seg;
+  int ld_seg = 0, ld_kin = 0;             // segment and k-tile within it of the NEXT tile to fetch
+  u32x4 rsa = rsrc_words(g.A_seg[0], nra), rsb = rsrc_words(g.B_seg[0], nrb);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(AXONN_LDS char*)smem;
+
+  // Copy instruction d (A chunks first, then B chunks) of the next tile into stage `buf`.
+#define AXONN_DMA(buf, d)                                                                      \
+  if ((d) < NCA) {                                                                             \
+    dma_chunk16(rsa, va[(d) < NCA ? (d) : 0], (uint32_t)ld_kin * sa,                           \
+                lds0 + (buf) * SA + ((d) * 4 + wave) * (A_KC ? 1024 : KS_BLOCK));              \
+  } else {                                                                                     \
+    dma_chunk16(rsb, vb[(d) >= NCA ? (d) - NCA : 0], (uint32_t)ld_kin * sb,                    \
+                lds0 + 2 * SA + (buf) * SB + (((d) - NCA) * 4 + wave) * (B_KC ? 1024 : KS_BLOCK)); \
+  }
+  // The tile after the last one of the last segment does not exist: a descriptor of size 0 makes its
+  // copies write zeros (the tile that pads an odd tile count is multiplied, the others are not read).
+#define AXONN_DMA_M0(buf, d)                                                                   \
+  if ((d) < NCA) dma_set_m0(lds0 + (buf) * SA + ((d) * 4 + wave) * (A_KC ? 1024 : KS_BLOCK));  \
+  else dma_set_m0(lds0 + 2 * SA + (buf) * SB + (((d) - NCA) * 4 + wave) * (B_KC ? 1024 : KS_BLOCK));
+#define AXONN_DMA_LOAD(d)                                                                      \
+  if ((d) < NCA) dma_chunk16_m0(rsa, va[(d) < NCA ? (d) : 0], (uint32_t)ld_kin * sa);          \
+  else dma_chunk16_m0(rsb, vb[(d) >= NCA ? (d) - NCA : 0], (uint32_t)ld_kin * sb);
+#define AXONN_DMA_NEXT()                                                                       \
+  if (++ld_kin == tps) {                                                                       \
+    ld_kin = 0;                                                                                \
+    ++ld_seg;                                                                                  \
+    const bool live = ld_seg < g.n_seg;                                                        \
+    const int sidx = live ? ld_seg : 0;                                                        \
+    rsa = rsrc_words(g.A_seg[sidx], live ? nra : 0u);                                          \
+    rsb = rsrc_words(g.B_seg[sidx], live ? nrb : 0u);                                          \
+  }
+#define AXONN_FRAG(F, buf, kk, f)                                                              \
+  if ((f) == 0 || (f) > TN) {                                                                  \
+    const int i = (f) == 0 ? 0 : (f) - TN;                                                     \
+    if (A_KC) {                                                                                \
+      fa[F][i] = *reinterpret_cast<const bf16x8*>(smem + fa_off[A_KC ? (kk) : 0] + (buf) * SA + i * 2048); \
+    } else {                                                                                   \
+      const char* pf = smem + fa_off[0] + (buf) * SA + (kk) * 16 * KS_BLOCK + i * 32;          \
+      union { bf16x8 v; short4v h[2]; } u;                                                     \
+      u.h[0] = lds_read_tr16(reinterpret_cast<const bf16_t*>(pf));                             \
+      u.h[1] = lds_read_tr16(reinterpret_cast<const bf16_t*>(pf + 512));                       \
+      fa[F][i] = u.v;                                                                          \
+    }                                                                                          \
+  } else {                                                                                     \
+    const int j = (f) - 1;                                                                     \
+    if (B_KC) {                                                                                \
+      fb[F][j] = *reinterpret_cast<const bf16x8*>(smem + fb_off[B_KC ? (kk) : 0] + (buf) * SB + j * 2048); \
+    } else {                                                                                   \
+      const char* pf = smem + fb_off[0] + (buf) * SB + (kk) * 16 * KS_BLOCK + j * 32;          \
+      union { bf16x8 v; short4v h[2]; } u;                                                     \
+      u.h[0] = lds_read_tr16(reinterpret_cast<const bf16_t*>(pf));                             \
+      u.h[1] = lds_read_tr16(reinterpret_cast<const bf16_t*>(pf + 512));                       \
+      fb[F][j] = u.v;                                                                          \
+    }                                                                                          \
+  }
+#define AXONN_MFMA(F, q) mfma16_acc(acc[(q) / TN][(q) % TN], fb[F][(q) % TN], fa[F][(q) / TN]);
+#define AXONN_KSTEP(CUR)                                                                       \
+  _Pragma("unroll") for (int q = 0; q < NM; ++q) {                                             \
+    AXONN_MFMA(0, q)                                                                           \
+    { const int f = item_at(q, NF, 0, NM - 3); if (f >= 0) { AXONN_FRAG(1, CUR, 1, f) } }      \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }                                                                                            \
+  _Pragma("unroll") for (int q = 0; q < 6; ++q) {                                              \
+    AXONN_MFMA(1, q)                                                                           \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }                                                                                            \
+  dma_wait_all();                                                                              \
+  lds_barrier();                                                                               \
+  _Pragma("unroll") for (int q = 6; q < NM; ++q) {                                             \
+    const int d = item_at(q, ND, DMA_FIRST, DMA_SPAN);                                         \
+    if (d >= 0) { AXONN_DMA_M0(CUR, d) }                                                       \
+    AXONN_MFMA(1, q)                                                                           \
+    if (d >= 0) { AXONN_DMA_LOAD(d) }                                                          \
+    { const int f = item_at(q, NF, 8, NM - 8); if (f >= 0) { AXONN_FRAG(0, (CUR) ^ 1, 0, f) } } \
+    __builtin_amdgcn_sched_barrier(0);                                                         \
+  }                                                                                            \
+  AXONN_DMA_NEXT()
+
+  floatx4 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
+  bf16x8 fa[2][TM], fb[2][TN];
+
+  // prologue: tiles 0 and 1 into stages 0 and 1
+#pragma unroll
+  for (int d = 0; d < ND; ++d) { AXONN_DMA(0, d) }
+  AXONN_DMA_NEXT()
+#pragma unroll
+  for (int d = 0; d < ND; ++d) { AXONN_DMA(1, d) }
+  AXONN_DMA_NEXT()
+  dma_wait_all();
+  lds_barrier();
+#pragma unroll
+  for (int f = 0; f < NF; ++f) { AXONN_FRAG(0, 0, 0, f) }
+  asm volatile("s_nop 7" ::: "memory");      // accumulators were just zeroed: settle before the first MFMA
+  for (int kt = 0; kt < nk; kt += 2) {
+    AXONN_KSTEP(0)
+    AXONN_KSTEP(1)
+  }
+  dma_wait_all();                            // copies of tiles past the end still write (zeros) to LDS
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // last MFMAs drain before the results are read
+#undef AXONN_DMA
+#undef AXONN_DMA_M0
+#undef AXONN_DMA_LOAD
+#undef AXONN_DMA_NEXT
+#undef AXONN_FRAG
+#undef AXONN_MFMA
+#undef AXONN_KSTEP
+
+  lds_barrier();                                          // every wave is done with the tiles in LDS
+  gemm_epilogue_staged<EPI, TN>(acc, g, m0 + wm * 128, n0 + wn * (16 * TN), lane,
+                                reinterpret_cast<float*>(smem) + wave * StageLayout<TN>::FLOATS_PER_WAVE);
+}
+
 // Only the (layout, epilogue) pairs the layer uses are instantiated: forward maps take the
 // bias epilogues, input gradients the plain / GeLU' ones, weight gradients the accumulating ones.
 constexpr bool epilogue_allowed(bool a_kc, bool b_kc, int e) {
@@ -661,15 +921,32 @@ static hipError_t launch_cfg(int epi, GemmArgs g, hipStream_t s) {
   return hipGetLastError();
 }
 
+static int64_t env_int(const char* name, int64_t dflt) {
+  const char* e = getenv(name);
+  return e && *e ? (int64_t)atoll(e) : dflt;
+}
+
 template <bool A_KC, bool B_KC, int TN>
 static hipError_t launch_big(int epi, GemmArgs g, hipStream_t s) {
   g.tiles_m = (g.M + 255) / 256;
   g.tiles_n = (g.N + 32 * TN - 1) / (32 * TN);
   const dim3 grid(g.tiles_m * g.tiles_n), block(256);
+  // the kernel with copies by the memory pipeline needs whole k tiles
+  // and pays where the operands come mostly from the L2: the weight gradients with a bf16 result.  Its copies
+  // have less time to arrive than the chunks of the register-staged kernel, and where more of them come
+  // from HBM (long K with few tiles per operand strip; the read-modify-write of an fp32 result in the
+  // background) it is the slower one.  AXONN_GEMM_DMA overrides the choice, for tuning: bit 0 (kc,kc),
+  // bit 1 (kc,ks), bit 2 (ks,ks) with a bf16 result, bit 3 (ks,ks) with an fp32 result.
+  static const int64_t dma_mask = env_int("AXONN_GEMM_DMA", 4);
+  const int dma_bit = A_KC ? (B_KC ? 0 : 1) : (epi == EPI_ACC_F32 ? 3 : 2);
+  const bool use_dma = ((dma_mask >> dma_bit) & 1) && g.K % 64 == 0;
 #define AXONN_GEMM_CASE(E)                                                                      \
   case E:                                                                                       \
     if constexpr (epilogue_allowed(A_KC, B_KC, E)) {                                            \
-      hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, E, TN>), grid, block, 0, s, g);           \
+      if (use_dma)                                                                              \
+        hipLaunchKernelGGL((gemm_dma_kernel<A_KC, B_KC, E, TN>), grid, block, 0, s, g);         \
+      else                                                                                      \
+        hipLaunchKernelGGL((gemm_big_kernel<A_KC, B_KC, E, TN>), grid, block, 0, s, g);         \
       break;                                                                                    \
     } else {                                                                                    \
       return hipErrorInvalidValue;                                                              \
@@ -695,10 +972,6 @@ static bool fits_32bit_offsets(int64_t rows, int64_t ld) {
 // Number of 256 x 256 tiles from which the large-problem kernel is used (half the CUs by default);
 // AXONN_GEMM_BIG_MIN_TILES overrides it, AXONN_GEMM_TILE_N (160, 192 or 256) fixes the block width: both
 // for tuning.
-static int64_t env_int(const char* name, int64_t dflt) {
-  const char* e = getenv(name);
-  return e && *e ? (int64_t)atoll(e) : dflt;
-}
 static int64_t big_tile_threshold() {
   static const int64_t v = env_int("AXONN_GEMM_BIG_MIN_TILES", 128);
   return v;

@@ -4,6 +4,8 @@ Tolerances (relative Frobenius, derived from the arithmetic): every output is on
 rounding (2^-9 relative per element, ~2.3e-3 worst case, ~1.1e-3 rms) of an fp32-accumulated
 value; fused epilogues add one more rounding of an intermediate.  5e-3 bounds single-op
 outputs with margin and is 4x tighter than the stage-level forward bound (2e-2)."""
+import itertools
+
 import numpy as np
 import pytest
 
@@ -35,6 +37,12 @@ GEMM_SHAPES = [
     (2056, 4512, 264),
     (2056, 5464, 264),
     (4096, 2048, 448),   # big-tile kernel: odd number of k-tiles, no tail
+    # whole k-tiles (the kernel that copies tiles without staging registers), ragged rows and columns,
+    # block widths 160, 192 and 256
+    (2056, 4104, 320),
+    (2056, 4512, 320),
+    (2056, 5464, 320),
+    (4096, 4096, 64),    # a single k-tile: the second stage holds a tile of zeros
 ]
 
 
@@ -101,8 +109,9 @@ def test_gemm_big_tile_strided_operands():
     beyond K in a row of a k-contiguous operand must not enter the sum."""
     import torch
     rng = np.random.default_rng(6)
-    M, N, K = 2048, 4096, 200
-    for a_kc, b_kc, epi in ((1, 0, B.EPI_BIAS), (1, 1, B.EPI_BIAS), (0, 0, B.EPI_ACC_BF16)):
+    for (M, N, K), (a_kc, b_kc, epi) in itertools.product(
+            ((2048, 4096, 200), (2048, 4096, 192)),
+            ((1, 0, B.EPI_BIAS), (1, 1, B.EPI_BIAS), (0, 0, B.EPI_ACC_BF16))):
         ash, bsh = ((M, K) if a_kc else (K, M)), ((N, K) if b_kc else (K, N))
         lda, ldb, ldc = ash[1] + 72, bsh[1] + 136, N + 8
         abuf = _rng_bf16(rng, (ash[0], lda)); bbuf = _rng_bf16(rng, (bsh[0], ldb), 0.05)
@@ -112,6 +121,21 @@ def test_gemm_big_tile_strided_operands():
         B.axonn_gemm_bf16(a_kc, b_kc, epi, M, N, K, dev_bf16(abuf), lda, dev_bf16(bbuf), ldb, out, ldc)
         assert rel_fro(host(out)[:, :N], ref) < TOL, (a_kc, b_kc)
         assert not host(out)[:, N:].any()
+
+
+def test_gemm_copy_kernel_all_layouts_and_results():
+    """The large-problem kernel whose tiles are copied by the memory pipeline is the default for one
+    (layout, result type) pair only; AXONN_GEMM_DMA=15 selects it wherever it applies.  The variable is read
+    once per process, so the GEMM cases of this file run again in a child process with it set."""
+    import os
+    import subprocess
+    import sys
+    env = dict(os.environ, AXONN_GEMM_DMA="15")
+    r = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-x", "-q", "-p", "no:cacheprovider",
+                        "-k", "gemm and not copy_kernel"], env=env, capture_output=True, text=True, timeout=600,
+                       cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-2000:]
+    assert " passed" in r.stdout and "failed" not in r.stdout
 
 
 def test_gemm_strided_operands_and_run_to_run_determinism():
