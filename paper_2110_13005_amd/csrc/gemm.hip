@@ -8,7 +8,8 @@
 //   dgrad    dx = dy W^T     : A k-contiguous, B k-contiguous
 //   wgrad    dW = x^T dy     : A k-strided,    B k-strided
 // A block computes a BM x BN tile with WGM x WGN waves; tiles of A and B stream through a
-// double-buffered LDS stage (global -> registers -> LDS, one barrier per k-step).  k-contiguous
+// double-buffered LDS stage (global -> registers -> LDS, or global -> LDS by the memory pipeline in
+// gemm_dma_kernel; one barrier per k-step).  k-contiguous
 // tiles are read back with 128-bit LDS loads, k-strided tiles with the transposing LDS load,
 // so no operand is ever transposed in HBM.  The MFMA is issued with the B fragment first, so a
 // lane of the result owns one row m and runs of 4 consecutive columns n: epilogue loads and
