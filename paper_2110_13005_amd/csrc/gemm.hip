@@ -932,13 +932,22 @@ static hipError_t launch_big(int epi, GemmArgs g, hipStream_t s) {
   g.tiles_m = (g.M + 255) / 256;
   g.tiles_n = (g.N + 32 * TN - 1) / (32 * TN);
   const dim3 grid(g.tiles_m * g.tiles_n), block(256);
-  // the kernel with copies by the memory pipeline needs whole k tiles
-  // and pays where the operands come mostly from the L2: the weight gradients with a bf16 result.  Its copies
-  // have less time to arrive than the chunks of the register-staged kernel, and where more of them come
-  // from HBM (long K with few tiles per operand strip; the read-modify-write of an fp32 result in the
-  // background) it is the slower one.  AXONN_GEMM_DMA overrides the choice, for tuning: bit 0 (kc,kc),
-  // bit 1 (kc,ks), bit 2 (ks,ks) with a bf16 result, bit 3 (ks,ks) with an fp32 result.
-  static const int64_t dma_mask = env_int("AXONN_GEMM_DMA", 4);
+  // The kernel with copies by the memory pipeline needs whole k tiles.  Alone on the chip it pays where the
+  // operands come mostly from the L2, the weight gradients with a bf16 result; its copies have less time to
+  // arrive than the chunks of the register-staged kernel, and where more of them come from HBM (long K with few
+  // tiles per operand strip; the read-modify-write of an fp32 result in the background) it is the slower one.
+  // When other kernels share the chip, throughput is bound by the chip's power limit and the kernel that
+  // draws less per k-step wins for the other layouts too, if the launch fills the chip at least once and K
+  // is not long (measured on whole batches of the stage: +2 % on the 24B shape, +1 % on the 100B shape, a
+  // tie on the 12B shape; with K = 18048 in it, -1.4 % on the h = 4512 shape).
+  // For tuning: AXONN_GEMM_DMA fixes the choice per class (bit 0 (kc,kc), bit 1 (kc,ks), bit 2 (ks,ks) with a
+  // bf16 result, bit 3 (ks,ks) with an fp32 result); AXONN_GEMM_DMA_MIN_TILES and AXONN_GEMM_DMA_MAX_K move
+  // the two bounds.
+  static const int64_t dma_mask_env = env_int("AXONN_GEMM_DMA", -1);
+  static const int64_t dma_min_tiles = env_int("AXONN_GEMM_DMA_MIN_TILES", 256);
+  static const int64_t dma_max_k = env_int("AXONN_GEMM_DMA_MAX_K", 16384);
+  const bool shared_chip_case = g.concurrent && (int64_t)g.tiles_m * g.tiles_n >= dma_min_tiles && g.K <= dma_max_k;
+  const int64_t dma_mask = dma_mask_env >= 0 ? dma_mask_env : (shared_chip_case ? 7 : 4);
   const int dma_bit = A_KC ? (B_KC ? 0 : 1) : (epi == EPI_ACC_F32 ? 3 : 2);
   const bool use_dma = ((dma_mask >> dma_bit) & 1) && g.K % 64 == 0;
 #define AXONN_GEMM_CASE(E)                                                                      \
