@@ -120,7 +120,7 @@ def main():
             for o in range(0, numel, step):
                 c = min(step, numel - o)
                 w = torch.randn(c, generator=g, device=dev, dtype=torch.float32) * 0.02
-                st.params[off + o: off + o + c] = w.to(torch.bfloat16)
+                st.params[off + o: off + o + c] = w.to(B.torch_elem_dtype())
                 if host_arrs:
                     host_arrs[0][off + o: off + o + c] = w.cpu()
         elif host_arrs:
@@ -134,11 +134,11 @@ def main():
             host_arrs[2][o:o + c] = (torch.randn(c, generator=g, device=dev) * 1e-6).abs().cpu()
         B.axonn_stage_optimizer_attach(st.handle, host_ptrs[0], host_ptrs[1], host_ptrs[2], n, args.bucket_elems)
     bsh = (sh.microbatch_size, sh.seq_len, sh.hidden)
-    X = [torch.randn(bsh, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(M)]
+    X = [torch.randn(bsh, generator=g, device=dev, dtype=torch.float32).to(B.torch_elem_dtype()) for _ in range(M)]
     # upstream gradients ~N(0,1), as a neighbouring stage would send them (any 1/M lives in grad_scale)
-    DY = [torch.randn(bsh, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16) for _ in range(M)]
-    Y = [torch.empty(bsh, device=dev, dtype=torch.bfloat16) for _ in range(M)]
-    DX = [torch.empty(bsh, device=dev, dtype=torch.bfloat16) for _ in range(M)]
+    DY = [torch.randn(bsh, generator=g, device=dev, dtype=torch.float32).to(B.torch_elem_dtype()) for _ in range(M)]
+    Y = [torch.empty(bsh, device=dev, dtype=B.torch_elem_dtype()) for _ in range(M)]
+    DX = [torch.empty(bsh, device=dev, dtype=B.torch_elem_dtype()) for _ in range(M)]
     VOCAB = 51200
     embed = head = None
     if args.ends:
@@ -151,7 +151,7 @@ def main():
             lo = 2 * sh.hidden if handle is head else 0          # the final LayerNorm keeps gain 1, shift 0
             for o in range(lo, nn, 1 << 26):
                 c = min(1 << 26, nn - o)
-                v[o:o + c] = (torch.randn(c, generator=g, device=dev, dtype=torch.float32) * 0.02).to(torch.bfloat16)
+                v[o:o + c] = (torch.randn(c, generator=g, device=dev, dtype=torch.float32) * 0.02).to(B.torch_elem_dtype())
             del v
         B.axonn_stage_attach_ends(st.handle, embed, head)
         TOK = [torch.randint(0, VOCAB, (sh.microbatch_size, sh.seq_len), generator=g, device=dev, dtype=torch.int32) for _ in range(M)]

@@ -238,6 +238,59 @@ int axonn_stage_optimizer_step_overlapped(axonn_stage_t* st, double lr, double b
                                           int32_t chunk_buckets, void* hip_stream);
 
 /* ------------------------------------------------------------------------------------
+ * Element type and loss scaling (Sec. 2, "Mixed precision": forward and backward run in half
+ * precision; to keep small gradients from underflowing, the loss is multiplied by a scaling
+ * factor, and the optimizer converts the half precision gradients to full precision and
+ * descales them).  The library is built twice from the same sources: libaxonn_stage.so
+ * computes with bfloat16 as its 16-bit element type, libaxonn_stage_fp16.so with IEEE half
+ * precision (the paper's arithmetic).  Every "bf16" in the names and comments of this
+ * header means "the 16-bit element type of the library at hand".  bfloat16 has fp32's range
+ * and needs no loss scale; with half precision the scale matters.  The paper does not say how
+ * the factor is chosen; the scaler here is the usual dynamic one (Micikevicius et al. 2018,
+ * Sec. 3.2): a batch whose gradients contain an infinity or a NaN is dropped and the scale
+ * multiplied by `backoff`; after `growth_interval` good batches in a row it is multiplied
+ * by `growth`.
+ * ---------------------------------------------------------------------------------- */
+
+/* 0: bfloat16, 1: IEEE half precision. */
+int32_t axonn_element_type(void);
+
+typedef struct axonn_loss_scaler {
+  float scale;              /* current loss scale S > 0 (the caller's initial value)       */
+  float growth;             /* >= 1, e.g. 2                                                 */
+  float backoff;            /* in (0, 1], e.g. 0.5                                          */
+  int32_t growth_interval;  /* good batches in a row before the scale grows, >= 1           */
+  int32_t good_steps;       /* good batches since the last change of the scale (state)      */
+} axonn_loss_scaler;
+
+/* Number of elements of x_dev[0..n) (device, 16-bit elements) that are infinite or NaN.
+ * workspace_dev: 1025 64-bit counters of device memory, all overwritten; the count is left
+ * in workspace_dev[1024].  Enqueued on hip_stream; no atomics, same result every run. */
+int axonn_count_nonfinite(const void* x_dev, uint64_t n, uint64_t* workspace_dev,
+                          void* hip_stream);
+
+/* The same over the stage's gradient buffer, after the batch's gradients are final (the
+ * ordering and state rules of axonn_stage_optimizer_step); *count_host (host) is valid on
+ * return: the call synchronizes hip_stream. */
+int axonn_stage_count_nonfinite_grads(axonn_stage_t* st, void* hip_stream,
+                                      uint64_t* count_host);
+
+/* Optimizer step under a dynamic loss scale.  The gradients of the batch were computed from a
+ * loss multiplied by scaler->scale (the upstream gradients that reached this stage carried
+ * it; a last stage sets it with axonn_head_set_loss_scale).  If the stage's gradients, or
+ * those the caller checked elsewhere (other_nonfinite: the sum of the counts of the other
+ * buffers that take part in the decision, 0 if none), contain a non-finite value: nothing
+ * is updated, scaler->scale *= backoff, good_steps = 0, *skipped = 1.  Otherwise
+ * axonn_stage_optimizer_step runs with grad_scale / scaler->scale, *skipped = 0, and after
+ * growth_interval such steps in a row scaler->scale *= growth.  Synchronizes hip_stream once
+ * (the decision is taken on the host).  AXONN_EINVAL for a scaler outside the ranges above. */
+int axonn_stage_optimizer_step_scaled(axonn_stage_t* st, double lr, double beta1, double beta2,
+                                      double eps, double weight_decay, int64_t step,
+                                      double grad_scale, axonn_loss_scaler* scaler,
+                                      uint64_t other_nonfinite, void* hip_stream,
+                                      int32_t* skipped);
+
+/* ------------------------------------------------------------------------------------
  * The two ends of the pipeline (the special cases of Alg. 2).  The first stage (i = 0)
  * turns a microbatch of token ids into activations: x[b,i,:] = wte[token[b,i],:] + wpe[i,:].
  * The last stage (i = G_inter - 1) applies a final LayerNorm and the LM head, computes the
@@ -286,6 +339,11 @@ int axonn_head_zero_grad(axonn_head_t* hd);
 int axonn_head_forward_backward(axonn_head_t* hd, const void* x_dev_bf16,
                                 const int32_t* targets_dev, float* loss_dev,
                                 void* dx_dev_bf16, void* hip_stream);
+
+/* Loss scale S of the last stage (default 1): dloss/dlogits, and with it every gradient of
+ * the backward pass, is multiplied by S; the loss written to loss_dev is not.  Positive and
+ * finite, else AXONN_EINVAL.  Takes effect from the next axonn_head_forward_backward. */
+int axonn_head_set_loss_scale(axonn_head_t* head, float loss_scale);
 /* Makes a stage the first and / or the last one of the pipeline (either handle may be NULL;
  * the handles stay the caller's).  In message-driven mode a forward message to a first
  * stage then carries int32 token ids [b,s] as payload (the buffer must stay valid until the

@@ -27,4 +27,5 @@ from .transformer import (  # noqa: F401
     causal_attention_bwd, layer_forward, layer_backward, stage_forward,
     stage_backward, stage_batch, PARAM_NAMES,
 )
-from .adam import adam_step, bf16_round  # noqa: F401
+from .adam import (adam_step, bf16_round, fp16_round, half_round, loss_scaled_adam_step,  # noqa: F401
+                   nonfinite_count)

@@ -1,4 +1,5 @@
-"""Plain float64 Adam step with decoupled weight decay, and bf16 rounding.
+"""Plain float64 Adam step with decoupled weight decay, rounding to the two 16-bit formats, and the
+dynamic loss scaler.
 
 Test infrastructure only (see package docstring).
 
@@ -10,6 +11,12 @@ update itself is Kingma & Ba's Adam with bias correction, epsilon added to the r
 the corrected second moment, and Loshchilov & Hutter's decoupled decay applied to the
 pre-update theta (the paper names Adam/AdamW and its hyper-parameters in Sec. 6.1 and
 prints no formula).
+
+Loss scale (same section): the loss is multiplied by a scaling factor S so that small half-precision
+gradients do not underflow; the optimizer descales.  The paper does not say how S is chosen.  Reading
+taken here, the usual dynamic scheme (Micikevicius et al. 2018, Sec. 3.2): if any gradient value of a batch
+is infinite or NaN, the batch is dropped (no state changes) and S is multiplied by `backoff`; after
+`growth_interval` batches in a row without such a value S is multiplied by `growth`.
 """
 import numpy as np
 
@@ -26,12 +33,23 @@ def bf16_round(x):
     return np.where(np.isnan(f), f, out).reshape(np.shape(x))
 
 
-def adam_step(theta, m, v, g16, lr, beta1, beta2, eps, weight_decay, step, grad_scale):
+def fp16_round(x):
+    """Round float values to the nearest IEEE half precision value (ties to even, overflow to infinity beyond
+    65504 + half a step, gradual underflow below 2^-14); returns float32.  numpy's own conversion."""
+    with np.errstate(over="ignore"):
+        return np.asarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
+def half_round(x, half="bf16"):
+    return fp16_round(x) if half == "fp16" else bf16_round(x)
+
+
+def adam_step(theta, m, v, g16, lr, beta1, beta2, eps, weight_decay, step, grad_scale, half="bf16"):
     """One Adam step on arrays of any shape.
 
     theta, m, v: fp32 master state (values used exactly, arithmetic in float64).
-    g16: the half-precision gradient values.  step: t >= 1.
-    Returns (theta', m', v') in float64 and theta16' = bf16(fp32(theta')) as float32."""
+    g16: the half-precision gradient values.  step: t >= 1.  half: the 16-bit format, "bf16" or "fp16".
+    Returns (theta', m', v') in float64 and theta16' = half(fp32(theta')) as float32."""
     theta = np.asarray(theta, np.float64)
     m = np.asarray(m, np.float64)
     v = np.asarray(v, np.float64)
@@ -41,4 +59,29 @@ def adam_step(theta, m, v, g16, lr, beta1, beta2, eps, weight_decay, step, grad_
     mhat = m1 / (1.0 - np.float64(beta1) ** step)
     vhat = v1 / (1.0 - np.float64(beta2) ** step)
     theta1 = theta - lr * (mhat / (np.sqrt(vhat) + eps) + weight_decay * theta)
-    return theta1, m1, v1, bf16_round(theta1.astype(np.float32))
+    return theta1, m1, v1, half_round(theta1.astype(np.float32), half)
+
+
+def nonfinite_count(g):
+    """Number of infinite or NaN values in g."""
+    return int(np.count_nonzero(~np.isfinite(np.asarray(g, np.float64))))
+
+
+def loss_scaled_adam_step(scaler, theta, m, v, g16, lr, beta1, beta2, eps, weight_decay, step, grad_scale,
+                          other_nonfinite=0, half="bf16"):
+    """One optimizer step under the dynamic loss scale.
+
+    scaler: dict with scale, growth, backoff, growth_interval, good_steps; g16: the gradients of a loss that was
+    multiplied by scaler["scale"].  Returns (scaler', theta', m', v', theta16' or None, skipped)."""
+    sc = dict(scaler)
+    if nonfinite_count(g16) + int(other_nonfinite) != 0:
+        sc["scale"] = sc["scale"] * sc["backoff"]
+        sc["good_steps"] = 0
+        return sc, np.asarray(theta, np.float64), np.asarray(m, np.float64), np.asarray(v, np.float64), None, True
+    t1, m1, v1, t16 = adam_step(theta, m, v, g16, lr, beta1, beta2, eps, weight_decay, step,
+                                grad_scale / sc["scale"], half)
+    sc["good_steps"] += 1
+    if sc["good_steps"] >= sc["growth_interval"]:
+        sc["scale"] = sc["scale"] * sc["growth"]
+        sc["good_steps"] = 0
+    return sc, t1, m1, v1, t16, False

@@ -11,7 +11,18 @@ import ctypes as C
 import os
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libaxonn_stage.so")
+# The library exists in two builds of the same sources: bfloat16 (default) or IEEE half precision as the
+# 16-bit element type.  A process uses one of them, chosen by AXONN_ELEM before this module is imported.
+ELEM = os.environ.get("AXONN_ELEM", "bf16")
+if ELEM not in ("bf16", "fp16"):
+    raise ValueError("AXONN_ELEM must be bf16 or fp16, not %r" % ELEM)
+LIB_PATH = os.path.join(_HERE, "libaxonn_stage.so" if ELEM == "bf16" else "libaxonn_stage_fp16.so")
+
+
+def torch_elem_dtype():
+    """torch dtype of the library's 16-bit element type."""
+    import torch
+    return torch.bfloat16 if ELEM == "bf16" else torch.float16
 
 AXONN_OK, AXONN_EINVAL, AXONN_ESTATE, AXONN_ENOMEM, AXONN_EHIP, AXONN_EUNSUPPORTED = 0, -1, -2, -3, -4, -5
 EPI_BIAS, EPI_BIAS_RES, EPI_BIAS_GELU, EPI_DGELU, EPI_ACC_F32, EPI_ACC_BF16 = range(6)
@@ -29,6 +40,11 @@ class axonn_stage_config(C.Structure):
                 ("n_microbatches", C.c_int32), ("pipeline_limit", C.c_int32), ("ln_eps", C.c_float),
                 ("device", C.c_int32), ("grad_accum_fp32", C.c_int32), ("wgrad_group", C.c_int32),
                 ("qkv_input_split", C.c_int32), ("ckpt_stride", C.c_int32)]
+
+
+class axonn_loss_scaler(C.Structure):
+    _fields_ = [("scale", C.c_float), ("growth", C.c_float), ("backoff", C.c_float),
+                ("growth_interval", C.c_int32), ("good_steps", C.c_int32)]
 
 
 class axonn_msg(C.Structure):
@@ -77,6 +93,11 @@ _PROTOTYPES = {
     "axonn_stage_optimizer_attach": [_vp, _vp, _vp, _vp, _u64, _u64],
     "axonn_stage_optimizer_step": [_vp, _d, _d, _d, _d, _d, _i64, _d, _vp],
     "axonn_stage_optimizer_step_overlapped": [_vp, _d, _d, _d, _d, _d, _i64, _d, _i32, _vp],
+    "axonn_count_nonfinite": [_vp, _u64, _vp, _vp],
+    "axonn_stage_count_nonfinite_grads": [_vp, _vp, C.POINTER(_u64)],
+    "axonn_stage_optimizer_step_scaled": [_vp, _d, _d, _d, _d, _d, _i64, _d, C.POINTER(axonn_loss_scaler), _u64, _vp,
+                                          C.POINTER(_i32)],
+    "axonn_head_set_loss_scale": [_vp, _f],
     "axonn_gemm_bf16": [_i32, _i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64,
                         _vp, _i64, _i32, _vp],
     "axonn_layernorm_fwd": [_i64, _i64, _vp, _vp, _vp, _f, _vp, _vp, _vp],
@@ -90,7 +111,7 @@ _PROTOTYPES = {
     "axonn_profile_collect": [C.POINTER(C.c_double), C.POINTER(_i64), _i32],
     "axonn_adam_bucket": [_u64, _vp, _vp, _vp, _vp, _vp, _d, _d, _d, _d, _d, _i64, _d, _vp],
 }
-EXPORTED_SYMBOLS = ["axonn_last_error"] + sorted(_PROTOTYPES)
+EXPORTED_SYMBOLS = ["axonn_last_error", "axonn_element_type"] + sorted(_PROTOTYPES)
 
 _lib = None
 
@@ -112,6 +133,12 @@ def load():
             fn = getattr(lib, name)
             fn.restype = C.c_int
             fn.argtypes = args
+        lib.axonn_element_type.restype = C.c_int32
+        lib.axonn_element_type.argtypes = []
+        want = 0 if ELEM == "bf16" else 1
+        if lib.axonn_element_type() != want:
+            raise ImportError("%s was built for element type %d, AXONN_ELEM=%s needs %d: rebuild"
+                              % (LIB_PATH, lib.axonn_element_type(), ELEM, want))
         _lib = lib
     return _lib
 
@@ -348,6 +375,34 @@ def axonn_stage_optimizer_step_overlapped(st, lr, beta1, beta2, eps, weight_deca
                                           stream=None):
     _check(load().axonn_stage_optimizer_step_overlapped(st, lr, beta1, beta2, eps, weight_decay, step, grad_scale,
                                                         chunk_buckets, _stream(stream)))
+
+
+def axonn_element_type():
+    return load().axonn_element_type()
+
+
+def axonn_count_nonfinite(x, n, workspace, stream=None):
+    _check(load().axonn_count_nonfinite(_ptr(x), n, _ptr(workspace), _stream(stream)))
+
+
+def axonn_stage_count_nonfinite_grads(st, stream=None):
+    out = _u64()
+    _check(load().axonn_stage_count_nonfinite_grads(st, _stream(stream), C.byref(out)))
+    return out.value
+
+
+def axonn_stage_optimizer_step_scaled(st, lr, beta1, beta2, eps, weight_decay, step, grad_scale, scaler,
+                                      other_nonfinite=0, stream=None):
+    """scaler: an axonn_loss_scaler, updated in place.  Returns True if the step was skipped."""
+    skipped = _i32()
+    _check(load().axonn_stage_optimizer_step_scaled(st, lr, beta1, beta2, eps, weight_decay, step, grad_scale,
+                                                    C.byref(scaler), other_nonfinite, _stream(stream),
+                                                    C.byref(skipped)))
+    return bool(skipped.value)
+
+
+def axonn_head_set_loss_scale(head, loss_scale):
+    _check(load().axonn_head_set_loss_scale(head, loss_scale))
 
 
 def axonn_gemm_bf16(a_kcontig, b_kcontig, epilogue, M, N, K, A, lda, B, ldb, Cmat, ldc, bias=None, res=None,

@@ -26,7 +26,7 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // padded columns of V give output columns nobody stores.  Heads then start at multiples of 8 bytes only, so
 // the 8 elements at columns [col, col + 8) of a head row are fetched as two 8-byte halves.
 template <bool EXACT>
-__device__ __forceinline__ uint4 load_cols8(const bf16_t* p, int col, int d) {
+__device__ __forceinline__ uint4 load_cols8(const elem_t* p, int col, int d) {
   if (EXACT) return *reinterpret_cast<const uint4*>(p);
   uint4 v = make_uint4(0, 0, 0, 0);
   if (col + 4 <= d) {
@@ -47,7 +47,7 @@ struct TileRegs {
   static constexpr int NCH = ROWS * D / 8 / 256;
   uint4 r[NCH];
   template <bool EXACT>
-  __device__ __forceinline__ void load(const bf16_t* base, int64_t ld, int row0, int n_rows, int d, int tid) {
+  __device__ __forceinline__ void load(const elem_t* base, int64_t ld, int row0, int n_rows, int d, int tid) {
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
       const int c = tid + j * 256;
@@ -58,7 +58,7 @@ struct TileRegs {
     }
   }
   template <int LD>
-  __device__ __forceinline__ void store(bf16_t* lds, int tid) const {
+  __device__ __forceinline__ void store(elem_t* lds, int tid) const {
 #pragma unroll
     for (int j = 0; j < NCH; ++j) {
       const int c = tid + j * 256;
@@ -67,22 +67,22 @@ struct TileRegs {
   }
 };
 
-__device__ __forceinline__ bf16x8 pack8(const floatx16& t, int first) {
-  bf16x8 o;
+__device__ __forceinline__ elemx8 pack8(const floatx16& t, int first) {
+  elemx8 o;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) o[e] = (bf16_t)t[first + e];
+  for (int e = 0; e < 8; ++e) o[e] = (elem_t)t[first + e];
   return o;
 }
 
 // Row fragment straight from global memory: lane holds row (row0 + lane%32), elements
 // [k0 + 8*(lane/32), +8) -- the MFMA operand layout.  Rows >= n_rows read as zero.
 template <bool EXACT>
-__device__ __forceinline__ bf16x8 global_frag(const bf16_t* base, int64_t ld, int row, int n_rows,
+__device__ __forceinline__ elemx8 global_frag(const elem_t* base, int64_t ld, int row, int n_rows,
                                               int k0, int lane, int d) {
   uint4 v = make_uint4(0, 0, 0, 0);
   const int col = k0 + 8 * (lane >> 5);
   if (row < n_rows) v = load_cols8<EXACT>(base + (int64_t)row * ld + col, col, d);
-  return __builtin_bit_cast(bf16x8, v);
+  return __builtin_bit_cast(elemx8, v);
 }
 
 // Work assignment of the attention kernels: block id of a 1-D grid of n_tiles * n_bh blocks -> (rank of
@@ -106,12 +106,12 @@ __device__ __forceinline__ void attn_block(int n_bh, int& rank, int& bh) {
 // grid: (ceil(s/128), b*a); 4 waves; wave w owns queries q0 + 32w .. +31.
 template <int D, bool EXACT>
 __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, int a, int n_bh, int d_arg,
-                                                       const bf16_t* __restrict__ qkv,
-                                                       bf16_t* __restrict__ o,
+                                                       const elem_t* __restrict__ qkv,
+                                                       elem_t* __restrict__ o,
                                                        float* __restrict__ lse) {
   constexpr int BKV = 64, LDK = D + 8, LDV = D + 32, DT = D / 32, KK = D / 16;
-  __shared__ __align__(16) bf16_t sK[BKV * LDK];
-  __shared__ __align__(16) bf16_t sV[BKV * LDV];
+  __shared__ __align__(16) elem_t sK[BKV * LDK];
+  __shared__ __align__(16) elem_t sV[BKV * LDV];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
   int rank, bh;
   attn_block(n_bh, rank, bh);
@@ -120,13 +120,13 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
   const int d = EXACT ? D : d_arg;
   const int h = a * d;
   const int64_t ld = 3 * (int64_t)h;
-  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * d;
-  const bf16_t* kb = qb + h;
-  const bf16_t* vb = qb + 2 * h;
+  const elem_t* qb = qkv + (int64_t)bi * s * ld + hd * d;
+  const elem_t* kb = qb + h;
+  const elem_t* vb = qb + 2 * h;
   const int q0 = qt * 128, qw0 = q0 + 32 * wave, qi = qw0 + (lane & 31);
   const float scale_log2 = kLog2e * rsqrtf((float)d);
 
-  bf16x8 qf[KK];
+  elemx8 qf[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) qf[kk] = global_frag<EXACT>(qb, ld, qi, s, kk * 16, lane, d);
 
@@ -199,7 +199,7 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        const bf16x8 pf = pack8(sacc[ks], 8 * c);
+        const elemx8 pf = pack8(sacc[ks], 8 * c);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
           oacc[dt] = mfma32(frag_kstrided<true>(sV + (32 * ks + 16 * c) * LDV + dt * 32, LDV, lane),
@@ -209,15 +209,15 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
   if (qi < s) {
     const float inv = 1.f / l_tot;
-    bf16_t* orow = o + ((int64_t)bi * s + qi) * h + hd * d;
+    elem_t* orow = o + ((int64_t)bi * s + qi) * h + hd * d;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        bf16x4 v;
+        elemx4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(oacc[dt][4 * q + e] * inv);
-        if (EXACT || dt * 32 + 8 * q + 4 * g < d) *reinterpret_cast<bf16x4*>(orow + dt * 32 + 8 * q + 4 * g) = v;
+        for (int e = 0; e < 4; ++e) v[e] = (elem_t)(oacc[dt][4 * q + e] * inv);
+        if (EXACT || dt * 32 + 8 * q + 4 * g < d) *reinterpret_cast<elemx4*>(orow + dt * 32 + 8 * q + 4 * g) = v;
       }
     if (g == 0) lse[((int64_t)bi * a + hd) * s + qi] = (m_run + __log2f(l_tot)) * kLn2;
   }
@@ -227,15 +227,15 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
 // delta[b][a][i] = sum_d dO[i][d] * O[i][d]
 template <int D>
 __global__ __launch_bounds__(256) void attn_delta_kernel(int64_t n_chunks, int s, int a,
-                                                         const bf16_t* __restrict__ o,
-                                                         const bf16_t* __restrict__ dout,
+                                                         const elem_t* __restrict__ o,
+                                                         const elem_t* __restrict__ dout,
                                                          float* __restrict__ delta) {
   constexpr int LPR = D / 8;  // lanes per (row, head)
   const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
   float p = 0.f;
   if (c < n_chunks) {
-    const bf16x8 ov = *reinterpret_cast<const bf16x8*>(o + c * 8);
-    const bf16x8 dv = *reinterpret_cast<const bf16x8*>(dout + c * 8);
+    const elemx8 ov = *reinterpret_cast<const elemx8*>(o + c * 8);
+    const elemx8 dv = *reinterpret_cast<const elemx8*>(dout + c * 8);
 #pragma unroll
     for (int e = 0; e < 8; ++e) p += (float)ov[e] * (float)dv[e];
   }
@@ -253,18 +253,18 @@ __global__ __launch_bounds__(256) void attn_delta_kernel(int64_t n_chunks, int s
 // The same for any head dimension d that is a multiple of 4: 16 lanes per (row, head), 4 elements per lane
 // and step.
 __global__ __launch_bounds__(256) void attn_delta_general_kernel(int64_t n_pairs, int s, int a, int d,
-                                                                 const bf16_t* __restrict__ o,
-                                                                 const bf16_t* __restrict__ dout,
+                                                                 const elem_t* __restrict__ o,
+                                                                 const elem_t* __restrict__ dout,
                                                                  float* __restrict__ delta) {
   const int64_t pair = (int64_t)blockIdx.x * 16 + (threadIdx.x >> 4);   // (row, head)
   const int j = threadIdx.x & 15;
   float p = 0.f;
   if (pair < n_pairs) {
-    const bf16_t* op = o + pair * d;          // rows are a * d long: pair * d = row * a * d + head * d
-    const bf16_t* dp = dout + pair * d;
+    const elem_t* op = o + pair * d;          // rows are a * d long: pair * d = row * a * d + head * d
+    const elem_t* dp = dout + pair * d;
     for (int c = 4 * j; c < d; c += 64) {
-      const bf16x4 ov = *reinterpret_cast<const bf16x4*>(op + c);
-      const bf16x4 dv = *reinterpret_cast<const bf16x4*>(dp + c);
+      const elemx4 ov = *reinterpret_cast<const elemx4*>(op + c);
+      const elemx4 dv = *reinterpret_cast<const elemx4*>(dp + c);
 #pragma unroll
       for (int e = 0; e < 4; ++e) p += (float)ov[e] * (float)dv[e];
     }
@@ -283,11 +283,11 @@ __global__ __launch_bounds__(256) void attn_delta_general_kernel(int64_t n_pairs
 // at or below the diagonal.
 template <int D, bool EXACT>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
-    int s, int a, int n_bh, int d_arg, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
-    const float* __restrict__ lse, const float* __restrict__ delta, bf16_t* __restrict__ dqkv) {
+    int s, int a, int n_bh, int d_arg, const elem_t* __restrict__ qkv, const elem_t* __restrict__ dout,
+    const float* __restrict__ lse, const float* __restrict__ delta, elem_t* __restrict__ dqkv) {
   constexpr int BQ = 64, LDQ = D + 8, DT = D / 32, KK = D / 16;
-  __shared__ __align__(16) bf16_t sQ[BQ * LDQ];
-  __shared__ __align__(16) bf16_t sdO[BQ * LDQ];
+  __shared__ __align__(16) elem_t sQ[BQ * LDQ];
+  __shared__ __align__(16) elem_t sdO[BQ * LDQ];
   __shared__ __align__(16) float s_lse[BQ];
   __shared__ __align__(16) float s_delta[BQ];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
@@ -297,16 +297,16 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
   const int d = EXACT ? D : d_arg;
   const int h = a * d;
   const int64_t ld = 3 * (int64_t)h;
-  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * d;
-  const bf16_t* kb = qb + h;
-  const bf16_t* vb = qb + 2 * h;
-  const bf16_t* dob = dout + (int64_t)bi * s * h + hd * d;
+  const elem_t* qb = qkv + (int64_t)bi * s * ld + hd * d;
+  const elem_t* kb = qb + h;
+  const elem_t* vb = qb + 2 * h;
+  const elem_t* dob = dout + (int64_t)bi * s * h + hd * d;
   const float* lse_b = lse + ((int64_t)bi * a + hd) * s;
   const float* delta_b = delta + ((int64_t)bi * a + hd) * s;
   const int k0 = rank * 128, kw0 = k0 + 32 * wave, kj = kw0 + (lane & 31);
   const float scale = rsqrtf((float)d), scale_log2 = kLog2e * scale;
 
-  bf16x8 kf[KK], vf[KK];
+  elemx8 kf[KK], vf[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
     kf[kk] = global_frag<EXACT>(kb, ld, kj, s, kk * 16, lane, d);
@@ -371,8 +371,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
       }
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        const bf16x8 pf = pack8(sacc, 8 * c);
-        const bf16x8 dsf = pack8(pacc, 8 * c);
+        const elemx8 pf = pack8(sacc, 8 * c);
+        const elemx8 dsf = pack8(pacc, 8 * c);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
           dvacc[dt] = mfma32(frag_kstrided<true>(sdO + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane),
@@ -384,21 +384,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
     }
   }
   if (kj < s) {
-    bf16_t* dk_row = dqkv + ((int64_t)bi * s + kj) * ld + h + hd * d;
-    bf16_t* dv_row = dk_row + h;
+    elem_t* dk_row = dqkv + ((int64_t)bi * s + kj) * ld + h + hd * d;
+    elem_t* dv_row = dk_row + h;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        bf16x4 kv4, vv4;
+        elemx4 kv4, vv4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          kv4[e] = (bf16_t)(dkacc[dt][4 * q + e] * scale);
-          vv4[e] = (bf16_t)dvacc[dt][4 * q + e];
+          kv4[e] = (elem_t)(dkacc[dt][4 * q + e] * scale);
+          vv4[e] = (elem_t)dvacc[dt][4 * q + e];
         }
         if (EXACT || dt * 32 + 8 * q + 4 * g < d) {
-          *reinterpret_cast<bf16x4*>(dk_row + dt * 32 + 8 * q + 4 * g) = kv4;
-          *reinterpret_cast<bf16x4*>(dv_row + dt * 32 + 8 * q + 4 * g) = vv4;
+          *reinterpret_cast<elemx4*>(dk_row + dt * 32 + 8 * q + 4 * g) = kv4;
+          *reinterpret_cast<elemx4*>(dv_row + dt * 32 + 8 * q + 4 * g) = vv4;
         }
       }
   }
@@ -408,11 +408,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
 // to the diagonal (same traversal as the forward kernel).
 template <int D, bool EXACT>
 __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
-    int s, int a, int n_bh, int d_arg, const bf16_t* __restrict__ qkv, const bf16_t* __restrict__ dout,
-    const float* __restrict__ lse, const float* __restrict__ delta, bf16_t* __restrict__ dqkv) {
+    int s, int a, int n_bh, int d_arg, const elem_t* __restrict__ qkv, const elem_t* __restrict__ dout,
+    const float* __restrict__ lse, const float* __restrict__ delta, elem_t* __restrict__ dqkv) {
   constexpr int BKV = 64, LDK = D + 8, DT = D / 32, KK = D / 16;
-  __shared__ __align__(16) bf16_t sK[BKV * LDK];
-  __shared__ __align__(16) bf16_t sV[BKV * LDK];
+  __shared__ __align__(16) elem_t sK[BKV * LDK];
+  __shared__ __align__(16) elem_t sV[BKV * LDK];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
   int rank, bh;
   attn_block(n_bh, rank, bh);
@@ -421,16 +421,16 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
   const int d = EXACT ? D : d_arg;
   const int h = a * d;
   const int64_t ld = 3 * (int64_t)h;
-  const bf16_t* qb = qkv + (int64_t)bi * s * ld + hd * d;
-  const bf16_t* kb = qb + h;
-  const bf16_t* vb = qb + 2 * h;
-  const bf16_t* dob = dout + (int64_t)bi * s * h + hd * d;
+  const elem_t* qb = qkv + (int64_t)bi * s * ld + hd * d;
+  const elem_t* kb = qb + h;
+  const elem_t* vb = qb + 2 * h;
+  const elem_t* dob = dout + (int64_t)bi * s * h + hd * d;
   const int q0 = qt * 128, qw0 = q0 + 32 * wave, qi = qw0 + (lane & 31);
   const float scale = rsqrtf((float)d), scale_log2 = kLog2e * scale;
   const float lse_q = (qi < s) ? lse[((int64_t)bi * a + hd) * s + qi] * kLog2e : 0.f;
   const float delta_q = (qi < s) ? delta[((int64_t)bi * a + hd) * s + qi] : 0.f;
 
-  bf16x8 qf[KK], dof[KK];
+  elemx8 qf[KK], dof[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) {
     qf[kk] = global_frag<EXACT>(qb, ld, qi, s, kk * 16, lane, d);
@@ -478,7 +478,7 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
       }
 #pragma unroll
       for (int c = 0; c < 2; ++c) {
-        const bf16x8 dsf = pack8(pacc, 8 * c);
+        const elemx8 dsf = pack8(pacc, 8 * c);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
           dqacc[dt] = mfma32(frag_kstrided<true>(sK + (32 * ks + 16 * c) * LDK + dt * 32, LDK, lane),
@@ -487,15 +487,15 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
     }
   }
   if (qi < s) {
-    bf16_t* dq_row = dqkv + ((int64_t)bi * s + qi) * ld + hd * d;
+    elem_t* dq_row = dqkv + ((int64_t)bi * s + qi) * ld + hd * d;
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        bf16x4 v;
+        elemx4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (bf16_t)(dqacc[dt][4 * q + e] * scale);
-        if (EXACT || dt * 32 + 8 * q + 4 * g < d) *reinterpret_cast<bf16x4*>(dq_row + dt * 32 + 8 * q + 4 * g) = v;
+        for (int e = 0; e < 4; ++e) v[e] = (elem_t)(dqacc[dt][4 * q + e] * scale);
+        if (EXACT || dt * 32 + 8 * q + 4 * g < d) *reinterpret_cast<elemx4*>(dq_row + dt * 32 + 8 * q + 4 * g) = v;
       }
   }
 }
@@ -518,7 +518,7 @@ hipError_t launch_attention_fwd(int b, int s, int a, int d, const void* qkv, voi
                                 hipStream_t st) {
   if (!head_dim_supported(d)) return hipErrorInvalidValue;
   const dim3 grid((unsigned)(((s + 127) / 128) * b * a));
-  AXONN_ATTN_DISPATCH(attn_fwd_kernel, s, a, b * a, d, (const bf16_t*)qkv, (bf16_t*)o, lse);
+  AXONN_ATTN_DISPATCH(attn_fwd_kernel, s, a, b * a, d, (const elem_t*)qkv, (elem_t*)o, lse);
   return hipGetLastError();
 }
 
@@ -530,21 +530,21 @@ hipError_t launch_attention_bwd(int b, int s, int a, int d, const void* qkv, con
     const int64_t n_chunks = (int64_t)b * s * a * d / 8;
     const dim3 gd((unsigned)((n_chunks + 255) / 256));
     if (d == 128)
-      hipLaunchKernelGGL(attn_delta_kernel<128>, gd, dim3(256), 0, st, n_chunks, s, a, (const bf16_t*)o, (const bf16_t*)dout, delta);
+      hipLaunchKernelGGL(attn_delta_kernel<128>, gd, dim3(256), 0, st, n_chunks, s, a, (const elem_t*)o, (const elem_t*)dout, delta);
     else
-      hipLaunchKernelGGL(attn_delta_kernel<64>, gd, dim3(256), 0, st, n_chunks, s, a, (const bf16_t*)o, (const bf16_t*)dout, delta);
+      hipLaunchKernelGGL(attn_delta_kernel<64>, gd, dim3(256), 0, st, n_chunks, s, a, (const elem_t*)o, (const elem_t*)dout, delta);
   } else {
     const int64_t n_pairs = (int64_t)b * s * a;
     hipLaunchKernelGGL(attn_delta_general_kernel, dim3((unsigned)((n_pairs + 15) / 16)), dim3(256), 0, st, n_pairs, s, a, d,
-                       (const bf16_t*)o, (const bf16_t*)dout, delta);
+                       (const elem_t*)o, (const elem_t*)dout, delta);
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const dim3 grid((unsigned)(((s + 127) / 128) * b * a));
-  AXONN_ATTN_DISPATCH(attn_bwd_dkdv_kernel, s, a, b * a, d, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+  AXONN_ATTN_DISPATCH(attn_bwd_dkdv_kernel, s, a, b * a, d, (const elem_t*)qkv, (const elem_t*)dout, lse, (const float*)delta, (elem_t*)dqkv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  AXONN_ATTN_DISPATCH(attn_bwd_dq_kernel, s, a, b * a, d, (const bf16_t*)qkv, (const bf16_t*)dout, lse, (const float*)delta, (bf16_t*)dqkv);
+  AXONN_ATTN_DISPATCH(attn_bwd_dq_kernel, s, a, b * a, d, (const elem_t*)qkv, (const elem_t*)dout, lse, (const float*)delta, (elem_t*)dqkv);
   return hipGetLastError();
 }
 #undef AXONN_ATTN_DISPATCH

@@ -6,10 +6,26 @@
 
 namespace axonn {
 
-typedef __bf16 bf16_t;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+// The 16-bit element type of activations, parameters and gradients: bfloat16, or IEEE half precision (the
+// paper's arithmetic, Sec. 2 "Mixed precision") when the sources are compiled with AXONN_ELEM_FP16: the
+// same kernels, the other conversion and MFMA instructions.  Both formats round to nearest even on
+// conversion from fp32; fp16 overflows to infinity beyond 65504, which is what the loss scaler looks for.
+#ifdef AXONN_ELEM_FP16
+typedef _Float16 elem_t;
+#define AXONN_ELEM_TYPE_ID 1
+#define AXONN_MFMA_32X32X16 __builtin_amdgcn_mfma_f32_32x32x16_f16
+#define AXONN_MFMA_16X16X32 __builtin_amdgcn_mfma_f32_16x16x32_f16
+#define AXONN_MFMA_16X16X32_ASM "v_mfma_f32_16x16x32_f16"
+#else
+typedef __bf16 elem_t;
+#define AXONN_ELEM_TYPE_ID 0
+#define AXONN_MFMA_32X32X16 __builtin_amdgcn_mfma_f32_32x32x16_bf16
+#define AXONN_MFMA_16X16X32 __builtin_amdgcn_mfma_f32_16x16x32_bf16
+#define AXONN_MFMA_16X16X32_ASM "v_mfma_f32_16x16x32_bf16"
+#endif
+typedef __attribute__((__vector_size__(2 * sizeof(elem_t)))) elem_t elemx2;
+typedef __attribute__((__vector_size__(4 * sizeof(elem_t)))) elem_t elemx4;
+typedef __attribute__((__vector_size__(8 * sizeof(elem_t)))) elem_t elemx8;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short short4v;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
@@ -18,36 +34,36 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 #ifdef __HIPCC__
 // ---------------------------------------------------------------------------------
-// v_mfma_f32_32x32x16_bf16 register layout (checked on hardware):
+// v_mfma_f32_32x32x16_{bf16,f16} register layout (checked on hardware):
 //   operand X (either input): lane l holds X[row = l%32][k = 8*(l/32) + i], i = 0..7
 //   result D[m][n]:           lane l, register r holds n = l%32, m = 8*(r/4) + 4*(l/32) + r%4
 // D = first_operand(rows -> m) x second_operand(rows -> n).
 // ---------------------------------------------------------------------------------
-__device__ __forceinline__ floatx16 mfma32(bf16x8 a, bf16x8 b, floatx16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+__device__ __forceinline__ floatx16 mfma32(elemx8 a, elemx8 b, floatx16 c) {
+  return AXONN_MFMA_32X32X16(a, b, c, 0, 0, 0);
 }
 
-// v_mfma_f32_16x16x32_bf16 register layout:
+// v_mfma_f32_16x16x32_{bf16,f16} register layout:
 //   operand X (either input): lane l holds X[row = l%16][k = 8*(l/16) + i], i = 0..7
 //   result D[m][n]:           lane l, register r holds n = l%16, m = 4*(l/16) + r
 // Same work per cycle as the 32x32x16 form, but it draws less power per FLOP (less accumulator
 // traffic), which matters once the whole chip runs MFMAs and the clock is power-limited.
-__device__ __forceinline__ floatx4 mfma16(bf16x8 a, bf16x8 b, floatx4 c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+__device__ __forceinline__ floatx4 mfma16(elemx8 a, elemx8 b, floatx4 c) {
+  return AXONN_MFMA_16X16X32(a, b, c, 0, 0, 0);
 }
 // The same instruction with the accumulator pinned to the accumulation registers (a[...]): a kernel
 // whose 256 accumulators fill that file exactly needs every one of them there, and the register
 // allocator does not get this right by itself.  The compiler does not see an MFMA here, so the
 // caller keeps MFMA hazards itself: a few idle cycles between writing an accumulator with another
 // instruction and the first MFMA on it, and >= 18 between the last MFMA and reading the result.
-__device__ __forceinline__ void mfma16_acc(floatx4& c, bf16x8 a, bf16x8 b) {
-  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+__device__ __forceinline__ void mfma16_acc(floatx4& c, elemx8 a, elemx8 b) {
+  asm volatile(AXONN_MFMA_16X16X32_ASM " %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 
 // Fragment of a 32(row) x 16(k) operand block from an LDS tile stored [row][k] (k
 // contiguous, `ld` elements per row).  `base` points at (row0, k0).
-__device__ __forceinline__ bf16x8 frag_kcontig(const bf16_t* base, int ld, int lane) {
-  return *reinterpret_cast<const bf16x8*>(base + (lane & 31) * ld + 8 * (lane >> 5));
+__device__ __forceinline__ elemx8 frag_kcontig(const elem_t* base, int ld, int lane) {
+  return *reinterpret_cast<const elemx8*>(base + (lane & 31) * ld + 8 * (lane >> 5));
 }
 
 // ds_read_b64_tr_b16 (checked on hardware): within each group of 16 lanes, lane t supplies
@@ -55,7 +71,7 @@ __device__ __forceinline__ bf16x8 frag_kcontig(const bf16_t* base, int ld, int l
 // addressed by lanes t/4, 4 + t/4, 8 + t/4, 12 + t/4.  So if lane t addresses
 // [k = kb + t/4][r = rb + 4*(t%4) .. +3] of a [k][r] tile, lane t ends up holding
 // r = rb + t for k = kb .. kb+3.
-__device__ __forceinline__ short4v lds_read_tr16(const bf16_t* p) {
+__device__ __forceinline__ short4v lds_read_tr16(const elem_t* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
       (AXONN_LDS short4v*)p);
 }
@@ -68,25 +84,25 @@ __device__ __forceinline__ short4v lds_read_tr16(const bf16_t* p) {
 //               order in which an MFMA result tile keeps its m index in registers 0..7 --
 //               to pair with an operand built in registers from a result tile.
 template <bool PERM>
-__device__ __forceinline__ bf16x8 frag_kstrided(const bf16_t* base, int ld, int lane) {
+__device__ __forceinline__ elemx8 frag_kstrided(const elem_t* base, int ld, int lane) {
   const int t = lane & 15, half = (lane >> 4) & 1, g = lane >> 5;
   const int kq = t >> 2, r = 16 * half + 4 * (t & 3);
   const int k_a = PERM ? 4 * g : 8 * g;
   const int k_b = PERM ? 8 + 4 * g : 8 * g + 4;
-  union { bf16x8 v; short4v h[2]; } u;
+  union { elemx8 v; short4v h[2]; } u;
   u.h[0] = lds_read_tr16(base + (k_a + kq) * ld + r);
   u.h[1] = lds_read_tr16(base + (k_b + kq) * ld + r);
   return u.v;
 }
 
 // The same two fragment readers for a 16(row) x 32(k) operand block of the 16x16x32 MFMA.
-__device__ __forceinline__ bf16x8 frag16_kcontig(const bf16_t* base, int ld, int lane) {
-  return *reinterpret_cast<const bf16x8*>(base + (lane & 15) * ld + 8 * (lane >> 4));
+__device__ __forceinline__ elemx8 frag16_kcontig(const elem_t* base, int ld, int lane) {
+  return *reinterpret_cast<const elemx8*>(base + (lane & 15) * ld + 8 * (lane >> 4));
 }
-__device__ __forceinline__ bf16x8 frag16_kstrided(const bf16_t* base, int ld, int lane) {
+__device__ __forceinline__ elemx8 frag16_kstrided(const elem_t* base, int ld, int lane) {
   const int t = lane & 15, g = lane >> 4;
   const int kq = t >> 2, r = 4 * (t & 3);
-  union { bf16x8 v; short4v h[2]; } u;
+  union { elemx8 v; short4v h[2]; } u;
   u.h[0] = lds_read_tr16(base + (8 * g + kq) * ld + r);
   u.h[1] = lds_read_tr16(base + (8 * g + 4 + kq) * ld + r);
   return u.v;
@@ -103,8 +119,8 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
-__device__ __forceinline__ float bf2f(bf16_t v) { return (float)v; }
-__device__ __forceinline__ bf16_t f2bf(float v) { return (bf16_t)v; }
+__device__ __forceinline__ float bf2f(elem_t v) { return (float)v; }
+__device__ __forceinline__ elem_t f2bf(float v) { return (elem_t)v; }
 
 // GeLU pieces in the exact (erf) form: Phi(x) = 0.5*(1+erf(x/sqrt2)), phi(x) = exp(-x^2/2)/sqrt(2pi).
 // erfc(z), z >= 0, is evaluated as a degree-5 polynomial in 1/(1 + p z) times exp(-z^2) (Abramowitz &
@@ -152,10 +168,10 @@ enum GemmEpilogue {
 // A_seg[s].  This is how a weight gradient is summed over several microbatches in one launch.
 constexpr int kMaxKSegments = 16;
 struct GemmArgs {
-  const bf16_t* A_seg[kMaxKSegments];
-  const bf16_t* B_seg[kMaxKSegments];
+  const elem_t* A_seg[kMaxKSegments];
+  const elem_t* B_seg[kMaxKSegments];
   void* C;
-  const bf16_t* bias; const bf16_t* res; bf16_t* aux;
+  const elem_t* bias; const elem_t* res; elem_t* aux;
   int64_t lda, ldb, ldc, ld_res, ld_aux;
   int M, N, K;       // K = length of ONE segment
   int n_seg;
@@ -179,8 +195,12 @@ hipError_t launch_layernorm_bwd(int64_t T, int64_t h, const void* dout, const vo
                                 float* ws, hipStream_t s);
 hipError_t launch_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, void* out, int acc_mode,
                          bool dst_fp32, float* ws, hipStream_t s);
-hipError_t launch_f32_to_bf16(uint64_t n, const float* src, void* dst, hipStream_t s);
-hipError_t launch_fill_bf16(uint64_t n, void* dst, float value, hipStream_t s);
+hipError_t launch_f32_to_elem(uint64_t n, const float* src, void* dst, hipStream_t s);
+hipError_t launch_fill_elem(uint64_t n, void* dst, float value, hipStream_t s);
+// Counts the non-finite elements of x[0..n) into ws[kNonfiniteWsCounters - 1]; ws: kNonfiniteWsCounters
+// 64-bit counters of device memory, all overwritten.
+constexpr int kNonfiniteWsCounters = 1025;
+hipError_t launch_count_nonfinite(uint64_t n, const void* x, uint64_t* ws, hipStream_t s);
 hipError_t launch_attention_fwd(int b, int s, int a, int d, const void* qkv, void* o,
                                 float* lse, hipStream_t st);
 hipError_t launch_attention_bwd(int b, int s, int a, int d, const void* qkv, const void* o,
@@ -192,8 +212,8 @@ hipError_t launch_embed_bwd(int b, int s, int h, int vocab, const int* tokens, c
                             void* dwpe, int accumulate, hipStream_t st);
 // Cross-entropy over bf16 logits [T, V]: token_loss[t] and loss[0] = sum_t token_loss[t] / (T * n_microbatches);
 // the logits are overwritten by dloss/dlogits.
-hipError_t launch_xent(int T, int V, void* logits, const int* targets, int n_microbatches, float* token_loss,
-                       float* loss, hipStream_t st);
+hipError_t launch_xent(int T, int V, void* logits, const int* targets, int n_microbatches, float loss_scale,
+                       float* token_loss, float* loss, hipStream_t st);
 hipError_t launch_adam(uint64_t n, float* theta, float* m, float* v, const void* g16,
                        void* p16, double lr, double b1, double b2, double eps, double wd,
                        int64_t step, double grad_scale, hipStream_t s);

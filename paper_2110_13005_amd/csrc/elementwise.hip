@@ -24,21 +24,21 @@ __device__ __forceinline__ float block_sum4(float v, float (&red)[4], int lane, 
 
 template <int MAXC>
 __global__ __launch_bounds__(LN_THREADS) void layernorm_fwd_kernel(
-    int T, int h, const bf16_t* __restrict__ x, const bf16_t* __restrict__ gamma,
-    const bf16_t* __restrict__ beta, float eps, bf16_t* __restrict__ out,
-    bf16_t* __restrict__ out_lo, float* __restrict__ stats) {
+    int T, int h, const elem_t* __restrict__ x, const elem_t* __restrict__ gamma,
+    const elem_t* __restrict__ beta, float eps, elem_t* __restrict__ out,
+    elem_t* __restrict__ out_lo, float* __restrict__ stats) {
   __shared__ float red[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int row = blockIdx.x;
   const int nch = h >> 3;
-  const bf16_t* xr = x + (int64_t)row * h;
-  bf16x8 v[MAXC];
+  const elem_t* xr = x + (int64_t)row * h;
+  elemx8 v[MAXC];
   float sum = 0.f;
 #pragma unroll
   for (int c = 0; c < MAXC; ++c) {
     const int ch = c * LN_THREADS + tid;
     if (ch < nch) {
-      v[c] = *reinterpret_cast<const bf16x8*>(xr + ch * 8);
+      v[c] = *reinterpret_cast<const elemx8*>(xr + ch * 8);
 #pragma unroll
       for (int e = 0; e < 8; ++e) sum += (float)v[c][e];
     }
@@ -61,22 +61,22 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_fwd_kernel(
     stats[2 * (int64_t)row] = mean;
     stats[2 * (int64_t)row + 1] = rstd;
   }
-  bf16_t* orow = out + (int64_t)row * h;
+  elem_t* orow = out + (int64_t)row * h;
 #pragma unroll
   for (int c = 0; c < MAXC; ++c) {
     const int ch = c * LN_THREADS + tid;
     if (ch < nch) {
-      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gamma + ch * 8);
-      const bf16x8 bv = *reinterpret_cast<const bf16x8*>(beta + ch * 8);
-      bf16x8 o, lo;
+      const elemx8 gv = *reinterpret_cast<const elemx8*>(gamma + ch * 8);
+      const elemx8 bv = *reinterpret_cast<const elemx8*>(beta + ch * 8);
+      elemx8 o, lo;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float val = (float)gv[e] * (((float)v[c][e] - mean) * rstd) + (float)bv[e];
-        o[e] = (bf16_t)val;
-        lo[e] = (bf16_t)(val - (float)o[e]);   // what the rounding to bf16 dropped
+        o[e] = (elem_t)val;
+        lo[e] = (elem_t)(val - (float)o[e]);   // what the rounding to bf16 dropped
       }
-      *reinterpret_cast<bf16x8*>(orow + ch * 8) = o;
-      if (out_lo) *reinterpret_cast<bf16x8*>(out_lo + (int64_t)row * h + ch * 8) = lo;
+      *reinterpret_cast<elemx8*>(orow + ch * 8) = o;
+      if (out_lo) *reinterpret_cast<elemx8*>(out_lo + (int64_t)row * h + ch * 8) = lo;
     }
   }
 }
@@ -84,25 +84,25 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_fwd_kernel(
 // dx = res + rstd * (dxhat - mean(dxhat) - xhat * mean(dxhat * xhat)),  dxhat = dout * gamma
 template <int MAXC>
 __global__ __launch_bounds__(LN_THREADS) void layernorm_bwd_dx_kernel(
-    int T, int h, const bf16_t* __restrict__ dout, const bf16_t* __restrict__ x,
-    const float* __restrict__ stats, const bf16_t* __restrict__ gamma,
-    const bf16_t* __restrict__ res, bf16_t* __restrict__ dx) {
+    int T, int h, const elem_t* __restrict__ dout, const elem_t* __restrict__ x,
+    const float* __restrict__ stats, const elem_t* __restrict__ gamma,
+    const elem_t* __restrict__ res, elem_t* __restrict__ dx) {
   __shared__ float red[4];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int row = blockIdx.x;
   const int nch = h >> 3;
   const float mean = stats[2 * (int64_t)row], rstd = stats[2 * (int64_t)row + 1];
-  const bf16_t* xr = x + (int64_t)row * h;
-  const bf16_t* dr = dout + (int64_t)row * h;
-  bf16x8 xv[MAXC], dv[MAXC];
+  const elem_t* xr = x + (int64_t)row * h;
+  const elem_t* dr = dout + (int64_t)row * h;
+  elemx8 xv[MAXC], dv[MAXC];
   float s1 = 0.f, s2 = 0.f;
 #pragma unroll
   for (int c = 0; c < MAXC; ++c) {
     const int ch = c * LN_THREADS + tid;
     if (ch < nch) {
-      xv[c] = *reinterpret_cast<const bf16x8*>(xr + ch * 8);
-      dv[c] = *reinterpret_cast<const bf16x8*>(dr + ch * 8);
-      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gamma + ch * 8);
+      xv[c] = *reinterpret_cast<const elemx8*>(xr + ch * 8);
+      dv[c] = *reinterpret_cast<const elemx8*>(dr + ch * 8);
+      const elemx8 gv = *reinterpret_cast<const elemx8*>(gamma + ch * 8);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float dxh = (float)dv[c][e] * (float)gv[e];
@@ -114,24 +114,24 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_bwd_dx_kernel(
   }
   const float m1 = block_sum4(s1, red, lane, wave) / (float)h;
   const float m2 = block_sum4(s2, red, lane, wave) / (float)h;
-  bf16_t* orow = dx + (int64_t)row * h;
+  elem_t* orow = dx + (int64_t)row * h;
 #pragma unroll
   for (int c = 0; c < MAXC; ++c) {
     const int ch = c * LN_THREADS + tid;
     if (ch < nch) {
-      const bf16x8 gv = *reinterpret_cast<const bf16x8*>(gamma + ch * 8);
-      bf16x8 rv;
-      if (res) rv = *reinterpret_cast<const bf16x8*>(res + (int64_t)row * h + ch * 8);
-      bf16x8 o;
+      const elemx8 gv = *reinterpret_cast<const elemx8*>(gamma + ch * 8);
+      elemx8 rv;
+      if (res) rv = *reinterpret_cast<const elemx8*>(res + (int64_t)row * h + ch * 8);
+      elemx8 o;
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         const float dxh = (float)dv[c][e] * (float)gv[e];
         const float xh = ((float)xv[c][e] - mean) * rstd;
         float r = rstd * (dxh - m1 - xh * m2);
         if (res) r += (float)rv[e];
-        o[e] = (bf16_t)r;
+        o[e] = (elem_t)r;
       }
-      *reinterpret_cast<bf16x8*>(orow + ch * 8) = o;
+      *reinterpret_cast<elemx8*>(orow + ch * 8) = o;
     }
   }
 }
@@ -143,7 +143,7 @@ __global__ __launch_bounds__(LN_THREADS) void layernorm_bwd_dx_kernel(
 constexpr int CS_ROWS = 64;
 template <int MODE>
 __global__ __launch_bounds__(256) void colsum_partial_kernel(
-    int T, int N, const bf16_t* __restrict__ y, int64_t ldy, const bf16_t* __restrict__ x,
+    int T, int N, const elem_t* __restrict__ y, int64_t ldy, const elem_t* __restrict__ x,
     const float* __restrict__ stats, float* __restrict__ partial) {
   __shared__ float red[3][2][64][8];
   const int lane = threadIdx.x & 63, q = threadIdx.x >> 6;
@@ -154,9 +154,9 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(
   for (int e = 0; e < 8; ++e) a0[e] = a1[e] = 0.f;
   if (col < N) {
     for (int r = r_begin; r < r_begin + CS_ROWS / 4 && r < T; ++r) {
-      const bf16x8 yv = *reinterpret_cast<const bf16x8*>(y + (int64_t)r * ldy + col);
+      const elemx8 yv = *reinterpret_cast<const elemx8*>(y + (int64_t)r * ldy + col);
       if (MODE == 1) {
-        const bf16x8 xv = *reinterpret_cast<const bf16x8*>(x + (int64_t)r * N + col);
+        const elemx8 xv = *reinterpret_cast<const elemx8*>(x + (int64_t)r * N + col);
         const float mean = stats[2 * (int64_t)r], rstd = stats[2 * (int64_t)r + 1];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -233,31 +233,31 @@ __global__ __launch_bounds__(256) void colsum_final_kernel(int nrb, int N,
     put_sum(reinterpret_cast<float*>(out0), n, s0, acc_mode);
     if (KSUM == 2) put_sum(reinterpret_cast<float*>(out1), n, s1, acc_mode);
   } else {
-    put_sum(reinterpret_cast<bf16_t*>(out0), n, s0, acc_mode);
-    if (KSUM == 2) put_sum(reinterpret_cast<bf16_t*>(out1), n, s1, acc_mode);
+    put_sum(reinterpret_cast<elem_t*>(out0), n, s0, acc_mode);
+    if (KSUM == 2) put_sum(reinterpret_cast<elem_t*>(out1), n, s1, acc_mode);
   }
 }
 
-__global__ __launch_bounds__(256) void f32_to_bf16_kernel(uint64_t n8, uint64_t n,
+__global__ __launch_bounds__(256) void f32_to_elem_kernel(uint64_t n8, uint64_t n,
                                                           const float* __restrict__ src,
-                                                          bf16_t* __restrict__ dst) {
+                                                          elem_t* __restrict__ dst) {
   const uint64_t stride = (uint64_t)gridDim.x * 256;
   for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
     const floatx4 a = *reinterpret_cast<const floatx4*>(src + i * 8);
     const floatx4 b = *reinterpret_cast<const floatx4*>(src + i * 8 + 4);
-    bf16x8 o;
+    elemx8 o;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) { o[e] = (bf16_t)a[e]; o[4 + e] = (bf16_t)b[e]; }
-    *reinterpret_cast<bf16x8*>(dst + i * 8) = o;
+    for (int e = 0; e < 4; ++e) { o[e] = (elem_t)a[e]; o[4 + e] = (elem_t)b[e]; }
+    *reinterpret_cast<elemx8*>(dst + i * 8) = o;
   }
   if (blockIdx.x == 0) {
-    for (uint64_t i = n8 * 8 + threadIdx.x; i < n; i += 256) dst[i] = (bf16_t)src[i];
+    for (uint64_t i = n8 * 8 + threadIdx.x; i < n; i += 256) dst[i] = (elem_t)src[i];
   }
 }
 
-__global__ __launch_bounds__(256) void fill_bf16_kernel(uint64_t n, bf16_t* dst, float value) {
+__global__ __launch_bounds__(256) void fill_elem_kernel(uint64_t n, elem_t* dst, float value) {
   const uint64_t stride = (uint64_t)gridDim.x * 256;
-  const bf16_t v = (bf16_t)value;
+  const elem_t v = (elem_t)value;
   for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) dst[i] = v;
 }
 
@@ -275,37 +275,44 @@ __device__ __forceinline__ void adam_elem(float& th, float& m, float& v, float g
   const float vhat = v * c.inv_bc2;
   th = th - c.lr * (mhat / (sqrtf(vhat) + c.eps) + c.wd * th);
 }
+// theta16 = the 16-bit rounding of the fp32 theta that is stored, not of the unrounded update: for half
+// precision the compiler would otherwise fuse the last multiply-add with the conversion (one rounding from
+// the exact result), which differs from rounding the stored value where that is an exact tie.
+__device__ __forceinline__ elem_t round_stored(float a) {
+  asm volatile("" : "+v"(a));
+  return (elem_t)a;
+}
 __global__ __launch_bounds__(256) void adam_kernel(uint64_t n8, uint64_t n, float* __restrict__ theta,
                                                    float* __restrict__ m, float* __restrict__ v,
-                                                   const bf16_t* __restrict__ g16,
-                                                   bf16_t* __restrict__ p16, AdamConsts c) {
+                                                   const elem_t* __restrict__ g16,
+                                                   elem_t* __restrict__ p16, AdamConsts c) {
   const uint64_t stride = (uint64_t)gridDim.x * 256;
   for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += stride) {
     const uint64_t o = i * 8;
     floatx4 t0 = *reinterpret_cast<const floatx4*>(theta + o), t1 = *reinterpret_cast<const floatx4*>(theta + o + 4);
     floatx4 m0 = *reinterpret_cast<const floatx4*>(m + o), m1 = *reinterpret_cast<const floatx4*>(m + o + 4);
     floatx4 v0 = *reinterpret_cast<const floatx4*>(v + o), v1 = *reinterpret_cast<const floatx4*>(v + o + 4);
-    const bf16x8 gv = *reinterpret_cast<const bf16x8*>(g16 + o);
-    bf16x8 pv;
+    const elemx8 gv = *reinterpret_cast<const elemx8*>(g16 + o);
+    elemx8 pv;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       float a = t0[e], b = m0[e], d = v0[e];
       adam_elem(a, b, d, (float)gv[e], c);
-      t0[e] = a; m0[e] = b; v0[e] = d; pv[e] = (bf16_t)a;
+      t0[e] = a; m0[e] = b; v0[e] = d; pv[e] = round_stored(a);
       a = t1[e]; b = m1[e]; d = v1[e];
       adam_elem(a, b, d, (float)gv[4 + e], c);
-      t1[e] = a; m1[e] = b; v1[e] = d; pv[4 + e] = (bf16_t)a;
+      t1[e] = a; m1[e] = b; v1[e] = d; pv[4 + e] = round_stored(a);
     }
     *reinterpret_cast<floatx4*>(theta + o) = t0; *reinterpret_cast<floatx4*>(theta + o + 4) = t1;
     *reinterpret_cast<floatx4*>(m + o) = m0; *reinterpret_cast<floatx4*>(m + o + 4) = m1;
     *reinterpret_cast<floatx4*>(v + o) = v0; *reinterpret_cast<floatx4*>(v + o + 4) = v1;
-    *reinterpret_cast<bf16x8*>(p16 + o) = pv;
+    *reinterpret_cast<elemx8*>(p16 + o) = pv;
   }
   if (blockIdx.x == 0) {
     for (uint64_t i = n8 * 8 + threadIdx.x; i < n; i += 256) {
       float a = theta[i], b = m[i], d = v[i];
       adam_elem(a, b, d, (float)g16[i], c);
-      theta[i] = a; m[i] = b; v[i] = d; p16[i] = (bf16_t)a;
+      theta[i] = a; m[i] = b; v[i] = d; p16[i] = round_stored(a);
     }
   }
 }
@@ -326,8 +333,8 @@ hipError_t launch_layernorm_fwd(int64_t T, int64_t h, const void* x, const void*
                                 const void* beta, float eps, void* out, void* out_lo, float* stats,
                                 hipStream_t s) {
   if (h > LN_MAX_COLS || T <= 0) return hipErrorInvalidValue;
-  AXONN_LN_DISPATCH(layernorm_fwd_kernel, (int)T, (int)h, (const bf16_t*)x, (const bf16_t*)gamma,
-                    (const bf16_t*)beta, eps, (bf16_t*)out, (bf16_t*)out_lo, stats)
+  AXONN_LN_DISPATCH(layernorm_fwd_kernel, (int)T, (int)h, (const elem_t*)x, (const elem_t*)gamma,
+                    (const elem_t*)beta, eps, (elem_t*)out, (elem_t*)out_lo, stats)
   return hipGetLastError();
 }
 
@@ -336,14 +343,14 @@ hipError_t launch_layernorm_bwd(int64_t T, int64_t h, const void* dout, const vo
                                 void* dx, void* dgamma, void* dbeta, int acc_mode, bool dst_fp32,
                                 float* ws, hipStream_t s) {
   if (h > LN_MAX_COLS || T <= 0) return hipErrorInvalidValue;
-  AXONN_LN_DISPATCH(layernorm_bwd_dx_kernel, (int)T, (int)h, (const bf16_t*)dout, (const bf16_t*)x,
-                    stats, (const bf16_t*)gamma, (const bf16_t*)res_grad, (bf16_t*)dx)
+  AXONN_LN_DISPATCH(layernorm_bwd_dx_kernel, (int)T, (int)h, (const elem_t*)dout, (const elem_t*)x,
+                    stats, (const elem_t*)gamma, (const elem_t*)res_grad, (elem_t*)dx)
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   const int nrb = (int)((T + CS_ROWS - 1) / CS_ROWS);
   const dim3 g2((unsigned)((h + 511) / 512), (unsigned)nrb);
   hipLaunchKernelGGL(colsum_partial_kernel<1>, g2, dim3(256), 0, s, (int)T, (int)h,
-                     (const bf16_t*)dout, (int64_t)h, (const bf16_t*)x, stats, ws);
+                     (const elem_t*)dout, (int64_t)h, (const elem_t*)x, stats, ws);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_final_kernel<2>, dim3((unsigned)((h + 63) / 64)), dim3(256), 0, s, nrb,
@@ -357,7 +364,7 @@ hipError_t launch_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, void*
   const int nrb = (int)((T + CS_ROWS - 1) / CS_ROWS);
   const dim3 g2((unsigned)((N + 511) / 512), (unsigned)nrb);
   hipLaunchKernelGGL(colsum_partial_kernel<0>, g2, dim3(256), 0, s, (int)T, (int)N,
-                     (const bf16_t*)y, ldy, (const bf16_t*)nullptr, (const float*)nullptr, ws);
+                     (const elem_t*)y, ldy, (const elem_t*)nullptr, (const float*)nullptr, ws);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(colsum_final_kernel<1>, dim3((unsigned)((N + 63) / 64)), dim3(256), 0, s, nrb,
@@ -372,14 +379,61 @@ static unsigned grid_for(uint64_t work_items) {
   return (unsigned)b;
 }
 
-hipError_t launch_f32_to_bf16(uint64_t n, const float* src, void* dst, hipStream_t s) {
-  hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(grid_for(n / 8)), dim3(256), 0, s, n / 8, n, src,
-                     (bf16_t*)dst);
+// Number of elements of x[0..n) that are not finite (infinity or NaN): what a dynamic loss scaler looks for
+// in the 16-bit gradients.  kNonfiniteBlocks workgroups write one partial count each, a second launch adds
+// them in a fixed order: no atomics, no buffer to clear.  ws holds kNonfiniteBlocks + 1 counters; the total
+// lands in ws[kNonfiniteBlocks].
+constexpr int kNonfiniteBlocks = 1024;
+__global__ __launch_bounds__(256) void nonfinite_partial_kernel(uint64_t n, const elem_t* __restrict__ x,
+                                                                unsigned long long* __restrict__ ws) {
+  __shared__ unsigned int red[4];
+  const uint64_t n8 = n / 8;
+  unsigned int c = 0;
+  for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (uint64_t)kNonfiniteBlocks * 256) {
+    const elemx8 v = *reinterpret_cast<const elemx8*>(x + i * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float f = (float)v[e];
+      c += (f - f == 0.f) ? 0u : 1u;          // inf - inf and NaN - NaN are NaN
+    }
+  }
+  if (blockIdx.x == 0 && threadIdx.x < (int)(n - n8 * 8)) {
+    const float f = (float)x[n8 * 8 + threadIdx.x];
+    c += (f - f == 0.f) ? 0u : 1u;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) ws[blockIdx.x] = (unsigned long long)red[0] + red[1] + red[2] + red[3];
+}
+__global__ __launch_bounds__(256) void nonfinite_final_kernel(unsigned long long* __restrict__ ws) {
+  __shared__ unsigned long long red[4];
+  unsigned long long c = 0;
+  for (int i = threadIdx.x; i < kNonfiniteBlocks; i += 256) c += ws[i];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o, 64);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = c;
+  __syncthreads();
+  if (threadIdx.x == 0) ws[kNonfiniteBlocks] = red[0] + red[1] + red[2] + red[3];
+}
+hipError_t launch_count_nonfinite(uint64_t n, const void* x, uint64_t* ws, hipStream_t s) {
+  hipLaunchKernelGGL(nonfinite_partial_kernel, dim3(kNonfiniteBlocks), dim3(256), 0, s, n, (const elem_t*)x,
+                     (unsigned long long*)ws);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(nonfinite_final_kernel, dim3(1), dim3(256), 0, s, (unsigned long long*)ws);
   return hipGetLastError();
 }
 
-hipError_t launch_fill_bf16(uint64_t n, void* dst, float value, hipStream_t s) {
-  hipLaunchKernelGGL(fill_bf16_kernel, dim3(grid_for(n)), dim3(256), 0, s, n, (bf16_t*)dst, value);
+hipError_t launch_f32_to_elem(uint64_t n, const float* src, void* dst, hipStream_t s) {
+  hipLaunchKernelGGL(f32_to_elem_kernel, dim3(grid_for(n / 8)), dim3(256), 0, s, n / 8, n, src,
+                     (elem_t*)dst);
+  return hipGetLastError();
+}
+
+hipError_t launch_fill_elem(uint64_t n, void* dst, float value, hipStream_t s) {
+  hipLaunchKernelGGL(fill_elem_kernel, dim3(grid_for(n)), dim3(256), 0, s, n, (elem_t*)dst, value);
   return hipGetLastError();
 }
 
@@ -395,7 +449,7 @@ hipError_t launch_adam(uint64_t n, float* theta, float* m, float* v, const void*
   c.inv_bc1 = (float)(1.0 / (1.0 - pow(b1, (double)step)));
   c.inv_bc2 = (float)(1.0 / (1.0 - pow(b2, (double)step)));
   hipLaunchKernelGGL(adam_kernel, dim3(grid_for(n / 8)), dim3(256), 0, s, n / 8, n, theta, m, v,
-                     (const bf16_t*)g16, (bf16_t*)p16, c);
+                     (const elem_t*)g16, (elem_t*)p16, c);
   return hipGetLastError();
 }
 

@@ -47,7 +47,7 @@ __device__ __forceinline__ void load_bias4(float (&bv)[4], const GemmArgs& g, in
   for (int e = 0; e < 4; ++e) bv[e] = 0.f;
   if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
     if (g.bias) {
-      const bf16x4 b4 = *reinterpret_cast<const bf16x4*>(g.bias + n);
+      const elemx4 b4 = *reinterpret_cast<const elemx4*>(g.bias + n);
 #pragma unroll
       for (int e = 0; e < 4; ++e) bv[e] = (float)b4[e];
     }
@@ -73,9 +73,9 @@ __device__ __forceinline__ EpiOperand epi_load_operand(const GemmArgs& g, int m,
     const u32x4 t = *reinterpret_cast<const u32x4*>(reinterpret_cast<const float*>(g.C) + (int64_t)m * g.ldc + n);
     o.raw[0] = t[0]; o.raw[1] = t[1]; o.raw[2] = t[2]; o.raw[3] = t[3];
   } else {
-    const bf16_t* p = EPI == EPI_BIAS_RES ? g.res + (int64_t)m * g.ld_res + n
+    const elem_t* p = EPI == EPI_BIAS_RES ? g.res + (int64_t)m * g.ld_res + n
                     : EPI == EPI_DGELU    ? g.aux + (int64_t)m * g.ld_aux + n
-                                          : reinterpret_cast<const bf16_t*>(g.C) + (int64_t)m * g.ldc + n;
+                                          : reinterpret_cast<const elem_t*>(g.C) + (int64_t)m * g.ldc + n;
     const uint2 t = *reinterpret_cast<const uint2*>(p);
     o.raw[0] = t.x; o.raw[1] = t.y; o.raw[2] = 0u; o.raw[3] = 0u;
   }
@@ -89,8 +89,13 @@ __device__ __forceinline__ void epi_operand_values(const EpiOperand& o, float (&
 #pragma unroll
     for (int e = 0; e < 4; ++e) x[e] = __uint_as_float(o.raw[e]);
   } else {
+#ifdef AXONN_ELEM_FP16
+    const elemx2 lo = __builtin_bit_cast(elemx2, o.raw[0]), hi = __builtin_bit_cast(elemx2, o.raw[1]);
+    x[0] = (float)lo[0]; x[1] = (float)lo[1]; x[2] = (float)hi[0]; x[3] = (float)hi[1];
+#else
     x[0] = __uint_as_float(o.raw[0] << 16); x[1] = __uint_as_float(o.raw[0] & 0xffff0000u);
     x[2] = __uint_as_float(o.raw[1] << 16); x[3] = __uint_as_float(o.raw[1] & 0xffff0000u);
+#endif
   }
 }
 
@@ -112,15 +117,15 @@ __device__ __forceinline__ void epi_finish(float (&v)[4], const float (&bv)[4], 
   if (EPI == EPI_BIAS_GELU) {
     // the derivative is formed here, from the unrounded pre-activation, and stored in its place: the
     // backward epilogue is then one multiplication
-    bf16x4 dv;
+    elemx4 dv;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       float y, dy;
       gelu_with_grad_f(v[e], y, dy);
       v[e] = y;
-      dv[e] = (bf16_t)dy;
+      dv[e] = (elem_t)dy;
     }
-    *reinterpret_cast<bf16x4*>(g.aux + (int64_t)m * g.ld_aux + n) = dv;
+    *reinterpret_cast<elemx4*>(g.aux + (int64_t)m * g.ld_aux + n) = dv;
   }
   if (EPI == EPI_DGELU) {
 #pragma unroll
@@ -130,10 +135,10 @@ __device__ __forceinline__ void epi_finish(float (&v)[4], const float (&bv)[4], 
     *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(g.C) + (int64_t)m * g.ldc + n) =
         floatx4{v[0], v[1], v[2], v[3]};
   } else {
-    bf16x4 ov;
+    elemx4 ov;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) ov[e] = (bf16_t)v[e];
-    *reinterpret_cast<bf16x4*>(reinterpret_cast<bf16_t*>(g.C) + (int64_t)m * g.ldc + n) = ov;
+    for (int e = 0; e < 4; ++e) ov[e] = (elem_t)v[e];
+    *reinterpret_cast<elemx4*>(reinterpret_cast<elem_t*>(g.C) + (int64_t)m * g.ldc + n) = ov;
   }
 }
 
@@ -249,8 +254,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
   static_assert(A_CH >= 1 && B_CH >= 1, "tile too small for the block");
   static_assert((BM * BK / 8) % NT == 0 && (BN * BK / 8) % NT == 0, "tile/threads mismatch");
 
-  __shared__ __align__(16) bf16_t sA[2][LA::ELEMS];
-  __shared__ __align__(16) bf16_t sB[2][LB::ELEMS];
+  __shared__ __align__(16) elem_t sA[2][LA::ELEMS];
+  __shared__ __align__(16) elem_t sB[2][LB::ELEMS];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / WGN, wn = wave % WGN;
@@ -274,8 +279,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
   // matrix (fixed) and its k is inside the segment (checked per step).  Out-of-range chunks read a
   // zero chunk instead, so the loads are unconditional and stay in registers until the next step
   // stores them to LDS.
-  const bf16_t* pa[A_CH];
-  const bf16_t* pb[B_CH];
+  const elem_t* pa[A_CH];
+  const elem_t* pb[B_CH];
   int64_t offa[A_CH], offb[B_CH];
   bool va[A_CH], vb[B_CH];
   int ka[A_CH], kb[B_CH], oa[A_CH], ob[B_CH];
@@ -316,7 +321,7 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
   const int K = g.K;
   const int tps = (K + BK - 1) / BK;      // k-tiles per segment
   const int nk = tps * g.n_seg;
-  const bf16_t* zero_chunk = reinterpret_cast<const bf16_t*>(g_zero_chunk);
+  const elem_t* zero_chunk = reinterpret_cast<const elem_t*>(g_zero_chunk);
   u32x4 ra[A_CH], rb[B_CH];
   int ld_seg = 0, ld_kin = 0;            // segment and k-tile within it of the NEXT tile to fetch
 
@@ -339,8 +344,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
       ld_kin = 0;                                                              \
       ++ld_seg;                                                                \
       const int sidx = ld_seg < g.n_seg ? ld_seg : 0;                          \
-      const bf16_t* na = g.A_seg[sidx];                                        \
-      const bf16_t* nb = g.B_seg[sidx];                                        \
+      const elem_t* na = g.A_seg[sidx];                                        \
+      const elem_t* nb = g.B_seg[sidx];                                        \
       _Pragma("unroll") for (int j = 0; j < A_CH; ++j) pa[j] = na + offa[j];   \
       _Pragma("unroll") for (int j = 0; j < B_CH; ++j) pb[j] = nb + offb[j];   \
     }                                                                          \
@@ -371,11 +376,11 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
     // registers hold tile kt+1: park it in the other buffer, then fetch tile kt+2
     AXONN_SSTORE(cur ^ 1)
     AXONN_GLOAD()
-    const bf16_t* a_s = sA[cur];
-    const bf16_t* b_s = sB[cur];
+    const elem_t* a_s = sA[cur];
+    const elem_t* b_s = sB[cur];
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 fa[TM], fb[TN];
+      elemx8 fa[TM], fb[TN];
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         const int r0 = wm * WTM + i * 32;
@@ -442,11 +447,11 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
   using LA = TileLayout<BM, BK, A_KC>;
   using LB = TileLayout<B_KC ? BN : 256, BK, B_KC>;
   // one LDS block: A buffers 0,1, then B buffers 0,1; the epilogue reuses it as staging space
-  constexpr int LDS_BYTES = 2 * (LA::ELEMS + LB::ELEMS) * (int)sizeof(bf16_t);
+  constexpr int LDS_BYTES = 2 * (LA::ELEMS + LB::ELEMS) * (int)sizeof(elem_t);
   static_assert(LDS_BYTES >= 4 * StageLayout<TN>::FLOATS_PER_WAVE * (int)sizeof(float), "staging space of the epilogue");
   __shared__ __align__(16) char smem[LDS_BYTES];
-#define sA(buf) (reinterpret_cast<bf16_t*>(smem) + (buf) * LA::ELEMS)
-#define sB(buf) (reinterpret_cast<bf16_t*>(smem) + 2 * LA::ELEMS + (buf) * LB::ELEMS)
+#define sA(buf) (reinterpret_cast<elem_t*>(smem) + (buf) * LA::ELEMS)
+#define sB(buf) (reinterpret_cast<elem_t*>(smem) + 2 * LA::ELEMS + (buf) * LB::ELEMS)
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -574,7 +579,7 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
-  bf16x8 fa[2][TM], fb[2][TN];
+  elemx8 fa[2][TM], fb[2][TN];
 
   // prologue: tile 0 in buffer 0; the A chunks of tile 1 in buffer 1 and its B chunks in registers;
   // the A chunks of tile 2 on their way (tiles that do not exist read as zeros)
@@ -804,23 +809,23 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
   if ((f) == 0 || (f) > TN) {                                                                  \
     const int i = (f) == 0 ? 0 : (f) - TN;                                                     \
     if (A_KC) {                                                                                \
-      fa[F][i] = *reinterpret_cast<const bf16x8*>(smem + fa_off[A_KC ? (kk) : 0] + (buf) * SA + i * 2048); \
+      fa[F][i] = *reinterpret_cast<const elemx8*>(smem + fa_off[A_KC ? (kk) : 0] + (buf) * SA + i * 2048); \
     } else {                                                                                   \
       const char* pf = smem + fa_off[0] + (buf) * SA + (kk) * 16 * KS_BLOCK + i * 32;          \
-      union { bf16x8 v; short4v h[2]; } u;                                                     \
-      u.h[0] = lds_read_tr16(reinterpret_cast<const bf16_t*>(pf));                             \
-      u.h[1] = lds_read_tr16(reinterpret_cast<const bf16_t*>(pf + 512));                       \
+      union { elemx8 v; short4v h[2]; } u;                                                     \
+      u.h[0] = lds_read_tr16(reinterpret_cast<const elem_t*>(pf));                             \
+      u.h[1] = lds_read_tr16(reinterpret_cast<const elem_t*>(pf + 512));                       \
       fa[F][i] = u.v;                                                                          \
     }                                                                                          \
   } else {                                                                                     \
     const int j = (f) - 1;                                                                     \
     if (B_KC) {                                                                                \
-      fb[F][j] = *reinterpret_cast<const bf16x8*>(smem + fb_off[B_KC ? (kk) : 0] + (buf) * SB + j * 2048); \
+      fb[F][j] = *reinterpret_cast<const elemx8*>(smem + fb_off[B_KC ? (kk) : 0] + (buf) * SB + j * 2048); \
     } else {                                                                                   \
       const char* pf = smem + fb_off[0] + (buf) * SB + (kk) * 16 * KS_BLOCK + j * 32;          \
-      union { bf16x8 v; short4v h[2]; } u;                                                     \
-      u.h[0] = lds_read_tr16(reinterpret_cast<const bf16_t*>(pf));                             \
-      u.h[1] = lds_read_tr16(reinterpret_cast<const bf16_t*>(pf + 512));                       \
+      union { elemx8 v; short4v h[2]; } u;                                                     \
+      u.h[0] = lds_read_tr16(reinterpret_cast<const elem_t*>(pf));                             \
+      u.h[1] = lds_read_tr16(reinterpret_cast<const elem_t*>(pf + 512));                       \
       fb[F][j] = u.v;                                                                          \
     }                                                                                          \
   }
@@ -854,7 +859,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
-  bf16x8 fa[2][TM], fb[2][TN];
+  elemx8 fa[2][TM], fb[2][TN];
 
   // prologue: tiles 0 and 1 into stages 0 and 1
 #pragma unroll

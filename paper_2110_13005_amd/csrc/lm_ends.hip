@@ -14,20 +14,20 @@ __device__ __forceinline__ int clamp_id(int id, int vocab) { return id < 0 ? 0 :
 
 // x[t, :] = wte[tokens[t], :] + wpe[t % s, :]; one workgroup per token, 8 columns per lane and step.
 __global__ __launch_bounds__(ENDS_THREADS) void embed_fwd_kernel(
-    int T, int h, int s, int vocab, const int* __restrict__ tokens, const bf16_t* __restrict__ wte,
-    const bf16_t* __restrict__ wpe, bf16_t* __restrict__ x) {
+    int T, int h, int s, int vocab, const int* __restrict__ tokens, const elem_t* __restrict__ wte,
+    const elem_t* __restrict__ wpe, elem_t* __restrict__ x) {
   const int t = blockIdx.x;
   const int id = clamp_id(tokens[t], vocab);
-  const bf16_t* e = wte + (int64_t)id * h;
-  const bf16_t* p = wpe + (int64_t)(t % s) * h;
-  bf16_t* o = x + (int64_t)t * h;
+  const elem_t* e = wte + (int64_t)id * h;
+  const elem_t* p = wpe + (int64_t)(t % s) * h;
+  elem_t* o = x + (int64_t)t * h;
   for (int c = threadIdx.x * 8; c < h; c += ENDS_THREADS * 8) {
-    const bf16x8 a = *reinterpret_cast<const bf16x8*>(e + c);
-    const bf16x8 b = *reinterpret_cast<const bf16x8*>(p + c);
-    bf16x8 r;
+    const elemx8 a = *reinterpret_cast<const elemx8*>(e + c);
+    const elemx8 b = *reinterpret_cast<const elemx8*>(p + c);
+    elemx8 r;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = (bf16_t)((float)a[i] + (float)b[i]);
-    *reinterpret_cast<bf16x8*>(o + c) = r;
+    for (int i = 0; i < 8; ++i) r[i] = (elem_t)((float)a[i] + (float)b[i]);
+    *reinterpret_cast<elemx8*>(o + c) = r;
   }
 }
 
@@ -36,8 +36,8 @@ __global__ __launch_bounds__(ENDS_THREADS) void embed_fwd_kernel(
 // rows of all occurrences in token order (fp32), so every table row has exactly one writer.  Rows
 // whose id does not occur are not touched (the caller clears the table before a batch's first pass).
 __global__ __launch_bounds__(ENDS_THREADS) void embed_bwd_wte_kernel(
-    int T, int h, int vocab, const int* __restrict__ tokens, const bf16_t* __restrict__ dx,
-    bf16_t* __restrict__ dwte, int accumulate) {
+    int T, int h, int vocab, const int* __restrict__ tokens, const elem_t* __restrict__ dx,
+    elem_t* __restrict__ dwte, int accumulate) {
   __shared__ int first_flag;
   const int t = blockIdx.x, tid = threadIdx.x;
   const int id = clamp_id(tokens[t], vocab);
@@ -47,11 +47,11 @@ __global__ __launch_bounds__(ENDS_THREADS) void embed_bwd_wte_kernel(
     if (clamp_id(tokens[u], vocab) == id) first_flag = 0;   // benign race: every writer stores 0
   __syncthreads();
   if (!first_flag) return;
-  bf16_t* g = dwte + (int64_t)id * h;
+  elem_t* g = dwte + (int64_t)id * h;
   for (int c = tid * 8; c < h; c += ENDS_THREADS * 8) {
     float acc[8];
     if (accumulate) {
-      const bf16x8 old = *reinterpret_cast<const bf16x8*>(g + c);
+      const elemx8 old = *reinterpret_cast<const elemx8*>(g + c);
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] = (float)old[i];
     } else {
@@ -60,26 +60,26 @@ __global__ __launch_bounds__(ENDS_THREADS) void embed_bwd_wte_kernel(
     }
     for (int u = t; u < T; ++u) {
       if (clamp_id(tokens[u], vocab) != id) continue;   // uniform over the workgroup
-      const bf16x8 v = *reinterpret_cast<const bf16x8*>(dx + (int64_t)u * h + c);
+      const elemx8 v = *reinterpret_cast<const elemx8*>(dx + (int64_t)u * h + c);
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] += (float)v[i];
     }
-    bf16x8 r;
+    elemx8 r;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = (bf16_t)acc[i];
-    *reinterpret_cast<bf16x8*>(g + c) = r;
+    for (int i = 0; i < 8; ++i) r[i] = (elem_t)acc[i];
+    *reinterpret_cast<elemx8*>(g + c) = r;
   }
 }
 
 // dwpe[p, :] (+)= sum over the b sequences of dx[b*s + p, :]; one workgroup per position.
 __global__ __launch_bounds__(ENDS_THREADS) void embed_bwd_wpe_kernel(
-    int b, int s, int h, const bf16_t* __restrict__ dx, bf16_t* __restrict__ dwpe, int accumulate) {
+    int b, int s, int h, const elem_t* __restrict__ dx, elem_t* __restrict__ dwpe, int accumulate) {
   const int p = blockIdx.x;
-  bf16_t* g = dwpe + (int64_t)p * h;
+  elem_t* g = dwpe + (int64_t)p * h;
   for (int c = threadIdx.x * 8; c < h; c += ENDS_THREADS * 8) {
     float acc[8];
     if (accumulate) {
-      const bf16x8 old = *reinterpret_cast<const bf16x8*>(g + c);
+      const elemx8 old = *reinterpret_cast<const elemx8*>(g + c);
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] = (float)old[i];
     } else {
@@ -87,14 +87,14 @@ __global__ __launch_bounds__(ENDS_THREADS) void embed_bwd_wpe_kernel(
       for (int i = 0; i < 8; ++i) acc[i] = 0.f;
     }
     for (int q = 0; q < b; ++q) {
-      const bf16x8 v = *reinterpret_cast<const bf16x8*>(dx + ((int64_t)q * s + p) * h + c);
+      const elemx8 v = *reinterpret_cast<const elemx8*>(dx + ((int64_t)q * s + p) * h + c);
 #pragma unroll
       for (int i = 0; i < 8; ++i) acc[i] += (float)v[i];
     }
-    bf16x8 r;
+    elemx8 r;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = (bf16_t)acc[i];
-    *reinterpret_cast<bf16x8*>(g + c) = r;
+    for (int i = 0; i < 8; ++i) r[i] = (elem_t)acc[i];
+    *reinterpret_cast<elemx8*>(g + c) = r;
   }
 }
 
@@ -111,15 +111,15 @@ __device__ __forceinline__ float block_reduce4(float v, float (&red)[4], int lan
 // token_loss[t] = max + log(sum) - l[target].  Second sweep: the row is overwritten by the gradient
 // of the microbatch's loss, (softmax - onehot) * scale with scale = 1 / (T * n_microbatches).
 __global__ __launch_bounds__(ENDS_THREADS) void xent_kernel(
-    int T, int V, bf16_t* __restrict__ logits, const int* __restrict__ targets, float scale,
+    int T, int V, elem_t* __restrict__ logits, const int* __restrict__ targets, float scale,
     float* __restrict__ token_loss) {
   __shared__ float red[4];
   const int t = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  bf16_t* row = logits + (int64_t)t * V;
+  elem_t* row = logits + (int64_t)t * V;
   const int tgt = clamp_id(targets[t], V);
   float m = -INFINITY, sum = 0.f;
   for (int c = tid * 8; c < V; c += ENDS_THREADS * 8) {
-    const bf16x8 v = *reinterpret_cast<const bf16x8*>(row + c);
+    const elemx8 v = *reinterpret_cast<const elemx8*>(row + c);
     float cm = (float)v[0];
 #pragma unroll
     for (int i = 1; i < 8; ++i) cm = fmaxf(cm, (float)v[i]);
@@ -136,14 +136,14 @@ __global__ __launch_bounds__(ENDS_THREADS) void xent_kernel(
   if (tid == 0) token_loss[t] = lse - (float)row[tgt];
   __syncthreads();   // the target logit is read before any lane overwrites the row
   for (int c = tid * 8; c < V; c += ENDS_THREADS * 8) {
-    const bf16x8 v = *reinterpret_cast<const bf16x8*>(row + c);
-    bf16x8 r;
+    const elemx8 v = *reinterpret_cast<const elemx8*>(row + c);
+    elemx8 r;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const float p = __expf((float)v[i] - lse);
-      r[i] = (bf16_t)((p - ((c + i) == tgt ? 1.f : 0.f)) * scale);
+      r[i] = (elem_t)((p - ((c + i) == tgt ? 1.f : 0.f)) * scale);
     }
-    *reinterpret_cast<bf16x8*>(row + c) = r;
+    *reinterpret_cast<elemx8*>(row + c) = r;
   }
 }
 
@@ -161,26 +161,27 @@ __global__ __launch_bounds__(ENDS_THREADS) void loss_sum_kernel(int T, const flo
 hipError_t launch_embed_fwd(int T, int h, int s, int vocab, const int* tokens, const void* wte, const void* wpe,
                             void* x, hipStream_t st) {
   hipLaunchKernelGGL(embed_fwd_kernel, dim3((unsigned)T), dim3(ENDS_THREADS), 0, st, T, h, s, vocab, tokens,
-                     (const bf16_t*)wte, (const bf16_t*)wpe, (bf16_t*)x);
+                     (const elem_t*)wte, (const elem_t*)wpe, (elem_t*)x);
   return hipGetLastError();
 }
 
 hipError_t launch_embed_bwd(int b, int s, int h, int vocab, const int* tokens, const void* dx, void* dwte,
                             void* dwpe, int accumulate, hipStream_t st) {
   hipLaunchKernelGGL(embed_bwd_wte_kernel, dim3((unsigned)(b * s)), dim3(ENDS_THREADS), 0, st, b * s, h, vocab,
-                     tokens, (const bf16_t*)dx, (bf16_t*)dwte, accumulate);
+                     tokens, (const elem_t*)dx, (elem_t*)dwte, accumulate);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(embed_bwd_wpe_kernel, dim3((unsigned)s), dim3(ENDS_THREADS), 0, st, b, s, h,
-                     (const bf16_t*)dx, (bf16_t*)dwpe, accumulate);
+                     (const elem_t*)dx, (elem_t*)dwpe, accumulate);
   return hipGetLastError();
 }
 
-hipError_t launch_xent(int T, int V, void* logits, const int* targets, int n_microbatches, float* token_loss,
-                       float* loss, hipStream_t st) {
+hipError_t launch_xent(int T, int V, void* logits, const int* targets, int n_microbatches, float loss_scale,
+                       float* token_loss, float* loss, hipStream_t st) {
   const float scale = 1.0f / ((float)T * (float)n_microbatches);
-  hipLaunchKernelGGL(xent_kernel, dim3((unsigned)T), dim3(ENDS_THREADS), 0, st, T, V, (bf16_t*)logits, targets,
-                     scale, token_loss);
+  // the gradient carries the loss scale (Sec. 2, mixed precision), the reported loss does not
+  hipLaunchKernelGGL(xent_kernel, dim3((unsigned)T), dim3(ENDS_THREADS), 0, st, T, V, (elem_t*)logits, targets,
+                     scale * loss_scale, token_loss);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(loss_sum_kernel, dim3(1), dim3(ENDS_THREADS), 0, st, T, (const float*)token_loss, scale, loss);

@@ -95,12 +95,12 @@ struct TensorInfo {
 
 struct LayerStash {
   // forward activations kept for the backward pass
-  bf16_t *x, *u, *qkv, *o, *y, *w, *pre, *g;   // pre: GeLU'(w W1 + b1), the derivative at the pre-activation
-  bf16_t* u_lo;   // only with qkv_input_split: the part of LayerNorm-1's output that bf16 rounding dropped
+  elem_t *x, *u, *qkv, *o, *y, *w, *pre, *g;   // pre: GeLU'(w W1 + b1), the derivative at the pre-activation
+  elem_t* u_lo;   // only with qkv_input_split: the part of LayerNorm-1's output that bf16 rounding dropped
   float *stats1, *stats2, *lse;
   // output gradients of the four linear maps, written by the backward pass and kept until the
   // weight gradients of a group of microbatches are formed in one contraction
-  bf16_t *dz, *dpre, *dy_mid, *dqkv;
+  elem_t *dz, *dpre, *dy_mid, *dqkv;
 };
 
 enum SlotState { SLOT_FREE, SLOT_LIVE, SLOT_AWAIT_WGRAD };
@@ -115,7 +115,7 @@ struct Slot {
   hipEvent_t fwd_done = nullptr, dgrad_done = nullptr, released = nullptr;
   bool released_recorded = false;
   const int32_t* tokens = nullptr;   // first stage: the microbatch's token ids, needed again by Backward
-  bf16_t* head_y = nullptr;          // last stage: the stage output the head consumes
+  elem_t* head_y = nullptr;          // last stage: the stage output the head consumes
 };
 
 struct PendingMsg {
@@ -128,7 +128,7 @@ struct PendingMsg {
 struct ActSet {
   char* base = nullptr;
   std::vector<LayerStash> layers;
-  bf16_t* x2 = nullptr;             // forward sets: second buffer for the layer inputs that are not kept
+  elem_t* x2 = nullptr;             // forward sets: second buffer for the layer inputs that are not kept
   hipEvent_t chain_done = nullptr;  // the backward chain through the set has finished (stream of the chain)
   hipEvent_t released = nullptr;    // the last work that reads or writes the set has finished
   bool released_recorded = false;
@@ -141,8 +141,8 @@ uint64_t align_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 struct axonn_offload_adam {
   int device = 0;
   uint64_t n = 0, bucket = 0;
-  bf16_t* p16 = nullptr;
-  const bf16_t* g16 = nullptr;
+  elem_t* p16 = nullptr;
+  const elem_t* g16 = nullptr;
   float *h_theta = nullptr, *h_m = nullptr, *h_v = nullptr;
   static constexpr int kSets = 3;  // one being filled, one being updated, one being drained
   float* d_buf[kSets][3] = {};
@@ -156,7 +156,7 @@ struct axonn_offload_adam {
 struct axonn_embed {
   int device = 0, vocab = 0, h = 0, s = 0, b = 0;
   uint64_t n_params = 0;
-  bf16_t *params = nullptr, *grads = nullptr;
+  elem_t *params = nullptr, *grads = nullptr;
   int bwd_count = 0;   // backward passes since zero_grad
 };
 
@@ -165,11 +165,12 @@ struct axonn_embed {
 struct axonn_head {
   int device = 0, vocab = 0, h = 0, T = 0, M = 0;
   float eps = 1e-5f;
+  float loss_scale = 1.0f;   // multiplies dloss/dlogits (Sec. 2, mixed precision), not the reported loss
   uint64_t n_params = 0;
-  bf16_t *params = nullptr, *grads = nullptr;
+  elem_t *params = nullptr, *grads = nullptr;
   char* ws_base = nullptr;
   uint64_t ws_bytes = 0;
-  bf16_t *a = nullptr, *logits = nullptr, *da = nullptr;
+  elem_t *a = nullptr, *logits = nullptr, *da = nullptr;
   float *stats = nullptr, *token_loss = nullptr, *red_ws = nullptr;
   int count = 0;       // microbatches since zero_grad
 };
@@ -179,15 +180,16 @@ struct axonn_stage {
   int T = 0, h = 0, f = 0, d = 0;
   uint64_t n_params = 0;
   std::vector<TensorInfo> tensors;
-  bf16_t* params = nullptr;
-  bf16_t* grads = nullptr;
+  elem_t* params = nullptr;
+  elem_t* grads = nullptr;
   float* grads32 = nullptr;
+  uint64_t* nonfinite_ws = nullptr;   // counters of launch_count_nonfinite, allocated on first use
   std::vector<Slot> slots;
   uint64_t slot_bytes = 0;
   // backward workspace
   char* ws_base = nullptr;
   uint64_t ws_bytes = 0;
-  bf16_t *dw = nullptr, *dattn = nullptr, *du = nullptr;
+  elem_t *dw = nullptr, *dattn = nullptr, *du = nullptr;
   float *delta = nullptr, *red_ws = nullptr;
   // activation checkpointing: shared activation sets (empty when cfg.ckpt_stride == 0)
   std::vector<ActSet> fwd_sets, regen_sets;
@@ -217,12 +219,12 @@ struct axonn_stage {
   // the two ends of the pipeline, when this stage is the first and / or the last one (borrowed handles)
   axonn_embed* embed = nullptr;
   axonn_head* head = nullptr;
-  bf16_t *embed_dx = nullptr, *head_dx = nullptr, *head_y_base = nullptr;
+  elem_t *embed_dx = nullptr, *head_dx = nullptr, *head_y_base = nullptr;
 };
 
 namespace {
 
-bf16_t* param_ptr(axonn_stage* st, int layer, int which) {
+elem_t* param_ptr(axonn_stage* st, int layer, int which) {
   return st->params + st->tensors[layer * kTensorsPerLayer + which].offset;
 }
 void* grad_ptr(axonn_stage* st, int layer, int which) {
@@ -244,8 +246,8 @@ int gemm(bool a_kc, bool b_kc, int epi, int M, int N, int K, const void* A, int6
          int64_t ld_res, void* aux, int64_t ld_aux, int accumulate, hipStream_t s) {
   GemmArgs g;
   memset(&g, 0, sizeof g);
-  g.A_seg[0] = (const bf16_t*)A; g.B_seg[0] = (const bf16_t*)B; g.C = C; g.n_seg = 1;
-  g.bias = (const bf16_t*)bias; g.res = (const bf16_t*)res; g.aux = (bf16_t*)aux;
+  g.A_seg[0] = (const elem_t*)A; g.B_seg[0] = (const elem_t*)B; g.C = C; g.n_seg = 1;
+  g.bias = (const elem_t*)bias; g.res = (const elem_t*)res; g.aux = (elem_t*)aux;
   g.lda = lda; g.ldb = ldb; g.ldc = ldc; g.ld_res = ld_res; g.ld_aux = ld_aux;
   g.M = M; g.N = N; g.K = K; g.accumulate = accumulate; g.tiles_m = g.tiles_n = 0;
   g.concurrent = t_concurrent;
@@ -292,7 +294,7 @@ int adam(uint64_t n, float* th, float* m, float* v, const void* g16, void* p16, 
 // ------------------------------------------------------------------- forward of a layer
 // Runs layer l on a.x, filling the activations of `a`; z receives the layer's output (null: the last
 // contraction is left out, for a regenerated layer whose output nobody reads).
-int forward_layer(axonn_stage* st, int l, const LayerStash& a, bf16_t* z, hipStream_t s) {
+int forward_layer(axonn_stage* st, int l, const LayerStash& a, elem_t* z, hipStream_t s) {
   const int T = st->T, h = st->h, f = st->f;
   AX_TRY(ln_fwd(T, h, a.x, param_ptr(st, l, P_LN1G), param_ptr(st, l, P_LN1B), st->cfg.ln_eps, a.u, a.u_lo,
                 a.stats1, s));
@@ -328,7 +330,7 @@ int forward_layer(axonn_stage* st, int l, const LayerStash& a, bf16_t* z, hipStr
 int forward_layers(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s) {
   const int L = st->cfg.n_layers;
   for (int l = 0; l < L; ++l)
-    AX_TRY(forward_layer(st, l, slot.layers[l], (l + 1 < L) ? slot.layers[l + 1].x : (bf16_t*)y_out, s));
+    AX_TRY(forward_layer(st, l, slot.layers[l], (l + 1 < L) ? slot.layers[l + 1].x : (elem_t*)y_out, s));
   return AXONN_OK;
 }
 
@@ -338,11 +340,11 @@ int forward_layers_ckpt(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s)
   const int L = st->cfg.n_layers, ac = st->cfg.ckpt_stride;
   ActSet& F = st->fwd_sets[st->fwd_set_rr++ % st->fwd_sets.size()];
   if (F.released_recorded) HIP_TRY(hipStreamWaitEvent(s, F.released, 0));
-  bf16_t* const xb[2] = {F.layers[0].x, F.x2};
+  elem_t* const xb[2] = {F.layers[0].x, F.x2};
   for (int l = 0; l < L; ++l) {
     LayerStash a = F.layers[0];
     a.x = (l % ac == 0) ? slot.layers[l].x : xb[l & 1];
-    bf16_t* z = (l + 1 == L) ? (bf16_t*)y_out : ((l + 1) % ac == 0) ? slot.layers[l + 1].x : xb[(l + 1) & 1];
+    elem_t* z = (l + 1 == L) ? (elem_t*)y_out : ((l + 1) % ac == 0) ? slot.layers[l + 1].x : xb[(l + 1) & 1];
     AX_TRY(forward_layer(st, l, a, z, s));
   }
   HIP_TRY(hipEventRecord(F.released, s));
@@ -353,9 +355,9 @@ int forward_layers_ckpt(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s)
 // ------------------------------------------------------------------ backward of a layer
 // Given dL/d(output) in a.dz, writes dL/d(input) to d_out, the output gradients of the four linear maps
 // to a.dpre, a.dy_mid, a.dqkv (a.dz is the fourth) and adds the bias / LayerNorm gradients.
-int backward_layer(axonn_stage* st, int l, const LayerStash& a, bf16_t* d_out, int acc, hipStream_t s) {
+int backward_layer(axonn_stage* st, int l, const LayerStash& a, elem_t* d_out, int acc, hipStream_t s) {
   const int T = st->T, h = st->h, f = st->f;
-  const bf16_t* d_in = a.dz;
+  const elem_t* d_in = a.dz;
   // z = y + g W2 + b2
   AX_TRY(gemm(true, true, EPI_DGELU, T, f, h, d_in, h, param_ptr(st, l, P_WFC2), h, a.dpre, f,
               nullptr, nullptr, 0, a.pre, f, 0, s));
@@ -391,10 +393,10 @@ int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out
   // gradient and the caller may recycle its receive buffer
   {
     ProfScope ps(PC_COPY_IN, s);
-    HIP_TRY(hipMemcpyAsync(slot.layers[L - 1].dz, dy_in, (uint64_t)T * h * sizeof(bf16_t), hipMemcpyDeviceToDevice, s));
+    HIP_TRY(hipMemcpyAsync(slot.layers[L - 1].dz, dy_in, (uint64_t)T * h * sizeof(elem_t), hipMemcpyDeviceToDevice, s));
   }
   for (int l = L - 1; l >= 0; --l) {
-    AX_TRY(backward_layer(st, l, slot.layers[l], (l == 0) ? (bf16_t*)dx_out : slot.layers[l - 1].dz, acc, s));
+    AX_TRY(backward_layer(st, l, slot.layers[l], (l == 0) ? (elem_t*)dx_out : slot.layers[l - 1].dz, acc, s));
     if (last) HIP_TRY(hipEventRecord(st->chain_layer[l], s));
   }
   return AXONN_OK;
@@ -404,7 +406,7 @@ int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out
 // microbatches inside one contraction per weight (the token index of all of them is the
 // contraction index): dW = sum_mb x_mb^T dy_mb.  Runs on `s` after the chains it reads and after
 // the previous such pass (they update the same accumulators), then releases the slots.
-int gemm_seg(int epi, int M, int N, int K, const bf16_t* const* A, int64_t lda, const bf16_t* const* B,
+int gemm_seg(int epi, int M, int N, int K, const elem_t* const* A, int64_t lda, const elem_t* const* B,
              int64_t ldb, int n_seg, void* C, int64_t ldc, int accumulate, hipStream_t s) {
   GemmArgs g;
   memset(&g, 0, sizeof g);
@@ -420,7 +422,7 @@ int gemm_seg(int epi, int M, int N, int K, const bf16_t* const* A, int64_t lda, 
 int wgrad_layer(axonn_stage* st, int l, const LayerStash* const* rec, int n, int acc, hipStream_t s) {
   const int T = st->T, h = st->h, f = st->f;
   const int epi = st->cfg.grad_accum_fp32 ? EPI_ACC_F32 : EPI_ACC_BF16;
-  const bf16_t *A[kMaxKSegments], *B[kMaxKSegments];
+  const elem_t *A[kMaxKSegments], *B[kMaxKSegments];
   for (int i = 0; i < n; ++i) { A[i] = rec[i]->g; B[i] = rec[i]->dz; }
   AX_TRY(gemm_seg(epi, f, h, T, A, f, B, h, n, grad_ptr(st, l, P_WFC2), h, acc, s));
   for (int i = 0; i < n; ++i) { A[i] = rec[i]->w; B[i] = rec[i]->dpre; }
@@ -439,7 +441,7 @@ int finish_layer_grads(axonn_stage* st, int l, hipStream_t s) {
     const uint64_t lo = st->tensors[l * kTensorsPerLayer].offset;
     const uint64_t hi = (l + 1 < st->cfg.n_layers) ? st->tensors[(l + 1) * kTensorsPerLayer].offset : st->n_params;
     ProfScope ps(PC_GRAD_CONVERT, s);
-    AX_TRY(check_launch(launch_f32_to_bf16(hi - lo, st->grads32 + lo, st->grads + lo, s), "f32_to_bf16"));
+    AX_TRY(check_launch(launch_f32_to_elem(hi - lo, st->grads32 + lo, st->grads + lo, s), "f32_to_bf16"));
   }
   HIP_TRY(hipEventRecord(st->grads_final[l], s));
   return AXONN_OK;
@@ -501,14 +503,14 @@ int backward_layers_ckpt(axonn_stage* st, Slot& slot, const void* dy_in, void* d
     if (seg == L / ac - 1) {
       // the upstream gradient is an operand of the weight gradient, which may outlive the caller's buffer
       ProfScope ps(PC_COPY_IN, s);
-      HIP_TRY(hipMemcpyAsync(R.layers[ac - 1].dz, dy_in, (uint64_t)T * h * sizeof(bf16_t), hipMemcpyDeviceToDevice, s));
+      HIP_TRY(hipMemcpyAsync(R.layers[ac - 1].dz, dy_in, (uint64_t)T * h * sizeof(elem_t), hipMemcpyDeviceToDevice, s));
     }
     std::vector<LayerStash> rec(R.layers.begin(), R.layers.begin() + ac);
     rec[0].x = slot.layers[seg * ac].x;
     for (int i = 0; i < ac; ++i)
       AX_TRY(forward_layer(st, seg * ac + i, rec[i], (i + 1 < ac) ? rec[i + 1].x : nullptr, s));
     for (int i = ac - 1; i >= 0; --i) {
-      bf16_t* d_out = (i > 0) ? rec[i - 1].dz : (seg == 0) ? (bf16_t*)dx_out : Rnext.layers[ac - 1].dz;
+      elem_t* d_out = (i > 0) ? rec[i - 1].dz : (seg == 0) ? (elem_t*)dx_out : Rnext.layers[ac - 1].dz;
       AX_TRY(backward_layer(st, seg * ac + i, rec[i], d_out, acc, s));
     }
     HIP_TRY(hipEventRecord(R.chain_done, s));
@@ -565,7 +567,7 @@ int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s
   if (!slot) return fail(AXONN_ESTATE, "forward: no free stash slot");
   // the weight-gradient pass that read the slot's previous contents must have finished
   if (slot->released_recorded) HIP_TRY(hipStreamWaitEvent(s, slot->released, 0));
-  const uint64_t bytes = (uint64_t)st->T * st->h * sizeof(bf16_t);
+  const uint64_t bytes = (uint64_t)st->T * st->h * sizeof(elem_t);
   if (st->head) y = slot->head_y;   // the last stage's output goes to its own head, not onwards
   if (st->embed) {
     slot->tokens = (const int32_t*)x;
@@ -698,6 +700,7 @@ void destroy_stage(axonn_stage* st) {
   if (st->params) (void)hipFree(st->params);
   if (st->grads) (void)hipFree(st->grads);
   if (st->grads32) (void)hipFree(st->grads32);
+  if (st->nonfinite_ws) (void)hipFree(st->nonfinite_ws);
   delete st;
 }
 
@@ -735,12 +738,12 @@ int embed_forward(axonn_embed* e, const int32_t* tokens, void* x, hipStream_t s)
 }
 
 int embed_backward(axonn_embed* e, const int32_t* tokens, const void* dx, hipStream_t s) {
-  bf16_t* dwte = e->grads;
-  bf16_t* dwpe = e->grads + (uint64_t)e->vocab * e->h;
+  elem_t* dwte = e->grads;
+  elem_t* dwpe = e->grads + (uint64_t)e->vocab * e->h;
   const int acc = e->bwd_count > 0 ? 1 : 0;
   ProfScope ps(PC_EMBED, s);
   // the table kernel touches only the rows whose ids occur: the first pass of a batch clears the table
-  if (!acc) AX_TRY(check_launch(launch_fill_bf16((uint64_t)e->vocab * e->h, dwte, 0.0f, s), "fill"));
+  if (!acc) AX_TRY(check_launch(launch_fill_elem((uint64_t)e->vocab * e->h, dwte, 0.0f, s), "fill"));
   AX_TRY(check_launch(launch_embed_bwd(e->b, e->s, e->h, e->vocab, tokens, dx, dwte, dwpe, acc, s), "embed_bwd"));
   e->bwd_count++;
   return AXONN_OK;
@@ -751,19 +754,19 @@ int embed_backward(axonn_embed* e, const int32_t* tokens, const void* dx, hipStr
 int head_forward_backward(axonn_head* hd, const void* x, const int32_t* targets, float* loss, void* dx,
                           hipStream_t s) {
   const int T = hd->T, h = hd->h, V = hd->vocab;
-  bf16_t* g = hd->params;
-  bf16_t* bt = hd->params + h;
-  bf16_t* W = hd->params + 2 * (uint64_t)h;
+  elem_t* g = hd->params;
+  elem_t* bt = hd->params + h;
+  elem_t* W = hd->params + 2 * (uint64_t)h;
   const int acc = hd->count > 0 ? 1 : 0;
   AX_TRY(ln_fwd(T, h, x, g, bt, hd->eps, hd->a, nullptr, hd->stats, s));
   AX_TRY(gemm(true, false, EPI_BIAS, T, V, h, hd->a, h, W, V, hd->logits, V, nullptr, nullptr, 0, nullptr, 0, 0, s));
   {
     ProfScope ps(PC_XENT, s);
-    AX_TRY(check_launch(launch_xent(T, V, hd->logits, targets, hd->M, hd->token_loss, loss, s), "cross_entropy"));
+    AX_TRY(check_launch(launch_xent(T, V, hd->logits, targets, hd->M, hd->loss_scale, hd->token_loss, loss, s), "cross_entropy"));
   }
   {
-    const bf16_t* A[1] = {hd->a};
-    const bf16_t* B[1] = {hd->logits};
+    const elem_t* A[1] = {hd->a};
+    const elem_t* B[1] = {hd->logits};
     AX_TRY(gemm_seg(EPI_ACC_BF16, h, V, T, A, h, B, V, 1, hd->grads + 2 * (uint64_t)h, V, acc, s));
   }
   AX_TRY(gemm(true, true, EPI_BIAS, T, h, V, hd->logits, V, W, V, hd->da, h, nullptr, nullptr, 0, nullptr, 0, 0, s));
@@ -835,17 +838,17 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
                        #expr, hipGetErrorString(e_)));                                           \
   } while (0)
 
-  CREATE_TRY(hipMalloc((void**)&st->params, st->n_params * sizeof(bf16_t)));
-  CREATE_TRY(hipMalloc((void**)&st->grads, st->n_params * sizeof(bf16_t)));
-  CREATE_TRY(hipMemset(st->params, 0, st->n_params * sizeof(bf16_t)));
-  CREATE_TRY(hipMemset(st->grads, 0, st->n_params * sizeof(bf16_t)));
+  CREATE_TRY(hipMalloc((void**)&st->params, st->n_params * sizeof(elem_t)));
+  CREATE_TRY(hipMalloc((void**)&st->grads, st->n_params * sizeof(elem_t)));
+  CREATE_TRY(hipMemset(st->params, 0, st->n_params * sizeof(elem_t)));
+  CREATE_TRY(hipMemset(st->grads, 0, st->n_params * sizeof(elem_t)));
   if (cfg->grad_accum_fp32) {
     CREATE_TRY(hipMalloc((void**)&st->grads32, st->n_params * sizeof(float)));
     CREATE_TRY(hipMemset(st->grads32, 0, st->n_params * sizeof(float)));
   }
   for (int l = 0; l < cfg->n_layers; ++l) {
-    CREATE_TRY(launch_fill_bf16(h, param_ptr(st, l, P_LN1G), 1.0f, nullptr));
-    CREATE_TRY(launch_fill_bf16(h, param_ptr(st, l, P_LN2G), 1.0f, nullptr));
+    CREATE_TRY(launch_fill_elem(h, param_ptr(st, l, P_LN1G), 1.0f, nullptr));
+    CREATE_TRY(launch_fill_elem(h, param_ptr(st, l, P_LN2G), 1.0f, nullptr));
   }
 
   // activation stash: per layer x,u,o,y,w [T,h], qkv [T,3h], pre (GeLU' of the pre-activation),g [T,f],
@@ -857,14 +860,14 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
   const uint64_t per_layer = (cfg->qkv_input_split ? 8 : 7) * e_th + 2 * e_t3h + 3 * e_tf + 2 * e_st + e_lse;
   // carves one layer's record out of p
   auto carve = [&](char*& p, LayerStash& a) {
-    a.x = (bf16_t*)p; p += e_th;  a.u = (bf16_t*)p; p += e_th;  a.o = (bf16_t*)p; p += e_th;
-    a.y = (bf16_t*)p; p += e_th;  a.w = (bf16_t*)p; p += e_th;  a.qkv = (bf16_t*)p; p += e_t3h;
-    a.pre = (bf16_t*)p; p += e_tf; a.g = (bf16_t*)p; p += e_tf;
+    a.x = (elem_t*)p; p += e_th;  a.u = (elem_t*)p; p += e_th;  a.o = (elem_t*)p; p += e_th;
+    a.y = (elem_t*)p; p += e_th;  a.w = (elem_t*)p; p += e_th;  a.qkv = (elem_t*)p; p += e_t3h;
+    a.pre = (elem_t*)p; p += e_tf; a.g = (elem_t*)p; p += e_tf;
     a.stats1 = (float*)p; p += e_st; a.stats2 = (float*)p; p += e_st; a.lse = (float*)p; p += e_lse;
-    a.dz = (bf16_t*)p; p += e_th; a.dy_mid = (bf16_t*)p; p += e_th;
-    a.dpre = (bf16_t*)p; p += e_tf; a.dqkv = (bf16_t*)p; p += e_t3h;
+    a.dz = (elem_t*)p; p += e_th; a.dy_mid = (elem_t*)p; p += e_th;
+    a.dpre = (elem_t*)p; p += e_tf; a.dqkv = (elem_t*)p; p += e_t3h;
     a.u_lo = nullptr;
-    if (cfg->qkv_input_split) { a.u_lo = (bf16_t*)p; p += e_th; }
+    if (cfg->qkv_input_split) { a.u_lo = (elem_t*)p; p += e_th; }
   };
   const int ac = cfg->ckpt_stride;
   st->slot_bytes = ac > 0 ? (uint64_t)(cfg->n_layers / ac) * e_th : per_layer * cfg->n_layers;
@@ -881,7 +884,7 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
       if (ac > 0) {
         // only the inputs of layers 0, ac, 2ac, ... are kept (Sec. 5.1)
         memset(&a, 0, sizeof a);
-        if (l % ac == 0) { a.x = (bf16_t*)p; p += e_th; }
+        if (l % ac == 0) { a.x = (elem_t*)p; p += e_th; }
       } else {
         carve(p, a);
       }
@@ -900,7 +903,7 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
       a.layers.resize(n_layers);
       char* p = a.base;
       for (LayerStash& l : a.layers) carve(p, l);
-      if (second_x) { a.x2 = (bf16_t*)p; p += e_th; }
+      if (second_x) { a.x2 = (elem_t*)p; p += e_th; }
       return hipSuccess;
     };
     st->fwd_sets.resize(2);
@@ -915,7 +918,7 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
   CREATE_TRY(hipMalloc((void**)&st->ws_base, st->ws_bytes));
   {
     char* p = st->ws_base;
-    st->dw = (bf16_t*)p; p += e_th; st->dattn = (bf16_t*)p; p += e_th; st->du = (bf16_t*)p; p += e_th;
+    st->dw = (elem_t*)p; p += e_th; st->dattn = (elem_t*)p; p += e_th; st->du = (elem_t*)p; p += e_th;
     st->delta = (float*)p; p += e_lse; st->red_ws = (float*)p; p += e_red;
   }
   CREATE_TRY(hipEventCreateWithFlags(&st->last_bwd, hipEventDisableTiming));
@@ -1204,7 +1207,7 @@ int axonn_offload_adam_create(int32_t device, uint64_t n, uint64_t bucket_elems,
   axonn_offload_adam* o = new (std::nothrow) axonn_offload_adam();
   if (!o) return fail(AXONN_ENOMEM, "adam_create: host allocation failed");
   o->device = device; o->n = n; o->bucket = std::min<uint64_t>(bucket_elems, align_up(n, 8));
-  o->p16 = (bf16_t*)param16_dev; o->g16 = (const bf16_t*)grad16_dev;
+  o->p16 = (elem_t*)param16_dev; o->g16 = (const elem_t*)grad16_dev;
   o->h_theta = host_master; o->h_m = host_m; o->h_v = host_v;
 #define ADAM_TRY(expr)                                                                           \
   do {                                                                                           \
@@ -1369,6 +1372,73 @@ int axonn_stage_optimizer_step_overlapped(axonn_stage_t* st, double lr, double b
                    chunk_buckets, &gate, early);
 }
 
+// ------------------------------------------------------------- loss scaling (Sec. 2, mixed precision)
+int32_t axonn_element_type(void) { return AXONN_ELEM_TYPE_ID; }
+
+int axonn_count_nonfinite(const void* x_dev, uint64_t n, uint64_t* workspace_dev, void* hip_stream) {
+  if (!x_dev || !workspace_dev) return fail(AXONN_EINVAL, "count_nonfinite: null argument");
+  return check_launch(launch_count_nonfinite(n, x_dev, workspace_dev, (hipStream_t)hip_stream), "count_nonfinite");
+}
+
+// Orders `user` behind the batch's gradients, as the optimizer entry points do.
+static int wait_for_gradients(axonn_stage_t* st, hipStream_t user, const char* who) {
+  if (st->in_flight) return fail(AXONN_ESTATE, "%s: %d microbatches in flight", who, st->in_flight);
+  if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(user, st->last_bwd, 0));
+  if (st->last_wgrad_recorded) HIP_TRY(hipStreamWaitEvent(user, st->last_wgrad, 0));
+  if (count_state(st, SLOT_AWAIT_WGRAD))
+    return fail(AXONN_ESTATE, "%s: %d microbatches still await their weight gradients (fewer than "
+                "n_microbatches backwards since zero_grad)", who, count_state(st, SLOT_AWAIT_WGRAD));
+  return AXONN_OK;
+}
+
+int axonn_stage_count_nonfinite_grads(axonn_stage_t* st, void* hip_stream, uint64_t* count_host) {
+  if (!st || !count_host) return fail(AXONN_EINVAL, "count_nonfinite_grads: null argument");
+  HIP_TRY(hipSetDevice(st->cfg.device));
+  hipStream_t user = (hipStream_t)hip_stream;
+  AX_TRY(wait_for_gradients(st, user, "count_nonfinite_grads"));
+  if (!st->nonfinite_ws) HIP_TRY(hipMalloc((void**)&st->nonfinite_ws, kNonfiniteWsCounters * sizeof(uint64_t)));
+  AX_TRY(check_launch(launch_count_nonfinite(st->n_params, st->grads, st->nonfinite_ws, user), "count_nonfinite"));
+  HIP_TRY(hipMemcpyAsync(count_host, st->nonfinite_ws + (kNonfiniteWsCounters - 1), sizeof(uint64_t),
+                         hipMemcpyDeviceToHost, user));
+  HIP_TRY(hipStreamSynchronize(user));
+  return AXONN_OK;
+}
+
+int axonn_stage_optimizer_step_scaled(axonn_stage_t* st, double lr, double beta1, double beta2, double eps,
+                                      double weight_decay, int64_t step, double grad_scale,
+                                      axonn_loss_scaler* scaler, uint64_t other_nonfinite, void* hip_stream,
+                                      int32_t* skipped) {
+  if (!st || !scaler || !skipped) return fail(AXONN_EINVAL, "optimizer_step_scaled: null argument");
+  if (!st->opt) return fail(AXONN_ESTATE, "optimizer_step_scaled: no optimizer attached");
+  if (!(scaler->scale > 0.f) || !(scaler->growth >= 1.f) || !(scaler->backoff > 0.f && scaler->backoff <= 1.f) ||
+      scaler->growth_interval < 1 || scaler->good_steps < 0)
+    return fail(AXONN_EINVAL, "optimizer_step_scaled: scaler needs scale > 0, growth >= 1, 0 < backoff <= 1, "
+                "growth_interval >= 1, good_steps >= 0");
+  uint64_t bad = 0;
+  AX_TRY(axonn_stage_count_nonfinite_grads(st, hip_stream, &bad));
+  if (bad + other_nonfinite != 0) {          // overflow somewhere: drop the batch, lower the scale
+    scaler->scale *= scaler->backoff;
+    scaler->good_steps = 0;
+    *skipped = 1;
+    return AXONN_OK;
+  }
+  *skipped = 0;
+  AX_TRY(axonn_stage_optimizer_step(st, lr, beta1, beta2, eps, weight_decay, step, grad_scale / scaler->scale,
+                                    hip_stream));
+  if (++scaler->good_steps >= scaler->growth_interval) {
+    scaler->scale *= scaler->growth;
+    scaler->good_steps = 0;
+  }
+  return AXONN_OK;
+}
+
+int axonn_head_set_loss_scale(axonn_head_t* hd, float loss_scale) {
+  if (!hd) return fail(AXONN_EINVAL, "head_set_loss_scale: null handle");
+  if (!(loss_scale > 0.f) || loss_scale > 3.0e38f) return fail(AXONN_EINVAL, "head_set_loss_scale: scale must be positive and finite");
+  hd->loss_scale = loss_scale;
+  return AXONN_OK;
+}
+
 // ------------------------------------------------------------- first / last stage extras
 int axonn_embed_create(int32_t device, int32_t vocab, int32_t hidden, int32_t seq_len, int32_t microbatch_size,
                        axonn_embed_t** out) {
@@ -1382,10 +1452,10 @@ int axonn_embed_create(int32_t device, int32_t vocab, int32_t hidden, int32_t se
   if (!e) return fail(AXONN_ENOMEM, "embed_create: host allocation failed");
   e->device = device; e->vocab = vocab; e->h = hidden; e->s = seq_len; e->b = microbatch_size;
   e->n_params = ((uint64_t)vocab + seq_len) * hidden;
-  hipError_t err = hipMalloc((void**)&e->params, e->n_params * sizeof(bf16_t));
-  if (err == hipSuccess) err = hipMalloc((void**)&e->grads, e->n_params * sizeof(bf16_t));
-  if (err == hipSuccess) err = hipMemset(e->params, 0, e->n_params * sizeof(bf16_t));
-  if (err == hipSuccess) err = hipMemset(e->grads, 0, e->n_params * sizeof(bf16_t));
+  hipError_t err = hipMalloc((void**)&e->params, e->n_params * sizeof(elem_t));
+  if (err == hipSuccess) err = hipMalloc((void**)&e->grads, e->n_params * sizeof(elem_t));
+  if (err == hipSuccess) err = hipMemset(e->params, 0, e->n_params * sizeof(elem_t));
+  if (err == hipSuccess) err = hipMemset(e->grads, 0, e->n_params * sizeof(elem_t));
   if (err != hipSuccess) {
     if (e->params) (void)hipFree(e->params);
     if (e->grads) (void)hipFree(e->grads);
@@ -1447,12 +1517,12 @@ int axonn_head_create(int32_t device, int32_t vocab, int32_t hidden, int32_t tok
   const uint64_t e_th = align_up(T * h * 2, 256), e_tv = align_up(T * V * 2, 256), e_st = align_up(T * 2 * 4, 256),
                  e_tl = align_up(T * 4, 256), e_red = align_up(2 * ((T + 63) / 64) * h * 4, 256);
   hd->ws_bytes = 2 * e_th + e_tv + e_st + e_tl + e_red;
-  hipError_t err = hipMalloc((void**)&hd->params, hd->n_params * sizeof(bf16_t));
-  if (err == hipSuccess) err = hipMalloc((void**)&hd->grads, hd->n_params * sizeof(bf16_t));
+  hipError_t err = hipMalloc((void**)&hd->params, hd->n_params * sizeof(elem_t));
+  if (err == hipSuccess) err = hipMalloc((void**)&hd->grads, hd->n_params * sizeof(elem_t));
   if (err == hipSuccess) err = hipMalloc((void**)&hd->ws_base, hd->ws_bytes);
-  if (err == hipSuccess) err = hipMemset(hd->params, 0, hd->n_params * sizeof(bf16_t));
-  if (err == hipSuccess) err = hipMemset(hd->grads, 0, hd->n_params * sizeof(bf16_t));
-  if (err == hipSuccess) err = launch_fill_bf16(h, hd->params, 1.0f, nullptr);   // LayerNorm gain 1
+  if (err == hipSuccess) err = hipMemset(hd->params, 0, hd->n_params * sizeof(elem_t));
+  if (err == hipSuccess) err = hipMemset(hd->grads, 0, hd->n_params * sizeof(elem_t));
+  if (err == hipSuccess) err = launch_fill_elem(h, hd->params, 1.0f, nullptr);   // LayerNorm gain 1
   if (err == hipSuccess) err = hipDeviceSynchronize();
   if (err != hipSuccess) {
     if (hd->params) (void)hipFree(hd->params);
@@ -1462,7 +1532,7 @@ int axonn_head_create(int32_t device, int32_t vocab, int32_t hidden, int32_t tok
     return fail(err == hipErrorOutOfMemory ? AXONN_ENOMEM : AXONN_EHIP, "head_create: %s", hipGetErrorString(err));
   }
   char* p = hd->ws_base;
-  hd->a = (bf16_t*)p; p += e_th; hd->da = (bf16_t*)p; p += e_th; hd->logits = (bf16_t*)p; p += e_tv;
+  hd->a = (elem_t*)p; p += e_th; hd->da = (elem_t*)p; p += e_th; hd->logits = (elem_t*)p; p += e_tv;
   hd->stats = (float*)p; p += e_st; hd->token_loss = (float*)p; p += e_tl; hd->red_ws = (float*)p; p += e_red;
   *out = hd;
   return AXONN_OK;
@@ -1515,7 +1585,7 @@ int axonn_stage_attach_ends(axonn_stage_t* st, axonn_embed_t* embed, axonn_head_
   if (head && !st->head_dx) {
     HIP_TRY(hipMalloc((void**)&st->head_dx, e_th));
     HIP_TRY(hipMalloc((void**)&st->head_y_base, e_th * st->slots.size()));
-    for (size_t i = 0; i < st->slots.size(); ++i) st->slots[i].head_y = (bf16_t*)((char*)st->head_y_base + i * e_th);
+    for (size_t i = 0; i < st->slots.size(); ++i) st->slots[i].head_y = (elem_t*)((char*)st->head_y_base + i * e_th);
   }
   st->embed = embed;
   st->head = head;

@@ -13,6 +13,8 @@ then the M upstream gradients dy with std `dy_std`.  Every value is rounded once
 bfloat16 (nearest, ties to even) and returned as float32.
 """
 from dataclasses import dataclass
+import os
+
 import numpy as np
 
 PARAM_NAMES = ("ln1_g", "ln1_b", "w_qkv", "b_qkv", "w_o", "b_o",
@@ -77,13 +79,28 @@ def snap_bf16(a):
     return from_bf16_bits(to_bf16_bits(a)).reshape(np.shape(a))
 
 
+def snap_fp16(a):
+    """Round a float32 array to IEEE half precision (nearest, ties to even; overflow to infinity), as float32."""
+    with np.errstate(over="ignore"):
+        return np.asarray(a, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
+# Element type of the library the process works with (AXONN_ELEM, as in binding.py): inputs are rounded to it.
+ELEM = os.environ.get("AXONN_ELEM", "bf16")
+
+
+def snap_elem(a):
+    """Round a float32 array to the 16-bit element type in use (bfloat16 unless AXONN_ELEM=fp16)."""
+    return snap_fp16(a) if ELEM == "fp16" else snap_bf16(a)
+
+
 def _normal(rng, shape, std, mean=0.0):
     a = rng.standard_normal(shape, dtype=np.float32)
     if std != 1.0:
         a *= np.float32(std)
     if mean != 0.0:
         a += np.float32(mean)
-    return snap_bf16(a)
+    return snap_elem(a)
 
 
 def make_stage_inputs(shape: StageShape, seed=0, perturb=False, weight_std=0.02,
@@ -149,5 +166,5 @@ def make_adam_inputs(n, seed=0, theta_std=0.02, grad_std=1e-3, m_std=1e-4, v_std
     else:
         m = rng.standard_normal(n, dtype=np.float32) * np.float32(m_std)
         v = np.abs(rng.standard_normal(n, dtype=np.float32) * np.float32(v_std))
-    g16 = snap_bf16(rng.standard_normal(n, dtype=np.float32) * np.float32(grad_std))
+    g16 = snap_elem(rng.standard_normal(n, dtype=np.float32) * np.float32(grad_std))
     return theta, m, v, g16

@@ -20,9 +20,8 @@ def _view(ptr, n, dtype):
 
 
 def view_bf16(ptr, n):
-    """bf16 torch view of `n` elements of library-owned device memory at `ptr`."""
-    import torch
-    return _view(ptr, n, torch.bfloat16)
+    """torch view (the library's 16-bit element type) of `n` elements of library-owned device memory at `ptr`."""
+    return _view(ptr, n, B.torch_elem_dtype())
 
 
 class Stage:
@@ -38,8 +37,8 @@ class Stage:
         for i in range(B.axonn_stage_num_tensors(self.handle)):
             name, off, dims = B.axonn_stage_param_layout(self.handle, i)
             self.layout[name] = (off, dims)
-        self.params = _view(B.axonn_stage_params(self.handle), self.n_params, torch.bfloat16)
-        self.grads = _view(B.axonn_stage_grads(self.handle), self.n_params, torch.bfloat16)
+        self.params = _view(B.axonn_stage_params(self.handle), self.n_params, B.torch_elem_dtype())
+        self.grads = _view(B.axonn_stage_grads(self.handle), self.n_params, B.torch_elem_dtype())
 
     def close(self):
         if self.handle:
@@ -59,11 +58,11 @@ class Stage:
         return (self.grads if grad else self.params)[off:off + n].view(*dims)
 
     def load_params(self, layers):
-        """layers: list of dicts name -> float32 numpy array of bf16-representable values."""
+        """layers: list of dicts name -> float32 numpy array of values representable in the element type."""
         import torch
         for li, p in enumerate(layers):
             for name, arr in p.items():
-                t = torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(torch.bfloat16)
+                t = torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(B.torch_elem_dtype())
                 self.tensor("layer%d.%s" % (li, name)).copy_(t)
         torch.cuda.synchronize()
 

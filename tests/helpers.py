@@ -22,9 +22,16 @@ def rel_fro(got, ref):
 
 
 def dev_bf16(a):
-    """float32 numpy array holding bf16-representable values -> bf16 cuda tensor."""
+    """float32 numpy array holding values of the library's 16-bit element type (bf16, or fp16 under
+    AXONN_ELEM=fp16) -> cuda tensor of that type."""
     import torch
-    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(torch.bfloat16).cuda()
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(B.torch_elem_dtype()).cuda()
+
+
+def round_elem(x):
+    """The oracle's rounding to the library's 16-bit element type."""
+    import oracle
+    return oracle.half_round(x, B.ELEM)
 
 
 def dev_f32(a):

@@ -69,8 +69,8 @@ def test_full_size_stage_parity(name, ac):
     with Stage(sh, **opts) as st:
         st.load_params(layers)
         bsh = (sh.microbatch_size, sh.seq_len, sh.hidden)
-        X = [dev_bf16(xs[0])] + [torch.randn(bsh, device="cuda").to(torch.bfloat16) for _ in range(M - 1)]
-        DY = [dev_bf16(dys[0])] + [torch.randn(bsh, device="cuda").to(torch.bfloat16) for _ in range(M - 1)]
+        X = [dev_bf16(xs[0])] + [torch.randn(bsh, device="cuda").to(B.torch_elem_dtype()) for _ in range(M - 1)]
+        DY = [dev_bf16(dys[0])] + [torch.randn(bsh, device="cuda").to(B.torch_elem_dtype()) for _ in range(M - 1)]
         Y = [torch.zeros_like(X[0]) for _ in range(M)]
         DX = [torch.zeros_like(X[0]) for _ in range(M)]
         _say("%s: GPU batch of %d microbatches, message-driven, 2 streams" % (name, M))
@@ -129,19 +129,19 @@ def test_full_size_last_stage_head():
     T, h, V, M = 2048, 5120, 51200, 8
     rng = np.random.default_rng(0)
     _say("head: generating inputs")
-    from paper_2110_13005_amd.inputs import snap_bf16
+    from paper_2110_13005_amd.inputs import snap_elem
     from paper_2110_13005_amd.stage import view_bf16
-    x = snap_bf16(rng.standard_normal((1, T, h), dtype=np.float32))
-    W = snap_bf16(rng.standard_normal((h, V), dtype=np.float32) * np.float32(0.02))
-    g = snap_bf16((1 + 0.02 * rng.standard_normal(h)).astype(np.float32))
-    bt = snap_bf16((0.02 * rng.standard_normal(h)).astype(np.float32))
+    x = snap_elem(rng.standard_normal((1, T, h), dtype=np.float32))
+    W = snap_elem(rng.standard_normal((h, V), dtype=np.float32) * np.float32(0.02))
+    g = snap_elem((1 + 0.02 * rng.standard_normal(h)).astype(np.float32))
+    bt = snap_elem((0.02 * rng.standard_normal(h)).astype(np.float32))
     tg = rng.integers(0, V, (1, T))
     hd = B.axonn_head_create(0, V, h, T, M, EPS)
     try:
         p, gr, n = B.axonn_head_buffers(hd)
         params, grads = view_bf16(p, n), view_bf16(gr, n)
         params[:h] = dev_bf16(g); params[h:2 * h] = dev_bf16(bt); params[2 * h:] = dev_bf16(W).reshape(-1)
-        loss = torch.zeros(1, device="cuda"); dx = torch.zeros(T, h, dtype=torch.bfloat16, device="cuda")
+        loss = torch.zeros(1, device="cuda"); dx = torch.zeros(T, h, dtype=B.torch_elem_dtype(), device="cuda")
         X = dev_bf16(x); TG = torch.from_numpy(tg.astype(np.int32)).cuda()
         _say("head: GPU forward + loss + backward")
         B.axonn_head_forward_backward(hd, X, TG, loss, dx)
@@ -178,15 +178,15 @@ def test_full_size_offloaded_adam():
     ptrs = [B.axonn_pinned_alloc(4 * n) for _ in range(3)]
     arrs = [np.ctypeslib.as_array((ctypes.c_float * n).from_address(p)) for p in ptrs]
     g = torch.Generator(device="cuda"); g.manual_seed(0)
-    G16 = torch.empty(n, dtype=torch.bfloat16, device="cuda")
-    P16 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    G16 = torch.empty(n, dtype=B.torch_elem_dtype(), device="cuda")
+    P16 = torch.zeros(n, dtype=B.torch_elem_dtype(), device="cuda")
     step = 1 << 26
     for o in range(0, n, step):
         c = min(step, n - o)
         torch.from_numpy(arrs[0][o:o + c]).copy_(torch.randn(c, generator=g, device="cuda") * 0.02)
         torch.from_numpy(arrs[1][o:o + c]).copy_(torch.randn(c, generator=g, device="cuda") * 1e-4)
         torch.from_numpy(arrs[2][o:o + c]).copy_((torch.randn(c, generator=g, device="cuda") * 1e-6).abs())
-        G16[o:o + c] = (torch.randn(c, generator=g, device="cuda") * 1e-3).to(torch.bfloat16)
+        G16[o:o + c] = (torch.randn(c, generator=g, device="cuda") * 1e-3).to(B.torch_elem_dtype())
     torch.cuda.synchronize()
     # sampled ranges, inputs copied out before the step overwrites them
     rng = np.random.default_rng(0)
@@ -204,17 +204,17 @@ def test_full_size_offloaded_adam():
         _say("adam: step took %.3f s" % (time.time() - t0))
         worst = 0.0
         for (a, b), (th, m, v, g16) in zip(sample, before):
-            rt, rm, rv, r16 = oracle.adam_step(th, m, v, g16, oc["lr"], oc["beta1"], oc["beta2"], oc["eps"], oc["weight_decay"], oc["step"], oc["grad_scale"])
+            rt, rm, rv, r16 = oracle.adam_step(th, m, v, g16, oc["lr"], oc["beta1"], oc["beta2"], oc["eps"], oc["weight_decay"], oc["step"], oc["grad_scale"], half=B.ELEM)
             worst = max(worst, rel_fro(arrs[0][a:b], rt), rel_fro(arrs[1][a:b], rm), rel_fro(arrs[2][a:b], rv))
             got16 = P16[a:b].float().cpu().numpy()
-            assert np.array_equal(got16, oracle.bf16_round(arrs[0][a:b]))
+            assert np.array_equal(got16, oracle.half_round(arrs[0][a:b], B.ELEM))
             assert np.abs(got16 - r16).max() <= np.abs(r16).max() * 2.0 ** -7
         _say("adam: worst relative error %.2e" % worst)
         assert worst <= 1e-6
         # everything was touched exactly once: bf16 parameters are the rounding of the master copy
         for o in range(0, n, step):
             c = min(step, n - o)
-            assert torch.equal(P16[o:o + c].cpu(), torch.from_numpy(arrs[0][o:o + c]).to(torch.bfloat16))
+            assert torch.equal(P16[o:o + c].cpu(), torch.from_numpy(arrs[0][o:o + c]).to(B.torch_elem_dtype()))
     finally:
         B.axonn_offload_adam_destroy(opt)
         for p in ptrs:

@@ -7,7 +7,7 @@ import pytest
 from oracle import lm_ends as OE
 from oracle import transformer as OT
 from paper_2110_13005_amd import binding as B
-from paper_2110_13005_amd.inputs import StageShape, make_stage_inputs, make_lm_inputs, snap_bf16
+from paper_2110_13005_amd.inputs import StageShape, make_stage_inputs, make_lm_inputs, snap_elem
 from paper_2110_13005_amd.stage import Stage, view_bf16
 from helpers import rel_fro, dev_bf16, host, dev_i32, EmbedHandle, HeadHandle, oracle_model, FWD_TOL, GRAD_TOL, EPS
 
@@ -18,7 +18,7 @@ def test_embedding_forward_backward_with_repeated_and_out_of_range_ids():
     import torch
     rng = np.random.default_rng(0)
     V, h, s, b = 40, 136, 24, 3                    # few rows: many repeats; 136 columns: a ragged vector tail
-    wte, wpe = snap_bf16(rng.standard_normal((V, h), dtype=np.float32)), snap_bf16(rng.standard_normal((s, h), dtype=np.float32))
+    wte, wpe = snap_elem(rng.standard_normal((V, h), dtype=np.float32)), snap_elem(rng.standard_normal((s, h), dtype=np.float32))
     e = EmbedHandle(V, h, s, b, wte, wpe)
     try:
         tot_te, tot_pe = 0.0, 0.0
@@ -27,11 +27,11 @@ def test_embedding_forward_backward_with_repeated_and_out_of_range_ids():
             if it == 1:
                 tokens[0, 0], tokens[1, 3], tokens[2, 5] = -7, V, V + 1000      # clamped to 0, V-1, V-1
             clamped = np.clip(tokens, 0, V - 1)
-            x = torch.zeros(b, s, h, dtype=torch.bfloat16, device="cuda")
+            x = torch.zeros(b, s, h, dtype=B.torch_elem_dtype(), device="cuda")
             B.axonn_embed_forward(e.h, dev_i32(tokens), x)
             ref = OE.embedding_forward(clamped, wte, wpe)
             assert rel_fro(host(x), ref) <= 4e-3                               # one bf16 rounding of the sum
-            dx = snap_bf16(rng.standard_normal((b, s, h), dtype=np.float32))
+            dx = snap_elem(rng.standard_normal((b, s, h), dtype=np.float32))
             B.axonn_embed_backward(e.h, dev_i32(tokens), dev_bf16(dx))
             torch.cuda.synchronize()
             dte, dpe = OE.embedding_backward(dx, clamped, V, s)
@@ -42,7 +42,7 @@ def test_embedding_forward_backward_with_repeated_and_out_of_range_ids():
             if it == 0 and len(unused):
                 assert not gte[unused].any()                                   # rows nobody used stay exactly zero
         B.axonn_embed_zero_grad(e.h)                                           # the next pass overwrites
-        tokens = rng.integers(0, V, (b, s)); dx = snap_bf16(rng.standard_normal((b, s, h), dtype=np.float32))
+        tokens = rng.integers(0, V, (b, s)); dx = snap_elem(rng.standard_normal((b, s, h), dtype=np.float32))
         B.axonn_embed_backward(e.h, dev_i32(tokens), dev_bf16(dx))
         torch.cuda.synchronize()
         dte, dpe = OE.embedding_backward(dx, tokens, V, s)
@@ -57,14 +57,14 @@ def test_head_loss_and_backward(T, h, V, M):
     """Several row tiles and ragged tails in every dimension; gradients accumulate over M microbatches."""
     import torch
     rng = np.random.default_rng(T)
-    g = snap_bf16((1 + 0.1 * rng.standard_normal(h)).astype(np.float32)); bt = snap_bf16((0.1 * rng.standard_normal(h)).astype(np.float32))
-    W = snap_bf16((0.05 * rng.standard_normal((h, V))).astype(np.float32))
+    g = snap_elem((1 + 0.1 * rng.standard_normal(h)).astype(np.float32)); bt = snap_elem((0.1 * rng.standard_normal(h)).astype(np.float32))
+    W = snap_elem((0.05 * rng.standard_normal((h, V))).astype(np.float32))
     hd = HeadHandle(V, h, T, M, g, bt, W)
     try:
         tot = None
         for it in range(M):
-            x = snap_bf16(rng.standard_normal((1, T, h), dtype=np.float32)); tg = rng.integers(0, V, (1, T))
-            loss = torch.zeros(1, device="cuda"); dx = torch.zeros(T, h, dtype=torch.bfloat16, device="cuda")
+            x = snap_elem(rng.standard_normal((1, T, h), dtype=np.float32)); tg = rng.integers(0, V, (1, T))
+            loss = torch.zeros(1, device="cuda"); dx = torch.zeros(T, h, dtype=B.torch_elem_dtype(), device="cuda")
             B.axonn_head_forward_backward(hd.h, dev_bf16(x), dev_i32(tg), loss, dx)
             torch.cuda.synchronize()
             rl, c = OE.head_loss_forward(x, g, bt, W, tg, EPS, M)
@@ -138,7 +138,7 @@ def test_first_stage_and_last_stage_separately():
         with Stage(sh) as st:
             st.load_params(layers)
             B.axonn_stage_attach_ends(st.handle, e.h, None)
-            Y = [torch.zeros(sh.microbatch_size, sh.seq_len, sh.hidden, dtype=torch.bfloat16, device="cuda") for _ in range(M)]
+            Y = [torch.zeros(sh.microbatch_size, sh.seq_len, sh.hidden, dtype=B.torch_elem_dtype(), device="cuda") for _ in range(M)]
             TK = [dev_i32(t) for t in tokens]; DY = [dev_bf16(d) for d in dys]
             st.zero_grad()
             for i in range(M):

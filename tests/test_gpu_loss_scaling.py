@@ -1,0 +1,159 @@
+"""GPU parity of the loss-scaling pieces (paper Sec. 2, "Mixed precision": scaled loss, descaling optimizer) against
+the oracle: the non-finite count, the head's scaled gradient, the optimizer step under the dynamic scaler.  The tests
+run with either 16-bit element type; the last one needs half precision, where the scale decides whether small
+gradients survive."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+from oracle import lm_ends as OE
+from paper_2110_13005_amd import binding as B
+from paper_2110_13005_amd.inputs import CONFIGS, make_stage_inputs, snap_elem
+from paper_2110_13005_amd.stage import Stage
+from helpers import ADAM_TOL, EPS, GRAD_TOL, HeadHandle, dev_bf16, dev_i32, host, rel_fro, run_direct
+
+pytestmark = pytest.mark.gpu
+
+
+def _pinned_array(n):
+    ptr = B.axonn_pinned_alloc(4 * n)
+    arr = np.ctypeslib.as_array(ctypes.cast(ptr, ctypes.POINTER(ctypes.c_float)), shape=(n,))
+    return ptr, arr
+
+
+@pytest.mark.parametrize("n", [8, 1003, 65536 + 24, (1 << 21) + 5])
+def test_count_nonfinite(n):
+    """Planted infinities and NaNs, also in the tail that is not a multiple of the vector width."""
+    import torch
+    rng = np.random.default_rng(n)
+    a = snap_elem(rng.standard_normal(n).astype(np.float32))
+    idx = np.unique(np.concatenate([rng.integers(0, n, min(n, 37)), [0, n - 1, n - (n % 8 or 1)]]))
+    a[idx[0::3]] = np.inf; a[idx[1::3]] = -np.inf; a[idx[2::3]] = np.nan
+    x = dev_bf16(a)
+    ws = torch.full((1025,), -1, dtype=torch.int64, device="cuda")
+    B.axonn_count_nonfinite(x, n, ws)
+    torch.cuda.synchronize()
+    assert ws[1024].item() == oracle.nonfinite_count(a) == len(idx)
+    B.axonn_count_nonfinite(dev_bf16(snap_elem(rng.standard_normal(n).astype(np.float32))), n, ws)
+    torch.cuda.synchronize()
+    assert ws[1024].item() == 0
+
+
+def test_element_type_matches_the_build():
+    assert B.axonn_element_type() == (1 if B.ELEM == "fp16" else 0)
+
+
+def test_head_loss_scale_scales_gradients_not_loss():
+    import torch
+    T, h, V, M, S = 264, 128, 520, 2, 1024.0
+    rng = np.random.default_rng(5)
+    g = snap_elem((1 + 0.1 * rng.standard_normal(h)).astype(np.float32)); bt = snap_elem((0.1 * rng.standard_normal(h)).astype(np.float32))
+    W = snap_elem((0.05 * rng.standard_normal((h, V))).astype(np.float32))
+    x = snap_elem(rng.standard_normal((1, T, h), dtype=np.float32)); tg = rng.integers(0, V, (1, T))
+    rl, c = OE.head_loss_forward(x, g, bt, W, tg, EPS, M)
+    rdx, rg = OE.head_loss_backward(c, g, W, tg, M)
+    hd = HeadHandle(V, h, T, M, g, bt, W)
+    try:
+        with pytest.raises(B.AxonnError):
+            B.axonn_head_set_loss_scale(hd.h, 0.0)
+        with pytest.raises(B.AxonnError):
+            B.axonn_head_set_loss_scale(hd.h, float("inf"))
+        B.axonn_head_set_loss_scale(hd.h, S)
+        loss = torch.zeros(1, device="cuda"); dx = torch.zeros(T, h, dtype=B.torch_elem_dtype(), device="cuda")
+        B.axonn_head_forward_backward(hd.h, dev_bf16(x), dev_i32(tg), loss, dx)
+        torch.cuda.synchronize()
+        assert abs(loss.item() - rl) <= 2e-3 * abs(rl)
+        assert rel_fro(host(dx).reshape(rdx.shape), S * rdx) <= GRAD_TOL
+        got = hd.grads_numpy()
+        for k in rg:
+            assert rel_fro(got[k], S * rg[k]) <= GRAD_TOL, k
+    finally:
+        hd.close()
+
+
+def test_optimizer_step_under_the_dynamic_loss_scale():
+    """Batches whose upstream gradients carry the scale; a planted overflow; growth after two good batches: the
+    master state, the 16-bit parameters and the scaler follow the oracle's at every step."""
+    import torch
+    sh = CONFIGS["tiny"]
+    M = sh.n_microbatches
+    layers, xs, dys = make_stage_inputs(sh, seed=3, perturb=True)
+    hyper = (1e-3, 0.9, 0.999, 1e-8, 0.01)
+    sc = B.axonn_loss_scaler(scale=64.0, growth=2.0, backoff=0.5, growth_interval=2, good_steps=0)
+    ref_sc = dict(scale=64.0, growth=2.0, backoff=0.5, growth_interval=2, good_steps=0)
+    with Stage(sh) as st:
+        st.load_params(layers)
+        n = st.n_params
+        ptrs, arrs = zip(*[_pinned_array(n) for _ in range(3)])
+        arrs[0][:] = st.params.float().cpu().numpy(); arrs[1][:] = 0; arrs[2][:] = 0
+        B.axonn_stage_optimizer_attach(st.handle, ptrs[0], ptrs[1], ptrs[2], n, 1 << 18)
+        th, m, v = arrs[0].astype(np.float64), np.zeros(n), np.zeros(n)
+        step = 1
+        for k, plant in enumerate([False, False, True, False, False]):
+            S = sc.scale
+            assert S == ref_sc["scale"]
+            run_direct(st, xs, [snap_elem((d * S).astype(np.float32)) for d in dys])
+            if plant:
+                st.grads[n // 3] = float("inf")
+                torch.cuda.synchronize()
+            g16 = st.grads.float().cpu().numpy()
+            assert B.axonn_stage_count_nonfinite_grads(st.handle) == oracle.nonfinite_count(g16) == (1 if plant else 0)
+            before16 = host(st.params).copy()
+            skipped = B.axonn_stage_optimizer_step_scaled(st.handle, *hyper, step, 1.0 / M, sc)
+            torch.cuda.synchronize()
+            ref_sc, th, m, v, r16, r_skipped = oracle.loss_scaled_adam_step(ref_sc, th, m, v, g16, *hyper, step, 1.0 / M,
+                                                                            half=B.ELEM)
+            assert skipped == r_skipped == plant
+            assert (sc.scale, sc.good_steps) == (ref_sc["scale"], ref_sc["good_steps"]), k
+            assert rel_fro(arrs[0], th) <= ADAM_TOL and rel_fro(arrs[1], m) <= ADAM_TOL and rel_fro(arrs[2], v) <= ADAM_TOL
+            if skipped:
+                assert np.array_equal(host(st.params), before16)
+            else:
+                assert np.array_equal(host(st.params), oracle.half_round(arrs[0], B.ELEM).astype(np.float64))
+                step += 1
+        assert [sc.scale, sc.good_steps] == [128.0, 0]     # 64 -> 128 after two good batches, -> 64 on the overflow, -> 128 after two more
+    for p in ptrs:
+        B.axonn_pinned_free(p)
+
+
+def test_scaler_arguments_are_checked():
+    sh = CONFIGS["tiny"]
+    with Stage(sh) as st:
+        bad = B.axonn_loss_scaler(scale=0.0, growth=2.0, backoff=0.5, growth_interval=2, good_steps=0)
+        with pytest.raises(B.AxonnError):      # no optimizer attached comes first
+            B.axonn_stage_optimizer_step_scaled(st.handle, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0, bad)
+        n = st.n_params
+        ptrs, arrs = zip(*[_pinned_array(n) for _ in range(3)])
+        B.axonn_stage_optimizer_attach(st.handle, ptrs[0], ptrs[1], ptrs[2], n, 1 << 18)
+        for kw in (dict(scale=0.0), dict(growth=0.5), dict(backoff=0.0), dict(backoff=1.5), dict(growth_interval=0)):
+            args = dict(scale=1.0, growth=2.0, backoff=0.5, growth_interval=2, good_steps=0); args.update(kw)
+            with pytest.raises(B.AxonnError):
+                B.axonn_stage_optimizer_step_scaled(st.handle, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0, B.axonn_loss_scaler(**args))
+    for p in ptrs:
+        B.axonn_pinned_free(p)
+
+
+@pytest.mark.skipif(B.ELEM != "fp16", reason="underflow of small gradients is a property of half precision")
+def test_loss_scale_rescues_small_gradients_in_half_precision():
+    """Upstream gradients of size 1e-6: in half precision the backward pass loses them to underflow (activation
+    gradients fall below 2^-24 in places, weight-gradient sums lose most of their bits); multiplied by 2^14 they
+    come through within the gradient bound, and the descaled values are those of the oracle."""
+    sh = CONFIGS["tiny"]
+    layers, xs, dys = make_stage_inputs(sh, seed=9, perturb=True, dy_std=1.0)
+    small = [(d * np.float32(1e-6)) for d in dys]
+    ref = oracle.stage_batch(xs, small, layers, sh.n_heads, EPS)
+    S = 2.0 ** 14
+    def worst(scale):
+        with Stage(sh) as st:
+            st.load_params(layers)
+            _, dxs, grads = run_direct(st, xs, [snap_elem((d * np.float32(scale)).astype(np.float32)) for d in small])
+        e = max(rel_fro(np.asarray(o) / scale, r.reshape(np.shape(o))) for o, r in zip(dxs, ref[1]))
+        for li, g in enumerate(grads):
+            for name, arr in g.items():
+                e = max(e, rel_fro(arr / scale, ref[2][li][name]))
+        return e
+    e_scaled, e_plain = worst(S), worst(1.0)
+    assert e_scaled <= GRAD_TOL, e_scaled
+    assert e_plain > 3 * GRAD_TOL, e_plain

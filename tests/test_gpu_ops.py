@@ -12,7 +12,7 @@ import pytest
 import oracle
 from oracle import transformer as OT
 from paper_2110_13005_amd import binding as B
-from paper_2110_13005_amd.inputs import snap_bf16
+from paper_2110_13005_amd.inputs import snap_elem
 from helpers import rel_fro, dev_bf16, dev_f32, host
 
 pytestmark = pytest.mark.gpu
@@ -20,7 +20,7 @@ TOL = 5e-3
 
 
 def _rng_bf16(rng, shape, std=1.0):
-    return snap_bf16((rng.standard_normal(shape) * std).astype(np.float32))
+    return snap_elem((rng.standard_normal(shape) * std).astype(np.float32))
 
 
 # ------------------------------------------------------------------------- GEMM
@@ -54,14 +54,14 @@ def test_gemm_forward_layout_bias_res_gelu(M, N, K):
     res = _rng_bf16(rng, (M, N))
     ref = x.astype(np.float64) @ w.astype(np.float64) + bias
     dx, dw, db, dr = dev_bf16(x), dev_bf16(w), dev_bf16(bias), dev_bf16(res)
-    out = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    out = torch.empty(M, N, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, dx, K, dw, N, out, N, bias=db)
     assert rel_fro(host(out), ref) < TOL
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, dx, K, dw, N, out, N, bias=None)
     assert rel_fro(host(out), ref - bias) < TOL
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS_RES, M, N, K, dx, K, dw, N, out, N, bias=db, res=dr, ld_res=N)
     assert rel_fro(host(out), ref + res) < TOL
-    pre = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    pre = torch.empty(M, N, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS_GELU, M, N, K, dx, K, dw, N, out, N, bias=db, aux=pre, ld_aux=N)
     torch.cuda.synchronize()
     assert rel_fro(host(pre), OT.gelu_grad(ref)) < TOL      # the epilogue stores GeLU'(z) in place of z
@@ -76,7 +76,7 @@ def test_gemm_dgrad_layout_plain_and_dgelu(M, N, K):
     dy = _rng_bf16(rng, (M, K)); w = _rng_bf16(rng, (N, K), 0.05); pre = _rng_bf16(rng, (M, N))
     ref = dy.astype(np.float64) @ w.astype(np.float64).T
     a, b, p = dev_bf16(dy), dev_bf16(w), dev_bf16(pre)
-    out = torch.empty(M, N, dtype=torch.bfloat16, device="cuda")
+    out = torch.empty(M, N, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_gemm_bf16(1, 1, B.EPI_BIAS, M, N, K, a, K, b, K, out, N)
     assert rel_fro(host(out), ref) < TOL
     B.axonn_gemm_bf16(1, 1, B.EPI_DGELU, M, N, K, a, K, b, K, out, N, aux=p, ld_aux=N)
@@ -96,7 +96,7 @@ def test_gemm_wgrad_layout_accumulate(M, N, K):
     assert rel_fro(host(c32), ref) < 1e-5
     B.axonn_gemm_bf16(0, 0, B.EPI_ACC_F32, M, N, K, a, M, b, N, c32, N, accumulate=1)
     assert rel_fro(host(c32), 2 * ref) < 1e-5
-    c16 = torch.full((M, N), 7.0, dtype=torch.bfloat16, device="cuda")
+    c16 = torch.full((M, N), 7.0, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_gemm_bf16(0, 0, B.EPI_ACC_BF16, M, N, K, a, M, b, N, c16, N, accumulate=0)
     first = host(c16)
     assert rel_fro(first, ref) < TOL
@@ -117,7 +117,7 @@ def test_gemm_big_tile_strided_operands():
         abuf = _rng_bf16(rng, (ash[0], lda)); bbuf = _rng_bf16(rng, (bsh[0], ldb), 0.05)
         am, bm = abuf[:, :ash[1]].astype(np.float64), bbuf[:, :bsh[1]].astype(np.float64)
         ref = (am if a_kc else am.T) @ (bm.T if b_kc else bm)
-        out = torch.zeros(M, ldc, dtype=torch.bfloat16, device="cuda")
+        out = torch.zeros(M, ldc, dtype=B.torch_elem_dtype(), device="cuda")
         B.axonn_gemm_bf16(a_kc, b_kc, epi, M, N, K, dev_bf16(abuf), lda, dev_bf16(bbuf), ldb, out, ldc)
         assert rel_fro(host(out)[:, :N], ref) < TOL, (a_kc, b_kc)
         assert not host(out)[:, N:].any()
@@ -146,7 +146,7 @@ def test_gemm_strided_operands_and_run_to_run_determinism():
     abuf = _rng_bf16(rng, (M, lda)); bbuf = _rng_bf16(rng, (K, ldb), 0.05)
     ref = abuf[:, :K].astype(np.float64) @ bbuf[:, :N].astype(np.float64)
     a, b = dev_bf16(abuf), dev_bf16(bbuf)
-    out = torch.zeros(M, ldc, dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros(M, ldc, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, a, lda, b, ldb, out, ldc)
     first = out.clone()
     assert rel_fro(host(out)[:, :N], ref) < TOL
@@ -161,23 +161,23 @@ def test_gemm_strided_operands_and_run_to_run_determinism():
 def test_layernorm_fwd_bwd(T, h):
     import torch
     rng = np.random.default_rng(T + h)
-    x = _rng_bf16(rng, (T, h), 2.0) + snap_bf16(np.float32(0.5))
-    x = snap_bf16(x)
-    g = _rng_bf16(rng, (h,), 0.2) + 1; g = snap_bf16(g)
+    x = _rng_bf16(rng, (T, h), 2.0) + snap_elem(np.float32(0.5))
+    x = snap_elem(x)
+    g = _rng_bf16(rng, (h,), 0.2) + 1; g = snap_elem(g)
     bta = _rng_bf16(rng, (h,), 0.2)
     dout = _rng_bf16(rng, (T, h)); resg = _rng_bf16(rng, (T, h))
     eps = 1e-5
     ref, xhat, rstd = OT.layernorm_fwd(x, g.astype(np.float64), bta.astype(np.float64), eps)
     dxr, dgr, dbr = OT.layernorm_bwd(dout.astype(np.float64), xhat, rstd, g.astype(np.float64))
     X, G, Bt, DO, RG = dev_bf16(x), dev_bf16(g), dev_bf16(bta), dev_bf16(dout), dev_bf16(resg)
-    out = torch.empty(T, h, dtype=torch.bfloat16, device="cuda")
+    out = torch.empty(T, h, dtype=B.torch_elem_dtype(), device="cuda")
     stats = torch.empty(T, 2, dtype=torch.float32, device="cuda")
     B.axonn_layernorm_fwd(T, h, X, G, Bt, eps, out, stats)
     assert rel_fro(host(out), ref) < TOL
     st = host(stats)
     assert rel_fro(st[:, 0], x.astype(np.float64).mean(-1)) < 1e-4 or np.abs(st[:, 0] - x.mean(-1)).max() < 1e-5
     assert rel_fro(st[:, 1], rstd[:, 0]) < 1e-5
-    dx = torch.empty(T, h, dtype=torch.bfloat16, device="cuda")
+    dx = torch.empty(T, h, dtype=B.torch_elem_dtype(), device="cuda")
     dg = torch.empty(h, dtype=torch.float32, device="cuda")
     db = torch.empty(h, dtype=torch.float32, device="cuda")
     ws = torch.empty(2 * ((T + 63) // 64) * h, dtype=torch.float32, device="cuda")
@@ -193,8 +193,8 @@ def test_layernorm_constant_row_gives_beta():
     import torch
     T, h = 8, 512
     x = np.full((T, h), 3.0, np.float32)
-    g = snap_bf16(np.linspace(0.5, 1.5, h).astype(np.float32)); bta = snap_bf16(np.linspace(-1, 1, h).astype(np.float32))
-    out = torch.empty(T, h, dtype=torch.bfloat16, device="cuda")
+    g = snap_elem(np.linspace(0.5, 1.5, h).astype(np.float32)); bta = snap_elem(np.linspace(-1, 1, h).astype(np.float32))
+    out = torch.empty(T, h, dtype=B.torch_elem_dtype(), device="cuda")
     stats = torch.empty(T, 2, dtype=torch.float32, device="cuda")
     B.axonn_layernorm_fwd(T, h, dev_bf16(x), dev_bf16(g), dev_bf16(bta), 1e-5, out, stats)
     assert np.array_equal(host(out), np.broadcast_to(bta.astype(np.float64), (T, h)))
@@ -256,12 +256,12 @@ def test_attention_fwd_bwd(b, s, a, d):
     qkv = _rng_bf16(rng, (b * s, 3 * h)); dout = _rng_bf16(rng, (b * s, h))
     o_ref, lse_ref, dqkv_ref = _attn_ref(qkv, dout, b, s, a, d)
     QKV, DO = dev_bf16(qkv), dev_bf16(dout)
-    o = torch.zeros(b * s, h, dtype=torch.bfloat16, device="cuda")
+    o = torch.zeros(b * s, h, dtype=B.torch_elem_dtype(), device="cuda")
     lse = torch.zeros(b, a, s, dtype=torch.float32, device="cuda")
     B.axonn_attention_fwd(b, s, a, d, QKV, o, lse)
     assert rel_fro(host(o), o_ref) < TOL
     assert np.abs(host(lse) - lse_ref).max() < 2e-3
-    dqkv = torch.zeros(b * s, 3 * h, dtype=torch.bfloat16, device="cuda")
+    dqkv = torch.zeros(b * s, 3 * h, dtype=B.torch_elem_dtype(), device="cuda")
     delta = torch.zeros(b * a * s, dtype=torch.float32, device="cuda")
     B.axonn_attention_bwd(b, s, a, d, QKV, o, lse, DO, dqkv, delta)
     got = host(dqkv)
@@ -279,9 +279,9 @@ def test_attention_large_scores_stay_finite():
     rng = np.random.default_rng(3)
     b, s, a, d = 1, 192, 2, 64
     h = a * d
-    qkv = _rng_bf16(rng, (b * s, 3 * h)); qkv[:, :2 * h] *= 4; qkv = snap_bf16(qkv)
+    qkv = _rng_bf16(rng, (b * s, 3 * h)); qkv[:, :2 * h] *= 4; qkv = snap_elem(qkv)
     o_ref, lse_ref, _ = _attn_ref(qkv, np.zeros((b * s, h), np.float32), b, s, a, d)
-    o = torch.zeros(b * s, h, dtype=torch.bfloat16, device="cuda")
+    o = torch.zeros(b * s, h, dtype=B.torch_elem_dtype(), device="cuda")
     lse = torch.zeros(b, a, s, dtype=torch.float32, device="cuda")
     B.axonn_attention_fwd(b, s, a, d, dev_bf16(qkv), o, lse)
     got = host(o)
@@ -296,14 +296,14 @@ def test_adam_bucket_kernel(n, fresh, wd, step, gs):
     from paper_2110_13005_amd.inputs import make_adam_inputs
     th, m, v, g16 = make_adam_inputs(n, seed=n, fresh=fresh)
     lr, b1, b2, eps = 1e-4, 0.9, 0.95, 1e-8
-    rt, rm, rv, r16 = oracle.adam_step(th, m, v, g16, lr, b1, b2, eps, wd, step, gs)
+    rt, rm, rv, r16 = oracle.adam_step(th, m, v, g16, lr, b1, b2, eps, wd, step, gs, half=B.ELEM)
     TH, Mm, V, G = dev_f32(th), dev_f32(m), dev_f32(v), dev_bf16(g16)
-    P16 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    P16 = torch.zeros(n, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_adam_bucket(n, TH, Mm, V, G, P16, lr, b1, b2, eps, wd, step, gs)
     assert rel_fro(host(TH), rt) <= 1e-6
     assert rel_fro(host(Mm), rm) <= 1e-6
     assert rel_fro(host(V), rv) <= 1e-6
     # theta16 is the bf16 rounding of the GPU's own fp32 theta, bit for bit
-    assert torch.equal(P16, TH.to(torch.bfloat16))
+    assert torch.equal(P16, TH.to(B.torch_elem_dtype()))
     # and within one bf16 ulp of the oracle's
     assert np.abs(host(P16) - r16).max() <= np.abs(r16).max() * 2.0 ** -7

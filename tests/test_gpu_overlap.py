@@ -70,7 +70,7 @@ def test_overlapped_step_equals_plain_step_and_oracle(opts):
     theta = np.concatenate([np.asarray(p[k], np.float32).ravel() for p in layers for k in oracle.PARAM_NAMES])
     m = np.zeros_like(theta); v = np.zeros_like(theta)
     for step, got in zip((1, 2), plain):
-        theta, m, v, _ = oracle.adam_step(theta, m, v, got[4], *HYPER, step, 1.0 / sh.n_microbatches)
+        theta, m, v, _ = oracle.adam_step(theta, m, v, got[4], *HYPER, step, 1.0 / sh.n_microbatches, half=B.ELEM)
         assert rel_fro(got[0], theta) <= 1e-6 and rel_fro(got[1], m) <= 1e-6 and rel_fro(got[2], v) <= 1e-6
         theta, m, v = (np.asarray(a, np.float32) for a in got[:3])      # continue from the GPU state
     for chunk, n_streams in ((1, 2), (3, 3), (1000, 2), (2, 1)):

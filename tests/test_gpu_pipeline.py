@@ -38,8 +38,8 @@ def test_two_stage_pipeline_message_driven(n_streams, limit_a):
             B.axonn_stage_attach_ends(Bst.handle, None, hd.h)
             bsh = (whole.microbatch_size, whole.seq_len, whole.hidden)
             TK = [dev_i32(t) for t in tokens]; TG = [dev_i32(t) for t in targets]
-            ACT = [torch.zeros(bsh, dtype=torch.bfloat16, device="cuda") for _ in range(M)]    # A -> B
-            GRD = [torch.zeros(bsh, dtype=torch.bfloat16, device="cuda") for _ in range(M)]    # B -> A
+            ACT = [torch.zeros(bsh, dtype=B.torch_elem_dtype(), device="cuda") for _ in range(M)]    # A -> B
+            GRD = [torch.zeros(bsh, dtype=B.torch_elem_dtype(), device="cuda") for _ in range(M)]    # B -> A
             sent = [_event() for _ in range(M)]; back = [_event() for _ in range(M)]
             losses = torch.zeros(M, device="cuda")
             torch.cuda.synchronize()

@@ -270,11 +270,11 @@ def test_offloaded_adam_matches_oracle(n, bucket, fresh, wd, step, gs):
     import torch
     th, m, v, g16 = make_adam_inputs(n, seed=n, fresh=fresh)
     lr, b1, b2, eps = 1e-4, 0.9, 0.95, 1e-8
-    rt, rm, rv, r16 = oracle.adam_step(th, m, v, g16, lr, b1, b2, eps, wd, step, gs)
+    rt, rm, rv, r16 = oracle.adam_step(th, m, v, g16, lr, b1, b2, eps, wd, step, gs, half=B.ELEM)
     ptrs, arrs = zip(*[_pinned_array(n) for _ in range(3)])
     arrs[0][:] = th; arrs[1][:] = m; arrs[2][:] = v
     G = dev_bf16(g16)
-    P16 = torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    P16 = torch.zeros(n, dtype=B.torch_elem_dtype(), device="cuda")
     opt = B.axonn_offload_adam_create(0, n, bucket, P16, G, ptrs[0], ptrs[1], ptrs[2])
     try:
         assert B.axonn_offload_adam_device_bytes(opt) == 3 * 12 * min(bucket, (n + 7) // 8 * 8)
@@ -284,10 +284,10 @@ def test_offloaded_adam_matches_oracle(n, bucket, fresh, wd, step, gs):
         assert rel_fro(arrs[1], rm) <= ADAM_TOL
         assert rel_fro(arrs[2], rv) <= ADAM_TOL
         got16 = host(P16)
-        assert np.array_equal(got16, oracle.bf16_round(arrs[0]).astype(np.float64))   # bf16 of own master, bit exact
+        assert np.array_equal(got16, oracle.half_round(arrs[0], B.ELEM).astype(np.float64))   # bf16 of own master, bit exact
         assert np.abs(got16 - r16).max() <= np.abs(r16).max() * 2.0 ** -7             # <= 1 ulp of the oracle's
         # second step continues from the offloaded state
-        rt2, rm2, rv2, _ = oracle.adam_step(rt, rm, rv, g16, lr, b1, b2, eps, wd, step + 1, gs)
+        rt2, rm2, rv2, _ = oracle.adam_step(rt, rm, rv, g16, lr, b1, b2, eps, wd, step + 1, gs, half=B.ELEM)
         B.axonn_offload_adam_step(opt, lr, b1, b2, eps, wd, step + 1, gs)
         torch.cuda.synchronize()
         assert rel_fro(arrs[0], rt2) <= ADAM_TOL and rel_fro(arrs[1], rm2) <= ADAM_TOL
@@ -317,8 +317,8 @@ def test_stage_batch_then_optimizer_step():
             B.axonn_stage_optimizer_attach(st.handle, ptrs[0], ptrs[1], ptrs[2], n - 8, 1 << 18)
         B.axonn_stage_optimizer_step(st.handle, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1, 1.0 / M)
         torch.cuda.synchronize()
-        rt, rm, rv, r16 = oracle.adam_step(theta0, 0 * theta0, 0 * theta0, g16, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1, 1.0 / M)
+        rt, rm, rv, r16 = oracle.adam_step(theta0, 0 * theta0, 0 * theta0, g16, 1e-3, 0.9, 0.999, 1e-8, 0.01, 1, 1.0 / M, half=B.ELEM)
         assert rel_fro(arrs[0], rt) <= ADAM_TOL and rel_fro(arrs[1], rm) <= ADAM_TOL and rel_fro(arrs[2], rv) <= ADAM_TOL
-        assert np.array_equal(host(st.params), oracle.bf16_round(arrs[0]).astype(np.float64))
+        assert np.array_equal(host(st.params), oracle.half_round(arrs[0], B.ELEM).astype(np.float64))
     for p in ptrs:
         B.axonn_pinned_free(p)

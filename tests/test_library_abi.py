@@ -26,6 +26,16 @@ def test_library_exports_every_declared_symbol():
     assert sorted(B.EXPORTED_SYMBOLS) == syms, "binding and header disagree"
 
 
+def test_half_precision_build_exports_the_same_symbols():
+    """libaxonn_stage_fp16.so is the same C ABI over the other 16-bit element type."""
+    from paper_2110_13005_amd import build as BLD
+    lib = ctypes.CDLL(BLD.LIB_PATH_FP16)
+    for s in _header_symbols():
+        assert hasattr(lib, s), "missing export: " + s
+    lib.axonn_element_type.restype = ctypes.c_int32
+    assert lib.axonn_element_type() == 1 and B.load().axonn_element_type() == 0
+
+
 def test_argument_validation_without_device():
     lib = B.load()
     assert lib.axonn_stage_create(None, None) == B.AXONN_EINVAL
