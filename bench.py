@@ -227,7 +227,7 @@ def main():
         "metric": "stage fwd+bwd TFLOP/s per MI355X and % of bf16 MFMA peak; tokens/s",
         "value": tflops, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "vs_baseline": None, "dtype": B.ELEM, "data": "synthetic",
         "config": {"workload": "%s stage: %d layers, h=%d, heads=%d, ffn=%d, seq=%d, microbatch=%d, %d microbatches, "
                                "pipeline_limit=%d" % (args.config, sh.n_layers, sh.hidden, sh.n_heads, sh.ffn,
                                                       sh.seq_len, sh.microbatch_size, M, P),
