@@ -179,38 +179,49 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
       for (int kk = 0; kk < KK; ++kk)
         sacc[ks] = mfma32(frag_kcontig(sK + (32 * ks) * LDK + kk * 16, LDK, lane), qf[kk], sacc[ks]);
     }
-    const bool need_mask = (k0 + BKV - 1 > qw0);
-    float mx = -INFINITY;
+    // Keys beyond the query are masked in the tiles that straddle the diagonal only: a real (wave-uniform)
+    // branch, so that the other tiles do not pay for the comparisons.
+    if (k0 + BKV - 1 > qw0) {
+      asm volatile("" ::: "memory");            // keeps the compiler from turning the branch into selects
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 32 * ks + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (key > qi) sacc[ks][r] = -INFINITY;
+        }
+    }
+    // Row maximum of the raw scores; in units of the exponent (log2) it is mx * scale_log2 (the scale is positive).
+    float mx = sacc[0][0];
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        float t = sacc[ks][r] * scale_log2;
-        if (need_mask) {
-          const int key = k0 + 32 * ks + 8 * (r >> 2) + 4 * g + (r & 3);
-          if (key > qi) t = -INFINITY;
-        }
-        sacc[ks][r] = t;
-        mx = fmaxf(mx, t);
-      }
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = fast_exp2(m_run - m_new);
-    m_run = m_new;
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[ks][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+    // m_run is the reference point of the exponentials, not necessarily the running maximum: it moves (and the
+    // sums so far are rescaled) only when some row's maximum has grown by more than 2^8 since it was set, so
+    // most tiles skip the rescaling; p stays <= 256 and the result is the same up to rounding.
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.0f) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = fast_exp2(m_run - m_new);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+    }
+    const float neg_m = -m_run;
     float psum = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const float p = fast_exp2(sacc[ks][r] - m_new);
+        const float p = fast_exp2(fmaf(sacc[ks][r], scale_log2, neg_m));
         sacc[ks][r] = p;
         psum += p;
       }
-    l_run = l_run * alpha + psum;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[dt][r] *= alpha;
+    l_run += psum;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -371,6 +382,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
         pacc = mfma32(frag_kcontig(sdO + (32 * qs) * LDQ + kk * 16, LDQ, lane), vf[kk], pacc);
       }
       // lane = key kj; register r = query qq0 + 8*(r/4) + 4g + r%4
+      // masking in the blocks that straddle the diagonal only (a wave-uniform branch, kept as one)
+      if (kw0 + 31 > qq0) {
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qrow = qq0 + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (kj > qrow) sacc[r] = -INFINITY;
+        }
+      }
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         const floatx4 l4 = *reinterpret_cast<const floatx4*>(&s_lse[32 * qs + 8 * q4 + 4 * g]);
@@ -378,9 +398,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int r = 4 * q4 + e;
-          const int qrow = qq0 + 8 * q4 + 4 * g + e;
-          float p = fast_exp2(sacc[r] * scale_log2 - l4[e]);
-          if (kj > qrow) p = 0.f;
+          const float p = fast_exp2(fmaf(sacc[r], scale_log2, -l4[e]));
           sacc[r] = p;
           pacc[r] = p * (pacc[r] - d4[e]);
         }
@@ -485,11 +503,19 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
         pacc = mfma32(frag_kcontig(sV + (32 * ks) * LDK + kk * 16, LDK, lane), dof[kk], pacc);
       }
       // lane = query qi; register r = key k0 + 32ks + 8*(r/4) + 4g + r%4
+      // masking in the blocks that straddle the diagonal only (a wave-uniform branch, kept as one)
+      if (k0 + 32 * ks + 31 > qw0) {
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + 32 * ks + 8 * (r >> 2) + 4 * g + (r & 3);
+          if (key > qi) sacc[r] = -INFINITY;
+        }
+      }
+      const float neg_lse = -lse_q;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int key = k0 + 32 * ks + 8 * (r >> 2) + 4 * g + (r & 3);
-        float p = fast_exp2(sacc[r] * scale_log2 - lse_q);
-        if (key > qi) p = 0.f;
+        const float p = fast_exp2(fmaf(sacc[r], scale_log2, neg_lse));
         pacc[r] = p * (pacc[r] - delta_q);
       }
 #pragma unroll

@@ -288,6 +288,45 @@ def test_attention_large_scores_stay_finite():
     assert np.isfinite(got).all() and rel_fro(got, o_ref) < TOL
 
 
+@pytest.mark.parametrize("slope,spike", [(0.02, 0.0), (0.12, 0.0), (0.02, 40.0)])
+def test_attention_growing_row_maxima(slope, spike):
+    """The forward kernel moves the reference point of its exponentials only when a row maximum has grown by more
+    than a threshold.  Scores that rise with the key index -- slowly (the reference stays behind the maximum for
+    many tiles), quickly (it moves in every tile), and with one late key far above the rest (a jump after a long
+    quiet stretch) -- must give the oracle's output, log-sum-exp and gradients."""
+    import torch
+    rng = np.random.default_rng(17)
+    b, s, a, d = 1, 640, 2, 64
+    h = a * d
+    qkv = 0.3 * rng.standard_normal((b * s, 3 * h)).astype(np.float32)
+    u = rng.standard_normal(d).astype(np.float32); u /= np.linalg.norm(u)
+    ramp = (slope * np.arange(s, dtype=np.float32))[:, None]
+    for hd in range(a):
+        qkv[:, hd * d:(hd + 1) * d] += np.sqrt(d) * u                       # every query has component sqrt(d) along u
+        qkv[:, h + hd * d:h + (hd + 1) * d] += ramp * u                     # key j has component slope * j: score rises by slope per key
+    if spike:
+        qkv[500, h:h + d] += spike * u                                     # one late key of head 0 stands out
+    qkv = snap_elem(qkv); dout = _rng_bf16(rng, (b * s, h))
+    o_ref, lse_ref, dqkv_ref = _attn_ref(qkv, dout, b, s, a, d)
+    QKV, DO = dev_bf16(qkv), dev_bf16(dout)
+    o = torch.zeros(b * s, h, dtype=B.torch_elem_dtype(), device="cuda")
+    lse = torch.zeros(b, a, s, dtype=torch.float32, device="cuda")
+    B.axonn_attention_fwd(b, s, a, d, QKV, o, lse)
+    assert np.isfinite(host(o)).all() and rel_fro(host(o), o_ref) < TOL
+    assert np.abs(host(lse) - lse_ref).max() < 2e-3 * max(1.0, np.abs(lse_ref).max() / 10)
+    dqkv = torch.zeros(b * s, 3 * h, dtype=B.torch_elem_dtype(), device="cuda")
+    delta = torch.zeros(b * a * s, dtype=torch.float32, device="cuda")
+    B.axonn_attention_bwd(b, s, a, d, QKV, o, lse, DO, dqkv, delta)
+    got = host(dqkv)
+    # dv is a plain contraction with P.  dq and dk contract dS with keys / queries that here carry a large common
+    # component along u, while the rows of dS sum to zero: the 16-bit rounding of dS is multiplied by that
+    # component, so their bound grows with the largest ramp value over the typical element size.
+    amp = max(1.0, slope * s / 3.0)       # measured: 5e-2 for dq at slope 0.12 (amp 25.6), inside 2 * TOL at slope 0.02
+    assert rel_fro(got[:, 2 * h:], dqkv_ref[:, 2 * h:]) < 2 * TOL
+    for name, sl in (("dq", slice(0, h)), ("dk", slice(h, 2 * h))):
+        assert rel_fro(got[:, sl], dqkv_ref[:, sl]) < 2 * TOL * amp, name
+
+
 # ------------------------------------------------------------------------- Adam
 @pytest.mark.parametrize("n", [8, 1000, 65536 + 24, 1 << 20])
 @pytest.mark.parametrize("fresh,wd,step,gs", [(False, 0.0, 100, 1.0), (True, 0.01, 1, 0.25)])
