@@ -57,6 +57,19 @@ struct TileRegs {
                  : make_uint4(0, 0, 0, 0);
     }
   }
+  // The same tile of an exact-size head through buffer loads, with next to no address arithmetic per tile:
+  // `off0` = byte offset, from the descriptor's base, of this thread's first chunk in the tile that starts at
+  // row 0 (see offset0); the tile starts at row0; rows outside the descriptor's range read as zeros.
+  static __device__ __forceinline__ uint32_t offset0(uint32_t row_bytes, int tid) {
+    return (uint32_t)(tid / (D / 8)) * row_bytes + (uint32_t)(tid % (D / 8)) * 16u;
+  }
+  __device__ __forceinline__ void load_buffer(__amdgpu_buffer_rsrc_t rsrc, uint32_t off0, uint32_t row_bytes, int row0) {
+    constexpr int RSTEP = 256 / (D / 8);        // rows between consecutive chunks of a thread
+    const uint32_t base = off0 + (uint32_t)row0 * row_bytes;
+#pragma unroll
+    for (int j = 0; j < NCH; ++j)
+      r[j] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, base + (uint32_t)(j * RSTEP) * row_bytes, 0, 0));
+  }
   template <int LD>
   __device__ __forceinline__ void store(elem_t* lds, int tid) const {
 #pragma unroll
@@ -156,18 +169,27 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
   const int kv_end = min(s, q0 + 128);
   const int n_kt = (kv_end + BKV - 1) / BKV;
   TileRegs<BKV, D> rk, rv;
-  rk.template load<EXACT>(kb, ld, 0, s, d, tid);
-  rv.template load<EXACT>(vb, ld, 0, s, d, tid);
+  // exact-size heads: tiles through buffer loads over the rows of this (batch, head)
+  const uint32_t row_bytes = (uint32_t)ld * 2u, tile_bytes = EXACT ? (uint32_t)(((int64_t)(s - 1) * ld + D) * 2) : 0u;
+  const __amdgpu_buffer_rsrc_t k_rsrc = make_rsrc(kb, tile_bytes), v_rsrc = make_rsrc(vb, tile_bytes);
+  const uint32_t off0 = TileRegs<BKV, D>::offset0(row_bytes, tid);
+  auto fetch = [&](int row0) {
+    if (EXACT) {
+      rk.load_buffer(k_rsrc, off0, row_bytes, row0);
+      rv.load_buffer(v_rsrc, off0, row_bytes, row0);
+    } else {
+      rk.template load<EXACT>(kb, ld, row0, s, d, tid);
+      rv.template load<EXACT>(vb, ld, row0, s, d, tid);
+    }
+  };
+  fetch(0);
   for (int kt = 0; kt < n_kt; ++kt) {
     const int k0 = kt * BKV;
     __syncthreads();
     rk.template store<LDK>(sK, tid);
     rv.template store<LDV>(sV, tid);
     __syncthreads();
-    if (kt + 1 < n_kt) {
-      rk.template load<EXACT>(kb, ld, k0 + BKV, s, d, tid);
-      rv.template load<EXACT>(vb, ld, k0 + BKV, s, d, tid);
-    }
+    if (kt + 1 < n_kt) fetch(k0 + BKV);
     if (k0 > qw0 + 31) continue;  // every key of the tile is in this wave's future
 
     floatx16 sacc[2];
@@ -348,9 +370,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
   const int qt_begin = k0 / BQ, n_qt = (s + BQ - 1) / BQ;
   TileRegs<BQ, D> rq, rdo;
   float r_lse = 0.f, r_delta = 0.f;
+  const uint32_t q_row_bytes = (uint32_t)ld * 2u, do_row_bytes = (uint32_t)h * 2u;
+  const __amdgpu_buffer_rsrc_t q_rsrc = make_rsrc(qb, EXACT ? (uint32_t)(((int64_t)(s - 1) * ld + D) * 2) : 0u);
+  const __amdgpu_buffer_rsrc_t do_rsrc = make_rsrc(dob, EXACT ? (uint32_t)(((int64_t)(s - 1) * h + D) * 2) : 0u);
+  const uint32_t q_off0 = TileRegs<BQ, D>::offset0(q_row_bytes, tid), do_off0 = TileRegs<BQ, D>::offset0(do_row_bytes, tid);
   auto prefetch = [&](int qt) {
-    rq.template load<EXACT>(qb, ld, qt * BQ, s, d, tid);
-    rdo.template load<EXACT>(dob, h, qt * BQ, s, d, tid);
+    if (EXACT) {
+      rq.load_buffer(q_rsrc, q_off0, q_row_bytes, qt * BQ);
+      rdo.load_buffer(do_rsrc, do_off0, do_row_bytes, qt * BQ);
+    } else {
+      rq.template load<EXACT>(qb, ld, qt * BQ, s, d, tid);
+      rdo.template load<EXACT>(dob, h, qt * BQ, s, d, tid);
+    }
     if (tid < BQ) {
       const int qrow = qt * BQ + tid;
       r_lse = qrow < s ? lse_b[qrow] : 0.f;
@@ -479,18 +510,26 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
   const int kv_end = min(s, q0 + 128);
   const int n_kt = (kv_end + BKV - 1) / BKV;
   TileRegs<BKV, D> rk, rv;
-  rk.template load<EXACT>(kb, ld, 0, s, d, tid);
-  rv.template load<EXACT>(vb, ld, 0, s, d, tid);
+  const uint32_t row_bytes = (uint32_t)ld * 2u, tile_bytes = EXACT ? (uint32_t)(((int64_t)(s - 1) * ld + D) * 2) : 0u;
+  const __amdgpu_buffer_rsrc_t k_rsrc = make_rsrc(kb, tile_bytes), v_rsrc = make_rsrc(vb, tile_bytes);
+  const uint32_t off0 = TileRegs<BKV, D>::offset0(row_bytes, tid);
+  auto fetch = [&](int row0) {
+    if (EXACT) {
+      rk.load_buffer(k_rsrc, off0, row_bytes, row0);
+      rv.load_buffer(v_rsrc, off0, row_bytes, row0);
+    } else {
+      rk.template load<EXACT>(kb, ld, row0, s, d, tid);
+      rv.template load<EXACT>(vb, ld, row0, s, d, tid);
+    }
+  };
+  fetch(0);
   for (int kt = 0; kt < n_kt; ++kt) {
     const int k0 = kt * BKV;
     __syncthreads();
     rk.template store<LDK>(sK, tid);
     rv.template store<LDK>(sV, tid);
     __syncthreads();
-    if (kt + 1 < n_kt) {
-      rk.template load<EXACT>(kb, ld, k0 + BKV, s, d, tid);
-      rv.template load<EXACT>(vb, ld, k0 + BKV, s, d, tid);
-    }
+    if (kt + 1 < n_kt) fetch(k0 + BKV);
     if (k0 > qw0 + 31) continue;
 #pragma unroll
     for (int ks = 0; ks < 2; ++ks) {
@@ -545,12 +584,15 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
 // ------------------------------------------------------------------------- launchers
 // d = 64 or 128: the kernels compiled for exactly that head dimension.  Any other multiple of 4 up to 192:
 // the next compiled size with the columns beyond d masked.
+// The exact-size kernels address the rows of a (batch, head) with 32-bit byte offsets (buffer loads): for sequences
+// too long for that (s * 3 * a * d * 2 bytes beyond 2^31) the general kernels take over.
 #define AXONN_ATTN_DISPATCH(KERNEL, ...)                                                              \
   do {                                                                                                \
-    if (d == 64) hipLaunchKernelGGL((KERNEL<64, true>), grid, dim3(256), 0, st, __VA_ARGS__);         \
-    else if (d == 128) hipLaunchKernelGGL((KERNEL<128, true>), grid, dim3(256), 0, st, __VA_ARGS__);  \
-    else if (d < 64) hipLaunchKernelGGL((KERNEL<64, false>), grid, dim3(256), 0, st, __VA_ARGS__);    \
-    else if (d < 128) hipLaunchKernelGGL((KERNEL<128, false>), grid, dim3(256), 0, st, __VA_ARGS__);  \
+    const bool off32 = ((int64_t)s + 256) * 3 * a * d * 2 < (int64_t(1) << 31);                       \
+    if (d == 64 && off32) hipLaunchKernelGGL((KERNEL<64, true>), grid, dim3(256), 0, st, __VA_ARGS__);         \
+    else if (d == 128 && off32) hipLaunchKernelGGL((KERNEL<128, true>), grid, dim3(256), 0, st, __VA_ARGS__);  \
+    else if (d <= 64) hipLaunchKernelGGL((KERNEL<64, false>), grid, dim3(256), 0, st, __VA_ARGS__);    \
+    else if (d <= 128) hipLaunchKernelGGL((KERNEL<128, false>), grid, dim3(256), 0, st, __VA_ARGS__); \
     else hipLaunchKernelGGL((KERNEL<192, false>), grid, dim3(256), 0, st, __VA_ARGS__);               \
   } while (0)
 

@@ -51,6 +51,12 @@ __device__ __forceinline__ floatx16 mfma32(elemx8 a, elemx8 b, floatx16 c) {
 __device__ __forceinline__ floatx4 mfma16(elemx8 a, elemx8 b, floatx4 c) {
   return AXONN_MFMA_16X16X32(a, b, c, 0, 0, 0);
 }
+// Raw buffer descriptor over `bytes` bytes at p: a load at an offset at or beyond `bytes` returns zeros
+// without touching memory.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
+
 // The same instruction with the accumulator pinned to the accumulation registers (a[...]): a kernel
 // whose 256 accumulators fill that file exactly needs every one of them there, and the register
 // allocator does not get this right by itself.  The compiler does not see an MFMA here, so the

@@ -422,9 +422,6 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
 // last one without branches or per-chunk pointers.
 constexpr uint32_t kOutOfRange = 0x80000000u;
 
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes) {
-  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
-}
 
 // Item idx of n items spread evenly over the MFMA slots [first, first + span), and its inverse (-1: no
 // item at slot q).  span >= n, so that no two items share a slot.
