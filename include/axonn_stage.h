@@ -202,8 +202,11 @@ int axonn_offload_adam_create(int32_t device, uint64_t n, uint64_t bucket_elems,
                               float* host_master, float* host_m, float* host_v,
                               axonn_offload_adam_t** out);
 int axonn_offload_adam_destroy(axonn_offload_adam_t* opt);
-/* Enqueues one full step (all buckets).  The work starts after everything already in
- * hip_stream and hip_stream waits for its end; step t >= 1. */
+/* One full step (all buckets).  The work starts after everything already in hip_stream;
+ * the call returns when the step is complete and the host arrays hold the new state (it
+ * synchronizes hip_stream): a caller that ran ahead and queued its next batch behind a
+ * pending step would fill the hardware queues that the step's copies share, which slows
+ * the step by half.  step t >= 1. */
 int axonn_offload_adam_step(axonn_offload_adam_t* opt, double lr, double beta1, double beta2,
                             double eps, double weight_decay, int64_t step, double grad_scale,
                             void* hip_stream);
@@ -230,7 +233,7 @@ int axonn_stage_optimizer_step(axonn_stage_t* st, double lr, double beta1, doubl
  * when the call is made).  Call it after the batch's last message has
  * been dispatched (axonn_stage_run has returned, or the n_microbatches-th
  * axonn_stage_backward) -- no axonn_stage_join is needed in between; AXONN_ESTATE before
- * that.  hip_stream continues when the step is complete, which implies the batch is.
+ * that.  The call returns when the step is complete, which implies the batch is.
  * Results are identical to axonn_stage_optimizer_step's. */
 int axonn_stage_optimizer_step_overlapped(axonn_stage_t* st, double lr, double beta1,
                                           double beta2, double eps, double weight_decay,

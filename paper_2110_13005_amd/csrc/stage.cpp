@@ -1311,6 +1311,10 @@ int adam_pass(axonn_offload_adam* o, double lr, double beta1, double beta2, doub
   const int last = (int)((nb - 1) % S);
   HIP_TRY(hipStreamWaitEvent(user, o->ev_d2h[last], 0));
   HIP_TRY(hipStreamWaitEvent(user, o->ev_k[last], 0));
+  // The call returns when the host copies are complete.  Without this, a caller that runs ahead and queues its
+  // next batch behind the pending pass fills the hardware queues that the pass's copies share: measured on the 12B
+  // stage, the pass then takes 500 ms instead of 323, and single batches behind it run 10 % slower.
+  HIP_TRY(hipStreamSynchronize(user));
   return AXONN_OK;
 }
 }  // namespace
