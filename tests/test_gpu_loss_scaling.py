@@ -10,9 +10,10 @@ import pytest
 import oracle
 from oracle import lm_ends as OE
 from paper_2110_13005_amd import binding as B
-from paper_2110_13005_amd.inputs import CONFIGS, make_stage_inputs, snap_elem
+from paper_2110_13005_amd.inputs import CONFIGS, StageShape, make_lm_inputs, make_stage_inputs, snap_elem
 from paper_2110_13005_amd.stage import Stage
-from helpers import ADAM_TOL, EPS, GRAD_TOL, HeadHandle, dev_bf16, dev_i32, host, rel_fro, run_direct
+from helpers import (ADAM_TOL, EPS, GRAD_TOL, EmbedHandle, HeadHandle, dev_bf16, dev_i32, host, oracle_model, rel_fro,
+                     run_direct)
 
 pytestmark = pytest.mark.gpu
 
@@ -116,6 +117,71 @@ def test_optimizer_step_under_the_dynamic_loss_scale():
         assert [sc.scale, sc.good_steps] == [128.0, 0]     # 64 -> 128 after two good batches, -> 64 on the overflow, -> 128 after two more
     for p in ptrs:
         B.axonn_pinned_free(p)
+
+
+def test_whole_model_batch_under_a_loss_scale():
+    """Alg. 2's last stage with mixed precision end to end: the head multiplies its gradient by S, every gradient
+    of the model (head, layers, embedding) comes out S times the oracle's and the losses unscaled; the decision of
+    the scaled step takes the non-finite counts of the two ends' gradient buffers as `other_nonfinite`."""
+    import torch
+    sh = StageShape(2, 128, 2, 64, 2, 4)
+    V, S = 520, 256.0
+    layers, _, _ = make_stage_inputs(sh, seed=21, perturb=True)
+    tokens, targets, wte, wpe, g, bt, W = make_lm_inputs(sh, V, seed=22)
+    ref_losses, ref = oracle_model(tokens, targets, wte, wpe, layers, g, bt, W, sh.n_heads, sh.n_microbatches)
+    M = sh.n_microbatches
+    e = EmbedHandle(V, sh.hidden, sh.seq_len, sh.microbatch_size, wte, wpe)
+    hd = HeadHandle(V, sh.hidden, sh.tokens, M, g, bt, W)
+    ptrs = []
+    try:
+        with Stage(sh, pipeline_limit=2) as st:
+            st.load_params(layers)
+            B.axonn_stage_attach_ends(st.handle, e.h, hd.h)
+            B.axonn_head_set_loss_scale(hd.h, S)
+            TK = [dev_i32(t) for t in tokens]; TG = [dev_i32(t) for t in targets]
+            losses = torch.zeros(M, device="cuda")
+            st.zero_grad()
+            for i in range(M):
+                st.post(0, i, TK[i], None, targets=TG[i], loss=losses[i:i + 1])
+            st.run(2)
+            st.join()
+            torch.cuda.synchronize()
+            for i in range(M):
+                assert abs(losses[i].item() - ref_losses[i]) <= 2e-3 * abs(ref_losses[i])
+            for li, gl in enumerate(st.grads_numpy()):
+                for k, v in gl.items():
+                    assert rel_fro(v, S * ref["layers"][li][k]) <= GRAD_TOL, (li, k)
+            got = hd.grads_numpy()
+            for k in got:
+                assert rel_fro(got[k], S * ref["head"][k]) <= GRAD_TOL, k
+            gte, gpe = e.grads_numpy()
+            assert rel_fro(gte, S * ref["wte"]) <= GRAD_TOL and rel_fro(gpe, S * ref["wpe"]) <= GRAD_TOL
+            # the ends' buffers take part in the overflow decision
+            ws = torch.zeros(1025, dtype=torch.int64, device="cuda")
+            others = 0
+            for buf in (e.grads, hd.grads):
+                B.axonn_count_nonfinite(buf, buf.numel(), ws)
+                torch.cuda.synchronize()
+                others += ws[1024].item()
+            assert others == 0
+            n = st.n_params
+            ptrs, arrs = zip(*[_pinned_array(n) for _ in range(3)])
+            theta0 = st.params.float().cpu().numpy()
+            arrs[0][:] = theta0; arrs[1][:] = 0; arrs[2][:] = 0
+            B.axonn_stage_optimizer_attach(st.handle, ptrs[0], ptrs[1], ptrs[2], n, 1 << 18)
+            sc = B.axonn_loss_scaler(scale=S, growth=2.0, backoff=0.5, growth_interval=1000, good_steps=0)
+            g16 = st.grads.float().cpu().numpy()
+            # one bad value in the embedding's gradients: the stage's step is skipped, the scale halves
+            assert B.axonn_stage_optimizer_step_scaled(st.handle, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0, sc, other_nonfinite=1)
+            assert sc.scale == S / 2 and np.array_equal(arrs[0], theta0)
+            sc.scale = S
+            assert not B.axonn_stage_optimizer_step_scaled(st.handle, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0, sc, other_nonfinite=others)
+            rt, rm, rv, _ = oracle.adam_step(theta0, 0 * theta0, 0 * theta0, g16, 1e-3, 0.9, 0.999, 1e-8, 0.0, 1, 1.0 / S, half=B.ELEM)
+            assert rel_fro(arrs[0], rt) <= ADAM_TOL and rel_fro(arrs[1], rm) <= ADAM_TOL and rel_fro(arrs[2], rv) <= ADAM_TOL
+    finally:
+        e.close(); hd.close()
+        for p in ptrs:
+            B.axonn_pinned_free(p)
 
 
 def test_scaler_arguments_are_checked():
