@@ -865,7 +865,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
 #pragma unroll
   for (int d = 0; d < ND; ++d) { AXONN_DMA(1, d) }
   AXONN_DMA_NEXT()
-  dma_wait_all();
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(ND) : "memory");   // tile 0 has arrived, tile 1 may still be on its way
   lds_barrier();
 #pragma unroll
   for (int f = 0; f < NF; ++f) { AXONN_FRAG(0, 0, 0, f) }
