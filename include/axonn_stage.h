@@ -397,6 +397,21 @@ int axonn_layernorm_bwd(int64_t T, int64_t h, const void* dout_bf16, const void*
                         const float* stats, const void* gamma_bf16, const void* res_grad_bf16,
                         void* dx_bf16, float* dgamma_f32, float* dbeta_f32,
                         float* workspace_f32, void* hip_stream);
+/* axonn_layernorm_bwd for callers that cannot allocate device memory and have no workspace to
+ * hand over (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc):
+ * same kernels, same results, but the column partial sums go to a buffer that is part of the
+ * library's own device image (AXONN_LAYERNORM_BWD_NOALLOC_MAX_FLOATS floats = 8 MiB, held on every
+ * GPU the library runs on until the process ends).  The call allocates and frees nothing; its
+ * first call on a device looks the buffer's address up.  AXONN_EUNSUPPORTED if
+ * 2*ceil(T/64)*h exceeds the buffer (e.g. T = 4096 rows at h = 16384 still fit).  The device that
+ * is current at the call is the one used.  All calls on one GPU share the one buffer: calls that
+ * may overlap on the same GPU (different streams, different host threads) race; keep them on one
+ * stream or order them with events.  Nothing needs clearing between calls. */
+#define AXONN_LAYERNORM_BWD_NOALLOC_MAX_FLOATS (2u * 64u * 16384u)
+int axonn_layernorm_bwd_noalloc(int64_t T, int64_t h, const void* dout_bf16, const void* x_bf16,
+                                const float* stats, const void* gamma_bf16,
+                                const void* res_grad_bf16, void* dx_bf16, float* dgamma_f32,
+                                float* dbeta_f32, void* hip_stream);
 /* out_f32[N] = sum_t y[t, n] over T rows (bias gradient).  workspace: ceil(T/64)*N floats. */
 int axonn_colsum(int64_t T, int64_t N, const void* y_bf16, int64_t ldy, float* out_f32,
                  float* workspace_f32, void* hip_stream);

@@ -102,6 +102,7 @@ _PROTOTYPES = {
                         _vp, _i64, _i32, _vp],
     "axonn_layernorm_fwd": [_i64, _i64, _vp, _vp, _vp, _f, _vp, _vp, _vp],
     "axonn_layernorm_bwd": [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
+    "axonn_layernorm_bwd_noalloc": [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "axonn_colsum": [_i64, _i64, _vp, _i64, _vp, _vp, _vp],
     "axonn_attention_fwd": [_i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp],
     "axonn_attention_bwd": [_i32, _i32, _i32, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
@@ -418,6 +419,11 @@ def axonn_layernorm_fwd(T, h, x, gamma, beta, eps, out, stats, stream=None):
 def axonn_layernorm_bwd(T, h, dout, x, stats, gamma, res_grad, dx, dgamma, dbeta, workspace, stream=None):
     _check(load().axonn_layernorm_bwd(T, h, _ptr(dout), _ptr(x), _ptr(stats), _ptr(gamma), _ptr(res_grad), _ptr(dx),
                                       _ptr(dgamma), _ptr(dbeta), _ptr(workspace), _stream(stream)))
+
+
+def axonn_layernorm_bwd_noalloc(T, h, dout, x, stats, gamma, res_grad, dx, dgamma, dbeta, stream=None):
+    _check(load().axonn_layernorm_bwd_noalloc(T, h, _ptr(dout), _ptr(x), _ptr(stats), _ptr(gamma), _ptr(res_grad),
+                                              _ptr(dx), _ptr(dgamma), _ptr(dbeta), _stream(stream)))
 
 
 def axonn_colsum(T, N, y, ldy, out, workspace, stream=None):

@@ -12,6 +12,7 @@
 #include <cstring>
 #include <deque>
 #include <functional>
+#include <mutex>
 #include <new>
 #include <string>
 #include <thread>
@@ -1670,6 +1671,58 @@ int axonn_layernorm_bwd(int64_t T, int64_t h, const void* dout, const void* x, c
   if (h % 8 || h > 16384) return fail(AXONN_EUNSUPPORTED, "layernorm_bwd: h must be a multiple of 8 and <= 16384");
   return check_launch(launch_layernorm_bwd(T, h, dout, x, stats, gamma, res_grad, dx, dgamma, dbeta, 0, true,
                                            workspace, (hipStream_t)hip_stream), "layernorm_bwd");
+}
+
+}  // extern "C"
+
+// Scratch of axonn_layernorm_bwd_noalloc: the column partial sums that axonn_layernorm_bwd takes as its
+// workspace argument, in device memory that exists from the moment the library is loaded.  Every GPU
+// holds its own copy of the array at its own address, so the address is looked up once per device, with
+// that device current; host code uses that address, never the array's name.
+namespace {
+constexpr uint64_t kNoallocScratchFloats = AXONN_LAYERNORM_BWD_NOALLOC_MAX_FLOATS;
+static __device__ __align__(256) float scratch[kNoallocScratchFloats];
+constexpr int kMaxDevices = 64;
+float* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+int noalloc_scratch(float** out) {
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices)
+    return fail(AXONN_EUNSUPPORTED, "layernorm_bwd_noalloc: device ordinal %d above %d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p) return fail(AXONN_EHIP, "layernorm_bwd_noalloc: the scratch array has no address on device %d", dev);
+    g_scratch_ptr[dev] = (float*)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return AXONN_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int axonn_layernorm_bwd_noalloc(int64_t T, int64_t h, const void* dout, const void* x, const float* stats,
+                                const void* gamma, const void* res_grad, void* dx, float* dgamma, float* dbeta,
+                                void* hip_stream) {
+  if (!dout || !x || !stats || !gamma || !dx || !dgamma || !dbeta)
+    return fail(AXONN_EINVAL, "layernorm_bwd_noalloc: null argument");
+  if (T < 1 || h < 1) return fail(AXONN_EINVAL, "layernorm_bwd_noalloc: non-positive size");
+  if (h % 8 || h > 16384)
+    return fail(AXONN_EUNSUPPORTED, "layernorm_bwd_noalloc: h must be a multiple of 8 and <= 16384");
+  const uint64_t need = 2 * (((uint64_t)T + 63) / 64) * (uint64_t)h;
+  if (need > kNoallocScratchFloats)
+    return fail(AXONN_EUNSUPPORTED, "layernorm_bwd_noalloc: 2*ceil(T/64)*h = %llu floats of scratch needed, the "
+                "built-in buffer holds %llu (use axonn_layernorm_bwd with a workspace of your own)",
+                (unsigned long long)need, (unsigned long long)kNoallocScratchFloats);
+  float* ws = nullptr;
+  AX_TRY(noalloc_scratch(&ws));
+  // every partial sum the final reduction reads is written by this call's own first launch: nothing to clear
+  return check_launch(launch_layernorm_bwd(T, h, dout, x, stats, gamma, res_grad, dx, dgamma, dbeta, 0, true, ws,
+                                           (hipStream_t)hip_stream), "layernorm_bwd");
 }
 
 int axonn_colsum(int64_t T, int64_t N, const void* y, int64_t ldy, float* out, float* workspace, void* hip_stream) {
