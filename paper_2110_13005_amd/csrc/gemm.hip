@@ -644,11 +644,21 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
 //                      rows 8c + w and 8c + w + 4 (one per half wave); its 1 KB block is followed by
 //                      32 bytes of padding, so that the 8 k rows a transposing read touches in one
 //                      pass (k0 .. k0+3 and k0+8 .. k0+11, 32 bytes each) fall into different banks.
-// Two stages of one 64-wide k tile each.  In k-step kt (tile kt in stage CUR): phase 0 multiplies k slice
-// 0 while the fragments of slice 1 are read; a few MFMAs into phase 1 the wave waits for its own copies
-// of tile kt+1 (issued a k-step earlier) and meets the others at the barrier: tile kt+1 is complete in
-// stage CUR^1 and nobody reads stage CUR any more; the rest of phase 1 reads the slice-0 fragments of
-// tile kt+1 and issues the copies of tile kt+2 into stage CUR.
+// Two stages of one 64-wide k tile each.  A k-step (tile kt in stage CUR) is two phases of 8*TN MFMAs:
+// phase 0 multiplies k slice 0 while the fragments of slice 1 are read, phase 1 multiplies slice 1 while the
+// slice-0 fragments of tile kt+1 are read from stage CUR^1.  Stage CUR is refilled with tile kt+2 as its
+// parts fall free:
+//   a k-strided tile by halves (copy instructions c < 4 hold k slice 0, the others slice 1): a few MFMAs
+//     into phase 0 a barrier tells that nobody reads slice 0 of stage CUR any more, and that half is copied
+//     during the rest of phase 0; the other half likewise behind the barrier of phase 1;
+//   a k-contiguous tile (each instruction spans both slices) behind the barrier of phase 1 only.
+// The wave waits for its own copies in front of each barrier: `s_waitcnt vmcnt(n)` with n = the number of
+// younger copies that may still be in flight; every copy has (nearly) a whole k-step to arrive.  With all 16
+// copies of a (k-strided, k-strided) problem behind the one barrier of phase 1 (the previous form, one copy
+// per 3.5 MFMAs) the memory pipeline did not keep up, and an MFMA behind a copy that cannot issue yet waits
+// with it; spread over both phases (one per 7 MFMAs) the weight-gradient shapes of the 12B stage gained
+// 4 % (1212 -> 1262 TFLOP/s).  Splitting k-contiguous tiles the same way needs copies of 64 bytes per row,
+// half a cache line: measured 3-6 % slower than whole lines behind one barrier.
 // The copies are inline assembly: the compiler neither sees them nor counts them in vmcnt, so the
 // waits on them are written out here, and the loop contains no other vector memory instruction.
 __device__ __forceinline__ void dma_chunk16(u32x4 rsrc, uint32_t voffset, uint32_t soffset, uint32_t lds_addr) {
@@ -657,12 +667,16 @@ __device__ __forceinline__ void dma_chunk16(u32x4 rsrc, uint32_t voffset, uint32
                : "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
                : "memory");
 }
-// The same in two parts, for an independent instruction (an MFMA) in between instead of the s_nop.
-__device__ __forceinline__ void dma_set_m0(uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0" : : "s"(lds_addr) : "memory");
-}
-__device__ __forceinline__ void dma_chunk16_m0(u32x4 rsrc, uint32_t voffset, uint32_t soffset) {
-  asm volatile("buffer_load_dwordx4 %0, %1, %2 offen lds" : : "v"(voffset), "s"(rsrc), "s"(soffset) : "memory");
+// One MFMA with a copy around it: M0 is written in front of the MFMA and consumed behind it (the MFMA is
+// the independent instruction the hardware wants between the two).  One statement, so that nothing the
+// compiler emits can come between the write of M0 and its use.
+__device__ __forceinline__ void mfma16_acc_dma(floatx4& c, elemx8 a, elemx8 b, u32x4 rsrc, uint32_t voffset,
+                                               uint32_t soffset, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %3\n\t" AXONN_MFMA_16X16X32_ASM " %0, %1, %2, %0\n\t"
+               "buffer_load_dwordx4 %4, %5, %6 offen lds"
+               : "+a"(c)
+               : "v"(a), "v"(b), "s"(lds_addr), "v"(voffset), "s"(rsrc), "s"(soffset)
+               : "memory");
 }
 __device__ __forceinline__ void dma_wait_all() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -674,18 +688,32 @@ __device__ __forceinline__ u32x4 rsrc_words(const void* p, uint32_t bytes) {
   return r;
 }
 
+// The copy instructions of a k-step in the order they are issued.  Phase 0: the first halves of the
+// k-strided operands.  Phase 1: the k-contiguous operands, then the second halves of the k-strided ones.
+// Returns c for copy instruction c of A, nca + c for copy instruction c of B.
+constexpr int dma_count(bool a_kc, bool b_kc, int nca, int ncb, int phase) {
+  return phase == 0 ? (a_kc ? 0 : nca / 2) + (b_kc ? 0 : ncb / 2) : (a_kc ? nca : nca / 2) + (b_kc ? ncb : ncb / 2);
+}
+constexpr int dma_item(bool a_kc, bool b_kc, int nca, int ncb, int phase, int d) {
+  if (phase == 0) {
+    if (!a_kc) { if (d < nca / 2) return d; d -= nca / 2; }
+    return nca + d;
+  }
+  if (a_kc) { if (d < nca) return d; d -= nca; }
+  if (b_kc) { if (d < ncb) return nca + d; d -= ncb; }
+  if (!a_kc) { if (d < nca / 2) return nca / 2 + d; d -= nca / 2; }
+  return nca + ncb / 2 + d;
+}
+
 template <bool A_KC, bool B_KC, int EPI, int TN>
 __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
   constexpr int BM = 256, BN = 32 * TN, BK = 64, TM = 8;
   constexpr int NCA = 8, NCB = B_KC ? TN : 8;     // copy instructions per wave and tile
   constexpr int NM = TM * TN, NF = TM + TN, ND = NCA + NCB;
-  // The copies of a k-step are spread over all of phase 1 behind the barrier.  Issued back to back they
-  // would have longer until the next barrier, but the memory pipeline takes them only so fast and the
-  // MFMAs behind a copy that cannot issue wait with it: measured 6-9 % slower.
-#ifndef AXONN_DMA_SPAN
-#define AXONN_DMA_SPAN (NM - 8)
-#endif
-  constexpr int DMA_FIRST = 7, DMA_SPAN = AXONN_DMA_SPAN;
+  // copies per phase; of those of phase 1, the ones that belong to k-strided operands (issued last)
+  constexpr int N0 = dma_count(A_KC, B_KC, NCA, NCB, 0), N1 = dma_count(A_KC, B_KC, NCA, NCB, 1);
+  constexpr int N1S = (A_KC ? 0 : NCA / 2) + (B_KC ? 0 : NCB / 2);
+  static_assert(N0 + N1 == ND && 2 * (N0 + N1) < 64, "copy bookkeeping");
   constexpr int KS_BLOCK = 1024 + 32;             // two k rows of a k-strided tile and their padding
   constexpr int SA = A_KC ? BM * BK * 2 : 32 * KS_BLOCK;              // bytes of one stage of A
   constexpr int SB = B_KC ? BN * BK * 2 : 32 * KS_BLOCK;              // and of B
@@ -787,12 +815,16 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
   }
   // The tile after the last one of the last segment does not exist: a descriptor of size 0 makes its
   // copies write zeros (the tile that pads an odd tile count is multiplied, the others are not read).
-#define AXONN_DMA_M0(buf, d)                                                                   \
-  if ((d) < NCA) dma_set_m0(lds0 + (buf) * SA + ((d) * 4 + wave) * (A_KC ? 1024 : KS_BLOCK));  \
-  else dma_set_m0(lds0 + 2 * SA + (buf) * SB + (((d) - NCA) * 4 + wave) * (B_KC ? 1024 : KS_BLOCK));
-#define AXONN_DMA_LOAD(d)                                                                      \
-  if ((d) < NCA) dma_chunk16_m0(rsa, va[(d) < NCA ? (d) : 0], (uint32_t)ld_kin * sa);          \
-  else dma_chunk16_m0(rsb, vb[(d) >= NCA ? (d) - NCA : 0], (uint32_t)ld_kin * sb);
+#define AXONN_MFMA_DMA(F, q, buf, d)                                                           \
+  if ((d) < NCA) {                                                                             \
+    mfma16_acc_dma(acc[(q) / TN][(q) % TN], fb[F][(q) % TN], fa[F][(q) / TN], rsa,             \
+                   va[(d) < NCA ? (d) : 0], (uint32_t)ld_kin * sa,                             \
+                   lds0 + (buf) * SA + ((d) * 4 + wave) * (A_KC ? 1024 : KS_BLOCK));           \
+  } else {                                                                                     \
+    mfma16_acc_dma(acc[(q) / TN][(q) % TN], fb[F][(q) % TN], fa[F][(q) / TN], rsb,             \
+                   vb[(d) >= NCA ? (d) - NCA : 0], (uint32_t)ld_kin * sb,                      \
+                   lds0 + 2 * SA + (buf) * SB + (((d) - NCA) * 4 + wave) * (B_KC ? 1024 : KS_BLOCK)); \
+  }
 #define AXONN_DMA_NEXT()                                                                       \
   if (++ld_kin == tps) {                                                                       \
     ld_kin = 0;                                                                                \
@@ -827,26 +859,37 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
     }                                                                                          \
   }
 #define AXONN_MFMA(F, q) mfma16_acc(acc[(q) / TN][(q) % TN], fb[F][(q) % TN], fa[F][(q) / TN]);
-#define AXONN_KSTEP(CUR)                                                                       \
-  _Pragma("unroll") for (int q = 0; q < NM; ++q) {                                             \
-    AXONN_MFMA(0, q)                                                                           \
-    { const int f = item_at(q, NF, 0, NM - 3); if (f >= 0) { AXONN_FRAG(1, CUR, 1, f) } }      \
-    __builtin_amdgcn_sched_barrier(0);                                                         \
-  }                                                                                            \
-  _Pragma("unroll") for (int q = 0; q < 6; ++q) {                                              \
-    AXONN_MFMA(1, q)                                                                           \
-    __builtin_amdgcn_sched_barrier(0);                                                         \
-  }                                                                                            \
-  dma_wait_all();                                                                              \
-  lds_barrier();                                                                               \
-  _Pragma("unroll") for (int q = 6; q < NM; ++q) {                                             \
-    const int d = item_at(q, ND, DMA_FIRST, DMA_SPAN);                                         \
-    if (d >= 0) { AXONN_DMA_M0(CUR, d) }                                                       \
-    AXONN_MFMA(1, q)                                                                           \
-    if (d >= 0) { AXONN_DMA_LOAD(d) }                                                          \
-    { const int f = item_at(q, NF, 8, NM - 8); if (f >= 0) { AXONN_FRAG(0, (CUR) ^ 1, 0, f) } } \
-    __builtin_amdgcn_sched_barrier(0);                                                         \
-  }                                                                                            \
+  // One phase: multiplies the fragments of set FMUL; reads k slice RDKK of stage RDBUF into set FRD and
+  // issues the copies of phase PH of the next tile to fetch into stage DMABUF.  Phase 0 of a problem without a
+  // k-strided operand has no copies, no wait and no barrier.
+#define AXONN_PHASE(FMUL, FRD, RDBUF, RDKK, DMABUF, PH)                                          \
+  if ((PH) == 1 || N0 > 0) {                                                                     \
+    _Pragma("unroll") for (int q = 0; q < 6; ++q) {                                              \
+      AXONN_MFMA(FMUL, q)                                                                        \
+      __builtin_amdgcn_sched_barrier(0);                                                         \
+    }                                                                                            \
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"((PH) == 0 ? N0 + N1 : N1S + N0) : "memory");      \
+    lds_barrier();                                                                               \
+    _Pragma("unroll") for (int q = 6; q < NM; ++q) {                                             \
+      const int dd = item_at(q, (PH) == 0 ? N0 : N1, 7, NM - 8);                                 \
+      if (dd >= 0) {                                                                             \
+        AXONN_MFMA_DMA(FMUL, q, DMABUF, dma_item(A_KC, B_KC, NCA, NCB, PH, dd))                  \
+      } else {                                                                                   \
+        AXONN_MFMA(FMUL, q)                                                                      \
+      }                                                                                          \
+      { const int f = item_at(q, NF, 8, NM - 8); if (f >= 0) { AXONN_FRAG(FRD, RDBUF, RDKK, f) } } \
+      __builtin_amdgcn_sched_barrier(0);                                                         \
+    }                                                                                            \
+  } else {                                                                                       \
+    _Pragma("unroll") for (int q = 0; q < NM; ++q) {                                             \
+      AXONN_MFMA(FMUL, q)                                                                        \
+      { const int f = item_at(q, NF, 0, NM - 3); if (f >= 0) { AXONN_FRAG(FRD, RDBUF, RDKK, f) } } \
+      __builtin_amdgcn_sched_barrier(0);                                                         \
+    }                                                                                            \
+  }
+#define AXONN_KSTEP(CUR)                                                                         \
+  AXONN_PHASE(0, 1, CUR, 1, CUR, 0)                                                              \
+  AXONN_PHASE(1, 0, (CUR) ^ 1, 0, CUR, 1)                                                        \
   AXONN_DMA_NEXT()
 
   floatx4 acc[TM][TN];
@@ -858,14 +901,17 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
   elemx8 fa[2][TM], fb[2][TN];
 
-  // prologue: tiles 0 and 1 into stages 0 and 1
+  // prologue: tiles 0 and 1 into stages 0 and 1, in the order of the loop
 #pragma unroll
-  for (int d = 0; d < ND; ++d) { AXONN_DMA(0, d) }
-  AXONN_DMA_NEXT()
+  for (int t = 0; t < 2; ++t) {
 #pragma unroll
-  for (int d = 0; d < ND; ++d) { AXONN_DMA(1, d) }
-  AXONN_DMA_NEXT()
-  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(ND) : "memory");   // tile 0 has arrived, tile 1 may still be on its way
+    for (int d = 0; d < N0; ++d) { AXONN_DMA(t, dma_item(A_KC, B_KC, NCA, NCB, 0, d)) }
+#pragma unroll
+    for (int d = 0; d < N1; ++d) { AXONN_DMA(t, dma_item(A_KC, B_KC, NCA, NCB, 1, d)) }
+    AXONN_DMA_NEXT()
+  }
+  // k slice 0 of tile 0 has arrived once the only copies in flight are its second halves and tile 1
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N1S + N0 + N1) : "memory");
   lds_barrier();
 #pragma unroll
   for (int f = 0; f < NF; ++f) { AXONN_FRAG(0, 0, 0, f) }
@@ -877,8 +923,8 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
   dma_wait_all();                            // copies of tiles past the end still write (zeros) to LDS
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // last MFMAs drain before the results are read
 #undef AXONN_DMA
-#undef AXONN_DMA_M0
-#undef AXONN_DMA_LOAD
+#undef AXONN_MFMA_DMA
+#undef AXONN_PHASE
 #undef AXONN_DMA_NEXT
 #undef AXONN_FRAG
 #undef AXONN_MFMA
@@ -934,22 +980,15 @@ static hipError_t launch_big(int epi, GemmArgs g, hipStream_t s) {
   g.tiles_m = (g.M + 255) / 256;
   g.tiles_n = (g.N + 32 * TN - 1) / (32 * TN);
   const dim3 grid(g.tiles_m * g.tiles_n), block(256);
-  // The kernel with copies by the memory pipeline needs whole k tiles.  Alone on the chip it pays where the
-  // operands come mostly from the L2, the weight gradients with a bf16 result; its copies have less time to
-  // arrive than the chunks of the register-staged kernel, and where more of them come from HBM (long K with few
-  // tiles per operand strip; the read-modify-write of an fp32 result in the background) it is the slower one.
-  // When other kernels share the chip, throughput is bound by the chip's power limit and the kernel that
-  // draws less per k-step wins for the other layouts too, if the launch fills the chip at least once and K
-  // is not long (measured on whole batches of the stage: +2 % on the 24B shape, +1 % on the 100B shape, a
-  // tie on the 12B shape; with K = 18048 in it, -1.4 % on the h = 4512 shape).
-  // For tuning: AXONN_GEMM_DMA fixes the choice per class (bit 0 (kc,kc), bit 1 (kc,ks), bit 2 (ks,ks) with a
-  // bf16 result, bit 3 (ks,ks) with an fp32 result); AXONN_GEMM_DMA_MIN_TILES and AXONN_GEMM_DMA_MAX_K move
-  // the two bounds.
+  // The kernel with copies by the memory pipeline needs whole k tiles.  It is the faster one for every layout
+  // with a 16-bit result (single launches of the 12B-shape problems: forward +11 %, input gradients +4 %, weight
+  // gradients +8 % over the register-staged kernel; whole batches of the 12B / 24B / 100B stage shapes 3.4 / 3.3 /
+  // 4.3 % faster than with the previous choice); with an fp32 read-modify-write result the register-staged
+  // kernel stays ahead (110.3 vs 111.0 ms per 12B batch).
+  // For tuning and tests: AXONN_GEMM_DMA fixes the choice per class (bit 0 (kc,kc), bit 1 (kc,ks), bit 2 (ks,ks)
+  // with a 16-bit result, bit 3 (ks,ks) with an fp32 result).
   static const int64_t dma_mask_env = env_int("AXONN_GEMM_DMA", -1);
-  static const int64_t dma_min_tiles = env_int("AXONN_GEMM_DMA_MIN_TILES", 256);
-  static const int64_t dma_max_k = env_int("AXONN_GEMM_DMA_MAX_K", 16384);
-  const bool shared_chip_case = g.concurrent && (int64_t)g.tiles_m * g.tiles_n >= dma_min_tiles && g.K <= dma_max_k;
-  const int64_t dma_mask = dma_mask_env >= 0 ? dma_mask_env : (shared_chip_case ? 7 : 4);
+  const int64_t dma_mask = dma_mask_env >= 0 ? dma_mask_env : 7;
   const int dma_bit = A_KC ? (B_KC ? 0 : 1) : (epi == EPI_ACC_F32 ? 3 : 2);
   const bool use_dma = ((dma_mask >> dma_bit) & 1) && g.K % 64 == 0;
 #define AXONN_GEMM_CASE(E)                                                                      \
@@ -998,7 +1037,8 @@ static int choose_tn(int64_t M, int64_t N, int64_t nk, bool concurrent) {
   static const int64_t forced = env_int("AXONN_GEMM_TILE_N", 0);
   if (forced == 160) return 5;
   if (forced == 192) return 6;
-  if (forced == 256 || concurrent) return 8;
+  static const int64_t ignore_conc = env_int("AXONN_GEMM_IGNORE_CONCURRENT", 0);
+  if (forced == 256 || (concurrent && !ignore_conc)) return 8;
   const int cand[3] = {8, 6, 5};
   int best = 8;
   double best_cost = 0;
