@@ -689,20 +689,42 @@ __device__ __forceinline__ u32x4 rsrc_words(const void* p, uint32_t bytes) {
 }
 
 // The copy instructions of a k-step in the order they are issued.  Phase 0: the first halves of the
-// k-strided operands.  Phase 1: the k-contiguous operands, then the second halves of the k-strided ones.
+// k-strided operands and the "early" rows of a k-contiguous A.  Phase 1: the rest of the k-contiguous
+// operands, then the second halves of the k-strided ones.
+// The early rows of a k-contiguous A are those of the fragments i < 4 of either wave row (tile rows 0..63 and
+// 128..191, copy instructions 0, 1, 4, 5): an MFMA phase uses A fragment i in MFMAs i*TN .. i*TN + TN-1 only, so
+// the registers of the fragments i < 4 of k slice 1 are free half way through phase 1, and that half of the phase
+// reads into them the same fragments of the NEXT tile (which a k-contiguous copy has delivered together with its
+// slice 0).  Those rows of the stage are then free one phase earlier than the others.
 // Returns c for copy instruction c of A, nca + c for copy instruction c of B.
+#ifndef AXONN_DMA_XY
+#define AXONN_DMA_XY 1
+#endif
+constexpr bool kDmaEarlyRows = AXONN_DMA_XY != 0;
 constexpr int dma_count(bool a_kc, bool b_kc, int nca, int ncb, int phase) {
-  return phase == 0 ? (a_kc ? 0 : nca / 2) + (b_kc ? 0 : ncb / 2) : (a_kc ? nca : nca / 2) + (b_kc ? ncb : ncb / 2);
+  const bool a_split = !a_kc || kDmaEarlyRows;
+  return phase == 0 ? (a_split ? nca / 2 : 0) + (b_kc ? 0 : ncb / 2) : (a_split ? nca / 2 : nca) + (b_kc ? ncb : ncb / 2);
+}
+constexpr int dma_early_row_item(int d, bool early) {      // 0, 1, 4, 5 / 2, 3, 6, 7
+  return (d & 1) + 4 * (d >> 1) + (early ? 0 : 2);
 }
 constexpr int dma_item(bool a_kc, bool b_kc, int nca, int ncb, int phase, int d) {
   if (phase == 0) {
-    if (!a_kc) { if (d < nca / 2) return d; d -= nca / 2; }
+    if (!a_kc || kDmaEarlyRows) { if (d < nca / 2) return a_kc ? dma_early_row_item(d, true) : d; d -= nca / 2; }
     return nca + d;
   }
-  if (a_kc) { if (d < nca) return d; d -= nca; }
+  if (a_kc && kDmaEarlyRows) { if (d < nca / 2) return dma_early_row_item(d, false); d -= nca / 2; }
+  if (a_kc && !kDmaEarlyRows) { if (d < nca) return d; d -= nca; }
   if (b_kc) { if (d < ncb) return nca + d; d -= ncb; }
   if (!a_kc) { if (d < nca / 2) return nca / 2 + d; d -= nca / 2; }
   return nca + ncb / 2 + d;
+}
+// Fragment f (0: a0, 1..tn: b0.., tn+1..: a1..) that is the k-th one read in a phase; with early rows the
+// fragments a0..a3 of slice 1 are not read in phase 0.
+constexpr int frag_count(bool a_early, int tn, int phase) { return 8 + tn - (a_early && phase == 0 ? 4 : 0); }
+constexpr int frag_item(bool a_early, int tn, int phase, int k) {
+  if (!(a_early && phase == 0)) return k;
+  return k < tn ? k + 1 : k + 4;      // b0 .. b(tn-1), then a4 .. a7
 }
 
 template <bool A_KC, bool B_KC, int EPI, int TN>
@@ -714,6 +736,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
   constexpr int N0 = dma_count(A_KC, B_KC, NCA, NCB, 0), N1 = dma_count(A_KC, B_KC, NCA, NCB, 1);
   constexpr int N1S = (A_KC ? 0 : NCA / 2) + (B_KC ? 0 : NCB / 2);
   static_assert(N0 + N1 == ND && 2 * (N0 + N1) < 64, "copy bookkeeping");
+  constexpr bool A_EARLY = A_KC && kDmaEarlyRows;
   constexpr int KS_BLOCK = 1024 + 32;             // two k rows of a k-strided tile and their padding
   constexpr int SA = A_KC ? BM * BK * 2 : 32 * KS_BLOCK;              // bytes of one stage of A
   constexpr int SB = B_KC ? BN * BK * 2 : 32 * KS_BLOCK;              // and of B
@@ -877,7 +900,12 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
       } else {                                                                                   \
         AXONN_MFMA(FMUL, q)                                                                      \
       }                                                                                          \
-      { const int f = item_at(q, NF, 8, NM - 8); if (f >= 0) { AXONN_FRAG(FRD, RDBUF, RDKK, f) } } \
+      { const int k = item_at(q, frag_count(A_EARLY, TN, PH), 8, NM - 8);                        \
+        if (k >= 0) { AXONN_FRAG(FRD, RDBUF, RDKK, frag_item(A_EARLY, TN, PH, k)) } }            \
+      if (A_EARLY && (PH) == 1) {      /* a0..a3 of slice 1 of the same tile, into registers that are free by now */ \
+        const int e = item_at(q, 4, 4 * TN + 2, NM - 4 * TN - 3);                                \
+        if (e >= 0) { AXONN_FRAG(FMUL, RDBUF, 1, e == 0 ? 0 : TN + e) }                          \
+      }                                                                                          \
       __builtin_amdgcn_sched_barrier(0);                                                         \
     }                                                                                            \
   } else {                                                                                       \
@@ -915,6 +943,10 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
   lds_barrier();
 #pragma unroll
   for (int f = 0; f < NF; ++f) { AXONN_FRAG(0, 0, 0, f) }
+  if (A_EARLY) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { AXONN_FRAG(1, 0, 1, e == 0 ? 0 : TN + e) }
+  }
   asm volatile("s_nop 7" ::: "memory");      // accumulators were just zeroed: settle before the first MFMA
   for (int kt = 0; kt < nk; kt += 2) {
     AXONN_KSTEP(0)
