@@ -18,7 +18,10 @@ SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "lm_ends.hip", "stage
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         "-Wall", "-Wno-unused-function"]
+         "-Wall", "-Wno-unused-function",
+         # the GEMM main loops are written as fully unrolled loops over compile-time schedules (`#pragma unroll`):
+         # left partly rolled, their fragment arrays would live in scratch memory instead of registers
+         "-mllvm", "-pragma-unroll-threshold=100000"]
 
 
 def _compile(job):

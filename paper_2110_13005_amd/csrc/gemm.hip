@@ -33,6 +33,28 @@ __device__ __forceinline__ void lds_barrier() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+// Output tile (tm, tn) of this workgroup.  Workgroups are dealt round-robin to the 8 XCDs, each with an L2 of
+// its own; the ids are remapped so that each XCD works on a contiguous run of tiles, and the tiles are ordered
+// in bands of 8 tiles across the SHORTER side of the tile grid, walked along the longer side: the ~32 tiles an
+// XCD has in flight then form an 8 x 4 patch that shares 8 + 4 operand panels instead of streaming 32 + 1, and
+// the eight XCDs together work on few bands at a time (bands across the longer side -- 80 x 20 tiles, the
+// weight gradient of the second MLP matrix -- put a different band, with 8 panels of the wide operand, on
+// every XCD: 192 MB of panels in flight, beyond what the 256 MB last-level cache holds beside the rest).
+__device__ __forceinline__ void tile_of_block(int tiles_m, int tiles_n, int& tm, int& tn) {
+  int pid = blockIdx.x;
+  const int nblk = gridDim.x;
+  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
+  constexpr int BAND = 8;
+  const bool wide = tiles_m <= tiles_n;                    // bands of tile rows, walked column by column
+  const int t_band = wide ? tiles_m : tiles_n, t_walk = wide ? tiles_n : tiles_m;
+  const int band_tiles = BAND * t_walk;
+  const int band = pid / band_tiles, in_band = pid - band * band_tiles;
+  const int band_w = min(BAND, t_band - band * BAND);
+  const int a = band * BAND + in_band % band_w, b = in_band / band_w;
+  tm = wide ? a : b;
+  tn = wide ? b : a;
+}
+
 template <int ROWS, int BK, bool KC>
 struct TileLayout {
   // leading dimension in elements, padded so that fragment reads spread over LDS banks
@@ -264,14 +286,8 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
   // contiguous run of tiles, and order tiles in bands of 8 tile-rows, column by column inside a band:
   // the ~32 tiles an XCD has in flight then form an 8 x 4 patch that shares 8 A panels and 4 B
   // panels instead of streaming 32 + 1.
-  int pid = blockIdx.x;
-  const int nblk = gridDim.x;
-  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
-  constexpr int BAND = 8;
-  const int band_tiles = BAND * g.tiles_n;
-  const int band = pid / band_tiles, in_band = pid - band * band_tiles;
-  const int band_rows = min(BAND, g.tiles_m - band * BAND);
-  const int tm = band * BAND + in_band % band_rows, tn = in_band / band_rows;
+  int tm, tn;
+  tile_of_block(g.tiles_m, g.tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
 
   // Per-thread view of the tile copy: chunk j of this thread is 16 bytes at offset offa[j] of the
@@ -455,14 +471,8 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
 
   // Workgroups are dealt round-robin to the 8 XCDs; remap so that each XCD (own L2) works on a
   // contiguous run of tiles, ordered in bands of 8 tile-rows, column by column inside a band.
-  int pid = blockIdx.x;
-  const int nblk = gridDim.x;
-  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
-  constexpr int BAND = 8;
-  const int band_tiles = BAND * g.tiles_n;
-  const int band = pid / band_tiles, in_band = pid - band * band_tiles;
-  const int band_rows = min(BAND, g.tiles_m - band * BAND);
-  const int tm = band * BAND + in_band % band_rows, tn = in_band / band_rows;
+  int tm, tn;
+  tile_of_block(g.tiles_m, g.tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
 
   // Chunk j of this thread of operand A: byte offset va + j * ja from the segment base, advanced by sa per
@@ -749,14 +759,8 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
-  int pid = blockIdx.x;
-  const int nblk = gridDim.x;
-  if ((nblk & 7) == 0) pid = (pid & 7) * (nblk >> 3) + (pid >> 3);
-  constexpr int BAND = 8;
-  const int band_tiles = BAND * g.tiles_n;
-  const int band = pid / band_tiles, in_band = pid - band * band_tiles;
-  const int band_rows = min(BAND, g.tiles_m - band * BAND);
-  const int tm = band * BAND + in_band % band_rows, tn = in_band / band_rows;
+  int tm, tn;
+  tile_of_block(g.tiles_m, g.tiles_n, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
 
   // Copy instruction c of this wave: the byte offset of each lane's chunk from the segment base in
