@@ -135,7 +135,7 @@ __device__ __forceinline__ elem_t f2bf(float v) { return (elem_t)v; }
 // the derivative needs as well.
 __device__ __forceinline__ float normal_cdf_f(float x, float& e) {
   const float z = fabsf(x) * 0.70710678118654752440f;
-  const float t = __frcp_rn(1.0f + 0.3275911f * z);
+  const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);   // v_rcp_f32 (1 ulp), not the 10-instruction IEEE division
   e = __expf(-z * z);
   float p = 1.061405429f;
   p = p * t - 1.453152027f;

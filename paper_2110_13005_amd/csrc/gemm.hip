@@ -88,16 +88,22 @@ __device__ __forceinline__ bool epi_reads_operand(const GemmArgs& g) {
          ((EPI == EPI_ACC_F32 || EPI == EPI_ACC_BF16) && g.accumulate);
 }
 
+// Leading dimension of what the epilogue reads or writes beside C (residual; stored derivative).
 template <int EPI>
-__device__ __forceinline__ EpiOperand epi_load_operand(const GemmArgs& g, int m, int n) {
+__device__ __forceinline__ int64_t epi_ld_side(const GemmArgs& g) {
+  return EPI == EPI_BIAS_RES ? g.ld_res : (EPI == EPI_DGELU || EPI == EPI_BIAS_GELU) ? g.ld_aux : g.ldc;
+}
+// off_c = m * ldc + n, off_side = m * epi_ld_side + n (element offsets of the position).
+template <int EPI>
+__device__ __forceinline__ EpiOperand epi_load_operand(const GemmArgs& g, int64_t off_c, int64_t off_side) {
   EpiOperand o;
   if (EPI == EPI_ACC_F32) {
-    const u32x4 t = *reinterpret_cast<const u32x4*>(reinterpret_cast<const float*>(g.C) + (int64_t)m * g.ldc + n);
+    const u32x4 t = *reinterpret_cast<const u32x4*>(reinterpret_cast<const float*>(g.C) + off_c);
     o.raw[0] = t[0]; o.raw[1] = t[1]; o.raw[2] = t[2]; o.raw[3] = t[3];
   } else {
-    const elem_t* p = EPI == EPI_BIAS_RES ? g.res + (int64_t)m * g.ld_res + n
-                    : EPI == EPI_DGELU    ? g.aux + (int64_t)m * g.ld_aux + n
-                                          : reinterpret_cast<const elem_t*>(g.C) + (int64_t)m * g.ldc + n;
+    const elem_t* p = EPI == EPI_BIAS_RES ? g.res + off_side
+                    : EPI == EPI_DGELU    ? g.aux + off_side
+                                          : reinterpret_cast<const elem_t*>(g.C) + off_c;
     const uint2 t = *reinterpret_cast<const uint2*>(p);
     o.raw[0] = t.x; o.raw[1] = t.y; o.raw[2] = 0u; o.raw[3] = 0u;
   }
@@ -125,7 +131,7 @@ __device__ __forceinline__ void epi_operand_values(const EpiOperand& o, float (&
 // bias, `o` = the operand loaded with epi_load_operand (ignored if the epilogue reads none).
 template <int EPI>
 __device__ __forceinline__ void epi_finish(float (&v)[4], const float (&bv)[4], const EpiOperand& o,
-                                           const GemmArgs& g, int m, int n) {
+                                           const GemmArgs& g, int64_t off_c, int64_t off_side) {
   float x[4] = {0.f, 0.f, 0.f, 0.f};
   if (epi_reads_operand<EPI>(g)) epi_operand_values<EPI>(o, x);
   if (EPI == EPI_BIAS || EPI == EPI_BIAS_RES || EPI == EPI_BIAS_GELU) {
@@ -147,20 +153,19 @@ __device__ __forceinline__ void epi_finish(float (&v)[4], const float (&bv)[4], 
       v[e] = y;
       dv[e] = (elem_t)dy;
     }
-    *reinterpret_cast<elemx4*>(g.aux + (int64_t)m * g.ld_aux + n) = dv;
+    *reinterpret_cast<elemx4*>(g.aux + off_side) = dv;
   }
   if (EPI == EPI_DGELU) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) v[e] *= x[e];
   }
   if (EPI == EPI_ACC_F32) {
-    *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(g.C) + (int64_t)m * g.ldc + n) =
-        floatx4{v[0], v[1], v[2], v[3]};
+    *reinterpret_cast<floatx4*>(reinterpret_cast<float*>(g.C) + off_c) = floatx4{v[0], v[1], v[2], v[3]};
   } else {
     elemx4 ov;
 #pragma unroll
     for (int e = 0; e < 4; ++e) ov[e] = (elem_t)v[e];
-    *reinterpret_cast<elemx4*>(reinterpret_cast<elem_t*>(g.C) + (int64_t)m * g.ldc + n) = ov;
+    *reinterpret_cast<elemx4*>(reinterpret_cast<elem_t*>(g.C) + off_c) = ov;
   }
 }
 
@@ -168,8 +173,9 @@ template <int EPI>
 __device__ __forceinline__ void epilogue_run(float (&v)[4], const float (&bv)[4], const GemmArgs& g,
                                              int m, int n) {
   EpiOperand o;
-  if (epi_reads_operand<EPI>(g)) o = epi_load_operand<EPI>(g, m, n);
-  epi_finish<EPI>(v, bv, o, g, m, n);
+  const int64_t off_c = (int64_t)m * g.ldc + n, off_side = (int64_t)m * epi_ld_side<EPI>(g) + n;
+  if (epi_reads_operand<EPI>(g)) o = epi_load_operand<EPI>(g, off_c, off_side);
+  epi_finish<EPI>(v, bv, o, g, off_c, off_side);
 }
 
 // Writes one wave's TM x TN result tiles of the 32x32x16 MFMA.  The MFMA was issued with the B
@@ -226,13 +232,22 @@ __device__ __forceinline__ void gemm_epilogue_staged(const floatx4 (&acc)[8][TN]
   constexpr int OB = (EPI == EPI_ACC_F32) ? 16 : 64;
   EpiOperand opnd[OB];
   const bool reads = epi_reads_operand<EPI>(g);
+  // element offsets of this lane's position in row pair 0 and their step from one row pair to the next:
+  // additions per position instead of 64-bit multiplications
+  const int64_t ld_side = epi_ld_side<EPI>(g);
+  const int64_t off_c0 = (int64_t)(m_base + (lane >> 5)) * g.ldc + n, off_s0 = (int64_t)(m_base + (lane >> 5)) * ld_side + n;
+  const int64_t step_c = 2 * g.ldc, step_s = 2 * ld_side;
   if (OB == 64 && reads) {
+    int64_t oc = off_c0, os = off_s0;
 #pragma unroll
     for (int t = 0; t < 64; ++t) {
       const int m = m_base + 2 * t + (lane >> 5);
-      if (m < g.M && col_ok) opnd[t] = epi_load_operand<EPI>(g, m, n);
+      if (m < g.M && col_ok) opnd[t] = epi_load_operand<EPI>(g, oc, os);
+      oc += step_c; os += step_s;
     }
   }
+  int64_t oc_l = off_c0, os_l = off_s0;       // positions of the loads of an fp32 C, 16 row pairs at a time
+  int64_t oc = off_c0, os = off_s0;
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
 #pragma unroll
@@ -247,7 +262,8 @@ __device__ __forceinline__ void gemm_epilogue_staged(const floatx4 (&acc)[8][TN]
 #pragma unroll
         for (int tt = 0; tt < 16; ++tt) {
           const int m = m_base + 64 * p + 2 * (16 * hh + tt) + (lane >> 5);
-          if (m < g.M && col_ok) opnd[tt] = epi_load_operand<EPI>(g, m, n);
+          if (m < g.M && col_ok) opnd[tt] = epi_load_operand<EPI>(g, oc_l, os_l);
+          oc_l += step_c; os_l += step_s;
         }
       }
 #pragma unroll
@@ -257,8 +273,9 @@ __device__ __forceinline__ void gemm_epilogue_staged(const floatx4 (&acc)[8][TN]
         if (m < g.M && col_ok) {
           const floatx4 x = *reinterpret_cast<const floatx4*>(stage + r * LD + nl);
           float v[4] = {x[0], x[1], x[2], x[3]};
-          epi_finish<EPI>(v, bv, opnd[OB == 64 ? 32 * p + 16 * hh + tt : tt], g, m, n);
+          epi_finish<EPI>(v, bv, opnd[OB == 64 ? 32 * p + 16 * hh + tt : tt], g, oc, os);
         }
+        oc += step_c; os += step_s;
       }
     }
   }
