@@ -77,7 +77,11 @@ typedef struct {
                               one contraction of length 2h, so that the bf16 rounding of
                               the LayerNorm output does not reach the attention logits
                               (for shapes with large logits, e.g. h = 10240 with N(0,0.02)
-                              weights; costs one more QKV-sized GEMM per layer forward)  */
+                              weights: without it the worst weight gradient of that shape is
+                              3.4e-2 off the fp64 result, with it 2.6e-2; costs one more
+                              QKV-sized GEMM per layer forward).  2: the same for the Q and K
+                              thirds only, V from the rounded output as usual (two thirds of
+                              the extra cost)                                              */
   int32_t ckpt_stride;     /* activation checkpointing (Sec. 5.1): 0 keeps every activation of
                               a microbatch in flight; ac > 0 (a factor of n_layers) keeps only
                               the inputs of layers 0, ac, 2ac, ... and Backward regenerates
@@ -171,6 +175,11 @@ int axonn_stage_run(axonn_stage_t* st, int32_t n_streams, void* hip_stream);
  * dispatch log shows as done (with the message's done_event as their ready_event). */
 int axonn_stage_poll(axonn_stage_t* st, int32_t n_streams, void* hip_stream,
                      int32_t* n_dispatched, int32_t* n_remaining);
+/* Limit, in seconds, of each wait of axonn_stage_run for the next message to arrive (default 120): counted from
+ * the moment the loop finds nothing it can dispatch until it dispatches again, not from the start of the call.
+ * When it expires, run returns AXONN_ESTATE; nothing is lost: posted messages stay posted, dispatched work stays
+ * enqueued, and another axonn_stage_run resumes the batch (or synchronize and start over with zero_grad). */
+int axonn_stage_set_message_wait(axonn_stage_t* st, double seconds);
 /* Makes user_stream wait for everything the library streams have been given so far. */
 int axonn_stage_join(axonn_stage_t* st, void* user_stream);
 /* Blocks the host until all enqueued work of the stage is complete. */
@@ -206,7 +215,9 @@ int axonn_offload_adam_destroy(axonn_offload_adam_t* opt);
  * the call returns when the step is complete and the host arrays hold the new state (it
  * synchronizes hip_stream): a caller that ran ahead and queued its next batch behind a
  * pending step would fill the hardware queues that the step's copies share, which slows
- * the step by half.  step t >= 1. */
+ * the step by half.  step t >= 1.  If a HIP call fails in the middle of the step, the step's streams are drained
+ * before the error is returned (nothing is in flight any more); the buckets processed up to then are updated, the
+ * others untouched, and the message says how many. */
 int axonn_offload_adam_step(axonn_offload_adam_t* opt, double lr, double beta1, double beta2,
                             double eps, double weight_decay, int64_t step, double grad_scale,
                             void* hip_stream);
@@ -447,6 +458,30 @@ int axonn_profile_enable(int32_t on);
 int axonn_profile_num_categories(int32_t* n);
 int axonn_profile_category_name(int32_t idx, const char** name);
 int axonn_profile_collect(double* total_ms, int64_t* launches, int32_t n_categories);
+
+/* Tuning and test hooks of the GEMM launcher; process-wide, not needed in normal use.  value -1 restores the
+ * built-in rule.  AXONN_EINVAL for an unknown knob or a value out of range.
+ *   AXONN_TUNE_GEMM_COPY_MASK      which problem classes take the large-problem kernel whose tiles are copied
+ *                                  into LDS by the memory pipeline (instead of the register-staged one), as a bit
+ *                                  mask: 1 input gradients, 2 forward, 4 weight gradients with a 16-bit result,
+ *                                  8 weight gradients with an fp32 result (built-in: 7); it applies where K is a
+ *                                  multiple of 64
+ *   AXONN_TUNE_GEMM_BIG_MIN_TILES  number of 256 x 256 tiles from which the large-problem kernels are used
+ *                                  (built-in: 128)
+ *   AXONN_TUNE_GEMM_TILE_N         block width of the large-problem kernels: 160, 192 or 256 (0 or -1: chosen per
+ *                                  problem) */
+typedef enum {
+  AXONN_TUNE_GEMM_COPY_MASK = 0,
+  AXONN_TUNE_GEMM_BIG_MIN_TILES = 1,
+  AXONN_TUNE_GEMM_TILE_N = 2
+} axonn_tuning_knob;
+int axonn_tuning(int32_t knob, int64_t value);
+
+/* Bare copy rates of the host link (measurement aid): `reps` copies of `bytes` between pinned host memory and
+ * device memory with hipMemcpyAsync, as the optimizer pipeline issues them.  gbps_out[0]: host to device alone,
+ * [1]: device to host alone, [2]: per direction with both running at once (10^9 bytes per second).  Allocates and
+ * frees its own buffers; synchronizes the device. */
+int axonn_host_link_probe(int32_t device, uint64_t bytes, int32_t reps, double gbps_out[3]);
 
 #ifdef __cplusplus
 }

@@ -72,6 +72,7 @@ _PROTOTYPES = {
     "axonn_stage_run": [_vp, _i32, _vp],
     "axonn_stage_poll": [_vp, _i32, _vp, C.POINTER(_i32), C.POINTER(_i32)],
     "axonn_stage_join": [_vp, _vp],
+    "axonn_stage_set_message_wait": [_vp, _d],
     "axonn_stage_synchronize": [_vp],
     "axonn_stage_dispatch_log": [_vp, C.POINTER(_i32), _i32, C.POINTER(_i32)],
     "axonn_embed_create": [_i32, _i32, _i32, _i32, _i32, C.POINTER(_vp)],
@@ -110,6 +111,8 @@ _PROTOTYPES = {
     "axonn_profile_num_categories": [C.POINTER(_i32)],
     "axonn_profile_category_name": [_i32, C.POINTER(C.c_char_p)],
     "axonn_profile_collect": [C.POINTER(C.c_double), C.POINTER(_i64), _i32],
+    "axonn_host_link_probe": [_i32, _u64, _i32, C.POINTER(_d)],
+    "axonn_tuning": [_i32, _i64],
     "axonn_adam_bucket": [_u64, _vp, _vp, _vp, _vp, _vp, _d, _d, _d, _d, _d, _i64, _d, _vp],
 }
 EXPORTED_SYMBOLS = ["axonn_last_error", "axonn_element_type"] + sorted(_PROTOTYPES)
@@ -443,6 +446,24 @@ def axonn_adam_bucket(n, theta, m, v, grad16, param16, lr, beta1, beta2, eps, we
                       stream=None):
     _check(load().axonn_adam_bucket(n, _ptr(theta), _ptr(m), _ptr(v), _ptr(grad16), _ptr(param16), lr, beta1, beta2,
                                     eps, weight_decay, step, grad_scale, _stream(stream)))
+
+
+TUNE_GEMM_COPY_MASK, TUNE_GEMM_BIG_MIN_TILES, TUNE_GEMM_TILE_N = 0, 1, 2
+
+
+def axonn_tuning(knob, value):
+    _check(load().axonn_tuning(knob, value))
+
+
+def axonn_host_link_probe(device, n_bytes, reps):
+    """(host-to-device alone, device-to-host alone, each way with both running) in GB/s."""
+    out = (_d * 3)()
+    _check(load().axonn_host_link_probe(device, n_bytes, reps, out))
+    return out[0], out[1], out[2]
+
+
+def axonn_stage_set_message_wait(st, seconds):
+    _check(load().axonn_stage_set_message_wait(st, seconds))
 
 
 def axonn_profile_enable(on):

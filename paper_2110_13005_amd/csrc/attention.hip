@@ -119,9 +119,6 @@ __device__ __forceinline__ void attn_block(int n_bh, int& rank, int& bh) {
 // at one column (conflict-free when the stride is an odd multiple of 4 words) and with the transposing 64-bit
 // reads that take 32 bytes from each of 4 consecutive rows (conflict-free when 4 consecutive rows start at
 // least 8 words apart modulo the 64 banks).  12 or 52 words modulo 64 satisfy both.
-#ifndef AXONN_BWD_LD
-#define AXONN_BWD_LD(D) BothWaysStride<D>::LD
-#endif
 template <int D>
 struct BothWaysStride {
   static constexpr int WORDS_MOD = (D / 2) % 64;
@@ -334,7 +331,7 @@ template <int D, bool EXACT>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
     int s, int a, int n_bh, int d_arg, const elem_t* __restrict__ qkv, const elem_t* __restrict__ dout,
     const float* __restrict__ lse, const float* __restrict__ delta, elem_t* __restrict__ dqkv) {
-  constexpr int BQ = 64, LDQ = AXONN_BWD_LD(D), DT = D / 32, KK = D / 16;
+  constexpr int BQ = 64, LDQ = BothWaysStride<D>::LD, DT = D / 32, KK = D / 16;
   __shared__ __align__(16) elem_t sQ[BQ * LDQ];
   __shared__ __align__(16) elem_t sdO[BQ * LDQ];
   __shared__ __align__(16) float s_lse[BQ];
@@ -475,7 +472,7 @@ template <int D, bool EXACT>
 __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
     int s, int a, int n_bh, int d_arg, const elem_t* __restrict__ qkv, const elem_t* __restrict__ dout,
     const float* __restrict__ lse, const float* __restrict__ delta, elem_t* __restrict__ dqkv) {
-  constexpr int BKV = 64, LDK = AXONN_BWD_LD(D), DT = D / 32, KK = D / 16;
+  constexpr int BKV = 64, LDK = BothWaysStride<D>::LD, DT = D / 32, KK = D / 16;
   __shared__ __align__(16) elem_t sK[BKV * LDK];
   __shared__ __align__(16) elem_t sV[BKV * LDK];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;

@@ -189,6 +189,9 @@ struct GemmArgs {
 
 // All return hipError_t of the launch (hipGetLastError) and validate nothing: callers check.
 hipError_t launch_gemm(bool a_kc, bool b_kc, int epilogue, const GemmArgs& g, hipStream_t s);
+// Launcher settings behind axonn_tuning(): knob 0 copy-kernel mask, 1 large-kernel threshold in tiles, 2 forced
+// block width (0 or -1: the launcher's rule).  false: unknown knob or value out of range.
+bool set_gemm_tuning(int knob, int64_t value);
 hipError_t launch_layernorm_fwd(int64_t T, int64_t h, const void* x, const void* gamma,
                                 const void* beta, float eps, void* out, void* out_lo, float* stats,
                                 hipStream_t s);

@@ -15,7 +15,7 @@
 // lane of the result owns one row m and runs of 4 consecutive columns n: epilogue loads and
 // stores are 8-byte (bf16) or 16-byte (fp32) vectors along the contiguous dimension of C.
 #include "common.h"
-#include <cstdlib>
+#include <atomic>
 
 namespace axonn {
 
@@ -724,10 +724,7 @@ __device__ __forceinline__ u32x4 rsrc_words(const void* p, uint32_t bytes) {
 // reads into them the same fragments of the NEXT tile (which a k-contiguous copy has delivered together with its
 // slice 0).  Those rows of the stage are then free one phase earlier than the others.
 // Returns c for copy instruction c of A, nca + c for copy instruction c of B.
-#ifndef AXONN_DMA_XY
-#define AXONN_DMA_XY 1
-#endif
-constexpr bool kDmaEarlyRows = AXONN_DMA_XY != 0;
+constexpr bool kDmaEarlyRows = true;
 constexpr int dma_count(bool a_kc, bool b_kc, int nca, int ncb, int phase) {
   const bool a_split = !a_kc || kDmaEarlyRows;
   return phase == 0 ? (a_split ? nca / 2 : 0) + (b_kc ? 0 : ncb / 2) : (a_split ? nca / 2 : nca) + (b_kc ? ncb : ncb / 2);
@@ -1023,9 +1020,18 @@ static hipError_t launch_cfg(int epi, GemmArgs g, hipStream_t s) {
   return hipGetLastError();
 }
 
-static int64_t env_int(const char* name, int64_t dflt) {
-  const char* e = getenv(name);
-  return e && *e ? (int64_t)atoll(e) : dflt;
+// Launcher settings that axonn_tuning() can change (process-wide; -1 = the built-in rule).
+static std::atomic<int64_t> g_tune_copy_mask{-1}, g_tune_big_min_tiles{-1}, g_tune_tile_n{-1};
+
+bool set_gemm_tuning(int knob, int64_t value) {
+  if (value < -1) return false;
+  switch (knob) {
+    case 0: if (value > 15) return false; g_tune_copy_mask = value; return true;
+    case 1: g_tune_big_min_tiles = value; return true;
+    case 2: if (value != -1 && value != 0 && value != 160 && value != 192 && value != 256) return false;
+            g_tune_tile_n = value; return true;
+    default: return false;
+  }
 }
 
 template <bool A_KC, bool B_KC, int TN>
@@ -1038,10 +1044,11 @@ static hipError_t launch_big(int epi, GemmArgs g, hipStream_t s) {
   // gradients +8 % over the register-staged kernel; whole batches of the 12B / 24B / 100B stage shapes 3.4 / 3.3 /
   // 4.3 % faster than with the previous choice); with an fp32 read-modify-write result the register-staged
   // kernel stays ahead (110.3 vs 111.0 ms per 12B batch).
-  // For tuning and tests: AXONN_GEMM_DMA fixes the choice per class (bit 0 (kc,kc), bit 1 (kc,ks), bit 2 (ks,ks)
-  // with a 16-bit result, bit 3 (ks,ks) with an fp32 result).
-  static const int64_t dma_mask_env = env_int("AXONN_GEMM_DMA", -1);
-  const int64_t dma_mask = dma_mask_env >= 0 ? dma_mask_env : 7;
+  // axonn_tuning(AXONN_TUNE_GEMM_COPY_MASK, m) fixes the choice per class instead (bit 0 (kc,kc), bit 1 (kc,ks),
+  // bit 2 (ks,ks) with a 16-bit result, bit 3 (ks,ks) with an fp32 result): the tests run every case through
+  // both kernels with it.
+  const int64_t mask_set = g_tune_copy_mask.load();
+  const int64_t dma_mask = mask_set >= 0 ? mask_set : 7;
   const int dma_bit = A_KC ? (B_KC ? 0 : 1) : (epi == EPI_ACC_F32 ? 3 : 2);
   const bool use_dma = ((dma_mask >> dma_bit) & 1) && g.K % 64 == 0;
 #define AXONN_GEMM_CASE(E)                                                                      \
@@ -1073,25 +1080,27 @@ static bool fits_32bit_offsets(int64_t rows, int64_t ld) {
   return ld > 0 && (rows + 1024) * ld * 2 < (int64_t(1) << 31);
 }
 
-// Number of 256 x 256 tiles from which the large-problem kernel is used (half the CUs by default);
-// AXONN_GEMM_BIG_MIN_TILES overrides it, AXONN_GEMM_TILE_N (160, 192 or 256) fixes the block width: both
-// for tuning.
+// Number of 256 x 256 tiles from which the large-problem kernel is used: half the CUs, unless
+// axonn_tuning(AXONN_TUNE_GEMM_BIG_MIN_TILES, n) says otherwise (the tests send small ragged problems through
+// the large-problem kernels with it).
 static int64_t big_tile_threshold() {
-  static const int64_t v = env_int("AXONN_GEMM_BIG_MIN_TILES", 128);
-  return v;
+  const int64_t v = g_tune_big_min_tiles.load();
+  return v >= 0 ? v : 128;
 }
 
-// Block width of the large-problem kernel for an M x N x (nk k-steps) problem: the one with the lowest
-// modelled time (when the launch has the chip to itself; otherwise the widest).  A round (up to 256 tiles, one per CU) costs a fixed part (fill, epilogue) plus nk
-// k-steps whose duration grows with the number of MFMAs (8 * TN per phase) on top of a part that does
-// not (the A tile is fetched whatever the width).  Constants in microseconds, fitted to measurements
-// on full rounds of the 12B-class shapes.
+// Block width of the large-problem kernel for an M x N x (nk k-steps) problem: when other kernels share the chip
+// (they fill the CUs a partly filled round leaves idle), the widest and most efficient one; when the launch has
+// the chip to itself, the one with the lowest modelled time: a round (up to 256 tiles, one per CU) costs a fixed
+// part (fill, epilogue) plus nk k-steps whose duration grows with the number of MFMAs (8 * TN per phase) on top of
+// a part that does not (the A tile is fetched whatever the width).  Constants in microseconds, fitted to full
+// rounds of the 12B-class shapes; on the forward and input-gradient shapes of the 24B and 100B stages the choice
+// is the fastest of the three widths, or within 3 % of it, in all 16 cases (single launches, each width forced in
+// turn with AXONN_TUNE_GEMM_TILE_N).
 static int choose_tn(int64_t M, int64_t N, int64_t nk, bool concurrent) {
-  static const int64_t forced = env_int("AXONN_GEMM_TILE_N", 0);
+  const int64_t forced = g_tune_tile_n.load();
   if (forced == 160) return 5;
   if (forced == 192) return 6;
-  static const int64_t ignore_conc = env_int("AXONN_GEMM_IGNORE_CONCURRENT", 0);
-  if (forced == 256 || (concurrent && !ignore_conc)) return 8;
+  if (forced == 256 || concurrent) return 8;
   const int cand[3] = {8, 6, 5};
   int best = 8;
   double best_cost = 0;

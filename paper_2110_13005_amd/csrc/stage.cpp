@@ -4,7 +4,9 @@
 // pipeline of Sec. 5.2.  No kernels live here; see gemm.hip, attention.hip, elementwise.hip.
 #include "../../include/axonn_stage.h"
 #include "common.h"
+#include "host_logic.h"
 
+#include <algorithm>
 #include <chrono>
 #include <cmath>
 #include <cstdarg>
@@ -104,7 +106,9 @@ struct LayerStash {
   elem_t *dz, *dpre, *dy_mid, *dqkv;
 };
 
-enum SlotState { SLOT_FREE, SLOT_LIVE, SLOT_AWAIT_WGRAD };
+using host::SLOT_AWAIT_WGRAD;
+using host::SLOT_FREE;
+using host::SLOT_LIVE;
 
 struct Slot {
   int state = SLOT_FREE;
@@ -215,6 +219,7 @@ struct axonn_stage {
   std::vector<hipEvent_t> stream_tail;
   int fwd_rr = 0;
   int fwd_issued = 0, bwd_issued = 0;  // within the current batch (run mode)
+  double message_wait_s = 120.0;       // limit of each wait of the blocking receive loop
   std::vector<int32_t> dispatch_log;
   axonn_offload_adam* opt = nullptr;
   // the two ends of the pipeline, when this stage is the first and / or the last one (borrowed handles)
@@ -300,17 +305,24 @@ int forward_layer(axonn_stage* st, int l, const LayerStash& a, elem_t* z, hipStr
   AX_TRY(ln_fwd(T, h, a.x, param_ptr(st, l, P_LN1G), param_ptr(st, l, P_LN1B), st->cfg.ln_eps, a.u, a.u_lo,
                 a.stats1, s));
   if (a.u_lo) {
-    // qkv = (u_hi + u_lo) W + b as one contraction of length 2h: segment 0 pairs u_hi with W,
-    // segment 1 pairs u_lo with the same W
+    // [q|k|v] = (u_hi + u_lo) W + b as one contraction of length 2h: segment 0 pairs u_hi with W, segment 1 pairs
+    // u_lo with the same W.  qkv_input_split == 2: for the q and k thirds only (the logits are what amplifies the
+    // rounding of u); v = u_hi W_v + b_v as usual.
+    const int n_split = st->cfg.qkv_input_split == 2 ? 2 * h : 3 * h;
     GemmArgs g;
     memset(&g, 0, sizeof g);
     g.A_seg[0] = a.u; g.A_seg[1] = a.u_lo;
     g.B_seg[0] = g.B_seg[1] = param_ptr(st, l, P_WQKV);
     g.n_seg = 2; g.C = a.qkv; g.bias = param_ptr(st, l, P_BQKV);
-    g.lda = h; g.ldb = 3 * h; g.ldc = 3 * h; g.M = T; g.N = 3 * h; g.K = h;
+    g.lda = h; g.ldb = 3 * h; g.ldc = 3 * h; g.M = T; g.N = n_split; g.K = h;
     g.concurrent = t_concurrent;
-    ProfScope ps(PC_GEMM_FWD, s);
-    AX_TRY(check_launch(launch_gemm(true, false, EPI_BIAS, g, s), "gemm (split input)"));
+    {
+      ProfScope ps(PC_GEMM_FWD, s);
+      AX_TRY(check_launch(launch_gemm(true, false, EPI_BIAS, g, s), "gemm (split input)"));
+    }
+    if (n_split < 3 * h)
+      AX_TRY(gemm(true, false, EPI_BIAS, T, h, h, a.u, h, param_ptr(st, l, P_WQKV) + 2 * h, 3 * h, a.qkv + 2 * h, 3 * h,
+                  param_ptr(st, l, P_BQKV) + 2 * h, nullptr, 0, nullptr, 0, 0, s));
   } else {
     AX_TRY(gemm(true, false, EPI_BIAS, T, 3 * h, h, a.u, h, param_ptr(st, l, P_WQKV), 3 * h, a.qkv, 3 * h,
                 param_ptr(st, l, P_BQKV), nullptr, 0, nullptr, 0, 0, s));
@@ -480,8 +492,8 @@ int flush_wgrad(axonn_stage* st, hipStream_t s, Slot* last_slot = nullptr) {
   for (Slot* sl : ready) {
     HIP_TRY(hipEventRecord(sl->released, s));
     sl->released_recorded = true;
-    sl->state = SLOT_FREE;
   }
+  host::release_awaiting(st->slots);
   return AXONN_OK;
 }
 
@@ -532,21 +544,11 @@ int backward_layers_ckpt(axonn_stage* st, Slot& slot, const void* dy_in, void* d
   return AXONN_OK;
 }
 
-int count_state(const axonn_stage* st, int state) {
-  int n = 0;
-  for (const Slot& s : st->slots) n += (s.state == state);
-  return n;
-}
+int slots_in_state(const axonn_stage* st, int state) { return host::count_state(st->slots, state); }
 
 Slot* find_live(axonn_stage* st, int mb_id) {
-  for (Slot& s : st->slots)
-    if (s.state == SLOT_LIVE && s.mb_id == mb_id) return &s;
-  return nullptr;
-}
-Slot* find_free(axonn_stage* st) {
-  for (Slot& s : st->slots)
-    if (s.state == SLOT_FREE) return &s;
-  return nullptr;
+  const int i = host::find_live(st->slots, mb_id);
+  return i >= 0 ? &st->slots[i] : nullptr;
 }
 
 // `ws` is the stream weight-gradient passes go to (the caller's stream in direct mode).
@@ -554,18 +556,22 @@ int embed_forward(axonn_embed* e, const int32_t* tokens, void* x, hipStream_t s)
 
 // `x` holds [b,s,h] bf16 activations, or, on a stage with an embedding attached, [b,s] int32 token ids.
 int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s, hipStream_t ws) {
-  if (mb_id < 0) return fail(AXONN_EINVAL, "forward: negative microbatch id %d", mb_id);
-  if (find_live(st, mb_id)) return fail(AXONN_ESTATE, "forward: microbatch %d is already in flight", mb_id);
-  if (st->in_flight >= st->cfg.pipeline_limit)
-    return fail(AXONN_ESTATE, "forward: pipeline_limit (%d) microbatches already in flight",
-                st->cfg.pipeline_limit);
-  Slot* slot = find_free(st);
-  if (!slot) {
+  int si = -1;
+  int adm = host::admit_forward(st->slots, mb_id, st->in_flight, st->cfg.pipeline_limit, &si);
+  if (adm == host::FWD_NEEDS_FLUSH) {
     // every slot not in flight is waiting for its weight gradients: form them now
     AX_TRY(flush_wgrad(st, ws));
-    slot = find_free(st);
+    adm = host::admit_forward(st->slots, mb_id, st->in_flight, st->cfg.pipeline_limit, &si);
   }
-  if (!slot) return fail(AXONN_ESTATE, "forward: no free stash slot");
+  switch (adm) {
+    case host::FWD_OK: break;
+    case host::FWD_NEGATIVE_ID: return fail(AXONN_EINVAL, "forward: negative microbatch id %d", mb_id);
+    case host::FWD_ALREADY_LIVE: return fail(AXONN_ESTATE, "forward: microbatch %d is already in flight", mb_id);
+    case host::FWD_PIPELINE_FULL:
+      return fail(AXONN_ESTATE, "forward: pipeline_limit (%d) microbatches already in flight", st->cfg.pipeline_limit);
+    default: return fail(AXONN_ESTATE, "forward: no free stash slot");
+  }
+  Slot* slot = &st->slots[si];
   // the weight-gradient pass that read the slot's previous contents must have finished
   if (slot->released_recorded) HIP_TRY(hipStreamWaitEvent(s, slot->released, 0));
   const uint64_t bytes = (uint64_t)st->T * st->h * sizeof(elem_t);
@@ -580,15 +586,14 @@ int do_forward(axonn_stage* st, int mb_id, const void* x, void* y, hipStream_t s
   if (st->cfg.ckpt_stride > 0) AX_TRY(forward_layers_ckpt(st, *slot, y, s));
   else AX_TRY(forward_layers(st, *slot, y, s));
   HIP_TRY(hipEventRecord(slot->fwd_done, s));
-  slot->state = SLOT_LIVE;
-  slot->mb_id = mb_id;
-  st->in_flight++;
+  host::commit_forward(st->slots, si, mb_id, &st->in_flight);
   return AXONN_OK;
 }
 
 int do_backward(axonn_stage* st, int mb_id, const void* dy, void* dx, hipStream_t s, hipStream_t ws) {
-  Slot* slot = (mb_id >= 0) ? find_live(st, mb_id) : nullptr;
-  if (!slot) return fail(AXONN_ESTATE, "backward: microbatch %d has no forward in flight", mb_id);
+  const int si = host::admit_backward(st->slots, mb_id);
+  if (si < 0) return fail(AXONN_ESTATE, "backward: microbatch %d has no forward in flight", mb_id);
+  Slot* slot = &st->slots[si];
   HIP_TRY(hipStreamWaitEvent(s, slot->fwd_done, 0));
   // backward chains share the workspace and the bias / LayerNorm accumulators: keep them in order
   if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_bwd, 0));
@@ -601,20 +606,19 @@ int do_backward(axonn_stage* st, int mb_id, const void* dy, void* dx, hipStream_
   HIP_TRY(hipEventRecord(slot->dgrad_done, s));
   HIP_TRY(hipEventRecord(st->last_bwd, s));
   st->last_bwd_recorded = true;
-  slot->mb_id = -1;
-  st->in_flight--;
+  host::commit_backward(st->slots, si, ckpt, &st->in_flight);
   if (ckpt) {
     // the weight gradients are already queued and read the shared sets: the slot (kept inputs only) is
     // free as soon as the chain on `s` is through
     HIP_TRY(hipEventRecord(slot->released, s));
     slot->released_recorded = true;
-    slot->state = SLOT_FREE;
     if (last) st->grads_final_recorded = true;
   } else {
-    slot->state = SLOT_AWAIT_WGRAD;
-    const int group = st->cfg.wgrad_group;
-    if (last) AX_TRY(flush_wgrad(st, ws, slot));
-    else if (group > 0 && count_state(st, SLOT_AWAIT_WGRAD) >= group) AX_TRY(flush_wgrad(st, ws));
+    switch (host::wgrad_action(last, st->cfg.wgrad_group, slots_in_state(st, SLOT_AWAIT_WGRAD))) {
+      case host::WGRAD_FLUSH_FINAL: AX_TRY(flush_wgrad(st, ws, slot)); break;
+      case host::WGRAD_FLUSH: AX_TRY(flush_wgrad(st, ws)); break;
+      default: break;
+    }
   }
   return AXONN_OK;
 }
@@ -715,6 +719,8 @@ int validate_config(const axonn_stage_config* c) {
   if (!(c->ln_eps > 0.f)) return fail(AXONN_EINVAL, "stage config: ln_eps must be positive");
   if (c->device < 0) return fail(AXONN_EINVAL, "stage config: negative device ordinal");
   if (c->wgrad_group < 0) return fail(AXONN_EINVAL, "stage config: negative wgrad_group");
+  if (c->qkv_input_split < 0 || c->qkv_input_split > 2)
+    return fail(AXONN_EINVAL, "config: qkv_input_split must be 0, 1 or 2 (got %d)", c->qkv_input_split);
   if (c->ckpt_stride < 0 || (c->ckpt_stride > 0 && c->n_layers % c->ckpt_stride != 0))
     return fail(AXONN_EINVAL, "stage config: ckpt_stride (%d) must be 0 or a factor of n_layers (%d)",
                 c->ckpt_stride, c->n_layers);
@@ -984,8 +990,7 @@ int axonn_stage_zero_grad(axonn_stage_t* st, void* hip_stream) {
   if (st->last_wgrad_recorded) HIP_TRY(hipStreamWaitEvent(s, st->last_wgrad, 0));
   // no memory is touched: the first backward / weight-gradient pass of a batch overwrites the
   // accumulators.  Microbatches whose weight gradients were still pending are dropped.
-  for (Slot& sl : st->slots)
-    if (sl.state == SLOT_AWAIT_WGRAD) sl.state = SLOT_FREE;
+  host::release_awaiting(st->slots);
   st->bwd_count = 0;
   st->wgrad_flushes = 0;
   st->grads_final_recorded = false;
@@ -1034,16 +1039,15 @@ int axonn_stage_post(axonn_stage_t* st, const axonn_msg* msg) {
   if (st->head && msg->kind == 0 && (!msg->targets_dev || !msg->loss_dev))
     return fail(AXONN_EINVAL, "post: a forward message to the last stage needs targets_dev and loss_dev");
   if (msg->mb_id < 0) return fail(AXONN_EINVAL, "post: negative microbatch id");
-  int same = 0;
-  for (const PendingMsg& p : st->inbox)
-    if (p.m.kind == msg->kind) {
-      ++same;
-      if (p.m.mb_id == msg->mb_id) return fail(AXONN_ESTATE, "post: duplicate message for microbatch %d", msg->mb_id);
-    }
-  const int issued = msg->kind == 0 ? st->fwd_issued : st->bwd_issued;
-  if (issued + same >= st->cfg.n_microbatches)
-    return fail(AXONN_ESTATE, "post: more than n_microbatches (%d) messages of kind %d in this batch",
-                st->cfg.n_microbatches, msg->kind);
+  const auto posted = [st](size_t i) { return std::make_pair((int)st->inbox[i].m.kind, (int)st->inbox[i].m.mb_id); };
+  switch (host::check_post(msg->kind, msg->mb_id, st->inbox.size(), posted,
+                           msg->kind == 0 ? st->fwd_issued : st->bwd_issued, st->cfg.n_microbatches)) {
+    case host::POST_DUPLICATE: return fail(AXONN_ESTATE, "post: duplicate message for microbatch %d", msg->mb_id);
+    case host::POST_SURPLUS:
+      return fail(AXONN_ESTATE, "post: more than n_microbatches (%d) messages of kind %d in this batch",
+                  st->cfg.n_microbatches, msg->kind);
+    default: break;
+  }
   st->inbox.push_back(PendingMsg{*msg});
   return AXONN_OK;
 }
@@ -1074,45 +1078,46 @@ int run_loop(axonn_stage* st, int n_streams, void* hip_stream, bool blocking, in
     HIP_TRY(hipStreamWaitEvent(ws, st->fork_ev, 0));
   }
   const int M = st->cfg.n_microbatches;
-  const auto t_start = std::chrono::steady_clock::now();
+  const auto t0 = std::chrono::steady_clock::now();
+  const auto now_s = [t0] { return std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count(); };
+  host::WaitClock wait(st->message_wait_s);
+  hipError_t query_error = hipSuccess;
+  const auto posted = [st](size_t i) { return std::make_pair((int)st->inbox[i].m.kind, (int)st->inbox[i].m.mb_id); };
+  const auto arrived = [st, &query_error](size_t i) {
+    void* ev = st->inbox[i].m.ready_event;
+    if (!ev) return 1;
+    const hipError_t q = hipEventQuery((hipEvent_t)ev);
+    if (q == hipSuccess) return 1;
+    if (q == hipErrorNotReady) return 0;
+    query_error = q;
+    return -1;
+  };
   while (st->fwd_issued < M || st->bwd_issued < M) {
     // first posted message that has arrived and is admissible
-    int chosen = -1;
     bool any_admissible = false;
-    for (size_t i = 0; i < st->inbox.size(); ++i) {
-      const axonn_msg& m = st->inbox[i].m;
-      const bool admissible = (m.kind == 0)
-                                  ? (st->in_flight < st->cfg.pipeline_limit && !find_live(st, m.mb_id))
-                                  : (find_live(st, m.mb_id) != nullptr);
-      if (!admissible) continue;
-      any_admissible = true;
-      if (m.ready_event) {
-        const hipError_t q = hipEventQuery((hipEvent_t)m.ready_event);
-        if (q == hipErrorNotReady) continue;
-        if (q != hipSuccess) return fail(AXONN_EHIP, "run: hipEventQuery failed: %s", hipGetErrorString(q));
-      }
-      chosen = (int)i;
-      break;
-    }
+    int err = 0;
+    const int chosen = host::choose_message(st->inbox.size(), posted, arrived, st->slots, st->in_flight,
+                                            st->cfg.pipeline_limit, &any_admissible, &err);
+    if (err) return fail(AXONN_EHIP, "run: hipEventQuery failed: %s", hipGetErrorString(query_error));
     if (chosen < 0) {
       if (!blocking) break;
       if (!any_admissible)
         return fail(AXONN_ESTATE,
                     "run: %d forward and %d backward messages still expected but none of the %zu posted "
                     "messages can be scheduled", M - st->fwd_issued, M - st->bwd_issued, st->inbox.size());
-      if (std::chrono::steady_clock::now() - t_start > std::chrono::seconds(120))
-        return fail(AXONN_ESTATE, "run: waited 120 s for a posted message to arrive");
+      // Every wait has its own limit (a long batch with a slow but live producer is no error).  On expiry nothing
+      // is lost: the posted messages stay posted, what was dispatched stays enqueued, and the caller may call run
+      // again, or synchronize and start over with zero_grad.
+      if (wait.expired(now_s()))
+        return fail(AXONN_ESTATE, "run: waited %.0f s for a posted message to arrive (axonn_stage_set_message_wait "
+                    "changes the limit); the batch can be resumed with another run", st->message_wait_s);
       std::this_thread::yield();
       continue;
     }
+    wait.dispatched();
     const axonn_msg m = st->inbox[chosen].m;
     st->inbox.erase(st->inbox.begin() + chosen);
-    int si;
-    if (m.kind == 1 || n_streams == 1) {
-      si = 0;  // backwards keep to one stream: they share accumulators and workspace
-    } else {
-      si = 1 + (st->fwd_rr++ % (n_streams - 1));
-    }
+    const int si = host::stream_index(m.kind, n_streams, &st->fwd_rr);
     hipStream_t s = st->streams[si];
     if (m.ready_event) HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)m.ready_event, 0));
     if (m.kind == 0) {
@@ -1160,6 +1165,13 @@ int axonn_stage_poll(axonn_stage_t* st, int32_t n_streams, void* hip_stream, int
   const int rc = run_loop(st, n_streams, hip_stream, false, n_dispatched);
   if (n_remaining) *n_remaining = 2 * st->cfg.n_microbatches - st->fwd_issued - st->bwd_issued;
   return rc;
+}
+
+int axonn_stage_set_message_wait(axonn_stage_t* st, double seconds) {
+  if (!st) return fail(AXONN_EINVAL, "set_message_wait: null handle");
+  if (!(seconds > 0.0)) return fail(AXONN_EINVAL, "set_message_wait: the limit must be positive");
+  st->message_wait_s = seconds;
+  return AXONN_OK;
 }
 
 int axonn_stage_join(axonn_stage_t* st, void* user_stream) {
@@ -1266,13 +1278,10 @@ int fetch_bucket(axonn_offload_adam* o, int set, uint64_t off, size_t bytes, hip
 // do not wait for gradients at all.  `early` (or null): a stream that has nothing left to do but the work
 // already queued on it; the first fetches (one per buffer set) go there instead of the fetch stream, whose
 // commands may share a hardware queue with busy streams and would then start behind all their queued work.
-int adam_pass(axonn_offload_adam* o, double lr, double beta1, double beta2, double eps, double weight_decay,
-              int64_t step, double grad_scale, hipStream_t user, int chunk_buckets,
-              const std::function<hipEvent_t(uint64_t, uint64_t)>* gate, hipStream_t early) {
-  if (step < 1) return fail(AXONN_EINVAL, "adam_step: step must be >= 1 (got %lld)", (long long)step);
-  if (!(beta1 >= 0. && beta1 < 1.) || !(beta2 >= 0. && beta2 < 1.))
-    return fail(AXONN_EINVAL, "adam_step: betas must be in [0,1)");
-  HIP_TRY(hipSetDevice(o->device));
+int adam_pass_body(axonn_offload_adam* o, double lr, double beta1, double beta2, double eps, double weight_decay,
+                   int64_t step, double grad_scale, hipStream_t user, int chunk_buckets,
+                   const std::function<hipEvent_t(uint64_t, uint64_t)>* gate, hipStream_t early,
+                   uint64_t* buckets_queued) {
   constexpr int S = axonn_offload_adam::kSets;
   // everything already queued on the caller's stream comes first
   HIP_TRY(hipEventRecord(o->ev_start, user));
@@ -1281,20 +1290,19 @@ int adam_pass(axonn_offload_adam* o, double lr, double beta1, double beta2, doub
   HIP_TRY(hipStreamWaitEvent(o->s_d2h, o->ev_start, 0));
   // the early fetches deliberately do not wait for the caller's stream: an event recorded there can sit in a
   // hardware queue behind the whole batch; they are ordered after the previous pass by the sets' drain events
-  const uint64_t nb = (o->n + o->bucket - 1) / o->bucket;
+  const uint64_t nb = host::bucket_count(o->n, o->bucket);
   for (uint64_t i = 0; i < nb; ++i) {
-    const uint64_t b = gate ? nb - 1 - i : i;
-    const int set = (int)(i % S);
-    const uint64_t off = b * o->bucket;
-    const uint64_t cnt = std::min<uint64_t>(o->bucket, o->n - off);
+    const host::BucketPlan bp = host::bucket_plan(o->n, o->bucket, S, i, gate != nullptr);
+    const int set = bp.set;
+    const uint64_t off = bp.offset, cnt = bp.count;
     const size_t bytes = cnt * sizeof(float);
     AX_TRY(fetch_bucket(o, set, off, bytes, (early && i < (uint64_t)S) ? early : o->s_h2d));
     // update
     if (gate && i % (uint64_t)chunk_buckets == 0) {
       // the chunk: the next chunk_buckets buckets in processing order, i.e. downwards from this one
-      const uint64_t n_in_chunk = std::min<uint64_t>((uint64_t)chunk_buckets, nb - i);
-      const uint64_t lo = (b + 1 - n_in_chunk) * o->bucket;
-      HIP_TRY(hipStreamWaitEvent(o->s_k, (*gate)(lo, off + cnt), 0));
+      uint64_t lo = 0, hi = 0;
+      host::chunk_span(o->n, o->bucket, (uint64_t)chunk_buckets, i, &lo, &hi);
+      HIP_TRY(hipStreamWaitEvent(o->s_k, (*gate)(lo, hi), 0));
     }
     HIP_TRY(hipStreamWaitEvent(o->s_k, o->ev_h2d[set], 0));
     AX_TRY(adam(cnt, o->d_buf[set][0], o->d_buf[set][1], o->d_buf[set][2], o->g16 + off, o->p16 + off, lr, beta1,
@@ -1307,6 +1315,7 @@ int adam_pass(axonn_offload_adam* o, double lr, double beta1, double beta2, doub
     HIP_TRY(hipMemcpyAsync(o->h_v + off, o->d_buf[set][2], bytes, hipMemcpyDeviceToHost, o->s_d2h));
     HIP_TRY(hipEventRecord(o->ev_d2h[set], o->s_d2h));
     o->d2h_recorded[set] = true;
+    ++*buckets_queued;
   }
   // the caller's stream continues after the last bucket is back in host memory
   const int last = (int)((nb - 1) % S);
@@ -1316,6 +1325,34 @@ int adam_pass(axonn_offload_adam* o, double lr, double beta1, double beta2, doub
   // next batch behind the pending pass fills the hardware queues that the pass's copies share: measured on the 12B
   // stage, the pass then takes 500 ms instead of 323, and single batches behind it run 10 % slower.
   HIP_TRY(hipStreamSynchronize(user));
+  return AXONN_OK;
+}
+
+int adam_pass(axonn_offload_adam* o, double lr, double beta1, double beta2, double eps, double weight_decay,
+              int64_t step, double grad_scale, hipStream_t user, int chunk_buckets,
+              const std::function<hipEvent_t(uint64_t, uint64_t)>* gate, hipStream_t early) {
+  if (step < 1) return fail(AXONN_EINVAL, "adam_step: step must be >= 1 (got %lld)", (long long)step);
+  if (!(beta1 >= 0. && beta1 < 1.) || !(beta2 >= 0. && beta2 < 1.))
+    return fail(AXONN_EINVAL, "adam_step: betas must be in [0,1)");
+  HIP_TRY(hipSetDevice(o->device));
+  uint64_t queued = 0;
+  const int rc = adam_pass_body(o, lr, beta1, beta2, eps, weight_decay, step, grad_scale, user, chunk_buckets, gate,
+                                early, &queued);
+  if (rc != AXONN_OK) {
+    // An error in the middle of the pass: whatever was queued may still be copying into the caller's host arrays
+    // or writing parameters.  Wait for it, so that nothing is in flight when the error reaches the caller; the
+    // buffer sets are then all drained.  The buckets queued before the error have been updated, the rest not.
+    const std::string first = g_last_error;
+    (void)hipStreamSynchronize(o->s_h2d);
+    (void)hipStreamSynchronize(o->s_k);
+    (void)hipStreamSynchronize(o->s_d2h);
+    if (early) (void)hipStreamSynchronize(early);
+    for (bool& r : o->d2h_recorded) r = false;
+    return fail(rc, "%s (optimizer pass stopped after %llu of %llu buckets in %s order; those are updated in host "
+                "memory and in the 16-bit parameters, the others are untouched)", first.c_str(),
+                (unsigned long long)queued, (unsigned long long)host::bucket_count(o->n, o->bucket),
+                gate ? "descending" : "ascending");
+  }
   return AXONN_OK;
 }
 }  // namespace
@@ -1346,9 +1383,9 @@ int axonn_stage_optimizer_step(axonn_stage_t* st, double lr, double beta1, doubl
   hipStream_t user = (hipStream_t)hip_stream;
   if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(user, st->last_bwd, 0));
   if (st->last_wgrad_recorded) HIP_TRY(hipStreamWaitEvent(user, st->last_wgrad, 0));
-  if (count_state(st, SLOT_AWAIT_WGRAD))
+  if (slots_in_state(st, SLOT_AWAIT_WGRAD))
     return fail(AXONN_ESTATE, "optimizer_step: %d microbatches still await their weight gradients (fewer than "
-                "n_microbatches backwards since zero_grad)", count_state(st, SLOT_AWAIT_WGRAD));
+                "n_microbatches backwards since zero_grad)", slots_in_state(st, SLOT_AWAIT_WGRAD));
   return axonn_offload_adam_step(st->opt, lr, beta1, beta2, eps, weight_decay, step, grad_scale, hip_stream);
 }
 
@@ -1366,10 +1403,10 @@ int axonn_stage_optimizer_step_overlapped(axonn_stage_t* st, double lr, double b
   HIP_TRY(hipSetDevice(st->cfg.device));
   const int L = st->cfg.n_layers;
   // gradients become final from the last layer down: a chunk may start once the lowest layer it touches is
-  const std::function<hipEvent_t(uint64_t, uint64_t)> gate = [st, L](uint64_t lo, uint64_t) {
-    int l = 0;
-    while (l + 1 < L && st->tensors[(l + 1) * kTensorsPerLayer].offset <= lo) ++l;
-    return st->grads_final[l];
+  std::vector<uint64_t> layer_begin(L);
+  for (int l = 0; l < L; ++l) layer_begin[l] = st->tensors[l * kTensorsPerLayer].offset;
+  const std::function<hipEvent_t(uint64_t, uint64_t)> gate = [st, &layer_begin, L](uint64_t lo, uint64_t) {
+    return st->grads_final[host::lowest_layer(layer_begin.data(), L, lo)];
   };
   // message-driven mode with forward streams: the first of them has no more work in this batch
   hipStream_t early = st->streams.size() > 1 ? st->streams[1] : nullptr;
@@ -1390,9 +1427,9 @@ static int wait_for_gradients(axonn_stage_t* st, hipStream_t user, const char* w
   if (st->in_flight) return fail(AXONN_ESTATE, "%s: %d microbatches in flight", who, st->in_flight);
   if (st->last_bwd_recorded) HIP_TRY(hipStreamWaitEvent(user, st->last_bwd, 0));
   if (st->last_wgrad_recorded) HIP_TRY(hipStreamWaitEvent(user, st->last_wgrad, 0));
-  if (count_state(st, SLOT_AWAIT_WGRAD))
+  if (slots_in_state(st, SLOT_AWAIT_WGRAD))
     return fail(AXONN_ESTATE, "%s: %d microbatches still await their weight gradients (fewer than "
-                "n_microbatches backwards since zero_grad)", who, count_state(st, SLOT_AWAIT_WGRAD));
+                "n_microbatches backwards since zero_grad)", who, slots_in_state(st, SLOT_AWAIT_WGRAD));
   return AXONN_OK;
 }
 
@@ -1597,6 +1634,13 @@ int axonn_stage_attach_ends(axonn_stage_t* st, axonn_embed_t* embed, axonn_head_
   return AXONN_OK;
 }
 
+// ----------------------------------------------------------------- tuning and test hooks
+int axonn_tuning(int32_t knob, int64_t value) {
+  if (!set_gemm_tuning(knob, value))
+    return fail(AXONN_EINVAL, "tuning: unknown knob %d or value %lld out of range", (int)knob, (long long)value);
+  return AXONN_OK;
+}
+
 // ----------------------------------------------------------------- launch timing
 int axonn_profile_enable(int32_t on) {
   g_prof_on = on != 0;
@@ -1628,6 +1672,59 @@ int axonn_profile_collect(double* total_ms, int64_t* launches, int32_t n_categor
     g_prof_pool.push_back(r.b);
   }
   g_prof_recs.clear();
+  return rc;
+}
+
+// Bare copy rates of the host link with the calls the optimizer pipeline makes (hipMemcpyAsync between pinned host
+// memory and device memory, one stream per direction): the denominator of the optimizer step's link fraction.
+int axonn_host_link_probe(int32_t device, uint64_t bytes, int32_t reps, double gbps_out[3]) {
+  if (!gbps_out || bytes == 0 || reps < 1) return fail(AXONN_EINVAL, "host_link_probe: bad argument");
+  HIP_TRY(hipSetDevice(device));
+  void *h_in = nullptr, *h_out = nullptr, *d_in = nullptr, *d_out = nullptr;
+  hipStream_t s_in = nullptr, s_out = nullptr;
+  hipEvent_t e[4] = {};
+  int rc = AXONN_OK;
+  auto run = [&]() -> int {
+    HIP_TRY(hipHostMalloc(&h_in, bytes, hipHostMallocDefault));
+    HIP_TRY(hipHostMalloc(&h_out, bytes, hipHostMallocDefault));
+    HIP_TRY(hipMalloc(&d_in, bytes));
+    HIP_TRY(hipMalloc(&d_out, bytes));
+    memset(h_in, 1, bytes);
+    memset(h_out, 2, bytes);
+    HIP_TRY(hipMemset(d_out, 3, bytes));
+    HIP_TRY(hipStreamCreateWithFlags(&s_in, hipStreamNonBlocking));
+    HIP_TRY(hipStreamCreateWithFlags(&s_out, hipStreamNonBlocking));
+    for (auto& ev : e) HIP_TRY(hipEventCreate(&ev));
+    for (int mode = -1; mode < 3; ++mode) {          // -1: warm-up of both directions; 0: in; 1: out; 2: both
+      const bool in = mode != 1, out = mode != 0;
+      HIP_TRY(hipDeviceSynchronize());
+      if (in) HIP_TRY(hipEventRecord(e[0], s_in));
+      if (out) HIP_TRY(hipEventRecord(e[2], s_out));
+      for (int r = 0; r < reps; ++r) {
+        if (in) HIP_TRY(hipMemcpyAsync(d_in, h_in, bytes, hipMemcpyHostToDevice, s_in));
+        if (out) HIP_TRY(hipMemcpyAsync(h_out, d_out, bytes, hipMemcpyDeviceToHost, s_out));
+      }
+      if (in) HIP_TRY(hipEventRecord(e[1], s_in));
+      if (out) HIP_TRY(hipEventRecord(e[3], s_out));
+      HIP_TRY(hipDeviceSynchronize());
+      float ms_in = 0.f, ms_out = 0.f;
+      if (in) HIP_TRY(hipEventElapsedTime(&ms_in, e[0], e[1]));
+      if (out) HIP_TRY(hipEventElapsedTime(&ms_out, e[2], e[3]));
+      const double total = (double)bytes * reps / 1e9;
+      if (mode == 0) gbps_out[0] = total / (ms_in * 1e-3);
+      if (mode == 1) gbps_out[1] = total / (ms_out * 1e-3);
+      if (mode == 2) gbps_out[2] = total / (std::max(ms_in, ms_out) * 1e-3);     // per direction, both running
+    }
+    return AXONN_OK;
+  };
+  rc = run();
+  for (auto& ev : e) if (ev) (void)hipEventDestroy(ev);
+  if (s_in) (void)hipStreamDestroy(s_in);
+  if (s_out) (void)hipStreamDestroy(s_out);
+  if (d_in) (void)hipFree(d_in);
+  if (d_out) (void)hipFree(d_out);
+  if (h_in) (void)hipHostFree(h_in);
+  if (h_out) (void)hipHostFree(h_out);
   return rc;
 }
 

@@ -26,3 +26,20 @@ def pytest_collection_modifyitems(config, items):
     for it in items:
         if "gpu" in it.keywords:
             it.add_marker(skip)
+
+
+def pytest_sessionfinish(session, exitstatus):
+    """AXONN_TEST_REPORT=1: the element-wise error factors the GPU parity checks measured, next to their bounds."""
+    if os.environ.get("AXONN_TEST_REPORT") != "1":
+        return
+    try:
+        import helpers
+    except Exception:
+        return
+    worst = {}
+    for label, f, c, e in helpers._elem_report:
+        w = worst.setdefault(label, [0.0, c, 0.0, 0])
+        w[0] = max(w[0], f); w[2] = max(w[2], e); w[3] += 1
+    print("\nelement-wise factors (worst per label: factor / bound, rel_fro, checks)")
+    for label, (f, c, e, n) in sorted(worst.items()):
+        print("  %-40s %8.3f / %-8g  %.2e  %d" % (label, f, c, e, n))

@@ -13,10 +13,19 @@ import oracle
 from oracle import transformer as OT
 from paper_2110_13005_amd import binding as B
 from paper_2110_13005_amd.inputs import snap_elem
-from helpers import rel_fro, dev_bf16, dev_f32, host
+from helpers import rel_fro, parity, dev_bf16, dev_f32, host
 
 pytestmark = pytest.mark.gpu
 TOL = 5e-3
+# Element-wise bounds, in roundings of the 16-bit format (helpers.elem_factor: 2^-8 of the element's own magnitude
+# plus that of a typical element of its row).
+# C_ONE: an fp32-accumulated value rounded once (GEMM with any epilogue, LayerNorm): 1/2 by the arithmetic
+#   (2^-9 relative), plus the fp32 summation error and, for GeLU, the 3e-7 of the erf form; 1 with margin.
+# C_ATTN: the attention output sums probabilities that were rounded to 16 bits (2^-9 each, independent signs: the
+#   sum over a row's keys grows like its root mean square) and is rounded once itself.
+# C_ATTN_BWD: dq, dk, dv sum products of two rounded tiles (P and dS) and go through one more rounding; delta comes
+#   from the rounded o.  Measured worst over the shapes below: 0.86 (one rounding), 2.2 (attention), 7.9 (its backward).
+C_ONE, C_ATTN, C_ATTN_BWD = 1.0, 4.0, 16.0
 
 
 def _rng_bf16(rng, shape, std=1.0):
@@ -56,16 +65,16 @@ def test_gemm_forward_layout_bias_res_gelu(M, N, K):
     dx, dw, db, dr = dev_bf16(x), dev_bf16(w), dev_bf16(bias), dev_bf16(res)
     out = torch.empty(M, N, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, dx, K, dw, N, out, N, bias=db)
-    assert rel_fro(host(out), ref) < TOL
+    parity(host(out), ref, TOL, C_ONE, label="gemm_forward_layout_bias_res_gelu")
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, dx, K, dw, N, out, N, bias=None)
-    assert rel_fro(host(out), ref - bias) < TOL
+    parity(host(out), ref - bias, TOL, C_ONE, label="gemm_forward_layout_bias_res_gelu")
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS_RES, M, N, K, dx, K, dw, N, out, N, bias=db, res=dr, ld_res=N)
-    assert rel_fro(host(out), ref + res) < TOL
+    parity(host(out), ref + res, TOL, C_ONE, label="gemm_forward_layout_bias_res_gelu")
     pre = torch.empty(M, N, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS_GELU, M, N, K, dx, K, dw, N, out, N, bias=db, aux=pre, ld_aux=N)
     torch.cuda.synchronize()
     assert rel_fro(host(pre), OT.gelu_grad(ref)) < TOL      # the epilogue stores GeLU'(z) in place of z
-    assert rel_fro(host(out), OT.gelu(ref)) < TOL
+    parity(host(out), OT.gelu(ref), TOL, C_ONE, label="gemm_forward_layout_bias_res_gelu")
 
 
 @pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
@@ -78,7 +87,7 @@ def test_gemm_dgrad_layout_plain_and_dgelu(M, N, K):
     a, b, p = dev_bf16(dy), dev_bf16(w), dev_bf16(pre)
     out = torch.empty(M, N, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_gemm_bf16(1, 1, B.EPI_BIAS, M, N, K, a, K, b, K, out, N)
-    assert rel_fro(host(out), ref) < TOL
+    parity(host(out), ref, TOL, C_ONE, label="gemm_dgrad_layout_plain_and_dgelu")
     B.axonn_gemm_bf16(1, 1, B.EPI_DGELU, M, N, K, a, K, b, K, out, N, aux=p, ld_aux=N)
     assert rel_fro(host(out), ref * pre.astype(np.float64)) < TOL       # aux holds the stored derivative
 
@@ -99,9 +108,9 @@ def test_gemm_wgrad_layout_accumulate(M, N, K):
     c16 = torch.full((M, N), 7.0, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_gemm_bf16(0, 0, B.EPI_ACC_BF16, M, N, K, a, M, b, N, c16, N, accumulate=0)
     first = host(c16)
-    assert rel_fro(first, ref) < TOL
+    parity(first, ref, TOL, C_ONE, label="gemm_wgrad_layout_accumulate")
     B.axonn_gemm_bf16(0, 0, B.EPI_ACC_BF16, M, N, K, a, M, b, N, c16, N, accumulate=1)
-    assert rel_fro(host(c16), first + ref) < TOL
+    parity(host(c16), first + ref, TOL, C_ONE, label="gemm_wgrad_layout_accumulate")
 
 
 def test_gemm_big_tile_strided_operands():
@@ -119,23 +128,38 @@ def test_gemm_big_tile_strided_operands():
         ref = (am if a_kc else am.T) @ (bm.T if b_kc else bm)
         out = torch.zeros(M, ldc, dtype=B.torch_elem_dtype(), device="cuda")
         B.axonn_gemm_bf16(a_kc, b_kc, epi, M, N, K, dev_bf16(abuf), lda, dev_bf16(bbuf), ldb, out, ldc)
-        assert rel_fro(host(out)[:, :N], ref) < TOL, (a_kc, b_kc)
+        parity(host(out)[:, :N], ref, TOL, C_ONE, label="gemm_big_tile_strided_operands")
         assert not host(out)[:, N:].any()
 
 
-def test_gemm_copy_kernel_all_layouts_and_results():
-    """The large-problem kernel whose tiles are copied by the memory pipeline is the default for one
-    (layout, result type) pair only; AXONN_GEMM_DMA=15 selects it wherever it applies.  The variable is read
-    once per process, so the GEMM cases of this file run again in a child process with it set."""
-    import os
-    import subprocess
-    import sys
-    env = dict(os.environ, AXONN_GEMM_DMA="15")
-    r = subprocess.run([sys.executable, "-m", "pytest", os.path.abspath(__file__), "-x", "-q", "-p", "no:cacheprovider",
-                        "-k", "gemm and not copy_kernel"], env=env, capture_output=True, text=True, timeout=600,
-                       cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
-    assert r.returncode == 0, r.stdout[-3000:] + r.stderr[-2000:]
-    assert " passed" in r.stdout and "failed" not in r.stdout
+@pytest.mark.parametrize("mask,min_tiles", [(15, 1), (0, 1), (15, -1)])
+def test_gemm_both_large_kernels_all_layouts_and_results(mask, min_tiles):
+    """The large-problem kernel whose tiles are copied by the memory pipeline serves three of the four (layout, result
+    type) classes by default and the register-staged one the fourth; axonn_tuning fixes the choice, so every GEMM
+    case of this file runs again through the copying kernel wherever it applies (K a multiple of 64: mask 15) and
+    through the register-staged kernel everywhere (mask 0), with the threshold lowered so that the small ragged
+    shapes reach the large-problem kernels too (all three block widths)."""
+    try:
+        B.axonn_tuning(B.TUNE_GEMM_COPY_MASK, mask)
+        B.axonn_tuning(B.TUNE_GEMM_BIG_MIN_TILES, min_tiles)
+        for width in ((-1,) if min_tiles < 0 else (-1, 160, 192)):
+            B.axonn_tuning(B.TUNE_GEMM_TILE_N, width)
+            for (M, N, K) in GEMM_SHAPES:
+                if width > 0 and M * N > 2048 * 4096:
+                    continue                          # the forced widths on the small and the ragged shapes only
+                test_gemm_forward_layout_bias_res_gelu(M, N, K)
+                test_gemm_dgrad_layout_plain_and_dgelu(M, N, K)
+                test_gemm_wgrad_layout_accumulate(M, N, K)
+        B.axonn_tuning(B.TUNE_GEMM_TILE_N, -1)
+        test_gemm_big_tile_strided_operands()
+        test_gemm_strided_operands_and_run_to_run_determinism()
+    finally:
+        for knob in (B.TUNE_GEMM_COPY_MASK, B.TUNE_GEMM_BIG_MIN_TILES, B.TUNE_GEMM_TILE_N):
+            B.axonn_tuning(knob, -1)
+    with pytest.raises(B.AxonnError):
+        B.axonn_tuning(B.TUNE_GEMM_TILE_N, 128)
+    with pytest.raises(B.AxonnError):
+        B.axonn_tuning(7, 0)
 
 
 def test_gemm_strided_operands_and_run_to_run_determinism():
@@ -149,7 +173,7 @@ def test_gemm_strided_operands_and_run_to_run_determinism():
     out = torch.zeros(M, ldc, dtype=B.torch_elem_dtype(), device="cuda")
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, a, lda, b, ldb, out, ldc)
     first = out.clone()
-    assert rel_fro(host(out)[:, :N], ref) < TOL
+    parity(host(out)[:, :N], ref, TOL, C_ONE, label="gemm_strided_operands_and_run_to_run_determinism")
     assert not host(out)[:, N:].any()                     # nothing written outside the tile
     B.axonn_gemm_bf16(1, 0, B.EPI_BIAS, M, N, K, a, lda, b, ldb, out, ldc)
     torch.cuda.synchronize()
@@ -173,7 +197,7 @@ def test_layernorm_fwd_bwd(T, h):
     out = torch.empty(T, h, dtype=B.torch_elem_dtype(), device="cuda")
     stats = torch.empty(T, 2, dtype=torch.float32, device="cuda")
     B.axonn_layernorm_fwd(T, h, X, G, Bt, eps, out, stats)
-    assert rel_fro(host(out), ref) < TOL
+    parity(host(out), ref, TOL, C_ONE, label="layernorm_fwd_bwd")
     st = host(stats)
     assert rel_fro(st[:, 0], x.astype(np.float64).mean(-1)) < 1e-4 or np.abs(st[:, 0] - x.mean(-1)).max() < 1e-5
     assert rel_fro(st[:, 1], rstd[:, 0]) < 1e-5
@@ -182,11 +206,11 @@ def test_layernorm_fwd_bwd(T, h):
     db = torch.empty(h, dtype=torch.float32, device="cuda")
     ws = torch.empty(2 * ((T + 63) // 64) * h, dtype=torch.float32, device="cuda")
     B.axonn_layernorm_bwd(T, h, DO, X, stats, G, RG, dx, dg, db, ws)
-    assert rel_fro(host(dx), dxr + resg) < TOL
+    parity(host(dx), dxr + resg, TOL, C_ONE, label="layernorm_fwd_bwd")
     assert rel_fro(host(dg), dgr) < 1e-4
     assert rel_fro(host(db), dbr) < 1e-4
     B.axonn_layernorm_bwd(T, h, DO, X, stats, G, None, dx, dg, db, ws)
-    assert rel_fro(host(dx), dxr) < TOL
+    parity(host(dx), dxr, TOL, C_ONE, label="layernorm_fwd_bwd")
 
 
 def test_layernorm_constant_row_gives_beta():
@@ -259,7 +283,7 @@ def test_attention_fwd_bwd(b, s, a, d):
     o = torch.zeros(b * s, h, dtype=B.torch_elem_dtype(), device="cuda")
     lse = torch.zeros(b, a, s, dtype=torch.float32, device="cuda")
     B.axonn_attention_fwd(b, s, a, d, QKV, o, lse)
-    assert rel_fro(host(o), o_ref) < TOL
+    parity(host(o), o_ref, TOL, C_ATTN, label="attention_fwd_bwd")
     assert np.abs(host(lse) - lse_ref).max() < 2e-3
     dqkv = torch.zeros(b * s, 3 * h, dtype=B.torch_elem_dtype(), device="cuda")
     delta = torch.zeros(b * a * s, dtype=torch.float32, device="cuda")
@@ -267,7 +291,7 @@ def test_attention_fwd_bwd(b, s, a, d):
     got = host(dqkv)
     # backward consumes the GPU's own bf16 o (one extra rounding in delta): 2x the single-op bound
     for name, sl in (("dq", slice(0, h)), ("dk", slice(h, 2 * h)), ("dv", slice(2 * h, 3 * h))):
-        assert rel_fro(got[:, sl], dqkv_ref[:, sl]) < 2 * TOL, name
+        parity(got[:, sl], dqkv_ref[:, sl], 2 * TOL, C_ATTN_BWD, label="attention_fwd_bwd_bwd")
     # first token attends only to itself: its output is its value row (bit exact)
     v0 = qkv.reshape(b, s, 3 * h)[:, 0, 2 * h:]
     assert np.array_equal(host(o).reshape(b, s, h)[:, 0], v0.astype(np.float64))
@@ -285,7 +309,8 @@ def test_attention_large_scores_stay_finite():
     lse = torch.zeros(b, a, s, dtype=torch.float32, device="cuda")
     B.axonn_attention_fwd(b, s, a, d, dev_bf16(qkv), o, lse)
     got = host(o)
-    assert np.isfinite(got).all() and rel_fro(got, o_ref) < TOL
+    assert np.isfinite(got).all()
+    parity(got, o_ref, TOL, C_ATTN, label="attention_large_scores_stay_finite")
 
 
 @pytest.mark.parametrize("slope,spike", [(0.02, 0.0), (0.12, 0.0), (0.02, 40.0)])
@@ -312,19 +337,37 @@ def test_attention_growing_row_maxima(slope, spike):
     o = torch.zeros(b * s, h, dtype=B.torch_elem_dtype(), device="cuda")
     lse = torch.zeros(b, a, s, dtype=torch.float32, device="cuda")
     B.axonn_attention_fwd(b, s, a, d, QKV, o, lse)
-    assert np.isfinite(host(o)).all() and rel_fro(host(o), o_ref) < TOL
+    assert np.isfinite(host(o)).all()
+    parity(host(o), o_ref, TOL, C_ATTN, label="attention_growing_row_maxima")
     assert np.abs(host(lse) - lse_ref).max() < 2e-3 * max(1.0, np.abs(lse_ref).max() / 10)
     dqkv = torch.zeros(b * s, 3 * h, dtype=B.torch_elem_dtype(), device="cuda")
     delta = torch.zeros(b * a * s, dtype=torch.float32, device="cuda")
     B.axonn_attention_bwd(b, s, a, d, QKV, o, lse, DO, dqkv, delta)
     got = host(dqkv)
-    # dv is a plain contraction with P.  dq and dk contract dS with keys / queries that here carry a large common
-    # component along u, while the rows of dS sum to zero: the 16-bit rounding of dS is multiplied by that
-    # component, so their bound grows with the largest ramp value over the typical element size.
-    amp = max(1.0, slope * s / 3.0)       # measured: 5e-2 for dq at slope 0.12 (amp 25.6), inside 2 * TOL at slope 0.02
-    assert rel_fro(got[:, 2 * h:], dqkv_ref[:, 2 * h:]) < 2 * TOL
-    for name, sl in (("dq", slice(0, h)), ("dk", slice(h, 2 * h))):
-        assert rel_fro(got[:, sl], dqkv_ref[:, sl]) < 2 * TOL * amp, name
+    # dv is a plain contraction with P.  dq = dS K / sqrt(d) and dk = dS^T Q / sqrt(d) contract the 16-bit rounding of dS
+    # with keys / queries that here carry a large common component along u, while the rows of dS sum to zero: the
+    # roundings do not cancel the way the exact terms do.  The bound follows from the input: roundings of relative
+    # size 2^-9 / sqrt(3) (uniform) with independent signs give an error of root mean square
+    # 2^-9 / sqrt(3) * sqrt((dS*dS) (K*K)) / sqrt(d) per element of dq.  The rounding of o, through delta = rowsum(dO o),
+    # adds a term of the same kind (an error per query times the probability-weighted mean key).  Bound: three times
+    # the prediction plus the bound of a well-conditioned input (measured at slope 0.12: 5.0e-2 against 6.7e-2).  (The lazy rescaling is a matter of the forward pass: its o, element by element, and
+    # its log-sum-exp are compared above.)
+    parity(got[:, 2 * h:], dqkv_ref[:, 2 * h:], 2 * TOL, C_ATTN_BWD, label="attention_growing_row_maxima_bwd")
+    q64 = qkv.astype(np.float64).reshape(s, 3, a, d)
+    for hd in range(a):
+        Q, K, V = q64[:, 0, hd], q64[:, 1, hd], q64[:, 2, hd]
+        S = np.where(np.tril(np.ones((s, s), bool)), Q @ K.T / np.sqrt(d), -np.inf)
+        P = np.exp(S - S.max(-1, keepdims=True)); P /= P.sum(-1, keepdims=True)
+        dO = dout.astype(np.float64).reshape(s, a, d)[:, hd]
+        dP = dO @ V.T
+        dS = P * (dP - (dP * P).sum(-1, keepdims=True))
+        r = 2.0 ** -9 / np.sqrt(3.0) / np.sqrt(d)
+        for name, c0, pred in (("dq", 0, r * np.sqrt((dS * dS) @ (K * K))), ("dk", h, r * np.sqrt((dS * dS).T @ (Q * Q)))):
+            sl = slice(c0 + hd * d, c0 + (hd + 1) * d)
+            ref_t = dqkv_ref[:, sl]
+            bound = 2 * TOL + 3 * np.linalg.norm(pred) / np.linalg.norm(ref_t)
+            e = rel_fro(got[:, sl], ref_t)
+            assert e < bound, (name, hd, e, bound)
 
 
 # ------------------------------------------------------------------------- Adam
