@@ -58,10 +58,11 @@ CONFIGS = {
     "table1_12b": StageShape(8, 4512, 24, 512, 8, 16),
 }
 PIPELINE_LIMITS = {"table1_12b": 6}   # configs whose pipeline_limit is not "all microbatches in flight"
-# configs whose stage is built with qkv_input_split = 1 (benchmark and full-size parity test alike): with
-# h = 10240 and N(0, 0.02) weights the attention logits have a standard deviation of 4, and the worst
-# parameter gradient misses the 3e-2 bound (3.4e-2) unless LayerNorm-1's output reaches the QKV projection unrounded
-QKV_INPUT_SPLIT = {"100b": 1}
+# configs whose stage is built with qkv_input_split (benchmark and full-size parity test alike): with h = 10240 and
+# N(0, 0.02) weights the attention logits have a standard deviation of 4, and the worst parameter gradient misses
+# the 3e-2 bound (3.4e-2) unless LayerNorm-1's output reaches the Q and K projections unrounded (mode 2: 2.7e-2;
+# mode 1, V as well: 2.6e-2)
+QKV_INPUT_SPLIT = {"100b": 2}
 OPT_CONFIG = dict(n=1_600_000_000, bucket_elems=1 << 26, lr=1e-4, beta1=0.9, beta2=0.95,
                   eps=1e-8, weight_decay=0.0, step=100, grad_scale=1.0)
 
