@@ -451,7 +451,10 @@ def main():
         if "optimizer" in out:
             hl = out["host_link"]
             o = out["optimizer"]
-            o["frac_of_link_measured"] = o["host_link_GBps_each_way"] / hl["both_GBps_each_way"]
+            # the step moves 12 B per parameter in each direction at once; the denominator is what the box
+            # delivers in one direction alone (two bare copy streams with nothing between them serialise on the copy
+            # engine: `both_GBps_each_way`; the step's drain copies run as kernels beside the engine's fetches)
+            o["frac_of_link_measured"] = o["host_link_GBps_each_way"] / min(hl["h2d_alone_GBps"], hl["d2h_alone_GBps"])
             o["frac_of_link_raw"] = o["host_link_GBps_each_way"] / hl["pcie_gen5_x16_raw_GBps"]
     # the other stage shapes of the benchmark definition, forward+backward only, a few batches each
     default_run = args.config == "12b" and not args.ends and not args.ckpt_stride
