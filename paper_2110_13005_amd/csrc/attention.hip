@@ -20,6 +20,15 @@ constexpr float kLn2 = 0.6931471805599453f;
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// max(v of this lane, v of lane ^ 32) with v_permlane32_swap: given the same register twice it leaves the lower half-wave's
+// values in both halves of one result and the upper half-wave's in both halves of the other.  Unlike a shuffle it does
+// not go through the LDS queue, whose results return in order: a shuffle behind a batch of fragment reads waits for all
+// of them.
+__device__ __forceinline__ float max_with_other_half(float v) {
+  const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // The kernels are compiled for head dimensions D = 64, 128 and 192.  EXACT: the head dimension is D.
 // Otherwise the real head dimension d (a multiple of 4, d <= D) is a run-time argument and the columns
 // d .. D-1 of every head read as zero and are never written: zero columns add nothing to q.k, and the
@@ -128,6 +137,44 @@ struct BothWaysStride {
   static_assert((LD / 2) % 64 == 12 || (LD / 2) % 64 == 52, "stride class");
 };
 
+// The rows a wave owns (32 of the workgroup's 128) enter and leave the kernels of the exact head dimensions through
+// LDS.  Fetched or stored straight from the MFMA layout, every lane touches a row of its own, 16 or 8 bytes at a time:
+// a memory instruction then covers 32 different lines, and the workgroups' first loads and last stores alone took a
+// fifth of the dK / dV kernel's time.  Staged, a load or store instruction covers whole rows (16 bytes per lane).
+//
+// stage_rows_in: the 128 x D tile at rows row0.. of a descriptor into LDS with row stride LD (all 256 threads; rows
+// beyond the descriptor's range read as zeros); the caller puts barriers around its use.
+template <int D, int LD>
+__device__ __forceinline__ void stage_rows_in(elem_t* lds, __amdgpu_buffer_rsrc_t rsrc, uint32_t row_bytes, int row0, int tid) {
+  TileRegs<128, D> t;
+  t.load_buffer(rsrc, TileRegs<128, D>::offset0(row_bytes, tid), row_bytes, row0);
+  t.template store<LD>(lds, tid);
+}
+// store_rows_out: one wave's 32 x D result (the MFMA result layout: lane = row lane % 32, registers 4q .. 4q+3 of
+// tile dt = columns 32 dt + 8 q + 4 (lane / 32) ..) times `mul`, rounded, to rows of `ld` elements at `dst`; `stage`
+// is 32 x (D + 8) elements of LDS that only this wave touches (no barrier: a wave's LDS operations keep their order).
+template <int D>
+__device__ __forceinline__ void store_rows_out(elem_t* stage, const floatx16* acc, float mul, elem_t* dst, int64_t ld,
+                                               int n_rows, int lane) {
+  constexpr int LDO = D + 8, DT = D / 32, CPR = D / 8;      // 16-byte chunks per row
+  const int g = lane >> 5;
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      elemx4 v;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = (elem_t)(acc[dt][4 * q + e] * mul);
+      *reinterpret_cast<elemx4*>(stage + (lane & 31) * LDO + dt * 32 + 8 * q + 4 * g) = v;
+    }
+#pragma unroll
+  for (int j = 0; j < 32 * CPR / 64; ++j) {
+    const int idx = lane + 64 * j, row = idx / CPR, ch = idx % CPR;
+    const uint4 v = *reinterpret_cast<const uint4*>(stage + row * LDO + ch * 8);
+    if (row < n_rows) *reinterpret_cast<uint4*>(dst + (int64_t)row * ld + ch * 8) = v;
+  }
+}
+
 // =============================================================================== forward
 // grid: (ceil(s/128), b*a); 4 waves; wave w owns queries q0 + 32w .. +31.
 template <int D, bool EXACT>
@@ -136,8 +183,10 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
                                                        elem_t* __restrict__ o,
                                                        float* __restrict__ lse) {
   constexpr int BKV = 64, LDK = D + 8, LDV = D + 32, DT = D / 32, KK = D / 16;
-  __shared__ __align__(16) elem_t sK[BKV * LDK];
-  __shared__ __align__(16) elem_t sV[BKV * LDV];
+  __shared__ __align__(16) elem_t smem[BKV * (LDK + LDV)];      // K and V tile; at the ends the staged Q and O rows
+  static_assert(BKV * (LDK + LDV) >= 128 * (D + 8), "the workgroup's 128 rows fit the tile buffers");
+  elem_t* sK = smem;
+  elem_t* sV = smem + BKV * LDK;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
   int rank, bh;
   attn_block(n_bh, rank, bh);
@@ -153,8 +202,15 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
   const float scale_log2 = kLog2e * rsqrtf((float)d);
 
   elemx8 qf[KK];
+  if (EXACT) {
+    stage_rows_in<D, D + 8>(smem, make_rsrc(qb, (uint32_t)(((int64_t)(s - 1) * ld + D) * 2)), (uint32_t)ld * 2u, q0, tid);
+    __syncthreads();
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) qf[kk] = global_frag<EXACT>(qb, ld, qi, s, kk * 16, lane, d);
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = frag_kcontig(smem + (32 * wave) * (D + 8) + kk * 16, D + 8, lane);
+  } else {
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = global_frag<EXACT>(qb, ld, qi, s, kk * 16, lane, d);
+  }
 
   floatx16 oacc[DT];
 #pragma unroll
@@ -189,14 +245,36 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
     if (kt + 1 < n_kt) fetch(k0 + BKV);
     if (k0 > qw0 + 31) continue;  // every key of the tile is in this wave's future
 
+    // All the K fragments of the tile are requested before the first MFMA, and the V fragments behind the last one,
+    // ahead of the exponentials: left to the compiler, every MFMA follows the LDS round trip of a read of its own.
+    // (Not where the fragments of a whole tile do not fit the registers: D = 192, and D = 128 with masked columns.)
+    constexpr bool BATCH = D <= 64 || (D <= 128 && EXACT);
+    elemx8 kfr[2][KK];
+    if (BATCH) {
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) kfr[ks][kk] = frag_kcontig(sK + (32 * ks) * LDK + kk * 16, LDK, lane);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     floatx16 sacc[2];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
+    for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int r = 0; r < 16; ++r) sacc[ks][r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk)
-        sacc[ks] = mfma32(frag_kcontig(sK + (32 * ks) * LDK + kk * 16, LDK, lane), qf[kk], sacc[ks]);
+    for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+      for (int ks = 0; ks < 2; ++ks)
+        sacc[ks] = mfma32(BATCH ? kfr[ks][kk] : frag_kcontig(sK + (32 * ks) * LDK + kk * 16, LDK, lane), qf[kk], sacc[ks]);
+    elemx8 vfr[4][DT];
+    if (BATCH) {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int kc = 0; kc < 4; ++kc)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) vfr[kc][dt] = frag_kstrided<true>(sV + (16 * kc) * LDV + dt * 32, LDV, lane);
+      __builtin_amdgcn_sched_barrier(0);
     }
     // Keys beyond the query are masked in the tiles that straddle the diagonal only: a real (wave-uniform)
     // branch, so that the other tiles do not pay for the comparisons.
@@ -216,7 +294,7 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
     for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[ks][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+    mx = max_with_other_half(mx) * scale_log2;
     // m_run is the reference point of the exponentials, not necessarily the running maximum: it moves (and the
     // sums so far are rescaled) only when some row's maximum has grown by more than 2^8 since it was set, so
     // most tiles skip the rescaling; p stays <= 256 and the result is the same up to rounding.
@@ -248,11 +326,17 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
         const elemx8 pf = pack8(sacc[ks], 8 * c);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
-          oacc[dt] = mfma32(frag_kstrided<true>(sV + (32 * ks + 16 * c) * LDV + dt * 32, LDV, lane),
+          oacc[dt] = mfma32(BATCH ? vfr[2 * ks + c][dt] : frag_kstrided<true>(sV + (32 * ks + 16 * c) * LDV + dt * 32, LDV, lane),
                             pf, oacc[dt]);
       }
   }
   const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  if (EXACT) {
+    __syncthreads();              // the tiles in LDS are done with
+    store_rows_out<D>(smem + wave * (32 * (D + 8)), oacc, 1.f / l_tot, o + ((int64_t)bi * s + qw0) * h + hd * d, h, s - qw0, lane);
+    if (g == 0 && qi < s) lse[((int64_t)bi * a + hd) * s + qi] = (m_run + __log2f(l_tot)) * kLn2;
+    return;
+  }
   if (qi < s) {
     const float inv = 1.f / l_tot;
     elem_t* orow = o + ((int64_t)bi * s + qi) * h + hd * d;
@@ -263,7 +347,7 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
         elemx4 v;
 #pragma unroll
         for (int e = 0; e < 4; ++e) v[e] = (elem_t)(oacc[dt][4 * q + e] * inv);
-        if (EXACT || dt * 32 + 8 * q + 4 * g < d) *reinterpret_cast<elemx4*>(orow + dt * 32 + 8 * q + 4 * g) = v;
+        if (dt * 32 + 8 * q + 4 * g < d) *reinterpret_cast<elemx4*>(orow + dt * 32 + 8 * q + 4 * g) = v;
       }
     if (g == 0) lse[((int64_t)bi * a + hd) * s + qi] = (m_run + __log2f(l_tot)) * kLn2;
   }
@@ -325,17 +409,27 @@ __global__ __launch_bounds__(256) void attn_delta_general_kernel(int64_t n_pairs
   }
 }
 
-// dK / dV: grid (ceil(s/128), b*a); wave w owns keys k0 + 32w .. +31 and walks the query tiles
-// at or below the diagonal.
+// dK / dV: grid (ceil(s/128), b*a); wave w owns keys k0 + 32w .. +31 and walks the 64-query tiles at or below the
+// diagonal.  The Q / dO tiles alternate between two LDS buffers: the next tile is fetched into registers at the top
+// of a step and stored to the other buffer at the end, so one barrier per tile is enough.
+//
+// A wave is alone on its SIMD (accumulators and K / V fragments take most of the register file), so nothing hides the
+// MFMA phases of a 32-query block behind its exponentials unless the instruction stream does.  Away from the diagonal
+// (no mask, no skipped block) the two 32-query blocks of a tile are therefore processed as a pair in four phases:
+// S and dP of block 0; S and dP of block 1 next to the exponentials of block 0; the dV / dK MFMAs of block 0 next to
+// the exponentials of block 1; the dV / dK MFMAs of block 1 next to the store of the next tile.  The fragment reads of
+// a phase are issued as a batch ahead of its MFMAs.  (Not at D = 192: the registers do not hold two blocks.)
 template <int D, bool EXACT>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
     int s, int a, int n_bh, int d_arg, const elem_t* __restrict__ qkv, const elem_t* __restrict__ dout,
     const float* __restrict__ lse, const float* __restrict__ delta, elem_t* __restrict__ dqkv) {
   constexpr int BQ = 64, LDQ = BothWaysStride<D>::LD, DT = D / 32, KK = D / 16;
-  __shared__ __align__(16) elem_t sQ[BQ * LDQ];
-  __shared__ __align__(16) elem_t sdO[BQ * LDQ];
-  __shared__ __align__(16) float s_lse[BQ];
-  __shared__ __align__(16) float s_delta[BQ];
+  constexpr bool PAIR = D <= 128;
+  constexpr int NBUF = 2;
+  __shared__ __align__(16) elem_t sQ_[NBUF][BQ * LDQ];
+  __shared__ __align__(16) elem_t sdO_[NBUF][BQ * LDQ];
+  __shared__ __align__(16) float s_lse_[NBUF][BQ];
+  __shared__ __align__(16) float s_delta_[NBUF][BQ];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
   int rank, bh;
   attn_block(n_bh, rank, bh);                  // key tile `rank` walks n_tiles - rank query tiles: longest first
@@ -353,10 +447,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
   const float scale = rsqrtf((float)d), scale_log2 = kLog2e * scale;
 
   elemx8 kf[KK], vf[KK];
+  if (EXACT) {
+    const uint32_t kv_bytes = (uint32_t)(((int64_t)(s - 1) * ld + D) * 2);
+    stage_rows_in<D, LDQ>(&sQ_[0][0], make_rsrc(kb, kv_bytes), (uint32_t)ld * 2u, k0, tid);
+    stage_rows_in<D, LDQ>(&sdO_[0][0], make_rsrc(vb, kv_bytes), (uint32_t)ld * 2u, k0, tid);
+    __syncthreads();
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    kf[kk] = global_frag<EXACT>(kb, ld, kj, s, kk * 16, lane, d);
-    vf[kk] = global_frag<EXACT>(vb, ld, kj, s, kk * 16, lane, d);
+    for (int kk = 0; kk < KK; ++kk) {
+      kf[kk] = frag_kcontig(&sQ_[0][0] + (32 * wave) * LDQ + kk * 16, LDQ, lane);
+      vf[kk] = frag_kcontig(&sdO_[0][0] + (32 * wave) * LDQ + kk * 16, LDQ, lane);
+    }
+    __syncthreads();
+  } else {
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      kf[kk] = global_frag<EXACT>(kb, ld, kj, s, kk * 16, lane, d);
+      vf[kk] = global_frag<EXACT>(vb, ld, kj, s, kk * 16, lane, d);
+    }
   }
   floatx16 dvacc[DT], dkacc[DT];
 #pragma unroll
@@ -385,18 +492,50 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
       r_delta = qrow < s ? delta_b[qrow] : 0.f;
     }
   };
-  prefetch(qt_begin);
-  for (int qt = qt_begin; qt < n_qt; ++qt) {
-    const int q0 = qt * BQ;
-    __syncthreads();
-    rq.template store<LDQ>(sQ, tid);
-    rdo.template store<LDQ>(sdO, tid);
+  auto store_tile = [&](int buf) {
+    rq.template store<LDQ>(sQ_[buf], tid);
+    rdo.template store<LDQ>(sdO_[buf], tid);
     if (tid < BQ) {
-      s_lse[tid] = r_lse * kLog2e;
-      s_delta[tid] = r_delta;
+      s_lse_[buf][tid] = r_lse * kLog2e;
+      s_delta_[buf][tid] = r_delta;
     }
-    __syncthreads();
-    if (qt + 1 < n_qt) prefetch(qt + 1);
+  };
+  // P and dS of one 32-query block from its scores and dP, in place, then rounded into MFMA operands:
+  // lane = key kj; register r = query 8*(r/4) + 4g + r%4 of the block
+  auto softmax_block = [&](const float* lse32, const float* delta32, floatx16& sacc, floatx16& pacc, elemx8* pf, elemx8* dsf) {
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const floatx4 l4 = *reinterpret_cast<const floatx4*>(&lse32[8 * q4 + 4 * g]);
+      const floatx4 d4 = *reinterpret_cast<const floatx4*>(&delta32[8 * q4 + 4 * g]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int r = 4 * q4 + e;
+        const float p = fast_exp2(fmaf(sacc[r], scale_log2, -l4[e]));
+        sacc[r] = p;
+        pacc[r] = p * (pacc[r] - d4[e]);
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      pf[c] = pack8(sacc, 8 * c);
+      dsf[c] = pack8(pacc, 8 * c);
+    }
+  };
+
+  prefetch(qt_begin);
+  store_tile(0);
+  // The two tiles on the diagonal (masks, blocks some waves skip), and every tile at D = 192, block by block
+  const int n_diag = PAIR ? min(n_qt, qt_begin + 2) : n_qt;
+  int qt = qt_begin;
+  for (; qt < n_diag; ++qt) {
+    const int q0 = qt * BQ, buf = (qt - qt_begin) & 1;
+    const elem_t* sQ = sQ_[buf];
+    const elem_t* sdO = sdO_[buf];
+    const float* s_lse = s_lse_[buf];
+    const float* s_delta = s_delta_[buf];
+    const bool more = qt + 1 < n_qt;
+    __syncthreads();              // tile qt is in LDS; every wave has left tile qt - 1, whose buffer the next store takes
+    if (more) prefetch(qt + 1);
 #pragma unroll
     for (int qs = 0; qs < 2; ++qs) {
       const int qq0 = q0 + 32 * qs;
@@ -409,7 +548,6 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
         sacc = mfma32(frag_kcontig(sQ + (32 * qs) * LDQ + kk * 16, LDQ, lane), kf[kk], sacc);
         pacc = mfma32(frag_kcontig(sdO + (32 * qs) * LDQ + kk * 16, LDQ, lane), vf[kk], pacc);
       }
-      // lane = key kj; register r = query qq0 + 8*(r/4) + 4g + r%4
       // masking in the blocks that straddle the diagonal only (a wave-uniform branch, kept as one)
       if (kw0 + 31 > qq0) {
         asm volatile("" ::: "memory");
@@ -419,31 +557,126 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
           if (kj > qrow) sacc[r] = -INFINITY;
         }
       }
+      elemx8 pf[2], dsf[2];
+      softmax_block(s_lse + 32 * qs, s_delta + 32 * qs, sacc, pacc, pf, dsf);
 #pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const floatx4 l4 = *reinterpret_cast<const floatx4*>(&s_lse[32 * qs + 8 * q4 + 4 * g]);
-        const floatx4 d4 = *reinterpret_cast<const floatx4*>(&s_delta[32 * qs + 8 * q4 + 4 * g]);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int r = 4 * q4 + e;
-          const float p = fast_exp2(fmaf(sacc[r], scale_log2, -l4[e]));
-          sacc[r] = p;
-          pacc[r] = p * (pacc[r] - d4[e]);
-        }
-      }
-#pragma unroll
-      for (int c = 0; c < 2; ++c) {
-        const elemx8 pf = pack8(sacc, 8 * c);
-        const elemx8 dsf = pack8(pacc, 8 * c);
+      for (int c = 0; c < 2; ++c)
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
           dvacc[dt] = mfma32(frag_kstrided<true>(sdO + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane),
-                             pf, dvacc[dt]);
+                             pf[c], dvacc[dt]);
           dkacc[dt] = mfma32(frag_kstrided<true>(sQ + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane),
-                             dsf, dkacc[dt]);
+                             dsf[c], dkacc[dt]);
         }
-      }
     }
+    if (more) store_tile(buf ^ 1);
+  }
+  // The tiles below the diagonal in pairs of blocks (a loop of its own, so that the accumulators keep one place in the
+  // register files throughout)
+  if constexpr (PAIR) {
+    // K and V fragments move to the accumulation registers, which the MFMAs below read them from
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) asm volatile("" : "+a"(kf[kk]), "+a"(vf[kk]));
+  }
+  if constexpr (PAIR) for (; qt < n_qt; ++qt) {
+    const int buf = (qt - qt_begin) & 1;
+    const elem_t* sQ = sQ_[buf];
+    const elem_t* sdO = sdO_[buf];
+    const float* s_lse = s_lse_[buf];
+    const float* s_delta = s_delta_[buf];
+    const bool more = qt + 1 < n_qt;
+    __syncthreads();              // tile qt is in LDS; every wave has left tile qt - 1, whose buffer the next store takes
+    if (more) prefetch(qt + 1);
+    // One pass over the pair's MFMAs in four phases of NS or NG slots each: scores of block 0, scores of block 1,
+    // gradients of block 0, gradients of block 1.  A slot is one MFMA, the LDS read of the fragment that the MFMA
+    // W - 1 slots later needs (a ring of W fragments, so the reads run ahead across the phase boundaries and only the
+    // first few of a tile are waited for), and a share of the other block's exponentials.  The MFMAs are volatile
+    // assembly: they keep this order, and the reads stay between them where they are written.
+    constexpr int NS = 2 * KK, NG = 4 * DT, NSLOT = 2 * NS + 2 * NG, W = 8;
+    constexpr int EPS = 16 / NS, EPG = 16 / NG;      // elements of a block per slot of the phase beside it
+    static_assert(16 % NS == 0 && 16 % NG == 0, "whole elements per slot");
+    floatx16 sacc[2], pacc[2];
+    uint32_t pfw[2][8], dsw[2][8];        // P and dS of a block rounded to 16 bits, two per word: MFMA operands
+    floatx4 l4[2], d4[2];                 // log-sum-exp and delta of the four queries of a group; two groups in flight
+    elemx8 ring[W];
+    auto load_stats = [&](int qs, int q4) {
+      l4[q4 & 1] = *reinterpret_cast<const floatx4*>(&s_lse[32 * qs + 8 * q4 + 4 * g]);
+      d4[q4 & 1] = *reinterpret_cast<const floatx4*>(&s_delta[32 * qs + 8 * q4 + 4 * g]);
+    };
+    // element r of a block: P = exp(S - lse), dS = P (dP - delta), both rounded once a pair is complete
+    auto softmax_elem = [&](int qs, int r) {
+      const int q4 = r >> 2;
+      const float p = fast_exp2(fmaf(sacc[qs][r], scale_log2, -l4[q4 & 1][r & 3]));
+      sacc[qs][r] = p;
+      pacc[qs][r] = p * (pacc[qs][r] - d4[q4 & 1][r & 3]);
+      if (r & 1) {
+        elemx2 pp, dd;
+        pp[0] = (elem_t)sacc[qs][r - 1]; pp[1] = (elem_t)sacc[qs][r];
+        dd[0] = (elem_t)pacc[qs][r - 1]; dd[1] = (elem_t)pacc[qs][r];
+        pfw[qs][r >> 1] = __builtin_bit_cast(uint32_t, pp);
+        dsw[qs][r >> 1] = __builtin_bit_cast(uint32_t, dd);
+      }
+      if ((r & 3) == 3 && q4 + 2 < 4) load_stats(qs, q4 + 2);     // the group after next, into the pair just used up
+    };
+    auto operand = [&](const uint32_t* w, int c) {
+      return __builtin_bit_cast(elemx8, make_uint4(w[4 * c], w[4 * c + 1], w[4 * c + 2], w[4 * c + 3]));
+    };
+    // fragment of slot j
+    auto load_frag = [&](int j) -> elemx8 {
+      if (j < 2 * NS) {
+        const int qs = j / NS, i = j % NS, kk = i >> 1;
+        return frag_kcontig(((i & 1) ? sdO : sQ) + (32 * qs) * LDQ + kk * 16, LDQ, lane);
+      }
+      const int qs = (j - 2 * NS) / NG, i = (j - 2 * NS) % NG, c = i / (2 * DT), dt = (i % (2 * DT)) >> 1;
+      return frag_kstrided<true>(((i & 1) ? sQ : sdO) + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane);
+    };
+    auto slot_mfma = [&](int j, elemx8 f) {
+      if (j < 2 * NS) {
+        const int qs = j / NS, i = j % NS, kk = i >> 1;
+        if (i & 1) {
+          if (kk == 0) mfma32_vgpr_zero_ba(pacc[qs], f, vf[kk]); else mfma32_vgpr_ba(pacc[qs], f, vf[kk]);
+        } else {
+          if (kk == 0) mfma32_vgpr_zero_ba(sacc[qs], f, kf[kk]); else mfma32_vgpr_ba(sacc[qs], f, kf[kk]);
+        }
+      } else {
+        const int qs = (j - 2 * NS) / NG, i = (j - 2 * NS) % NG, c = i / (2 * DT), dt = (i % (2 * DT)) >> 1;
+        if (i & 1) mfma32_agpr(dkacc[dt], f, operand(dsw[qs], c));
+        else mfma32_agpr(dvacc[dt], f, operand(pfw[qs], c));
+      }
+    };
+#pragma unroll
+    for (int j = 0; j < W - 1; ++j) ring[j] = load_frag(j);
+    load_stats(0, 0);
+    load_stats(0, 1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < NSLOT; ++j) {
+      if (j == NS) mfma32_settle(sacc[0], pacc[0]);                  // block 0's scores, read from this slot on
+      if (j == 2 * NS) mfma32_settle(sacc[1], pacc[1]);
+      slot_mfma(j, ring[j % W]);
+      if (j + W - 1 < NSLOT) ring[(j + W - 1) % W] = load_frag(j + W - 1);   // into the fragment of the slot before
+      if (j >= NS && j < 2 * NS) {
+#pragma unroll
+        for (int e = 0; e < EPS; ++e) softmax_elem(0, (j - NS) * EPS + e);
+        if (j == 2 * NS - 1) { load_stats(1, 0); load_stats(1, 1); }
+      } else if (j >= 2 * NS && j < 2 * NS + NG) {
+#pragma unroll
+        for (int e = 0; e < EPG; ++e) softmax_elem(1, (j - 2 * NS) * EPG + e);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (more) store_tile(buf ^ 1);
+  }
+  if (PAIR) {
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) mfma32_settle_agpr(dvacc[dt], dkacc[dt]);
+  }
+  if (EXACT) {
+    __syncthreads();              // the tiles in LDS are done with
+    elem_t* dk_rows = dqkv + ((int64_t)bi * s + kw0) * ld + h + hd * d;
+    store_rows_out<D>(&sQ_[0][0] + wave * (32 * (D + 8)), dkacc, scale, dk_rows, ld, s - kw0, lane);
+    store_rows_out<D>(&sdO_[0][0] + wave * (32 * (D + 8)), dvacc, 1.f, dk_rows + h, ld, s - kw0, lane);
+    return;
   }
   if (kj < s) {
     elem_t* dk_row = dqkv + ((int64_t)bi * s + kj) * ld + h + hd * d;
@@ -473,8 +706,10 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
     int s, int a, int n_bh, int d_arg, const elem_t* __restrict__ qkv, const elem_t* __restrict__ dout,
     const float* __restrict__ lse, const float* __restrict__ delta, elem_t* __restrict__ dqkv) {
   constexpr int BKV = 64, LDK = BothWaysStride<D>::LD, DT = D / 32, KK = D / 16;
-  __shared__ __align__(16) elem_t sK[BKV * LDK];
-  __shared__ __align__(16) elem_t sV[BKV * LDK];
+  __shared__ __align__(16) elem_t smem[2 * BKV * LDK];          // K and V tile; at the ends the staged Q, dO and dQ rows
+  static_assert(2 * BKV * LDK >= 128 * (D + 8), "the workgroup's 128 rows fit the tile buffers");
+  elem_t* sK = smem;
+  elem_t* sV = smem + BKV * LDK;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
   int rank, bh;
   attn_block(n_bh, rank, bh);
@@ -493,10 +728,22 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
   const float delta_q = (qi < s) ? delta[((int64_t)bi * a + hd) * s + qi] : 0.f;
 
   elemx8 qf[KK], dof[KK];
+  if (EXACT) {
+    stage_rows_in<D, D + 8>(smem, make_rsrc(qb, (uint32_t)(((int64_t)(s - 1) * ld + D) * 2)), (uint32_t)ld * 2u, q0, tid);
+    __syncthreads();
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) {
-    qf[kk] = global_frag<EXACT>(qb, ld, qi, s, kk * 16, lane, d);
-    dof[kk] = global_frag<EXACT>(dob, h, qi, s, kk * 16, lane, d);
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = frag_kcontig(smem + (32 * wave) * (D + 8) + kk * 16, D + 8, lane);
+    __syncthreads();
+    stage_rows_in<D, D + 8>(smem, make_rsrc(dob, (uint32_t)(((int64_t)(s - 1) * h + D) * 2)), (uint32_t)h * 2u, q0, tid);
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) dof[kk] = frag_kcontig(smem + (32 * wave) * (D + 8) + kk * 16, D + 8, lane);
+  } else {
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      qf[kk] = global_frag<EXACT>(qb, ld, qi, s, kk * 16, lane, d);
+      dof[kk] = global_frag<EXACT>(dob, h, qi, s, kk * 16, lane, d);
+    }
   }
   floatx16 dqacc[DT];
 #pragma unroll
@@ -563,6 +810,11 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
                              dsf, dqacc[dt]);
       }
     }
+  }
+  if (EXACT) {
+    __syncthreads();              // the tiles in LDS are done with
+    store_rows_out<D>(smem + wave * (32 * (D + 8)), dqacc, scale, dqkv + ((int64_t)bi * s + qw0) * ld + hd * d, ld, s - qw0, lane);
+    return;
   }
   if (qi < s) {
     elem_t* dq_row = dqkv + ((int64_t)bi * s + qi) * ld + hd * d;

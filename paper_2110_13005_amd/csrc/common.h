@@ -16,12 +16,14 @@ typedef _Float16 elem_t;
 #define AXONN_MFMA_32X32X16 __builtin_amdgcn_mfma_f32_32x32x16_f16
 #define AXONN_MFMA_16X16X32 __builtin_amdgcn_mfma_f32_16x16x32_f16
 #define AXONN_MFMA_16X16X32_ASM "v_mfma_f32_16x16x32_f16"
+#define AXONN_MFMA_32X32X16_ASM "v_mfma_f32_32x32x16_f16"
 #else
 typedef __bf16 elem_t;
 #define AXONN_ELEM_TYPE_ID 0
 #define AXONN_MFMA_32X32X16 __builtin_amdgcn_mfma_f32_32x32x16_bf16
 #define AXONN_MFMA_16X16X32 __builtin_amdgcn_mfma_f32_16x16x32_bf16
 #define AXONN_MFMA_16X16X32_ASM "v_mfma_f32_16x16x32_bf16"
+#define AXONN_MFMA_32X32X16_ASM "v_mfma_f32_32x32x16_bf16"
 #endif
 typedef __attribute__((__vector_size__(2 * sizeof(elem_t)))) elem_t elemx2;
 typedef __attribute__((__vector_size__(4 * sizeof(elem_t)))) elem_t elemx4;
@@ -65,6 +67,40 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 __device__ __forceinline__ void mfma16_acc(floatx4& c, elemx8 a, elemx8 b) {
   asm volatile(AXONN_MFMA_16X16X32_ASM " %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
+
+// The 32x32x16 form as inline assembly, for kernels that fix the order of their MFMAs and the register file of every
+// accumulator themselves (volatile statements keep their order, and memory operations do not move across them): a
+// kernel with more than 256 registers per lane gets the accumulation-register form of the builtin for every MFMA, and
+// results that vector instructions consume next would be copied out one register at a time.
+//   mfma32_agpr:   c += a x b, c in the accumulation registers (long-lived accumulators)
+//   mfma32_vgpr:   c += a x b, c in ordinary registers; mfma32_vgpr_zero: c = a x b
+// B may live in either file (BA variants: in the accumulation registers).  Hazards the caller keeps (the compiler does
+// not know these are MFMAs): results are read by other instructions only behind mfma32_settle() on them; operands
+// written by vector instructions just before are separated from the MFMA by mfma32_operand_gap().
+__device__ __forceinline__ void mfma32_agpr(floatx16& c, elemx8 a, elemx8 b) {
+  asm volatile(AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32_vgpr(floatx16& c, elemx8 a, elemx8 b) {
+  asm volatile(AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32_vgpr_zero(floatx16& c, elemx8 a, elemx8 b) {
+  asm volatile(AXONN_MFMA_32X32X16_ASM " %0, %1, %2, 0" : "=&v"(c) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32_vgpr_ba(floatx16& c, elemx8 a, elemx8 b) {
+  asm volatile(AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b));
+}
+__device__ __forceinline__ void mfma32_vgpr_zero_ba(floatx16& c, elemx8 a, elemx8 b) {
+  asm volatile(AXONN_MFMA_32X32X16_ASM " %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b));
+}
+// 24 idle cycles tied to the tiles: more than the eight passes of the last MFMA plus the distance the hazard rules ask
+// for before another kind of instruction reads its result.
+__device__ __forceinline__ void mfma32_settle(floatx16& c0, floatx16& c1) {
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(c0), "+v"(c1));
+}
+__device__ __forceinline__ void mfma32_settle_agpr(floatx16& c0, floatx16& c1) {
+  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+a"(c0), "+a"(c1));
+}
+__device__ __forceinline__ void mfma32_operand_gap() { asm volatile("s_nop 1"); }
 
 // Fragment of a 32(row) x 16(k) operand block from an LDS tile stored [row][k] (k
 // contiguous, `ld` elements per row).  `base` points at (row0, k0).

@@ -249,6 +249,10 @@ ATTN_SHAPES = [
     (1, 300, 4, 136),   # Table 1: 6528 / 48
     (1, 520, 2, 156),   # Table 1: 9360 / 60
     (2, 136, 2, 44),    # on the 64 kernel, half of a 16-byte chunk at the end of every head
+    # long enough for the tiles below the diagonal, which the backward kernels process in pairs of blocks
+    (1, 520, 2, 64),
+    (1, 400, 2, 100),   # on the 128 kernel with masked columns
+    (1, 400, 2, 44),    # on the 64 kernel with masked columns
     (1, 300, 4, 100),   # on the 128 kernel
     (1, 96, 2, 32),     # less than the smallest kernel
     (1, 130, 6, 36),
