@@ -13,6 +13,8 @@
 // in the backward kernels) are fetched with the transposing LDS read.
 #include "common.h"
 
+#include <type_traits>
+
 namespace axonn {
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -78,6 +80,16 @@ struct TileRegs {
 #pragma unroll
     for (int j = 0; j < NCH; ++j)
       r[j] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, base + (uint32_t)(j * RSTEP) * row_bytes, 0, 0));
+  }
+  // chunk j alone: for kernels that spread a tile's loads and stores over their instruction stream
+  __device__ __forceinline__ void load_buffer_one(int j, __amdgpu_buffer_rsrc_t rsrc, uint32_t off0, uint32_t row_bytes, int row0) {
+    constexpr int RSTEP = 256 / (D / 8);
+    r[j] = __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, off0 + (uint32_t)(row0 + j * RSTEP) * row_bytes, 0, 0));
+  }
+  template <int LD>
+  __device__ __forceinline__ void store_one(int j, elem_t* lds, int tid) const {
+    const int c = tid + j * 256;
+    *reinterpret_cast<uint4*>(lds + (c / (D / 8)) * LD + (c % (D / 8)) * 8) = r[j];
   }
   template <int LD>
   __device__ __forceinline__ void store(elem_t* lds, int tid) const {
@@ -409,27 +421,33 @@ __global__ __launch_bounds__(256) void attn_delta_general_kernel(int64_t n_pairs
   }
 }
 
-// dK / dV: grid (ceil(s/128), b*a); wave w owns keys k0 + 32w .. +31 and walks the 64-query tiles at or below the
+// dK / dV: grid (ceil(s/128), b*a); wave w owns keys k0 + 32w .. +31 and walks the query tiles at or below the
 // diagonal.  The Q / dO tiles alternate between two LDS buffers: the next tile is fetched into registers at the top
 // of a step and stored to the other buffer at the end, so one barrier per tile is enough.
 //
 // A wave is alone on its SIMD (accumulators and K / V fragments take most of the register file), so nothing hides the
-// MFMA phases of a 32-query block behind its exponentials unless the instruction stream does.  Away from the diagonal
-// (no mask, no skipped block) the two 32-query blocks of a tile are therefore processed as a pair in four phases:
-// S and dP of block 0; S and dP of block 1 next to the exponentials of block 0; the dV / dK MFMAs of block 0 next to
-// the exponentials of block 1; the dV / dK MFMAs of block 1 next to the store of the next tile.  The fragment reads of
-// a phase are issued as a batch ahead of its MFMAs.  (Not at D = 192: the registers do not hold two blocks.)
+// MFMA phases of a 32-query block behind its exponentials, or an LDS round trip behind an MFMA, unless the instruction
+// stream does.  Up to D = 128 a tile has 128 queries, four blocks, processed as two pairs in four phases each: S and
+// dP of the first block; S and dP of the second next to the exponentials of the first; the dV / dK MFMAs of the first
+// next to the exponentials of the second; the dV / dK MFMAs of the second.  A phase is a run of slots: one MFMA, the
+// LDS read of the fragment that the MFMA W - 1 slots later needs (a ring of W fragments, so the reads run ahead
+// across the phase boundaries and only the first few of a tile are waited for), and a share of the other block's
+// exponentials.  The MFMAs are volatile assembly: they keep this order, and the reads stay between them where they
+// are written.  The tile on the diagonal takes the same path with the mask applied to every element (a block above
+// the diagonal comes out as zeros; the wave with the lowest keys needs all four blocks anyway).
+// At D = 192 the registers do not hold two blocks: tiles of 64 queries, block by block.
 template <int D, bool EXACT>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
     int s, int a, int n_bh, int d_arg, const elem_t* __restrict__ qkv, const elem_t* __restrict__ dout,
     const float* __restrict__ lse, const float* __restrict__ delta, elem_t* __restrict__ dqkv) {
-  constexpr int BQ = 64, LDQ = BothWaysStride<D>::LD, DT = D / 32, KK = D / 16;
   constexpr bool PAIR = D <= 128;
+  constexpr int BQ = PAIR ? 128 : 64, LDQ = BothWaysStride<D>::LD, DT = D / 32, KK = D / 16;
   constexpr int NBUF = 2;
   __shared__ __align__(16) elem_t sQ_[NBUF][BQ * LDQ];
   __shared__ __align__(16) elem_t sdO_[NBUF][BQ * LDQ];
   __shared__ __align__(16) float s_lse_[NBUF][BQ];
   __shared__ __align__(16) float s_delta_[NBUF][BQ];
+  static_assert(NBUF * BQ * LDQ >= 128 * LDQ, "the workgroup's 128 keys fit the tile buffers");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5;
   int rank, bh;
   attn_block(n_bh, rank, bh);                  // key tile `rank` walks n_tiles - rank query tiles: longest first
@@ -478,6 +496,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
   const __amdgpu_buffer_rsrc_t q_rsrc = make_rsrc(qb, EXACT ? (uint32_t)(((int64_t)(s - 1) * ld + D) * 2) : 0u);
   const __amdgpu_buffer_rsrc_t do_rsrc = make_rsrc(dob, EXACT ? (uint32_t)(((int64_t)(s - 1) * h + D) * 2) : 0u);
   const uint32_t q_off0 = TileRegs<BQ, D>::offset0(q_row_bytes, tid), do_off0 = TileRegs<BQ, D>::offset0(do_row_bytes, tid);
+  auto prefetch_stats = [&](int qt) {
+    if (tid < BQ) {
+      const int qrow = qt * BQ + tid;
+      r_lse = qrow < s ? lse_b[qrow] : 0.f;
+      r_delta = qrow < s ? delta_b[qrow] : 0.f;
+    }
+  };
+  auto store_stats = [&](int buf) {
+    if (tid < BQ) {
+      s_lse_[buf][tid] = r_lse * kLog2e;
+      s_delta_[buf][tid] = r_delta;
+    }
+  };
   auto prefetch = [&](int qt) {
     if (EXACT) {
       rq.load_buffer(q_rsrc, q_off0, q_row_bytes, qt * BQ);
@@ -486,19 +517,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
       rq.template load<EXACT>(qb, ld, qt * BQ, s, d, tid);
       rdo.template load<EXACT>(dob, h, qt * BQ, s, d, tid);
     }
-    if (tid < BQ) {
-      const int qrow = qt * BQ + tid;
-      r_lse = qrow < s ? lse_b[qrow] : 0.f;
-      r_delta = qrow < s ? delta_b[qrow] : 0.f;
-    }
+    prefetch_stats(qt);
   };
   auto store_tile = [&](int buf) {
     rq.template store<LDQ>(sQ_[buf], tid);
     rdo.template store<LDQ>(sdO_[buf], tid);
-    if (tid < BQ) {
-      s_lse_[buf][tid] = r_lse * kLog2e;
-      s_delta_[buf][tid] = r_delta;
-    }
+    store_stats(buf);
   };
   // P and dS of one 32-query block from its scores and dP, in place, then rounded into MFMA operands:
   // lane = key kj; register r = query 8*(r/4) + 4g + r%4 of the block
@@ -524,150 +548,176 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
 
   prefetch(qt_begin);
   store_tile(0);
-  // The two tiles on the diagonal (masks, blocks some waves skip), and every tile at D = 192, block by block
-  const int n_diag = PAIR ? min(n_qt, qt_begin + 2) : n_qt;
-  int qt = qt_begin;
-  for (; qt < n_diag; ++qt) {
-    const int q0 = qt * BQ, buf = (qt - qt_begin) & 1;
-    const elem_t* sQ = sQ_[buf];
-    const elem_t* sdO = sdO_[buf];
-    const float* s_lse = s_lse_[buf];
-    const float* s_delta = s_delta_[buf];
-    const bool more = qt + 1 < n_qt;
-    __syncthreads();              // tile qt is in LDS; every wave has left tile qt - 1, whose buffer the next store takes
-    if (more) prefetch(qt + 1);
+  if constexpr (!PAIR) {
+    for (int qt = qt_begin; qt < n_qt; ++qt) {
+      const int q0 = qt * BQ, buf = (qt - qt_begin) & 1;
+      const elem_t* sQ = sQ_[buf];
+      const elem_t* sdO = sdO_[buf];
+      const float* s_lse = s_lse_[buf];
+      const float* s_delta = s_delta_[buf];
+      const bool more = qt + 1 < n_qt;
+      __syncthreads();            // tile qt is in LDS; every wave has left tile qt - 1, whose buffer the next store takes
+      if (more) prefetch(qt + 1);
 #pragma unroll
-    for (int qs = 0; qs < 2; ++qs) {
-      const int qq0 = q0 + 32 * qs;
-      if (qq0 + 31 < kw0) continue;  // all these queries precede every key of this wave
-      floatx16 sacc, pacc;
+      for (int qs = 0; qs < BQ / 32; ++qs) {
+        const int qq0 = q0 + 32 * qs;
+        if (qq0 + 31 < kw0) continue;  // all these queries precede every key of this wave
+        floatx16 sacc, pacc;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sacc[r] = pacc[r] = 0.f;
+        for (int r = 0; r < 16; ++r) sacc[r] = pacc[r] = 0.f;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        sacc = mfma32(frag_kcontig(sQ + (32 * qs) * LDQ + kk * 16, LDQ, lane), kf[kk], sacc);
-        pacc = mfma32(frag_kcontig(sdO + (32 * qs) * LDQ + kk * 16, LDQ, lane), vf[kk], pacc);
-      }
-      // masking in the blocks that straddle the diagonal only (a wave-uniform branch, kept as one)
-      if (kw0 + 31 > qq0) {
-        asm volatile("" ::: "memory");
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int qrow = qq0 + 8 * (r >> 2) + 4 * g + (r & 3);
-          if (kj > qrow) sacc[r] = -INFINITY;
+        for (int kk = 0; kk < KK; ++kk) {
+          sacc = mfma32(frag_kcontig(sQ + (32 * qs) * LDQ + kk * 16, LDQ, lane), kf[kk], sacc);
+          pacc = mfma32(frag_kcontig(sdO + (32 * qs) * LDQ + kk * 16, LDQ, lane), vf[kk], pacc);
         }
-      }
-      elemx8 pf[2], dsf[2];
-      softmax_block(s_lse + 32 * qs, s_delta + 32 * qs, sacc, pacc, pf, dsf);
+        // masking in the blocks that straddle the diagonal only (a wave-uniform branch, kept as one)
+        if (kw0 + 31 > qq0) {
+          asm volatile("" ::: "memory");
 #pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          dvacc[dt] = mfma32(frag_kstrided<true>(sdO + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane),
-                             pf[c], dvacc[dt]);
-          dkacc[dt] = mfma32(frag_kstrided<true>(sQ + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane),
-                             dsf[c], dkacc[dt]);
+          for (int r = 0; r < 16; ++r) {
+            const int qrow = qq0 + 8 * (r >> 2) + 4 * g + (r & 3);
+            if (kj > qrow) sacc[r] = -INFINITY;
+          }
         }
-    }
+        elemx8 pf[2], dsf[2];
+        softmax_block(s_lse + 32 * qs, s_delta + 32 * qs, sacc, pacc, pf, dsf);
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int dt = 0; dt < DT; ++dt) {
+            dvacc[dt] = mfma32(frag_kstrided<true>(sdO + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane),
+                               pf[c], dvacc[dt]);
+            dkacc[dt] = mfma32(frag_kstrided<true>(sQ + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane),
+                               dsf[c], dkacc[dt]);
+          }
+      }
     if (more) store_tile(buf ^ 1);
-  }
-  // The tiles below the diagonal in pairs of blocks (a loop of its own, so that the accumulators keep one place in the
-  // register files throughout)
-  if constexpr (PAIR) {
+    }
+  } else {
     // K and V fragments move to the accumulation registers, which the MFMAs below read them from
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) asm volatile("" : "+a"(kf[kk]), "+a"(vf[kk]));
-  }
-  if constexpr (PAIR) for (; qt < n_qt; ++qt) {
-    const int buf = (qt - qt_begin) & 1;
-    const elem_t* sQ = sQ_[buf];
-    const elem_t* sdO = sdO_[buf];
-    const float* s_lse = s_lse_[buf];
-    const float* s_delta = s_delta_[buf];
-    const bool more = qt + 1 < n_qt;
-    __syncthreads();              // tile qt is in LDS; every wave has left tile qt - 1, whose buffer the next store takes
-    if (more) prefetch(qt + 1);
-    // One pass over the pair's MFMAs in four phases of NS or NG slots each: scores of block 0, scores of block 1,
-    // gradients of block 0, gradients of block 1.  A slot is one MFMA, the LDS read of the fragment that the MFMA
-    // W - 1 slots later needs (a ring of W fragments, so the reads run ahead across the phase boundaries and only the
-    // first few of a tile are waited for), and a share of the other block's exponentials.  The MFMAs are volatile
-    // assembly: they keep this order, and the reads stay between them where they are written.
-    constexpr int NS = 2 * KK, NG = 4 * DT, NSLOT = 2 * NS + 2 * NG, W = 8;
+    constexpr int NS = 2 * KK, NG = 4 * DT, PS = 2 * NS + 2 * NG, NSLOT = 2 * PS, W = 8;
     constexpr int EPS = 16 / NS, EPG = 16 / NG;      // elements of a block per slot of the phase beside it
     static_assert(16 % NS == 0 && 16 % NG == 0, "whole elements per slot");
-    floatx16 sacc[2], pacc[2];
-    uint32_t pfw[2][8], dsw[2][8];        // P and dS of a block rounded to 16 bits, two per word: MFMA operands
-    floatx4 l4[2], d4[2];                 // log-sum-exp and delta of the four queries of a group; two groups in flight
-    elemx8 ring[W];
-    auto load_stats = [&](int qs, int q4) {
-      l4[q4 & 1] = *reinterpret_cast<const floatx4*>(&s_lse[32 * qs + 8 * q4 + 4 * g]);
-      d4[q4 & 1] = *reinterpret_cast<const floatx4*>(&s_delta[32 * qs + 8 * q4 + 4 * g]);
-    };
-    // element r of a block: P = exp(S - lse), dS = P (dP - delta), both rounded once a pair is complete
-    auto softmax_elem = [&](int qs, int r) {
-      const int q4 = r >> 2;
-      const float p = fast_exp2(fmaf(sacc[qs][r], scale_log2, -l4[q4 & 1][r & 3]));
-      sacc[qs][r] = p;
-      pacc[qs][r] = p * (pacc[qs][r] - d4[q4 & 1][r & 3]);
-      if (r & 1) {
-        elemx2 pp, dd;
-        pp[0] = (elem_t)sacc[qs][r - 1]; pp[1] = (elem_t)sacc[qs][r];
-        dd[0] = (elem_t)pacc[qs][r - 1]; dd[1] = (elem_t)pacc[qs][r];
-        pfw[qs][r >> 1] = __builtin_bit_cast(uint32_t, pp);
-        dsw[qs][r >> 1] = __builtin_bit_cast(uint32_t, dd);
-      }
-      if ((r & 3) == 3 && q4 + 2 < 4) load_stats(qs, q4 + 2);     // the group after next, into the pair just used up
-    };
-    auto operand = [&](const uint32_t* w, int c) {
-      return __builtin_bit_cast(elemx8, make_uint4(w[4 * c], w[4 * c + 1], w[4 * c + 2], w[4 * c + 3]));
-    };
-    // fragment of slot j
-    auto load_frag = [&](int j) -> elemx8 {
-      if (j < 2 * NS) {
-        const int qs = j / NS, i = j % NS, kk = i >> 1;
-        return frag_kcontig(((i & 1) ? sdO : sQ) + (32 * qs) * LDQ + kk * 16, LDQ, lane);
-      }
-      const int qs = (j - 2 * NS) / NG, i = (j - 2 * NS) % NG, c = i / (2 * DT), dt = (i % (2 * DT)) >> 1;
-      return frag_kstrided<true>(((i & 1) ? sQ : sdO) + (32 * qs + 16 * c) * LDQ + dt * 32, LDQ, lane);
-    };
-    auto slot_mfma = [&](int j, elemx8 f) {
-      if (j < 2 * NS) {
-        const int qs = j / NS, i = j % NS, kk = i >> 1;
-        if (i & 1) {
-          if (kk == 0) mfma32_vgpr_zero_ba(pacc[qs], f, vf[kk]); else mfma32_vgpr_ba(pacc[qs], f, vf[kk]);
-        } else {
-          if (kk == 0) mfma32_vgpr_zero_ba(sacc[qs], f, kf[kk]); else mfma32_vgpr_ba(sacc[qs], f, kf[kk]);
+    // One tile: `masked` is a std::integral_constant (the tile on the diagonal: keys beyond the query get no weight)
+    // `fetch_row0` >= 0: the tile at that row is fetched on the way and stored to the other buffer (exact head
+    // dimensions): one 16-byte piece per thread and slot, the loads in the first score phase and the stores in the
+    // last gradient phase, whose slots have no exponentials beside their MFMAs.  Issued in one go, the loads of the
+    // four waves wait for the memory pipeline, and the stores for the LDS, with nothing to do meanwhile.
+    constexpr int NCH = TileRegs<BQ, D>::NCH, STORE_SLOT0 = NSLOT - 2 * NCH;
+    static_assert(2 * NCH <= NS && 2 * NCH <= NG, "a piece per slot of one phase");
+    auto tile_stream = [&](int q0, int buf, int fetch_row0, auto masked) {
+      constexpr bool MASKED = decltype(masked)::value;
+      const elem_t* sQ = sQ_[buf];
+      const elem_t* sdO = sdO_[buf];
+      const float* s_lse = s_lse_[buf];
+      const float* s_delta = s_delta_[buf];
+      floatx16 sacc[2], pacc[2];          // of the pair in flight
+      uint32_t pfw[2][8], dsw[2][8];      // P and dS of a block rounded to 16 bits, two per word: MFMA operands
+      floatx4 l4[2], d4[2];               // log-sum-exp and delta of the four queries of a group; two groups in flight
+      elemx8 ring[W];
+      auto load_stats = [&](int blk, int q4) {
+        l4[q4 & 1] = *reinterpret_cast<const floatx4*>(&s_lse[32 * blk + 8 * q4 + 4 * g]);
+        d4[q4 & 1] = *reinterpret_cast<const floatx4*>(&s_delta[32 * blk + 8 * q4 + 4 * g]);
+      };
+      // element r of block blk (half hf of its pair): P = exp(S - lse), dS = P (dP - delta), rounded once a pair of
+      // elements is complete
+      auto softmax_elem = [&](int blk, int r) {
+        const int hf = blk & 1, q4 = r >> 2;
+        float x = fmaf(sacc[hf][r], scale_log2, -l4[q4 & 1][r & 3]);
+        if (MASKED && kj > q0 + 32 * blk + 8 * q4 + 4 * g + (r & 3)) x = -INFINITY;
+        const float p = fast_exp2(x);
+        sacc[hf][r] = p;
+        pacc[hf][r] = p * (pacc[hf][r] - d4[q4 & 1][r & 3]);
+        if (r & 1) {
+          elemx2 pp, dd;
+          pp[0] = (elem_t)sacc[hf][r - 1]; pp[1] = (elem_t)sacc[hf][r];
+          dd[0] = (elem_t)pacc[hf][r - 1]; dd[1] = (elem_t)pacc[hf][r];
+          pfw[hf][r >> 1] = __builtin_bit_cast(uint32_t, pp);
+          dsw[hf][r >> 1] = __builtin_bit_cast(uint32_t, dd);
         }
-      } else {
-        const int qs = (j - 2 * NS) / NG, i = (j - 2 * NS) % NG, c = i / (2 * DT), dt = (i % (2 * DT)) >> 1;
-        if (i & 1) mfma32_agpr(dkacc[dt], f, operand(dsw[qs], c));
-        else mfma32_agpr(dvacc[dt], f, operand(pfw[qs], c));
+        if ((r & 3) == 3 && q4 + 2 < 4) load_stats(blk, q4 + 2);     // the group after next, into the pair just used up
+      };
+      auto operand = [&](const uint32_t* w, int c) {
+        return __builtin_bit_cast(elemx8, make_uint4(w[4 * c], w[4 * c + 1], w[4 * c + 2], w[4 * c + 3]));
+      };
+      // slot j: pair j / PS; within the pair, score slots of its two blocks, then gradient slots of its two blocks
+      auto load_frag = [&](int j) -> elemx8 {
+        const int pair = j / PS, jj = j % PS;
+        if (jj < 2 * NS) {
+          const int blk = 2 * pair + jj / NS, i = jj % NS, kk = i >> 1;
+          return frag_kcontig(((i & 1) ? sdO : sQ) + (32 * blk) * LDQ + kk * 16, LDQ, lane);
+        }
+        const int blk = 2 * pair + (jj - 2 * NS) / NG, i = (jj - 2 * NS) % NG, c = i / (2 * DT), dt = (i % (2 * DT)) >> 1;
+        return frag_kstrided<true>(((i & 1) ? sQ : sdO) + (32 * blk + 16 * c) * LDQ + dt * 32, LDQ, lane);
+      };
+      auto slot_mfma = [&](int j, elemx8 f) {
+        const int jj = j % PS;
+        if (jj < 2 * NS) {
+          const int hf = jj / NS, i = jj % NS, kk = i >> 1;
+          if (i & 1) {
+            if (kk == 0) mfma32_vgpr_zero_ba(pacc[hf], f, vf[kk]);
+            else if (kk == KK - 1) mfma32_vgpr_settled_ba(pacc[hf], f, vf[kk]);     // the phase's last: its block's scores settle
+            else mfma32_vgpr_ba(pacc[hf], f, vf[kk]);
+          } else {
+            if (kk == 0) mfma32_vgpr_zero_ba(sacc[hf], f, kf[kk]); else mfma32_vgpr_ba(sacc[hf], f, kf[kk]);
+          }
+        } else {
+          const int hf = (jj - 2 * NS) / NG, i = (jj - 2 * NS) % NG, c = i / (2 * DT), dt = (i % (2 * DT)) >> 1;
+          if (i & 1) mfma32_agpr(dkacc[dt], f, operand(dsw[hf], c));
+          else mfma32_agpr(dvacc[dt], f, operand(pfw[hf], c));
+        }
+      };
+#pragma unroll
+      for (int j = 0; j < W - 1; ++j) ring[j] = load_frag(j);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < NSLOT; ++j) {
+        const int pair = j / PS, jj = j % PS;
+        slot_mfma(j, ring[j % W]);
+        if (j + W - 1 < NSLOT) ring[(j + W - 1) % W] = load_frag(j + W - 1);   // into the fragment of the slot before
+        if (jj == NS - 1) { load_stats(2 * pair, 0); load_stats(2 * pair, 1); }
+        if (EXACT && fetch_row0 >= 0) {
+          if (j < 2 * NCH) {
+            const int k = j;
+            if (k < NCH) rq.load_buffer_one(k, q_rsrc, q_off0, q_row_bytes, fetch_row0);
+            else rdo.load_buffer_one(k - NCH, do_rsrc, do_off0, do_row_bytes, fetch_row0);
+          }
+          if (j >= STORE_SLOT0) {
+            const int k = j - STORE_SLOT0;
+            if (k < NCH) rq.template store_one<LDQ>(k, sQ_[buf ^ 1], tid);
+            else rdo.template store_one<LDQ>(k - NCH, sdO_[buf ^ 1], tid);
+          }
+        }
+        if (jj >= NS && jj < 2 * NS) {
+#pragma unroll
+          for (int e = 0; e < EPS; ++e) softmax_elem(2 * pair, (jj - NS) * EPS + e);
+          if (jj == 2 * NS - 1) { load_stats(2 * pair + 1, 0); load_stats(2 * pair + 1, 1); }
+        } else if (jj >= 2 * NS && jj < 2 * NS + NG) {
+#pragma unroll
+          for (int e = 0; e < EPG; ++e) softmax_elem(2 * pair + 1, (jj - 2 * NS) * EPG + e);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     };
-#pragma unroll
-    for (int j = 0; j < W - 1; ++j) ring[j] = load_frag(j);
-    load_stats(0, 0);
-    load_stats(0, 1);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < NSLOT; ++j) {
-      if (j == NS) mfma32_settle(sacc[0], pacc[0]);                  // block 0's scores, read from this slot on
-      if (j == 2 * NS) mfma32_settle(sacc[1], pacc[1]);
-      slot_mfma(j, ring[j % W]);
-      if (j + W - 1 < NSLOT) ring[(j + W - 1) % W] = load_frag(j + W - 1);   // into the fragment of the slot before
-      if (j >= NS && j < 2 * NS) {
-#pragma unroll
-        for (int e = 0; e < EPS; ++e) softmax_elem(0, (j - NS) * EPS + e);
-        if (j == 2 * NS - 1) { load_stats(1, 0); load_stats(1, 1); }
-      } else if (j >= 2 * NS && j < 2 * NS + NG) {
-#pragma unroll
-        for (int e = 0; e < EPG; ++e) softmax_elem(1, (j - 2 * NS) * EPG + e);
-      }
-      __builtin_amdgcn_sched_barrier(0);
+    // the tile on the diagonal, then the others in a loop of their own (so that the accumulators keep one place in
+    // the register files throughout it)
+    {
+      const bool more = qt_begin + 1 < n_qt;
+      __syncthreads();
+      if (more) { if (EXACT) prefetch_stats(qt_begin + 1); else prefetch(qt_begin + 1); }
+      tile_stream(qt_begin * BQ, 0, more ? (qt_begin + 1) * BQ : -1, std::true_type{});
+      if (more) { if (EXACT) store_stats(1); else store_tile(1); }
     }
-    if (more) store_tile(buf ^ 1);
-  }
-  if (PAIR) {
+    for (int qt = qt_begin + 1; qt < n_qt; ++qt) {
+      const int buf = (qt - qt_begin) & 1;
+      const bool more = qt + 1 < n_qt;
+      __syncthreads();            // tile qt is in LDS; every wave has left tile qt - 1, whose buffer the next store takes
+      if (more) { if (EXACT) prefetch_stats(qt + 1); else prefetch(qt + 1); }
+      tile_stream(qt * BQ, buf, more ? (qt + 1) * BQ : -1, std::false_type{});
+      if (more) { if (EXACT) store_stats(buf ^ 1); else store_tile(buf ^ 1); }
+    }
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) mfma32_settle_agpr(dvacc[dt], dkacc[dt]);
   }
@@ -691,7 +741,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
           kv4[e] = (elem_t)(dkacc[dt][4 * q + e] * scale);
           vv4[e] = (elem_t)dvacc[dt][4 * q + e];
         }
-        if (EXACT || dt * 32 + 8 * q + 4 * g < d) {
+        if (dt * 32 + 8 * q + 4 * g < d) {
           *reinterpret_cast<elemx4*>(dk_row + dt * 32 + 8 * q + 4 * g) = kv4;
           *reinterpret_cast<elemx4*>(dv_row + dt * 32 + 8 * q + 4 * g) = vv4;
         }

@@ -73,34 +73,42 @@ __device__ __forceinline__ void mfma16_acc(floatx4& c, elemx8 a, elemx8 b) {
 // kernel with more than 256 registers per lane gets the accumulation-register form of the builtin for every MFMA, and
 // results that vector instructions consume next would be copied out one register at a time.
 //   mfma32_agpr:   c += a x b, c in the accumulation registers (long-lived accumulators)
-//   mfma32_vgpr:   c += a x b, c in ordinary registers; mfma32_vgpr_zero: c = a x b
-// B may live in either file (BA variants: in the accumulation registers).  Hazards the caller keeps (the compiler does
-// not know these are MFMAs): results are read by other instructions only behind mfma32_settle() on them; operands
-// written by vector instructions just before are separated from the MFMA by mfma32_operand_gap().
+//   mfma32_vgpr:   c += a x b, c in ordinary registers; _zero: c = a x b
+//   _ba:           b in the accumulation registers
+// The compiler does not know these are MFMAs and keeps none of their hazards, so the statements carry them:
+//   * two wait states ahead of every MFMA: the distance a register written by a vector instruction needs before an
+//     MFMA reads it, and the compiler may place such a write (a copy, an initialisation, the conversion that produces
+//     an operand) directly in front of the statement;
+//   * _settled: 20 wait states behind the MFMA, inside the statement, so that nothing can come between: more than
+//     the eight passes plus the distance the rules ask for before another kind of instruction reads (or the
+//     compiler copies) the result.  They pass while the MFMA executes.  A chain's last MFMA is issued this way, or
+//     one MFMA before such a one; mfma32_settle_agpr does the same for accumulators at the end of a kernel.
+#define AXONN_MFMA32_GAP "s_nop 1\n\t"
+#define AXONN_MFMA32_SETTLE "\n\ts_nop 7\n\ts_nop 7\n\ts_nop 3"
 __device__ __forceinline__ void mfma32_agpr(floatx16& c, elemx8 a, elemx8 b) {
-  asm volatile(AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
+  asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma32_vgpr(floatx16& c, elemx8 a, elemx8 b) {
-  asm volatile(AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+  asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma32_vgpr_zero(floatx16& c, elemx8 a, elemx8 b) {
-  asm volatile(AXONN_MFMA_32X32X16_ASM " %0, %1, %2, 0" : "=&v"(c) : "v"(a), "v"(b));
+  asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, 0" : "=&v"(c) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void mfma32_vgpr_settled(floatx16& c, elemx8 a, elemx8 b) {
+  asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" AXONN_MFMA32_SETTLE : "+v"(c) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma32_vgpr_ba(floatx16& c, elemx8 a, elemx8 b) {
-  asm volatile(AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b));
+  asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b));
 }
 __device__ __forceinline__ void mfma32_vgpr_zero_ba(floatx16& c, elemx8 a, elemx8 b) {
-  asm volatile(AXONN_MFMA_32X32X16_ASM " %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b));
+  asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, 0" : "=&v"(c) : "v"(a), "a"(b));
 }
-// 24 idle cycles tied to the tiles: more than the eight passes of the last MFMA plus the distance the hazard rules ask
-// for before another kind of instruction reads its result.
-__device__ __forceinline__ void mfma32_settle(floatx16& c0, floatx16& c1) {
-  asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+v"(c0), "+v"(c1));
+__device__ __forceinline__ void mfma32_vgpr_settled_ba(floatx16& c, elemx8 a, elemx8 b) {
+  asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" AXONN_MFMA32_SETTLE : "+v"(c) : "v"(a), "a"(b));
 }
 __device__ __forceinline__ void mfma32_settle_agpr(floatx16& c0, floatx16& c1) {
   asm volatile("s_nop 7\n\ts_nop 7\n\ts_nop 7" : "+a"(c0), "+a"(c1));
 }
-__device__ __forceinline__ void mfma32_operand_gap() { asm volatile("s_nop 1"); }
 
 // Fragment of a 32(row) x 16(k) operand block from an LDS tile stored [row][k] (k
 // contiguous, `ld` elements per row).  `base` points at (row0, k0).
