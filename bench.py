@@ -27,7 +27,7 @@ import numpy as np  # noqa: E402
 
 # L2-miss bytes per launch of the weight-gradient GEMM from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # (summaries and the scaling by a plain copy under profiles/); keyed by (config, wgrad_group, grad_accum).
-WGRAD_TRAFFIC_BYTES = {("12b", 3, "bf16"): 1.685e9}   # profiles/gemm_wgrad_12b_hbm_traffic.md
+WGRAD_TRAFFIC_BYTES = {("12b", 3, "bf16"): 1.687e9}   # profiles/gemm_wgrad_12b_hbm_traffic.md
 VOCAB = 51200
 
 
