@@ -72,9 +72,8 @@ __device__ __forceinline__ void mfma16_acc(floatx4& c, elemx8 a, elemx8 b) {
 // accumulator themselves (volatile statements keep their order, and memory operations do not move across them): a
 // kernel with more than 256 registers per lane gets the accumulation-register form of the builtin for every MFMA, and
 // results that vector instructions consume next would be copied out one register at a time.
-//   mfma32_agpr:   c += a x b, c in the accumulation registers (long-lived accumulators)
-//   mfma32_vgpr:   c += a x b, c in ordinary registers; _zero: c = a x b
-//   _ba:           b in the accumulation registers
+//   mfma32_agpr:      c += a x b, c in the accumulation registers (long-lived accumulators)
+//   mfma32_vgpr_*_ba: c in ordinary registers, b in the accumulation registers; plain: c += a x b, _zero: c = a x b
 // The compiler does not know these are MFMAs and keeps none of their hazards, so the statements carry them:
 //   * two wait states ahead of every MFMA: the distance a register written by a vector instruction needs before an
 //     MFMA reads it, and the compiler may place such a write (a copy, an initialisation, the conversion that produces
@@ -87,15 +86,6 @@ __device__ __forceinline__ void mfma16_acc(floatx4& c, elemx8 a, elemx8 b) {
 #define AXONN_MFMA32_SETTLE "\n\ts_nop 7\n\ts_nop 7\n\ts_nop 3"
 __device__ __forceinline__ void mfma32_agpr(floatx16& c, elemx8 a, elemx8 b) {
   asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+a"(c) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma32_vgpr(floatx16& c, elemx8 a, elemx8 b) {
-  asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma32_vgpr_zero(floatx16& c, elemx8 a, elemx8 b) {
-  asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, 0" : "=&v"(c) : "v"(a), "v"(b));
-}
-__device__ __forceinline__ void mfma32_vgpr_settled(floatx16& c, elemx8 a, elemx8 b) {
-  asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" AXONN_MFMA32_SETTLE : "+v"(c) : "v"(a), "v"(b));
 }
 __device__ __forceinline__ void mfma32_vgpr_ba(floatx16& c, elemx8 a, elemx8 b) {
   asm volatile(AXONN_MFMA32_GAP AXONN_MFMA_32X32X16_ASM " %0, %1, %2, %0" : "+v"(c) : "v"(a), "a"(b));
