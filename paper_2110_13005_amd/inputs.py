@@ -90,12 +90,12 @@ def snap_fp16(a):
         return np.asarray(a, dtype=np.float32).astype(np.float16).astype(np.float32)
 
 
-# Element type of the library the process works with (AXONN_ELEM, as in binding.py): inputs are rounded to it.
+# Element type in use (AXONN_ELEM at import, then binding.select_elem): inputs are rounded to it.
 ELEM = os.environ.get("AXONN_ELEM", "bf16")
 
 
 def snap_elem(a):
-    """Round a float32 array to the 16-bit element type in use (bfloat16 unless AXONN_ELEM=fp16)."""
+    """Round a float32 array to the 16-bit element type in use (bfloat16 unless half precision is selected: AXONN_ELEM, binding.select_elem)."""
     return snap_fp16(a) if ELEM == "fp16" else snap_bf16(a)
 
 

@@ -1,44 +1,61 @@
-"""The half-precision build of the library (libaxonn_stage_fp16.so: the paper's arithmetic, Sec. 2 "Mixed
-precision") against the same fp64 oracle, to the same bounds as the bfloat16 build.
+"""The two builds of the library (bfloat16 and half precision, the paper's arithmetic: Sec. 2 "Mixed precision") in one
+process.
 
-A process works with one of the two builds (AXONN_ELEM, read when the binding is imported), so the parity tests of the
-single operations, of the stage, of the pipeline's ends and of loss scaling run again in a child process with
-AXONN_ELEM=fp16: inputs are then rounded to half precision, device buffers are torch.float16, and the oracle rounds the
-16-bit parameter copy to half precision."""
-import os
-import subprocess
-import sys
-
+The parity tests of the single operations, of the stage, of the pipeline's ends, of checkpointing and of loss scaling
+run once per element type (the `axonn_elem` parametrization in conftest.py).  What is left for this file: stages of
+both element types alive at the same time, their calls interleaved, each still giving its own library's result."""
+import numpy as np
 import pytest
+
+import oracle
+from paper_2110_13005_amd import binding as B
+from paper_2110_13005_amd.inputs import StageShape, make_stage_inputs
+from paper_2110_13005_amd.stage import Stage
+from helpers import dev_bf16, host, check_batch, EPS
 
 pytestmark = pytest.mark.gpu
 
-FP16_FILES = ["test_gpu_ops.py", "test_gpu_stage.py", "test_gpu_lm_ends.py", "test_gpu_loss_scaling.py",
-              "test_gpu_checkpointing.py", "test_gpu_pipeline.py"]
 
-
-@pytest.mark.skipif(os.environ.get("AXONN_ELEM", "bf16") != "bf16", reason="already the child process")
-@pytest.mark.timeout(1500)
-def test_half_precision_build_parity_suite():
-    here = os.path.dirname(os.path.abspath(__file__))
-    env = dict(os.environ, AXONN_ELEM="fp16")
-    r = subprocess.run([sys.executable, "-m", "pytest", *[os.path.join(here, f) for f in FP16_FILES], "-x", "-q",
-                        "-p", "no:cacheprovider", "-m", "gpu", "-k", "not copy_kernel"],
-                       env=env, capture_output=True, text=True, timeout=1400, cwd=os.path.dirname(here))
-    tail = r.stdout[-4000:] + r.stderr[-2000:]
-    assert r.returncode == 0, tail
-    assert " passed" in r.stdout and " failed" not in r.stdout, tail
-
-
-@pytest.mark.skipif(os.environ.get("AXONN_ELEM", "bf16") != "bf16", reason="already the child process")
-@pytest.mark.timeout(900)
-def test_half_precision_build_full_size_stage():
-    """The 12B-shape stage at full size, in the benchmark's launch configuration, with the half-precision build."""
-    here = os.path.dirname(os.path.abspath(__file__))
-    env = dict(os.environ, AXONN_ELEM="fp16")
-    r = subprocess.run([sys.executable, "-m", "pytest", os.path.join(here, "test_gpu_fullsize.py"), "-x", "-q",
-                        "-p", "no:cacheprovider", "-m", "gpu", "-k", "test_full_size_stage_parity and 12b-0 and not table1"],
-                       env=env, capture_output=True, text=True, timeout=800, cwd=os.path.dirname(here))
-    tail = r.stdout[-4000:] + r.stderr[-2000:]
-    assert r.returncode == 0, tail
-    assert "1 passed" in r.stdout, tail
+def test_stages_of_both_element_types_side_by_side():
+    import torch
+    sh = StageShape(2, 256, 4, 128, 2, 2)
+    M = sh.n_microbatches
+    before = B.ELEM
+    made = {}
+    try:
+        for elem in ("bf16", "fp16"):
+            B.select_elem(elem)
+            layers, xs, dys = make_stage_inputs(sh, seed=11, perturb=True)          # rounded to `elem`
+            st = Stage(sh)
+            st.load_params(layers)
+            X = [dev_bf16(x) for x in xs]
+            DY = [dev_bf16(d) for d in dys]
+            Y = [torch.zeros_like(X[0]) for _ in range(M)]
+            DX = [torch.zeros_like(X[0]) for _ in range(M)]
+            ref = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
+            made[elem] = (st, X, DY, Y, DX, ref)
+            assert B.axonn_element_type() == (1 if elem == "fp16" else 0)
+        assert made["bf16"][0].params.dtype == torch.bfloat16 and made["fp16"][0].params.dtype == torch.float16
+        # both batches with their calls interleaved, whichever type is selected: a handle goes to the library
+        # that created it
+        for pick, (st, *_rest) in zip(("fp16", "bf16"), made.values()):
+            B.select_elem(pick)
+            st.zero_grad()
+        for i in range(M):
+            for elem in ("bf16", "fp16"):
+                B.select_elem("fp16" if (i + (elem == "fp16")) % 2 else "bf16")
+                st, X, DY, Y, DX, _ = made[elem]
+                st.forward(i, X[i], Y[i])
+        for i in range(M):
+            for elem in ("fp16", "bf16"):
+                B.select_elem("bf16" if (i + (elem == "fp16")) % 2 else "fp16")
+                st, X, DY, Y, DX, _ = made[elem]
+                st.backward(i, DY[i], DX[i])
+        torch.cuda.synchronize()
+        for elem in ("bf16", "fp16"):
+            st, X, DY, Y, DX, ref = made[elem]
+            check_batch([host(y) for y in Y], [host(d) for d in DX], st.grads_numpy(), ref)
+    finally:
+        for st, *_ in made.values():
+            st.close()
+        B.select_elem(before)

@@ -201,11 +201,12 @@ def test_scaler_arguments_are_checked():
         B.axonn_pinned_free(p)
 
 
-@pytest.mark.skipif(B.ELEM != "fp16", reason="underflow of small gradients is a property of half precision")
 def test_loss_scale_rescues_small_gradients_in_half_precision():
     """Upstream gradients of size 1e-6: in half precision the backward pass loses them to underflow (activation
     gradients fall below 2^-24 in places, weight-gradient sums lose most of their bits); multiplied by 2^14 they
     come through within the gradient bound, and the descaled values are those of the oracle."""
+    if B.ELEM != "fp16":
+        pytest.skip("underflow of small gradients is a property of half precision")
     sh = CONFIGS["tiny"]
     layers, xs, dys = make_stage_inputs(sh, seed=9, perturb=True, dy_std=1.0)
     small = [(d * np.float32(1e-6)) for d in dys]
