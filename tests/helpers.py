@@ -61,8 +61,8 @@ def parity(got, ref, tol, c, axis=-1, label=""):
 
 
 def dev_bf16(a):
-    """float32 numpy array holding values of the library's 16-bit element type (bf16, or fp16 under
-    half precision is selected) -> cuda tensor of that type."""
+    """float32 numpy array holding values of the selected 16-bit element type (bfloat16 or half precision) -> cuda
+    tensor of that type."""
     import torch
     return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(B.torch_elem_dtype()).cuda()
 
