@@ -36,6 +36,34 @@ def test_half_precision_build_exports_the_same_symbols():
     assert lib.axonn_element_type() == 1 and B.load().axonn_element_type() == 0
 
 
+def test_binding_holds_both_builds_and_routes_by_selection():
+    """select_elem() switches the library that handle-free calls go to, the torch dtype and the rounding of the
+    synthetic inputs; both libraries stay loaded, and each keeps an error message of its own."""
+    import numpy as np
+    import torch
+    from paper_2110_13005_amd import inputs
+    before = B.ELEM
+    try:
+        B.select_elem("bf16")
+        lib_b = B.load()
+        assert B.axonn_element_type() == 0 and B.torch_elem_dtype() == torch.bfloat16
+        x = np.float32(1.0 + 2.0 ** -10)
+        assert inputs.snap_elem(np.array([x]))[0] == np.float32(1.0)            # bfloat16 keeps 8 bits
+        B.select_elem("fp16")
+        lib_h = B.load()
+        assert lib_h is not lib_b and B.load("bf16") is lib_b
+        assert B.axonn_element_type() == 1 and B.torch_elem_dtype() == torch.float16
+        assert inputs.snap_elem(np.array([x]))[0] == x                          # half precision keeps 11
+        with pytest.raises(B.AxonnError) as e:
+            B.axonn_tuning(99, 0)
+        assert e.value.status == B.AXONN_EINVAL and b"99" in lib_h.axonn_last_error()
+        assert b"99" not in lib_b.axonn_last_error()
+        with pytest.raises(ValueError):
+            B.select_elem("fp8")
+    finally:
+        B.select_elem(before)
+
+
 def test_argument_validation_without_device():
     lib = B.load()
     assert lib.axonn_stage_create(None, None) == B.AXONN_EINVAL
