@@ -153,19 +153,34 @@ __global__ __launch_bounds__(256) void colsum_partial_kernel(
 #pragma unroll
   for (int e = 0; e < 8; ++e) a0[e] = a1[e] = 0.f;
   if (col < N) {
-    for (int r = r_begin; r < r_begin + CS_ROWS / 4 && r < T; ++r) {
-      const elemx8 yv = *reinterpret_cast<const elemx8*>(y + (int64_t)r * ldy + col);
-      if (MODE == 1) {
-        const elemx8 xv = *reinterpret_cast<const elemx8*>(x + (int64_t)r * N + col);
-        const float mean = stats[2 * (int64_t)r], rstd = stats[2 * (int64_t)r + 1];
+    // the rows of a batch are all requested before the first is added: with one load in flight per lane every
+    // row costs a round trip to HBM
+    constexpr int QR = CS_ROWS / 4;
+    constexpr int HB = MODE == 1 ? 4 : 8;  // rows per batch of loads (two operands and the row statistics in mode 1)
+#pragma unroll
+    for (int i0 = 0; i0 < QR; i0 += HB) {
+      elemx8 yv[HB], xv[HB];
+      float mean[HB], rstd[HB];
+#pragma unroll
+      for (int i = 0; i < HB; ++i) {
+        // rows past the end re-read the last row and are left out of the sums below
+        const int r = min(r_begin + i0 + i, T - 1);
+        yv[i] = *reinterpret_cast<const elemx8*>(y + (int64_t)r * ldy + col);
+        if (MODE == 1) {
+          xv[i] = *reinterpret_cast<const elemx8*>(x + (int64_t)r * N + col);
+          mean[i] = stats[2 * (int64_t)r];
+          rstd[i] = stats[2 * (int64_t)r + 1];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < HB; ++i) {
+        const bool in_range = r_begin + i0 + i < T;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-          a0[e] += (float)yv[e];
-          a1[e] += (float)yv[e] * (((float)xv[e] - mean) * rstd);
+          const float v = in_range ? (float)yv[i][e] : 0.f;
+          a0[e] += v;
+          if (MODE == 1) a1[e] += v * (((float)xv[i][e] - mean[i]) * rstd[i]);
         }
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) a0[e] += (float)yv[e];
       }
     }
   }
