@@ -396,6 +396,19 @@ int axonn_gemm_bf16(int32_t a_kcontig, int32_t b_kcontig, int32_t epilogue,
                     const void* res, int64_t ld_res, void* aux, int64_t ld_aux,
                     int32_t accumulate, void* hip_stream);
 
+/* Weight gradient and bias gradient of a linear map in one call (Sec. 2: both are sums over the
+ * tokens of the microbatches, of x^T dy and of dy): axonn_gemm_bf16 with (a_kcontig, b_kcontig) =
+ * (0, 0) and epilogue 4 or 5, so C[M,N] (+)= sum_k A[k*lda + m] * B[k*ldb + n], and beside it
+ *   colsum[n] = (accumulate ? colsum[n] : 0) + sum_k B[k*ldb + n],   n < N,
+ * in C's element type (float32 for epilogue 4, bf16 for 5; sums in fp32, one rounding).  Problems of
+ * at least 128 tiles of 256 x 256 form the sums inside the GEMM kernel, from the tiles of B it
+ * multiplies (B is read once); smaller ones run axonn_colsum's kernels behind the GEMM.
+ * workspace_f32: ceil(K/64)*N floats, needed either way.  Sizes as for axonn_gemm_bf16. */
+int axonn_gemm_wgrad_colsum(int32_t epilogue, int64_t M, int64_t N, int64_t K,
+                            const void* A, int64_t lda, const void* B, int64_t ldb,
+                            void* C, int64_t ldc, void* colsum, float* workspace_f32,
+                            int32_t accumulate, void* hip_stream);
+
 /* Per-row LayerNorm over h (multiple of 8, <= 16384): out = g*(x-mean)*rstd + b, biased
  * variance, rstd = 1/sqrt(var+eps).  stats[T,2] float32 = (mean, rstd). */
 int axonn_layernorm_fwd(int64_t T, int64_t h, const void* x_bf16, const void* gamma_bf16,

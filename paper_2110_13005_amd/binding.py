@@ -116,6 +116,7 @@ _PROTOTYPES = {
     "axonn_head_set_loss_scale": [_vp, _f],
     "axonn_gemm_bf16": [_i32, _i32, _i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i64,
                         _vp, _i64, _i32, _vp],
+    "axonn_gemm_wgrad_colsum": [_i32, _i64, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _vp, _i32, _vp],
     "axonn_layernorm_fwd": [_i64, _i64, _vp, _vp, _vp, _f, _vp, _vp, _vp],
     "axonn_layernorm_bwd": [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
     "axonn_layernorm_bwd_noalloc": [_i64, _i64, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp],
@@ -460,6 +461,11 @@ def axonn_gemm_bf16(a_kcontig, b_kcontig, epilogue, M, N, K, A, lda, B, ldb, Cma
                     ld_res=0, aux=None, ld_aux=0, accumulate=0, stream=None):
     _call("axonn_gemm_bf16", a_kcontig, b_kcontig, epilogue, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(Cmat),
                                   ldc, _ptr(bias), _ptr(res), ld_res, _ptr(aux), ld_aux, accumulate, _stream(stream))
+
+
+def axonn_gemm_wgrad_colsum(epilogue, M, N, K, A, lda, B, ldb, Cmat, ldc, colsum, workspace, accumulate=0, stream=None):
+    _call("axonn_gemm_wgrad_colsum", epilogue, M, N, K, _ptr(A), lda, _ptr(B), ldb, _ptr(Cmat), ldc, _ptr(colsum),
+                                          _ptr(workspace), accumulate, _stream(stream))
 
 
 def axonn_layernorm_fwd(T, h, x, gamma, beta, eps, out, stats, stream=None):

@@ -367,33 +367,8 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_fwd_kernel(int s, i
 
 // ============================================================================ backward
 // delta[b][a][i] = sum_d dO[i][d] * O[i][d]
-template <int D>
-__global__ __launch_bounds__(256) void attn_delta_kernel(int64_t n_chunks, int s, int a,
-                                                         const elem_t* __restrict__ o,
-                                                         const elem_t* __restrict__ dout,
-                                                         float* __restrict__ delta) {
-  constexpr int LPR = D / 8;  // lanes per (row, head)
-  const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  float p = 0.f;
-  if (c < n_chunks) {
-    const elemx8 ov = *reinterpret_cast<const elemx8*>(o + c * 8);
-    const elemx8 dv = *reinterpret_cast<const elemx8*>(dout + c * 8);
-#pragma unroll
-    for (int e = 0; e < 8; ++e) p += (float)ov[e] * (float)dv[e];
-  }
-#pragma unroll
-  for (int off = LPR / 2; off > 0; off >>= 1) p += __shfl_xor(p, off, 64);
-  if (c < n_chunks && (c % LPR) == 0) {
-    const int64_t hc = a * (int64_t)LPR;  // chunks per row
-    const int64_t row = c / hc;
-    const int hd = (int)((c % hc) / LPR);
-    const int64_t bi = row / s, i = row % s;
-    delta[(bi * a + hd) * s + i] = p;
-  }
-}
-
-// The same for any head dimension d that is a multiple of 4: 16 lanes per (row, head), 4 elements per lane
-// and step.
+// For any head dimension d that is a multiple of 4: 16 lanes per (row, head), 4 elements per lane and step.
+// (Launched in front of the general kernels only: the exact-size dQ kernel forms delta itself.)
 __global__ __launch_bounds__(256) void attn_delta_general_kernel(int64_t n_pairs, int s, int a, int d,
                                                                  const elem_t* __restrict__ o,
                                                                  const elem_t* __restrict__ dout,
@@ -751,10 +726,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_kernel(
 
 // dQ: grid (ceil(s/128), b*a); wave w owns queries q0 + 32w .. +31 and walks the key tiles up
 // to the diagonal (same traversal as the forward kernel).
+// The exact-size kernels also form delta (above) for their 128 queries, from the rows of dO they stage anyway and
+// the same rows of O, and leave it in `delta` for the dK / dV kernel, which then has to run behind this one: no
+// launch of its own for it, and dO is read once less.  The general kernels read `delta` and ignore `o`.
 template <int D, bool EXACT>
 __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
-    int s, int a, int n_bh, int d_arg, const elem_t* __restrict__ qkv, const elem_t* __restrict__ dout,
-    const float* __restrict__ lse, const float* __restrict__ delta, elem_t* __restrict__ dqkv) {
+    int s, int a, int n_bh, int d_arg, const elem_t* __restrict__ qkv, const elem_t* __restrict__ o,
+    const elem_t* __restrict__ dout, const float* __restrict__ lse, float* __restrict__ delta,
+    elem_t* __restrict__ dqkv) {
   constexpr int BKV = 64, LDK = BothWaysStride<D>::LD, DT = D / 32, KK = D / 16;
   __shared__ __align__(16) elem_t smem[2 * BKV * LDK];          // K and V tile; at the ends the staged Q, dO and dQ rows
   static_assert(2 * BKV * LDK >= 128 * (D + 8), "the workgroup's 128 rows fit the tile buffers");
@@ -775,20 +754,45 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
   const int q0 = qt * 128, qw0 = q0 + 32 * wave, qi = qw0 + (lane & 31);
   const float scale = rsqrtf((float)d), scale_log2 = kLog2e * scale;
   const float lse_q = (qi < s) ? lse[((int64_t)bi * a + hd) * s + qi] * kLog2e : 0.f;
-  const float delta_q = (qi < s) ? delta[((int64_t)bi * a + hd) * s + qi] : 0.f;
+  float delta_q;
+  __shared__ float s_delta[128];
 
   elemx8 qf[KK], dof[KK];
   if (EXACT) {
+    // dO and O rows of the workgroup's queries, chunk for chunk in the same registers of the same threads: the
+    // D / 8 lanes that hold a row's chunks add up its products
+    using Rows = TileRegs<128, D>;
+    constexpr int LPR = D / 8, RSTEP = 256 / LPR;
+    const uint32_t o_bytes = (uint32_t)(((int64_t)(s - 1) * h + D) * 2), o_off0 = Rows::offset0((uint32_t)h * 2u, tid);
+    Rows r_do, r_o;
+    r_do.load_buffer(make_rsrc(dob, o_bytes), o_off0, (uint32_t)h * 2u, q0);
+    r_o.load_buffer(make_rsrc(o + (int64_t)bi * s * h + hd * d, o_bytes), o_off0, (uint32_t)h * 2u, q0);
     stage_rows_in<D, D + 8>(smem, make_rsrc(qb, (uint32_t)(((int64_t)(s - 1) * ld + D) * 2)), (uint32_t)ld * 2u, q0, tid);
     __syncthreads();
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qf[kk] = frag_kcontig(smem + (32 * wave) * (D + 8) + kk * 16, D + 8, lane);
     __syncthreads();
-    stage_rows_in<D, D + 8>(smem, make_rsrc(dob, (uint32_t)(((int64_t)(s - 1) * h + D) * 2)), (uint32_t)h * 2u, q0, tid);
+    r_do.template store<D + 8>(smem, tid);
+#pragma unroll
+    for (int j = 0; j < Rows::NCH; ++j) {
+      const elemx8 ov = __builtin_bit_cast(elemx8, r_o.r[j]), dv = __builtin_bit_cast(elemx8, r_do.r[j]);
+      float p = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) p += (float)ov[e] * (float)dv[e];
+#pragma unroll
+      for (int off = LPR / 2; off > 0; off >>= 1) p += __shfl_xor(p, off, 64);
+      const int row = tid / LPR + j * RSTEP;
+      if (tid % LPR == 0) {
+        s_delta[row] = p;
+        if (q0 + row < s) delta[((int64_t)bi * a + hd) * s + q0 + row] = p;
+      }
+    }
     __syncthreads();
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) dof[kk] = frag_kcontig(smem + (32 * wave) * (D + 8) + kk * 16, D + 8, lane);
+    delta_q = s_delta[32 * wave + (lane & 31)];
   } else {
+    delta_q = (qi < s) ? delta[((int64_t)bi * a + hd) * s + qi] : 0.f;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       qf[kk] = global_frag<EXACT>(qb, ld, qi, s, kk * 16, lane, d);
@@ -909,25 +913,26 @@ hipError_t launch_attention_bwd(int b, int s, int a, int d, const void* qkv, con
                                 const float* lse, const void* dout, void* dqkv, float* delta,
                                 hipStream_t st) {
   if (!head_dim_supported(d)) return hipErrorInvalidValue;
-  if (d == 64 || d == 128) {
-    const int64_t n_chunks = (int64_t)b * s * a * d / 8;
-    const dim3 gd((unsigned)((n_chunks + 255) / 256));
-    if (d == 128)
-      hipLaunchKernelGGL(attn_delta_kernel<128>, gd, dim3(256), 0, st, n_chunks, s, a, (const elem_t*)o, (const elem_t*)dout, delta);
-    else
-      hipLaunchKernelGGL(attn_delta_kernel<64>, gd, dim3(256), 0, st, n_chunks, s, a, (const elem_t*)o, (const elem_t*)dout, delta);
-  } else {
-    const int64_t n_pairs = (int64_t)b * s * a;
-    hipLaunchKernelGGL(attn_delta_general_kernel, dim3((unsigned)((n_pairs + 15) / 16)), dim3(256), 0, st, n_pairs, s, a, d,
-                       (const elem_t*)o, (const elem_t*)dout, delta);
-  }
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
   const dim3 grid((unsigned)(((s + 127) / 128) * b * a));
+  // the exact-size dQ kernel (the dispatch's condition for it) forms delta itself and runs first
+  const bool dq_forms_delta = (d == 64 || d == 128) && ((int64_t)s + 256) * 3 * a * d * 2 < (int64_t(1) << 31);
+  hipError_t e;
+  if (dq_forms_delta) {
+    AXONN_ATTN_DISPATCH(attn_bwd_dq_kernel, s, a, b * a, d, (const elem_t*)qkv, (const elem_t*)o, (const elem_t*)dout, lse, delta, (elem_t*)dqkv);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    AXONN_ATTN_DISPATCH(attn_bwd_dkdv_kernel, s, a, b * a, d, (const elem_t*)qkv, (const elem_t*)dout, lse, (const float*)delta, (elem_t*)dqkv);
+    return hipGetLastError();
+  }
+  const int64_t n_pairs = (int64_t)b * s * a;
+  hipLaunchKernelGGL(attn_delta_general_kernel, dim3((unsigned)((n_pairs + 15) / 16)), dim3(256), 0, st, n_pairs, s, a, d,
+                     (const elem_t*)o, (const elem_t*)dout, delta);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
   AXONN_ATTN_DISPATCH(attn_bwd_dkdv_kernel, s, a, b * a, d, (const elem_t*)qkv, (const elem_t*)dout, lse, (const float*)delta, (elem_t*)dqkv);
   e = hipGetLastError();
   if (e != hipSuccess) return e;
-  AXONN_ATTN_DISPATCH(attn_bwd_dq_kernel, s, a, b * a, d, (const elem_t*)qkv, (const elem_t*)dout, lse, (const float*)delta, (elem_t*)dqkv);
+  AXONN_ATTN_DISPATCH(attn_bwd_dq_kernel, s, a, b * a, d, (const elem_t*)qkv, (const elem_t*)o, (const elem_t*)dout, lse, delta, (elem_t*)dqkv);
   return hipGetLastError();
 }
 #undef AXONN_ATTN_DISPATCH

@@ -219,6 +219,12 @@ struct GemmArgs {
   int concurrent;    // other kernels share the chip with this launch: prefer the most efficient tile shape
                      // over one whose tile count fills the CUs a whole number of times
   int tiles_m, tiles_n;
+  // Weight gradients (both operands k-strided, accumulating epilogues) only: if colsum is not null, the sums
+  // over k (all segments) of B's N columns are stored in colsum[0..N), or added to it if `accumulate`; colsum
+  // has C's element type.  The large-problem kernels form them on the way; for the others colsum_ws must hold
+  // ceil(K/64) * N floats of workspace.
+  void* colsum;
+  float* colsum_ws;
 };
 
 // All return hipError_t of the launch (hipGetLastError) and validate nothing: callers check.

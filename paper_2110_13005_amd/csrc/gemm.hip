@@ -16,6 +16,7 @@
 // stores are 8-byte (bf16) or 16-byte (fp32) vectors along the contiguous dimension of C.
 #include "common.h"
 #include <atomic>
+#include <type_traits>
 
 namespace axonn {
 
@@ -439,6 +440,54 @@ __global__ __launch_bounds__(WGM* WGN * 64) void gemm_kernel(const GemmArgs g) {
   gemm_epilogue<EPI, TM, TN>(acc, g, m0 + wm * WTM, n0 + wn * WTN, lane);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Column sums of B beside a weight gradient.  The bias gradient of a linear map is the column sum of the same
+// dy whose product with x^T is the weight gradient (Sec. 2: both are sums over the tokens of the microbatches),
+// and the tiles of dy pass through the registers of the weight-gradient kernel anyway: the workgroups of tile
+// row 0 (one per block of columns) add up their B fragments as they multiply them, so dy is not read from
+// memory a second time.  A B fragment of the 16x16x32 MFMA holds, in lane l, 8 consecutive k of column l % 16;
+// the sum over its elements, then over the four lanes that share the column, then over all k-steps is the
+// column sum over every segment of the launch.  One wave per column half (wm == 0) does it, one pair of
+// elements behind each of the first 4*TN MFMAs of a phase (the fragment that MFMA has just used), in a copy of
+// the k loop of its own, so that the other waves' loop carries nothing of it.  The summing workgroup of column
+// block tn is the one of tile row tn * tiles_m / tiles_n: the extra work is then spread evenly over the launch
+// order, and with it over the XCDs (all in tile row 0 it made the XCD of the first band finish last: 20 us per
+// launch of the 12B-shape weight gradients).
+// Adds elements 2*pair and 2*pair + 1 of a B fragment to the lane's partial sum.
+__device__ __forceinline__ void colsum_pair(float& cs, const elemx8& fb, int pair) {
+#ifdef AXONN_ELEM_FP16
+  cs += (float)fb[2 * pair] + (float)fb[2 * pair + 1];
+#else
+  const elemx2 ones = {(elem_t)1.0f, (elem_t)1.0f};
+  const elemx2 two = {fb[2 * pair], fb[2 * pair + 1]};
+  cs = __builtin_amdgcn_fdot2_f32_bf16(two, ones, cs, false);   // fp32 sum of the two and cs
+#endif
+}
+// Stores (or, for an accumulating launch, adds) the sums of the wave's 16*TN columns from n_base on to
+// g.colsum, which has the element type of C.
+template <int EPI, int TN>
+__device__ __forceinline__ void colsum_store(const float (&cs)[TN], const GemmArgs& g, int n_base, int lane) {
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    float v = cs[j];
+    v += __shfl_xor(v, 16);
+    v += __shfl_xor(v, 32);
+    const int n = n_base + 16 * j + lane;
+    if (lane < 16 && n < g.N) {
+      if (EPI == EPI_ACC_F32) {
+        float* o = reinterpret_cast<float*>(g.colsum) + n;
+        *o = g.accumulate ? *o + v : v;
+      } else {
+        elem_t* o = reinterpret_cast<elem_t*>(g.colsum) + n;
+        *o = (elem_t)(g.accumulate ? (float)*o + v : v);
+      }
+    }
+  }
+}
+constexpr bool epilogue_sums_columns(bool a_kc, bool b_kc, int e) {
+  return !a_kc && !b_kc && (e == EPI_ACC_F32 || e == EPI_ACC_BF16);
+}
+
 // ------------------------------------------------------------------------------------------
 // Large-problem kernel: 256 x (32*TN) x 64 block tile, 4 waves (2 x 2), wave tile 128 x 16*TN = 8 x TN
 // tiles of the 16x16x32 MFMA held in accumulation registers (all 256 of them for TN = 8), so that each
@@ -561,7 +610,8 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
     fb[F][j] = B_KC ? frag16_kcontig(sB(buf) + r0 * LB::LD + (kk) * 32, LB::LD, lane)          \
                     : frag16_kstrided(sB(buf) + ((kk) * 32) * LB::LD + r0, LB::LD, lane);      \
   }
-#define AXONN_MFMA(F, q) mfma16_acc(acc[(q) / TN][(q) % TN], fb[F][(q) % TN], fa[F][(q) / TN]);
+#define AXONN_CS(F, q) if (CSL && (q) < 4 * TN) colsum_pair(cs[(q) % TN], fb[F][(q) % TN], (q) / TN);
+#define AXONN_MFMA(F, q) mfma16_acc(acc[(q) / TN][(q) % TN], fb[F][(q) % TN], fa[F][(q) / TN]); AXONN_CS(F, q)
   // One k-step on the tile kt in buffer CUR: two phases of NM MFMAs (k slices 0 and 1), between which
   // the other memory instructions are spread as evenly as their dependences allow, so that neither the
   // LDS nor the issue port sees bursts:
@@ -604,6 +654,12 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
   elemx8 fa[2][TM], fb[2][TN];
+  constexpr bool CS = epilogue_sums_columns(A_KC, B_KC, EPI);
+  const bool cs_on = CS && g.colsum != nullptr && wm == 0 &&              // the same for all lanes of a wave
+                     tm == (int)((int64_t)tn * g.tiles_m / g.tiles_n);
+  float cs[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) cs[j] = 0.f;
 
   // prologue: tile 0 in buffer 0; the A chunks of tile 1 in buffer 1 and its B chunks in registers;
   // the A chunks of tile 2 on their way (tiles that do not exist read as zeros)
@@ -634,10 +690,14 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
   asm volatile("s_nop 7" ::: "memory");      // accumulators were just zeroed: settle before the first MFMA
   // two k-steps per iteration so that the buffer index is a constant; an odd tile count is padded
   // with a tile of zeros
-  for (int kt = 0; kt < nk; kt += 2) {
-    AXONN_KSTEP(0)
-    AXONN_KSTEP(1)
-  }
+  auto k_loop = [&](auto with_colsum) {
+    constexpr bool CSL = decltype(with_colsum)::value;
+    for (int kt = 0; kt < nk; kt += 2) {
+      AXONN_KSTEP(0)
+      AXONN_KSTEP(1)
+    }
+  };
+  if (CS && cs_on) k_loop(std::true_type{}); else k_loop(std::false_type{});
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // last MFMAs drain before the results are read
 #undef AXONN_GLOAD_BEGIN
 #undef AXONN_LOAD_A
@@ -647,11 +707,13 @@ __global__ __launch_bounds__(256) void gemm_big_kernel(const GemmArgs g) {
 #undef AXONN_STORE_B
 #undef AXONN_FRAG
 #undef AXONN_MFMA
+#undef AXONN_CS
 #undef AXONN_KSTEP
 
   lds_barrier();                                          // every wave is done with the tiles in LDS
   gemm_epilogue_staged<EPI, TN>(acc, g, m0 + wm * 128, n0 + wn * (16 * TN), lane,
                                 reinterpret_cast<float*>(smem) + wave * StageLayout<TN>::FLOATS_PER_WAVE);
+  if (CS) { if (cs_on) colsum_store<EPI, TN>(cs, g, n0 + wn * (16 * TN), lane); }
 #undef sA
 #undef sB
 }
@@ -899,7 +961,8 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
       fb[F][j] = u.v;                                                                          \
     }                                                                                          \
   }
-#define AXONN_MFMA(F, q) mfma16_acc(acc[(q) / TN][(q) % TN], fb[F][(q) % TN], fa[F][(q) / TN]);
+#define AXONN_CS(F, q) if (CSL && (q) < 4 * TN) colsum_pair(cs[(q) % TN], fb[F][(q) % TN], (q) / TN);
+#define AXONN_MFMA(F, q) mfma16_acc(acc[(q) / TN][(q) % TN], fb[F][(q) % TN], fa[F][(q) / TN]); AXONN_CS(F, q)
   // One phase: multiplies the fragments of set FMUL; reads k slice RDKK of stage RDBUF into set FRD and
   // issues the copies of phase PH of the next tile to fetch into stage DMABUF.  Phase 0 of a problem without a
   // k-strided operand has no copies, no wait and no barrier.
@@ -915,6 +978,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
       const int dd = item_at(q, (PH) == 0 ? N0 : N1, 7, NM - 8);                                 \
       if (dd >= 0) {                                                                             \
         AXONN_MFMA_DMA(FMUL, q, DMABUF, dma_item(A_KC, B_KC, NCA, NCB, PH, dd))                  \
+        AXONN_CS(FMUL, q)                                                                        \
       } else {                                                                                   \
         AXONN_MFMA(FMUL, q)                                                                      \
       }                                                                                          \
@@ -946,6 +1010,12 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) acc[i][j][r] = 0.f;
   elemx8 fa[2][TM], fb[2][TN];
+  constexpr bool CS = epilogue_sums_columns(A_KC, B_KC, EPI);
+  const bool cs_on = CS && g.colsum != nullptr && wm == 0 &&              // the same for all lanes of a wave
+                     tm == (int)((int64_t)tn * g.tiles_m / g.tiles_n);
+  float cs[TN];
+#pragma unroll
+  for (int j = 0; j < TN; ++j) cs[j] = 0.f;
 
   // prologue: tiles 0 and 1 into stages 0 and 1, in the order of the loop
 #pragma unroll
@@ -966,10 +1036,14 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
     for (int e = 0; e < 4; ++e) { AXONN_FRAG(1, 0, 1, e == 0 ? 0 : TN + e) }
   }
   asm volatile("s_nop 7" ::: "memory");      // accumulators were just zeroed: settle before the first MFMA
-  for (int kt = 0; kt < nk; kt += 2) {
-    AXONN_KSTEP(0)
-    AXONN_KSTEP(1)
-  }
+  auto k_loop = [&](auto with_colsum) {
+    constexpr bool CSL = decltype(with_colsum)::value;
+    for (int kt = 0; kt < nk; kt += 2) {
+      AXONN_KSTEP(0)
+      AXONN_KSTEP(1)
+    }
+  };
+  if (CS && cs_on) k_loop(std::true_type{}); else k_loop(std::false_type{});
   dma_wait_all();                            // copies of tiles past the end still write (zeros) to LDS
   asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");   // last MFMAs drain before the results are read
 #undef AXONN_DMA
@@ -978,11 +1052,13 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(const GemmArgs g) {
 #undef AXONN_DMA_NEXT
 #undef AXONN_FRAG
 #undef AXONN_MFMA
+#undef AXONN_CS
 #undef AXONN_KSTEP
 
   lds_barrier();                                          // every wave is done with the tiles in LDS
   gemm_epilogue_staged<EPI, TN>(acc, g, m0 + wm * 128, n0 + wn * (16 * TN), lane,
                                 reinterpret_cast<float*>(smem) + wave * StageLayout<TN>::FLOATS_PER_WAVE);
+  if (CS) { if (cs_on) colsum_store<EPI, TN>(cs, g, n0 + wn * (16 * TN), lane); }
 }
 
 // Only the (layout, epilogue) pairs the layer uses are instantiated: forward maps take the
@@ -992,6 +1068,19 @@ constexpr bool epilogue_allowed(bool a_kc, bool b_kc, int e) {
   if (a_kc && b_kc) return e == EPI_BIAS || e == EPI_DGELU;
   if (!a_kc && !b_kc) return e == EPI_ACC_F32 || e == EPI_ACC_BF16;
   return false;
+}
+
+// The column sums a launch asks for (g.colsum) by the stand-alone kernels, segment by segment: for the kernels
+// that do not form them on the way.  g.colsum_ws: what launch_colsum needs for K rows of N columns.
+static hipError_t colsum_separately(int epi, const GemmArgs& g, hipStream_t s) {
+  if (!g.colsum) return hipSuccess;
+  if (!g.colsum_ws || !(epi == EPI_ACC_F32 || epi == EPI_ACC_BF16)) return hipErrorInvalidValue;
+  for (int i = 0; i < g.n_seg; ++i) {
+    const hipError_t e = launch_colsum(g.K, g.N, g.B_seg[i], g.ldb, g.colsum, (g.accumulate || i > 0) ? 2 : 1,
+                                       epi == EPI_ACC_F32, g.colsum_ws, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 template <int BM, int BN, int BK, int WGM, int WGN, bool A_KC, bool B_KC>
@@ -1017,7 +1106,8 @@ static hipError_t launch_cfg(int epi, GemmArgs g, hipStream_t s) {
     default: return hipErrorInvalidValue;
   }
 #undef AXONN_GEMM_CASE
-  return hipGetLastError();
+  const hipError_t e = hipGetLastError();
+  return e != hipSuccess ? e : colsum_separately(epi, g, s);   // these kernels leave the column sums to others
 }
 
 // Launcher settings that axonn_tuning() can change (process-wide; -1 = the built-in rule).
@@ -1072,7 +1162,7 @@ static hipError_t launch_big(int epi, GemmArgs g, hipStream_t s) {
     default: return hipErrorInvalidValue;
   }
 #undef AXONN_GEMM_CASE
-  return hipGetLastError();
+  return hipGetLastError();          // both kernels form the column sums of a weight gradient themselves
 }
 
 // The large-problem kernel addresses an operand with 32-bit byte offsets from the segment base.

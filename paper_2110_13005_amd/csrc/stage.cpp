@@ -195,7 +195,7 @@ struct axonn_stage {
   char* ws_base = nullptr;
   uint64_t ws_bytes = 0;
   elem_t *dw = nullptr, *dattn = nullptr, *du = nullptr;
-  float *delta = nullptr, *red_ws = nullptr;
+  float *delta = nullptr, *red_ws = nullptr, *wgrad_red_ws = nullptr;
   // activation checkpointing: shared activation sets (empty when cfg.ckpt_stride == 0)
   std::vector<ActSet> fwd_sets, regen_sets;
   unsigned fwd_set_rr = 0, regen_rr = 0;
@@ -275,12 +275,6 @@ int ln_bwd(axonn_stage* st, int layer, int which_g, int which_b, int64_t T, int6
   return check_launch(launch_layernorm_bwd(T, h, dout, x, stats, g, res, dx, grad_ptr(st, layer, which_g),
                                            grad_ptr(st, layer, which_b), acc ? 2 : 1,
                                            st->cfg.grad_accum_fp32 != 0, st->red_ws, s), "layernorm_bwd");
-}
-int bias_grad(axonn_stage* st, int layer, int which, int64_t T, int64_t N, const void* y, int64_t ldy, int acc,
-              hipStream_t s) {
-  ProfScope ps(PC_COLSUM, s);
-  return check_launch(launch_colsum(T, N, y, ldy, grad_ptr(st, layer, which), acc ? 2 : 1,
-                                    st->cfg.grad_accum_fp32 != 0, st->red_ws, s), "colsum");
 }
 int attn_fwd(int b, int sq, int a, int d, const void* qkv, void* o, float* lse, hipStream_t s) {
   ProfScope ps(PC_ATTN_FWD, s);
@@ -367,32 +361,29 @@ int forward_layers_ckpt(axonn_stage* st, Slot& slot, void* y_out, hipStream_t s)
 
 // ------------------------------------------------------------------ backward of a layer
 // Given dL/d(output) in a.dz, writes dL/d(input) to d_out, the output gradients of the four linear maps
-// to a.dpre, a.dy_mid, a.dqkv (a.dz is the fourth) and adds the bias / LayerNorm gradients.
+// to a.dpre, a.dy_mid, a.dqkv (a.dz is the fourth) and adds the LayerNorm gradients.  The bias gradients, column
+// sums of those four, are left to the weight-gradient pass, which reads the same four matrices.
 int backward_layer(axonn_stage* st, int l, const LayerStash& a, elem_t* d_out, int acc, hipStream_t s) {
   const int T = st->T, h = st->h, f = st->f;
   const elem_t* d_in = a.dz;
   // z = y + g W2 + b2
   AX_TRY(gemm(true, true, EPI_DGELU, T, f, h, d_in, h, param_ptr(st, l, P_WFC2), h, a.dpre, f,
               nullptr, nullptr, 0, a.pre, f, 0, s));
-  AX_TRY(bias_grad(st, l, P_BFC2, T, h, d_in, h, acc, s));
   // pre = w W1 + b1
   AX_TRY(gemm(true, true, EPI_BIAS, T, h, f, a.dpre, f, param_ptr(st, l, P_WFC1), f, st->dw, h,
               nullptr, nullptr, 0, nullptr, 0, 0, s));
-  AX_TRY(bias_grad(st, l, P_BFC1, T, f, a.dpre, f, acc, s));
   // w = LN2(y); residual: dy = d_in + dLN2
   AX_TRY(ln_bwd(st, l, P_LN2G, P_LN2B, T, h, st->dw, a.y, a.stats2, param_ptr(st, l, P_LN2G), d_in, a.dy_mid,
                 acc, s));
   // y = x + o Wo + bo
   AX_TRY(gemm(true, true, EPI_BIAS, T, h, h, a.dy_mid, h, param_ptr(st, l, P_WO), h, st->dattn, h,
               nullptr, nullptr, 0, nullptr, 0, 0, s));
-  AX_TRY(bias_grad(st, l, P_BO, T, h, a.dy_mid, h, acc, s));
   // attention
   AX_TRY(attn_bwd(st->cfg.microbatch_size, st->cfg.seq_len, st->cfg.n_heads, st->d, a.qkv, a.o, a.lse, st->dattn,
                   a.dqkv, st->delta, s));
   // qkv = u Wqkv + b
   AX_TRY(gemm(true, true, EPI_BIAS, T, h, 3 * h, a.dqkv, 3 * h, param_ptr(st, l, P_WQKV), 3 * h, st->du, h,
               nullptr, nullptr, 0, nullptr, 0, 0, s));
-  AX_TRY(bias_grad(st, l, P_BQKV, T, 3 * h, a.dqkv, 3 * h, acc, s));
   // u = LN1(x); residual: dx = dy + dLN1
   AX_TRY(ln_bwd(st, l, P_LN1G, P_LN1B, T, h, st->du, a.x, a.stats1, param_ptr(st, l, P_LN1G), a.dy_mid, d_out,
                 acc, s));
@@ -420,30 +411,35 @@ int backward_layers(axonn_stage* st, Slot& slot, const void* dy_in, void* dx_out
 // contraction index): dW = sum_mb x_mb^T dy_mb.  Runs on `s` after the chains it reads and after
 // the previous such pass (they update the same accumulators), then releases the slots.
 int gemm_seg(int epi, int M, int N, int K, const elem_t* const* A, int64_t lda, const elem_t* const* B,
-             int64_t ldb, int n_seg, void* C, int64_t ldc, int accumulate, hipStream_t s) {
+             int64_t ldb, int n_seg, void* C, int64_t ldc, void* colsum, float* colsum_ws, int accumulate,
+             hipStream_t s) {
   GemmArgs g;
   memset(&g, 0, sizeof g);
   for (int i = 0; i < n_seg; ++i) { g.A_seg[i] = A[i]; g.B_seg[i] = B[i]; }
   g.n_seg = n_seg; g.C = C; g.lda = lda; g.ldb = ldb; g.ldc = ldc;
   g.M = M; g.N = N; g.K = K; g.accumulate = accumulate;
+  g.colsum = colsum; g.colsum_ws = colsum_ws;
   g.concurrent = t_concurrent;
   ProfScope ps(PC_GEMM_WGRAD, s);
   return check_launch(launch_gemm(false, false, epi, g, s), "gemm (weight gradient)");
 }
 
-// dW += sum_i in_i^T dout_i for the four weights of layer l over n activation records
+// dW += sum_i in_i^T dout_i for the four weights of layer l over n activation records, and with each the bias
+// gradient db += sum_i (column sums of dout_i), formed by the same launch
 int wgrad_layer(axonn_stage* st, int l, const LayerStash* const* rec, int n, int acc, hipStream_t s) {
   const int T = st->T, h = st->h, f = st->f;
   const int epi = st->cfg.grad_accum_fp32 ? EPI_ACC_F32 : EPI_ACC_BF16;
+  float* const cws = st->wgrad_red_ws;
   const elem_t *A[kMaxKSegments], *B[kMaxKSegments];
   for (int i = 0; i < n; ++i) { A[i] = rec[i]->g; B[i] = rec[i]->dz; }
-  AX_TRY(gemm_seg(epi, f, h, T, A, f, B, h, n, grad_ptr(st, l, P_WFC2), h, acc, s));
+  AX_TRY(gemm_seg(epi, f, h, T, A, f, B, h, n, grad_ptr(st, l, P_WFC2), h, grad_ptr(st, l, P_BFC2), cws, acc, s));
   for (int i = 0; i < n; ++i) { A[i] = rec[i]->w; B[i] = rec[i]->dpre; }
-  AX_TRY(gemm_seg(epi, h, f, T, A, h, B, f, n, grad_ptr(st, l, P_WFC1), f, acc, s));
+  AX_TRY(gemm_seg(epi, h, f, T, A, h, B, f, n, grad_ptr(st, l, P_WFC1), f, grad_ptr(st, l, P_BFC1), cws, acc, s));
   for (int i = 0; i < n; ++i) { A[i] = rec[i]->o; B[i] = rec[i]->dy_mid; }
-  AX_TRY(gemm_seg(epi, h, h, T, A, h, B, h, n, grad_ptr(st, l, P_WO), h, acc, s));
+  AX_TRY(gemm_seg(epi, h, h, T, A, h, B, h, n, grad_ptr(st, l, P_WO), h, grad_ptr(st, l, P_BO), cws, acc, s));
   for (int i = 0; i < n; ++i) { A[i] = rec[i]->u; B[i] = rec[i]->dqkv; }
-  AX_TRY(gemm_seg(epi, h, 3 * h, T, A, h, B, 3 * h, n, grad_ptr(st, l, P_WQKV), 3 * h, acc, s));
+  AX_TRY(gemm_seg(epi, h, 3 * h, T, A, h, B, 3 * h, n, grad_ptr(st, l, P_WQKV), 3 * h, grad_ptr(st, l, P_BQKV), cws,
+                  acc, s));
   return AXONN_OK;
 }
 
@@ -774,7 +770,7 @@ int head_forward_backward(axonn_head* hd, const void* x, const int32_t* targets,
   {
     const elem_t* A[1] = {hd->a};
     const elem_t* B[1] = {hd->logits};
-    AX_TRY(gemm_seg(EPI_ACC_BF16, h, V, T, A, h, B, V, 1, hd->grads + 2 * (uint64_t)h, V, acc, s));
+    AX_TRY(gemm_seg(EPI_ACC_BF16, h, V, T, A, h, B, V, 1, hd->grads + 2 * (uint64_t)h, V, nullptr, nullptr, acc, s));
   }
   AX_TRY(gemm(true, true, EPI_BIAS, T, h, V, hd->logits, V, W, V, hd->da, h, nullptr, nullptr, 0, nullptr, 0, 0, s));
   {
@@ -920,13 +916,17 @@ int axonn_stage_create(const axonn_stage_config* cfg, axonn_stage_t** out) {
   }
   // backward workspace
   const int64_t wide = std::max<int64_t>(f, 3 * h);
-  const uint64_t e_red = align_up((uint64_t)2 * ((T + 63) / 64) * wide * 4, 256);
-  st->ws_bytes = 3 * e_th + e_lse + e_red;
+  // partial column sums: of the LayerNorm parameter gradients (gradient chain), and of the bias gradients where
+  // a weight-gradient kernel does not form them itself (weight-gradient stream): one area each
+  const uint64_t e_red = align_up((uint64_t)2 * ((T + 63) / 64) * h * 4, 256);
+  const uint64_t e_wred = align_up((uint64_t)2 * ((T + 63) / 64) * wide * 4, 256);
+  st->ws_bytes = 3 * e_th + e_lse + e_red + e_wred;
   CREATE_TRY(hipMalloc((void**)&st->ws_base, st->ws_bytes));
   {
     char* p = st->ws_base;
     st->dw = (elem_t*)p; p += e_th; st->dattn = (elem_t*)p; p += e_th; st->du = (elem_t*)p; p += e_th;
     st->delta = (float*)p; p += e_lse; st->red_ws = (float*)p; p += e_red;
+    st->wgrad_red_ws = (float*)p; p += e_wred;
   }
   CREATE_TRY(hipEventCreateWithFlags(&st->last_bwd, hipEventDisableTiming));
   CREATE_TRY(hipEventCreateWithFlags(&st->last_wgrad, hipEventDisableTiming));
@@ -1749,6 +1749,23 @@ int axonn_gemm_bf16(int32_t a_kcontig, int32_t b_kcontig, int32_t epilogue, int6
   if ((epilogue == 2 || epilogue == 3) && (!aux || ld_aux < N || ld_aux % 8)) return fail(AXONN_EINVAL, "gemm: epilogue %d needs aux with ld_aux >= N, multiple of 8", epilogue);
   return gemm(akc, bkc, epilogue, (int)M, (int)N, (int)K, A, lda, B, ldb, C, ldc, bias, res, ld_res, aux, ld_aux,
               accumulate, (hipStream_t)hip_stream);
+}
+
+int axonn_gemm_wgrad_colsum(int32_t epilogue, int64_t M, int64_t N, int64_t K, const void* A, int64_t lda,
+                            const void* B, int64_t ldb, void* C, int64_t ldc, void* colsum, float* workspace,
+                            int32_t accumulate, void* hip_stream) {
+  if (!A || !B || !C || !colsum || !workspace) return fail(AXONN_EINVAL, "gemm_wgrad_colsum: null argument");
+  if (M < 1 || N < 1 || K < 1) return fail(AXONN_EINVAL, "gemm_wgrad_colsum: non-positive size");
+  if (M > (1 << 24) || N > (1 << 24) || K > (1 << 24))
+    return fail(AXONN_EUNSUPPORTED, "gemm_wgrad_colsum: dimension above 2^24");
+  if ((M | N | K | lda | ldb | ldc) % 8)
+    return fail(AXONN_EUNSUPPORTED, "gemm_wgrad_colsum: M, N, K and leading dimensions must be multiples of 8");
+  if (epilogue != 4 && epilogue != 5) return fail(AXONN_EINVAL, "gemm_wgrad_colsum: epilogue must be 4 or 5 (got %d)", epilogue);
+  if (lda < M || ldb < N || ldc < N) return fail(AXONN_EINVAL, "gemm_wgrad_colsum: leading dimension too small");
+  const elem_t* a1[1] = {(const elem_t*)A};
+  const elem_t* b1[1] = {(const elem_t*)B};
+  return gemm_seg(epilogue, (int)M, (int)N, (int)K, a1, lda, b1, ldb, 1, C, ldc, colsum, workspace, accumulate,
+                  (hipStream_t)hip_stream);
 }
 
 int axonn_layernorm_fwd(int64_t T, int64_t h, const void* x, const void* gamma, const void* beta, float eps,

@@ -113,6 +113,41 @@ def test_gemm_wgrad_layout_accumulate(M, N, K):
     parity(host(c16), first + ref, TOL, C_ONE, label="gemm_wgrad_layout_accumulate")
 
 
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_wgrad_with_bias_gradient(M, N, K):
+    """dW = x^T dy and db = the column sums of dy from one call (the large-problem kernels form db from the tiles of
+    dy they multiply, the others run the column-sum kernels behind the GEMM): stored, then accumulated, in fp32 and
+    in 16-bit accumulators; dy with a leading dimension beyond N, whose padding must stay out of the sums."""
+    import torch
+    rng = np.random.default_rng(M + N * 7 + K)
+    ldb = N + 24
+    x = _rng_bf16(rng, (K, M)); dybuf = _rng_bf16(rng, (K, ldb)); dy = dybuf[:, :N]
+    ref = x.astype(np.float64).T @ dy.astype(np.float64)
+    ref_db = dy.astype(np.float64).sum(axis=0)
+    bound32 = 1e-5 * np.abs(dy.astype(np.float64)).sum(axis=0) + 1e-30     # fp32 summation of K terms
+    a, b = dev_bf16(x), dev_bf16(dybuf)
+    ws = torch.empty(((K + 63) // 64) * N, dtype=torch.float32, device="cuda")
+    c32 = torch.full((M, N), 7.0, dtype=torch.float32, device="cuda")
+    db32 = torch.full((N + 8,), 3.0, dtype=torch.float32, device="cuda")
+    B.axonn_gemm_wgrad_colsum(B.EPI_ACC_F32, M, N, K, a, M, b, ldb, c32, N, db32, ws, accumulate=0)   # overwrite
+    assert rel_fro(host(c32), ref) < 1e-5
+    assert (np.abs(host(db32)[:N] - ref_db) <= bound32).all()
+    B.axonn_gemm_wgrad_colsum(B.EPI_ACC_F32, M, N, K, a, M, b, ldb, c32, N, db32, ws, accumulate=1)
+    assert rel_fro(host(c32), 2 * ref) < 1e-5
+    assert (np.abs(host(db32)[:N] - 2 * ref_db) <= 2 * bound32).all()
+    assert (host(db32)[N:] == 3.0).all()                                   # nothing written past column N
+    c16 = torch.full((M, N), 7.0, dtype=B.torch_elem_dtype(), device="cuda")
+    db16 = torch.full((N + 8,), 3.0, dtype=B.torch_elem_dtype(), device="cuda")
+    B.axonn_gemm_wgrad_colsum(B.EPI_ACC_BF16, M, N, K, a, M, b, ldb, c16, N, db16, ws, accumulate=0)
+    first, first_db = host(c16), host(db16)[:N]
+    parity(first, ref, TOL, C_ONE, label="gemm_wgrad_with_bias_gradient")
+    parity(first_db, ref_db, TOL, C_ONE, label="gemm_wgrad_with_bias_gradient")
+    B.axonn_gemm_wgrad_colsum(B.EPI_ACC_BF16, M, N, K, a, M, b, ldb, c16, N, db16, ws, accumulate=1)
+    parity(host(c16), first + ref, TOL, C_ONE, label="gemm_wgrad_with_bias_gradient")
+    parity(host(db16)[:N], first_db + ref_db, TOL, C_ONE, label="gemm_wgrad_with_bias_gradient")
+    assert (host(db16)[N:] == 3.0).all()
+
+
 def test_gemm_big_tile_strided_operands():
     """The big-tile kernel with leading dimensions larger than the logical widths and a k tail: what lies
     beyond K in a row of a k-contiguous operand must not enter the sum."""
@@ -150,6 +185,7 @@ def test_gemm_both_large_kernels_all_layouts_and_results(mask, min_tiles):
                 test_gemm_forward_layout_bias_res_gelu(M, N, K)
                 test_gemm_dgrad_layout_plain_and_dgelu(M, N, K)
                 test_gemm_wgrad_layout_accumulate(M, N, K)
+                test_gemm_wgrad_with_bias_gradient(M, N, K)
         B.axonn_tuning(B.TUNE_GEMM_TILE_N, -1)
         test_gemm_big_tile_strided_operands()
         test_gemm_strided_operands_and_run_to_run_determinism()
