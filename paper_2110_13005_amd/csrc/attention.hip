@@ -764,10 +764,12 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_bwd_dq_kernel(
     using Rows = TileRegs<128, D>;
     constexpr int LPR = D / 8, RSTEP = 256 / LPR;
     const uint32_t o_bytes = (uint32_t)(((int64_t)(s - 1) * h + D) * 2), o_off0 = Rows::offset0((uint32_t)h * 2u, tid);
-    Rows r_do, r_o;
+    Rows r_q, r_do, r_o;         // all three requested at once; Q, needed first, in front
+    r_q.load_buffer(make_rsrc(qb, (uint32_t)(((int64_t)(s - 1) * ld + D) * 2)), Rows::offset0((uint32_t)ld * 2u, tid),
+                    (uint32_t)ld * 2u, q0);
     r_do.load_buffer(make_rsrc(dob, o_bytes), o_off0, (uint32_t)h * 2u, q0);
     r_o.load_buffer(make_rsrc(o + (int64_t)bi * s * h + hd * d, o_bytes), o_off0, (uint32_t)h * 2u, q0);
-    stage_rows_in<D, D + 8>(smem, make_rsrc(qb, (uint32_t)(((int64_t)(s - 1) * ld + D) * 2)), (uint32_t)ld * 2u, q0, tid);
+    r_q.template store<D + 8>(smem, tid);
     __syncthreads();
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qf[kk] = frag_kcontig(smem + (32 * wave) * (D + 8) + kk * 16, D + 8, lane);

@@ -64,6 +64,29 @@ def test_ragged_and_degenerate_shapes(sh):
     check_batch(outs, dxs, grads, ref)
 
 
+@pytest.mark.parametrize("mask", [15, 0])
+def test_parity_through_the_large_problem_gemm_kernels(mask):
+    """The weight-gradient kernels of large problems also add up the bias gradients, from the tiles they multiply.
+    With the launcher's threshold lowered the small shapes go through them too (the copying kernels where the token
+    count is a multiple of 64, mask 15; the register-staged ones everywhere, mask 0), element by element against
+    the oracle."""
+    try:
+        B.axonn_tuning(B.TUNE_GEMM_COPY_MASK, mask)
+        B.axonn_tuning(B.TUNE_GEMM_BIG_MIN_TILES, 1)
+        for sh, fp32_acc, seed in ((CONFIGS["tiny"], 1, 0), (CONFIGS["tiny"], 0, 0),
+                                   (StageShape(3, 384, 3, 200, 2, 3, 1000), 0, 3),      # ragged T = 400
+                                   (StageShape(1, 64, 1, 8, 1, 1), 1, 3)):              # one block of 8 tokens
+            layers, xs, dys = make_stage_inputs(sh, seed=seed, perturb=True)
+            ref = oracle.stage_batch(xs, dys, layers, sh.n_heads, EPS)
+            with Stage(sh, grad_accum_fp32=fp32_acc) as st:
+                st.load_params(layers)
+                outs, dxs, grads = run_direct(st, xs, dys)
+            check_batch(outs, dxs, grads, ref)
+    finally:
+        for knob in (B.TUNE_GEMM_COPY_MASK, B.TUNE_GEMM_BIG_MIN_TILES):
+            B.axonn_tuning(knob, -1)
+
+
 def test_zero_output_projections_give_identity():
     """Degenerate case of the method: W_o = W_fc2 = 0 (and zero biases) makes every layer the
     identity, forward and backward, bit for bit."""
