@@ -88,6 +88,15 @@ def test_argument_validation_without_device():
         B.axonn_gemm_bf16(0, 1, 0, 64, 64, 64, 1, 64, 1, 64, 1, 64)          # layout not built
     assert e.value.status == B.AXONN_EUNSUPPORTED
     with pytest.raises(B.AxonnError) as e:
+        B.axonn_gemm_wgrad_colsum(3, 64, 64, 64, 1, 64, 1, 64, 1, 64, 1, 1)     # not an accumulating epilogue
+    assert e.value.status == B.AXONN_EINVAL
+    with pytest.raises(B.AxonnError) as e:
+        B.axonn_gemm_wgrad_colsum(5, 64, 64, 64, 1, 64, 1, 64, 1, 64, None, 1)  # no place for the column sums
+    assert e.value.status == B.AXONN_EINVAL
+    with pytest.raises(B.AxonnError) as e:
+        B.axonn_gemm_wgrad_colsum(5, 64, 64, 64, 1, 64, 1, 56, 1, 64, 1, 1)     # ldb < N
+    assert e.value.status == B.AXONN_EINVAL
+    with pytest.raises(B.AxonnError) as e:
         B.axonn_adam_bucket(8, 1, 1, 1, 1, 1, 1e-3, 0.9, 0.95, 1e-8, 0.0, 0, 1.0)  # step 0
     assert e.value.status == B.AXONN_EINVAL
     with pytest.raises(B.AxonnError) as e:
