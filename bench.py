@@ -409,11 +409,10 @@ def main():
             # launches of a call (dx; column partial sums; their reduction) read dout and x a second time
             kern["layernorm_bwd"]["GBps"] = (8.0 * T * h + 8.0 * T) / (kern["layernorm_bwd"]["avg_ms"] * 1e-3) / 1e9
             kern["layernorm_bwd"]["GBps_as_launched"] = 12.0 * T * h / (kern["layernorm_bwd"]["avg_ms"] * 1e-3) / 1e9
-        if "colsum" in kern and not args.ends:   # bias gradients: each of the layer's four output gradients read once
-            kern["colsum"]["GBps"] = 2.0 * T * (3 * h + h + f_ + h) * LM / (kern["colsum"]["total_ms"] * 1e-3) / 1e9
+        # (the bias gradients have no launches of their own: the weight-gradient GEMMs form them)
         if "adam" in kern:               # theta, m, v read and written (fp32), gradient read and parameter written (bf16)
             kern["adam"]["GBps"] = 28.0 * n / (kern["adam"]["total_ms"] * 1e-3) / 1e9
-        for cat in ("layernorm_fwd", "layernorm_bwd", "colsum", "adam", "cross_entropy"):
+        for cat in ("layernorm_fwd", "layernorm_bwd", "adam", "cross_entropy"):
             if cat in kern and "GBps" in kern[cat]:
                 kern[cat]["frac_of_hbm_peak"] = kern[cat]["GBps"] / flops.PEAK_HBM_GBPS
         out["kernels"] = kern

@@ -53,10 +53,10 @@ int fail(int code, const char* fmt, ...) {
 
 // ---- optional per-launch timing: event pairs around every kernel launch, by category ----
 enum ProfCat { PC_GEMM_FWD, PC_GEMM_DGRAD, PC_GEMM_WGRAD, PC_ATTN_FWD, PC_ATTN_BWD, PC_LN_FWD,
-               PC_LN_BWD, PC_COLSUM, PC_GRAD_CONVERT, PC_ADAM, PC_COPY_IN, PC_EMBED, PC_XENT, PC_COUNT };
+               PC_LN_BWD, PC_GRAD_CONVERT, PC_ADAM, PC_COPY_IN, PC_EMBED, PC_XENT, PC_COUNT };
 const char* const kProfNames[PC_COUNT] = {
     "gemm_fwd", "gemm_dgrad", "gemm_wgrad", "attention_fwd", "attention_bwd", "layernorm_fwd",
-    "layernorm_bwd", "colsum", "grad_convert", "adam", "copy_in", "embedding", "cross_entropy"};
+    "layernorm_bwd", "grad_convert", "adam", "copy_in", "embedding", "cross_entropy"};
 struct ProfRec { int cat; hipEvent_t a, b; };
 bool g_prof_on = false;
 std::vector<ProfRec> g_prof_recs;
