@@ -462,9 +462,10 @@ int axonn_adam_bucket(uint64_t n, float* theta, float* m, float* v, const void* 
  * library makes is bracketed by a pair of HIP events on the stream it is launched on;
  * collect() waits for them, adds up elapsed milliseconds and launch counts per category
  * and clears the records.  Categories (num_categories of them, names by index): the three
- * GEMM layouts, attention forward / backward, LayerNorm forward / backward, column sums,
- * small accumulations, gradient conversion, Adam, input copy.  Process-wide, not
- * thread-safe.  Intervals of kernels that overlap on different streams are each counted
+ * GEMM layouts (the bias gradients come with the weight-gradient launches), attention
+ * forward / backward, LayerNorm forward / backward (the backward with the reduction of its
+ * gain and shift gradients), gradient conversion, Adam, input copy, embedding,
+ * cross-entropy.  Process-wide, not thread-safe.  Intervals of kernels that overlap on different streams are each counted
  * in full.
  * ---------------------------------------------------------------------------------- */
 int axonn_profile_enable(int32_t on);

@@ -87,6 +87,36 @@ def test_parity_through_the_large_problem_gemm_kernels(mask):
             B.axonn_tuning(knob, -1)
 
 
+def test_launch_timing_counts_the_launches_of_a_batch():
+    """The launch-timing aid (what bench.py's `kernels` and `roofline` fields are made of): per category the launches of
+    one batch of direct calls, and a positive time wherever something was launched.  The bias gradients have no
+    launches of their own."""
+    import torch
+    sh = CONFIGS["tiny"]
+    L, M = sh.n_layers, sh.n_microbatches
+    layers, xs, dys = make_stage_inputs(sh, seed=0)
+    with Stage(sh, grad_accum_fp32=0) as st:
+        st.load_params(layers)
+        torch.cuda.synchronize()
+        B.axonn_profile_enable(True)
+        try:
+            run_direct(st, xs, dys)
+            torch.cuda.synchronize()
+            got = B.axonn_profile_collect()
+        finally:
+            B.axonn_profile_enable(False)
+    assert "colsum" not in got
+    launches = {k: v[1] for k, v in got.items()}
+    assert launches["gemm_fwd"] == 4 * L * M and launches["gemm_dgrad"] == 4 * L * M
+    assert launches["attention_fwd"] == L * M and launches["attention_bwd"] == L * M
+    assert launches["layernorm_fwd"] == 2 * L * M and launches["layernorm_bwd"] == 2 * L * M
+    assert launches["copy_in"] == 2 * M                      # the input and the upstream gradient of every microbatch
+    assert launches["gemm_wgrad"] > 0 and launches["gemm_wgrad"] % (4 * L) == 0
+    for k, (ms, n) in got.items():
+        assert (ms > 0) == (n > 0), (k, ms, n)
+    assert B.axonn_profile_collect()["gemm_fwd"] == (0.0, 0)   # collect cleared the records
+
+
 def test_zero_output_projections_give_identity():
     """Degenerate case of the method: W_o = W_fc2 = 0 (and zero biases) makes every layer the
     identity, forward and backward, bit for bit."""
